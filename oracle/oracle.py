@@ -1,0 +1,196 @@
+"""Python face of the CPU oracle (TEST INFRASTRUCTURE ONLY).
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this
+module.  It loads oracle/libsbi_oracle.so (plain C, fp64) and adds two numpy-only pieces:
+
+* layout_weights / unlayout_weights - the weight pre-layout written as a reshape/transpose
+  from the layout's published definition (the paper, Sec. III-C "Leveraging Full
+  Cache-line", only fixes the idea: re-tile W once at initialisation so that each thread
+  reads several consecutive input-dimension elements of a column in one access);
+* ulp16 / check_close - the acceptance rule |gpu - oracle| <= max(2 ulp16(oracle), 1e-3).
+
+Nothing here imports the GPU package; inputs are numpy arrays of fp16 (or their uint16 bits).
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+EPI_BIAS = 1
+EPI_GELU = 2
+EPI_RES = 4
+
+# layout constants, restated here from the layout's definition (not imported from the GPU side)
+CHUNK_K = 8      # consecutive k of one column held by one lane (16 bytes)
+TILE_N = 16      # columns per tile
+TILE_K = 32      # k per tile  = 4 lane groups x CHUNK_K
+PANEL_TILES = 4  # tiles per panel -> a panel is 64 columns wide
+PANEL_N = TILE_N * PANEL_TILES
+HEADER_BYTES = 256
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build()
+        L = ctypes.CDLL(path)
+        L.sbi_oracle_half_to_double.restype = ctypes.c_double
+        L.sbi_oracle_half_to_double.argtypes = [ctypes.c_uint16]
+        L.sbi_oracle_double_to_half.restype = ctypes.c_uint16
+        L.sbi_oracle_double_to_half.argtypes = [ctypes.c_double]
+        L.sbi_oracle_gelu.restype = ctypes.c_double
+        L.sbi_oracle_gelu.argtypes = [ctypes.c_double]
+        L.sbi_oracle_half_to_double_array.restype = None
+        L.sbi_oracle_half_to_double_array.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
+        L.sbi_oracle_double_to_half_array.restype = None
+        L.sbi_oracle_double_to_half_array.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
+        L.sbi_oracle_max_threads.restype = ctypes.c_int
+        L.sbi_oracle_gemm.restype = ctypes.c_int
+        L.sbi_oracle_gemm.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] + [ctypes.c_int64] * 3 + \
+            [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def _bits(a, name):
+    """fp16 array (or uint16 bit patterns) -> contiguous uint16 view."""
+    a = np.asarray(a)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    if a.dtype != np.uint16:
+        raise TypeError(f"{name}: expected float16 or uint16, got {a.dtype}")
+    return np.ascontiguousarray(a)
+
+
+def half_to_double(bits):
+    b = _bits(bits, "bits")
+    out = np.empty(b.shape, dtype=np.float64)
+    lib().sbi_oracle_half_to_double_array(b.ctypes.data, out.ctypes.data, b.size)
+    return out
+
+
+def double_to_half(values):
+    """fp64 array -> fp16 array, one round-to-nearest-even step (the oracle's own rounding)."""
+    v = np.ascontiguousarray(np.asarray(values, dtype=np.float64))
+    out = np.empty(v.shape, dtype=np.uint16)
+    lib().sbi_oracle_double_to_half_array(v.ctypes.data, out.ctypes.data, v.size)
+    return out.view(np.float16)
+
+
+def gelu(v):
+    return lib().sbi_oracle_gelu(float(v))
+
+
+def max_threads():
+    return int(lib().sbi_oracle_max_threads())
+
+
+def gemm(X, W, bias=None, residual=None, epi=0, threads=0, return_pre=False):
+    """Y = epilogue(X @ W + bias) per the oracle definition.  X [B,K], W [K,N] fp16.
+
+    epi is a bit set of EPI_BIAS | EPI_GELU | EPI_RES.  Returns fp16 [B,N]
+    (and the fp64 values before the final rounding when return_pre is set).
+    """
+    Xb, Wb = _bits(X, "X"), _bits(W, "W")
+    if Xb.ndim != 2 or Wb.ndim != 2 or Xb.shape[1] != Wb.shape[0]:
+        raise ValueError(f"shape mismatch X{Xb.shape} W{Wb.shape}")
+    B, K = Xb.shape
+    N = Wb.shape[1]
+    bb = rb = None
+    if epi & EPI_BIAS:
+        bb = _bits(bias, "bias")
+        if bb.shape != (N,):
+            raise ValueError("bias shape")
+    if epi & EPI_RES:
+        rb = _bits(residual, "residual")
+        if rb.shape != (B, N):
+            raise ValueError("residual shape")
+    Y = np.empty((B, N), dtype=np.uint16)
+    pre = np.empty((B, N), dtype=np.float64) if return_pre else None
+    rc = lib().sbi_oracle_gemm(Xb.ctypes.data, Wb.ctypes.data,
+                               bb.ctypes.data if bb is not None else None,
+                               rb.ctypes.data if rb is not None else None,
+                               int(epi), B, K, N, Y.ctypes.data,
+                               pre.ctypes.data if pre is not None else None, int(threads))
+    if rc != 0:
+        raise RuntimeError(f"sbi_oracle_gemm failed rc={rc}")
+    Yh = Y.view(np.float16)
+    return (Yh, pre) if return_pre else Yh
+
+
+# --------------------------------------------------------------------------------------
+# Weight pre-layout, from its definition.  W [K,N] is zero-padded to Kp = ceil32(K),
+# Np = ceil64(N).  Element (k, n) lands at half-index
+#     ((((p*KS + ks)*4 + t)*64 + lane)*8 + e)
+# with p = n // 64, t = (n % 64) // 16, i = n % 16, ks = k // 32, g = (k % 32) // 8,
+# e = k % 8, lane = g*16 + i, KS = Kp // 32 -- i.e. one lane of a 64-wide wavefront owns
+# 8 consecutive k of one column (16 bytes), a wavefront load covers a 16-column x 32-k tile
+# (1 KiB) and four such tiles (64 columns) of the same k range are adjacent.
+# --------------------------------------------------------------------------------------
+def layout_dims(K, N):
+    KS = -(-K // TILE_K)
+    P = -(-N // PANEL_N)
+    return KS, P
+
+
+def layout_weights(W):
+    """W [K,N] fp16 -> flat uint16 array of P*KS*4*64*8 halfs (no header)."""
+    Wb = _bits(W, "W")
+    K, N = Wb.shape
+    KS, P = layout_dims(K, N)
+    Wp = np.zeros((KS * TILE_K, P * PANEL_N), dtype=np.uint16)
+    Wp[:K, :N] = Wb
+    # axes: ks, g, e, p, t, i
+    T = Wp.reshape(KS, 4, CHUNK_K, P, PANEL_TILES, TILE_N)
+    # target order: p, ks, t, g, i, e
+    return np.ascontiguousarray(T.transpose(3, 0, 4, 1, 5, 2)).reshape(-1)
+
+
+def unlayout_weights(flat, K, N):
+    """Inverse of layout_weights: flat halfs -> W [K,N] uint16 bits (padding dropped)."""
+    KS, P = layout_dims(K, N)
+    T = np.asarray(flat, dtype=np.uint16).reshape(P, KS, PANEL_TILES, 4, TILE_N, CHUNK_K)
+    Wp = T.transpose(1, 3, 5, 0, 2, 4).reshape(KS * TILE_K, P * PANEL_N)
+    return np.ascontiguousarray(Wp[:K, :N])
+
+
+# --------------------------------------------------------------------------------------
+# Acceptance rule.
+# --------------------------------------------------------------------------------------
+def ulp16(v):
+    """Spacing of fp16 numbers at |v| (2^-24 in the subnormal range)."""
+    a = np.abs(np.asarray(v, dtype=np.float64))
+    e = np.floor(np.log2(np.maximum(a, 2.0 ** -14)))
+    return np.exp2(np.maximum(e, -14.0) - 10.0)
+
+
+def check_close(got, want, ulps=2, abs_tol=1e-3):
+    """Element-wise |got - want| <= max(ulps * ulp16(want), abs_tol); inf must match inf.
+
+    Returns (ok, report dict with max abs error, max error in ulp16, number of failures).
+    """
+    g = np.asarray(got, dtype=np.float16).astype(np.float64)
+    w = np.asarray(want, dtype=np.float16).astype(np.float64)
+    if g.shape != w.shape:
+        raise ValueError(f"shape mismatch {g.shape} vs {w.shape}")
+    fin = np.isfinite(w)
+    same_nonfinite = np.where(fin, True, (g == w) | (np.isnan(g) & np.isnan(w)))
+    with np.errstate(invalid="ignore"):
+        diff = np.where(fin, np.abs(g - w), 0.0)
+    diff = np.where(np.isfinite(diff), diff, np.inf)
+    tol = np.maximum(ulps * ulp16(np.where(fin, w, 1.0)), abs_tol)
+    bad = (diff > tol) | ~same_nonfinite
+    rep = {
+        "max_abs": float(diff.max()) if diff.size else 0.0,
+        "max_ulp": float((diff / ulp16(np.where(fin, w, 1.0))).max()) if diff.size else 0.0,
+        "n_bad": int(bad.sum()),
+        "n": int(bad.size),
+    }
+    if rep["n_bad"]:
+        idx = np.argwhere(bad)[0]
+        rep["first_bad"] = (tuple(int(i) for i in idx), float(g[tuple(idx)]), float(w[tuple(idx)]))
+    return rep["n_bad"] == 0, rep

@@ -1,0 +1,182 @@
+/*
+ * CPU oracle for the small-batch inference GeMM  Y[B,N] = epilogue(X[B,K] . W[K,N] + bias).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct definition the GPU
+ * library is checked against.  It shares no code, header, table or constant with the HIP
+ * path and must never be called from it.
+ *
+ * What it follows.  The paper (Sec. III-C, "SBI-GeMM") states the operation only as a
+ * "skinny matrix multiplication" of a small batch of activations with a layer's weight
+ * matrix, and Sec. III-D names "bias and residual addition" as the fused tail of a
+ * transformer layer.  The method is a faster way to reach the plain matrix product, so
+ * the oracle is that definition written out:
+ *
+ *     acc[b,n] = sum_{k=0}^{K-1} X[b,k] * W[k,n]          fp64, k ascending
+ *     v        = acc[b,n] (+ bias[n])
+ *     GeLU:      v = 0.5 * v * (1 + erf(v / sqrt 2))        exact-erf form, libm erf
+ *     residual:  v = v + R[b,n]
+ *     Y[b,n]   = fp16(v)                                    ONE round-to-nearest-even step
+ *
+ * All tensors are IEEE binary16 bit patterns (uint16_t), row-major, contiguous.
+ * fp16*fp16 products are exact in fp64 and the fp64 sum has relative error about
+ * K*2^-53, so before the final rounding this is "the exact result" at fp16 resolution.
+ * No blocking, fusion or reordering changes any output: the only blocking is over
+ * independent columns (each output still sums k = 0..K-1 in order).
+ *
+ * Every function here is pinned by tests/test_oracle_*.py (brute-force rational
+ * arithmetic, identity / one-hot weights, linearity, GeLU closed forms, exhaustive
+ * fp16 round trips): no part is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* epilogue selector: bit 0 = add bias, bit 1 = GeLU, bit 2 = add residual */
+#define ORACLE_EPI_BIAS 1
+#define ORACLE_EPI_GELU 2
+#define ORACLE_EPI_RES  4
+
+/* binary16 bit pattern -> double (exact: every fp16 value is a double) */
+double sbi_oracle_half_to_double(uint16_t h)
+{
+    const int sign = (h >> 15) & 1;
+    const int exp  = (h >> 10) & 0x1f;
+    const int man  = h & 0x3ff;
+    double v;
+    if (exp == 0)        v = ldexp((double)man, -24);              /* zero / subnormal */
+    else if (exp == 31)  v = man ? NAN : INFINITY;
+    else                 v = ldexp((double)(man | 0x400), exp - 25); /* 1.man * 2^(exp-15) */
+    return sign ? -v : v;
+}
+
+/* double -> binary16 bit pattern, a single round-to-nearest-even step (never via float) */
+uint16_t sbi_oracle_double_to_half(double v)
+{
+    uint64_t bits;
+    memcpy(&bits, &v, sizeof bits);
+    const uint16_t sign = (uint16_t)((bits >> 63) << 15);
+    const int      bexp = (int)((bits >> 52) & 0x7ff);
+    const uint64_t man  = bits & ((1ull << 52) - 1);
+
+    if (bexp == 0x7ff) return (uint16_t)(sign | (man ? 0x7e00 : 0x7c00));  /* NaN / inf */
+    if (bexp == 0)     return sign;            /* fp64 zero or subnormal: far below 2^-25 */
+
+    const int e = bexp - 1023;                 /* v = 1.man * 2^e */
+    if (e > 15) return (uint16_t)(sign | 0x7c00);
+
+    if (e >= -14) {                            /* fp16 normal range: keep 10 fraction bits */
+        uint64_t q   = man >> 42;
+        uint64_t rem = man & ((1ull << 42) - 1);
+        uint64_t half = 1ull << 41;
+        uint32_t out = (uint32_t)(((uint32_t)(e + 15) << 10) | (uint32_t)q);
+        if (rem > half || (rem == half && (q & 1))) out += 1;   /* carry may reach exponent / inf */
+        return (uint16_t)(sign | out);
+    }
+    /* fp16 subnormal range: count units of 2^-24 */
+    const int shift = 42 + (-14 - e);          /* >= 43 */
+    if (shift >= 64) return sign;
+    const uint64_t full = (1ull << 52) | man;
+    uint64_t q    = full >> shift;
+    uint64_t rem  = full & ((1ull << shift) - 1);
+    uint64_t half = 1ull << (shift - 1);
+    if (rem > half || (rem == half && (q & 1))) q += 1;          /* may become 0x400 = min normal */
+    return (uint16_t)(sign | (uint16_t)q);
+}
+
+/* exact-erf GeLU in fp64 */
+double sbi_oracle_gelu(double v)
+{
+    return 0.5 * v * (1.0 + erf(v / sqrt(2.0)));
+}
+
+void sbi_oracle_half_to_double_array(const uint16_t* h, double* d, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) d[i] = sbi_oracle_half_to_double(h[i]);
+}
+
+void sbi_oracle_double_to_half_array(const double* d, uint16_t* h, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) h[i] = sbi_oracle_double_to_half(d[i]);
+}
+
+int sbi_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/*
+ * The GeMM.  X [B,K], W [K,N], bias [N] or NULL, R [B,N] or NULL, Y [B,N] (fp16 bits).
+ * `pre` (optional, [B,N] doubles) receives v before the final fp16 rounding.
+ * `threads` <= 0 means "all cores".  Returns 0, or -1 on a bad argument.
+ * Columns are processed in independent blocks of CB; each output sums k = 0..K-1 in order.
+ */
+int sbi_oracle_gemm(const uint16_t* X, const uint16_t* W, const uint16_t* bias,
+                    const uint16_t* R, int epi, int64_t B, int64_t K, int64_t N,
+                    uint16_t* Y, double* pre, int threads)
+{
+    if (!X || !W || !Y || B <= 0 || K <= 0 || N <= 0) return -1;
+    if ((epi & ORACLE_EPI_BIAS) && !bias) return -1;
+    if ((epi & ORACLE_EPI_RES) && !R) return -1;
+    if (epi & ~7) return -1;
+
+    enum { CB = 128 };
+    double* Xd = (double*)malloc(sizeof(double) * (size_t)B * (size_t)K);
+    if (!Xd) return -1;
+    sbi_oracle_half_to_double_array(X, Xd, B * K);
+
+    const int64_t nblocks = (N + CB - 1) / CB;
+#ifdef _OPENMP
+    if (threads <= 0) threads = omp_get_max_threads();
+#else
+    threads = 1;
+#endif
+    int failed = 0;
+
+#pragma omp parallel num_threads(threads)
+    {
+        double* acc  = (double*)malloc(sizeof(double) * (size_t)B * CB);
+        double  wrow[CB];
+        if (!acc) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t blk = 0; blk < nblocks; ++blk) {
+            if (!acc) continue;
+            const int64_t n0 = blk * CB;
+            const int     nb = (int)((N - n0 < CB) ? (N - n0) : CB);
+            for (int64_t i = 0; i < B * CB; ++i) acc[i] = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                const uint16_t* wr = W + k * N + n0;
+                for (int j = 0; j < nb; ++j) wrow[j] = sbi_oracle_half_to_double(wr[j]);
+                for (int64_t b = 0; b < B; ++b) {
+                    const double x = Xd[b * K + k];
+                    double* a = acc + b * CB;
+                    for (int j = 0; j < nb; ++j) a[j] += x * wrow[j];
+                }
+            }
+            for (int64_t b = 0; b < B; ++b) {
+                for (int j = 0; j < nb; ++j) {
+                    const int64_t n = n0 + j;
+                    double v = acc[b * CB + j];
+                    if (epi & ORACLE_EPI_BIAS) v += sbi_oracle_half_to_double(bias[n]);
+                    if (epi & ORACLE_EPI_GELU) v = sbi_oracle_gelu(v);
+                    if (epi & ORACLE_EPI_RES)  v += sbi_oracle_half_to_double(R[b * N + n]);
+                    if (pre) pre[b * N + n] = v;
+                    Y[b * N + n] = sbi_oracle_double_to_half(v);
+                }
+            }
+        }
+        free(acc);
+    }
+    free(Xd);
+    return failed ? -1 : 0;
+}
