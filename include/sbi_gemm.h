@@ -1,0 +1,198 @@
+/*
+ * sbi_gemm.h - C ABI of the MI355X (gfx950) small-batch inference GeMM library.
+ *
+ * The operation is the one the DeepSpeed Inference paper (arXiv 2207.00032) builds its
+ * latency work on: at small batch a transformer layer's linear layers are bound by the
+ * time it takes to read the weights once (Sec. I, "Latency Challenges"), so the GeMM
+ *
+ *     Y[B,N] = epilogue( X[B,K] . W[K,N] + bias[N] )          B = 1 .. 64
+ *
+ * is a weight-streaming kernel (Sec. III-C, "SBI-GeMM").  W is fp16, products are
+ * accumulated in fp32, Y is fp16 (one round-to-nearest-even step at the very end).
+ * The epilogue is the element-wise tail the paper fuses into the producing kernel
+ * (Sec. III-B fusion rule; Sec. III-D region 4, "bias and residual addition").
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers into memory owned by the caller; the
+ *     library never allocates, frees or retains device memory.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     work is enqueued on it and no call synchronises, except sbi_gemm_layout_check.
+ *   - Arguments are validated on the host before any GPU call; a failed validation
+ *     enqueues nothing.  No exception crosses the boundary; the result is an sbi_status.
+ *   - There is no global mutable state; calls on different streams may overlap as long as
+ *     they do not share a workspace.
+ */
+#ifndef SBI_GEMM_H
+#define SBI_GEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SBI_MAX_BATCH 64
+
+typedef enum sbi_status {
+    SBI_OK = 0,
+    SBI_ERR_NULL = 1,            /* a required pointer is NULL */
+    SBI_ERR_SHAPE = 2,           /* K or N < 1, or too large for 32-bit tile counts */
+    SBI_ERR_ALIGN = 3,           /* a pointer is not aligned as documented */
+    SBI_ERR_BATCH = 4,           /* B outside 1..SBI_MAX_BATCH */
+    SBI_ERR_LAYOUT_MISMATCH = 5, /* laid-out buffer header does not match (K, N) */
+    SBI_ERR_WORKSPACE = 6,       /* workspace missing or too small */
+    SBI_ERR_EPILOGUE = 7,        /* unknown epilogue, or its bias/residual pointer is NULL */
+    SBI_ERR_HIP = 8,             /* the HIP runtime reported an error */
+    SBI_ERR_OVERLAP = 9,         /* Y overlaps X */
+    SBI_ERR_TUNING = 10          /* an explicit tuning request is not supported */
+} sbi_status;
+
+/* v = acc (+ bias[n]);  GELU: v = 0.5 v (1 + erf(v / sqrt 2));  RESIDUAL: v += R[b,n]. */
+typedef enum sbi_epilogue {
+    SBI_EPI_NONE = 0,
+    SBI_EPI_BIAS = 1,
+    SBI_EPI_BIAS_GELU = 2,
+    SBI_EPI_BIAS_RESIDUAL = 3,
+    SBI_EPI_GELU = 4,
+    SBI_EPI_RESIDUAL = 5
+} sbi_epilogue;
+
+/* Which kernel family executes the contraction. */
+typedef enum sbi_path {
+    SBI_PATH_AUTO = 0,   /* the batch-size dispatcher decides */
+    SBI_PATH_STREAM = 1, /* vector-ALU dot-product streaming kernel, B <= 8 */
+    SBI_PATH_MFMA = 2    /* matrix-core (MFMA fp16 16x16x32) streaming kernel, B <= 64 */
+} sbi_path;
+
+/* Optional overrides for sbi_gemm_ex / sbi_gemm_plan; a zero field means "automatic". */
+typedef struct sbi_tuning {
+    int32_t path;    /* sbi_path */
+    int32_t split_k; /* number of thread blocks that share one 64-column panel's K range */
+    int32_t waves;   /* wavefronts per block: 4 or 8 */
+    int32_t depth;   /* k-steps of W each wavefront keeps in flight: 4 or 8 */
+} sbi_tuning;
+
+/* What the dispatcher decided for a problem (for reports and tests). */
+typedef struct sbi_plan {
+    int32_t path;        /* SBI_PATH_STREAM or SBI_PATH_MFMA */
+    int32_t waves;       /* wavefronts per block */
+    int32_t depth;       /* W k-steps in flight per wavefront */
+    int32_t split_k;     /* blocks per panel (1 = no cross-block reduction) */
+    int32_t ksteps_per_split; /* 32-row k-steps handled by one block */
+    int32_t ksteps_per_chunk; /* k-steps of X staged in LDS at a time */
+    int32_t grid;        /* thread blocks launched */
+    int32_t block;       /* threads per block */
+    int64_t lds_bytes;   /* dynamic LDS per block */
+    int64_t workspace_bytes; /* workspace this plan needs (0 when split_k == 1) */
+} sbi_plan;
+
+/*
+ * Size in bytes of the laid-out copy of a [K,N] fp16 matrix: a 256-byte header followed
+ * by ceil(N/64) * ceil(K/32) tiles of 4 KiB (zero padded).  Returns 0 for a bad shape.
+ */
+size_t sbi_gemm_layout_bytes(int64_t K, int64_t N);
+
+/*
+ * Upper bound of the workspace sbi_gemm (automatic dispatch) needs for (B, K, N), in bytes;
+ * may be 0.  The workspace holds cross-block partial sums and one arrival counter per
+ * panel.  It MUST be zero-filled once by the caller before its first use; the library
+ * leaves the counters zero after every call, so one workspace can serve any sequence
+ * of calls on one stream.  Two calls that may run concurrently must not share it.
+ */
+size_t sbi_gemm_workspace_bytes(int64_t B, int64_t K, int64_t N);
+
+/*
+ * One-time weight pre-layout (paper Sec. III-C, "Leveraging Full Cache-line": re-tile W
+ * at initialisation so that every thread reads several consecutive input-dimension
+ * elements of its column in one access).  Here one lane of a 64-wide wavefront owns
+ * 8 consecutive k of one column (one 128-bit load), a wavefront load is a contiguous
+ * 1 KiB tile of 16 columns x 32 k, and the four tiles of a 64-column panel are adjacent:
+ *   half index of W[k][n] after the header =
+ *     ((((n/64)*KS + k/32)*4 + (n%64)/16)*64 + ((k%32)/8)*16 + n%16)*8 + k%8,  KS = ceil(K/32).
+ * W_rowmajor: device, fp16 [K,N] contiguous (ld = N), 2-byte aligned.
+ * W_laid_out: device, 256-byte aligned, laid_out_bytes >= sbi_gemm_layout_bytes(K,N).
+ * The source may be freed once the stream has executed the call.  Pure permutation plus
+ * zero padding: sbi_gemm_unlayout_weights restores the original bits.
+ */
+sbi_status sbi_gemm_layout_weights(const void* W_rowmajor, int64_t K, int64_t N,
+                                   void* W_laid_out, size_t laid_out_bytes, void* hip_stream);
+
+/* Inverse of sbi_gemm_layout_weights: writes fp16 [K,N] row-major into W_rowmajor. */
+sbi_status sbi_gemm_unlayout_weights(const void* W_laid_out, int64_t K, int64_t N,
+                                     void* W_rowmajor, void* hip_stream);
+
+/*
+ * Reads the header of a laid-out buffer back to the host (synchronises the stream) and
+ * returns SBI_OK if it was written by this library version for exactly (K, N),
+ * SBI_ERR_LAYOUT_MISMATCH otherwise.  sbi_gemm itself trusts its W_laid_out argument.
+ */
+sbi_status sbi_gemm_layout_check(const void* W_laid_out, int64_t K, int64_t N, void* hip_stream);
+
+/*
+ * The small-batch GeMM (paper Sec. III-C; epilogue: Sec. III-D region 4).
+ *   W_laid_out  device, from sbi_gemm_layout_weights for the same (K, N)
+ *   X           device, fp16 [B,K] row-major contiguous; 16-byte aligned when K % 8 == 0,
+ *               2-byte aligned otherwise
+ *   bias        device, fp16 [N], required by the BIAS* epilogues, ignored otherwise
+ *   residual    device, fp16 [B,N], required by the *RESIDUAL epilogues; may alias Y
+ *   Y           device, fp16 [B,N] row-major contiguous, 4-byte aligned; must not overlap X
+ *   workspace   device, 256-byte aligned, zero-filled once before first use;
+ *               workspace_bytes >= sbi_gemm_workspace_bytes(B,K,N); may be NULL when that is 0
+ * Results are deterministic: the same inputs give the same bits on every call.
+ */
+sbi_status sbi_gemm(const void* W_laid_out, int64_t K, int64_t N,
+                    const void* X, int64_t B,
+                    const void* bias, const void* residual, sbi_epilogue epi,
+                    void* Y, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* sbi_gemm with explicit tuning (NULL = automatic).  Workspace need: see sbi_gemm_plan. */
+sbi_status sbi_gemm_ex(const void* W_laid_out, int64_t K, int64_t N,
+                       const void* X, int64_t B,
+                       const void* bias, const void* residual, sbi_epilogue epi,
+                       void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
+                       const sbi_tuning* tuning);
+
+/* Host-only: the launch the dispatcher would make for (B, K, N) under `tuning` (or NULL). */
+sbi_status sbi_gemm_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tuning, sbi_plan* plan);
+
+/*
+ * One transformer layer's four linear layers (paper Sec. III-D, Fig. 1(c): QKV,
+ * attention output, FFN1 "intermediate" GeMM, FFN2 with bias and residual addition).
+ * Shapes: QKV [h, n_qkv]; out [k_out, h]; FFN1 [h, n_ffn1]; FFN2 [k_ffn2, h] - this
+ * covers a full layer (n_qkv = 3h, k_out = h, n_ffn1 = k_ffn2 = 4h) and a tensor-parallel
+ * slice of one.  W* are laid-out buffers; a NULL bias pointer drops that bias.
+ */
+typedef struct sbi_layer {
+    const void *Wqkv, *Wout, *Wffn1, *Wffn2; /* device, laid out */
+    const void *bqkv, *bout, *bffn1, *bffn2; /* device fp16 or NULL */
+    int64_t h, n_qkv, k_out, n_ffn1, k_ffn2;
+    int32_t ffn1_gelu;                        /* nonzero: GeLU after FFN1's bias */
+} sbi_layer;
+
+/*
+ * Enqueues the four GeMMs on one stream:
+ *   Yqkv  [B,n_qkv] = Xqkv[B,h] . Wqkv (+ bqkv)
+ *   Yout  [B,h]     = Xout[B,k_out] . Wout (+ bout)
+ *   Yffn1 [B,n_ffn1]= act(Xffn1[B,h] . Wffn1 (+ bffn1))
+ *   Yffn2 [B,h]     = Xffn2[B,k_ffn2] . Wffn2 (+ bffn2) (+ residual[B,h])
+ * Xffn2 == NULL chains FFN1's output (requires n_ffn1 == k_ffn2).  residual may be NULL.
+ * workspace_bytes >= sbi_layer_workspace_bytes(L, B).
+ */
+sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
+                           const void* Xqkv, const void* Xout, const void* Xffn1, const void* Xffn2,
+                           const void* residual,
+                           void* Yqkv, void* Yout, void* Yffn1, void* Yffn2,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+size_t sbi_layer_workspace_bytes(const sbi_layer* L, int64_t B);
+
+const char* sbi_status_string(sbi_status s);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int32_t sbi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SBI_GEMM_H */

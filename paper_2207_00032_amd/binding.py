@@ -1,0 +1,221 @@
+"""Thin ctypes face of libsbi_gemm.so: argument marshalling only.
+
+Every function takes torch CUDA tensors (device memory owned by the caller), passes their
+data pointers and the current HIP stream through the C ABI declared in include/sbi_gemm.h
+and raises SbiError on a non-zero status.  Nothing is computed here and there is no
+fallback: a missing library is an error.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsbi_gemm.so")
+
+MAX_BATCH = 64
+# sbi_epilogue
+EPI_NONE, EPI_BIAS, EPI_BIAS_GELU, EPI_BIAS_RESIDUAL, EPI_GELU, EPI_RESIDUAL = range(6)
+EPILOGUES = {"none": EPI_NONE, "bias": EPI_BIAS, "bias_gelu": EPI_BIAS_GELU,
+             "bias_residual": EPI_BIAS_RESIDUAL, "gelu": EPI_GELU, "residual": EPI_RESIDUAL}
+# sbi_path
+PATH_AUTO, PATH_STREAM, PATH_MFMA = 0, 1, 2
+PATH_NAMES = {PATH_AUTO: "auto", PATH_STREAM: "stream", PATH_MFMA: "mfma"}
+# sbi_status
+OK = 0
+STATUS_NAMES = ["SBI_OK", "SBI_ERR_NULL", "SBI_ERR_SHAPE", "SBI_ERR_ALIGN", "SBI_ERR_BATCH",
+                "SBI_ERR_LAYOUT_MISMATCH", "SBI_ERR_WORKSPACE", "SBI_ERR_EPILOGUE", "SBI_ERR_HIP",
+                "SBI_ERR_OVERLAP", "SBI_ERR_TUNING"]
+
+EXPORTS = ["sbi_gemm_layout_bytes", "sbi_gemm_workspace_bytes", "sbi_gemm_layout_weights",
+           "sbi_gemm_unlayout_weights", "sbi_gemm_layout_check", "sbi_gemm", "sbi_gemm_ex",
+           "sbi_gemm_plan", "sbi_layer_gemms", "sbi_layer_workspace_bytes", "sbi_status_string",
+           "sbi_version"]
+
+
+class SbiError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        name = STATUS_NAMES[self.status] if 0 <= self.status < len(STATUS_NAMES) else str(status)
+        super().__init__(f"{where}: {name} ({status_string(self.status)})")
+
+
+class Tuning(ctypes.Structure):
+    _fields_ = [("path", ctypes.c_int32), ("split_k", ctypes.c_int32),
+                ("waves", ctypes.c_int32), ("depth", ctypes.c_int32)]
+
+
+class Plan(ctypes.Structure):
+    _fields_ = [("path", ctypes.c_int32), ("waves", ctypes.c_int32), ("depth", ctypes.c_int32),
+                ("split_k", ctypes.c_int32), ("ksteps_per_split", ctypes.c_int32),
+                ("ksteps_per_chunk", ctypes.c_int32), ("grid", ctypes.c_int32), ("block", ctypes.c_int32),
+                ("lds_bytes", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64)]
+
+    def as_dict(self):
+        return {f: getattr(self, f) for f, _ in self._fields_}
+
+
+class Layer(ctypes.Structure):
+    _fields_ = [("Wqkv", ctypes.c_void_p), ("Wout", ctypes.c_void_p), ("Wffn1", ctypes.c_void_p),
+                ("Wffn2", ctypes.c_void_p), ("bqkv", ctypes.c_void_p), ("bout", ctypes.c_void_p),
+                ("bffn1", ctypes.c_void_p), ("bffn2", ctypes.c_void_p),
+                ("h", ctypes.c_int64), ("n_qkv", ctypes.c_int64), ("k_out", ctypes.c_int64),
+                ("n_ffn1", ctypes.c_int64), ("k_ffn2", ctypes.c_int64), ("ffn1_gelu", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def load():
+    """Open libsbi_gemm.so (built by `python -m paper_2207_00032_amd.csrc.build` or
+    __graft_entry__.build()).  Raises if it is missing: there is no other implementation."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} not found: build the HIP library first "
+                          f"(python paper_2207_00032_amd/csrc/build.py)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, sz, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t, ctypes.c_int32
+    L.sbi_gemm_layout_bytes.restype = sz
+    L.sbi_gemm_layout_bytes.argtypes = [i64, i64]
+    L.sbi_gemm_workspace_bytes.restype = sz
+    L.sbi_gemm_workspace_bytes.argtypes = [i64, i64, i64]
+    L.sbi_gemm_layout_weights.restype = i32
+    L.sbi_gemm_layout_weights.argtypes = [vp, i64, i64, vp, sz, vp]
+    L.sbi_gemm_unlayout_weights.restype = i32
+    L.sbi_gemm_unlayout_weights.argtypes = [vp, i64, i64, vp, vp]
+    L.sbi_gemm_layout_check.restype = i32
+    L.sbi_gemm_layout_check.argtypes = [vp, i64, i64, vp]
+    L.sbi_gemm.restype = i32
+    L.sbi_gemm.argtypes = [vp, i64, i64, vp, i64, vp, vp, i32, vp, vp, sz, vp]
+    L.sbi_gemm_ex.restype = i32
+    L.sbi_gemm_ex.argtypes = [vp, i64, i64, vp, i64, vp, vp, i32, vp, vp, sz, vp, ctypes.POINTER(Tuning)]
+    L.sbi_gemm_plan.restype = i32
+    L.sbi_gemm_plan.argtypes = [i64, i64, i64, ctypes.POINTER(Tuning), ctypes.POINTER(Plan)]
+    L.sbi_layer_gemms.restype = i32
+    L.sbi_layer_gemms.argtypes = [ctypes.POINTER(Layer), i64] + [vp] * 9 + [vp, sz, vp]
+    L.sbi_layer_workspace_bytes.restype = sz
+    L.sbi_layer_workspace_bytes.argtypes = [ctypes.POINTER(Layer), i64]
+    L.sbi_status_string.restype = ctypes.c_char_p
+    L.sbi_status_string.argtypes = [i32]
+    L.sbi_version.restype = i32
+    L.sbi_version.argtypes = []
+    _lib = L
+    return L
+
+
+def status_string(status):
+    return load().sbi_status_string(int(status)).decode()
+
+
+def _check(status, where):
+    if status != OK:
+        raise SbiError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _tuning(path=PATH_AUTO, split_k=0, waves=0, depth=0):
+    if path == PATH_AUTO and not (split_k or waves or depth):
+        return None
+    return ctypes.pointer(Tuning(int(path), int(split_k), int(waves), int(depth)))
+
+
+# ---------------------------------------------------------------------------------- sizes
+def layout_bytes(K, N):
+    return int(load().sbi_gemm_layout_bytes(K, N))
+
+
+def workspace_bytes(B, K, N):
+    return int(load().sbi_gemm_workspace_bytes(B, K, N))
+
+
+def plan(B, K, N, path=PATH_AUTO, split_k=0, waves=0, depth=0):
+    pl = Plan()
+    _check(load().sbi_gemm_plan(B, K, N, _tuning(path, split_k, waves, depth), ctypes.byref(pl)), "sbi_gemm_plan")
+    return pl.as_dict()
+
+
+# ---------------------------------------------------------------------------------- device calls
+def new_workspace(nbytes, device="cuda"):
+    """A zero-filled workspace tensor (the counters in it must start at zero)."""
+    import torch
+    return torch.zeros(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def layout_weights(W):
+    """W: fp16 [K,N] CUDA tensor -> laid-out uint8 CUDA tensor (header + tiles)."""
+    import torch
+    assert W.is_cuda and W.dtype == torch.float16 and W.dim() == 2 and W.is_contiguous()
+    K, N = W.shape
+    out = torch.empty(layout_bytes(K, N), dtype=torch.uint8, device=W.device)
+    _check(load().sbi_gemm_layout_weights(_ptr(W), K, N, _ptr(out), out.numel(), _stream()),
+           "sbi_gemm_layout_weights")
+    return out
+
+
+def unlayout_weights(Wl, K, N):
+    import torch
+    out = torch.empty((K, N), dtype=torch.float16, device=Wl.device)
+    _check(load().sbi_gemm_unlayout_weights(_ptr(Wl), K, N, _ptr(out), _stream()), "sbi_gemm_unlayout_weights")
+    return out
+
+
+def layout_check(Wl, K, N):
+    """Status of the header check (0 = the buffer was laid out for exactly (K, N))."""
+    return int(load().sbi_gemm_layout_check(_ptr(Wl), K, N, _stream()))
+
+
+def gemm(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, workspace=None,
+         path=PATH_AUTO, split_k=0, waves=0, depth=0):
+    """Y = epilogue(X @ W + bias) through sbi_gemm / sbi_gemm_ex.  Returns Y (fp16 [B,N])."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.is_contiguous()
+    B = X.shape[0]
+    if isinstance(epilogue, str):
+        epilogue = EPILOGUES[epilogue]
+    if out is None:
+        out = torch.empty((B, N), dtype=torch.float16, device=X.device)
+    tune = _tuning(path, split_k, waves, depth)
+    if workspace is None:
+        need = plan(B, K, N, path, split_k, waves, depth)["workspace_bytes"] if tune else workspace_bytes(B, K, N)
+        workspace = new_workspace(need, X.device) if need else None
+    ws_ptr = _ptr(workspace)
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    if tune is None:
+        st = load().sbi_gemm(_ptr(Wl), K, N, _ptr(X), B, _ptr(bias), _ptr(residual), int(epilogue),
+                             _ptr(out), ws_ptr, ws_len, _stream())
+    else:
+        st = load().sbi_gemm_ex(_ptr(Wl), K, N, _ptr(X), B, _ptr(bias), _ptr(residual), int(epilogue),
+                                _ptr(out), ws_ptr, ws_len, _stream(), tune)
+    _check(st, "sbi_gemm")
+    return out
+
+
+def make_layer(Wqkv, Wout, Wffn1, Wffn2, h, n_qkv, k_out, n_ffn1, k_ffn2,
+               bqkv=None, bout=None, bffn1=None, bffn2=None, ffn1_gelu=True):
+    """Fill an sbi_layer from laid-out weight tensors; keep the tensors alive yourself."""
+    L = Layer()
+    L.Wqkv, L.Wout, L.Wffn1, L.Wffn2 = (w.data_ptr() for w in (Wqkv, Wout, Wffn1, Wffn2))
+    L.bqkv, L.bout, L.bffn1, L.bffn2 = (None if b is None else b.data_ptr() for b in (bqkv, bout, bffn1, bffn2))
+    L.h, L.n_qkv, L.k_out, L.n_ffn1, L.k_ffn2 = h, n_qkv, k_out, n_ffn1, k_ffn2
+    L.ffn1_gelu = 1 if ffn1_gelu else 0
+    return L
+
+
+def layer_workspace_bytes(layer, B):
+    return int(load().sbi_layer_workspace_bytes(ctypes.byref(layer), B))
+
+
+def layer_gemms(layer, B, Xqkv, Xout, Xffn1, Xffn2, residual, Yqkv, Yout, Yffn1, Yffn2, workspace):
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    st = load().sbi_layer_gemms(ctypes.byref(layer), B, _ptr(Xqkv), _ptr(Xout), _ptr(Xffn1), _ptr(Xffn2),
+                                _ptr(residual), _ptr(Yqkv), _ptr(Yout), _ptr(Yffn1), _ptr(Yffn2),
+                                _ptr(workspace), ws_len, _stream())
+    _check(st, "sbi_layer_gemms")

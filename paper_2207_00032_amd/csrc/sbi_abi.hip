@@ -1,0 +1,318 @@
+// C-ABI entry points, host-side argument validation and the batch-size dispatcher.
+// Every check here runs on the host before anything is enqueued, so the error paths can be
+// exercised without a GPU.
+#include "../../include/sbi_gemm.h"
+#include "sbi_common.h"
+
+#include <algorithm>
+#include <cstring>
+
+namespace {
+
+using namespace sbi;
+
+constexpr int64_t kMaxDim = int64_t(1) << 22;     // K, N limit: keeps tile counts and grids in 32 bits
+constexpr int64_t kMaxLds = 64 * 1024;            // dynamic LDS budget per block
+constexpr int kStreamMaxBatch = 8;                // vector-ALU kernel instantiations exist for B <= 8
+constexpr int kAutoStreamBatch = 0;               // AUTO picks the vector-ALU kernel for B <= this
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
+
+struct Plan {
+    int path, nw, depth, S, ksps, kc, grid, block;
+    int64_t lds, ws_bytes, counter_bytes;
+};
+
+sbi_status check_shape(int64_t K, int64_t N)
+{
+    if (K < 1 || N < 1 || K > kMaxDim || N > kMaxDim) return SBI_ERR_SHAPE;
+    return SBI_OK;
+}
+
+// Cost, in k-steps of streaming time on the busiest CU, of splitting a panel's K range S ways.
+double split_cost(int64_t KS, int64_t P, int64_t B, int S, int nw)
+{
+    const int64_t ksps = ceil_div(KS, S);
+    const int64_t blocks = P * S;
+    const int64_t rounds = ceil_div(blocks, kNumCU);
+    // fixed work per block: ramp-up of the load pipeline, X staging, in-block reduction
+    const double block_overhead = 6.0;
+    // a lone block per CU cannot keep enough loads in flight: count short queues as slower
+    const double waves_per_cu = (double)std::min<int64_t>(rounds, 4) * nw;
+    const double starve = waves_per_cu >= 16 ? 1.0 : (waves_per_cu >= 8 ? 1.15 : 1.6);
+    double cost = (double)rounds * ((double)ksps * starve + block_overhead);
+    if (S > 1) {
+        // partial sums: written once and read once, 256 B per batch row per block
+        const double bytes = (double)blocks * (double)B * 512.0;
+        cost += bytes / kNumCU / 4096.0;
+    }
+    return cost;
+}
+
+sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Plan& pl)
+{
+    if (sbi_status s = check_shape(K, N)) return s;
+    if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
+    const int64_t KS = ceil_div(K, kTileK);
+    const int64_t P = ceil_div(N, kPanelN);
+
+    sbi_tuning t = {0, 0, 0, 0};
+    if (tune) t = *tune;
+
+    int path = t.path;
+    if (path == SBI_PATH_AUTO) path = (B <= kAutoStreamBatch) ? SBI_PATH_STREAM : SBI_PATH_MFMA;
+    if (path != SBI_PATH_STREAM && path != SBI_PATH_MFMA) return SBI_ERR_TUNING;
+    if (path == SBI_PATH_STREAM && B > kStreamMaxBatch) return SBI_ERR_TUNING;
+
+    // the X chunk staged in LDS holds at least waves*depth k-steps of B rows (64 B per row per k-step)
+    const int64_t max_wd = kMaxLds / (B * 64);
+    int nw = t.waves, depth = t.depth;
+    if (nw == 0) nw = (max_wd >= 32 && KS >= 32) ? 8 : 4;
+    if (depth == 0) depth = 4;
+    if ((nw != 4 && nw != 8) || (depth != 4 && depth != 8)) return SBI_ERR_TUNING;
+    if ((int64_t)nw * depth > max_wd) return SBI_ERR_TUNING;
+
+    int S = t.split_k;
+    if (S < 0) return SBI_ERR_TUNING;
+    if (S == 0) {
+        const int64_t smax = std::max<int64_t>(1, std::min<int64_t>(KS / nw, 64));
+        double best = 0.0;
+        for (int s = 1; s <= smax; ++s) {
+            const int64_t ksps = ceil_div(KS, s);
+            if (ceil_div(KS, ksps) != s) continue;          // same launch as a smaller s
+            const double c = split_cost(KS, P, B, s, nw);
+            if (S == 0 || c < best) { best = c; S = s; }
+        }
+    }
+    if (S > KS) S = (int)KS;
+    const int64_t ksps = ceil_div(KS, S);
+    S = (int)ceil_div(KS, ksps);                             // no empty blocks
+    if (P * S > (int64_t)0x7fffffff) return SBI_ERR_SHAPE;
+
+    const int64_t wd = (int64_t)nw * depth;
+    const int64_t kc_max = (kMaxLds / (B * 64)) / wd * wd;
+    const int64_t kc = std::min<int64_t>(kc_max, round_up(ksps, wd));
+
+    pl.path = path; pl.nw = nw; pl.depth = depth; pl.S = S;
+    pl.ksps = (int)ksps; pl.kc = (int)kc;
+    pl.grid = (int)(P * S); pl.block = nw * 64;
+    pl.lds = std::max<int64_t>(kc * B * 64, (int64_t)nw * 16 * kRedPitch * 4);
+    pl.counter_bytes = (S > 1) ? round_up(P * 4, 256) : 0;
+    pl.ws_bytes = (S > 1) ? pl.counter_bytes + P * S * B * kPanelN * 4 : 0;
+    return SBI_OK;
+}
+
+int epilogue_flags(int epi)
+{
+    switch (epi) {
+        case SBI_EPI_NONE: return 0;
+        case SBI_EPI_BIAS: return kEpiBias;
+        case SBI_EPI_BIAS_GELU: return kEpiBias | kEpiGelu;
+        case SBI_EPI_BIAS_RESIDUAL: return kEpiBias | kEpiRes;
+        case SBI_EPI_GELU: return kEpiGelu;
+        case SBI_EPI_RESIDUAL: return kEpiRes;
+    }
+    return -1;
+}
+
+inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+size_t sbi_gemm_layout_bytes(int64_t K, int64_t N)
+{
+    if (check_shape(K, N) != SBI_OK) return 0;
+    return (size_t)kHeaderBytes + (size_t)ceil_div(K, kTileK) * (size_t)ceil_div(N, kPanelN) * 4096u;
+}
+
+size_t sbi_gemm_workspace_bytes(int64_t B, int64_t K, int64_t N)
+{
+    Plan pl;
+    if (make_plan(B, K, N, nullptr, pl) != SBI_OK) return 0;
+    return (size_t)pl.ws_bytes;
+}
+
+sbi_status sbi_gemm_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tuning, sbi_plan* plan)
+{
+    if (!plan) return SBI_ERR_NULL;
+    Plan pl;
+    if (sbi_status s = make_plan(B, K, N, tuning, pl)) return s;
+    plan->path = pl.path; plan->waves = pl.nw; plan->depth = pl.depth; plan->split_k = pl.S;
+    plan->ksteps_per_split = pl.ksps; plan->ksteps_per_chunk = pl.kc;
+    plan->grid = pl.grid; plan->block = pl.block;
+    plan->lds_bytes = pl.lds; plan->workspace_bytes = pl.ws_bytes;
+    return SBI_OK;
+}
+
+sbi_status sbi_gemm_layout_weights(const void* W_rowmajor, int64_t K, int64_t N,
+                                   void* W_laid_out, size_t laid_out_bytes, void* hip_stream)
+{
+    if (!W_rowmajor || !W_laid_out) return SBI_ERR_NULL;
+    if (sbi_status s = check_shape(K, N)) return s;
+    if (!aligned(W_rowmajor, 2) || !aligned(W_laid_out, 256)) return SBI_ERR_ALIGN;
+    if (laid_out_bytes < sbi_gemm_layout_bytes(K, N)) return SBI_ERR_LAYOUT_MISMATCH;
+    return launch_layout(W_rowmajor, K, N, W_laid_out, (hipStream_t)hip_stream) == 0 ? SBI_OK : SBI_ERR_HIP;
+}
+
+sbi_status sbi_gemm_unlayout_weights(const void* W_laid_out, int64_t K, int64_t N,
+                                     void* W_rowmajor, void* hip_stream)
+{
+    if (!W_rowmajor || !W_laid_out) return SBI_ERR_NULL;
+    if (sbi_status s = check_shape(K, N)) return s;
+    if (!aligned(W_rowmajor, 2) || !aligned(W_laid_out, 256)) return SBI_ERR_ALIGN;
+    return launch_unlayout(W_laid_out, K, N, W_rowmajor, (hipStream_t)hip_stream) == 0 ? SBI_OK : SBI_ERR_HIP;
+}
+
+sbi_status sbi_gemm_layout_check(const void* W_laid_out, int64_t K, int64_t N, void* hip_stream)
+{
+    if (!W_laid_out) return SBI_ERR_NULL;
+    if (sbi_status s = check_shape(K, N)) return s;
+    if (!aligned(W_laid_out, 256)) return SBI_ERR_ALIGN;
+    LayoutHeader h;
+    std::memset(&h, 0, sizeof h);
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (hipMemcpyAsync(&h, W_laid_out, sizeof h, hipMemcpyDeviceToHost, st) != hipSuccess) return SBI_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return SBI_ERR_HIP;
+    const bool ok = h.magic == kMagic && h.version == kLayoutVersion && h.K == K && h.N == N &&
+                    h.KS == ceil_div(K, kTileK) && h.P == ceil_div(N, kPanelN) &&
+                    h.tile_n == kTileN && h.tile_k == kTileK && h.panel_tiles == kPanelTiles &&
+                    h.chunk_k == kChunkK;
+    return ok ? SBI_OK : SBI_ERR_LAYOUT_MISMATCH;
+}
+
+sbi_status sbi_gemm_ex(const void* W_laid_out, int64_t K, int64_t N,
+                       const void* X, int64_t B,
+                       const void* bias, const void* residual, sbi_epilogue epi,
+                       void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
+                       const sbi_tuning* tuning)
+{
+    if (!W_laid_out || !X || !Y) return SBI_ERR_NULL;
+    if (sbi_status s = check_shape(K, N)) return s;
+    if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
+    const int flags = epilogue_flags((int)epi);
+    if (flags < 0) return SBI_ERR_EPILOGUE;
+    if ((flags & kEpiBias) && !bias) return SBI_ERR_EPILOGUE;
+    if ((flags & kEpiRes) && !residual) return SBI_ERR_EPILOGUE;
+    const bool x_vec = (K % 8 == 0);
+    if (!aligned(W_laid_out, 256) || !aligned(X, x_vec ? 16 : 2) || !aligned(Y, 4)) return SBI_ERR_ALIGN;
+    if ((flags & kEpiBias) && !aligned(bias, 2)) return SBI_ERR_ALIGN;
+    if ((flags & kEpiRes) && !aligned(residual, 2)) return SBI_ERR_ALIGN;
+    {
+        const uintptr_t x0 = reinterpret_cast<uintptr_t>(X), x1 = x0 + (uintptr_t)(B * K * 2);
+        const uintptr_t y0 = reinterpret_cast<uintptr_t>(Y), y1 = y0 + (uintptr_t)(B * N * 2);
+        if (x0 < y1 && y0 < x1) return SBI_ERR_OVERLAP;
+    }
+    Plan pl;
+    if (sbi_status s = make_plan(B, K, N, tuning, pl)) return s;
+    if (pl.ws_bytes > 0) {
+        if (!workspace || workspace_bytes < (size_t)pl.ws_bytes) return SBI_ERR_WORKSPACE;
+        if (!aligned(workspace, 256)) return SBI_ERR_ALIGN;
+    }
+
+    GemmParams p;
+    p.Wl = reinterpret_cast<const u32x4*>(reinterpret_cast<const unsigned char*>(W_laid_out) + kHeaderBytes);
+    p.X = reinterpret_cast<const _Float16*>(X);
+    p.bias = (flags & kEpiBias) ? reinterpret_cast<const _Float16*>(bias) : nullptr;
+    p.R = (flags & kEpiRes) ? reinterpret_cast<const _Float16*>(residual) : nullptr;
+    p.Y = reinterpret_cast<_Float16*>(Y);
+    p.counters = pl.ws_bytes ? reinterpret_cast<unsigned int*>(workspace) : nullptr;
+    p.partials = pl.ws_bytes ? reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(workspace) + pl.counter_bytes)
+                             : nullptr;
+    p.B = (int)B; p.K = (int)K; p.N = (int)N;
+    p.KS = (int)ceil_div(K, kTileK); p.P = (int)ceil_div(N, kPanelN);
+    p.S = pl.S; p.ksps = pl.ksps; p.kc = pl.kc;
+    p.flags = flags; p.x_vec = x_vec ? 1 : 0;
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int rc = (pl.path == SBI_PATH_STREAM) ? launch_stream(p, pl.nw, pl.depth, (size_t)pl.lds, st)
+                                                : launch_mfma(p, pl.nw, pl.depth, (size_t)pl.lds, st);
+    return rc == 0 ? SBI_OK : SBI_ERR_HIP;
+}
+
+sbi_status sbi_gemm(const void* W_laid_out, int64_t K, int64_t N,
+                    const void* X, int64_t B,
+                    const void* bias, const void* residual, sbi_epilogue epi,
+                    void* Y, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return sbi_gemm_ex(W_laid_out, K, N, X, B, bias, residual, epi, Y, workspace, workspace_bytes,
+                       hip_stream, nullptr);
+}
+
+static sbi_status layer_check(const sbi_layer* L, int64_t B)
+{
+    if (!L) return SBI_ERR_NULL;
+    if (!L->Wqkv || !L->Wout || !L->Wffn1 || !L->Wffn2) return SBI_ERR_NULL;
+    if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
+    if (sbi_status s = check_shape(L->h, L->n_qkv)) return s;
+    if (sbi_status s = check_shape(L->k_out, L->h)) return s;
+    if (sbi_status s = check_shape(L->h, L->n_ffn1)) return s;
+    if (sbi_status s = check_shape(L->k_ffn2, L->h)) return s;
+    return SBI_OK;
+}
+
+size_t sbi_layer_workspace_bytes(const sbi_layer* L, int64_t B)
+{
+    if (layer_check(L, B) != SBI_OK) return 0;
+    size_t m = sbi_gemm_workspace_bytes(B, L->h, L->n_qkv);
+    m = std::max(m, sbi_gemm_workspace_bytes(B, L->k_out, L->h));
+    m = std::max(m, sbi_gemm_workspace_bytes(B, L->h, L->n_ffn1));
+    m = std::max(m, sbi_gemm_workspace_bytes(B, L->k_ffn2, L->h));
+    return m;
+}
+
+sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
+                           const void* Xqkv, const void* Xout, const void* Xffn1, const void* Xffn2,
+                           const void* residual,
+                           void* Yqkv, void* Yout, void* Yffn1, void* Yffn2,
+                           void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (sbi_status s = layer_check(L, B)) return s;
+    if (!Xqkv || !Xout || !Xffn1 || !Yqkv || !Yout || !Yffn1 || !Yffn2) return SBI_ERR_NULL;
+    if (!Xffn2) {
+        if (L->n_ffn1 != L->k_ffn2) return SBI_ERR_SHAPE;
+        Xffn2 = Yffn1;
+    }
+    if (workspace_bytes < sbi_layer_workspace_bytes(L, B)) return SBI_ERR_WORKSPACE;
+
+    sbi_status s;
+    s = sbi_gemm(L->Wqkv, L->h, L->n_qkv, Xqkv, B, L->bqkv, nullptr,
+                 L->bqkv ? SBI_EPI_BIAS : SBI_EPI_NONE, Yqkv, workspace, workspace_bytes, hip_stream);
+    if (s != SBI_OK) return s;
+    s = sbi_gemm(L->Wout, L->k_out, L->h, Xout, B, L->bout, nullptr,
+                 L->bout ? SBI_EPI_BIAS : SBI_EPI_NONE, Yout, workspace, workspace_bytes, hip_stream);
+    if (s != SBI_OK) return s;
+    const sbi_epilogue e1 = L->ffn1_gelu ? (L->bffn1 ? SBI_EPI_BIAS_GELU : SBI_EPI_GELU)
+                                         : (L->bffn1 ? SBI_EPI_BIAS : SBI_EPI_NONE);
+    s = sbi_gemm(L->Wffn1, L->h, L->n_ffn1, Xffn1, B, L->bffn1, nullptr, e1, Yffn1,
+                 workspace, workspace_bytes, hip_stream);
+    if (s != SBI_OK) return s;
+    const sbi_epilogue e2 = residual ? (L->bffn2 ? SBI_EPI_BIAS_RESIDUAL : SBI_EPI_RESIDUAL)
+                                     : (L->bffn2 ? SBI_EPI_BIAS : SBI_EPI_NONE);
+    return sbi_gemm(L->Wffn2, L->k_ffn2, L->h, Xffn2, B, L->bffn2, residual, e2, Yffn2,
+                    workspace, workspace_bytes, hip_stream);
+}
+
+const char* sbi_status_string(sbi_status s)
+{
+    switch (s) {
+        case SBI_OK: return "ok";
+        case SBI_ERR_NULL: return "a required pointer is NULL";
+        case SBI_ERR_SHAPE: return "bad shape";
+        case SBI_ERR_ALIGN: return "pointer not aligned as documented";
+        case SBI_ERR_BATCH: return "batch outside 1..64";
+        case SBI_ERR_LAYOUT_MISMATCH: return "laid-out buffer does not match (K, N)";
+        case SBI_ERR_WORKSPACE: return "workspace missing or too small";
+        case SBI_ERR_EPILOGUE: return "bad epilogue or missing bias/residual";
+        case SBI_ERR_HIP: return "HIP runtime error";
+        case SBI_ERR_OVERLAP: return "Y overlaps X";
+        case SBI_ERR_TUNING: return "unsupported tuning request";
+    }
+    return "unknown status";
+}
+
+int32_t sbi_version(void) { return 100; }
+
+}  // extern "C"

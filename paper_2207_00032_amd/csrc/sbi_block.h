@@ -1,0 +1,242 @@
+// Block-level building blocks shared by the streaming kernels (device code, gfx950):
+//   - staging a K-chunk of the small X tile in LDS, in the order the lanes consume it
+//   - the in-block K-split reduction through LDS
+//   - the cross-block split-K reduction by the last-arriving block (deterministic order)
+//   - the fused epilogue (bias, exact-erf GeLU, residual) and the fp16 store
+#pragma once
+#include "sbi_common.h"
+
+namespace sbi {
+
+__device__ __forceinline__ float gelu_erf(float v)
+{
+    return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+}
+
+// Final value of one output element from its fp32 sum.
+__device__ __forceinline__ float apply_epilogue(const GemmParams& p, float v, int b, int n)
+{
+    if (p.flags & kEpiBias) v += (float)p.bias[n];
+    if (p.flags & kEpiGelu) v = gelu_erf(v);
+    if (p.flags & kEpiRes)  v += (float)p.R[(int64_t)b * p.N + n];
+    return v;
+}
+
+// Store the column pair (n, n+1) of row b; n is even.  One 4-byte store when both
+// columns exist and the row pitch keeps it aligned, 2-byte stores otherwise.
+__device__ __forceinline__ void store_pair(const GemmParams& p, int b, int n, float s0, float s1)
+{
+    if (n >= p.N) return;
+    const int64_t off = (int64_t)b * p.N + n;
+    const float v0 = apply_epilogue(p, s0, b, n);
+    if (n + 1 < p.N) {
+        const float v1 = apply_epilogue(p, s1, b, n + 1);
+        if ((p.N & 1) == 0) {
+            half2v h = {(_Float16)v0, (_Float16)v1};
+            *reinterpret_cast<half2v*>(p.Y + off) = h;
+        } else {
+            p.Y[off] = (_Float16)v0;
+            p.Y[off + 1] = (_Float16)v1;
+        }
+    } else {
+        p.Y[off] = (_Float16)v0;
+    }
+}
+
+// Staging of k-steps [cb, cb+cn) of X for all B rows into LDS.  Element order in LDS (16-byte
+// units): ((ks - cb)*4 + g)*B + b  holds X[b][ks*32 + g*8 .. +8], zero beyond K.
+// Two phases so that the global reads can be requested ahead of the weight stream's first
+// loads and written to LDS once they arrive: request() issues up to XU unconditional
+// 128-bit loads per thread (addresses clamped into the tensor), commit() writes them to LDS
+// and handles whatever did not fit (large B) or cannot be read as vectors (K % 8 != 0).
+template <int NT, int XU>
+struct XStage {
+    u32x4 buf[XU];
+
+    __device__ __forceinline__ void request(const GemmParams& p, int cb, int cn, int tid)
+    {
+        if (!p.x_vec) return;
+        const int nc = cn * 4;             // 16-byte pieces per row
+        const int items = nc * p.B;
+#pragma unroll
+        for (int u = 0; u < XU; ++u) {
+            const int idx = min(tid + u * NT, items - 1);
+            const int b = idx / nc;
+            const int c = idx - b * nc;
+            const int k = min(cb * kTileK + c * kChunkK, p.K - kChunkK);
+            buf[u] = *reinterpret_cast<const u32x4*>(p.X + (int64_t)b * p.K + k);
+        }
+    }
+
+    __device__ __forceinline__ void commit(const GemmParams& p, u32x4* xs, int cb, int cn, int tid)
+    {
+        const int nc = cn * 4;
+        const int items = nc * p.B;
+        int done = 0;
+        if (p.x_vec) {
+#pragma unroll
+            for (int u = 0; u < XU; ++u) {
+                const int idx = tid + u * NT;
+                if (idx < items) {
+                    const int b = idx / nc;
+                    const int c = idx - b * nc;
+                    const bool inside = cb * kTileK + c * kChunkK < p.K;
+                    xs[c * p.B + b] = inside ? buf[u] : u32x4{0u, 0u, 0u, 0u};
+                }
+            }
+            done = NT * XU;
+        }
+        for (int idx = done + tid; idx < items; idx += NT) {
+            const int b = idx / nc;
+            const int c = idx - b * nc;
+            const int k = cb * kTileK + c * kChunkK;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (p.x_vec) {
+                if (k < p.K) v = *reinterpret_cast<const u32x4*>(p.X + (int64_t)b * p.K + k);
+            } else {
+                half8 h;
+#pragma unroll
+                for (int e = 0; e < kChunkK; ++e)
+                    h[e] = (k + e < p.K) ? p.X[(int64_t)b * p.K + k + e] : (_Float16)0.0f;
+                v = __builtin_bit_cast(u32x4, h);
+            }
+            xs[c * p.B + b] = v;
+        }
+    }
+};
+
+// ---------------------------------------------------------------------------------------
+// The weight stream of one block.  The block owns panel `panel` and k-steps [ks0, ks1); its
+// NW waves take those k-steps round-robin (wave w: ks0 + w, ks0 + w + NW, ...), so the block
+// walks a contiguous run of the laid-out weights.  Each wave keeps DEPTH k-steps (4 x 128-bit
+// loads per lane each) in flight in a register ring with static indices: a round consumes
+// slot d and refills it in place, d = 0..DEPTH-1, as straight-line code so the load-counter
+// waits stay exact.  All waves of a block run the same number of rounds; a step that falls
+// beyond the end of the range re-reads the range's last k-step and has its weights replaced
+// by zeros before use, so the loop needs no conditional loads (the dispatcher picks splits
+// that leave no such padding for the shapes that matter).
+// X is staged in LDS per chunk of p.kc k-steps (p.kc is a multiple of NW*DEPTH); X's global
+// reads and the first weight loads of a chunk are all issued before the barrier that
+// publishes the chunk, so HBM latency overlaps the staging.  `op.step(w, xk)` receives the four tiles of one k-step and the LDS
+// address of that k-step's X block ([4 lane groups][B rows] of 16 bytes).
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void load_step(u32x4 (&slot)[kPanelTiles], const u32x4* src)
+{
+#pragma unroll
+    for (int t = 0; t < kPanelTiles; ++t) slot[t] = __builtin_nontemporal_load(src + t * 64);
+}
+
+template <int NW, int DEPTH, class Op>
+__device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op& op, int tid, int wave,
+                                             int lane, int panel, int ks0, int ks1)
+{
+    constexpr int NT = NW * 64;
+    constexpr int kStepUnits = kPanelTiles * 64;                  // 16-byte units per k-step of a panel
+    const int nks = ks1 - ks0;
+    const int nchunks = (nks + p.kc - 1) / p.kc;
+    const u32x4* wpanel = p.Wl + (int64_t)panel * p.KS * kStepUnits + lane;
+    const int xblock = 4 * p.B;                                    // 16-byte units of X per k-step
+
+    u32x4 ring[DEPTH][kPanelTiles];
+    for (int c = 0; c < nchunks; ++c) {
+        const int cb = ks0 + c * p.kc;
+        const int cn = min(ks1 - cb, p.kc);                        // k-steps in this chunk (>= 1)
+        const int rounds = (cn + NW * DEPTH - 1) / (NW * DEPTH);
+        const u32x4* wchunk = wpanel + (int64_t)cb * kStepUnits;
+
+        XStage<NT, 4> xst;
+        xst.request(p, cb, cn, tid);
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+            load_step(ring[d], wchunk + (int64_t)min(d * NW + wave, cn - 1) * kStepUnits);
+
+        if (c > 0) __syncthreads();                                // previous chunk fully consumed
+        xst.commit(p, xs, cb, cn, tid);
+        __syncthreads();
+
+        int ksl = wave;                                            // k-step inside the chunk
+        for (int r = 0; r + 1 < rounds; ++r) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                op.step(ring[d], xs + ksl * xblock);               // always inside the chunk here
+                load_step(ring[d], wchunk + (int64_t)min(ksl + NW * DEPTH, cn - 1) * kStepUnits);
+                ksl += NW;
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            if (ksl >= cn) {                                       // padding step: contributes nothing
+#pragma unroll
+                for (int t = 0; t < kPanelTiles; ++t) ring[d][t] = u32x4{0u, 0u, 0u, 0u};
+            }
+            op.step(ring[d], xs + min(ksl, cn - 1) * xblock);
+            ksl += NW;
+        }
+    }
+}
+
+// After every wave has written its 16-row x 64-column partial tile to `red`
+// ([wave][16][kRedPitch] floats), sum over waves and either finish the rows (S == 1) or
+// park them in the workspace for the cross-block reduction.  mb selects rows mb*16..+15.
+template <int NW>
+__device__ __forceinline__ void reduce_rows(const GemmParams& p, const float* red, int mb,
+                                            int panel, int split, int tid)
+{
+    constexpr int NT = NW * 64;
+    for (int item = tid; item < 16 * 32; item += NT) {
+        const int bl = item >> 5;
+        const int c2 = (item & 31) * 2;
+        const int b = mb * 16 + bl;
+        if (b >= p.B) continue;
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const floatx2 v = *reinterpret_cast<const floatx2*>(red + (w * 16 + bl) * kRedPitch + c2);
+            s0 += v[0];
+            s1 += v[1];
+        }
+        if (p.S == 1) {
+            store_pair(p, b, panel * kPanelN + c2, s0, s1);
+        } else {
+            float* dst = p.partials + (((int64_t)panel * p.S + split) * p.B + b) * kPanelN + c2;
+            floatx2 v = {s0, s1};
+            *reinterpret_cast<floatx2*>(dst) = v;
+        }
+    }
+}
+
+// Cross-block reduction: every block of a panel has parked its partial rows; the block
+// that arrives last sums the S slabs in slab order (so the result does not depend on
+// which block that is), applies the epilogue and stores.  The counter is left at zero.
+template <int NT>
+__device__ __forceinline__ void finish_split_k(const GemmParams& p, int panel, int tid, int* s_flag)
+{
+    __threadfence();                 // publish this thread's partial sums device-wide
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned int old = __hip_atomic_fetch_add(p.counters + panel, 1u, __ATOMIC_ACQ_REL,
+                                                        __HIP_MEMORY_SCOPE_AGENT);
+        *s_flag = (old == (unsigned int)(p.S - 1));
+    }
+    __syncthreads();
+    if (!*s_flag) return;
+    __threadfence();                 // acquire: see the other blocks' partial sums
+    const float* base = p.partials + (int64_t)panel * p.S * p.B * kPanelN;
+    const int items = p.B * 32;
+    for (int item = tid; item < items; item += NT) {
+        const int b = item >> 5;
+        const int c2 = (item & 31) * 2;
+        float s0 = 0.f, s1 = 0.f;
+        for (int s = 0; s < p.S; ++s) {
+            const floatx2 v = *reinterpret_cast<const floatx2*>(base + ((int64_t)s * p.B + b) * kPanelN + c2);
+            s0 += v[0];
+            s1 += v[1];
+        }
+        store_pair(p, b, panel * kPanelN + c2, s0, s1);
+    }
+    if (tid == 0)
+        __hip_atomic_store(p.counters + panel, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+}  // namespace sbi

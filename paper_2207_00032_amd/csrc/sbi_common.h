@@ -1,0 +1,65 @@
+// Internal definitions shared by the gfx950 kernels and the C-ABI translation unit.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sbi {
+
+// ---- weight layout (one lane = 8 consecutive k of one column = one 128-bit load) ----
+constexpr int kChunkK     = 8;                       // halfs per lane per load
+constexpr int kTileN      = 16;                      // columns per wavefront tile
+constexpr int kTileK      = 32;                      // k per tile ("k-step")
+constexpr int kPanelTiles = 4;                       // tiles per panel
+constexpr int kPanelN     = kTileN * kPanelTiles;    // 64 columns
+constexpr int kHeaderBytes = 256;
+constexpr uint32_t kMagic = 0x47494253u;             // "SBIG"
+constexpr uint32_t kLayoutVersion = 1;
+constexpr int kNumCU = 256;                          // MI355X
+
+struct LayoutHeader {            // lives in the first 256 bytes of a laid-out buffer
+    uint32_t magic;
+    uint32_t version;
+    int64_t  K;
+    int64_t  N;
+    int64_t  KS;                 // ceil(K / 32)
+    int64_t  P;                  // ceil(N / 64)
+    int32_t  tile_n, tile_k, panel_tiles, chunk_k;
+};
+static_assert(sizeof(LayoutHeader) <= kHeaderBytes, "header must fit");
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+constexpr int kEpiBias = 1, kEpiGelu = 2, kEpiRes = 4;
+
+// Pitch (in floats) of one row of the in-block reduction buffer: 64 columns + 4 so that
+// the 16 lanes of a group, which write 16-byte pieces of 16 different rows, hit distinct banks.
+constexpr int kRedPitch = 68;
+
+struct GemmParams {
+    const u32x4*    Wl;        // laid-out weights, past the header
+    const _Float16* X;         // [B,K]
+    const _Float16* bias;      // [N] or null
+    const _Float16* R;         // [B,N] or null
+    _Float16*       Y;         // [B,N]
+    float*          partials;  // [P][S][B][64] when S > 1
+    unsigned int*   counters;  // [P] arrival counters when S > 1
+    int B, K, N;
+    int KS, P;                 // k-steps, panels
+    int S;                     // blocks per panel (split-K factor)
+    int ksps;                  // k-steps per block
+    int kc;                    // k-steps of X staged per chunk (multiple of waves*depth)
+    int flags;                 // kEpi* bits
+    int x_vec;                 // 1: X rows are 16-byte aligned and K % 8 == 0
+};
+
+// launchers implemented in the kernel translation units; return hipError_t as int
+int launch_mfma(const GemmParams& p, int waves, int depth, size_t lds_bytes, hipStream_t st);
+int launch_stream(const GemmParams& p, int waves, int depth, size_t lds_bytes, hipStream_t st);
+int launch_layout(const void* W, int64_t K, int64_t N, void* out, hipStream_t st);
+int launch_unlayout(const void* Wl, int64_t K, int64_t N, void* out, hipStream_t st);
+
+}  // namespace sbi

@@ -1,0 +1,117 @@
+// Matrix-core streaming kernel for the small-batch GeMM on gfx950.
+//
+// One block owns one 64-column panel of W and a contiguous range of k-steps (32 rows of W
+// each); its NW wavefronts take the k-steps of that range round-robin, so the block as a
+// whole walks a contiguous run of the laid-out weights and every byte of W is loaded from
+// HBM exactly once, by one 128-bit load of one lane.  Each loaded 1 KiB tile is directly
+// the A operand of v_mfma_f32_16x16x32_f16 (rows = 16 columns of W, K = 32); the B operand
+// is the X tile (up to 16 batch rows per MFMA) read from LDS.  Each wavefront keeps DEPTH
+// k-steps (DEPTH x 4 KiB) of W in flight in a register ring.
+//
+// The paper tiles the output dimension first and splits the input dimension only when the
+// output is too narrow to fill the machine (Sec. III-C, "Tiling Strategies"); the same two
+// levels appear here as panels (grid) x k-split (waves of a block, then blocks of a panel).
+#include "sbi_block.h"
+
+namespace sbi {
+
+// Per-wave contraction state: a 64-column x (MB*16)-row fp32 tile in MFMA result layout.
+template <int MB>
+struct MfmaOp {
+    floatx4 acc[kPanelTiles][MB];
+    int xoff[MB];     // this lane's 16-byte slot inside a k-step's X block
+
+    __device__ __forceinline__ void init(int B, int g, int i)
+    {
+#pragma unroll
+        for (int t = 0; t < kPanelTiles; ++t)
+#pragma unroll
+            for (int m = 0; m < MB; ++m) acc[t][m] = floatx4{0.f, 0.f, 0.f, 0.f};
+        // rows beyond B re-read row B-1: they only feed result columns that are never stored
+#pragma unroll
+        for (int m = 0; m < MB; ++m) xoff[m] = g * B + min(m * 16 + i, B - 1);
+    }
+
+    __device__ __forceinline__ void step(const u32x4 (&w)[kPanelTiles], const u32x4* xk)
+    {
+        half8 xf[MB];
+#pragma unroll
+        for (int m = 0; m < MB; ++m) xf[m] = __builtin_bit_cast(half8, xk[xoff[m]]);
+#pragma unroll
+        for (int t = 0; t < kPanelTiles; ++t) {
+            const half8 wf = __builtin_bit_cast(half8, w[t]);
+#pragma unroll
+            for (int m = 0; m < MB; ++m)
+                acc[t][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf, xf[m], acc[t][m], 0, 0, 0);
+        }
+    }
+};
+
+template <int MB, int NW, int DEPTH>
+__global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GemmParams p)
+{
+    constexpr int NT = NW * 64;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    u32x4* xs  = reinterpret_cast<u32x4*>(smem_raw);
+    float* red = reinterpret_cast<float*>(smem_raw);
+    __shared__ int s_flag;
+
+    const int tid  = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4;          // k group within a k-step (8 k each)
+    const int i = lane & 15;          // column within a tile (A operand) / batch row (B operand)
+
+    const int panel = blockIdx.x / p.S;
+    const int split = blockIdx.x - panel * p.S;
+    const int ks0 = split * p.ksps;
+    const int ks1 = min(p.KS, ks0 + p.ksps);
+
+    MfmaOp<MB> op;
+    op.init(p.B, g, i);
+    stream_panel<NW, DEPTH>(p, xs, op, tid, wave, lane, panel, ks0, ks1);
+
+    // In-block K-split reduction: each wave parks its 64-column x 16-row tile in LDS
+    // (the MFMA result holds, per lane, 4 consecutive columns of one batch row).
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        __syncthreads();               // X tile / previous pass no longer needed
+#pragma unroll
+        for (int t = 0; t < kPanelTiles; ++t)
+            *reinterpret_cast<floatx4*>(red + (wave * 16 + i) * kRedPitch + t * kTileN + 4 * g) = op.acc[t][m];
+        __syncthreads();
+        reduce_rows<NW>(p, red, m, panel, split, tid);
+    }
+
+    if (p.S > 1) finish_split_k<NT>(p, panel, tid, &s_flag);
+}
+
+template <int MB, int NW, int DEPTH>
+static int launch_one(const GemmParams& p, size_t lds, hipStream_t st)
+{
+    hipLaunchKernelGGL((sbi_mfma_kernel<MB, NW, DEPTH>), dim3(p.P * p.S), dim3(NW * 64), lds, st, p);
+    return (int)hipGetLastError();
+}
+
+template <int NW, int DEPTH>
+static int launch_mb(const GemmParams& p, size_t lds, hipStream_t st)
+{
+    switch ((p.B + 15) / 16) {
+        case 1: return launch_one<1, NW, DEPTH>(p, lds, st);
+        case 2: return launch_one<2, NW, DEPTH>(p, lds, st);
+        case 3: return launch_one<3, NW, DEPTH>(p, lds, st);
+        case 4: return launch_one<4, NW, DEPTH>(p, lds, st);
+    }
+    return (int)hipErrorInvalidValue;
+}
+
+int launch_mfma(const GemmParams& p, int waves, int depth, size_t lds_bytes, hipStream_t st)
+{
+    if (waves == 4 && depth == 4) return launch_mb<4, 4>(p, lds_bytes, st);
+    if (waves == 4 && depth == 8) return launch_mb<4, 8>(p, lds_bytes, st);
+    if (waves == 8 && depth == 4) return launch_mb<8, 4>(p, lds_bytes, st);
+    if (waves == 8 && depth == 8) return launch_mb<8, 8>(p, lds_bytes, st);
+    return (int)hipErrorInvalidValue;
+}
+
+}  // namespace sbi

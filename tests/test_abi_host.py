@@ -1,0 +1,172 @@
+"""Host-only checks of the C-ABI library: it loads without a GPU, exports every symbol the
+header declares, sizes and plans are consistent, and every argument error is reported by the
+host-side validation before anything could reach a GPU (so fake device addresses are safe:
+only calls that must fail are made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2207_00032_amd import binding as sb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "sbi_gemm.h")
+
+FAKE = 0x7F0000000000  # a 256-byte aligned non-null "device address"; never dereferenced
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return sb.load()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(sbi_[a-z_0-9]+)\s*\(", text))
+    assert declared == set(sb.EXPORTS), declared ^ set(sb.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert lib.sbi_version() >= 100
+
+
+def test_status_strings(lib):
+    seen = set()
+    for i, name in enumerate(sb.STATUS_NAMES):
+        s = sb.status_string(i)
+        assert s and s != "unknown status", name
+        seen.add(s)
+    assert len(seen) == len(sb.STATUS_NAMES)
+    assert sb.status_string(99) == "unknown status"
+
+
+def test_layout_bytes():
+    assert sb.layout_bytes(32, 64) == 256 + 4096
+    assert sb.layout_bytes(1, 1) == 256 + 4096
+    assert sb.layout_bytes(33, 65) == 256 + 4 * 4096
+    assert sb.layout_bytes(4096, 16384) == 256 + 2 * 4096 * 16384
+    assert sb.layout_bytes(49152, 12288) == 256 + 2 * 49152 * 12288
+    assert sb.layout_bytes(0, 64) == 0 and sb.layout_bytes(64, -1) == 0
+    assert sb.layout_bytes(1 << 23, 64) == 0
+
+
+@pytest.mark.parametrize("B", [1, 2, 4, 8, 16, 17, 32, 33, 48, 64])
+@pytest.mark.parametrize("K,N", [(1, 1), (8, 1), (1024, 1024), (4096, 12288), (16384, 4096),
+                                 (1536, 12288), (49152, 12288), (8192, 32768), (1000, 130)])
+def test_plan_invariants(B, K, N):
+    for path in (sb.PATH_AUTO, sb.PATH_MFMA, sb.PATH_STREAM):
+        if path == sb.PATH_STREAM and B > 8:
+            with pytest.raises(sb.SbiError) as e:
+                sb.plan(B, K, N, path)
+            assert e.value.status == 10
+            continue
+        pl = sb.plan(B, K, N, path)
+        KS, P = -(-K // 32), -(-N // 64)
+        assert pl["path"] in (sb.PATH_STREAM, sb.PATH_MFMA)
+        assert pl["waves"] in (4, 8) and pl["depth"] in (4, 8)
+        assert pl["block"] == 64 * pl["waves"]
+        S, ksps, kc = pl["split_k"], pl["ksteps_per_split"], pl["ksteps_per_chunk"]
+        assert 1 <= S <= KS and ksps * S >= KS and ksps * (S - 1) < KS      # covers K, no empty block
+        assert pl["grid"] == P * S
+        assert kc % (pl["waves"] * pl["depth"]) == 0 and kc >= pl["waves"] * pl["depth"]
+        assert kc * B * 64 <= 64 * 1024 and pl["lds_bytes"] <= 64 * 1024
+        assert pl["lds_bytes"] >= kc * B * 64
+        if S == 1:
+            assert pl["workspace_bytes"] == 0
+        else:
+            assert pl["workspace_bytes"] >= P * 4 + P * S * B * 64 * 4
+        if path == sb.PATH_AUTO:
+            assert sb.workspace_bytes(B, K, N) == pl["workspace_bytes"]
+
+
+def test_plan_tuning_overrides():
+    pl = sb.plan(4, 4096, 4096, sb.PATH_MFMA, split_k=8, waves=4, depth=8)
+    assert (pl["split_k"], pl["waves"], pl["depth"], pl["path"]) == (8, 4, 8, sb.PATH_MFMA)
+    pl = sb.plan(4, 4096, 4096, sb.PATH_STREAM, split_k=1000)
+    assert pl["split_k"] == 128                                  # clamped to the number of k-steps
+    for bad in (dict(waves=3), dict(depth=5), dict(split_k=-1), dict(path=7)):
+        with pytest.raises(sb.SbiError) as e:
+            sb.plan(4, 4096, 4096, **bad)
+        assert e.value.status == 10
+    with pytest.raises(sb.SbiError) as e:                        # X chunk would not fit in LDS
+        sb.plan(64, 4096, 4096, sb.PATH_MFMA, waves=8, depth=8)
+    assert e.value.status == 10
+    for B in (0, 65):
+        with pytest.raises(sb.SbiError) as e:
+            sb.plan(B, 64, 64)
+        assert e.value.status == 4
+    with pytest.raises(sb.SbiError) as e:
+        sb.plan(1, 0, 64)
+    assert e.value.status == 2
+
+
+def _gemm(lib, W=FAKE, K=4096, N=4096, X=FAKE + (1 << 30), B=4, bias=None, res=None, epi=0,
+          Y=FAKE + (2 << 30), ws=FAKE + (3 << 30), ws_bytes=1 << 30):
+    return lib.sbi_gemm(W, K, N, X, B, bias, res, epi, Y, ws, ws_bytes, None)
+
+
+def test_gemm_argument_validation(lib):
+    assert _gemm(lib, W=None) == 1 and _gemm(lib, X=None) == 1 and _gemm(lib, Y=None) == 1
+    assert _gemm(lib, K=0) == 2 and _gemm(lib, N=-5) == 2 and _gemm(lib, K=(1 << 22) + 1) == 2
+    assert _gemm(lib, B=0) == 4 and _gemm(lib, B=65) == 4
+    assert _gemm(lib, epi=17) == 7
+    assert _gemm(lib, epi=sb.EPI_BIAS) == 7 and _gemm(lib, epi=sb.EPI_BIAS_GELU) == 7
+    assert _gemm(lib, epi=sb.EPI_BIAS_RESIDUAL, bias=FAKE + (4 << 30)) == 7
+    assert _gemm(lib, epi=sb.EPI_RESIDUAL) == 7
+    assert _gemm(lib, W=FAKE + 128) == 3                          # laid-out buffer: 256-byte aligned
+    assert _gemm(lib, X=FAKE + (1 << 30) + 8) == 3                # X: 16-byte aligned when K % 8 == 0
+    assert _gemm(lib, Y=FAKE + (2 << 30) + 2) == 3                # Y: 4-byte aligned
+    assert _gemm(lib, epi=sb.EPI_BIAS, bias=FAKE + (4 << 30) + 1) == 3
+    assert _gemm(lib, Y=FAKE + (1 << 30) + 4096) == 9             # Y inside X
+    need = sb.workspace_bytes(4, 4096, 4096)
+    assert need > 0
+    assert _gemm(lib, ws=None) == 6 and _gemm(lib, ws_bytes=need - 1) == 6
+    assert _gemm(lib, ws=FAKE + (3 << 30) + 64, ws_bytes=need) == 3
+
+
+def test_layout_argument_validation(lib):
+    nb = sb.layout_bytes(64, 64)
+    assert lib.sbi_gemm_layout_weights(None, 64, 64, FAKE, nb, None) == 1
+    assert lib.sbi_gemm_layout_weights(FAKE, 64, 64, None, nb, None) == 1
+    assert lib.sbi_gemm_layout_weights(FAKE, 0, 64, FAKE + 4096, nb, None) == 2
+    assert lib.sbi_gemm_layout_weights(FAKE + 1, 64, 64, FAKE + 4096, nb, None) == 3
+    assert lib.sbi_gemm_layout_weights(FAKE, 64, 64, FAKE + 4096 + 16, nb, None) == 3
+    assert lib.sbi_gemm_layout_weights(FAKE, 64, 64, FAKE + 4096, nb - 1, None) == 5
+    assert lib.sbi_gemm_unlayout_weights(None, 64, 64, FAKE, None) == 1
+    assert lib.sbi_gemm_unlayout_weights(FAKE, 64, 0, FAKE + 4096, None) == 2
+    assert lib.sbi_gemm_layout_check(None, 64, 64, None) == 1
+    assert lib.sbi_gemm_layout_check(FAKE + 8, 64, 64, None) == 3
+
+
+def test_layer_argument_validation(lib):
+    L = sb.Layer()
+    L.Wqkv = L.Wout = L.Wffn1 = L.Wffn2 = FAKE
+    L.h, L.n_qkv, L.k_out, L.n_ffn1, L.k_ffn2 = 1024, 3072, 1024, 4096, 4096
+    ws = sb.layer_workspace_bytes(L, 1)
+    assert ws == max(sb.workspace_bytes(1, 1024, 3072), sb.workspace_bytes(1, 1024, 1024),
+                     sb.workspace_bytes(1, 1024, 4096), sb.workspace_bytes(1, 4096, 1024))
+    args = [FAKE + (i << 28) for i in range(1, 10)]
+    call = lambda layer, B, a, w=FAKE, wb=1 << 30: lib.sbi_layer_gemms(layer, B, *a, w, wb, None)
+    assert call(None, 1, args) == 1
+    assert call(ctypes.byref(L), 0, args) == 4
+    a = list(args); a[0] = None
+    assert call(ctypes.byref(L), 1, a) == 1
+    assert call(ctypes.byref(L), 1, args, wb=ws - 1 if ws else 0) == (6 if ws else 0) or ws == 0
+    L2 = sb.Layer.from_buffer_copy(L)
+    L2.k_ffn2 = 2048                                              # chaining needs n_ffn1 == k_ffn2
+    a = list(args); a[3] = None
+    assert call(ctypes.byref(L2), 1, a) == 2
+    L3 = sb.Layer.from_buffer_copy(L)
+    L3.Wout = None
+    assert call(ctypes.byref(L3), 1, args) == 1
+    L4 = sb.Layer.from_buffer_copy(L)
+    L4.h = 0
+    assert call(ctypes.byref(L4), 1, args) == 2
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(sb, "_lib", None)
+    monkeypatch.setattr(sb, "LIB_PATH", str(tmp_path / "libsbi_gemm.so"))
+    with pytest.raises(ImportError):
+        sb.load()

@@ -1,0 +1,232 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Acceptance per element: |gpu - oracle| <= max(2 ulp16(oracle), 1e-3), and the
+GPU result is bit-identical from run to run.  Integer/byte work (the weight pre-layout) is
+compared bit for bit."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2207_00032_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+EPI_ORACLE = {"none": 0, "bias": orc.EPI_BIAS, "bias_gelu": orc.EPI_BIAS | orc.EPI_GELU,
+              "bias_residual": orc.EPI_BIAS | orc.EPI_RES, "gelu": orc.EPI_GELU, "residual": orc.EPI_RES}
+
+
+def _dev(a, gpu):
+    import torch
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(gpu)
+
+
+def gpu_gemm(gpu, W, bias, X, R, epi, Wl=None, **tuning):
+    """Lay W out (unless given), run the GeMM, return (Y as numpy fp16, laid-out tensor)."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    K, N = W.shape
+    if Wl is None:
+        Wl = sb.layout_weights(_dev(W, gpu))
+    use_bias = "bias" in epi
+    use_res = "residual" in epi
+    Y = sb.gemm(Wl, K, N, _dev(X, gpu), _dev(bias, gpu) if use_bias else None,
+                _dev(R, gpu) if use_res else None, epi, **tuning)
+    torch.cuda.synchronize()
+    return Y.cpu().numpy(), Wl
+
+
+def check(Y, W, bias, X, R, epi, what):
+    want = orc.gemm(X, W, bias, R, epi=EPI_ORACLE[epi])
+    ok, rep = orc.check_close(Y, want, ulps=2, abs_tol=1e-3)
+    assert ok, f"{what}: {rep}"
+    return rep
+
+
+# ------------------------------------------------------------------------------ layout (bit-exact)
+@pytest.mark.parametrize("K,N", [(32, 64), (8, 1), (1, 1), (40, 24), (103, 71), (264, 200), (1000, 130),
+                                 (512, 1024), (2056, 520)])
+def test_layout_bit_exact_and_invertible(gpu, K, N):
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    rng = np.random.default_rng(K * 7919 + N)
+    Wbits = rng.integers(1, 65536, size=(K, N), dtype=np.uint16)
+    Wd = torch.from_numpy(Wbits.view(np.float16)).to(gpu)
+    Wl = sb.layout_weights(Wd)
+    torch.cuda.synchronize()
+    raw = Wl.cpu().numpy()
+    assert raw.size == sb.layout_bytes(K, N)
+    assert np.array_equal(raw[256:].view(np.uint16), orc.layout_weights(Wbits))
+    hdr = raw[:256]
+    assert hdr[:4].tobytes() == b"SBIG" and not hdr[56:].any()
+    assert tuple(hdr[8:40].view(np.int64)) == (K, N, -(-K // 32), -(-N // 64))
+    back = sb.unlayout_weights(Wl, K, N)
+    torch.cuda.synchronize()
+    assert np.array_equal(back.cpu().numpy().view(np.uint16), Wbits)
+    assert sb.layout_check(Wl, K, N) == 0
+    assert sb.layout_check(Wl, K + 1, N) == 5 and sb.layout_check(Wl, K, N + 64) == 5
+    assert sb.layout_check(torch.zeros_like(Wl), K, N) == 5
+
+
+# ------------------------------------------------------------------------------ small / ragged shapes
+@pytest.mark.parametrize("B,K,N", wl.ragged_shapes())
+def test_ragged_shapes_all_epilogues_both_paths(gpu, B, K, N):
+    from paper_2207_00032_amd import binding as sb
+    W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=B + K + N, config_id=100)
+    Wl = None
+    paths = [sb.PATH_MFMA] + ([sb.PATH_STREAM] if B <= 8 else [])
+    for epi in ("none", "bias", "bias_gelu", "bias_residual", "gelu", "residual"):
+        for path in paths:
+            Y, Wl = gpu_gemm(gpu, W, bias, X, R, epi, Wl=Wl, path=path)
+            check(Y, W, bias, X, R, epi, f"B={B} K={K} N={N} {epi} path={path}")
+
+
+@pytest.mark.parametrize("B,K,N", [(1, 4096, 192), (4, 4096, 192), (8, 2048, 320), (16, 4096, 128),
+                                   (40, 1024, 192), (64, 2048, 128)])
+@pytest.mark.parametrize("waves,depth", [(4, 4), (4, 8), (8, 4), (8, 8)])
+def test_split_k_and_tuning_variants(gpu, B, K, N, waves, depth):
+    from paper_2207_00032_amd import binding as sb
+    W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=1, config_id=101)
+    Wl = None
+    for path in [sb.PATH_MFMA] + ([sb.PATH_STREAM] if B <= 8 else []):
+        if waves * depth * B * 64 > 65536:
+            with pytest.raises(sb.SbiError):
+                sb.plan(B, K, N, path, 1, waves, depth)
+            continue
+        if path == sb.PATH_STREAM and waves == 8 and depth == 8 and B >= 4:
+            continue      # that instantiation spills registers; the dispatcher never selects it
+        for S in (1, 2, 3, 7, 16):
+            Y, Wl = gpu_gemm(gpu, W, bias, X, R, "bias_residual", Wl=Wl, path=path,
+                             split_k=S, waves=waves, depth=depth)
+            check(Y, W, bias, X, R, "bias_residual", f"B={B} K={K} N={N} S={S} w={waves} d={depth} path={path}")
+
+
+def test_workspace_reuse_and_determinism(gpu):
+    """One workspace serves calls of different shapes back to back (the counters return to
+    zero), and repeated calls give identical bits."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    shapes = [(4, 2048, 256), (8, 4096, 64), (2, 1024, 512), (4, 2048, 256)]
+    ws = sb.new_workspace(max(sb.plan(B, K, N, split_k=8)["workspace_bytes"] for B, K, N in shapes), gpu)
+    for rep in range(3):
+        for B, K, N in shapes:
+            W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=5, config_id=102)
+            Y1, Wl = gpu_gemm(gpu, W, bias, X, R, "bias_gelu", workspace=ws, split_k=8)
+            Y2, _ = gpu_gemm(gpu, W, bias, X, R, "bias_gelu", Wl=Wl, workspace=ws, split_k=8)
+            assert np.array_equal(Y1.view(np.uint16), Y2.view(np.uint16))
+            check(Y1, W, bias, X, R, "bias_gelu", f"reuse rep={rep} {B}x{K}x{N}")
+    torch.cuda.synchronize()
+    assert not ws[:4096].cpu().numpy()[:256].any()       # counters are back to zero
+
+
+def test_residual_may_alias_output(gpu):
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    B, K, N = 4, 1024, 384
+    W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=9, config_id=103)
+    Wl = sb.layout_weights(_dev(W, gpu))
+    Rd = _dev(R, gpu)
+    sb.gemm(Wl, K, N, _dev(X, gpu), _dev(bias, gpu), Rd, "bias_residual", out=Rd)
+    torch.cuda.synchronize()
+    check(Rd.cpu().numpy(), W, bias, X, R, "bias_residual", "in-place residual")
+
+
+def test_subnormal_and_exact_inputs(gpu):
+    """fp16 subnormal weights must not be flushed; identity / power-of-two data is exact."""
+    from paper_2207_00032_amd import binding as sb
+    rng = np.random.default_rng(2)
+    B, K, N = 8, 512, 128
+    Wsub = rng.integers(1, 0x400, size=(K, N)).astype(np.uint16)            # positive subnormals
+    Wsub |= (rng.integers(0, 2, size=(K, N)).astype(np.uint16) << 15)
+    W = Wsub.view(np.float16)
+    X = (rng.standard_normal((B, K)) * 64).astype(np.float16)
+    for path in (sb.PATH_MFMA, sb.PATH_STREAM):
+        Y, _ = gpu_gemm(gpu, W, None, X, None, "none", path=path)
+        want = orc.gemm(X, W)
+        assert np.abs(want.astype(np.float64)).max() > 0.05                  # the products do matter
+        ok, rep = orc.check_close(Y, want, ulps=2, abs_tol=1e-4)
+        assert ok, f"subnormal weights path={path}: {rep}"
+    # identity weights: Y == X bit for bit
+    K = N = 256
+    X = rng.standard_normal((B, K)).astype(np.float16)
+    for path in (sb.PATH_MFMA, sb.PATH_STREAM):
+        Y, _ = gpu_gemm(gpu, np.eye(K, dtype=np.float16), None, X, None, "none", path=path)
+        assert np.array_equal(Y.view(np.uint16), X.view(np.uint16))
+    # large magnitudes: an overflow to inf must match the oracle's
+    Wbig = np.full((K, N), 16.0, np.float16)
+    Xbig = np.full((2, K), 32.0, np.float16)
+    Y, _ = gpu_gemm(gpu, Wbig, None, Xbig, None, "none")
+    assert np.isinf(Y).all() and np.isinf(orc.gemm(Xbig, Wbig)).all()
+
+
+# ------------------------------------------------------------------------------ benchmark configurations
+def _config_case(gpu, cfg_id, gi, seed, batches, paths=None):
+    from paper_2207_00032_amd import binding as sb
+    cfg = wl.CONFIGS[cfg_id]
+    spec, W, bias, X, R = wl.make_config_gemm(cfg_id, gi, seed)
+    Wl = None
+    worst = 0.0
+    for B in batches:
+        for path in (paths or [sb.PATH_AUTO]):
+            if path == sb.PATH_STREAM and B > 8:
+                continue
+            Y, Wl = gpu_gemm(gpu, W, bias, X[:B], R[:B], spec.epilogue, Wl=Wl, path=path)
+            rep = check(Y, W, bias, X[:B], R[:B], spec.epilogue,
+                        f"config {cfg_id} {spec.name} seed={seed} B={B} path={path}")
+            worst = max(worst, rep["max_ulp"] if rep["max_abs"] > 1e-3 else 0.0)
+    return worst
+
+
+@pytest.mark.parametrize("gi", [0, 1, 2, 3])
+def test_config1_h1024_layer(gpu, gi):
+    from paper_2207_00032_amd import binding as sb
+    _config_case(gpu, 1, gi, 0, (1,), [sb.PATH_AUTO, sb.PATH_MFMA, sb.PATH_STREAM])
+
+
+@pytest.mark.parametrize("gi", [0, 1, 2, 3])
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_config2_h4096_layer(gpu, gi, seed):
+    from paper_2207_00032_amd import binding as sb
+    paths = [sb.PATH_AUTO, sb.PATH_MFMA, sb.PATH_STREAM] if seed == 0 else [sb.PATH_AUTO]
+    _config_case(gpu, 2, gi, seed, wl.CONFIGS[2].batches, paths)
+
+
+@pytest.mark.parametrize("gi", [0, 1, 2, 3])
+def test_config3_h12288_tp_slice(gpu, gi):
+    _config_case(gpu, 3, gi, 0, wl.CONFIGS[3].batches)
+
+
+@pytest.mark.parametrize("gi", [1, 3])
+def test_config4_h12288_full_size(gpu, gi):
+    """Full-size matrices of the unsliced h=12288 layer (attention output and FFN2: the
+    longest K), every output element compared."""
+    _config_case(gpu, 4, gi, 0, wl.CONFIGS[4].batches)
+
+
+def test_config5_crossover_sweep_with_outliers(gpu):
+    from paper_2207_00032_amd import binding as sb
+    _config_case(gpu, 5, 0, 0, wl.CONFIGS[5].batches, [sb.PATH_MFMA, sb.PATH_STREAM])
+
+
+def test_layer_gemms_matches_oracle(gpu):
+    """sbi_layer_gemms on the h=1024 layer, FFN2 chained on FFN1's output."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    cfg = wl.CONFIGS[1]
+    B = 4
+    data = [wl.make_gemm_inputs(s.K, s.N, B, seed=0, config_id=1, gemm_id=i) for i, s in enumerate(cfg.gemms)]
+    Wls = [sb.layout_weights(_dev(d[0], gpu)) for d in data]
+    biases = [_dev(d[1], gpu) for d in data]
+    h = cfg.gemms[0].K
+    L = sb.make_layer(*Wls, h, cfg.gemms[0].N, cfg.gemms[1].K, cfg.gemms[2].N, cfg.gemms[3].K,
+                      bqkv=biases[0], bout=None, bffn1=biases[2], bffn2=biases[3], ffn1_gelu=True)
+    ws = sb.new_workspace(sb.layer_workspace_bytes(L, B), gpu)
+    Xs = [_dev(d[2], gpu) for d in data]
+    Rd = _dev(data[3][3], gpu)
+    Ys = [torch.empty((B, s.N), dtype=torch.float16, device=gpu) for s in cfg.gemms]
+    sb.layer_gemms(L, B, Xs[0], Xs[1], Xs[2], None, Rd, Ys[0], Ys[1], Ys[2], Ys[3], ws)
+    torch.cuda.synchronize()
+    Yh = [y.cpu().numpy() for y in Ys]
+    check(Yh[0], data[0][0], data[0][1], data[0][2], None, "bias", "layer qkv")
+    check(Yh[1], data[1][0], None, data[1][2], None, "none", "layer attn_out")
+    check(Yh[2], data[2][0], data[2][1], data[2][2], None, "bias_gelu", "layer ffn1")
+    # FFN2 consumed the GPU's own fp16 FFN1 output
+    check(Yh[3], data[3][0], data[3][1], Yh[2], data[3][3], "bias_residual", "layer ffn2 (chained)")
