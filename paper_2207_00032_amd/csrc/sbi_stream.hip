@@ -36,14 +36,16 @@ struct DotOp {
         for (int b = 0; b < BT; ++b) xf[b] = xk[xoff + b];     // same address in all 16 lanes: broadcast
 #pragma unroll
         for (int t = 0; t < kPanelTiles; ++t) {
+            const unsigned int wq[4] = {w[t].x, w[t].y, w[t].z, w[t].w};      // k pairs (0,1) (2,3) (4,5) (6,7)
 #pragma unroll
             for (int b = 0; b < BT; ++b) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const half2v wv = __builtin_bit_cast(half2v, w[t][q]);
-                    const half2v xv = __builtin_bit_cast(half2v, xf[b][q]);
-                    acc[t][b] = __builtin_amdgcn_fdot2(wv, xv, acc[t][b], false);
-                }
+                const unsigned int xq[4] = {xf[b].x, xf[b].y, xf[b].z, xf[b].w};
+                float a = acc[t][b];
+                a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, wq[0]), __builtin_bit_cast(half2v, xq[0]), a, false);
+                a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, wq[1]), __builtin_bit_cast(half2v, xq[1]), a, false);
+                a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, wq[2]), __builtin_bit_cast(half2v, xq[2]), a, false);
+                a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, wq[3]), __builtin_bit_cast(half2v, xq[3]), a, false);
+                acc[t][b] = a;
             }
         }
     }
