@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the small-batch GeMM hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch sweep: for every batch size B of
+the workload, the four linear layers of one transformer layer (QKV, attention output,
+FFN1 + bias + GeLU, FFN2 + bias + residual) through sbi_layer_gemms.  The default workload
+is the h=4096 layer at B in {1, 2, 4, 8} (W shapes [4096,12288], [4096,4096], [4096,16384],
+[16384,4096], 384 MiB of fp16 weights).  Steps rotate over several device copies of the
+laid-out weights so that every pass streams them from HBM rather than from the 256 MB
+last-level cache.  All inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line: whole-job weight-streaming throughput (algorithmic bytes / time), the
+roofline figure of the dominant kernel measured with events around each of its launches,
+and the CPU oracle timed on the host cores for the same GeMMs.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload configuration (2, 3 or 4)")
+    ap.add_argument("--batches", type=str, default="", help="comma list overriding the batch sweep")
+    ap.add_argument("--copies", type=int, default=0, help="weight copies to rotate over (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--path", type=str, default="auto", choices=["auto", "stream", "mfma"])
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    from paper_2207_00032_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    sb.load()
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS[args.config]
+    assert len(cfg.gemms) == 4, "bench.py times a four-GeMM layer configuration"
+    batches = tuple(int(b) for b in args.batches.split(",")) if args.batches else cfg.batches
+    Bmax = max(batches)
+    specs = cfg.gemms
+    layer_weight_bytes = sum(s.weight_bytes for s in specs)
+    copies = args.copies or max(2, -(-3 * 256 * 1000 * 1000 // layer_weight_bytes))
+
+    # ---- seeded synthetic inputs (host), uploaded and laid out once ------------------------
+    host = []
+    for gi, s in enumerate(specs):
+        _, W, bias, X, R = wl.make_config_gemm(args.config, gi, seed=0, B=None)
+        host.append((W, bias, X[:Bmax], R[:Bmax]))
+    use_bias = [s.epilogue in (wl.BIAS, wl.BIAS_GELU, wl.BIAS_RESIDUAL) for s in specs]
+    use_res = specs[3].epilogue in (wl.BIAS_RESIDUAL, wl.RESIDUAL)
+    gelu = specs[2].epilogue in (wl.BIAS_GELU, wl.GELU)
+
+    Wl0 = [sb.layout_weights(torch.from_numpy(h[0]).to(dev)) for h in host]
+    for w, s in zip(Wl0, specs):
+        assert sb.layout_check(w, s.K, s.N) == 0
+    Wl = [Wl0] + [[w.clone() for w in Wl0] for _ in range(copies - 1)]
+    bias_d = [torch.from_numpy(h[1]).to(dev) if ub else None for h, ub in zip(host, use_bias)]
+    X_d = {B: [torch.from_numpy(np.ascontiguousarray(h[2][:B])).to(dev) for h in host] for B in batches}
+    R_d = {B: torch.from_numpy(np.ascontiguousarray(host[3][3][:B])).to(dev) if use_res else None for B in batches}
+    Y_d = {B: [torch.empty((B, s.N), dtype=torch.float16, device=dev) for s in specs] for B in batches}
+    h_dim = specs[0].K
+    layers = [sb.make_layer(*Wl[c], h_dim, specs[0].N, specs[1].K, specs[2].N, specs[3].K,
+                            bqkv=bias_d[0], bout=bias_d[1], bffn1=bias_d[2], bffn2=bias_d[3], ffn1_gelu=gelu)
+              for c in range(copies)]
+    ws = sb.new_workspace(max(sb.layer_workspace_bytes(layers[0], B) for B in batches), dev)
+    path = {"auto": sb.PATH_AUTO, "stream": sb.PATH_STREAM, "mfma": sb.PATH_MFMA}[args.path]
+
+    def step(i):
+        L = layers[i % copies]
+        for B in batches:
+            x, y = X_d[B], Y_d[B]
+            if path == sb.PATH_AUTO:
+                sb.layer_gemms(L, B, x[0], x[1], x[2], x[3], R_d[B], y[0], y[1], y[2], y[3], ws)
+            else:
+                Wc = Wl[i % copies]
+                for gi, s in enumerate(specs):
+                    sb.gemm(Wc[gi], s.K, s.N, x[gi], bias_d[gi], R_d[B] if gi == 3 else None, s.epilogue,
+                            out=y[gi], workspace=ws, path=path)
+
+    # ---- timed region ---------------------------------------------------------------------
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sec_per_step = (t1 - t0) / args.steps
+    bytes_per_step = sum(s.algorithmic_bytes(B) for B in batches for s in specs)
+    flops_per_step = sum(s.flops(B) for B in batches for s in specs)
+    value = bytes_per_step / sec_per_step / 1e9
+
+    # ---- per-kernel durations: events around every launch, on the launch stream ------------
+    # (a second pass over the same steps, so the events do not perturb `value`)
+    ev_steps = min(args.steps, 20)
+    records = []      # (gemm index, B, start event, stop event)
+    plans = {(gi, B): sb.plan(B, s.K, s.N, path) for gi, s in enumerate(specs) for B in batches}
+    for i in range(ev_steps):
+        Wc = Wl[(args.warmup + i) % copies]
+        for B in batches:
+            x, y = X_d[B], Y_d[B]
+            for gi, s in enumerate(specs):
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                sb.gemm(Wc[gi], s.K, s.N, x[gi], bias_d[gi], R_d[B] if gi == 3 else None, s.epilogue,
+                        out=y[gi], workspace=ws, path=path)
+                e1.record()
+                records.append((gi, B, e0, e1))
+    torch.cuda.synchronize()
+    per = {}
+    for gi, B, e0, e1 in records:
+        per.setdefault((gi, B), []).append(e0.elapsed_time(e1) * 1e3)   # microseconds
+    per_gemm = []
+    groups = {}
+    for (gi, B), us in sorted(per.items()):
+        s = specs[gi]
+        us_sorted = sorted(us)
+        med = us_sorted[len(us_sorted) // 2]
+        avg = sum(us) / len(us)
+        pl = plans[(gi, B)]
+        kname = f"{'mfma' if pl['path'] == sb.PATH_MFMA else 'stream'}" \
+                f"<{(B + 15) // 16 if pl['path'] == sb.PATH_MFMA else B},{pl['waves']},{pl['depth']}>"
+        per_gemm.append({"gemm": s.name, "K": s.K, "N": s.N, "B": B, "us_median": round(med, 2),
+                         "us_mean": round(avg, 2),
+                         "GBps": round(s.algorithmic_bytes(B) / (med * 1e-6) / 1e9, 1),
+                         "hbm_frac": round(s.algorithmic_bytes(B) / (med * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                         "TFLOPs": round(s.flops(B) / (med * 1e-6) / 1e12, 3),
+                         "kernel": kname, "split_k": pl["split_k"], "grid": pl["grid"]})
+        g = groups.setdefault(kname, {"bytes": 0.0, "us": 0.0, "launches": 0})
+        g["bytes"] += s.algorithmic_bytes(B) * len(us)
+        g["us"] += sum(us)
+        g["launches"] += len(us)
+    dom_name, dom = max(groups.items(), key=lambda kv: kv[1]["us"])
+    achieved = dom["bytes"] / (dom["us"] * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "kernel": dom_name, "launches": dom["launches"],
+                "avg_launch_us": round(dom["us"] / dom["launches"], 2),
+                "avg_bytes_per_launch": round(dom["bytes"] / dom["launches"])}
+
+    # ---- CPU oracle on the host cores, same GeMMs (a reported baseline, not a target) -------
+    cpu = None
+    parity = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        epi_map = {wl.NONE: 0, wl.BIAS: orc.EPI_BIAS, wl.BIAS_GELU: orc.EPI_BIAS | orc.EPI_GELU,
+                   wl.BIAS_RESIDUAL: orc.EPI_BIAS | orc.EPI_RES, wl.GELU: orc.EPI_GELU, wl.RESIDUAL: orc.EPI_RES}
+        torch.cuda.synchronize()
+        step(0)                      # outputs of copy 0 for the parity check below
+        torch.cuda.synchronize()
+        t_cpu = 0.0
+        cpu_bytes = 0
+        worst = {"max_abs": 0.0, "max_ulp": 0.0, "n_bad": 0}
+        sample_batches = batches if layer_weight_bytes < (1 << 30) else (Bmax,)
+        for B in sample_batches:
+            for gi, s in enumerate(specs):
+                W, bias, X, R = host[gi]
+                xin = X[:B]
+                if gi == 3 and path == sb.PATH_AUTO:
+                    xin = X[:B]      # sbi_layer_gemms was given FFN2's own input, not chained
+                c0 = time.perf_counter()
+                want = orc.gemm(xin, W, bias, R[:B], epi=epi_map[s.epilogue])
+                t_cpu += time.perf_counter() - c0
+                cpu_bytes += s.algorithmic_bytes(B)
+                ok, rep = orc.check_close(Y_d[B][gi].cpu().numpy(), want)
+                worst["max_abs"] = max(worst["max_abs"], rep["max_abs"])
+                worst["max_ulp"] = max(worst["max_ulp"], rep["max_ulp"] if rep["max_abs"] > 1e-3 else 0.0)
+                worst["n_bad"] += rep["n_bad"]
+        cpu = {"value": round(cpu_bytes / t_cpu / 1e9, 3), "unit": "GB/s", "cores": orc.max_threads(),
+               "kind": "oracle",
+               "sample": f"{len(sample_batches) * len(specs)} GeMMs (config {args.config}, B in "
+                         f"{list(sample_batches)}), {t_cpu:.1f} s of CPU time"}
+        parity = {"ok": worst["n_bad"] == 0, "max_abs": worst["max_abs"],
+                  "max_ulp_where_abs_gt_1e-3": worst["max_ulp"], "tolerance": "max(2 ulp16, 1e-3)"}
+
+    out = {
+        "metric": "weight-stream HBM GB/s (algorithmic bytes of the layer's four GeMMs / time)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec_per_step * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"config{args.config}:{cfg.name} four-GeMM layer, B in {list(batches)}, "
+                               f"rotating over {copies} weight copies ({copies * layer_weight_bytes >> 20} MiB)",
+                   "batches": list(batches), "weight_copies": copies, "dispatch": args.path},
+        "hbm_frac": round(value / HBM_PEAK_GBPS, 4),
+        "us_per_gemm_mean": round(sec_per_step * 1e6 / (len(batches) * len(specs)), 2),
+        "TFLOPs": round(flops_per_step / sec_per_step / 1e12, 3),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "parity": parity,
+        "per_gemm": per_gemm,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

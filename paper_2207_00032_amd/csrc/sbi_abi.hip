@@ -13,6 +13,7 @@ using namespace sbi;
 
 constexpr int64_t kMaxDim = int64_t(1) << 22;     // K, N limit: keeps tile counts and grids in 32 bits
 constexpr int64_t kMaxLds = 64 * 1024;            // dynamic LDS budget per block
+constexpr int64_t kCounterBytes = (kMaxDim / kPanelN) * 4;   // one arrival counter per possible panel: 256 KiB
 constexpr int kStreamMaxBatch = 8;                // vector-ALU kernel instantiations exist for B <= 8
 constexpr int kAutoStreamBatch = 0;               // AUTO picks the vector-ALU kernel for B <= this
 
@@ -98,7 +99,9 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     pl.ksps = (int)ksps; pl.kc = (int)kc;
     pl.grid = (int)(P * S); pl.block = nw * 64;
     pl.lds = std::max<int64_t>(kc * B * 64, (int64_t)nw * 16 * kRedPitch * 4);
-    pl.counter_bytes = (S > 1) ? round_up(P * 4, 256) : 0;
+    // fixed-size counter region: calls of different shapes that share a workspace must never
+    // see each other's partial sums where they expect counters
+    pl.counter_bytes = (S > 1) ? kCounterBytes : 0;
     pl.ws_bytes = (S > 1) ? pl.counter_bytes + P * S * B * kPanelN * 4 : 0;
     return SBI_OK;
 }
