@@ -95,8 +95,9 @@ size_t sbi_gemm_layout_bytes(int64_t K, int64_t N);
 
 /*
  * Upper bound of the workspace sbi_gemm (automatic dispatch) needs for (B, K, N), in bytes;
- * may be 0.  The workspace holds cross-block partial sums and one arrival counter per
- * panel.  It MUST be zero-filled once by the caller before its first use; the library
+ * may be 0.  The workspace holds a fixed 256 KiB region of arrival counters (one per
+ * 64-column panel) followed by the cross-block partial sums.
+ * It MUST be zero-filled once by the caller before its first use; the library
  * leaves the counters zero after every call, so one workspace can serve any sequence
  * of calls on one stream.  Two calls that may run concurrently must not share it.
  */
@@ -186,6 +187,21 @@ sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
 size_t sbi_layer_workspace_bytes(const sbi_layer* L, int64_t B);
+
+/*
+ * Measurement helpers (no part of the GeMM path; for callers that profile it).
+ * sbi_calib_read streams `bytes` (a multiple of 4096, 256-byte aligned, device) from src
+ * with the GeMM's own access shape - `blocks` thread blocks of `waves` wavefronts (4, 8 or
+ * 16), each wavefront keeping `depth` (4 or 8) 4 KiB units in flight, 128-bit loads,
+ * non-temporal if `nontemporal` - and writes nothing in practice (sink, device, >= 16 bytes
+ * per block, only keeps the loads alive).  Its bandwidth is the ceiling this access pattern
+ * can reach.  sbi_calib_copy copies `bytes` (a multiple of 16; both pointers 16-byte
+ * aligned, device) with plain 128-bit loads and stores: a kernel of known HBM traffic
+ * against which hardware byte counters are scaled.
+ */
+sbi_status sbi_calib_read(const void* src, size_t bytes, void* sink, size_t sink_bytes,
+                          int32_t blocks, int32_t waves, int32_t depth, int32_t nontemporal, void* hip_stream);
+sbi_status sbi_calib_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
 
 const char* sbi_status_string(sbi_status s);
 

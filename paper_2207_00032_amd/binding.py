@@ -28,7 +28,7 @@ STATUS_NAMES = ["SBI_OK", "SBI_ERR_NULL", "SBI_ERR_SHAPE", "SBI_ERR_ALIGN", "SBI
 EXPORTS = ["sbi_gemm_layout_bytes", "sbi_gemm_workspace_bytes", "sbi_gemm_layout_weights",
            "sbi_gemm_unlayout_weights", "sbi_gemm_layout_check", "sbi_gemm", "sbi_gemm_ex",
            "sbi_gemm_plan", "sbi_layer_gemms", "sbi_layer_workspace_bytes", "sbi_status_string",
-           "sbi_version"]
+           "sbi_version", "sbi_calib_read", "sbi_calib_copy"]
 
 
 class SbiError(RuntimeError):
@@ -95,6 +95,10 @@ def load():
     L.sbi_layer_gemms.argtypes = [ctypes.POINTER(Layer), i64] + [vp] * 9 + [vp, sz, vp]
     L.sbi_layer_workspace_bytes.restype = sz
     L.sbi_layer_workspace_bytes.argtypes = [ctypes.POINTER(Layer), i64]
+    L.sbi_calib_read.restype = i32
+    L.sbi_calib_read.argtypes = [vp, sz, vp, sz, i32, i32, i32, i32, vp]
+    L.sbi_calib_copy.restype = i32
+    L.sbi_calib_copy.argtypes = [vp, vp, sz, vp]
     L.sbi_status_string.restype = ctypes.c_char_p
     L.sbi_status_string.argtypes = [i32]
     L.sbi_version.restype = i32
@@ -219,3 +223,16 @@ def layer_gemms(layer, B, Xqkv, Xout, Xffn1, Xffn2, residual, Yqkv, Yout, Yffn1,
                                 _ptr(residual), _ptr(Yqkv), _ptr(Yout), _ptr(Yffn1), _ptr(Yffn2),
                                 _ptr(workspace), ws_len, _stream())
     _check(st, "sbi_layer_gemms")
+
+
+# ---------------------------------------------------------------------------------- measurement helpers
+def calib_read(src, sink, blocks, waves=8, depth=4, nontemporal=True):
+    """Stream the whole uint8 tensor `src` (numel a multiple of 4096) with the GeMM's access shape."""
+    _check(load().sbi_calib_read(_ptr(src), src.numel(), _ptr(sink), sink.numel() * sink.element_size(),
+                                 int(blocks), int(waves), int(depth), 1 if nontemporal else 0, _stream()),
+           "sbi_calib_read")
+
+
+def calib_copy(src, dst):
+    _check(load().sbi_calib_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream()),
+           "sbi_calib_copy")

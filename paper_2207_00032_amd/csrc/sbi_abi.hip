@@ -32,17 +32,19 @@ sbi_status check_shape(int64_t K, int64_t N)
 }
 
 // Cost, in k-steps of streaming time on the busiest CU, of splitting a panel's K range S ways.
+// Measured on MI355X: one block of 8 waves per CU already saturates HBM, every further
+// block costs about as much as streaming 20 k-steps (launch, X staging, reduction, arrival),
+// and a grid that leaves CUs idle only hurts below about 3/4 occupancy.
 double split_cost(int64_t KS, int64_t P, int64_t B, int S, int nw)
 {
     const int64_t ksps = ceil_div(KS, S);
     const int64_t blocks = P * S;
     const int64_t rounds = ceil_div(blocks, kNumCU);
-    // fixed work per block: ramp-up of the load pipeline, X staging, in-block reduction
-    const double block_overhead = 6.0;
-    // a lone block per CU cannot keep enough loads in flight: count short queues as slower
-    const double waves_per_cu = (double)std::min<int64_t>(rounds, 4) * nw;
-    const double starve = waves_per_cu >= 16 ? 1.0 : (waves_per_cu >= 8 ? 1.15 : 1.6);
-    double cost = (double)rounds * ((double)ksps * starve + block_overhead);
+    const double block_overhead = 20.0;
+    const double busy = (double)std::min<int64_t>(blocks, kNumCU) / kNumCU;     // fraction of CUs with work
+    const double starve = busy >= 0.75 ? 1.0 : 0.75 / busy;
+    double cost = (double)rounds * ((double)ksps + block_overhead) * starve;
+    if (nw == 4) cost *= 1.03;
     if (S > 1) {
         // partial sums: written once and read once, 256 B per batch row per block
         const double bytes = (double)blocks * (double)B * 512.0;
