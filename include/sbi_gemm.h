@@ -61,26 +61,29 @@ typedef enum sbi_epilogue {
 /* Which kernel family executes the contraction. */
 typedef enum sbi_path {
     SBI_PATH_AUTO = 0,   /* the batch-size dispatcher decides */
-    SBI_PATH_STREAM = 1, /* vector-ALU dot-product streaming kernel, B <= 8 */
-    SBI_PATH_MFMA = 2    /* matrix-core (MFMA fp16 16x16x32) streaming kernel, B <= 64 */
+    SBI_PATH_STREAM = 1, /* vector-ALU dot-product kernel, one block per (panel, k-range), B <= 8 */
+    SBI_PATH_MFMA = 2,   /* matrix-core (MFMA fp16 16x16x32) kernel, one block per (panel, k-range) */
+    SBI_PATH_STREAMK = 3 /* matrix-core kernel with the weight stream cut into equal ranges, one per
+                            wavefront; needs K % 8 == 0; the only path that groups a layer's GeMMs */
 } sbi_path;
 
 /* Optional overrides for sbi_gemm_ex / sbi_gemm_plan; a zero field means "automatic". */
 typedef struct sbi_tuning {
     int32_t path;    /* sbi_path */
-    int32_t split_k; /* number of thread blocks that share one 64-column panel's K range */
+    int32_t split_k; /* blocks that share one 64-column panel's K range (STREAM / MFMA paths) */
     int32_t waves;   /* wavefronts per block: 4 or 8 */
     int32_t depth;   /* k-steps of W each wavefront keeps in flight: 4 or 8 */
+    int32_t blocks;  /* STREAMK path: upper bound on the number of thread blocks */
 } sbi_tuning;
 
 /* What the dispatcher decided for a problem (for reports and tests). */
 typedef struct sbi_plan {
-    int32_t path;        /* SBI_PATH_STREAM or SBI_PATH_MFMA */
+    int32_t path;        /* SBI_PATH_STREAM, SBI_PATH_MFMA or SBI_PATH_STREAMK */
     int32_t waves;       /* wavefronts per block */
     int32_t depth;       /* W k-steps in flight per wavefront */
-    int32_t split_k;     /* blocks per panel (1 = no cross-block reduction) */
-    int32_t ksteps_per_split; /* 32-row k-steps handled by one block */
-    int32_t ksteps_per_chunk; /* k-steps of X staged in LDS at a time */
+    int32_t split_k;     /* blocks per panel (1 = no cross-block reduction); 0 on the STREAMK path */
+    int32_t ksteps_per_split; /* k-steps handled by one block (STREAMK: 4 KiB units per wavefront) */
+    int32_t ksteps_per_chunk; /* k-steps of X staged in LDS at a time; 0 on the STREAMK path */
     int32_t grid;        /* thread blocks launched */
     int32_t block;       /* threads per block */
     int64_t lds_bytes;   /* dynamic LDS per block */
@@ -89,7 +92,8 @@ typedef struct sbi_plan {
 
 /*
  * Size in bytes of the laid-out copy of a [K,N] fp16 matrix: a 256-byte header followed
- * by ceil(N/64) * ceil(K/32) tiles of 4 KiB (zero padded).  Returns 0 for a bad shape.
+ * by ceil(N/64) * KS k-steps of 4 KiB (zero padded), KS = ceil(K/32) rounded up to a
+ * multiple of 8.  Returns 0 for a bad shape.
  */
 size_t sbi_gemm_layout_bytes(int64_t K, int64_t N);
 
@@ -110,7 +114,8 @@ size_t sbi_gemm_workspace_bytes(int64_t B, int64_t K, int64_t N);
  * 8 consecutive k of one column (one 128-bit load), a wavefront load is a contiguous
  * 1 KiB tile of 16 columns x 32 k, and the four tiles of a 64-column panel are adjacent:
  *   half index of W[k][n] after the header =
- *     ((((n/64)*KS + k/32)*4 + (n%64)/16)*64 + ((k%32)/8)*16 + n%16)*8 + k%8,  KS = ceil(K/32).
+ *     ((((n/64)*KS + k/32)*4 + (n%64)/16)*64 + ((k%32)/8)*16 + n%16)*8 + k%8,
+ *   KS = ceil(K/32) rounded up to a multiple of 8 (so K is zero padded to a multiple of 256).
  * W_rowmajor: device, fp16 [K,N] contiguous (ld = N), 2-byte aligned.
  * W_laid_out: device, 256-byte aligned, laid_out_bytes >= sbi_gemm_layout_bytes(K,N).
  * The source may be freed once the stream has executed the call.  Pure permutation plus

@@ -28,6 +28,7 @@ TILE_N = 16      # columns per tile
 TILE_K = 32      # k per tile  = 4 lane groups x CHUNK_K
 PANEL_TILES = 4  # tiles per panel -> a panel is 64 columns wide
 PANEL_N = TILE_N * PANEL_TILES
+STEP_GROUP = 8   # k-steps per panel are padded to a multiple of this
 HEADER_BYTES = 256
 
 _lib = None
@@ -123,8 +124,8 @@ def gemm(X, W, bias=None, residual=None, epi=0, threads=0, return_pre=False):
 
 
 # --------------------------------------------------------------------------------------
-# Weight pre-layout, from its definition.  W [K,N] is zero-padded to Kp = ceil32(K),
-# Np = ceil64(N).  Element (k, n) lands at half-index
+# Weight pre-layout, from its definition.  W [K,N] is zero-padded to Kp = ceil256(K)
+# (KS = Kp // 32 k-steps, a multiple of 8), Np = ceil64(N).  Element (k, n) lands at half-index
 #     ((((p*KS + ks)*4 + t)*64 + lane)*8 + e)
 # with p = n // 64, t = (n % 64) // 16, i = n % 16, ks = k // 32, g = (k % 32) // 8,
 # e = k % 8, lane = g*16 + i, KS = Kp // 32 -- i.e. one lane of a 64-wide wavefront owns
@@ -132,7 +133,7 @@ def gemm(X, W, bias=None, residual=None, epi=0, threads=0, return_pre=False):
 # (1 KiB) and four such tiles (64 columns) of the same k range are adjacent.
 # --------------------------------------------------------------------------------------
 def layout_dims(K, N):
-    KS = -(-K // TILE_K)
+    KS = -(-(-(-K // TILE_K)) // STEP_GROUP) * STEP_GROUP
     P = -(-N // PANEL_N)
     return KS, P
 

@@ -17,8 +17,8 @@ EPI_NONE, EPI_BIAS, EPI_BIAS_GELU, EPI_BIAS_RESIDUAL, EPI_GELU, EPI_RESIDUAL = r
 EPILOGUES = {"none": EPI_NONE, "bias": EPI_BIAS, "bias_gelu": EPI_BIAS_GELU,
              "bias_residual": EPI_BIAS_RESIDUAL, "gelu": EPI_GELU, "residual": EPI_RESIDUAL}
 # sbi_path
-PATH_AUTO, PATH_STREAM, PATH_MFMA = 0, 1, 2
-PATH_NAMES = {PATH_AUTO: "auto", PATH_STREAM: "stream", PATH_MFMA: "mfma"}
+PATH_AUTO, PATH_STREAM, PATH_MFMA, PATH_STREAMK = 0, 1, 2, 3
+PATH_NAMES = {PATH_AUTO: "auto", PATH_STREAM: "stream", PATH_MFMA: "mfma", PATH_STREAMK: "streamk"}
 # sbi_status
 OK = 0
 STATUS_NAMES = ["SBI_OK", "SBI_ERR_NULL", "SBI_ERR_SHAPE", "SBI_ERR_ALIGN", "SBI_ERR_BATCH",
@@ -40,7 +40,7 @@ class SbiError(RuntimeError):
 
 class Tuning(ctypes.Structure):
     _fields_ = [("path", ctypes.c_int32), ("split_k", ctypes.c_int32),
-                ("waves", ctypes.c_int32), ("depth", ctypes.c_int32)]
+                ("waves", ctypes.c_int32), ("depth", ctypes.c_int32), ("blocks", ctypes.c_int32)]
 
 
 class Plan(ctypes.Structure):
@@ -125,10 +125,10 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def _tuning(path=PATH_AUTO, split_k=0, waves=0, depth=0):
-    if path == PATH_AUTO and not (split_k or waves or depth):
+def _tuning(path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0):
+    if path == PATH_AUTO and not (split_k or waves or depth or blocks):
         return None
-    return ctypes.pointer(Tuning(int(path), int(split_k), int(waves), int(depth)))
+    return ctypes.pointer(Tuning(int(path), int(split_k), int(waves), int(depth), int(blocks)))
 
 
 # ---------------------------------------------------------------------------------- sizes
@@ -140,9 +140,10 @@ def workspace_bytes(B, K, N):
     return int(load().sbi_gemm_workspace_bytes(B, K, N))
 
 
-def plan(B, K, N, path=PATH_AUTO, split_k=0, waves=0, depth=0):
+def plan(B, K, N, path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0):
     pl = Plan()
-    _check(load().sbi_gemm_plan(B, K, N, _tuning(path, split_k, waves, depth), ctypes.byref(pl)), "sbi_gemm_plan")
+    _check(load().sbi_gemm_plan(B, K, N, _tuning(path, split_k, waves, depth, blocks), ctypes.byref(pl)),
+           "sbi_gemm_plan")
     return pl.as_dict()
 
 
@@ -177,7 +178,7 @@ def layout_check(Wl, K, N):
 
 
 def gemm(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, workspace=None,
-         path=PATH_AUTO, split_k=0, waves=0, depth=0):
+         path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0):
     """Y = epilogue(X @ W + bias) through sbi_gemm / sbi_gemm_ex.  Returns Y (fp16 [B,N])."""
     import torch
     assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.is_contiguous()
@@ -186,9 +187,10 @@ def gemm(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, wor
         epilogue = EPILOGUES[epilogue]
     if out is None:
         out = torch.empty((B, N), dtype=torch.float16, device=X.device)
-    tune = _tuning(path, split_k, waves, depth)
+    tune = _tuning(path, split_k, waves, depth, blocks)
     if workspace is None:
-        need = plan(B, K, N, path, split_k, waves, depth)["workspace_bytes"] if tune else workspace_bytes(B, K, N)
+        need = plan(B, K, N, path, split_k, waves, depth, blocks)["workspace_bytes"] if tune \
+            else workspace_bytes(B, K, N)
         workspace = new_workspace(need, X.device) if need else None
     ws_ptr = _ptr(workspace)
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0

@@ -23,7 +23,31 @@ inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
 struct Plan {
     int path, nw, depth, S, ksps, kc, grid, block;
     int64_t lds, ws_bytes, counter_bytes;
+    int upw, nwaves;          // STREAMK path: units per wavefront, wavefronts
 };
+
+constexpr int kSkDefaultWaves = 2048;             // wavefronts of a STREAMK launch: 8 per CU
+constexpr int64_t kSkMaxUnits = int64_t(1) << 30; // keeps unit indices in 32 bits
+
+// Launch shape of the work-balanced kernel for `units` 4 KiB units in total.
+sbi_status plan_streamk(int64_t B, int64_t units, int64_t panels, const sbi_tuning& t, Plan& pl)
+{
+    if (units > kSkMaxUnits || panels > kCounterBytes / 4) return SBI_ERR_SHAPE;
+    int nw = t.waves ? t.waves : 4;
+    int depth = t.depth ? t.depth : 4;
+    if ((nw != 4 && nw != 8) || (depth != 4 && depth != 8) || t.blocks < 0) return SBI_ERR_TUNING;
+    if (nw == 8 && depth == 8 && B > 16) return SBI_ERR_TUNING;      // would not fit the register file
+    const int64_t want = t.blocks ? (int64_t)t.blocks * nw : kSkDefaultWaves;
+    const int64_t upw = round_up(ceil_div(units, want), kStepGroup);
+    const int64_t nwaves = ceil_div(units, upw);
+    pl.path = SBI_PATH_STREAMK; pl.nw = nw; pl.depth = depth; pl.S = 0;
+    pl.ksps = (int)upw; pl.kc = 0;
+    pl.grid = (int)ceil_div(nwaves, nw); pl.block = nw * 64; pl.lds = 0;
+    pl.upw = (int)upw; pl.nwaves = (int)nwaves;
+    pl.counter_bytes = kCounterBytes;
+    pl.ws_bytes = kCounterBytes + nwaves * 2 * B * kPanelN * 4;
+    return SBI_OK;
+}
 
 sbi_status check_shape(int64_t K, int64_t N)
 {
@@ -57,14 +81,20 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
 {
     if (sbi_status s = check_shape(K, N)) return s;
     if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
-    const int64_t KS = ceil_div(K, kTileK);
+    const int64_t KS = ksteps_of(K);
     const int64_t P = ceil_div(N, kPanelN);
 
-    sbi_tuning t = {0, 0, 0, 0};
+    sbi_tuning t = {0, 0, 0, 0, 0};
     if (tune) t = *tune;
 
     int path = t.path;
-    if (path == SBI_PATH_AUTO) path = (B <= kAutoStreamBatch) ? SBI_PATH_STREAM : SBI_PATH_MFMA;
+    const bool sk_ok = (K % kChunkK == 0);            // X rows readable as 128-bit pieces
+    if (path == SBI_PATH_AUTO)
+        path = sk_ok ? SBI_PATH_STREAMK : ((B <= kAutoStreamBatch) ? SBI_PATH_STREAM : SBI_PATH_MFMA);
+    if (path == SBI_PATH_STREAMK) {
+        if (!sk_ok) return SBI_ERR_TUNING;
+        return plan_streamk(B, KS * P, P, t, pl);
+    }
     if (path != SBI_PATH_STREAM && path != SBI_PATH_MFMA) return SBI_ERR_TUNING;
     if (path == SBI_PATH_STREAM && B > kStreamMaxBatch) return SBI_ERR_TUNING;
 
@@ -105,6 +135,7 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     // see each other's partial sums where they expect counters
     pl.counter_bytes = (S > 1) ? kCounterBytes : 0;
     pl.ws_bytes = (S > 1) ? pl.counter_bytes + P * S * B * kPanelN * 4 : 0;
+    pl.upw = 0; pl.nwaves = 0;
     return SBI_OK;
 }
 
@@ -123,6 +154,60 @@ int epilogue_flags(int epi)
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
+// One GeMM of a launch, already validated.
+struct GemmArgs {
+    const void* Wl; int64_t K, N; const void* X; const void* bias; const void* R; int flags; void* Y;
+};
+
+// Validation shared by sbi_gemm_ex and sbi_layer_gemms (everything except the workspace).
+sbi_status check_gemm_args(const void* W_laid_out, int64_t K, int64_t N, const void* X, int64_t B,
+                           const void* bias, const void* residual, int epi, const void* Y, int& flags)
+{
+    if (!W_laid_out || !X || !Y) return SBI_ERR_NULL;
+    if (sbi_status s = check_shape(K, N)) return s;
+    if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
+    flags = epilogue_flags(epi);
+    if (flags < 0) return SBI_ERR_EPILOGUE;
+    if ((flags & kEpiBias) && !bias) return SBI_ERR_EPILOGUE;
+    if ((flags & kEpiRes) && !residual) return SBI_ERR_EPILOGUE;
+    const bool x_vec = (K % 8 == 0);
+    if (!aligned(W_laid_out, 256) || !aligned(X, x_vec ? 16 : 2) || !aligned(Y, 4)) return SBI_ERR_ALIGN;
+    if ((flags & kEpiBias) && !aligned(bias, 2)) return SBI_ERR_ALIGN;
+    if ((flags & kEpiRes) && !aligned(residual, 2)) return SBI_ERR_ALIGN;
+    const uintptr_t x0 = reinterpret_cast<uintptr_t>(X), x1 = x0 + (uintptr_t)(B * K * 2);
+    const uintptr_t y0 = reinterpret_cast<uintptr_t>(Y), y1 = y0 + (uintptr_t)(B * N * 2);
+    if (x0 < y1 && y0 < x1) return SBI_ERR_OVERLAP;
+    return SBI_OK;
+}
+
+// Launch `G` independent GeMMs of batch B as one work-balanced kernel.
+sbi_status launch_group(const GemmArgs* a, int G, int64_t B, const Plan& pl, void* workspace, hipStream_t st)
+{
+    SkParams p;
+    std::memset(&p, 0, sizeof p);
+    int64_t units = 0, panels = 0;
+    for (int g = 0; g < G; ++g) {
+        SkProblem& q = p.prob[g];
+        q.Wl = reinterpret_cast<const u32x4*>(reinterpret_cast<const unsigned char*>(a[g].Wl) + kHeaderBytes);
+        q.X = reinterpret_cast<const _Float16*>(a[g].X);
+        q.bias = (a[g].flags & kEpiBias) ? reinterpret_cast<const _Float16*>(a[g].bias) : nullptr;
+        q.R = (a[g].flags & kEpiRes) ? reinterpret_cast<const _Float16*>(a[g].R) : nullptr;
+        q.Y = reinterpret_cast<_Float16*>(a[g].Y);
+        q.K = (int)a[g].K; q.N = (int)a[g].N;
+        q.KS = (int)ksteps_of(a[g].K); q.P = (int)ceil_div(a[g].N, kPanelN);
+        q.flags = a[g].flags;
+        q.unit_base = (int)units; q.panel_base = (int)panels;
+        q.fast = (a[g].N % 4 == 0) && aligned(a[g].Y, 8) && (!q.bias || aligned(q.bias, 8)) &&
+                 (!q.R || aligned(q.R, 8));
+        units += (int64_t)q.KS * q.P;
+        panels += q.P;
+    }
+    p.G = G; p.B = (int)B; p.U = (int)units; p.upw = pl.upw;
+    p.counters = reinterpret_cast<unsigned int*>(workspace);
+    p.partials = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(workspace) + pl.counter_bytes);
+    return launch_streamk(p, pl.nw, pl.depth, pl.grid, st) == 0 ? SBI_OK : SBI_ERR_HIP;
+}
+
 }  // namespace
 
 extern "C" {
@@ -130,7 +215,7 @@ extern "C" {
 size_t sbi_gemm_layout_bytes(int64_t K, int64_t N)
 {
     if (check_shape(K, N) != SBI_OK) return 0;
-    return (size_t)kHeaderBytes + (size_t)ceil_div(K, kTileK) * (size_t)ceil_div(N, kPanelN) * 4096u;
+    return (size_t)kHeaderBytes + (size_t)ksteps_of(K) * (size_t)ceil_div(N, kPanelN) * 4096u;
 }
 
 size_t sbi_gemm_workspace_bytes(int64_t B, int64_t K, int64_t N)
@@ -182,7 +267,7 @@ sbi_status sbi_gemm_layout_check(const void* W_laid_out, int64_t K, int64_t N, v
     if (hipMemcpyAsync(&h, W_laid_out, sizeof h, hipMemcpyDeviceToHost, st) != hipSuccess) return SBI_ERR_HIP;
     if (hipStreamSynchronize(st) != hipSuccess) return SBI_ERR_HIP;
     const bool ok = h.magic == kMagic && h.version == kLayoutVersion && h.K == K && h.N == N &&
-                    h.KS == ceil_div(K, kTileK) && h.P == ceil_div(N, kPanelN) &&
+                    h.KS == ksteps_of(K) && h.P == ceil_div(N, kPanelN) &&
                     h.tile_n == kTileN && h.tile_k == kTileK && h.panel_tiles == kPanelTiles &&
                     h.chunk_k == kChunkK;
     return ok ? SBI_OK : SBI_ERR_LAYOUT_MISMATCH;
@@ -194,27 +279,18 @@ sbi_status sbi_gemm_ex(const void* W_laid_out, int64_t K, int64_t N,
                        void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
                        const sbi_tuning* tuning)
 {
-    if (!W_laid_out || !X || !Y) return SBI_ERR_NULL;
-    if (sbi_status s = check_shape(K, N)) return s;
-    if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
-    const int flags = epilogue_flags((int)epi);
-    if (flags < 0) return SBI_ERR_EPILOGUE;
-    if ((flags & kEpiBias) && !bias) return SBI_ERR_EPILOGUE;
-    if ((flags & kEpiRes) && !residual) return SBI_ERR_EPILOGUE;
-    const bool x_vec = (K % 8 == 0);
-    if (!aligned(W_laid_out, 256) || !aligned(X, x_vec ? 16 : 2) || !aligned(Y, 4)) return SBI_ERR_ALIGN;
-    if ((flags & kEpiBias) && !aligned(bias, 2)) return SBI_ERR_ALIGN;
-    if ((flags & kEpiRes) && !aligned(residual, 2)) return SBI_ERR_ALIGN;
-    {
-        const uintptr_t x0 = reinterpret_cast<uintptr_t>(X), x1 = x0 + (uintptr_t)(B * K * 2);
-        const uintptr_t y0 = reinterpret_cast<uintptr_t>(Y), y1 = y0 + (uintptr_t)(B * N * 2);
-        if (x0 < y1 && y0 < x1) return SBI_ERR_OVERLAP;
-    }
+    int flags = 0;
+    if (sbi_status s = check_gemm_args(W_laid_out, K, N, X, B, bias, residual, (int)epi, Y, flags)) return s;
     Plan pl;
     if (sbi_status s = make_plan(B, K, N, tuning, pl)) return s;
     if (pl.ws_bytes > 0) {
         if (!workspace || workspace_bytes < (size_t)pl.ws_bytes) return SBI_ERR_WORKSPACE;
         if (!aligned(workspace, 256)) return SBI_ERR_ALIGN;
+    }
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (pl.path == SBI_PATH_STREAMK) {
+        const GemmArgs a = {W_laid_out, K, N, X, bias, residual, flags, Y};
+        return launch_group(&a, 1, B, pl, workspace, st);
     }
 
     GemmParams p;
@@ -227,11 +303,10 @@ sbi_status sbi_gemm_ex(const void* W_laid_out, int64_t K, int64_t N,
     p.partials = pl.ws_bytes ? reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(workspace) + pl.counter_bytes)
                              : nullptr;
     p.B = (int)B; p.K = (int)K; p.N = (int)N;
-    p.KS = (int)ceil_div(K, kTileK); p.P = (int)ceil_div(N, kPanelN);
+    p.KS = (int)ksteps_of(K); p.P = (int)ceil_div(N, kPanelN);
     p.S = pl.S; p.ksps = pl.ksps; p.kc = pl.kc;
-    p.flags = flags; p.x_vec = x_vec ? 1 : 0;
+    p.flags = flags; p.x_vec = (K % 8 == 0) ? 1 : 0;
 
-    hipStream_t st = (hipStream_t)hip_stream;
     const int rc = (pl.path == SBI_PATH_STREAM) ? launch_stream(p, pl.nw, pl.depth, (size_t)pl.lds, st)
                                                 : launch_mfma(p, pl.nw, pl.depth, (size_t)pl.lds, st);
     return rc == 0 ? SBI_OK : SBI_ERR_HIP;
@@ -258,6 +333,26 @@ static sbi_status layer_check(const sbi_layer* L, int64_t B)
     return SBI_OK;
 }
 
+// The four GeMMs can share work-balanced launches when each of them can take that path.
+static bool layer_groupable(const sbi_layer* L)
+{
+    return L->h % kChunkK == 0 && L->k_out % kChunkK == 0 && L->k_ffn2 % kChunkK == 0;
+}
+
+// Plan of a grouped launch over GeMMs [first, first+count) of the layer.
+static sbi_status layer_group_plan(const sbi_layer* L, int64_t B, int first, int count, Plan& pl)
+{
+    const int64_t Ks[4] = {L->h, L->k_out, L->h, L->k_ffn2};
+    const int64_t Ns[4] = {L->n_qkv, L->h, L->n_ffn1, L->h};
+    int64_t units = 0, panels = 0;
+    for (int g = first; g < first + count; ++g) {
+        units += ksteps_of(Ks[g]) * ceil_div(Ns[g], kPanelN);
+        panels += ceil_div(Ns[g], kPanelN);
+    }
+    const sbi_tuning t = {0, 0, 0, 0, 0};
+    return plan_streamk(B, units, panels, t, pl);
+}
+
 size_t sbi_layer_workspace_bytes(const sbi_layer* L, int64_t B)
 {
     if (layer_check(L, B) != SBI_OK) return 0;
@@ -265,6 +360,11 @@ size_t sbi_layer_workspace_bytes(const sbi_layer* L, int64_t B)
     m = std::max(m, sbi_gemm_workspace_bytes(B, L->k_out, L->h));
     m = std::max(m, sbi_gemm_workspace_bytes(B, L->h, L->n_ffn1));
     m = std::max(m, sbi_gemm_workspace_bytes(B, L->k_ffn2, L->h));
+    if (layer_groupable(L)) {
+        Plan pl;
+        if (layer_group_plan(L, B, 0, 4, pl) == SBI_OK) m = std::max(m, (size_t)pl.ws_bytes);
+        if (layer_group_plan(L, B, 0, 3, pl) == SBI_OK) m = std::max(m, (size_t)pl.ws_bytes);
+    }
     return m;
 }
 
@@ -276,28 +376,47 @@ sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
 {
     if (sbi_status s = layer_check(L, B)) return s;
     if (!Xqkv || !Xout || !Xffn1 || !Yqkv || !Yout || !Yffn1 || !Yffn2) return SBI_ERR_NULL;
-    if (!Xffn2) {
+    const bool chained = (Xffn2 == nullptr);
+    if (chained) {
         if (L->n_ffn1 != L->k_ffn2) return SBI_ERR_SHAPE;
         Xffn2 = Yffn1;
     }
-    if (workspace_bytes < sbi_layer_workspace_bytes(L, B)) return SBI_ERR_WORKSPACE;
+    const size_t need = sbi_layer_workspace_bytes(L, B);
+    if (workspace_bytes < need || (need > 0 && !workspace)) return SBI_ERR_WORKSPACE;
+    if (need > 0 && !aligned(workspace, 256)) return SBI_ERR_ALIGN;
 
-    sbi_status s;
-    s = sbi_gemm(L->Wqkv, L->h, L->n_qkv, Xqkv, B, L->bqkv, nullptr,
-                 L->bqkv ? SBI_EPI_BIAS : SBI_EPI_NONE, Yqkv, workspace, workspace_bytes, hip_stream);
-    if (s != SBI_OK) return s;
-    s = sbi_gemm(L->Wout, L->k_out, L->h, Xout, B, L->bout, nullptr,
-                 L->bout ? SBI_EPI_BIAS : SBI_EPI_NONE, Yout, workspace, workspace_bytes, hip_stream);
-    if (s != SBI_OK) return s;
+    const sbi_epilogue e0 = L->bqkv ? SBI_EPI_BIAS : SBI_EPI_NONE;
+    const sbi_epilogue eo = L->bout ? SBI_EPI_BIAS : SBI_EPI_NONE;
     const sbi_epilogue e1 = L->ffn1_gelu ? (L->bffn1 ? SBI_EPI_BIAS_GELU : SBI_EPI_GELU)
                                          : (L->bffn1 ? SBI_EPI_BIAS : SBI_EPI_NONE);
-    s = sbi_gemm(L->Wffn1, L->h, L->n_ffn1, Xffn1, B, L->bffn1, nullptr, e1, Yffn1,
-                 workspace, workspace_bytes, hip_stream);
-    if (s != SBI_OK) return s;
     const sbi_epilogue e2 = residual ? (L->bffn2 ? SBI_EPI_BIAS_RESIDUAL : SBI_EPI_RESIDUAL)
                                      : (L->bffn2 ? SBI_EPI_BIAS : SBI_EPI_NONE);
-    return sbi_gemm(L->Wffn2, L->k_ffn2, L->h, Xffn2, B, L->bffn2, residual, e2, Yffn2,
-                    workspace, workspace_bytes, hip_stream);
+    GemmArgs a[4] = {
+        {L->Wqkv, L->h, L->n_qkv, Xqkv, L->bqkv, nullptr, 0, Yqkv},
+        {L->Wout, L->k_out, L->h, Xout, L->bout, nullptr, 0, Yout},
+        {L->Wffn1, L->h, L->n_ffn1, Xffn1, L->bffn1, nullptr, 0, Yffn1},
+        {L->Wffn2, L->k_ffn2, L->h, Xffn2, L->bffn2, residual, 0, Yffn2},
+    };
+    const sbi_epilogue epis[4] = {e0, eo, e1, e2};
+    for (int g = 0; g < 4; ++g)
+        if (sbi_status s = check_gemm_args(a[g].Wl, a[g].K, a[g].N, a[g].X, B, a[g].bias, a[g].R,
+                                           (int)epis[g], a[g].Y, a[g].flags)) return s;
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (layer_groupable(L)) {
+        // one launch for the independent GeMMs; a chained FFN2 needs FFN1's output and follows
+        const int count = chained ? 3 : 4;
+        Plan pl;
+        if (sbi_status s = layer_group_plan(L, B, 0, count, pl)) return s;
+        if (sbi_status s = launch_group(a, count, B, pl, workspace, st)) return s;
+        if (!chained) return SBI_OK;
+        return sbi_gemm(L->Wffn2, L->k_ffn2, L->h, Xffn2, B, L->bffn2, residual, e2, Yffn2,
+                        workspace, workspace_bytes, hip_stream);
+    }
+    for (int g = 0; g < 4; ++g)
+        if (sbi_status s = sbi_gemm(a[g].Wl, a[g].K, a[g].N, a[g].X, B, a[g].bias, a[g].R, epis[g], a[g].Y,
+                                    workspace, workspace_bytes, hip_stream)) return s;
+    return SBI_OK;
 }
 
 const char* sbi_status_string(sbi_status s)

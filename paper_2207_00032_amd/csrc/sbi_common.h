@@ -9,19 +9,23 @@ namespace sbi {
 constexpr int kChunkK     = 8;                       // halfs per lane per load
 constexpr int kTileN      = 16;                      // columns per wavefront tile
 constexpr int kTileK      = 32;                      // k per tile ("k-step")
+constexpr int kStepGroup  = 8;                       // k-steps per panel are padded to a multiple of this
 constexpr int kPanelTiles = 4;                       // tiles per panel
 constexpr int kPanelN     = kTileN * kPanelTiles;    // 64 columns
 constexpr int kHeaderBytes = 256;
 constexpr uint32_t kMagic = 0x47494253u;             // "SBIG"
-constexpr uint32_t kLayoutVersion = 1;
+constexpr uint32_t kLayoutVersion = 2;
 constexpr int kNumCU = 256;                          // MI355X
+
+// k-steps per panel of the laid-out buffer (zero padded)
+constexpr int64_t ksteps_of(int64_t K) { return ((K + kTileK - 1) / kTileK + kStepGroup - 1) / kStepGroup * kStepGroup; }
 
 struct LayoutHeader {            // lives in the first 256 bytes of a laid-out buffer
     uint32_t magic;
     uint32_t version;
     int64_t  K;
     int64_t  N;
-    int64_t  KS;                 // ceil(K / 32)
+    int64_t  KS;                 // k-steps per panel: ceil(K / 32) rounded up to a multiple of 8
     int64_t  P;                  // ceil(N / 64)
     int32_t  tile_n, tile_k, panel_tiles, chunk_k;
 };
@@ -56,7 +60,35 @@ struct GemmParams {
     int x_vec;                 // 1: X rows are 16-byte aligned and K % 8 == 0
 };
 
+// ---- work-balanced kernel: up to kMaxGroup independent GeMMs of one batch size per launch ----
+constexpr int kMaxGroup = 4;
+
+struct SkProblem {
+    const u32x4*    Wl;        // laid-out weights, past the header
+    const _Float16* X;         // [B,K], 16-byte aligned, K % 8 == 0
+    const _Float16* bias;
+    const _Float16* R;
+    _Float16*       Y;
+    int K, N;
+    int KS, P;                 // k-steps per panel (multiple of 8), panels
+    int flags;                 // kEpi* bits
+    int unit_base;             // index of this problem's first 4 KiB unit in the launch
+    int panel_base;            // index of this problem's first panel counter
+    int fast;                  // N % 4 == 0 and bias / R / Y 8-byte aligned: 4-wide epilogue
+};
+
+struct SkParams {
+    SkProblem     prob[kMaxGroup];
+    int           G;           // problems in this launch
+    int           B;
+    int           U;           // total units
+    int           upw;         // units per wavefront (multiple of 8)
+    float*        partials;    // [wavefronts][2][B][64] fp32
+    unsigned int* counters;    // one arrival counter per panel of the launch
+};
+
 // launchers implemented in the kernel translation units; return hipError_t as int
+int launch_streamk(const SkParams& p, int waves, int depth, int grid, hipStream_t st);
 int launch_mfma(const GemmParams& p, int waves, int depth, size_t lds_bytes, hipStream_t st);
 int launch_stream(const GemmParams& p, int waves, int depth, size_t lds_bytes, hipStream_t st);
 int launch_layout(const void* W, int64_t K, int64_t N, void* out, hipStream_t st);

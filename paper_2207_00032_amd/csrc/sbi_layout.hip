@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void sbi_unlayout_kernel(const unsigned char* 
 
 int launch_layout(const void* W, int64_t K, int64_t N, void* out, hipStream_t st)
 {
-    const int64_t KS = (K + kTileK - 1) / kTileK;
+    const int64_t KS = ksteps_of(K);
     const int64_t P = (N + kPanelN - 1) / kPanelN;
     const int w_vec = (N % 8 == 0) && ((reinterpret_cast<uintptr_t>(W) & 15) == 0);
     hipLaunchKernelGGL(sbi_layout_kernel, dim3((unsigned)(KS * P)), dim3(256), 0, st,
@@ -114,7 +114,7 @@ int launch_layout(const void* W, int64_t K, int64_t N, void* out, hipStream_t st
 
 int launch_unlayout(const void* Wl, int64_t K, int64_t N, void* out, hipStream_t st)
 {
-    const int64_t KS = (K + kTileK - 1) / kTileK;
+    const int64_t KS = ksteps_of(K);
     const int64_t P = (N + kPanelN - 1) / kPanelN;
     hipLaunchKernelGGL(sbi_unlayout_kernel, dim3((unsigned)(KS * P)), dim3(256), 0, st,
                        reinterpret_cast<const unsigned char*>(Wl), K, N, KS, reinterpret_cast<_Float16*>(out));

@@ -57,7 +57,7 @@ def test_layout_bit_exact_and_invertible(gpu, K, N):
     assert np.array_equal(raw[256:].view(np.uint16), orc.layout_weights(Wbits))
     hdr = raw[:256]
     assert hdr[:4].tobytes() == b"SBIG" and not hdr[56:].any()
-    assert tuple(hdr[8:40].view(np.int64)) == (K, N, -(-K // 32), -(-N // 64))
+    assert tuple(hdr[8:40].view(np.int64)) == (K, N, orc.layout_dims(K, N)[0], -(-N // 64))
     back = sb.unlayout_weights(Wl, K, N)
     torch.cuda.synchronize()
     assert np.array_equal(back.cpu().numpy().view(np.uint16), Wbits)
@@ -72,7 +72,8 @@ def test_ragged_shapes_all_epilogues_both_paths(gpu, B, K, N):
     from paper_2207_00032_amd import binding as sb
     W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=B + K + N, config_id=100)
     Wl = None
-    paths = [sb.PATH_MFMA] + ([sb.PATH_STREAM] if B <= 8 else [])
+    paths = [sb.PATH_AUTO, sb.PATH_MFMA] + ([sb.PATH_STREAM] if B <= 8 else []) + \
+        ([sb.PATH_STREAMK] if K % 8 == 0 else [])
     for epi in ("none", "bias", "bias_gelu", "bias_residual", "gelu", "residual"):
         for path in paths:
             Y, Wl = gpu_gemm(gpu, W, bias, X, R, epi, Wl=Wl, path=path)
@@ -99,22 +100,41 @@ def test_split_k_and_tuning_variants(gpu, B, K, N, waves, depth):
             check(Y, W, bias, X, R, "bias_residual", f"B={B} K={K} N={N} S={S} w={waves} d={depth} path={path}")
 
 
+@pytest.mark.parametrize("B,K,N", [(1, 4096, 192), (5, 2048, 320), (8, 1032, 1000), (16, 520, 72),
+                                   (17, 4096, 130), (40, 1024, 192), (64, 2048, 136)])
+def test_streamk_range_cuts(gpu, B, K, N):
+    """The work-balanced kernel with every kind of range cut: one wavefront for everything,
+    ranges that end inside panels, ranges shorter than a panel (many slabs per panel)."""
+    from paper_2207_00032_amd import binding as sb
+    W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=3, config_id=104)
+    Wl = None
+    for waves, depth in ((4, 4), (4, 8), (8, 4), (8, 8)):
+        if waves == 8 and depth == 8 and B > 16:
+            continue
+        for blocks in (1, 2, 3, 7, 64, 512):
+            for epi in ("bias_gelu", "bias_residual"):
+                Y, Wl = gpu_gemm(gpu, W, bias, X, R, epi, Wl=Wl, path=sb.PATH_STREAMK,
+                                 waves=waves, depth=depth, blocks=blocks)
+                check(Y, W, bias, X, R, epi, f"streamk B={B} K={K} N={N} w={waves} d={depth} blocks={blocks} {epi}")
+
+
 def test_workspace_reuse_and_determinism(gpu):
     """One workspace serves calls of different shapes back to back (the counters return to
     zero), and repeated calls give identical bits."""
     import torch
     from paper_2207_00032_amd import binding as sb
-    shapes = [(4, 2048, 256), (8, 4096, 64), (2, 1024, 512), (4, 2048, 256)]
-    ws = sb.new_workspace(max(sb.plan(B, K, N, split_k=8)["workspace_bytes"] for B, K, N in shapes), gpu)
-    for rep in range(3):
-        for B, K, N in shapes:
-            W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=5, config_id=102)
-            Y1, Wl = gpu_gemm(gpu, W, bias, X, R, "bias_gelu", workspace=ws, split_k=8)
-            Y2, _ = gpu_gemm(gpu, W, bias, X, R, "bias_gelu", Wl=Wl, workspace=ws, split_k=8)
-            assert np.array_equal(Y1.view(np.uint16), Y2.view(np.uint16))
-            check(Y1, W, bias, X, R, "bias_gelu", f"reuse rep={rep} {B}x{K}x{N}")
-    torch.cuda.synchronize()
-    assert not ws[:4096].cpu().numpy()[:256].any()       # counters are back to zero
+    shapes = [(4, 2048, 256), (8, 4096, 64), (2, 1024, 16384), (4, 2048, 256), (3, 512, 40000)]
+    for tune in (dict(path=sb.PATH_MFMA, split_k=8), dict(path=sb.PATH_STREAMK), dict(path=sb.PATH_STREAMK, blocks=37)):
+        ws = sb.new_workspace(max(sb.plan(B, K, N, **tune)["workspace_bytes"] for B, K, N in shapes), gpu)
+        for rep in range(2):
+            for B, K, N in shapes:
+                W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=5, config_id=102)
+                Y1, Wl = gpu_gemm(gpu, W, bias, X, R, "bias_gelu", workspace=ws, **tune)
+                Y2, _ = gpu_gemm(gpu, W, bias, X, R, "bias_gelu", Wl=Wl, workspace=ws, **tune)
+                assert np.array_equal(Y1.view(np.uint16), Y2.view(np.uint16))
+                check(Y1, W, bias, X, R, "bias_gelu", f"reuse rep={rep} {B}x{K}x{N} {tune}")
+        torch.cuda.synchronize()
+        assert not ws[:256 * 1024].cpu().numpy().any()   # every arrival counter is back to zero
 
 
 def test_residual_may_alias_output(gpu):
@@ -138,7 +158,7 @@ def test_subnormal_and_exact_inputs(gpu):
     Wsub |= (rng.integers(0, 2, size=(K, N)).astype(np.uint16) << 15)
     W = Wsub.view(np.float16)
     X = (rng.standard_normal((B, K)) * 64).astype(np.float16)
-    for path in (sb.PATH_MFMA, sb.PATH_STREAM):
+    for path in (sb.PATH_MFMA, sb.PATH_STREAM, sb.PATH_STREAMK):
         Y, _ = gpu_gemm(gpu, W, None, X, None, "none", path=path)
         want = orc.gemm(X, W)
         assert np.abs(want.astype(np.float64)).max() > 0.05                  # the products do matter
@@ -147,7 +167,7 @@ def test_subnormal_and_exact_inputs(gpu):
     # identity weights: Y == X bit for bit
     K = N = 256
     X = rng.standard_normal((B, K)).astype(np.float16)
-    for path in (sb.PATH_MFMA, sb.PATH_STREAM):
+    for path in (sb.PATH_MFMA, sb.PATH_STREAM, sb.PATH_STREAMK):
         Y, _ = gpu_gemm(gpu, np.eye(K, dtype=np.float16), None, X, None, "none", path=path)
         assert np.array_equal(Y.view(np.uint16), X.view(np.uint16))
     # large magnitudes: an overflow to inf must match the oracle's
@@ -178,7 +198,7 @@ def _config_case(gpu, cfg_id, gi, seed, batches, paths=None):
 @pytest.mark.parametrize("gi", [0, 1, 2, 3])
 def test_config1_h1024_layer(gpu, gi):
     from paper_2207_00032_amd import binding as sb
-    _config_case(gpu, 1, gi, 0, (1,), [sb.PATH_AUTO, sb.PATH_MFMA, sb.PATH_STREAM])
+    _config_case(gpu, 1, gi, 0, (1,), [sb.PATH_AUTO, sb.PATH_MFMA, sb.PATH_STREAM, sb.PATH_STREAMK])
 
 
 @pytest.mark.parametrize("gi", [0, 1, 2, 3])
@@ -203,16 +223,17 @@ def test_config4_h12288_full_size(gpu, gi):
 
 def test_config5_crossover_sweep_with_outliers(gpu):
     from paper_2207_00032_amd import binding as sb
-    _config_case(gpu, 5, 0, 0, wl.CONFIGS[5].batches, [sb.PATH_MFMA, sb.PATH_STREAM])
+    _config_case(gpu, 5, 0, 0, wl.CONFIGS[5].batches, [sb.PATH_STREAMK, sb.PATH_MFMA, sb.PATH_STREAM])
 
 
-def test_layer_gemms_matches_oracle(gpu):
-    """sbi_layer_gemms on the h=1024 layer, FFN2 chained on FFN1's output."""
+@pytest.mark.parametrize("cfg_id,B,chained", [(1, 4, True), (1, 1, False), (2, 8, False), (2, 3, True)])
+def test_layer_gemms_matches_oracle(gpu, cfg_id, B, chained):
+    """sbi_layer_gemms: the independent GeMMs go out as one grouped launch; with Xffn2 = NULL
+    FFN2 is chained on FFN1's fp16 output."""
     import torch
     from paper_2207_00032_amd import binding as sb
-    cfg = wl.CONFIGS[1]
-    B = 4
-    data = [wl.make_gemm_inputs(s.K, s.N, B, seed=0, config_id=1, gemm_id=i) for i, s in enumerate(cfg.gemms)]
+    cfg = wl.CONFIGS[cfg_id]
+    data = [wl.make_gemm_inputs(s.K, s.N, B, seed=0, config_id=cfg_id, gemm_id=i) for i, s in enumerate(cfg.gemms)]
     Wls = [sb.layout_weights(_dev(d[0], gpu)) for d in data]
     biases = [_dev(d[1], gpu) for d in data]
     h = cfg.gemms[0].K
@@ -222,11 +243,15 @@ def test_layer_gemms_matches_oracle(gpu):
     Xs = [_dev(d[2], gpu) for d in data]
     Rd = _dev(data[3][3], gpu)
     Ys = [torch.empty((B, s.N), dtype=torch.float16, device=gpu) for s in cfg.gemms]
-    sb.layer_gemms(L, B, Xs[0], Xs[1], Xs[2], None, Rd, Ys[0], Ys[1], Ys[2], Ys[3], ws)
-    torch.cuda.synchronize()
-    Yh = [y.cpu().numpy() for y in Ys]
-    check(Yh[0], data[0][0], data[0][1], data[0][2], None, "bias", "layer qkv")
-    check(Yh[1], data[1][0], None, data[1][2], None, "none", "layer attn_out")
-    check(Yh[2], data[2][0], data[2][1], data[2][2], None, "bias_gelu", "layer ffn1")
-    # FFN2 consumed the GPU's own fp16 FFN1 output
-    check(Yh[3], data[3][0], data[3][1], Yh[2], data[3][3], "bias_residual", "layer ffn2 (chained)")
+    for rep in range(2):
+        sb.layer_gemms(L, B, Xs[0], Xs[1], Xs[2], None if chained else Xs[3], Rd,
+                       Ys[0], Ys[1], Ys[2], Ys[3], ws)
+        torch.cuda.synchronize()
+        Yh = [y.cpu().numpy() for y in Ys]
+        check(Yh[0], data[0][0], data[0][1], data[0][2], None, "bias", "layer qkv")
+        check(Yh[1], data[1][0], None, data[1][2], None, "none", "layer attn_out")
+        check(Yh[2], data[2][0], data[2][1], data[2][2], None, "bias_gelu", "layer ffn1")
+        # a chained FFN2 consumed the GPU's own fp16 FFN1 output
+        xin = Yh[2] if chained else data[3][2]
+        check(Yh[3], data[3][0], data[3][1], xin, data[3][3], "bias_residual", "layer ffn2")
+    assert not ws[:256 * 1024].cpu().numpy().any()

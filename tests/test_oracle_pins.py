@@ -329,6 +329,7 @@ def test_layout_index_formula_brute_force():
         for n in range(N):
             p, t, i = n // 64, (n % 64) // 16, n % 16
             ks, g, e = k // 32, (k % 32) // 8, k % 8
+            assert KS == 8 * -(-(-(-K // 32)) // 8)
             lane = g * 16 + i
             assert flat[((((p * KS + ks) * 4 + t) * 64 + lane) * 8) + e] == W[k, n]
 
