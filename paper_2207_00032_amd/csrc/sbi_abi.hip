@@ -87,10 +87,10 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     sbi_tuning t = {0, 0, 0, 0, 0};
     if (tune) t = *tune;
 
+    if (t.split_k < 0 || t.blocks < 0) return SBI_ERR_TUNING;
     int path = t.path;
     const bool sk_ok = (K % kChunkK == 0);            // X rows readable as 128-bit pieces
-    if (path == SBI_PATH_AUTO)
-        path = sk_ok ? SBI_PATH_STREAMK : ((B <= kAutoStreamBatch) ? SBI_PATH_STREAM : SBI_PATH_MFMA);
+    if (path == SBI_PATH_AUTO) path = (B <= kAutoStreamBatch) ? SBI_PATH_STREAM : SBI_PATH_MFMA;
     if (path == SBI_PATH_STREAMK) {
         if (!sk_ok) return SBI_ERR_TUNING;
         return plan_streamk(B, KS * P, P, t, pl);
@@ -208,6 +208,113 @@ sbi_status launch_group(const GemmArgs* a, int G, int64_t B, const Plan& pl, voi
     return launch_streamk(p, pl.nw, pl.depth, pl.grid, st) == 0 ? SBI_OK : SBI_ERR_HIP;
 }
 
+// Block-kernel parameters of one validated GeMM under plan `pl`; its arrival counters start at
+// counter index `panel_base` and its partial sums at byte offset `partial_off` of the workspace.
+GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* workspace,
+                       int64_t panel_base, int64_t partial_off)
+{
+    GemmParams p;
+    p.Wl = reinterpret_cast<const u32x4*>(reinterpret_cast<const unsigned char*>(a.Wl) + kHeaderBytes);
+    p.X = reinterpret_cast<const _Float16*>(a.X);
+    p.bias = (a.flags & kEpiBias) ? reinterpret_cast<const _Float16*>(a.bias) : nullptr;
+    p.R = (a.flags & kEpiRes) ? reinterpret_cast<const _Float16*>(a.R) : nullptr;
+    p.Y = reinterpret_cast<_Float16*>(a.Y);
+    unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
+    p.counters = (pl.S > 1) ? reinterpret_cast<unsigned int*>(ws) + panel_base : nullptr;
+    p.partials = (pl.S > 1) ? reinterpret_cast<float*>(ws + kCounterBytes + partial_off) : nullptr;
+    p.B = (int)B; p.K = (int)a.K; p.N = (int)a.N;
+    p.KS = (int)ksteps_of(a.K); p.P = (int)ceil_div(a.N, kPanelN);
+    p.S = pl.S; p.ksps = pl.ksps; p.kc = pl.kc;
+    p.flags = a.flags; p.x_vec = (a.K % 8 == 0) ? 1 : 0;
+    return p;
+}
+
+// Plans for `G` GeMMs that go out as one launch of the block kernel: a common block size T
+// (k-steps) is chosen so that all blocks of the launch carry about the same work; problem g is
+// split S_g = ceil(KS_g / T) ways.  Returns per-problem plans plus the launch totals in `tot`
+// (nw, depth, lds, grid, ws_bytes).
+sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot)
+{
+    if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
+    const int64_t max_wd = kMaxLds / (B * 64);
+    int64_t KS[kMaxGroup], P[kMaxGroup], maxKS = 0, minKS = kMaxDim, panels = 0;
+    for (int g = 0; g < G; ++g) {
+        if (sbi_status s = check_shape(Ks[g], Ns[g])) return s;
+        KS[g] = ksteps_of(Ks[g]); P[g] = ceil_div(Ns[g], kPanelN);
+        maxKS = std::max(maxKS, KS[g]); minKS = std::min(minKS, KS[g]); panels += P[g];
+    }
+    if (panels > kCounterBytes / 4) return SBI_ERR_SHAPE;
+    const int nw = (max_wd >= 32 && minKS >= 32) ? 8 : 4;
+    const int depth = 4;
+    const int64_t wd = (int64_t)nw * depth;
+    int64_t bestT = 0;
+    double best = 0.0;
+    for (int64_t T = wd; T < maxKS + wd; T += wd) {
+        int64_t blocks = 0, maxk = 0;
+        double partial = 0.0;
+        for (int g = 0; g < G; ++g) {
+            const int64_t S = ceil_div(KS[g], T);
+            const int64_t ksps = ceil_div(KS[g], S);
+            blocks += P[g] * S;
+            maxk = std::max(maxk, ksps);
+            if (S > 1) partial += (double)(P[g] * S) * (double)B * 512.0;
+        }
+        const int64_t rounds = ceil_div(blocks, kNumCU);
+        const double busy = (double)std::min<int64_t>(blocks, kNumCU) / kNumCU;
+        const double cost = (double)rounds * ((double)maxk + 20.0) * (busy >= 0.75 ? 1.0 : 0.75 / busy) +
+                            partial / kNumCU / 4096.0;
+        if (bestT == 0 || cost < best) { best = cost; bestT = T; }
+    }
+    int64_t grid = 0, partial_bytes = 0, lds = 0;
+    bool any_split = false;
+    for (int g = 0; g < G; ++g) {
+        Plan& pl = pls[g];
+        const int64_t S = ceil_div(KS[g], bestT);
+        const int64_t ksps = ceil_div(KS[g], S);
+        const int64_t kc_max = (kMaxLds / (B * 64)) / wd * wd;
+        const int64_t kc = std::min<int64_t>(kc_max, round_up(ksps, wd));
+        pl.path = SBI_PATH_MFMA; pl.nw = nw; pl.depth = depth;
+        pl.S = (int)ceil_div(KS[g], ksps); pl.ksps = (int)ksps; pl.kc = (int)kc;
+        pl.grid = (int)(P[g] * pl.S); pl.block = nw * 64;
+        pl.lds = std::max<int64_t>(kc * B * 64, (int64_t)nw * 16 * kRedPitch * 4);
+        pl.counter_bytes = kCounterBytes;
+        pl.ws_bytes = (pl.S > 1) ? P[g] * pl.S * B * kPanelN * 4 : 0;     // partial sums only
+        pl.upw = 0; pl.nwaves = 0;
+        grid += pl.grid; partial_bytes += pl.ws_bytes; lds = std::max(lds, pl.lds);
+        any_split = any_split || pl.S > 1;
+    }
+    if (grid > (int64_t)0x7fffffff) return SBI_ERR_SHAPE;
+    tot = pls[0];
+    tot.grid = (int)grid; tot.lds = lds;
+    tot.ws_bytes = any_split ? kCounterBytes + partial_bytes : 0;
+    return SBI_OK;
+}
+
+// Launch G validated GeMMs as one grouped block-kernel launch (split problems first: their
+// cross-block tails then overlap with the streaming of the blocks that start later).
+sbi_status launch_block_group(const GemmArgs* a, const Plan* pls, const Plan& tot, int G, int64_t B,
+                              void* workspace, hipStream_t st)
+{
+    int order[kMaxGroup];
+    for (int g = 0; g < G; ++g) order[g] = g;
+    std::stable_sort(order, order + G, [&](int x, int y) { return pls[x].S > pls[y].S; });
+    GroupParams gp;
+    std::memset(&gp, 0, sizeof gp);
+    gp.G = G;
+    int64_t panel_base = 0, partial_off = 0;
+    int first = 0;
+    for (int k = 0; k < G; ++k) {
+        const int g = order[k];
+        gp.g[k] = fill_params(a[g], B, pls[g], workspace, panel_base, partial_off);
+        gp.first_block[k] = first;
+        first += pls[g].grid;
+        panel_base += gp.g[k].P;
+        partial_off += pls[g].ws_bytes;
+    }
+    gp.first_block[G] = first;
+    return launch_mfma(gp, tot.nw, tot.depth, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
+}
+
 }  // namespace
 
 extern "C" {
@@ -293,23 +400,12 @@ sbi_status sbi_gemm_ex(const void* W_laid_out, int64_t K, int64_t N,
         return launch_group(&a, 1, B, pl, workspace, st);
     }
 
-    GemmParams p;
-    p.Wl = reinterpret_cast<const u32x4*>(reinterpret_cast<const unsigned char*>(W_laid_out) + kHeaderBytes);
-    p.X = reinterpret_cast<const _Float16*>(X);
-    p.bias = (flags & kEpiBias) ? reinterpret_cast<const _Float16*>(bias) : nullptr;
-    p.R = (flags & kEpiRes) ? reinterpret_cast<const _Float16*>(residual) : nullptr;
-    p.Y = reinterpret_cast<_Float16*>(Y);
-    p.counters = pl.ws_bytes ? reinterpret_cast<unsigned int*>(workspace) : nullptr;
-    p.partials = pl.ws_bytes ? reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(workspace) + pl.counter_bytes)
-                             : nullptr;
-    p.B = (int)B; p.K = (int)K; p.N = (int)N;
-    p.KS = (int)ksteps_of(K); p.P = (int)ceil_div(N, kPanelN);
-    p.S = pl.S; p.ksps = pl.ksps; p.kc = pl.kc;
-    p.flags = flags; p.x_vec = (K % 8 == 0) ? 1 : 0;
-
-    const int rc = (pl.path == SBI_PATH_STREAM) ? launch_stream(p, pl.nw, pl.depth, (size_t)pl.lds, st)
-                                                : launch_mfma(p, pl.nw, pl.depth, (size_t)pl.lds, st);
-    return rc == 0 ? SBI_OK : SBI_ERR_HIP;
+    const GemmArgs a = {W_laid_out, K, N, X, bias, residual, flags, Y};
+    Plan one = pl;
+    one.ws_bytes = (pl.S > 1) ? pl.ws_bytes - pl.counter_bytes : 0;
+    if (pl.path == SBI_PATH_MFMA) return launch_block_group(&a, &one, pl, 1, B, workspace, st);
+    const GemmParams p = fill_params(a, B, pl, workspace, 0, 0);
+    return launch_stream(p, pl.nw, pl.depth, (size_t)pl.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
 }
 
 sbi_status sbi_gemm(const void* W_laid_out, int64_t K, int64_t N,
@@ -333,38 +429,21 @@ static sbi_status layer_check(const sbi_layer* L, int64_t B)
     return SBI_OK;
 }
 
-// The four GeMMs can share work-balanced launches when each of them can take that path.
-static bool layer_groupable(const sbi_layer* L)
-{
-    return L->h % kChunkK == 0 && L->k_out % kChunkK == 0 && L->k_ffn2 % kChunkK == 0;
-}
-
-// Plan of a grouped launch over GeMMs [first, first+count) of the layer.
-static sbi_status layer_group_plan(const sbi_layer* L, int64_t B, int first, int count, Plan& pl)
+// Plans of a grouped launch over GeMMs [0, count) of the layer.
+static sbi_status layer_group_plan(const sbi_layer* L, int64_t B, int count, Plan* pls, Plan& tot)
 {
     const int64_t Ks[4] = {L->h, L->k_out, L->h, L->k_ffn2};
     const int64_t Ns[4] = {L->n_qkv, L->h, L->n_ffn1, L->h};
-    int64_t units = 0, panels = 0;
-    for (int g = first; g < first + count; ++g) {
-        units += ksteps_of(Ks[g]) * ceil_div(Ns[g], kPanelN);
-        panels += ceil_div(Ns[g], kPanelN);
-    }
-    const sbi_tuning t = {0, 0, 0, 0, 0};
-    return plan_streamk(B, units, panels, t, pl);
+    return plan_group(B, Ks, Ns, count, pls, tot);
 }
 
 size_t sbi_layer_workspace_bytes(const sbi_layer* L, int64_t B)
 {
     if (layer_check(L, B) != SBI_OK) return 0;
-    size_t m = sbi_gemm_workspace_bytes(B, L->h, L->n_qkv);
-    m = std::max(m, sbi_gemm_workspace_bytes(B, L->k_out, L->h));
-    m = std::max(m, sbi_gemm_workspace_bytes(B, L->h, L->n_ffn1));
-    m = std::max(m, sbi_gemm_workspace_bytes(B, L->k_ffn2, L->h));
-    if (layer_groupable(L)) {
-        Plan pl;
-        if (layer_group_plan(L, B, 0, 4, pl) == SBI_OK) m = std::max(m, (size_t)pl.ws_bytes);
-        if (layer_group_plan(L, B, 0, 3, pl) == SBI_OK) m = std::max(m, (size_t)pl.ws_bytes);
-    }
+    size_t m = sbi_gemm_workspace_bytes(B, L->k_ffn2, L->h);        // a chained FFN2 runs on its own
+    Plan pls[4], tot;
+    if (layer_group_plan(L, B, 4, pls, tot) == SBI_OK) m = std::max(m, (size_t)tot.ws_bytes);
+    if (layer_group_plan(L, B, 3, pls, tot) == SBI_OK) m = std::max(m, (size_t)tot.ws_bytes);
     return m;
 }
 
@@ -402,21 +481,15 @@ sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
         if (sbi_status s = check_gemm_args(a[g].Wl, a[g].K, a[g].N, a[g].X, B, a[g].bias, a[g].R,
                                            (int)epis[g], a[g].Y, a[g].flags)) return s;
 
+    // one launch for the independent GeMMs; a chained FFN2 needs FFN1's output and follows
     hipStream_t st = (hipStream_t)hip_stream;
-    if (layer_groupable(L)) {
-        // one launch for the independent GeMMs; a chained FFN2 needs FFN1's output and follows
-        const int count = chained ? 3 : 4;
-        Plan pl;
-        if (sbi_status s = layer_group_plan(L, B, 0, count, pl)) return s;
-        if (sbi_status s = launch_group(a, count, B, pl, workspace, st)) return s;
-        if (!chained) return SBI_OK;
-        return sbi_gemm(L->Wffn2, L->k_ffn2, L->h, Xffn2, B, L->bffn2, residual, e2, Yffn2,
-                        workspace, workspace_bytes, hip_stream);
-    }
-    for (int g = 0; g < 4; ++g)
-        if (sbi_status s = sbi_gemm(a[g].Wl, a[g].K, a[g].N, a[g].X, B, a[g].bias, a[g].R, epis[g], a[g].Y,
-                                    workspace, workspace_bytes, hip_stream)) return s;
-    return SBI_OK;
+    const int count = chained ? 3 : 4;
+    Plan pls[4], tot;
+    if (sbi_status s = layer_group_plan(L, B, count, pls, tot)) return s;
+    if (sbi_status s = launch_block_group(a, pls, tot, count, B, workspace, st)) return s;
+    if (!chained) return SBI_OK;
+    return sbi_gemm(L->Wffn2, L->k_ffn2, L->h, Xffn2, B, L->bffn2, residual, e2, Yffn2,
+                    workspace, workspace_bytes, hip_stream);
 }
 
 const char* sbi_status_string(sbi_status s)

@@ -60,8 +60,16 @@ struct GemmParams {
     int x_vec;                 // 1: X rows are 16-byte aligned and K % 8 == 0
 };
 
-// ---- work-balanced kernel: up to kMaxGroup independent GeMMs of one batch size per launch ----
+// ---- grouped launches: up to kMaxGroup independent GeMMs of one batch size per launch ----
 constexpr int kMaxGroup = 4;
+
+// Block-decomposed kernel over several problems: blocks [first_block[g], first_block[g+1])
+// belong to problem g and are numbered (panel, split) inside it.
+struct GroupParams {
+    GemmParams g[kMaxGroup];
+    int        G;
+    int        first_block[kMaxGroup + 1];
+};
 
 struct SkProblem {
     const u32x4*    Wl;        // laid-out weights, past the header
@@ -89,7 +97,7 @@ struct SkParams {
 
 // launchers implemented in the kernel translation units; return hipError_t as int
 int launch_streamk(const SkParams& p, int waves, int depth, int grid, hipStream_t st);
-int launch_mfma(const GemmParams& p, int waves, int depth, size_t lds_bytes, hipStream_t st);
+int launch_mfma(const GroupParams& gp, int waves, int depth, size_t lds_bytes, hipStream_t st);
 int launch_stream(const GemmParams& p, int waves, int depth, size_t lds_bytes, hipStream_t st);
 int launch_layout(const void* W, int64_t K, int64_t N, void* out, hipStream_t st);
 int launch_unlayout(const void* Wl, int64_t K, int64_t N, void* out, hipStream_t st);

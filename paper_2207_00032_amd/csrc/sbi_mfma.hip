@@ -47,10 +47,17 @@ struct MfmaOp {
     }
 };
 
+// One launch may carry several independent GeMMs of the same batch size (the linear layers of
+// one transformer layer): their blocks are simply concatenated, so the ramp-up and the tail of
+// a launch are paid once per layer instead of once per GeMM.
 template <int MB, int NW, int DEPTH>
-__global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GemmParams p)
+__global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
 {
     constexpr int NT = NW * 64;
+    int gi = 0;
+    while (gi + 1 < gp.G && (int)blockIdx.x >= gp.first_block[gi + 1]) ++gi;
+    const GemmParams& p = gp.g[gi];
+    const int bid = (int)blockIdx.x - gp.first_block[gi];
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     u32x4* xs  = reinterpret_cast<u32x4*>(smem_raw);
     float* red = reinterpret_cast<float*>(smem_raw);
@@ -62,8 +69,8 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GemmParams p)
     const int g = lane >> 4;          // k group within a k-step (8 k each)
     const int i = lane & 15;          // column within a tile (A operand) / batch row (B operand)
 
-    const int panel = blockIdx.x / p.S;
-    const int split = blockIdx.x - panel * p.S;
+    const int panel = bid / p.S;
+    const int split = bid - panel * p.S;
     const int ks0 = split * p.ksps;
     const int ks1 = min(p.KS, ks0 + p.ksps);
 
@@ -87,30 +94,31 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GemmParams p)
 }
 
 template <int MB, int NW, int DEPTH>
-static int launch_one(const GemmParams& p, size_t lds, hipStream_t st)
+static int launch_one(const GroupParams& gp, size_t lds, hipStream_t st)
 {
-    hipLaunchKernelGGL((sbi_mfma_kernel<MB, NW, DEPTH>), dim3(p.P * p.S), dim3(NW * 64), lds, st, p);
+    hipLaunchKernelGGL((sbi_mfma_kernel<MB, NW, DEPTH>), dim3(gp.first_block[gp.G]), dim3(NW * 64), lds, st, gp);
     return (int)hipGetLastError();
 }
 
 template <int NW, int DEPTH>
-static int launch_mb(const GemmParams& p, size_t lds, hipStream_t st)
+static int launch_mb(const GroupParams& gp, size_t lds, hipStream_t st)
 {
-    switch ((p.B + 15) / 16) {
-        case 1: return launch_one<1, NW, DEPTH>(p, lds, st);
-        case 2: return launch_one<2, NW, DEPTH>(p, lds, st);
-        case 3: return launch_one<3, NW, DEPTH>(p, lds, st);
-        case 4: return launch_one<4, NW, DEPTH>(p, lds, st);
+    switch ((gp.g[0].B + 15) / 16) {
+        case 1: return launch_one<1, NW, DEPTH>(gp, lds, st);
+        case 2: return launch_one<2, NW, DEPTH>(gp, lds, st);
+        case 3: return launch_one<3, NW, DEPTH>(gp, lds, st);
+        case 4: return launch_one<4, NW, DEPTH>(gp, lds, st);
     }
     return (int)hipErrorInvalidValue;
 }
 
-int launch_mfma(const GemmParams& p, int waves, int depth, size_t lds_bytes, hipStream_t st)
+int launch_mfma(const GroupParams& gp, int waves, int depth, size_t lds_bytes, hipStream_t st)
 {
-    if (waves == 4 && depth == 4) return launch_mb<4, 4>(p, lds_bytes, st);
-    if (waves == 4 && depth == 8) return launch_mb<4, 8>(p, lds_bytes, st);
-    if (waves == 8 && depth == 4) return launch_mb<8, 4>(p, lds_bytes, st);
-    if (waves == 8 && depth == 8) return launch_mb<8, 8>(p, lds_bytes, st);
+    if (gp.G < 1 || gp.G > kMaxGroup) return (int)hipErrorInvalidValue;
+    if (waves == 4 && depth == 4) return launch_mb<4, 4>(gp, lds_bytes, st);
+    if (waves == 4 && depth == 8) return launch_mb<4, 8>(gp, lds_bytes, st);
+    if (waves == 8 && depth == 4) return launch_mb<8, 4>(gp, lds_bytes, st);
+    if (waves == 8 && depth == 8) return launch_mb<8, 8>(gp, lds_bytes, st);
     return (int)hipErrorInvalidValue;
 }
 

@@ -43,54 +43,90 @@ __device__ __forceinline__ void sk_load_pair(const float* src, float& s0, float&
     s1 = __builtin_bit_cast(float, (unsigned int)(bits >> 32));
 }
 
+// Epilogue + fp16 store of four consecutive columns n0..n0+3 of batch row b.
+__device__ __forceinline__ void sk_finish4(const SkProblem& q, int b, int n0, float (&v)[4])
+{
+    if (n0 >= q.N) return;
+    const int flags = q.flags;
+    const int64_t off = (int64_t)b * q.N + n0;
+    if (q.fast) {
+        typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+        if (flags & kEpiBias) {
+            const half4 bv = *reinterpret_cast<const half4*>(q.bias + n0);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] += (float)bv[r];
+        }
+        if (flags & kEpiGelu) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] = sk_gelu(v[r]);
+        }
+        if (flags & kEpiRes) {
+            const half4 rv = *reinterpret_cast<const half4*>(q.R + off);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] += (float)rv[r];
+        }
+        half4 out = {(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+        *reinterpret_cast<half4*>(q.Y + off) = out;
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int n = n0 + r;
+            if (n >= q.N) continue;
+            float x = v[r];
+            if (flags & kEpiBias) x += (float)q.bias[n];
+            if (flags & kEpiGelu) x = sk_gelu(x);
+            if (flags & kEpiRes) x += (float)q.R[off + r];
+            q.Y[off + r] = (_Float16)x;
+        }
+    }
+}
+
 // Epilogue + store of one panel from the MFMA result layout: lane (g4, i) holds, for tile t
 // and row block m, columns panel*64 + t*16 + 4*g4 .. +3 of batch row m*16 + i.
 template <int MB>
 __device__ __forceinline__ void sk_epilogue_store(const SkProblem& q, int B, int panel,
                                                   const floatx4 (&acc)[kPanelTiles][MB], int g4, int i)
 {
-    const int flags = q.flags;
 #pragma unroll
     for (int m = 0; m < MB; ++m) {
         const int b = m * 16 + i;
         if (b >= B) continue;
 #pragma unroll
         for (int t = 0; t < kPanelTiles; ++t) {
-            const int n0 = panel * kPanelN + t * kTileN + 4 * g4;
-            if (n0 >= q.N) continue;
             float v[4] = {acc[t][m][0], acc[t][m][1], acc[t][m][2], acc[t][m][3]};
-            const int64_t off = (int64_t)b * q.N + n0;
-            if (q.fast) {
-                typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-                if (flags & kEpiBias) {
-                    const half4 bv = *reinterpret_cast<const half4*>(q.bias + n0);
+            sk_finish4(q, b, panel * kPanelN + t * kTileN + 4 * g4, v);
+        }
+    }
+}
+
+// Finish a panel that several wavefronts contributed to: the B x 64 tile is spread flat over
+// the 64 lanes (4 columns each); every lane sums its piece over the slabs of wavefronts
+// wf..wl in that order (so the result does not depend on who does it), requesting the slabs
+// eight at a time so their latencies overlap, then runs the epilogue.
+__device__ __forceinline__ void sk_fixup(const SkParams& p, const SkProblem& q, int panel, int wf, int wl, int lane)
+{
+    constexpr int kBatch = 8;
+    const int pieces = p.B * (kPanelN / 4);
+    for (int e = lane; e < pieces; e += 64) {
+        const int b = e >> 4;
+        const int c4 = (e & 15) * 4;
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int w0 = wf; w0 <= wl; w0 += kBatch) {
+            float t0[kBatch], t1[kBatch], t2[kBatch], t3[kBatch];
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) v[r] += (float)bv[r];
-                }
-                if (flags & kEpiGelu) {
+            for (int j = 0; j < kBatch; ++j) {
+                const int ww = min(w0 + j, wl);          // repeats of the last slab are dropped below
+                const int slab = (ww == wf) ? 2 * ww + 1 : 2 * ww;
+                const float* src = p.partials + ((int64_t)slab * p.B + b) * kPanelN + c4;
+                sk_load_pair(src, t0[j], t1[j]);
+                sk_load_pair(src + 2, t2[j], t3[j]);
+            }
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) v[r] = sk_gelu(v[r]);
-                }
-                if (flags & kEpiRes) {
-                    const half4 rv = *reinterpret_cast<const half4*>(q.R + off);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) v[r] += (float)rv[r];
-                }
-                half4 out = {(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
-                *reinterpret_cast<half4*>(q.Y + off) = out;
-            } else {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int n = n0 + r;
-                    if (n >= q.N) continue;
-                    float x = v[r];
-                    if (flags & kEpiBias) x += (float)q.bias[n];
-                    if (flags & kEpiGelu) x = sk_gelu(x);
-                    if (flags & kEpiRes) x += (float)q.R[off + r];
-                    q.Y[off + r] = (_Float16)x;
-                }
+            for (int j = 0; j < kBatch; ++j) {
+                if (w0 + j <= wl) { v[0] += t0[j]; v[1] += t1[j]; v[2] += t2[j]; v[3] += t3[j]; }
             }
         }
+        sk_finish4(q, b, panel * kPanelN + c4, v);
     }
 }
 
@@ -245,29 +281,7 @@ __global__ __launch_bounds__(NW * 64) void sbi_streamk_kernel(const SkParams p)
         old = __builtin_amdgcn_readfirstlane(old);
         if (old != (unsigned int)(nseg - 1)) continue;
         // last to arrive: sum the slabs in range order, then the epilogue
-#pragma unroll
-        for (int t = 0; t < kPanelTiles; ++t)
-#pragma unroll
-            for (int m = 0; m < MB; ++m) acc[t][m] = floatx4{0.f, 0.f, 0.f, 0.f};
-        for (int ww = wf; ww <= wl; ++ww) {
-            const int slab = (ww == wf) ? 2 * ww + 1 : 2 * ww;
-            const float* src = p.partials + (int64_t)slab * p.B * kPanelN;
-#pragma unroll
-            for (int m = 0; m < MB; ++m) {
-                const int b = m * 16 + i;
-                if (b < p.B) {
-#pragma unroll
-                    for (int t = 0; t < kPanelTiles; ++t) {
-                        const float* s2 = src + (int64_t)b * kPanelN + t * kTileN + 4 * g4;
-                        float a0, a1, a2, a3;
-                        sk_load_pair(s2, a0, a1);
-                        sk_load_pair(s2 + 2, a2, a3);
-                        acc[t][m][0] += a0; acc[t][m][1] += a1; acc[t][m][2] += a2; acc[t][m][3] += a3;
-                    }
-                }
-            }
-        }
-        sk_epilogue_store<MB>(q, p.B, pn, acc, g4, i);
+        sk_fixup(p, q, pn, wf, wl, lane);
         if (lane == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
