@@ -36,7 +36,9 @@ def parse_args():
     ap.add_argument("--copies", type=int, default=0, help="weight copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-gemm", action="store_true", help="also time every GeMM as a launch of its own")
-    ap.add_argument("--path", type=str, default="auto", choices=["auto", "stream", "mfma"])
+    ap.add_argument("--path", type=str, default="auto", choices=["auto", "stream", "mfma", "streamk"])
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="run a few copy-kernel and layer launches and exit (for rocprofv3 --pmc runs)")
     return ap.parse_args()
 
 
@@ -84,8 +86,10 @@ def main():
     layers = [sb.make_layer(*Wl[c], h_dim, specs[0].N, specs[1].K, specs[2].N, specs[3].K,
                             bqkv=bias_d[0], bout=bias_d[1], bffn1=bias_d[2], bffn2=bias_d[3], ffn1_gelu=gelu)
               for c in range(copies)]
-    ws = sb.new_workspace(max(sb.layer_workspace_bytes(layers[0], B) for B in batches), dev)
-    path = {"auto": sb.PATH_AUTO, "stream": sb.PATH_STREAM, "mfma": sb.PATH_MFMA}[args.path]
+    ws = sb.new_workspace(max([sb.layer_workspace_bytes(layers[0], B) for B in batches] +
+                              [sb.plan(B, s.K, s.N)["workspace_bytes"] for B in batches for s in specs]), dev)
+    path = {"auto": sb.PATH_AUTO, "stream": sb.PATH_STREAM, "mfma": sb.PATH_MFMA,
+            "streamk": sb.PATH_STREAMK}[args.path]
 
     def step(i):
         L = layers[i % copies]
@@ -98,6 +102,19 @@ def main():
                 for gi, s in enumerate(specs):
                     sb.gemm(Wc[gi], s.K, s.N, x[gi], bias_d[gi], R_d[B] if gi == 3 else None, s.epilogue,
                             out=y[gi], workspace=ws, path=path)
+
+    if args.pmc_probe:
+        # known-traffic reference (reads 256 MiB, writes 256 MiB), then the layer launches
+        src = torch.randint(0, 255, (256 << 20,), dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            sb.calib_copy(src, dst)
+        for i in range(4):
+            step(i)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_probe": True, "copy_bytes": 256 << 20, "batches": list(batches),
+                          "layer_bytes": {str(B): sum(s.algorithmic_bytes(B) for s in specs) for B in batches}}))
+        return
 
     # ---- timed region ---------------------------------------------------------------------
     for i in range(args.warmup):

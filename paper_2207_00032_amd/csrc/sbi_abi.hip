@@ -77,6 +77,8 @@ double split_cost(int64_t KS, int64_t P, int64_t B, int S, int nw)
     return cost;
 }
 
+sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot);
+
 sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Plan& pl)
 {
     if (sbi_status s = check_shape(K, N)) return s;
@@ -97,6 +99,12 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     }
     if (path != SBI_PATH_STREAM && path != SBI_PATH_MFMA) return SBI_ERR_TUNING;
     if (path == SBI_PATH_STREAM && B > kStreamMaxBatch) return SBI_ERR_TUNING;
+    if (path == SBI_PATH_MFMA && t.split_k == 0 && t.waves == 0 && t.depth == 0) {
+        Plan one;
+        if (sbi_status s = plan_group(B, &K, &N, 1, &one, pl)) return s;
+        pl.S = one.S; pl.ksps = one.ksps; pl.kc = one.kc;
+        return SBI_OK;
+    }
 
     // the X chunk staged in LDS holds at least waves*depth k-steps of B rows (64 B per row per k-step)
     const int64_t max_wd = kMaxLds / (B * 64);
@@ -229,49 +237,84 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
     return p;
 }
 
-// Plans for `G` GeMMs that go out as one launch of the block kernel: a common block size T
-// (k-steps) is chosen so that all blocks of the launch carry about the same work; problem g is
-// split S_g = ceil(KS_g / T) ways.  Returns per-problem plans plus the launch totals in `tot`
-// (nw, depth, lds, grid, ws_bytes).
+// Wavefronts per CU that the register file lets the MFMA block kernel keep resident (from the
+// compiled kernels' register counts: MB = ceil(B/16) row blocks of accumulators).
+int resident_waves(int mb, int nw)
+{
+    if (mb <= 1) return nw == 8 ? 16 : 12;
+    if (mb == 2) return 12;
+    return 8;
+}
+
+// Plans for `G` GeMMs that go out as one launch of the block kernel.  A common block size T
+// (k-steps) gives all blocks of the launch about the same work; problem g is split
+// S_g = ceil(KS_g / T) ways.  Measured on MI355X: the launch is fastest when ALL its blocks
+// are resident at once (a second dispatch round lands unevenly on the CUs), so candidates are
+// ranked by  rounds x blocks-per-CU x block time, where the blocks a CU can hold follow from
+// the LDS each block needs for its X chunk and from the register file.  Returns per-problem
+// plans plus the launch totals in `tot` (nw, depth, lds, grid, ws_bytes).
 sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot)
 {
     if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
-    const int64_t max_wd = kMaxLds / (B * 64);
-    int64_t KS[kMaxGroup], P[kMaxGroup], maxKS = 0, minKS = kMaxDim, panels = 0;
+    const int mb = (int)ceil_div(B, 16);
+    int64_t KS[kMaxGroup], P[kMaxGroup], maxKS = 0, panels = 0;
     for (int g = 0; g < G; ++g) {
         if (sbi_status s = check_shape(Ks[g], Ns[g])) return s;
         KS[g] = ksteps_of(Ks[g]); P[g] = ceil_div(Ns[g], kPanelN);
-        maxKS = std::max(maxKS, KS[g]); minKS = std::min(minKS, KS[g]); panels += P[g];
+        maxKS = std::max(maxKS, KS[g]); panels += P[g];
     }
     if (panels > kCounterBytes / 4) return SBI_ERR_SHAPE;
-    const int nw = (max_wd >= 32 && minKS >= 32) ? 8 : 4;
-    const int depth = 4;
-    const int64_t wd = (int64_t)nw * depth;
-    int64_t bestT = 0;
+    constexpr int depth = 4;
+    constexpr int64_t kLdsPerCU = 160 * 1024;
+    const int64_t lds_caps[3] = {16 * 1024, 32 * 1024, kMaxLds};
+
+    int best_nw = 0;
+    int64_t bestT = 0, best_cap = 0;
     double best = 0.0;
-    for (int64_t T = wd; T < maxKS + wd; T += wd) {
-        int64_t blocks = 0, maxk = 0;
-        double partial = 0.0;
-        for (int g = 0; g < G; ++g) {
-            const int64_t S = ceil_div(KS[g], T);
-            const int64_t ksps = ceil_div(KS[g], S);
-            blocks += P[g] * S;
-            maxk = std::max(maxk, ksps);
-            if (S > 1) partial += (double)(P[g] * S) * (double)B * 512.0;
+    for (int nw = 4; nw <= 8; nw += 4) {
+        const int64_t wd = (int64_t)nw * depth;
+        const int64_t red_bytes = (int64_t)nw * 16 * kRedPitch * 4;
+        for (int64_t cap : lds_caps) {
+            const int64_t kc_cap = (cap / (B * 64)) / wd * wd;
+            if (kc_cap < wd) continue;
+            for (int64_t T = wd; T < maxKS + wd; T += wd) {
+                int64_t blocks = 0, maxk = 0, lds = red_bytes, chunks = 1;
+                double partial = 0.0;
+                for (int g = 0; g < G; ++g) {
+                    const int64_t S = ceil_div(KS[g], T);
+                    const int64_t ksps = ceil_div(KS[g], S);
+                    const int64_t kc = std::min<int64_t>(kc_cap, round_up(ksps, wd));
+                    blocks += P[g] * S;
+                    maxk = std::max(maxk, ksps);
+                    lds = std::max(lds, kc * B * 64);
+                    chunks = std::max(chunks, ceil_div(ksps, kc));
+                    if (S > 1) partial += (double)(P[g] * S) * (double)B * 512.0;
+                }
+                const int64_t fit = std::max<int64_t>(1, std::min<int64_t>(kLdsPerCU / lds,
+                                                                           resident_waves(mb, nw) / nw));
+                const int64_t per_cu = std::min<int64_t>(fit, ceil_div(blocks, kNumCU));   // concurrent blocks on a CU
+                const int64_t rounds = ceil_div(blocks, (int64_t)kNumCU * fit);
+                const double busy = (double)std::min<int64_t>(blocks, kNumCU) / kNumCU;
+                // every block: ramp-up, reduction, epilogue (about 20 k-steps of streaming time);
+                // every further X chunk restarts the load pipeline (about 6)
+                const double block_time = (double)maxk + 20.0 + 6.0 * (double)(chunks - 1);
+                double cost = (double)rounds * (double)per_cu * block_time * (busy >= 0.75 ? 1.0 : 0.75 / busy) +
+                              partial / kNumCU / 4096.0;
+                if ((int64_t)per_cu * nw < 8) cost *= 1.3;        // too few wavefronts to keep HBM busy
+                if (best_nw == 0 || cost < best) { best = cost; best_nw = nw; bestT = T; best_cap = cap; }
+            }
         }
-        const int64_t rounds = ceil_div(blocks, kNumCU);
-        const double busy = (double)std::min<int64_t>(blocks, kNumCU) / kNumCU;
-        const double cost = (double)rounds * ((double)maxk + 20.0) * (busy >= 0.75 ? 1.0 : 0.75 / busy) +
-                            partial / kNumCU / 4096.0;
-        if (bestT == 0 || cost < best) { best = cost; bestT = T; }
     }
+    if (best_nw == 0) return SBI_ERR_SHAPE;
+    const int nw = best_nw;
+    const int64_t wd = (int64_t)nw * depth;
     int64_t grid = 0, partial_bytes = 0, lds = 0;
     bool any_split = false;
     for (int g = 0; g < G; ++g) {
         Plan& pl = pls[g];
         const int64_t S = ceil_div(KS[g], bestT);
         const int64_t ksps = ceil_div(KS[g], S);
-        const int64_t kc_max = (kMaxLds / (B * 64)) / wd * wd;
+        const int64_t kc_max = (best_cap / (B * 64)) / wd * wd;
         const int64_t kc = std::min<int64_t>(kc_max, round_up(ksps, wd));
         pl.path = SBI_PATH_MFMA; pl.nw = nw; pl.depth = depth;
         pl.S = (int)ceil_div(KS[g], ksps); pl.ksps = (int)ksps; pl.kc = (int)kc;
