@@ -42,6 +42,21 @@ def parse_args():
     return ap.parse_args()
 
 
+def measured_traffic(args, batches):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE
+    runs scaled against the copy kernel), if it covers exactly this workload; else None."""
+    if args.config != 2 or tuple(batches) != (1, 2, 4, 8) or args.path != "auto":
+        return None
+    path = os.path.join(ROOT, "profiles", "sbi_mfma_kernel_config2_pmc_traffic.md")
+    try:
+        for line in open(path):
+            if line.strip().startswith("traffic_bytes_per_launch"):
+                return int(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -192,7 +207,7 @@ def main():
              sb.PATH_STREAM: "sbi_stream_kernel"}[pl0["path"]]
     achieved = tot_bytes / (tot_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(args, batches),
                 "kernel": f"{kname}<{(Bmax + 15) // 16 if pl0['path'] != sb.PATH_STREAM else Bmax},"
                           f"{pl0['waves']},{pl0['depth']}>",
                 "launches": tot_n, "avg_launch_us": round(tot_us / tot_n, 2),
