@@ -194,6 +194,14 @@ sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
 size_t sbi_layer_workspace_bytes(const sbi_layer* L, int64_t B);
 
 /*
+ * Host-only: the launch sbi_layer_gemms makes for the layer's independent GeMMs (`chained`
+ * nonzero: QKV, attention output, FFN1; zero: all four).  plans[g] receives GeMM g's share:
+ * its split, k-steps per block, X chunk and number of blocks; waves, depth, block and
+ * lds_bytes are those of the common launch.  *total_grid receives the launch's block count.
+ */
+sbi_status sbi_layer_plan(const sbi_layer* L, int64_t B, int32_t chained, sbi_plan plans[4], int32_t* total_grid);
+
+/*
  * Measurement helpers (no part of the GeMM path; for callers that profile it).
  * sbi_calib_read streams `bytes` (a multiple of 4096, 256-byte aligned, device) from src
  * with the GeMM's own access shape - `blocks` thread blocks of `waves` wavefronts (4, 8 or

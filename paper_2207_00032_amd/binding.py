@@ -28,7 +28,7 @@ STATUS_NAMES = ["SBI_OK", "SBI_ERR_NULL", "SBI_ERR_SHAPE", "SBI_ERR_ALIGN", "SBI
 EXPORTS = ["sbi_gemm_layout_bytes", "sbi_gemm_workspace_bytes", "sbi_gemm_layout_weights",
            "sbi_gemm_unlayout_weights", "sbi_gemm_layout_check", "sbi_gemm", "sbi_gemm_ex",
            "sbi_gemm_plan", "sbi_layer_gemms", "sbi_layer_workspace_bytes", "sbi_status_string",
-           "sbi_version", "sbi_calib_read", "sbi_calib_copy"]
+           "sbi_version", "sbi_calib_read", "sbi_calib_copy", "sbi_layer_plan"]
 
 
 class SbiError(RuntimeError):
@@ -95,6 +95,8 @@ def load():
     L.sbi_layer_gemms.argtypes = [ctypes.POINTER(Layer), i64] + [vp] * 9 + [vp, sz, vp]
     L.sbi_layer_workspace_bytes.restype = sz
     L.sbi_layer_workspace_bytes.argtypes = [ctypes.POINTER(Layer), i64]
+    L.sbi_layer_plan.restype = i32
+    L.sbi_layer_plan.argtypes = [ctypes.POINTER(Layer), i64, i32, ctypes.POINTER(Plan), ctypes.POINTER(i32)]
     L.sbi_calib_read.restype = i32
     L.sbi_calib_read.argtypes = [vp, sz, vp, sz, i32, i32, i32, i32, vp]
     L.sbi_calib_copy.restype = i32
@@ -217,6 +219,15 @@ def make_layer(Wqkv, Wout, Wffn1, Wffn2, h, n_qkv, k_out, n_ffn1, k_ffn2,
 
 def layer_workspace_bytes(layer, B):
     return int(load().sbi_layer_workspace_bytes(ctypes.byref(layer), B))
+
+
+def layer_plan(layer, B, chained=False):
+    """Per-GeMM plans of the grouped launch sbi_layer_gemms would make, and its total grid."""
+    plans = (Plan * 4)()
+    grid = ctypes.c_int32(0)
+    _check(load().sbi_layer_plan(ctypes.byref(layer), B, 1 if chained else 0, plans, ctypes.byref(grid)),
+           "sbi_layer_plan")
+    return [p.as_dict() for p in plans][: 3 if chained else 4], grid.value
 
 
 def layer_gemms(layer, B, Xqkv, Xout, Xffn1, Xffn2, residual, Yqkv, Yout, Yffn1, Yffn2, workspace):

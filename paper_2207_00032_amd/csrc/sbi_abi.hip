@@ -79,6 +79,22 @@ double split_cost(int64_t KS, int64_t P, int64_t B, int S, int nw)
 
 sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot);
 
+// X staging of a block that streams `ksps` k-steps with `wd` = waves*depth k-steps per round and
+// at most `cap` bytes of LDS: one buffer if the whole range fits, else two buffers of `kc`
+// k-steps each (64 B per batch row per k-step).  False if not even one round fits.
+bool chunking(int64_t B, int64_t ksps, int64_t wd, int64_t cap, int64_t red_bytes, int64_t& kc, int64_t& lds)
+{
+    const int64_t single = (cap / (B * 64)) / wd * wd;
+    if (round_up(ksps, wd) <= single) {
+        kc = round_up(ksps, wd);
+        lds = std::max(kc * B * 64, red_bytes);
+        return true;
+    }
+    kc = (cap / 2 / (B * 64)) / wd * wd;
+    lds = std::max(2 * kc * B * 64, red_bytes);
+    return kc >= wd;
+}
+
 sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Plan& pl)
 {
     if (sbi_status s = check_shape(K, N)) return s;
@@ -106,14 +122,11 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
         return SBI_OK;
     }
 
-    // the X chunk staged in LDS holds at least waves*depth k-steps of B rows (64 B per row per k-step)
-    const int64_t max_wd = kMaxLds / (B * 64);
     int nw = t.waves, depth = t.depth;
-    if (nw == 0) nw = (max_wd >= 32 && KS >= 32) ? 8 : 4;
-    if (depth == 0) depth = 4;
-    if ((nw != 4 && nw != 8) || (depth != 4 && depth != 8)) return SBI_ERR_TUNING;
-    if ((int64_t)nw * depth > max_wd) return SBI_ERR_TUNING;
-
+    if (nw == 0) nw = (B <= 32 && KS >= 32) ? 8 : 4;
+    if (depth == 0) depth = (B > 32) ? 2 : 4;
+    const bool depth_ok = depth == 4 || depth == 8 || (depth == 2 && nw == 4 && path == SBI_PATH_MFMA);
+    if ((nw != 4 && nw != 8) || !depth_ok) return SBI_ERR_TUNING;
     int S = t.split_k;
     if (S < 0) return SBI_ERR_TUNING;
     if (S == 0) {
@@ -132,15 +145,13 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     if (P * S > (int64_t)0x7fffffff) return SBI_ERR_SHAPE;
 
     const int64_t wd = (int64_t)nw * depth;
-    const int64_t kc_max = (kMaxLds / (B * 64)) / wd * wd;
-    const int64_t kc = std::min<int64_t>(kc_max, round_up(ksps, wd));
+    int64_t kc = 0, lds = 0;
+    if (!chunking(B, ksps, wd, kMaxLds, (int64_t)nw * 16 * kRedPitch * 4, kc, lds)) return SBI_ERR_TUNING;
 
     pl.path = path; pl.nw = nw; pl.depth = depth; pl.S = S;
     pl.ksps = (int)ksps; pl.kc = (int)kc;
     pl.grid = (int)(P * S); pl.block = nw * 64;
-    pl.lds = std::max<int64_t>(kc * B * 64, (int64_t)nw * 16 * kRedPitch * 4);
-    // fixed-size counter region: calls of different shapes that share a workspace must never
-    // see each other's partial sums where they expect counters
+    pl.lds = lds;
     pl.counter_bytes = (S > 1) ? kCounterBytes : 0;
     pl.ws_bytes = (S > 1) ? pl.counter_bytes + P * S * B * kPanelN * 4 : 0;
     pl.upw = 0; pl.nwaves = 0;
@@ -237,13 +248,17 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
     return p;
 }
 
-// Wavefronts per CU that the register file lets the MFMA block kernel keep resident (from the
-// compiled kernels' register counts: MB = ceil(B/16) row blocks of accumulators).
-int resident_waves(int mb, int nw)
+// Wavefronts per CU that the register file lets the MFMA block kernel keep resident: the
+// vector registers of the compiled kernel variants (row blocks MB = ceil(B/16), waves, depth),
+// 512 registers per SIMD lane, 4 SIMDs per CU.
+int resident_waves(int mb, int nw, int depth)
 {
-    if (mb <= 1) return nw == 8 ? 16 : 12;
-    if (mb == 2) return 12;
-    return 8;
+    static const int vgpr_w4d2[4] = {92, 116, 148, 172};
+    static const int vgpr_w4d4[4] = {128, 152, 192, 230};
+    static const int vgpr_w8d4[4] = {120, 138, 158, 180};
+    const int* tab = (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);
+    const int v = (tab[std::min(std::max(mb, 1), 4) - 1] + 7) / 8 * 8;
+    return 4 * std::min(8, 512 / v);
 }
 
 // Plans for `G` GeMMs that go out as one launch of the block kernel.  A common block size T
@@ -264,49 +279,57 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
         maxKS = std::max(maxKS, KS[g]); panels += P[g];
     }
     if (panels > kCounterBytes / 4) return SBI_ERR_SHAPE;
-    constexpr int depth = 4;
     constexpr int64_t kLdsPerCU = 160 * 1024;
     const int64_t lds_caps[3] = {16 * 1024, 32 * 1024, kMaxLds};
+    const int shapes[3][2] = {{4, 4}, {8, 4}, {4, 2}};             // (waves, depth) candidates
 
-    int best_nw = 0;
+    int best_nw = 0, best_depth = 0;
     int64_t bestT = 0, best_cap = 0;
     double best = 0.0;
-    for (int nw = 4; nw <= 8; nw += 4) {
+    for (const auto& shp : shapes) {
+        const int nw = shp[0], depth = shp[1];
         const int64_t wd = (int64_t)nw * depth;
         const int64_t red_bytes = (int64_t)nw * 16 * kRedPitch * 4;
         for (int64_t cap : lds_caps) {
-            const int64_t kc_cap = (cap / (B * 64)) / wd * wd;
-            if (kc_cap < wd) continue;
             for (int64_t T = wd; T < maxKS + wd; T += wd) {
                 int64_t blocks = 0, maxk = 0, lds = red_bytes, chunks = 1;
                 double partial = 0.0;
-                for (int g = 0; g < G; ++g) {
+                bool ok = true, slow_stage = false;   // slow: a chunk needs a second staging pass
+                for (int g = 0; g < G && ok; ++g) {
                     const int64_t S = ceil_div(KS[g], T);
                     const int64_t ksps = ceil_div(KS[g], S);
-                    const int64_t kc = std::min<int64_t>(kc_cap, round_up(ksps, wd));
+                    int64_t kc = 0, l = 0;
+                    ok = chunking(B, ksps, wd, cap, red_bytes, kc, l);
+                    if (!ok) break;
                     blocks += P[g] * S;
                     maxk = std::max(maxk, ksps);
-                    lds = std::max(lds, kc * B * 64);
+                    lds = std::max(lds, l);
                     chunks = std::max(chunks, ceil_div(ksps, kc));
+                    if (ceil_div(ksps, kc) > 1 && kc * B * 64 > (int64_t)nw * 64 * 64) slow_stage = true;
                     if (S > 1) partial += (double)(P[g] * S) * (double)B * 512.0;
                 }
+                if (!ok) continue;
                 const int64_t fit = std::max<int64_t>(1, std::min<int64_t>(kLdsPerCU / lds,
-                                                                           resident_waves(mb, nw) / nw));
+                                                                           resident_waves(mb, nw, depth) / nw));
                 const int64_t per_cu = std::min<int64_t>(fit, ceil_div(blocks, kNumCU));   // concurrent blocks on a CU
                 const int64_t rounds = ceil_div(blocks, (int64_t)kNumCU * fit);
                 const double busy = (double)std::min<int64_t>(blocks, kNumCU) / kNumCU;
                 // every block: ramp-up, reduction, epilogue (about 20 k-steps of streaming time);
-                // every further X chunk restarts the load pipeline (about 6)
-                const double block_time = (double)maxk + 20.0 + 6.0 * (double)(chunks - 1);
+                // every further X chunk costs a barrier (about 1)
+                const double block_time = (double)maxk + 20.0 + 1.0 * (double)(chunks - 1);
                 double cost = (double)rounds * (double)per_cu * block_time * (busy >= 0.75 ? 1.0 : 0.75 / busy) +
                               partial / kNumCU / 4096.0;
                 if ((int64_t)per_cu * nw < 8) cost *= 1.3;        // too few wavefronts to keep HBM busy
-                if (best_nw == 0 || cost < best) { best = cost; best_nw = nw; bestT = T; best_cap = cap; }
+                if (depth < 4) cost *= 1.1;                       // a shallow ring hides less latency
+                if (slow_stage) cost *= 1.1;
+                if (best_nw == 0 || cost < best) {
+                    best = cost; best_nw = nw; best_depth = depth; bestT = T; best_cap = cap;
+                }
             }
         }
     }
     if (best_nw == 0) return SBI_ERR_SHAPE;
-    const int nw = best_nw;
+    const int nw = best_nw, depth = best_depth;
     const int64_t wd = (int64_t)nw * depth;
     int64_t grid = 0, partial_bytes = 0, lds = 0;
     bool any_split = false;
@@ -314,12 +337,12 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
         Plan& pl = pls[g];
         const int64_t S = ceil_div(KS[g], bestT);
         const int64_t ksps = ceil_div(KS[g], S);
-        const int64_t kc_max = (best_cap / (B * 64)) / wd * wd;
-        const int64_t kc = std::min<int64_t>(kc_max, round_up(ksps, wd));
+        int64_t kc = 0, l = 0;
+        chunking(B, ksps, wd, best_cap, (int64_t)nw * 16 * kRedPitch * 4, kc, l);
         pl.path = SBI_PATH_MFMA; pl.nw = nw; pl.depth = depth;
         pl.S = (int)ceil_div(KS[g], ksps); pl.ksps = (int)ksps; pl.kc = (int)kc;
         pl.grid = (int)(P[g] * pl.S); pl.block = nw * 64;
-        pl.lds = std::max<int64_t>(kc * B * 64, (int64_t)nw * 16 * kRedPitch * 4);
+        pl.lds = l;
         pl.counter_bytes = kCounterBytes;
         pl.ws_bytes = (pl.S > 1) ? P[g] * pl.S * B * kPanelN * 4 : 0;     // partial sums only
         pl.upw = 0; pl.nwaves = 0;
@@ -488,6 +511,24 @@ size_t sbi_layer_workspace_bytes(const sbi_layer* L, int64_t B)
     if (layer_group_plan(L, B, 4, pls, tot) == SBI_OK) m = std::max(m, (size_t)tot.ws_bytes);
     if (layer_group_plan(L, B, 3, pls, tot) == SBI_OK) m = std::max(m, (size_t)tot.ws_bytes);
     return m;
+}
+
+sbi_status sbi_layer_plan(const sbi_layer* L, int64_t B, int32_t chained, sbi_plan plans[4], int32_t* total_grid)
+{
+    if (!plans || !total_grid) return SBI_ERR_NULL;
+    if (sbi_status s = layer_check(L, B)) return s;
+    const int count = chained ? 3 : 4;
+    Plan pls[4], tot;
+    if (sbi_status s = layer_group_plan(L, B, count, pls, tot)) return s;
+    std::memset(plans, 0, 4 * sizeof(sbi_plan));
+    for (int g = 0; g < count; ++g) {
+        plans[g].path = pls[g].path; plans[g].waves = tot.nw; plans[g].depth = tot.depth;
+        plans[g].split_k = pls[g].S; plans[g].ksteps_per_split = pls[g].ksps;
+        plans[g].ksteps_per_chunk = pls[g].kc; plans[g].grid = pls[g].grid; plans[g].block = tot.block;
+        plans[g].lds_bytes = tot.lds; plans[g].workspace_bytes = pls[g].ws_bytes;
+    }
+    *total_grid = tot.grid;
+    return SBI_OK;
 }
 
 sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,

@@ -111,14 +111,17 @@ struct XStage {
 // walks a contiguous run of the laid-out weights.  Each wave keeps DEPTH k-steps (4 x 128-bit
 // loads per lane each) in flight in a register ring with static indices: a round consumes
 // slot d and refills it in place, d = 0..DEPTH-1, as straight-line code so the load-counter
-// waits stay exact.  All waves of a block run the same number of rounds; a step that falls
-// beyond the end of the range re-reads the range's last k-step and has its weights replaced
-// by zeros before use, so the loop needs no conditional loads (the dispatcher picks splits
-// that leave no such padding for the shapes that matter).
-// X is staged in LDS per chunk of p.kc k-steps (p.kc is a multiple of NW*DEPTH); X's global
-// reads and the first weight loads of a chunk are all issued before the barrier that
-// publishes the chunk, so HBM latency overlaps the staging.  `op.step(w, xk)` receives the four tiles of one k-step and the LDS
-// address of that k-step's X block ([4 lane groups][B rows] of 16 bytes).
+// waits stay exact.  The ring runs without interruption over the whole range.  All waves of a
+// block run the same number of rounds; a step that falls beyond the end of the range re-reads
+// the range's last k-step and has its weights replaced by zeros before use, so the loop
+// needs no conditional loads (the dispatcher picks splits that leave no such padding for
+// the shapes that matter).
+// X is staged in LDS in chunks of p.kc k-steps (a multiple of NW*DEPTH, so a round never
+// straddles a chunk).  With more than one chunk the LDS holds two buffers: the global reads
+// of chunk c+1 are requested when chunk c starts, written to the other buffer when chunk c
+// ends, and one barrier separates the chunks - the weight ring is not drained.
+// `op.step(w, xk)` receives the four tiles of one k-step and the LDS address of that
+// k-step's X block ([4 lane groups][B rows] of 16 bytes).
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ void load_step(u32x4 (&slot)[kPanelTiles], const u32x4* src)
 {
@@ -131,48 +134,55 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op&
                                              int lane, int panel, int ks0, int ks1)
 {
     constexpr int NT = NW * 64;
+    constexpr int RS = NW * DEPTH;                                 // k-steps a block consumes per round
     constexpr int kStepUnits = kPanelTiles * 64;                  // 16-byte units per k-step of a panel
-    const int nks = ks1 - ks0;
-    const int nchunks = (nks + p.kc - 1) / p.kc;
-    const u32x4* wpanel = p.Wl + (int64_t)panel * p.KS * kStepUnits + lane;
+    const int nks = ks1 - ks0;                                     // >= 1
+    const int rounds = (nks + RS - 1) / RS;
+    const int rpc = p.kc / RS;                                     // rounds per X chunk
+    const int nchunks = (rounds + rpc - 1) / rpc;
+    const u32x4* wbase = p.Wl + ((int64_t)panel * p.KS + ks0) * kStepUnits + lane;
     const int xblock = 4 * p.B;                                    // 16-byte units of X per k-step
+    const int xbuf = p.kc * xblock;                                // 16-byte units per X buffer
 
     u32x4 ring[DEPTH][kPanelTiles];
-    for (int c = 0; c < nchunks; ++c) {
-        const int cb = ks0 + c * p.kc;
-        const int cn = min(ks1 - cb, p.kc);                        // k-steps in this chunk (>= 1)
-        const int rounds = (cn + NW * DEPTH - 1) / (NW * DEPTH);
-        const u32x4* wchunk = wpanel + (int64_t)cb * kStepUnits;
-
-        XStage<NT, 4> xst;
-        xst.request(p, cb, cn, tid);
+    XStage<NT, 4> xst;                                             // covers NT*64 bytes of X per chunk without a second pass
+    xst.request(p, ks0, min(nks, p.kc), tid);
 #pragma unroll
-        for (int d = 0; d < DEPTH; ++d)
-            load_step(ring[d], wchunk + (int64_t)min(d * NW + wave, cn - 1) * kStepUnits);
+    for (int d = 0; d < DEPTH; ++d)
+        load_step(ring[d], wbase + (int64_t)min(d * NW + wave, nks - 1) * kStepUnits);
+    xst.commit(p, xs, ks0, min(nks, p.kc), tid);
+    if (nchunks > 1) xst.request(p, ks0 + p.kc, min(nks - p.kc, p.kc), tid);
+    __syncthreads();
 
-        if (c > 0) __syncthreads();                                // previous chunk fully consumed
-        xst.commit(p, xs, cb, cn, tid);
-        __syncthreads();
-
-        int ksl = wave;                                            // k-step inside the chunk
-        for (int r = 0; r + 1 < rounds; ++r) {
-#pragma unroll
-            for (int d = 0; d < DEPTH; ++d) {
-                op.step(ring[d], xs + ksl * xblock);               // always inside the chunk here
-                load_step(ring[d], wchunk + (int64_t)min(ksl + NW * DEPTH, cn - 1) * kStepUnits);
-                ksl += NW;
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
+    int t = wave;                                                  // this wave's k-step inside the range
+    int c = 0, rc = 0;                                             // X chunk, round inside the chunk
+    const u32x4* xc = xs;                                          // xc + t*xblock: X block of step t
+    for (int r = 0; r + 1 < rounds; ++r) {
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
-            if (ksl >= cn) {                                       // padding step: contributes nothing
-#pragma unroll
-                for (int t = 0; t < kPanelTiles; ++t) ring[d][t] = u32x4{0u, 0u, 0u, 0u};
-            }
-            op.step(ring[d], xs + min(ksl, cn - 1) * xblock);
-            ksl += NW;
+            op.step(ring[d], xc + t * xblock);                     // always inside the range here
+            load_step(ring[d], wbase + (int64_t)min(t + RS, nks - 1) * kStepUnits);
+            t += NW;
+            __builtin_amdgcn_sched_barrier(0);
         }
+        if (++rc == rpc) {                                         // chunk c is consumed, c+1 exists
+            rc = 0;
+            ++c;
+            u32x4* dst = xs + (c & 1) * xbuf;
+            xst.commit(p, dst, ks0 + c * p.kc, min(nks - c * p.kc, p.kc), tid);
+            __syncthreads();
+            xc = dst - c * p.kc * xblock;
+            if (c + 1 < nchunks) xst.request(p, ks0 + (c + 1) * p.kc, min(nks - (c + 1) * p.kc, p.kc), tid);
+        }
+    }
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+        if (t >= nks) {                                            // padding step: contributes nothing
+#pragma unroll
+            for (int q = 0; q < kPanelTiles; ++q) ring[d][q] = u32x4{0u, 0u, 0u, 0u};
+        }
+        op.step(ring[d], xc + min(t, nks - 1) * xblock);
+        t += NW;
     }
 }
 

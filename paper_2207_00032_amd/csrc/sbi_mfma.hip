@@ -115,6 +115,7 @@ static int launch_mb(const GroupParams& gp, size_t lds, hipStream_t st)
 int launch_mfma(const GroupParams& gp, int waves, int depth, size_t lds_bytes, hipStream_t st)
 {
     if (gp.G < 1 || gp.G > kMaxGroup) return (int)hipErrorInvalidValue;
+    if (waves == 4 && depth == 2) return launch_mb<4, 2>(gp, lds_bytes, st);
     if (waves == 4 && depth == 4) return launch_mb<4, 4>(gp, lds_bytes, st);
     if (waves == 4 && depth == 8) return launch_mb<4, 8>(gp, lds_bytes, st);
     if (waves == 8 && depth == 4) return launch_mb<8, 4>(gp, lds_bytes, st);
