@@ -78,7 +78,7 @@ def main():
     Bmax = max(batches)
     specs = cfg.gemms
     layer_weight_bytes = sum(s.weight_bytes for s in specs)
-    copies = args.copies or max(2, -(-3 * 256 * 1000 * 1000 // layer_weight_bytes))
+    copies = args.copies or max(3, -(-3 * 256 * 1000 * 1000 // layer_weight_bytes))
 
     # ---- seeded synthetic inputs (host), uploaded and laid out once ------------------------
     host = []
@@ -106,17 +106,27 @@ def main():
     path = {"auto": sb.PATH_AUTO, "stream": sb.PATH_STREAM, "mfma": sb.PATH_MFMA,
             "streamk": sb.PATH_STREAMK}[args.path]
 
+    launch_no = [0]
+
+    def next_copy():
+        """Every launch streams a different weight copy than the one before it."""
+        c = launch_no[0] % copies
+        launch_no[0] += 1
+        return c
+
+    def launch_layer(B):
+        x, y = X_d[B], Y_d[B]
+        c = next_copy()
+        if path == sb.PATH_AUTO:
+            sb.layer_gemms(layers[c], B, x[0], x[1], x[2], x[3], R_d[B], y[0], y[1], y[2], y[3], ws)
+        else:
+            for gi, s in enumerate(specs):
+                sb.gemm(Wl[c][gi], s.K, s.N, x[gi], bias_d[gi], R_d[B] if gi == 3 else None, s.epilogue,
+                        out=y[gi], workspace=ws, path=path)
+
     def step(i):
-        L = layers[i % copies]
         for B in batches:
-            x, y = X_d[B], Y_d[B]
-            if path == sb.PATH_AUTO:
-                sb.layer_gemms(L, B, x[0], x[1], x[2], x[3], R_d[B], y[0], y[1], y[2], y[3], ws)
-            else:
-                Wc = Wl[i % copies]
-                for gi, s in enumerate(specs):
-                    sb.gemm(Wc[gi], s.K, s.N, x[gi], bias_d[gi], R_d[B] if gi == 3 else None, s.epilogue,
-                            out=y[gi], workspace=ws, path=path)
+            launch_layer(B)
 
     if args.pmc_probe:
         # known-traffic reference (reads 256 MiB, writes 256 MiB), then the layer launches
@@ -131,87 +141,70 @@ def main():
                           "layer_bytes": {str(B): sum(s.algorithmic_bytes(B) for s in specs) for B in batches}}))
         return
 
-    # ---- timed region ---------------------------------------------------------------------
+    # ---- timed region: K steps, one event per step boundary on the launch stream -------------
     for i in range(args.warmup):
         step(i)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    marks[0].record()
     for i in range(args.steps):
         step(args.warmup + i)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     sec_per_step = (t1 - t0) / args.steps
     bytes_per_step = sum(s.algorithmic_bytes(B) for B in batches for s in specs)
     flops_per_step = sum(s.flops(B) for B in batches for s in specs)
     value = bytes_per_step / sec_per_step / 1e9
+    # dominant kernel: with the automatic dispatch a step is len(batches) launches of it, back to back
+    step_us = [marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(args.steps)]
+    launches_per_step = len(batches) * (1 if path == sb.PATH_AUTO else len(specs))
+    avg_launch_us = sum(step_us) / len(step_us) / launches_per_step
 
-    # ---- per-kernel durations: events around every launch, on the launch stream ------------
-    # (a second pass over the same steps, so the events do not perturb `value`).  With the
-    # automatic dispatch one sbi_layer_gemms call is ONE kernel launch covering the four GeMMs.
-    ev_steps = min(args.steps, 30)
-    records = []      # (label, B, bytes, flops, start event, stop event)
-    def timed(label, B, nbytes, nflops, fn):
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
-        fn()
-        e1.record()
-        records.append((label, B, nbytes, nflops, e0, e1))
-
-    for i in range(ev_steps):
-        c = (args.warmup + i) % copies
-        for B in batches:
-            x, y = X_d[B], Y_d[B]
-            if path == sb.PATH_AUTO:
-                timed("layer", B, sum(s.algorithmic_bytes(B) for s in specs), sum(s.flops(B) for s in specs),
-                      lambda: sb.layer_gemms(layers[c], B, x[0], x[1], x[2], x[3], R_d[B],
-                                             y[0], y[1], y[2], y[3], ws))
-            else:
-                for gi, s in enumerate(specs):
-                    timed(s.name, B, s.algorithmic_bytes(B), s.flops(B),
-                          lambda gi=gi, s=s: sb.gemm(Wl[c][gi], s.K, s.N, x[gi], bias_d[gi],
-                                                     R_d[B] if gi == 3 else None, s.epilogue,
-                                                     out=y[gi], workspace=ws, path=path))
-    if args.per_gemm:
-        for i in range(ev_steps):
-            c = (args.warmup + i) % copies
-            for B in batches:
-                x, y = X_d[B], Y_d[B]
-                for gi, s in enumerate(specs):
-                    timed("single:" + s.name, B, s.algorithmic_bytes(B), s.flops(B),
-                          lambda gi=gi, s=s: sb.gemm(Wl[c][gi], s.K, s.N, x[gi], bias_d[gi],
-                                                     R_d[B] if gi == 3 else None, s.epilogue,
-                                                     out=y[gi], workspace=ws, path=path))
-    torch.cuda.synchronize()
-    per = {}
-    for label, B, nbytes, nflops, e0, e1 in records:
-        per.setdefault((label, B), {"bytes": nbytes, "flops": nflops, "us": []})["us"].append(
-            e0.elapsed_time(e1) * 1e3)
+    # ---- per-batch launch times: events around runs of 10 back-to-back launches of one B ------
     per_launch = []
-    tot_bytes = tot_us = 0.0
-    tot_n = 0
-    for (label, B), d in per.items():
-        us = sorted(d["us"])
-        med = us[len(us) // 2]
+    def timed_run(label, B, nbytes, nflops, fn, reps=10, runs=5):
+        us = []
+        for _ in range(runs):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            us.append(e0.elapsed_time(e1) * 1e3 / reps)
+        med = sorted(us)[len(us) // 2]
         per_launch.append({"launch": label, "B": B, "us_median": round(med, 2),
-                           "us_mean": round(sum(us) / len(us), 2),
-                           "GBps": round(d["bytes"] / (med * 1e-6) / 1e9, 1),
-                           "hbm_frac": round(d["bytes"] / (med * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
-                           "TFLOPs": round(d["flops"] / (med * 1e-6) / 1e12, 3)})
-        if not label.startswith("single:"):
-            tot_bytes += d["bytes"] * len(us)
-            tot_us += sum(us)
-            tot_n += len(us)
+                           "GBps": round(nbytes / (med * 1e-6) / 1e9, 1),
+                           "hbm_frac": round(nbytes / (med * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                           "TFLOPs": round(nflops / (med * 1e-6) / 1e12, 3)})
+
+    for B in batches:
+        timed_run("layer", B, sum(s.algorithmic_bytes(B) for s in specs), sum(s.flops(B) for s in specs),
+                  lambda: launch_layer(B))
+    if args.per_gemm:
+        for B in batches:
+            for gi, s in enumerate(specs):
+                timed_run("single:" + s.name, B, s.algorithmic_bytes(B), s.flops(B),
+                          lambda: sb.gemm(Wl[next_copy()][gi], s.K, s.N, X_d[B][gi], bias_d[gi],
+                                          R_d[B] if gi == 3 else None, s.epilogue, out=Y_d[B][gi],
+                                          workspace=ws, path=path))
     pl0 = sb.plan(Bmax, specs[0].K, specs[0].N, path)
+    if path == sb.PATH_AUTO:
+        lp, _ = sb.layer_plan(layers[0], Bmax)
+        pl0 = lp[0]
     kname = {sb.PATH_STREAMK: "sbi_streamk_kernel", sb.PATH_MFMA: "sbi_mfma_kernel",
              sb.PATH_STREAM: "sbi_stream_kernel"}[pl0["path"]]
-    achieved = tot_bytes / (tot_us * 1e-6) / 1e9
+    bytes_per_launch = bytes_per_step / launches_per_step
+    achieved = bytes_per_launch / (avg_launch_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(args, batches),
                 "kernel": f"{kname}<{(Bmax + 15) // 16 if pl0['path'] != sb.PATH_STREAM else Bmax},"
                           f"{pl0['waves']},{pl0['depth']}>",
-                "launches": tot_n, "avg_launch_us": round(tot_us / tot_n, 2),
-                "avg_bytes_per_launch": round(tot_bytes / tot_n)}
+                "launches": args.steps * launches_per_step, "avg_launch_us": round(avg_launch_us, 2),
+                "avg_bytes_per_launch": round(bytes_per_launch)}
 
     # ---- CPU oracle on the host cores, same GeMMs (a reported baseline, not a target) -------
     cpu = None
