@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-gemm", action="store_true", help="also time every GeMM as a launch of its own")
     ap.add_argument("--path", type=str, default="auto", choices=["auto", "stream", "mfma", "streamk"])
+    ap.add_argument("--graph", type=int, default=0, metavar="N",
+                    help="capture N consecutive steps into one HIP graph and time replays of it "
+                         "(removes host launch overhead; steps is rounded to a multiple of N)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run a few copy-kernel and layer launches and exit (for rocprofv3 --pmc runs)")
     return ap.parse_args()
@@ -124,9 +127,11 @@ def main():
                 sb.gemm(Wl[c][gi], s.K, s.N, x[gi], bias_d[gi], R_d[B] if gi == 3 else None, s.epilogue,
                         out=y[gi], workspace=ws, path=path)
 
-    def step(i):
+    def eager_step(i):
         for B in batches:
             launch_layer(B)
+
+    step = eager_step
 
     if args.pmc_probe:
         # known-traffic reference (reads 256 MiB, writes 256 MiB), then the layer launches
@@ -144,12 +149,30 @@ def main():
     # ---- timed region: K steps, one event per step boundary on the launch stream -------------
     for i in range(args.warmup):
         step(i)
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    per_mark = 1                               # steps between two event marks
+    if args.graph:
+        per_mark = args.graph
+        args.steps = max(per_mark, args.steps // per_mark * per_mark)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for j in range(per_mark):
+                    eager_step(j)
+        torch.cuda.synchronize()
+        for _ in range(2):
+            graph.replay()
+    nmarks = args.steps // per_mark
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(nmarks + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     marks[0].record()
-    for i in range(args.steps):
-        step(args.warmup + i)
+    for i in range(nmarks):
+        if args.graph:
+            graph.replay()
+        else:
+            step(args.warmup + i)
         marks[i + 1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -158,7 +181,7 @@ def main():
     flops_per_step = sum(s.flops(B) for B in batches for s in specs)
     value = bytes_per_step / sec_per_step / 1e9
     # dominant kernel: with the automatic dispatch a step is len(batches) launches of it, back to back
-    step_us = [marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(args.steps)]
+    step_us = [marks[i].elapsed_time(marks[i + 1]) * 1e3 / per_mark for i in range(nmarks)]
     launches_per_step = len(batches) * (1 if path == sb.PATH_AUTO else len(specs))
     avg_launch_us = sum(step_us) / len(step_us) / launches_per_step
 
@@ -247,7 +270,8 @@ def main():
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"config{args.config}:{cfg.name} four-GeMM layer, B in {list(batches)}, "
                                f"rotating over {copies} weight copies ({copies * layer_weight_bytes >> 20} MiB)",
-                   "batches": list(batches), "weight_copies": copies, "dispatch": args.path},
+                   "batches": list(batches), "weight_copies": copies, "dispatch": args.path,
+                   "graph_replay_steps": args.graph},
         "hbm_frac": round(value / HBM_PEAK_GBPS, 4),
         "us_per_gemm_mean": round(sec_per_step * 1e6 / (len(batches) * len(specs)), 2),
         "TFLOPs": round(flops_per_step / sec_per_step / 1e12, 3),

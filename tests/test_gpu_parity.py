@@ -259,3 +259,48 @@ def test_layer_gemms_matches_oracle(gpu, cfg_id, B, chained):
         xin = Yh[2] if chained else data[3][2]
         check(Yh[3], data[3][0], data[3][1], xin, data[3][3], "bias_residual", "layer ffn2")
     assert not ws[:256 * 1024].cpu().numpy().any()
+
+
+def test_layer_gemms_under_graph_replay(gpu):
+    """The library enqueues only kernels (no memset, no allocation, no synchronisation), so a
+    layer can be captured into a HIP graph; every replay must reproduce the eager bits, also
+    with eager launches on the same workspace in between."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    cfg = wl.CONFIGS[1]
+    B = 2
+    data = [wl.make_gemm_inputs(s.K, s.N, B, seed=1, config_id=1, gemm_id=i) for i, s in enumerate(cfg.gemms)]
+    Wls = [sb.layout_weights(_dev(d[0], gpu)) for d in data]
+    biases = [_dev(d[1], gpu) for d in data]
+    h = cfg.gemms[0].K
+    L = sb.make_layer(*Wls, h, cfg.gemms[0].N, cfg.gemms[1].K, cfg.gemms[2].N, cfg.gemms[3].K,
+                      bqkv=biases[0], bout=biases[1], bffn1=biases[2], bffn2=biases[3], ffn1_gelu=True)
+    ws = sb.new_workspace(sb.layer_workspace_bytes(L, B), gpu)
+    Xs = [_dev(d[2], gpu) for d in data]
+    Rd = _dev(data[3][3], gpu)
+    Ys = [torch.empty((B, s.N), dtype=torch.float16, device=gpu) for s in cfg.gemms]
+
+    def run():
+        sb.layer_gemms(L, B, Xs[0], Xs[1], Xs[2], None, Rd, Ys[0], Ys[1], Ys[2], Ys[3], ws)
+
+    run()
+    torch.cuda.synchronize()
+    eager = [y.clone() for y in Ys]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for y in Ys:
+            y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for y, e in zip(Ys, eager):
+            assert torch.equal(y.view(torch.int16), e.view(torch.int16)), f"replay {rep} differs"
+        run()                                   # eager work between replays
+        torch.cuda.synchronize()
+    assert not ws[:256 * 1024].cpu().numpy().any()
+    check(eager[3].cpu().numpy(), data[3][0], data[3][1], eager[2].cpu().numpy(), data[3][3],
+          "bias_residual", "graph layer ffn2")
