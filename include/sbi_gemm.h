@@ -74,6 +74,8 @@ typedef struct sbi_tuning {
     int32_t waves;   /* wavefronts per block: 4 or 8 */
     int32_t depth;   /* k-steps of W each wavefront keeps in flight: 4 or 8 */
     int32_t blocks;  /* STREAMK path: upper bound on the number of thread blocks */
+    int32_t panels;  /* MFMA path: 64-column panels per block, 1 or 2 (2: X is staged and read once
+                        for 128 columns; for larger batches) */
 } sbi_tuning;
 
 /* What the dispatcher decided for a problem (for reports and tests). */
@@ -86,6 +88,8 @@ typedef struct sbi_plan {
     int32_t ksteps_per_chunk; /* k-steps of X staged in LDS at a time; 0 on the STREAMK path */
     int32_t grid;        /* thread blocks launched */
     int32_t block;       /* threads per block */
+    int32_t panels;      /* 64-column panels per block (MFMA path), else 1 */
+    int32_t reserved;
     int64_t lds_bytes;   /* dynamic LDS per block */
     int64_t workspace_bytes; /* workspace this plan needs (0 when split_k == 1) */
 } sbi_plan;

@@ -40,13 +40,15 @@ class SbiError(RuntimeError):
 
 class Tuning(ctypes.Structure):
     _fields_ = [("path", ctypes.c_int32), ("split_k", ctypes.c_int32),
-                ("waves", ctypes.c_int32), ("depth", ctypes.c_int32), ("blocks", ctypes.c_int32)]
+                ("waves", ctypes.c_int32), ("depth", ctypes.c_int32), ("blocks", ctypes.c_int32),
+                ("panels", ctypes.c_int32)]
 
 
 class Plan(ctypes.Structure):
     _fields_ = [("path", ctypes.c_int32), ("waves", ctypes.c_int32), ("depth", ctypes.c_int32),
                 ("split_k", ctypes.c_int32), ("ksteps_per_split", ctypes.c_int32),
                 ("ksteps_per_chunk", ctypes.c_int32), ("grid", ctypes.c_int32), ("block", ctypes.c_int32),
+                ("panels", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("lds_bytes", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64)]
 
     def as_dict(self):
@@ -127,10 +129,10 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def _tuning(path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0):
-    if path == PATH_AUTO and not (split_k or waves or depth or blocks):
+def _tuning(path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0, panels=0):
+    if path == PATH_AUTO and not (split_k or waves or depth or blocks or panels):
         return None
-    return ctypes.pointer(Tuning(int(path), int(split_k), int(waves), int(depth), int(blocks)))
+    return ctypes.pointer(Tuning(int(path), int(split_k), int(waves), int(depth), int(blocks), int(panels)))
 
 
 # ---------------------------------------------------------------------------------- sizes
@@ -142,9 +144,9 @@ def workspace_bytes(B, K, N):
     return int(load().sbi_gemm_workspace_bytes(B, K, N))
 
 
-def plan(B, K, N, path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0):
+def plan(B, K, N, path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0, panels=0):
     pl = Plan()
-    _check(load().sbi_gemm_plan(B, K, N, _tuning(path, split_k, waves, depth, blocks), ctypes.byref(pl)),
+    _check(load().sbi_gemm_plan(B, K, N, _tuning(path, split_k, waves, depth, blocks, panels), ctypes.byref(pl)),
            "sbi_gemm_plan")
     return pl.as_dict()
 
@@ -180,7 +182,7 @@ def layout_check(Wl, K, N):
 
 
 def gemm(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, workspace=None,
-         path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0):
+         path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0, panels=0):
     """Y = epilogue(X @ W + bias) through sbi_gemm / sbi_gemm_ex.  Returns Y (fp16 [B,N])."""
     import torch
     assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.is_contiguous()
@@ -189,9 +191,9 @@ def gemm(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, wor
         epilogue = EPILOGUES[epilogue]
     if out is None:
         out = torch.empty((B, N), dtype=torch.float16, device=X.device)
-    tune = _tuning(path, split_k, waves, depth, blocks)
+    tune = _tuning(path, split_k, waves, depth, blocks, panels)
     if workspace is None:
-        need = plan(B, K, N, path, split_k, waves, depth, blocks)["workspace_bytes"] if tune \
+        need = plan(B, K, N, path, split_k, waves, depth, blocks, panels)["workspace_bytes"] if tune \
             else workspace_bytes(B, K, N)
         workspace = new_workspace(need, X.device) if need else None
     ws_ptr = _ptr(workspace)

@@ -12,7 +12,8 @@ namespace {
 using namespace sbi;
 
 constexpr int64_t kMaxDim = int64_t(1) << 22;     // K, N limit: keeps tile counts and grids in 32 bits
-constexpr int64_t kMaxLds = 64 * 1024;            // dynamic LDS budget per block
+constexpr int64_t kMaxLds = 64 * 1024;            // dynamic LDS budget per block (several blocks per CU)
+constexpr int64_t kMaxLdsWide = 128 * 1024;       // two-panel blocks of large batches: one block per CU
 constexpr int64_t kCounterBytes = (kMaxDim / kPanelN) * 4;   // one arrival counter per possible panel: 256 KiB
 constexpr int kStreamMaxBatch = 8;                // vector-ALU kernel instantiations exist for B <= 8
 constexpr int kAutoStreamBatch = 0;               // AUTO picks the vector-ALU kernel for B <= this
@@ -24,6 +25,7 @@ struct Plan {
     int path, nw, depth, S, ksps, kc, grid, block;
     int64_t lds, ws_bytes, counter_bytes;
     int upw, nwaves;          // STREAMK path: units per wavefront, wavefronts
+    int pw;                   // MFMA path: panels per block
 };
 
 constexpr int kSkDefaultWaves = 2048;             // wavefronts of a STREAMK launch: 8 per CU
@@ -41,7 +43,7 @@ sbi_status plan_streamk(int64_t B, int64_t units, int64_t panels, const sbi_tuni
     const int64_t upw = round_up(ceil_div(units, want), kStepGroup);
     const int64_t nwaves = ceil_div(units, upw);
     pl.path = SBI_PATH_STREAMK; pl.nw = nw; pl.depth = depth; pl.S = 0;
-    pl.ksps = (int)upw; pl.kc = 0;
+    pl.ksps = (int)upw; pl.kc = 0; pl.pw = 1;
     pl.grid = (int)ceil_div(nwaves, nw); pl.block = nw * 64; pl.lds = 0;
     pl.upw = (int)upw; pl.nwaves = (int)nwaves;
     pl.counter_bytes = kCounterBytes;
@@ -102,10 +104,10 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     const int64_t KS = ksteps_of(K);
     const int64_t P = ceil_div(N, kPanelN);
 
-    sbi_tuning t = {0, 0, 0, 0, 0};
+    sbi_tuning t = {0, 0, 0, 0, 0, 0};
     if (tune) t = *tune;
 
-    if (t.split_k < 0 || t.blocks < 0) return SBI_ERR_TUNING;
+    if (t.split_k < 0 || t.blocks < 0 || t.panels < 0 || t.panels > 2) return SBI_ERR_TUNING;
     int path = t.path;
     const bool sk_ok = (K % kChunkK == 0);            // X rows readable as 128-bit pieces
     if (path == SBI_PATH_AUTO) path = (B <= kAutoStreamBatch) ? SBI_PATH_STREAM : SBI_PATH_MFMA;
@@ -115,17 +117,20 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     }
     if (path != SBI_PATH_STREAM && path != SBI_PATH_MFMA) return SBI_ERR_TUNING;
     if (path == SBI_PATH_STREAM && B > kStreamMaxBatch) return SBI_ERR_TUNING;
-    if (path == SBI_PATH_MFMA && t.split_k == 0 && t.waves == 0 && t.depth == 0) {
+    if (path == SBI_PATH_MFMA && t.split_k == 0 && t.waves == 0 && t.depth == 0 && t.panels == 0) {
         Plan one;
         if (sbi_status s = plan_group(B, &K, &N, 1, &one, pl)) return s;
-        pl.S = one.S; pl.ksps = one.ksps; pl.kc = one.kc;
+        pl.S = one.S; pl.ksps = one.ksps; pl.kc = one.kc; pl.pw = one.pw;
         return SBI_OK;
     }
 
     int nw = t.waves, depth = t.depth;
+    const int pw = (t.panels == 2 && path == SBI_PATH_MFMA) ? 2 : 1;
+    if (t.panels == 2 && path != SBI_PATH_MFMA) return SBI_ERR_TUNING;
     if (nw == 0) nw = (B <= 32 && KS >= 32) ? 8 : 4;
-    if (depth == 0) depth = (B > 32) ? 2 : 4;
-    const bool depth_ok = depth == 4 || depth == 8 || (depth == 2 && nw == 4 && path == SBI_PATH_MFMA);
+    if (depth == 0) depth = (B > 32 || pw == 2) ? 2 : 4;
+    bool depth_ok = depth == 4 || depth == 8 || (depth == 2 && nw == 4 && path == SBI_PATH_MFMA);
+    if (pw == 2) depth_ok = (nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 2);
     if ((nw != 4 && nw != 8) || !depth_ok) return SBI_ERR_TUNING;
     int S = t.split_k;
     if (S < 0) return SBI_ERR_TUNING;
@@ -142,15 +147,17 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     if (S > KS) S = (int)KS;
     const int64_t ksps = ceil_div(KS, S);
     S = (int)ceil_div(KS, ksps);                             // no empty blocks
-    if (P * S > (int64_t)0x7fffffff) return SBI_ERR_SHAPE;
+    const int64_t PG = ceil_div(P, pw);                          // panel groups = blocks per split
+    if (PG * S > (int64_t)0x7fffffff) return SBI_ERR_SHAPE;
 
     const int64_t wd = (int64_t)nw * depth;
     int64_t kc = 0, lds = 0;
-    if (!chunking(B, ksps, wd, kMaxLds, (int64_t)nw * 16 * kRedPitch * 4, kc, lds)) return SBI_ERR_TUNING;
+    if (!chunking(B, ksps, wd, pw == 2 ? kMaxLdsWide : kMaxLds, (int64_t)nw * 16 * kRedPitch * 4, kc, lds))
+        return SBI_ERR_TUNING;
 
-    pl.path = path; pl.nw = nw; pl.depth = depth; pl.S = S;
+    pl.path = path; pl.nw = nw; pl.depth = depth; pl.S = S; pl.pw = pw;
     pl.ksps = (int)ksps; pl.kc = (int)kc;
-    pl.grid = (int)(P * S); pl.block = nw * 64;
+    pl.grid = (int)(PG * S); pl.block = nw * 64;
     pl.lds = lds;
     pl.counter_bytes = (S > 1) ? kCounterBytes : 0;
     pl.ws_bytes = (S > 1) ? pl.counter_bytes + P * S * B * kPanelN * 4 : 0;
@@ -251,12 +258,13 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
 // Wavefronts per CU that the register file lets the MFMA block kernel keep resident: the
 // vector registers of the compiled kernel variants (row blocks MB = ceil(B/16), waves, depth),
 // 512 registers per SIMD lane, 4 SIMDs per CU.
-int resident_waves(int mb, int nw, int depth)
+int resident_waves(int mb, int nw, int depth, int pw)
 {
-    static const int vgpr_w4d2[4] = {92, 116, 148, 172};
-    static const int vgpr_w4d4[4] = {128, 152, 192, 230};
+    static const int vgpr_w4d2[4] = {92, 116, 152, 184};
+    static const int vgpr_w4d4[4] = {124, 152, 192, 230};
     static const int vgpr_w8d4[4] = {120, 138, 158, 180};
-    const int* tab = (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);
+    static const int vgpr_w8d2p2[4] = {136, 170, 206, 244};
+    const int* tab = (pw == 2) ? vgpr_w8d2p2 : (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);
     const int v = (tab[std::min(std::max(mb, 1), 4) - 1] + 7) / 8 * 8;
     return 4 * std::min(8, 512 / v);
 }
@@ -280,17 +288,20 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
     }
     if (panels > kCounterBytes / 4) return SBI_ERR_SHAPE;
     constexpr int64_t kLdsPerCU = 160 * 1024;
-    const int64_t lds_caps[3] = {16 * 1024, 32 * 1024, kMaxLds};
-    const int shapes[3][2] = {{4, 4}, {8, 4}, {4, 2}};             // (waves, depth) candidates
+    const int64_t lds_caps[4] = {16 * 1024, 32 * 1024, kMaxLds, kMaxLdsWide};
+    // (waves, depth, panels per block) candidates; two-panel blocks only pay off for B > 16
+    const int shapes[4][3] = {{4, 4, 1}, {8, 4, 1}, {4, 2, 1}, {8, 2, 2}};
 
-    int best_nw = 0, best_depth = 0;
+    int best_nw = 0, best_depth = 0, best_pw = 1;
     int64_t bestT = 0, best_cap = 0;
     double best = 0.0;
     for (const auto& shp : shapes) {
-        const int nw = shp[0], depth = shp[1];
+        const int nw = shp[0], depth = shp[1], pw = shp[2];
+        if (pw == 2 && mb < 2) continue;
         const int64_t wd = (int64_t)nw * depth;
         const int64_t red_bytes = (int64_t)nw * 16 * kRedPitch * 4;
         for (int64_t cap : lds_caps) {
+            if ((cap > kMaxLds) != (pw == 2)) continue;            // the wide budget belongs to two-panel blocks
             for (int64_t T = wd; T < maxKS + wd; T += wd) {
                 int64_t blocks = 0, maxk = 0, lds = red_bytes, chunks = 1;
                 double partial = 0.0;
@@ -301,8 +312,8 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
                     int64_t kc = 0, l = 0;
                     ok = chunking(B, ksps, wd, cap, red_bytes, kc, l);
                     if (!ok) break;
-                    blocks += P[g] * S;
-                    maxk = std::max(maxk, ksps);
+                    blocks += ceil_div(P[g], pw) * S;
+                    maxk = std::max(maxk, ksps * pw);
                     lds = std::max(lds, l);
                     chunks = std::max(chunks, ceil_div(ksps, kc));
                     if (ceil_div(ksps, kc) > 1 && kc * B * 64 > (int64_t)nw * 64 * 64) slow_stage = true;
@@ -310,26 +321,29 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
                 }
                 if (!ok) continue;
                 const int64_t fit = std::max<int64_t>(1, std::min<int64_t>(kLdsPerCU / lds,
-                                                                           resident_waves(mb, nw, depth) / nw));
+                                                                           resident_waves(mb, nw, depth, pw) / nw));
                 const int64_t per_cu = std::min<int64_t>(fit, ceil_div(blocks, kNumCU));   // concurrent blocks on a CU
                 const int64_t rounds = ceil_div(blocks, (int64_t)kNumCU * fit);
                 const double busy = (double)std::min<int64_t>(blocks, kNumCU) / kNumCU;
                 // every block: ramp-up, reduction, epilogue (about 20 k-steps of streaming time);
                 // every further X chunk costs a barrier (about 1)
-                const double block_time = (double)maxk + 20.0 + 1.0 * (double)(chunks - 1);
+                // X staged per block rivals the weight stream once B/(64 pw) exceeds about 0.2
+                const double x_ratio = (double)B / (64.0 * pw);
+                const double block_time = (double)maxk * (1.0 + 0.6 * std::max(0.0, x_ratio - 0.2)) + 20.0 +
+                                          1.0 * (double)(chunks - 1);
                 double cost = (double)rounds * (double)per_cu * block_time * (busy >= 0.75 ? 1.0 : 0.75 / busy) +
                               partial / kNumCU / 4096.0;
                 if ((int64_t)per_cu * nw < 8) cost *= 1.3;        // too few wavefronts to keep HBM busy
                 if (depth < 4) cost *= 1.1;                       // a shallow ring hides less latency
                 if (slow_stage) cost *= 1.1;
                 if (best_nw == 0 || cost < best) {
-                    best = cost; best_nw = nw; best_depth = depth; bestT = T; best_cap = cap;
+                    best = cost; best_nw = nw; best_depth = depth; best_pw = pw; bestT = T; best_cap = cap;
                 }
             }
         }
     }
     if (best_nw == 0) return SBI_ERR_SHAPE;
-    const int nw = best_nw, depth = best_depth;
+    const int nw = best_nw, depth = best_depth, pw = best_pw;
     const int64_t wd = (int64_t)nw * depth;
     int64_t grid = 0, partial_bytes = 0, lds = 0;
     bool any_split = false;
@@ -339,9 +353,9 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
         const int64_t ksps = ceil_div(KS[g], S);
         int64_t kc = 0, l = 0;
         chunking(B, ksps, wd, best_cap, (int64_t)nw * 16 * kRedPitch * 4, kc, l);
-        pl.path = SBI_PATH_MFMA; pl.nw = nw; pl.depth = depth;
+        pl.path = SBI_PATH_MFMA; pl.nw = nw; pl.depth = depth; pl.pw = pw;
         pl.S = (int)ceil_div(KS[g], ksps); pl.ksps = (int)ksps; pl.kc = (int)kc;
-        pl.grid = (int)(P[g] * pl.S); pl.block = nw * 64;
+        pl.grid = (int)(ceil_div(P[g], pw) * pl.S); pl.block = nw * 64;
         pl.lds = l;
         pl.counter_bytes = kCounterBytes;
         pl.ws_bytes = (pl.S > 1) ? P[g] * pl.S * B * kPanelN * 4 : 0;     // partial sums only
@@ -378,7 +392,7 @@ sbi_status launch_block_group(const GemmArgs* a, const Plan* pls, const Plan& to
         partial_off += pls[g].ws_bytes;
     }
     gp.first_block[G] = first;
-    return launch_mfma(gp, tot.nw, tot.depth, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
+    return launch_mfma(gp, tot.nw, tot.depth, tot.pw, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
 }
 
 }  // namespace
@@ -405,7 +419,7 @@ sbi_status sbi_gemm_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tuni
     if (sbi_status s = make_plan(B, K, N, tuning, pl)) return s;
     plan->path = pl.path; plan->waves = pl.nw; plan->depth = pl.depth; plan->split_k = pl.S;
     plan->ksteps_per_split = pl.ksps; plan->ksteps_per_chunk = pl.kc;
-    plan->grid = pl.grid; plan->block = pl.block;
+    plan->grid = pl.grid; plan->block = pl.block; plan->panels = pl.pw; plan->reserved = 0;
     plan->lds_bytes = pl.lds; plan->workspace_bytes = pl.ws_bytes;
     return SBI_OK;
 }
@@ -525,6 +539,7 @@ sbi_status sbi_layer_plan(const sbi_layer* L, int64_t B, int32_t chained, sbi_pl
         plans[g].path = pls[g].path; plans[g].waves = tot.nw; plans[g].depth = tot.depth;
         plans[g].split_k = pls[g].S; plans[g].ksteps_per_split = pls[g].ksps;
         plans[g].ksteps_per_chunk = pls[g].kc; plans[g].grid = pls[g].grid; plans[g].block = tot.block;
+        plans[g].panels = tot.pw;
         plans[g].lds_bytes = tot.lds; plans[g].workspace_bytes = pls[g].ws_bytes;
     }
     *total_grid = tot.grid;

@@ -123,15 +123,24 @@ struct XStage {
 // `op.step(w, xk)` receives the four tiles of one k-step and the LDS address of that
 // k-step's X block ([4 lane groups][B rows] of 16 bytes).
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ void load_step(u32x4 (&slot)[kPanelTiles], const u32x4* src)
+// One k-step of PW adjacent panels: tiles 0..3 from the first panel, 4..7 from the next one
+// (`pstride` 16-byte units further on: the same k-step of the following panel).
+template <int PW>
+__device__ __forceinline__ void load_step(u32x4 (&slot)[kPanelTiles * PW], const u32x4* src, int64_t pstride)
 {
 #pragma unroll
-    for (int t = 0; t < kPanelTiles; ++t) slot[t] = __builtin_nontemporal_load(src + t * 64);
+    for (int q = 0; q < PW; ++q)
+#pragma unroll
+        for (int t = 0; t < kPanelTiles; ++t)
+            slot[q * kPanelTiles + t] = __builtin_nontemporal_load(src + q * pstride + t * 64);
 }
 
-template <int NW, int DEPTH, class Op>
+// PW = panels per block (1 or 2): with two panels every wave streams both for the same
+// k-steps, so one X operand read from LDS feeds twice as many MFMAs and the X tile is staged
+// once for 128 columns - what larger batches need, where X traffic rivals the weight stream.
+template <int NW, int DEPTH, int PW, class Op>
 __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op& op, int tid, int wave,
-                                             int lane, int panel, int ks0, int ks1)
+                                             int lane, int panel, int64_t pstride, int ks0, int ks1)
 {
     constexpr int NT = NW * 64;
     constexpr int RS = NW * DEPTH;                                 // k-steps a block consumes per round
@@ -144,12 +153,12 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op&
     const int xblock = 4 * p.B;                                    // 16-byte units of X per k-step
     const int xbuf = p.kc * xblock;                                // 16-byte units per X buffer
 
-    u32x4 ring[DEPTH][kPanelTiles];
+    u32x4 ring[DEPTH][kPanelTiles * PW];
     XStage<NT, 4> xst;                                             // covers NT*64 bytes of X per chunk without a second pass
     xst.request(p, ks0, min(nks, p.kc), tid);
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
-        load_step(ring[d], wbase + (int64_t)min(d * NW + wave, nks - 1) * kStepUnits);
+        load_step<PW>(ring[d], wbase + (int64_t)min(d * NW + wave, nks - 1) * kStepUnits, pstride);
     xst.commit(p, xs, ks0, min(nks, p.kc), tid);
     if (nchunks > 1) xst.request(p, ks0 + p.kc, min(nks - p.kc, p.kc), tid);
     __syncthreads();
@@ -161,7 +170,7 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op&
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             op.step(ring[d], xc + t * xblock);                     // always inside the range here
-            load_step(ring[d], wbase + (int64_t)min(t + RS, nks - 1) * kStepUnits);
+            load_step<PW>(ring[d], wbase + (int64_t)min(t + RS, nks - 1) * kStepUnits, pstride);
             t += NW;
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -179,7 +188,7 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op&
     for (int d = 0; d < DEPTH; ++d) {
         if (t >= nks) {                                            // padding step: contributes nothing
 #pragma unroll
-            for (int q = 0; q < kPanelTiles; ++q) ring[d][q] = u32x4{0u, 0u, 0u, 0u};
+            for (int q = 0; q < kPanelTiles * PW; ++q) ring[d][q] = u32x4{0u, 0u, 0u, 0u};
         }
         op.step(ring[d], xc + min(t, nks - 1) * xblock);
         t += NW;

@@ -97,7 +97,7 @@ struct SkParams {
 
 // launchers implemented in the kernel translation units; return hipError_t as int
 int launch_streamk(const SkParams& p, int waves, int depth, int grid, hipStream_t st);
-int launch_mfma(const GroupParams& gp, int waves, int depth, size_t lds_bytes, hipStream_t st);
+int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, size_t lds_bytes, hipStream_t st);
 int launch_stream(const GemmParams& p, int waves, int depth, size_t lds_bytes, hipStream_t st);
 int launch_layout(const void* W, int64_t K, int64_t N, void* out, hipStream_t st);
 int launch_unlayout(const void* Wl, int64_t K, int64_t N, void* out, hipStream_t st);

@@ -15,16 +15,16 @@
 
 namespace sbi {
 
-// Per-wave contraction state: a 64-column x (MB*16)-row fp32 tile in MFMA result layout.
-template <int MB>
+// Per-wave contraction state: PW 64-column x (MB*16)-row fp32 tiles in MFMA result layout.
+template <int MB, int PW>
 struct MfmaOp {
-    floatx4 acc[kPanelTiles][MB];
+    floatx4 acc[kPanelTiles * PW][MB];
     int xoff[MB];     // this lane's 16-byte slot inside a k-step's X block
 
     __device__ __forceinline__ void init(int B, int g, int i)
     {
 #pragma unroll
-        for (int t = 0; t < kPanelTiles; ++t)
+        for (int t = 0; t < kPanelTiles * PW; ++t)
 #pragma unroll
             for (int m = 0; m < MB; ++m) acc[t][m] = floatx4{0.f, 0.f, 0.f, 0.f};
         // rows beyond B re-read row B-1: they only feed result columns that are never stored
@@ -32,13 +32,13 @@ struct MfmaOp {
         for (int m = 0; m < MB; ++m) xoff[m] = g * B + min(m * 16 + i, B - 1);
     }
 
-    __device__ __forceinline__ void step(const u32x4 (&w)[kPanelTiles], const u32x4* xk)
+    __device__ __forceinline__ void step(const u32x4 (&w)[kPanelTiles * PW], const u32x4* xk)
     {
         half8 xf[MB];
 #pragma unroll
         for (int m = 0; m < MB; ++m) xf[m] = __builtin_bit_cast(half8, xk[xoff[m]]);
 #pragma unroll
-        for (int t = 0; t < kPanelTiles; ++t) {
+        for (int t = 0; t < kPanelTiles * PW; ++t) {
             const half8 wf = __builtin_bit_cast(half8, w[t]);
 #pragma unroll
             for (int m = 0; m < MB; ++m)
@@ -50,7 +50,7 @@ struct MfmaOp {
 // One launch may carry several independent GeMMs of the same batch size (the linear layers of
 // one transformer layer): their blocks are simply concatenated, so the ramp-up and the tail of
 // a launch are paid once per layer instead of once per GeMM.
-template <int MB, int NW, int DEPTH>
+template <int MB, int NW, int DEPTH, int PW>
 __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
 {
     constexpr int NT = NW * 64;
@@ -69,57 +69,78 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
     const int g = lane >> 4;          // k group within a k-step (8 k each)
     const int i = lane & 15;          // column within a tile (A operand) / batch row (B operand)
 
-    const int panel = bid / p.S;
-    const int split = bid - panel * p.S;
+    const int pgroup = bid / p.S;     // group of PW adjacent panels
+    const int split = bid - pgroup * p.S;
+    const int panel = pgroup * PW;
+    const int npanels = min(PW, p.P - panel);       // the last group of an odd P has one panel
     const int ks0 = split * p.ksps;
     const int ks1 = min(p.KS, ks0 + p.ksps);
+    // a missing second panel streams the first one again; its result is dropped
+    const int64_t pstride = (npanels > 1) ? (int64_t)p.KS * (kPanelTiles * 64) : 0;
 
-    MfmaOp<MB> op;
+    MfmaOp<MB, PW> op;
     op.init(p.B, g, i);
-    stream_panel<NW, DEPTH>(p, xs, op, tid, wave, lane, panel, ks0, ks1);
+    stream_panel<NW, DEPTH, PW>(p, xs, op, tid, wave, lane, panel, pstride, ks0, ks1);
 
     // In-block K-split reduction: each wave parks its 64-column x 16-row tile in LDS
     // (the MFMA result holds, per lane, 4 consecutive columns of one batch row).
 #pragma unroll
-    for (int m = 0; m < MB; ++m) {
-        __syncthreads();               // X tile / previous pass no longer needed
+    for (int q = 0; q < PW; ++q) {
+        if (q < npanels) {
 #pragma unroll
-        for (int t = 0; t < kPanelTiles; ++t)
-            *reinterpret_cast<floatx4*>(red + (wave * 16 + i) * kRedPitch + t * kTileN + 4 * g) = op.acc[t][m];
-        __syncthreads();
-        reduce_rows<NW>(p, red, m, panel, split, tid);
+            for (int m = 0; m < MB; ++m) {
+                __syncthreads();               // X tile / previous pass no longer needed
+#pragma unroll
+                for (int t = 0; t < kPanelTiles; ++t)
+                    *reinterpret_cast<floatx4*>(red + (wave * 16 + i) * kRedPitch + t * kTileN + 4 * g) =
+                        op.acc[q * kPanelTiles + t][m];
+                __syncthreads();
+                reduce_rows<NW>(p, red, m, panel + q, split, tid);
+            }
+            if (p.S > 1) finish_split_k<NT>(p, panel + q, tid, &s_flag);
+        }
     }
-
-    if (p.S > 1) finish_split_k<NT>(p, panel, tid, &s_flag);
 }
 
-template <int MB, int NW, int DEPTH>
+template <int MB, int NW, int DEPTH, int PW>
 static int launch_one(const GroupParams& gp, size_t lds, hipStream_t st)
 {
-    hipLaunchKernelGGL((sbi_mfma_kernel<MB, NW, DEPTH>), dim3(gp.first_block[gp.G]), dim3(NW * 64), lds, st, gp);
+    if (lds > 64 * 1024) {
+        // more than the default 64 KiB of dynamic LDS has to be granted to the kernel first
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sbi_mfma_kernel<MB, NW, DEPTH, PW>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return (int)e;
+    }
+    hipLaunchKernelGGL((sbi_mfma_kernel<MB, NW, DEPTH, PW>), dim3(gp.first_block[gp.G]), dim3(NW * 64), lds, st, gp);
     return (int)hipGetLastError();
 }
 
-template <int NW, int DEPTH>
+template <int NW, int DEPTH, int PW>
 static int launch_mb(const GroupParams& gp, size_t lds, hipStream_t st)
 {
     switch ((gp.g[0].B + 15) / 16) {
-        case 1: return launch_one<1, NW, DEPTH>(gp, lds, st);
-        case 2: return launch_one<2, NW, DEPTH>(gp, lds, st);
-        case 3: return launch_one<3, NW, DEPTH>(gp, lds, st);
-        case 4: return launch_one<4, NW, DEPTH>(gp, lds, st);
+        case 1: return launch_one<1, NW, DEPTH, PW>(gp, lds, st);
+        case 2: return launch_one<2, NW, DEPTH, PW>(gp, lds, st);
+        case 3: return launch_one<3, NW, DEPTH, PW>(gp, lds, st);
+        case 4: return launch_one<4, NW, DEPTH, PW>(gp, lds, st);
     }
     return (int)hipErrorInvalidValue;
 }
 
-int launch_mfma(const GroupParams& gp, int waves, int depth, size_t lds_bytes, hipStream_t st)
+int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, size_t lds_bytes, hipStream_t st)
 {
     if (gp.G < 1 || gp.G > kMaxGroup) return (int)hipErrorInvalidValue;
-    if (waves == 4 && depth == 2) return launch_mb<4, 2>(gp, lds_bytes, st);
-    if (waves == 4 && depth == 4) return launch_mb<4, 4>(gp, lds_bytes, st);
-    if (waves == 4 && depth == 8) return launch_mb<4, 8>(gp, lds_bytes, st);
-    if (waves == 8 && depth == 4) return launch_mb<8, 4>(gp, lds_bytes, st);
-    if (waves == 8 && depth == 8) return launch_mb<8, 8>(gp, lds_bytes, st);
+    if (panels == 1) {
+        if (waves == 4 && depth == 2) return launch_mb<4, 2, 1>(gp, lds_bytes, st);
+        if (waves == 4 && depth == 4) return launch_mb<4, 4, 1>(gp, lds_bytes, st);
+        if (waves == 4 && depth == 8) return launch_mb<4, 8, 1>(gp, lds_bytes, st);
+        if (waves == 8 && depth == 4) return launch_mb<8, 4, 1>(gp, lds_bytes, st);
+        if (waves == 8 && depth == 8) return launch_mb<8, 8, 1>(gp, lds_bytes, st);
+    } else if (panels == 2) {
+        if (waves == 4 && depth == 2) return launch_mb<4, 2, 2>(gp, lds_bytes, st);
+        if (waves == 4 && depth == 4) return launch_mb<4, 4, 2>(gp, lds_bytes, st);
+        if (waves == 8 && depth == 2) return launch_mb<8, 2, 2>(gp, lds_bytes, st);
+    }
     return (int)hipErrorInvalidValue;
 }
 

@@ -79,10 +79,12 @@ def test_plan_invariants(B, K, N):
             continue
         S, ksps, kc = pl["split_k"], pl["ksteps_per_split"], pl["ksteps_per_chunk"]
         assert 1 <= S <= KS and ksps * S >= KS and ksps * (S - 1) < KS      # covers K, no empty block
-        assert pl["grid"] == P * S
+        pw = pl["panels"]
+        assert pw in (1, 2) and (pw == 1 or B > 16)
+        assert pl["grid"] == -(-P // pw) * S
         assert kc % (pl["waves"] * pl["depth"]) == 0 and kc >= pl["waves"] * pl["depth"]
         buffers = 1 if kc >= ksps else 2                         # X is double-buffered when chunked
-        assert pl["lds_bytes"] <= 64 * 1024 and pl["lds_bytes"] >= buffers * kc * B * 64
+        assert pl["lds_bytes"] <= (128 if pw == 2 else 64) * 1024 and pl["lds_bytes"] >= buffers * kc * B * 64
         if S == 1:
             assert pl["workspace_bytes"] == 0
         else:

@@ -122,6 +122,28 @@ def test_streamk_range_cuts(gpu, B, K, N):
                 check(Y, W, bias, X, R, epi, f"streamk B={B} K={K} N={N} w={waves} d={depth} blocks={blocks} {epi}")
 
 
+@pytest.mark.parametrize("B,K,N", [(1, 1024, 192), (8, 2048, 320), (16, 520, 72), (17, 4096, 136),
+                                   (33, 1024, 448), (48, 2048, 200), (64, 4096, 192)])
+def test_two_panel_blocks(gpu, B, K, N):
+    """Blocks that stream two adjacent panels (odd panel counts leave a lone last panel)."""
+    from paper_2207_00032_amd import binding as sb
+    W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=7, config_id=105)
+    Wl = None
+    ran = 0
+    for waves, depth in ((4, 2), (4, 4), (8, 2)):
+        for S in (1, 2, 5):
+            try:
+                sb.plan(B, K, N, sb.PATH_MFMA, S, waves, depth, panels=2)
+            except sb.SbiError:
+                continue
+            for epi in ("bias_gelu", "bias_residual"):
+                Y, Wl = gpu_gemm(gpu, W, bias, X, R, epi, Wl=Wl, path=sb.PATH_MFMA, split_k=S,
+                                 waves=waves, depth=depth, panels=2)
+                check(Y, W, bias, X, R, epi, f"2-panel B={B} K={K} N={N} S={S} w={waves} d={depth} {epi}")
+                ran += 1
+    assert ran > 0
+
+
 def test_workspace_reuse_and_determinism(gpu):
     """One workspace serves calls of different shapes back to back (the counters return to
     zero), and repeated calls give identical bits."""
