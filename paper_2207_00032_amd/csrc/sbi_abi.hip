@@ -81,18 +81,28 @@ double split_cost(int64_t KS, int64_t P, int64_t B, int S, int nw)
 
 sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot);
 
-// X staging of a block that streams `ksps` k-steps with `wd` = waves*depth k-steps per round and
-// at most `cap` bytes of LDS: one buffer if the whole range fits, else two buffers of `kc`
-// k-steps each (64 B per batch row per k-step).  False if not even one round fits.
-bool chunking(int64_t B, int64_t ksps, int64_t wd, int64_t cap, int64_t red_bytes, int64_t& kc, int64_t& lds)
+// X staging of a block of `nw` waves that streams `ksps` k-steps, `wd` = waves*depth k-steps per
+// round, with at most `cap` bytes of LDS (64 B per batch row per k-step).  One staging pass
+// moves 4 pieces of 16 bytes per thread, i.e. nw * 4 KiB; every further pass costs a memory
+// latency, so: one buffer if the whole range fits in one pass, else two buffers of `kc` k-steps,
+// each within one pass where a round of k-steps allows it.  False if not even one round fits.
+bool chunking(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t red_bytes,
+              int64_t& kc, int64_t& lds)
 {
-    const int64_t single = (cap / (B * 64)) / wd * wd;
-    if (round_up(ksps, wd) <= single) {
-        kc = round_up(ksps, wd);
+    const int64_t pass_bytes = (int64_t)nw * 4096;
+    const int64_t whole = round_up(ksps, wd);
+    if (whole * B * 64 <= std::min(cap, pass_bytes)) {
+        kc = whole;
         lds = std::max(kc * B * 64, red_bytes);
         return true;
     }
-    kc = (cap / 2 / (B * 64)) / wd * wd;
+    kc = (std::min(cap / 2, pass_bytes) / (B * 64)) / wd * wd;
+    if (kc < wd) kc = (cap / 2 / (B * 64) >= wd) ? wd : 0;       // a round needs more than one pass
+    if (kc >= whole) {                                           // fits in one buffer after all
+        kc = whole;
+        lds = std::max(kc * B * 64, red_bytes);
+        return kc * B * 64 <= cap;
+    }
     lds = std::max(2 * kc * B * 64, red_bytes);
     return kc >= wd;
 }
@@ -152,7 +162,7 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
 
     const int64_t wd = (int64_t)nw * depth;
     int64_t kc = 0, lds = 0;
-    if (!chunking(B, ksps, wd, pw == 2 ? kMaxLdsWide : kMaxLds, (int64_t)nw * 16 * kRedPitch * 4, kc, lds))
+    if (!chunking(B, ksps, wd, nw, pw == 2 ? kMaxLdsWide : kMaxLds, (int64_t)nw * 16 * kRedPitch * 4, kc, lds))
         return SBI_ERR_TUNING;
 
     pl.path = path; pl.nw = nw; pl.depth = depth; pl.S = S; pl.pw = pw;
@@ -310,7 +320,7 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
                     const int64_t S = ceil_div(KS[g], T);
                     const int64_t ksps = ceil_div(KS[g], S);
                     int64_t kc = 0, l = 0;
-                    ok = chunking(B, ksps, wd, cap, red_bytes, kc, l);
+                    ok = chunking(B, ksps, wd, nw, cap, red_bytes, kc, l);
                     if (!ok) break;
                     blocks += ceil_div(P[g], pw) * S;
                     maxk = std::max(maxk, ksps * pw);
@@ -352,7 +362,7 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
         const int64_t S = ceil_div(KS[g], bestT);
         const int64_t ksps = ceil_div(KS[g], S);
         int64_t kc = 0, l = 0;
-        chunking(B, ksps, wd, best_cap, (int64_t)nw * 16 * kRedPitch * 4, kc, l);
+        chunking(B, ksps, wd, nw, best_cap, (int64_t)nw * 16 * kRedPitch * 4, kc, l);
         pl.path = SBI_PATH_MFMA; pl.nw = nw; pl.depth = depth; pl.pw = pw;
         pl.S = (int)ceil_div(KS[g], ksps); pl.ksps = (int)ksps; pl.kc = (int)kc;
         pl.grid = (int)(ceil_div(P[g], pw) * pl.S); pl.block = nw * 64;

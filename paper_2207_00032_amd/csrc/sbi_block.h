@@ -86,21 +86,41 @@ struct XStage {
             }
             done = NT * XU;
         }
-        for (int idx = done + tid; idx < items; idx += NT) {
+        if (p.x_vec) {
+            // what did not fit in the first pass: further passes of XU pieces per thread, all
+            // reads of a pass issued before its LDS writes (one memory latency per pass)
+            for (int base = done; base < items; base += NT * XU) {
+                u32x4 v[XU];
+#pragma unroll
+                for (int u = 0; u < XU; ++u) {
+                    const int idx = min(base + tid + u * NT, items - 1);
+                    const int b = idx / nc;
+                    const int c = idx - b * nc;
+                    const int k = min(cb * kTileK + c * kChunkK, p.K - kChunkK);
+                    v[u] = *reinterpret_cast<const u32x4*>(p.X + (int64_t)b * p.K + k);
+                }
+#pragma unroll
+                for (int u = 0; u < XU; ++u) {
+                    const int idx = base + tid + u * NT;
+                    if (idx < items) {
+                        const int b = idx / nc;
+                        const int c = idx - b * nc;
+                        const bool inside = cb * kTileK + c * kChunkK < p.K;
+                        xs[c * p.B + b] = inside ? v[u] : u32x4{0u, 0u, 0u, 0u};
+                    }
+                }
+            }
+            return;
+        }
+        for (int idx = tid; idx < items; idx += NT) {      // K % 8 != 0: element-wise reads
             const int b = idx / nc;
             const int c = idx - b * nc;
             const int k = cb * kTileK + c * kChunkK;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (p.x_vec) {
-                if (k < p.K) v = *reinterpret_cast<const u32x4*>(p.X + (int64_t)b * p.K + k);
-            } else {
-                half8 h;
+            half8 h;
 #pragma unroll
-                for (int e = 0; e < kChunkK; ++e)
-                    h[e] = (k + e < p.K) ? p.X[(int64_t)b * p.K + k + e] : (_Float16)0.0f;
-                v = __builtin_bit_cast(u32x4, h);
-            }
-            xs[c * p.B + b] = v;
+            for (int e = 0; e < kChunkK; ++e)
+                h[e] = (k + e < p.K) ? p.X[(int64_t)b * p.K + k + e] : (_Float16)0.0f;
+            xs[c * p.B + b] = __builtin_bit_cast(u32x4, h);
         }
     }
 };
