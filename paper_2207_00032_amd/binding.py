@@ -9,7 +9,8 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsbi_gemm.so")
+# SBI_GEMM_LIB points at another build of the same library (e.g. one with tracing compiled in)
+LIB_PATH = os.environ.get("SBI_GEMM_LIB") or os.path.join(_HERE, "libsbi_gemm.so")
 
 MAX_BATCH = 64
 # sbi_epilogue

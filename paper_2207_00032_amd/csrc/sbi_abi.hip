@@ -6,6 +6,9 @@
 
 #include <algorithm>
 #include <cstring>
+#ifdef SBI_TRACE
+#include <cstdlib>
+#endif
 
 namespace {
 
@@ -262,6 +265,9 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
     p.KS = (int)ksteps_of(a.K); p.P = (int)ceil_div(a.N, kPanelN);
     p.S = pl.S; p.ksps = pl.ksps; p.kc = pl.kc;
     p.flags = a.flags; p.x_vec = (a.K % 8 == 0) ? 1 : 0;
+#ifdef SBI_TRACE
+    p.trace = getenv("SBI_TRACE_PTR") ? reinterpret_cast<unsigned long long*>(strtoull(getenv("SBI_TRACE_PTR"), nullptr, 16)) : nullptr;
+#endif
     return p;
 }
 

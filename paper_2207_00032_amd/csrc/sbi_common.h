@@ -58,6 +58,9 @@ struct GemmParams {
     int kc;                    // k-steps of X staged per chunk (multiple of waves*depth)
     int flags;                 // kEpi* bits
     int x_vec;                 // 1: X rows are 16-byte aligned and K % 8 == 0
+#ifdef SBI_TRACE
+    unsigned long long* trace; // development builds: 4 timestamps per block
+#endif
 };
 
 // ---- grouped launches: up to kMaxGroup independent GeMMs of one batch size per launch ----

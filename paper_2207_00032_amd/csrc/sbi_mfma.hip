@@ -78,9 +78,15 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
     // a missing second panel streams the first one again; its result is dropped
     const int64_t pstride = (npanels > 1) ? (int64_t)p.KS * (kPanelTiles * 64) : 0;
 
+#ifdef SBI_TRACE
+    const unsigned long long t_start = wall_clock64();
+#endif
     MfmaOp<MB, PW> op;
     op.init(p.B, g, i);
     stream_panel<NW, DEPTH, PW>(p, xs, op, tid, wave, lane, panel, pstride, ks0, ks1);
+#ifdef SBI_TRACE
+    const unsigned long long t_stream = wall_clock64();
+#endif
 
     // In-block K-split reduction: each wave parks its 64-column x 16-row tile in LDS
     // (the MFMA result holds, per lane, 4 consecutive columns of one batch row).
@@ -100,6 +106,13 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
             if (p.S > 1) finish_split_k<NT>(p, panel + q, tid, &s_flag);
         }
     }
+#ifdef SBI_TRACE
+    if (p.trace && tid == 0) {
+        unsigned long long* t = p.trace + (size_t)blockIdx.x * 4;
+        t[0] = t_start; t[1] = t_stream; t[2] = wall_clock64();
+        t[3] = ((unsigned long long)gi << 32) | (unsigned)bid;
+    }
+#endif
 }
 
 template <int MB, int NW, int DEPTH, int PW>
