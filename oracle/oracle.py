@@ -49,6 +49,9 @@ def lib():
         L.sbi_oracle_half_to_double_array.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
         L.sbi_oracle_double_to_half_array.restype = None
         L.sbi_oracle_double_to_half_array.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
+        L.sbi_oracle_layernorm.restype = ctypes.c_int
+        L.sbi_oracle_layernorm.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_double, ctypes.c_int64, ctypes.c_int64,
+                                           ctypes.c_void_p, ctypes.c_void_p]
         L.sbi_oracle_max_threads.restype = ctypes.c_int
         L.sbi_oracle_gemm.restype = ctypes.c_int
         L.sbi_oracle_gemm.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] + [ctypes.c_int64] * 3 + \
@@ -121,6 +124,22 @@ def gemm(X, W, bias=None, residual=None, epi=0, threads=0, return_pre=False):
         raise RuntimeError(f"sbi_oracle_gemm failed rc={rc}")
     Yh = Y.view(np.float16)
     return (Yh, pre) if return_pre else Yh
+
+
+def layernorm(X, gamma, beta, eps, return_pre=False):
+    """Row-wise layer normalisation of X [B,K] in fp64, rounded once to fp16 (it is the fp16
+    operand of the GeMM that follows).  eps is taken at fp32 precision, as the C ABI passes it."""
+    Xb, gb, bb = _bits(X, "X"), _bits(gamma, "gamma"), _bits(beta, "beta")
+    if Xb.ndim != 2 or gb.shape != (Xb.shape[1],) or bb.shape != (Xb.shape[1],):
+        raise ValueError("layernorm shapes")
+    B, K = Xb.shape
+    out = np.empty((B, K), dtype=np.uint16)
+    pre = np.empty((B, K), dtype=np.float64) if return_pre else None
+    rc = lib().sbi_oracle_layernorm(Xb.ctypes.data, gb.ctypes.data, bb.ctypes.data, float(np.float32(eps)),
+                                    B, K, out.ctypes.data, pre.ctypes.data if pre is not None else None)
+    if rc != 0:
+        raise RuntimeError(f"sbi_oracle_layernorm failed rc={rc}")
+    return (out.view(np.float16), pre) if return_pre else out.view(np.float16)
 
 
 # --------------------------------------------------------------------------------------

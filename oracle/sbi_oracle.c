@@ -93,6 +93,42 @@ double sbi_oracle_gelu(double v)
     return 0.5 * v * (1.0 + erf(v / sqrt(2.0)));
 }
 
+/*
+ * Layer normalisation of each row of X [B,K] (fp16 bits) in fp64, the operation the paper
+ * fuses in front of the QKV and the intermediate (FFN1) GeMM (Sec. III-D, regions 1 and 3;
+ * the layer-norm itself is the standard one it cites: per-row mean and biased variance over
+ * the K features):
+ *     mean = (1/K) sum_k x[k]        var = (1/K) sum_k (x[k] - mean)^2
+ *     y[k] = (x[k] - mean) / sqrt(var + eps) * gamma[k] + beta[k]
+ * The result is rounded once to fp16, because it is the fp16 operand of the GeMM that follows.
+ * `pre` (optional, [B,K] doubles) receives y before that rounding.
+ */
+int sbi_oracle_layernorm(const uint16_t* X, const uint16_t* gamma, const uint16_t* beta, double eps,
+                         int64_t B, int64_t K, uint16_t* out, double* pre)
+{
+    if (!X || !gamma || !beta || !out || B <= 0 || K <= 0 || !(eps >= 0.0)) return -1;
+    for (int64_t b = 0; b < B; ++b) {
+        const uint16_t* x = X + b * K;
+        double mean = 0.0;
+        for (int64_t k = 0; k < K; ++k) mean += sbi_oracle_half_to_double(x[k]);
+        mean /= (double)K;
+        double var = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            const double d = sbi_oracle_half_to_double(x[k]) - mean;
+            var += d * d;
+        }
+        var /= (double)K;
+        const double rstd = 1.0 / sqrt(var + eps);
+        for (int64_t k = 0; k < K; ++k) {
+            const double y = (sbi_oracle_half_to_double(x[k]) - mean) * rstd *
+                             sbi_oracle_half_to_double(gamma[k]) + sbi_oracle_half_to_double(beta[k]);
+            if (pre) pre[b * K + k] = y;
+            out[b * K + k] = sbi_oracle_double_to_half(y);
+        }
+    }
+    return 0;
+}
+
 void sbi_oracle_half_to_double_array(const uint16_t* h, double* d, int64_t n)
 {
     for (int64_t i = 0; i < n; ++i) d[i] = sbi_oracle_half_to_double(h[i]);

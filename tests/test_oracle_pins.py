@@ -349,3 +349,57 @@ def test_ulp16_and_check_close():
     assert not ok
     ok, _ = orc.check_close(np.array([8.0, 8.0, 0.1, 0.1, 65504.0], np.float16), w)
     assert not ok
+
+
+# ----------------------------------------------------------------------------- layer norm
+def test_layernorm_golden_and_closed_forms():
+    d = {}
+    for l in open(os.path.join(GOLDEN, "layernorm_case.txt")):
+        if l.strip() and not l.startswith("#"):
+            k, *v = l.split()
+            d[k] = np.array([float(t) for t in v])
+    y, pre = orc.layernorm(d["x"].reshape(1, 4).astype(np.float16), d["gamma"].astype(np.float16),
+                           d["beta"].astype(np.float16), d["eps"][0], return_pre=True)
+    assert np.allclose(pre[0], d["y"], rtol=0, atol=1e-15)
+    assert np.array_equal(y[0].astype(np.float64), d["y"])
+    K = 64
+    g = np.linspace(0.5, 2.0, K).astype(np.float16)
+    b = np.linspace(-1.0, 1.0, K).astype(np.float16)
+    # a constant row has zero variance: every output is beta
+    y = orc.layernorm(np.full((1, K), 3.25, np.float16), g, b, 1e-5)
+    assert np.array_equal(y[0].view(np.uint16), b.view(np.uint16))
+    # alternating +-1: mean 0, variance 1 -> x / sqrt(1 + eps) * gamma + beta
+    x = np.tile(np.array([1.0, -1.0], np.float16), K // 2).reshape(1, K)
+    eps = float(np.float32(1e-5))
+    _, pre = orc.layernorm(x, g, b, 1e-5, return_pre=True)
+    want = x[0].astype(np.float64) / math.sqrt(1.0 + eps) * g.astype(np.float64) + b.astype(np.float64)
+    assert np.allclose(pre[0], want, rtol=1e-15, atol=0)
+
+
+def test_layernorm_invariants_and_numpy():
+    rng = np.random.default_rng(21)
+    B, K = 5, 777
+    X = (rng.standard_normal((B, K)) * 3 + 1.5).astype(np.float16)
+    g = (1 + 0.1 * rng.standard_normal(K)).astype(np.float16)
+    b = (0.1 * rng.standard_normal(K)).astype(np.float16)
+    y, pre = orc.layernorm(X, g, b, 1e-5, return_pre=True)
+    Xd = X.astype(np.float64)
+    mu = Xd.mean(axis=1, keepdims=True)
+    var = ((Xd - mu) ** 2).mean(axis=1, keepdims=True)            # biased variance
+    ref = (Xd - mu) / np.sqrt(var + float(np.float32(1e-5))) * g.astype(np.float64) + b.astype(np.float64)
+    assert np.allclose(pre, ref, rtol=1e-12, atol=1e-13)
+    assert np.array_equal(y.view(np.uint16), ref.astype(np.float16).view(np.uint16))
+    # unbiased variance (K-1) would be visibly different: the oracle uses the biased one
+    ref_unbiased = (Xd - mu) / np.sqrt(var * K / (K - 1) + 1e-5) * g.astype(np.float64) + b.astype(np.float64)
+    assert np.abs(pre - ref_unbiased).max() > 1e-4
+    # with gamma = 1, beta = 0, eps = 0 the output has mean 0 and variance 1 ...
+    one, zero = np.ones(K, np.float16), np.zeros(K, np.float16)
+    _, p0 = orc.layernorm(X, one, zero, 0.0, return_pre=True)
+    assert np.allclose(p0.mean(axis=1), 0, atol=1e-13) and np.allclose((p0 ** 2).mean(axis=1), 1, rtol=1e-12)
+    # ... and is invariant to a power-of-two scaling of the row (exact in fp16)
+    _, p2 = orc.layernorm((Xd * 4).astype(np.float16), one, zero, 0.0, return_pre=True)
+    assert np.allclose(p2, p0, rtol=1e-12, atol=1e-13)
+    # rows are independent
+    assert np.array_equal(orc.layernorm(X[2:3], g, b, 1e-5).view(np.uint16), y[2:3].view(np.uint16))
+    with pytest.raises(ValueError):
+        orc.layernorm(X, g[:-1], b, 1e-5)
