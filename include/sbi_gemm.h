@@ -76,6 +76,9 @@ typedef struct sbi_tuning {
     int32_t blocks;  /* STREAMK path: upper bound on the number of thread blocks */
     int32_t panels;  /* MFMA path: 64-column panels per block, 1 or 2 (2: X is staged and read once
                         for 128 columns; for larger batches) */
+    int32_t layernorm; /* sbi_gemm_plan: nonzero plans the launch sbi_gemm_ln makes (layer-norm fused
+                          in front: MFMA path, one panel per block, K % 8 == 0, (waves, depth) one of
+                          (4,2), (4,4), (8,4)); sbi_gemm_ex rejects it, sbi_gemm_ln implies it */
 } sbi_tuning;
 
 /* What the dispatcher decided for a problem (for reports and tests). */
@@ -163,6 +166,37 @@ sbi_status sbi_gemm_ex(const void* W_laid_out, int64_t K, int64_t N,
                        void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
                        const sbi_tuning* tuning);
 
+/*
+ * Layer normalisation fused in front of the GeMM (paper Sec. III-D: regions 1 and 3 of the
+ * fused layer start with "input layer-norm" and run into the QKV / intermediate GeMM, with
+ * the input batch broadcast to every thread block so that no kernel boundary is needed):
+ *
+ *     mean_b = (1/K) sum_k X[b,k]          var_b = (1/K) sum_k (X[b,k] - mean_b)^2
+ *     Xn[b,k] = fp16( (X[b,k] - mean_b) / sqrt(var_b + eps) * gamma[k] + beta[k] )
+ *     Y = epilogue( Xn . W + bias )
+ *
+ * Every thread block recomputes the B row statistics (fp32, two passes) and normalises its
+ * share of X on the way into LDS; Xn is rounded to fp16 because it is the matrix-core operand.
+ *   gamma, beta  device, fp16 [K], 16-byte aligned
+ *   eps          finite, >= 0
+ * Needs K % 8 == 0 (SBI_ERR_SHAPE otherwise).  Everything else as for sbi_gemm_ex; `tuning`
+ * may be NULL.  Workspace need: sbi_gemm_ln_workspace_bytes, or sbi_gemm_plan with
+ * tuning->layernorm set (it can differ from the plain GeMM's).
+ */
+typedef struct sbi_layernorm {
+    const void* gamma;
+    const void* beta;
+    float eps;
+} sbi_layernorm;
+
+sbi_status sbi_gemm_ln(const void* W_laid_out, int64_t K, int64_t N,
+                       const void* X, int64_t B, const sbi_layernorm* ln,
+                       const void* bias, const void* residual, sbi_epilogue epi,
+                       void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
+                       const sbi_tuning* tuning);
+
+size_t sbi_gemm_ln_workspace_bytes(int64_t B, int64_t K, int64_t N);
+
 /* Host-only: the launch the dispatcher would make for (B, K, N) under `tuning` (or NULL). */
 sbi_status sbi_gemm_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tuning, sbi_plan* plan);
 
@@ -178,13 +212,18 @@ typedef struct sbi_layer {
     const void *bqkv, *bout, *bffn1, *bffn2; /* device fp16 or NULL */
     int64_t h, n_qkv, k_out, n_ffn1, k_ffn2;
     int32_t ffn1_gelu;                        /* nonzero: GeLU after FFN1's bias */
+    /* optional layer-norms fused in front of QKV (ln1, over Xqkv's rows) and FFN1 (ln2, over
+       Xffn1's rows), as in sbi_gemm_ln: device fp16 [h], 16-byte aligned, gamma and beta both
+       set or both NULL; they need h % 8 == 0 */
+    const void *ln1_gamma, *ln1_beta, *ln2_gamma, *ln2_beta;
+    float ln_eps;
 } sbi_layer;
 
 /*
  * Enqueues the four GeMMs on one stream:
- *   Yqkv  [B,n_qkv] = Xqkv[B,h] . Wqkv (+ bqkv)
+ *   Yqkv  [B,n_qkv] = LN1?(Xqkv[B,h]) . Wqkv (+ bqkv)
  *   Yout  [B,h]     = Xout[B,k_out] . Wout (+ bout)
- *   Yffn1 [B,n_ffn1]= act(Xffn1[B,h] . Wffn1 (+ bffn1))
+ *   Yffn1 [B,n_ffn1]= act(LN2?(Xffn1[B,h]) . Wffn1 (+ bffn1))
  *   Yffn2 [B,h]     = Xffn2[B,k_ffn2] . Wffn2 (+ bffn2) (+ residual[B,h])
  * Xffn2 == NULL chains FFN1's output (requires n_ffn1 == k_ffn2).  residual may be NULL.
  * workspace_bytes >= sbi_layer_workspace_bytes(L, B).

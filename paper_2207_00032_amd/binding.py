@@ -29,7 +29,8 @@ STATUS_NAMES = ["SBI_OK", "SBI_ERR_NULL", "SBI_ERR_SHAPE", "SBI_ERR_ALIGN", "SBI
 EXPORTS = ["sbi_gemm_layout_bytes", "sbi_gemm_workspace_bytes", "sbi_gemm_layout_weights",
            "sbi_gemm_unlayout_weights", "sbi_gemm_layout_check", "sbi_gemm", "sbi_gemm_ex",
            "sbi_gemm_plan", "sbi_layer_gemms", "sbi_layer_workspace_bytes", "sbi_status_string",
-           "sbi_version", "sbi_calib_read", "sbi_calib_copy", "sbi_layer_plan"]
+           "sbi_version", "sbi_calib_read", "sbi_calib_copy", "sbi_layer_plan", "sbi_gemm_ln",
+           "sbi_gemm_ln_workspace_bytes"]
 
 
 class SbiError(RuntimeError):
@@ -42,7 +43,11 @@ class SbiError(RuntimeError):
 class Tuning(ctypes.Structure):
     _fields_ = [("path", ctypes.c_int32), ("split_k", ctypes.c_int32),
                 ("waves", ctypes.c_int32), ("depth", ctypes.c_int32), ("blocks", ctypes.c_int32),
-                ("panels", ctypes.c_int32)]
+                ("panels", ctypes.c_int32), ("layernorm", ctypes.c_int32)]
+
+
+class LayerNorm(ctypes.Structure):
+    _fields_ = [("gamma", ctypes.c_void_p), ("beta", ctypes.c_void_p), ("eps", ctypes.c_float)]
 
 
 class Plan(ctypes.Structure):
@@ -61,7 +66,9 @@ class Layer(ctypes.Structure):
                 ("Wffn2", ctypes.c_void_p), ("bqkv", ctypes.c_void_p), ("bout", ctypes.c_void_p),
                 ("bffn1", ctypes.c_void_p), ("bffn2", ctypes.c_void_p),
                 ("h", ctypes.c_int64), ("n_qkv", ctypes.c_int64), ("k_out", ctypes.c_int64),
-                ("n_ffn1", ctypes.c_int64), ("k_ffn2", ctypes.c_int64), ("ffn1_gelu", ctypes.c_int32)]
+                ("n_ffn1", ctypes.c_int64), ("k_ffn2", ctypes.c_int64), ("ffn1_gelu", ctypes.c_int32),
+                ("ln1_gamma", ctypes.c_void_p), ("ln1_beta", ctypes.c_void_p),
+                ("ln2_gamma", ctypes.c_void_p), ("ln2_beta", ctypes.c_void_p), ("ln_eps", ctypes.c_float)]
 
 
 _lib = None
@@ -92,6 +99,11 @@ def load():
     L.sbi_gemm.argtypes = [vp, i64, i64, vp, i64, vp, vp, i32, vp, vp, sz, vp]
     L.sbi_gemm_ex.restype = i32
     L.sbi_gemm_ex.argtypes = [vp, i64, i64, vp, i64, vp, vp, i32, vp, vp, sz, vp, ctypes.POINTER(Tuning)]
+    L.sbi_gemm_ln.restype = i32
+    L.sbi_gemm_ln.argtypes = [vp, i64, i64, vp, i64, ctypes.POINTER(LayerNorm), vp, vp, i32, vp, vp, sz, vp,
+                              ctypes.POINTER(Tuning)]
+    L.sbi_gemm_ln_workspace_bytes.restype = sz
+    L.sbi_gemm_ln_workspace_bytes.argtypes = [i64, i64, i64]
     L.sbi_gemm_plan.restype = i32
     L.sbi_gemm_plan.argtypes = [i64, i64, i64, ctypes.POINTER(Tuning), ctypes.POINTER(Plan)]
     L.sbi_layer_gemms.restype = i32
@@ -130,10 +142,11 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def _tuning(path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0, panels=0):
-    if path == PATH_AUTO and not (split_k or waves or depth or blocks or panels):
+def _tuning(path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0, panels=0, layernorm=0):
+    if path == PATH_AUTO and not (split_k or waves or depth or blocks or panels or layernorm):
         return None
-    return ctypes.pointer(Tuning(int(path), int(split_k), int(waves), int(depth), int(blocks), int(panels)))
+    return ctypes.pointer(Tuning(int(path), int(split_k), int(waves), int(depth), int(blocks), int(panels),
+                                 1 if layernorm else 0))
 
 
 # ---------------------------------------------------------------------------------- sizes
@@ -145,10 +158,14 @@ def workspace_bytes(B, K, N):
     return int(load().sbi_gemm_workspace_bytes(B, K, N))
 
 
-def plan(B, K, N, path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0, panels=0):
+def ln_workspace_bytes(B, K, N):
+    return int(load().sbi_gemm_ln_workspace_bytes(B, K, N))
+
+
+def plan(B, K, N, path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0, panels=0, layernorm=False):
     pl = Plan()
-    _check(load().sbi_gemm_plan(B, K, N, _tuning(path, split_k, waves, depth, blocks, panels), ctypes.byref(pl)),
-           "sbi_gemm_plan")
+    _check(load().sbi_gemm_plan(B, K, N, _tuning(path, split_k, waves, depth, blocks, panels, layernorm),
+                                ctypes.byref(pl)), "sbi_gemm_plan")
     return pl.as_dict()
 
 
@@ -183,8 +200,10 @@ def layout_check(Wl, K, N):
 
 
 def gemm(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, workspace=None,
-         path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0, panels=0):
-    """Y = epilogue(X @ W + bias) through sbi_gemm / sbi_gemm_ex.  Returns Y (fp16 [B,N])."""
+         path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0, panels=0, layernorm=None):
+    """Y = epilogue(X @ W + bias) through sbi_gemm / sbi_gemm_ex, or, with
+    layernorm=(gamma, beta, eps), Y = epilogue(LN(X) @ W + bias) through sbi_gemm_ln.
+    Returns Y (fp16 [B,N])."""
     import torch
     assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.is_contiguous()
     B = X.shape[0]
@@ -194,11 +213,21 @@ def gemm(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, wor
         out = torch.empty((B, N), dtype=torch.float16, device=X.device)
     tune = _tuning(path, split_k, waves, depth, blocks, panels)
     if workspace is None:
-        need = plan(B, K, N, path, split_k, waves, depth, blocks, panels)["workspace_bytes"] if tune \
-            else workspace_bytes(B, K, N)
+        if tune or layernorm is not None:
+            need = plan(B, K, N, path, split_k, waves, depth, blocks, panels,
+                        layernorm is not None)["workspace_bytes"]
+        else:
+            need = workspace_bytes(B, K, N)
         workspace = new_workspace(need, X.device) if need else None
     ws_ptr = _ptr(workspace)
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    if layernorm is not None:
+        gamma, beta, eps = layernorm
+        ln = LayerNorm(gamma.data_ptr(), beta.data_ptr(), float(eps))
+        st = load().sbi_gemm_ln(_ptr(Wl), K, N, _ptr(X), B, ctypes.byref(ln), _ptr(bias), _ptr(residual),
+                                int(epilogue), _ptr(out), ws_ptr, ws_len, _stream(), tune)
+        _check(st, "sbi_gemm_ln")
+        return out
     if tune is None:
         st = load().sbi_gemm(_ptr(Wl), K, N, _ptr(X), B, _ptr(bias), _ptr(residual), int(epilogue),
                              _ptr(out), ws_ptr, ws_len, _stream())
@@ -210,13 +239,18 @@ def gemm(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, wor
 
 
 def make_layer(Wqkv, Wout, Wffn1, Wffn2, h, n_qkv, k_out, n_ffn1, k_ffn2,
-               bqkv=None, bout=None, bffn1=None, bffn2=None, ffn1_gelu=True):
+               bqkv=None, bout=None, bffn1=None, bffn2=None, ffn1_gelu=True, ln1=None, ln2=None, ln_eps=1e-5):
     """Fill an sbi_layer from laid-out weight tensors; keep the tensors alive yourself."""
     L = Layer()
     L.Wqkv, L.Wout, L.Wffn1, L.Wffn2 = (w.data_ptr() for w in (Wqkv, Wout, Wffn1, Wffn2))
     L.bqkv, L.bout, L.bffn1, L.bffn2 = (None if b is None else b.data_ptr() for b in (bqkv, bout, bffn1, bffn2))
     L.h, L.n_qkv, L.k_out, L.n_ffn1, L.k_ffn2 = h, n_qkv, k_out, n_ffn1, k_ffn2
     L.ffn1_gelu = 1 if ffn1_gelu else 0
+    if ln1 is not None:                       # (gamma, beta) tensors, fp16 [h]
+        L.ln1_gamma, L.ln1_beta = ln1[0].data_ptr(), ln1[1].data_ptr()
+    if ln2 is not None:
+        L.ln2_gamma, L.ln2_beta = ln2[0].data_ptr(), ln2[1].data_ptr()
+    L.ln_eps = float(ln_eps)
     return L
 
 

@@ -5,6 +5,7 @@
 #include "sbi_common.h"
 
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #ifdef SBI_TRACE
 #include <cstdlib>
@@ -29,6 +30,7 @@ struct Plan {
     int64_t lds, ws_bytes, counter_bytes;
     int upw, nwaves;          // STREAMK path: units per wavefront, wavefronts
     int pw;                   // MFMA path: panels per block
+    bool ln;                  // MFMA path: the kernel variant that can layer-normalise X
 };
 
 constexpr int kSkDefaultWaves = 2048;             // wavefronts of a STREAMK launch: 8 per CU
@@ -45,7 +47,7 @@ sbi_status plan_streamk(int64_t B, int64_t units, int64_t panels, const sbi_tuni
     const int64_t want = t.blocks ? (int64_t)t.blocks * nw : kSkDefaultWaves;
     const int64_t upw = round_up(ceil_div(units, want), kStepGroup);
     const int64_t nwaves = ceil_div(units, upw);
-    pl.path = SBI_PATH_STREAMK; pl.nw = nw; pl.depth = depth; pl.S = 0;
+    pl.ln = false; pl.path = SBI_PATH_STREAMK; pl.nw = nw; pl.depth = depth; pl.S = 0;
     pl.ksps = (int)upw; pl.kc = 0; pl.pw = 1;
     pl.grid = (int)ceil_div(nwaves, nw); pl.block = nw * 64; pl.lds = 0;
     pl.upw = (int)upw; pl.nwaves = (int)nwaves;
@@ -82,7 +84,7 @@ double split_cost(int64_t KS, int64_t P, int64_t B, int S, int nw)
     return cost;
 }
 
-sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot);
+sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot, bool ln);
 
 // X staging of a block of `nw` waves that streams `ksps` k-steps, `wd` = waves*depth k-steps per
 // round, with at most `cap` bytes of LDS (64 B per batch row per k-step).  One staging pass
@@ -90,7 +92,11 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
 // latency, so: one buffer if the whole range fits in one pass, else two buffers of `kc` k-steps,
 // each within one pass where a round of k-steps allows it.  False if not even one round fits.
 bool chunking(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t red_bytes,
-              int64_t& kc, int64_t& lds)
+              int64_t& kc, int64_t& lds, int64_t front = 0);
+
+// The same with `front` bytes of LDS reserved ahead of the X buffers (layer-norm statistics).
+bool chunking_impl(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t red_bytes,
+                   int64_t& kc, int64_t& lds)
 {
     const int64_t pass_bytes = (int64_t)nw * 4096;
     const int64_t whole = round_up(ksps, wd);
@@ -110,6 +116,14 @@ bool chunking(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t 
     return kc >= wd;
 }
 
+bool chunking(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t red_bytes,
+              int64_t& kc, int64_t& lds, int64_t front)
+{
+    const bool ok = chunking_impl(B, ksps, wd, nw, cap - front, std::max<int64_t>(red_bytes - front, 0), kc, lds);
+    lds += front;
+    return ok;
+}
+
 sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Plan& pl)
 {
     if (sbi_status s = check_shape(K, N)) return s;
@@ -117,13 +131,16 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     const int64_t KS = ksteps_of(K);
     const int64_t P = ceil_div(N, kPanelN);
 
-    sbi_tuning t = {0, 0, 0, 0, 0, 0};
+    sbi_tuning t = {0, 0, 0, 0, 0, 0, 0};
     if (tune) t = *tune;
+    const bool ln = t.layernorm != 0;
 
     if (t.split_k < 0 || t.blocks < 0 || t.panels < 0 || t.panels > 2) return SBI_ERR_TUNING;
     int path = t.path;
     const bool sk_ok = (K % kChunkK == 0);            // X rows readable as 128-bit pieces
-    if (path == SBI_PATH_AUTO) path = (B <= kAutoStreamBatch) ? SBI_PATH_STREAM : SBI_PATH_MFMA;
+    if (path == SBI_PATH_AUTO) path = (B <= kAutoStreamBatch && !ln) ? SBI_PATH_STREAM : SBI_PATH_MFMA;
+    // layer-norm in front of the GeMM: matrix-core block kernel only, rows read as 128-bit pieces
+    if (ln && (path != SBI_PATH_MFMA || K % kChunkK != 0 || t.panels == 2)) return SBI_ERR_TUNING;
     if (path == SBI_PATH_STREAMK) {
         if (!sk_ok) return SBI_ERR_TUNING;
         return plan_streamk(B, KS * P, P, t, pl);
@@ -132,7 +149,7 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     if (path == SBI_PATH_STREAM && B > kStreamMaxBatch) return SBI_ERR_TUNING;
     if (path == SBI_PATH_MFMA && t.split_k == 0 && t.waves == 0 && t.depth == 0 && t.panels == 0) {
         Plan one;
-        if (sbi_status s = plan_group(B, &K, &N, 1, &one, pl)) return s;
+        if (sbi_status s = plan_group(B, &K, &N, 1, &one, pl, ln)) return s;
         pl.S = one.S; pl.ksps = one.ksps; pl.kc = one.kc; pl.pw = one.pw;
         return SBI_OK;
     }
@@ -145,6 +162,7 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     bool depth_ok = depth == 4 || depth == 8 || (depth == 2 && nw == 4 && path == SBI_PATH_MFMA);
     if (pw == 2) depth_ok = (nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 2);
     if ((nw != 4 && nw != 8) || !depth_ok) return SBI_ERR_TUNING;
+    if (ln && !((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))) return SBI_ERR_TUNING;
     int S = t.split_k;
     if (S < 0) return SBI_ERR_TUNING;
     if (S == 0) {
@@ -165,9 +183,11 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
 
     const int64_t wd = (int64_t)nw * depth;
     int64_t kc = 0, lds = 0;
-    if (!chunking(B, ksps, wd, nw, pw == 2 ? kMaxLdsWide : kMaxLds, (int64_t)nw * 16 * kRedPitch * 4, kc, lds))
+    if (!chunking(B, ksps, wd, nw, (pw == 2 || ln) ? kMaxLdsWide : kMaxLds, (int64_t)nw * 16 * kRedPitch * 4, kc, lds,
+                  ln ? kLnStatsBytes : 0))
         return SBI_ERR_TUNING;
 
+    pl.ln = ln;
     pl.path = path; pl.nw = nw; pl.depth = depth; pl.S = S; pl.pw = pw;
     pl.ksps = (int)ksps; pl.kc = (int)kc;
     pl.grid = (int)(PG * S); pl.block = nw * 64;
@@ -196,7 +216,18 @@ inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintp
 // One GeMM of a launch, already validated.
 struct GemmArgs {
     const void* Wl; int64_t K, N; const void* X; const void* bias; const void* R; int flags; void* Y;
+    const void* gamma; const void* beta; float eps;     // layer-norm of X's rows when gamma != null
 };
+
+// Validation of a layer-norm request in front of a GeMM with K input features.
+sbi_status check_layernorm(const void* gamma, const void* beta, float eps, int64_t K)
+{
+    if (!gamma || !beta) return SBI_ERR_NULL;
+    if (K % kChunkK != 0) return SBI_ERR_SHAPE;
+    if (!aligned(gamma, 16) || !aligned(beta, 16)) return SBI_ERR_ALIGN;
+    if (!(eps >= 0.0f) || !std::isfinite(eps)) return SBI_ERR_EPILOGUE;
+    return SBI_OK;
+}
 
 // Validation shared by sbi_gemm_ex and sbi_layer_gemms (everything except the workspace).
 sbi_status check_gemm_args(const void* W_laid_out, int64_t K, int64_t N, const void* X, int64_t B,
@@ -265,6 +296,12 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
     p.KS = (int)ksteps_of(a.K); p.P = (int)ceil_div(a.N, kPanelN);
     p.S = pl.S; p.ksps = pl.ksps; p.kc = pl.kc;
     p.flags = a.flags; p.x_vec = (a.K % 8 == 0) ? 1 : 0;
+    // the layer-norm kernel variant reads gamma and beta pieces unconditionally: a problem
+    // without layer-norm points them at its X (K readable halfs) and ignores the values
+    p.ln = a.gamma ? 1 : 0;
+    p.ln_gamma = reinterpret_cast<const _Float16*>(a.gamma ? a.gamma : a.X);
+    p.ln_beta = reinterpret_cast<const _Float16*>(a.gamma ? a.beta : a.X);
+    p.ln_eps = a.eps;
 #ifdef SBI_TRACE
     p.trace = getenv("SBI_TRACE_PTR") ? reinterpret_cast<unsigned long long*>(strtoull(getenv("SBI_TRACE_PTR"), nullptr, 16)) : nullptr;
 #endif
@@ -274,13 +311,17 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
 // Wavefronts per CU that the register file lets the MFMA block kernel keep resident: the
 // vector registers of the compiled kernel variants (row blocks MB = ceil(B/16), waves, depth),
 // 512 registers per SIMD lane, 4 SIMDs per CU.
-int resident_waves(int mb, int nw, int depth, int pw)
+int resident_waves(int mb, int nw, int depth, int pw, bool ln)
 {
-    static const int vgpr_w4d2[4] = {92, 116, 152, 184};
-    static const int vgpr_w4d4[4] = {124, 152, 192, 230};
-    static const int vgpr_w8d4[4] = {120, 138, 158, 180};
-    static const int vgpr_w8d2p2[4] = {136, 170, 206, 244};
+    static const int vgpr_w4d2[4] = {108, 128, 156, 180};
+    static const int vgpr_w4d4[4] = {140, 164, 196, 226};
+    static const int vgpr_w8d4[4] = {134, 152, 170, 188};
+    static const int vgpr_w8d2p2[4] = {150, 184, 218, 252};
+    static const int vgpr_ln_w4d2[4] = {152, 172, 200, 224};
+    static const int vgpr_ln_w4d4[4] = {184, 208, 232, 270};
+    static const int vgpr_ln_w8d4[4] = {178, 196, 213, 230};
     const int* tab = (pw == 2) ? vgpr_w8d2p2 : (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);
+    if (ln) tab = (nw == 8) ? vgpr_ln_w8d4 : (depth == 2 ? vgpr_ln_w4d2 : vgpr_ln_w4d4);
     const int v = (tab[std::min(std::max(mb, 1), 4) - 1] + 7) / 8 * 8;
     return 4 * std::min(8, 512 / v);
 }
@@ -292,7 +333,7 @@ int resident_waves(int mb, int nw, int depth, int pw)
 // ranked by  rounds x blocks-per-CU x block time, where the blocks a CU can hold follow from
 // the LDS each block needs for its X chunk and from the register file.  Returns per-problem
 // plans plus the launch totals in `tot` (nw, depth, lds, grid, ws_bytes).
-sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot)
+sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot, bool ln)
 {
     if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
     const int mb = (int)ceil_div(B, 16);
@@ -305,6 +346,7 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
     if (panels > kCounterBytes / 4) return SBI_ERR_SHAPE;
     constexpr int64_t kLdsPerCU = 160 * 1024;
     const int64_t lds_caps[4] = {16 * 1024, 32 * 1024, kMaxLds, kMaxLdsWide};
+    const int64_t front = ln ? kLnStatsBytes : 0;
     // (waves, depth, panels per block) candidates; two-panel blocks only pay off for B > 16
     const int shapes[4][3] = {{4, 4, 1}, {8, 4, 1}, {4, 2, 1}, {8, 2, 2}};
 
@@ -313,11 +355,13 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
     double best = 0.0;
     for (const auto& shp : shapes) {
         const int nw = shp[0], depth = shp[1], pw = shp[2];
-        if (pw == 2 && mb < 2) continue;
+        if (pw == 2 && (mb < 2 || ln)) continue;
         const int64_t wd = (int64_t)nw * depth;
         const int64_t red_bytes = (int64_t)nw * 16 * kRedPitch * 4;
         for (int64_t cap : lds_caps) {
-            if ((cap > kMaxLds) != (pw == 2)) continue;            // the wide budget belongs to two-panel blocks
+            // the wide budget belongs to two-panel blocks, and to layer-norm blocks (their statistics
+            // take the room that a batch of 64 needs for two X buffers within 64 KiB)
+            if ((cap > kMaxLds) != (pw == 2) && !(ln && cap > kMaxLds)) continue;
             for (int64_t T = wd; T < maxKS + wd; T += wd) {
                 int64_t blocks = 0, maxk = 0, lds = red_bytes, chunks = 1;
                 double partial = 0.0;
@@ -326,7 +370,7 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
                     const int64_t S = ceil_div(KS[g], T);
                     const int64_t ksps = ceil_div(KS[g], S);
                     int64_t kc = 0, l = 0;
-                    ok = chunking(B, ksps, wd, nw, cap, red_bytes, kc, l);
+                    ok = chunking(B, ksps, wd, nw, cap, red_bytes, kc, l, front);
                     if (!ok) break;
                     blocks += ceil_div(P[g], pw) * S;
                     maxk = std::max(maxk, ksps * pw);
@@ -337,7 +381,7 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
                 }
                 if (!ok) continue;
                 const int64_t fit = std::max<int64_t>(1, std::min<int64_t>(kLdsPerCU / lds,
-                                                                           resident_waves(mb, nw, depth, pw) / nw));
+                                                                           resident_waves(mb, nw, depth, pw, ln) / nw));
                 const int64_t per_cu = std::min<int64_t>(fit, ceil_div(blocks, kNumCU));   // concurrent blocks on a CU
                 const int64_t rounds = ceil_div(blocks, (int64_t)kNumCU * fit);
                 const double busy = (double)std::min<int64_t>(blocks, kNumCU) / kNumCU;
@@ -368,8 +412,8 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
         const int64_t S = ceil_div(KS[g], bestT);
         const int64_t ksps = ceil_div(KS[g], S);
         int64_t kc = 0, l = 0;
-        chunking(B, ksps, wd, nw, best_cap, (int64_t)nw * 16 * kRedPitch * 4, kc, l);
-        pl.path = SBI_PATH_MFMA; pl.nw = nw; pl.depth = depth; pl.pw = pw;
+        chunking(B, ksps, wd, nw, best_cap, (int64_t)nw * 16 * kRedPitch * 4, kc, l, front);
+        pl.path = SBI_PATH_MFMA; pl.nw = nw; pl.depth = depth; pl.pw = pw; pl.ln = ln;
         pl.S = (int)ceil_div(KS[g], ksps); pl.ksps = (int)ksps; pl.kc = (int)kc;
         pl.grid = (int)(ceil_div(P[g], pw) * pl.S); pl.block = nw * 64;
         pl.lds = l;
@@ -408,7 +452,7 @@ sbi_status launch_block_group(const GemmArgs* a, const Plan* pls, const Plan& to
         partial_off += pls[g].ws_bytes;
     }
     gp.first_block[G] = first;
-    return launch_mfma(gp, tot.nw, tot.depth, tot.pw, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
+    return launch_mfma(gp, tot.nw, tot.depth, tot.pw, tot.ln, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
 }
 
 }  // namespace
@@ -425,6 +469,14 @@ size_t sbi_gemm_workspace_bytes(int64_t B, int64_t K, int64_t N)
 {
     Plan pl;
     if (make_plan(B, K, N, nullptr, pl) != SBI_OK) return 0;
+    return (size_t)pl.ws_bytes;
+}
+
+size_t sbi_gemm_ln_workspace_bytes(int64_t B, int64_t K, int64_t N)
+{
+    const sbi_tuning t = {0, 0, 0, 0, 0, 0, 1};
+    Plan pl;
+    if (make_plan(B, K, N, &t, pl) != SBI_OK) return 0;
     return (size_t)pl.ws_bytes;
 }
 
@@ -476,27 +528,29 @@ sbi_status sbi_gemm_layout_check(const void* W_laid_out, int64_t K, int64_t N, v
     return ok ? SBI_OK : SBI_ERR_LAYOUT_MISMATCH;
 }
 
-sbi_status sbi_gemm_ex(const void* W_laid_out, int64_t K, int64_t N,
-                       const void* X, int64_t B,
-                       const void* bias, const void* residual, sbi_epilogue epi,
-                       void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
-                       const sbi_tuning* tuning)
+static sbi_status gemm_impl(const void* W_laid_out, int64_t K, int64_t N,
+                            const void* X, int64_t B, const sbi_layernorm* ln,
+                            const void* bias, const void* residual, sbi_epilogue epi,
+                            void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
+                            const sbi_tuning* tuning)
 {
     int flags = 0;
     if (sbi_status s = check_gemm_args(W_laid_out, K, N, X, B, bias, residual, (int)epi, Y, flags)) return s;
+    sbi_tuning t = {0, 0, 0, 0, 0, 0, 0};
+    if (tuning) t = *tuning;
+    t.layernorm = ln ? 1 : 0;
+    if (ln)
+        if (sbi_status s = check_layernorm(ln->gamma, ln->beta, ln->eps, K)) return s;
     Plan pl;
-    if (sbi_status s = make_plan(B, K, N, tuning, pl)) return s;
+    if (sbi_status s = make_plan(B, K, N, &t, pl)) return s;
     if (pl.ws_bytes > 0) {
         if (!workspace || workspace_bytes < (size_t)pl.ws_bytes) return SBI_ERR_WORKSPACE;
         if (!aligned(workspace, 256)) return SBI_ERR_ALIGN;
     }
     hipStream_t st = (hipStream_t)hip_stream;
-    if (pl.path == SBI_PATH_STREAMK) {
-        const GemmArgs a = {W_laid_out, K, N, X, bias, residual, flags, Y};
-        return launch_group(&a, 1, B, pl, workspace, st);
-    }
-
-    const GemmArgs a = {W_laid_out, K, N, X, bias, residual, flags, Y};
+    GemmArgs a = {W_laid_out, K, N, X, bias, residual, flags, Y, nullptr, nullptr, 0.0f};
+    if (pl.path == SBI_PATH_STREAMK) return launch_group(&a, 1, B, pl, workspace, st);
+    if (ln) { a.gamma = ln->gamma; a.beta = ln->beta; a.eps = ln->eps; }
     Plan one = pl;
     one.ws_bytes = (pl.S > 1) ? pl.ws_bytes - pl.counter_bytes : 0;
     if (pl.path == SBI_PATH_MFMA) return launch_block_group(&a, &one, pl, 1, B, workspace, st);
@@ -504,13 +558,35 @@ sbi_status sbi_gemm_ex(const void* W_laid_out, int64_t K, int64_t N,
     return launch_stream(p, pl.nw, pl.depth, (size_t)pl.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
 }
 
+sbi_status sbi_gemm_ex(const void* W_laid_out, int64_t K, int64_t N,
+                       const void* X, int64_t B,
+                       const void* bias, const void* residual, sbi_epilogue epi,
+                       void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
+                       const sbi_tuning* tuning)
+{
+    if (tuning && tuning->layernorm) return SBI_ERR_TUNING;      // layer-norm needs its parameters: sbi_gemm_ln
+    return gemm_impl(W_laid_out, K, N, X, B, nullptr, bias, residual, epi, Y, workspace, workspace_bytes,
+                     hip_stream, tuning);
+}
+
 sbi_status sbi_gemm(const void* W_laid_out, int64_t K, int64_t N,
                     const void* X, int64_t B,
                     const void* bias, const void* residual, sbi_epilogue epi,
                     void* Y, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    return sbi_gemm_ex(W_laid_out, K, N, X, B, bias, residual, epi, Y, workspace, workspace_bytes,
-                       hip_stream, nullptr);
+    return gemm_impl(W_laid_out, K, N, X, B, nullptr, bias, residual, epi, Y, workspace, workspace_bytes,
+                     hip_stream, nullptr);
+}
+
+sbi_status sbi_gemm_ln(const void* W_laid_out, int64_t K, int64_t N,
+                       const void* X, int64_t B, const sbi_layernorm* ln,
+                       const void* bias, const void* residual, sbi_epilogue epi,
+                       void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
+                       const sbi_tuning* tuning)
+{
+    if (!ln) return SBI_ERR_NULL;
+    return gemm_impl(W_laid_out, K, N, X, B, ln, bias, residual, epi, Y, workspace, workspace_bytes,
+                     hip_stream, tuning);
 }
 
 static sbi_status layer_check(const sbi_layer* L, int64_t B)
@@ -522,6 +598,10 @@ static sbi_status layer_check(const sbi_layer* L, int64_t B)
     if (sbi_status s = check_shape(L->k_out, L->h)) return s;
     if (sbi_status s = check_shape(L->h, L->n_ffn1)) return s;
     if (sbi_status s = check_shape(L->k_ffn2, L->h)) return s;
+    if (L->ln1_gamma || L->ln1_beta)
+        if (sbi_status s = check_layernorm(L->ln1_gamma, L->ln1_beta, L->ln_eps, L->h)) return s;
+    if (L->ln2_gamma || L->ln2_beta)
+        if (sbi_status s = check_layernorm(L->ln2_gamma, L->ln2_beta, L->ln_eps, L->h)) return s;
     return SBI_OK;
 }
 
@@ -530,7 +610,7 @@ static sbi_status layer_group_plan(const sbi_layer* L, int64_t B, int count, Pla
 {
     const int64_t Ks[4] = {L->h, L->k_out, L->h, L->k_ffn2};
     const int64_t Ns[4] = {L->n_qkv, L->h, L->n_ffn1, L->h};
-    return plan_group(B, Ks, Ns, count, pls, tot);
+    return plan_group(B, Ks, Ns, count, pls, tot, L->ln1_gamma || L->ln2_gamma);
 }
 
 size_t sbi_layer_workspace_bytes(const sbi_layer* L, int64_t B)
@@ -586,10 +666,10 @@ sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
     const sbi_epilogue e2 = residual ? (L->bffn2 ? SBI_EPI_BIAS_RESIDUAL : SBI_EPI_RESIDUAL)
                                      : (L->bffn2 ? SBI_EPI_BIAS : SBI_EPI_NONE);
     GemmArgs a[4] = {
-        {L->Wqkv, L->h, L->n_qkv, Xqkv, L->bqkv, nullptr, 0, Yqkv},
-        {L->Wout, L->k_out, L->h, Xout, L->bout, nullptr, 0, Yout},
-        {L->Wffn1, L->h, L->n_ffn1, Xffn1, L->bffn1, nullptr, 0, Yffn1},
-        {L->Wffn2, L->k_ffn2, L->h, Xffn2, L->bffn2, residual, 0, Yffn2},
+        {L->Wqkv, L->h, L->n_qkv, Xqkv, L->bqkv, nullptr, 0, Yqkv, L->ln1_gamma, L->ln1_beta, L->ln_eps},
+        {L->Wout, L->k_out, L->h, Xout, L->bout, nullptr, 0, Yout, nullptr, nullptr, 0.0f},
+        {L->Wffn1, L->h, L->n_ffn1, Xffn1, L->bffn1, nullptr, 0, Yffn1, L->ln2_gamma, L->ln2_beta, L->ln_eps},
+        {L->Wffn2, L->k_ffn2, L->h, Xffn2, L->bffn2, residual, 0, Yffn2, nullptr, nullptr, 0.0f},
     };
     const sbi_epilogue epis[4] = {e0, eo, e1, e2};
     for (int g = 0; g < 4; ++g)

@@ -43,15 +43,93 @@ __device__ __forceinline__ void store_pair(const GemmParams& p, int b, int n, fl
     }
 }
 
+// ---- layer normalisation in front of the GeMM (paper Sec. III-D, regions 1 and 3) ----------
+// Every block recomputes the statistics of all B rows of X (the paper does the same: the input
+// batch is broadcast to every SM and the operations before the GeMM are repeated there, so no
+// kernel boundary is needed).  Wave w takes rows w, w+NW, ...; two passes over the row (mean,
+// then the biased variance around it) in fp32, lanes strided over 16-byte pieces, the second
+// pass re-reading the row from L2.  stats[b] = (mean, 1/sqrt(var + eps)).
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+template <int NW>
+__device__ __forceinline__ void ln_stats(const GemmParams& p, floatx2* stats, int wave, int lane)
+{
+    constexpr int U = 8;                       // 128-bit loads in flight per lane: 4096 elements of a row
+    const int pieces = p.K / kChunkK;
+    const bool resident = pieces <= 64 * U;    // the whole row stays in registers for the second pass
+    for (int r = wave; r < p.B; r += NW) {
+        const _Float16* row = p.X + (int64_t)r * p.K;
+        u32x4 h[U];
+        float s = 0.f;
+        for (int c0 = 0; c0 < pieces; c0 += 64 * U) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                h[u] = *reinterpret_cast<const u32x4*>(row + min(c0 + u * 64 + lane, pieces - 1) * kChunkK);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const half8 v = __builtin_bit_cast(half8, h[u]);
+                float t = 0.f;
+#pragma unroll
+                for (int e = 0; e < kChunkK; ++e) t += (float)v[e];
+                s += (c0 + u * 64 + lane < pieces) ? t : 0.f;
+            }
+        }
+        const float mean = wave_sum(s) / (float)p.K;
+        float q = 0.f;
+        for (int c0 = 0; c0 < pieces; c0 += 64 * U) {
+            if (!resident) {
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    h[u] = *reinterpret_cast<const u32x4*>(row + min(c0 + u * 64 + lane, pieces - 1) * kChunkK);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const half8 v = __builtin_bit_cast(half8, h[u]);
+                float t = 0.f;
+#pragma unroll
+                for (int e = 0; e < kChunkK; ++e) {
+                    const float d = (float)v[e] - mean;
+                    t += d * d;
+                }
+                q += (c0 + u * 64 + lane < pieces) ? t : 0.f;
+            }
+        }
+        const float var = wave_sum(q) / (float)p.K;
+        if (lane == 0) stats[r] = floatx2{mean, 1.0f / sqrtf(var + p.ln_eps)};
+    }
+}
+
+// y = (x - mean) * rstd * gamma + beta on 8 halfs, computed in fp32, rounded once to fp16.
+__device__ __forceinline__ u32x4 ln_apply(u32x4 x, u32x4 g, u32x4 b, floatx2 st)
+{
+    const half8 xh = __builtin_bit_cast(half8, x);
+    const half8 gh = __builtin_bit_cast(half8, g);
+    const half8 bh = __builtin_bit_cast(half8, b);
+    half8 y;
+#pragma unroll
+    for (int e = 0; e < kChunkK; ++e)
+        y[e] = (_Float16)(((float)xh[e] - st[0]) * st[1] * (float)gh[e] + (float)bh[e]);
+    return __builtin_bit_cast(u32x4, y);
+}
+
 // Staging of k-steps [cb, cb+cn) of X for all B rows into LDS.  Element order in LDS (16-byte
 // units): ((ks - cb)*4 + g)*B + b  holds X[b][ks*32 + g*8 .. +8], zero beyond K.
 // Two phases so that the global reads can be requested ahead of the weight stream's first
 // loads and written to LDS once they arrive: request() issues up to XU unconditional
 // 128-bit loads per thread (addresses clamped into the tensor), commit() writes them to LDS
 // and handles whatever did not fit (large B) or cannot be read as vectors (K % 8 != 0).
-template <int NT, int XU>
+// With LN the pieces are layer-normalised on their way into LDS (gamma and beta pieces
+// travel with the X pieces; `stats` holds the rows' statistics).
+template <int NT, int XU, bool LN>
 struct XStage {
     u32x4 buf[XU];
+    u32x4 gam[LN ? XU : 1];
+    u32x4 bet[LN ? XU : 1];
 
     __device__ __forceinline__ void request(const GemmParams& p, int cb, int cn, int tid)
     {
@@ -65,14 +143,18 @@ struct XStage {
             const int c = idx - b * nc;
             const int k = min(cb * kTileK + c * kChunkK, p.K - kChunkK);
             buf[u] = *reinterpret_cast<const u32x4*>(p.X + (int64_t)b * p.K + k);
+            if constexpr (LN) {        // unconditional: a problem without layer-norm gets valid dummy pointers
+                gam[u] = *reinterpret_cast<const u32x4*>(p.ln_gamma + k);
+                bet[u] = *reinterpret_cast<const u32x4*>(p.ln_beta + k);
+            }
         }
     }
 
-    __device__ __forceinline__ void commit(const GemmParams& p, u32x4* xs, int cb, int cn, int tid)
+    __device__ __forceinline__ void commit(const GemmParams& p, u32x4* xs, const floatx2* stats,
+                                           int cb, int cn, int tid)
     {
         const int nc = cn * 4;
         const int items = nc * p.B;
-        int done = 0;
         if (p.x_vec) {
 #pragma unroll
             for (int u = 0; u < XU; ++u) {
@@ -81,33 +163,48 @@ struct XStage {
                     const int b = idx / nc;
                     const int c = idx - b * nc;
                     const bool inside = cb * kTileK + c * kChunkK < p.K;
-                    xs[c * p.B + b] = inside ? buf[u] : u32x4{0u, 0u, 0u, 0u};
+                    u32x4 v = buf[u];
+                    if constexpr (LN) {
+                        const u32x4 y = ln_apply(v, gam[u], bet[u], stats[b]);
+                        v = p.ln ? y : v;
+                    }
+                    xs[c * p.B + b] = inside ? v : u32x4{0u, 0u, 0u, 0u};
                 }
+                if constexpr (LN) __builtin_amdgcn_sched_barrier(0);      // one piece at a time: few temporaries
             }
-            done = NT * XU;
-        }
-        if (p.x_vec) {
-            // what did not fit in the first pass: further passes of XU pieces per thread, all
-            // reads of a pass issued before its LDS writes (one memory latency per pass)
-            for (int base = done; base < items; base += NT * XU) {
-                u32x4 v[XU];
+            // what did not fit in the first pass: further passes of XF pieces per thread, all
+            // reads of a pass issued before its LDS writes (one memory latency per pass); fewer
+            // pieces per pass with layer-norm, whose gamma and beta pieces need registers too
+            constexpr int XF = LN ? XU / 2 : XU;
+            for (int base = NT * XU; base < items; base += NT * XF) {
+                u32x4 v[XF], g[LN ? XF : 1], bb[LN ? XF : 1];
 #pragma unroll
-                for (int u = 0; u < XU; ++u) {
+                for (int u = 0; u < XF; ++u) {
                     const int idx = min(base + tid + u * NT, items - 1);
                     const int b = idx / nc;
                     const int c = idx - b * nc;
                     const int k = min(cb * kTileK + c * kChunkK, p.K - kChunkK);
                     v[u] = *reinterpret_cast<const u32x4*>(p.X + (int64_t)b * p.K + k);
+                    if constexpr (LN) {
+                        g[u] = *reinterpret_cast<const u32x4*>(p.ln_gamma + k);
+                        bb[u] = *reinterpret_cast<const u32x4*>(p.ln_beta + k);
+                    }
                 }
 #pragma unroll
-                for (int u = 0; u < XU; ++u) {
+                for (int u = 0; u < XF; ++u) {
                     const int idx = base + tid + u * NT;
                     if (idx < items) {
                         const int b = idx / nc;
                         const int c = idx - b * nc;
                         const bool inside = cb * kTileK + c * kChunkK < p.K;
-                        xs[c * p.B + b] = inside ? v[u] : u32x4{0u, 0u, 0u, 0u};
+                        u32x4 w = v[u];
+                        if constexpr (LN) {
+                            const u32x4 y = ln_apply(w, g[u], bb[u], stats[b]);
+                            w = p.ln ? y : w;
+                        }
+                        xs[c * p.B + b] = inside ? w : u32x4{0u, 0u, 0u, 0u};
                     }
+                    if constexpr (LN) __builtin_amdgcn_sched_barrier(0);
                 }
             }
             return;
@@ -158,9 +255,10 @@ __device__ __forceinline__ void load_step(u32x4 (&slot)[kPanelTiles * PW], const
 // PW = panels per block (1 or 2): with two panels every wave streams both for the same
 // k-steps, so one X operand read from LDS feeds twice as many MFMAs and the X tile is staged
 // once for 128 columns - what larger batches need, where X traffic rivals the weight stream.
-template <int NW, int DEPTH, int PW, class Op>
-__device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op& op, int tid, int wave,
-                                             int lane, int panel, int64_t pstride, int ks0, int ks1)
+template <int NW, int DEPTH, int PW, bool LN, class Op>
+__device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, const floatx2* stats, Op& op,
+                                             int tid, int wave, int lane, int panel, int64_t pstride,
+                                             int ks0, int ks1)
 {
     constexpr int NT = NW * 64;
     constexpr int RS = NW * DEPTH;                                 // k-steps a block consumes per round
@@ -174,12 +272,12 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op&
     const int xbuf = p.kc * xblock;                                // 16-byte units per X buffer
 
     u32x4 ring[DEPTH][kPanelTiles * PW];
-    XStage<NT, 4> xst;                                             // covers NT*64 bytes of X per chunk without a second pass
+    XStage<NT, 4, LN> xst;                                         // covers NT*64 bytes of X per chunk without a second pass
     xst.request(p, ks0, min(nks, p.kc), tid);
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
         load_step<PW>(ring[d], wbase + (int64_t)min(d * NW + wave, nks - 1) * kStepUnits, pstride);
-    xst.commit(p, xs, ks0, min(nks, p.kc), tid);
+    xst.commit(p, xs, stats, ks0, min(nks, p.kc), tid);
     if (nchunks > 1) xst.request(p, ks0 + p.kc, min(nks - p.kc, p.kc), tid);
     __syncthreads();
 
@@ -198,7 +296,7 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op&
             rc = 0;
             ++c;
             u32x4* dst = xs + (c & 1) * xbuf;
-            xst.commit(p, dst, ks0 + c * p.kc, min(nks - c * p.kc, p.kc), tid);
+            xst.commit(p, dst, stats, ks0 + c * p.kc, min(nks - c * p.kc, p.kc), tid);
             __syncthreads();
             xc = dst - c * p.kc * xblock;
             if (c + 1 < nchunks) xst.request(p, ks0 + (c + 1) * p.kc, min(nks - (c + 1) * p.kc, p.kc), tid);

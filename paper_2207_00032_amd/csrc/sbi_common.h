@@ -58,6 +58,10 @@ struct GemmParams {
     int kc;                    // k-steps of X staged per chunk (multiple of waves*depth)
     int flags;                 // kEpi* bits
     int x_vec;                 // 1: X rows are 16-byte aligned and K % 8 == 0
+    int ln;                    // 1: layer-normalise the rows of X on their way into LDS
+    const _Float16* ln_gamma;  // [K]; in a launch of the layer-norm kernel variant always readable
+    const _Float16* ln_beta;   // [K]    (problems with ln == 0 point both at X)
+    float ln_eps;
 #ifdef SBI_TRACE
     unsigned long long* trace; // development builds: 4 timestamps per block
 #endif
@@ -100,7 +104,9 @@ struct SkParams {
 
 // launchers implemented in the kernel translation units; return hipError_t as int
 int launch_streamk(const SkParams& p, int waves, int depth, int grid, hipStream_t st);
-int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, size_t lds_bytes, hipStream_t st);
+int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, bool layernorm, size_t lds_bytes,
+                hipStream_t st);
+constexpr int kLnStatsBytes = 512;                   // LDS in front of the X tile: (mean, 1/std) per batch row
 int launch_stream(const GemmParams& p, int waves, int depth, size_t lds_bytes, hipStream_t st);
 int launch_layout(const void* W, int64_t K, int64_t N, void* out, hipStream_t st);
 int launch_unlayout(const void* Wl, int64_t K, int64_t N, void* out, hipStream_t st);

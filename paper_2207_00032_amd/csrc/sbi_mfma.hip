@@ -50,7 +50,9 @@ struct MfmaOp {
 // One launch may carry several independent GeMMs of the same batch size (the linear layers of
 // one transformer layer): their blocks are simply concatenated, so the ramp-up and the tail of
 // a launch are paid once per layer instead of once per GeMM.
-template <int MB, int NW, int DEPTH, int PW>
+// LN: the launch may contain problems whose X is layer-normalised on its way into LDS; the
+// first kLnStatsBytes of the dynamic LDS then hold the rows' statistics.
+template <int MB, int NW, int DEPTH, int PW, bool LN>
 __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
 {
     constexpr int NT = NW * 64;
@@ -59,7 +61,8 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
     const GemmParams& p = gp.g[gi];
     const int bid = (int)blockIdx.x - gp.first_block[gi];
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    u32x4* xs  = reinterpret_cast<u32x4*>(smem_raw);
+    u32x4* xs  = reinterpret_cast<u32x4*>(smem_raw + (LN ? kLnStatsBytes : 0));
+    floatx2* stats = reinterpret_cast<floatx2*>(smem_raw);
     float* red = reinterpret_cast<float*>(smem_raw);
     __shared__ int s_flag;
 
@@ -68,6 +71,13 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4;          // k group within a k-step (8 k each)
     const int i = lane & 15;          // column within a tile (A operand) / batch row (B operand)
+
+    if constexpr (LN) {
+        if (p.ln) {
+            ln_stats<NW>(p, stats, wave, lane);
+            __syncthreads();
+        }
+    }
 
     const int pgroup = bid / p.S;     // group of PW adjacent panels
     const int split = bid - pgroup * p.S;
@@ -83,7 +93,7 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
 #endif
     MfmaOp<MB, PW> op;
     op.init(p.B, g, i);
-    stream_panel<NW, DEPTH, PW>(p, xs, op, tid, wave, lane, panel, pstride, ks0, ks1);
+    stream_panel<NW, DEPTH, PW, LN>(p, xs, stats, op, tid, wave, lane, panel, pstride, ks0, ks1);
 #ifdef SBI_TRACE
     const unsigned long long t_stream = wall_clock64();
 #endif
@@ -115,44 +125,54 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
 #endif
 }
 
-template <int MB, int NW, int DEPTH, int PW>
+template <int MB, int NW, int DEPTH, int PW, bool LN>
 static int launch_one(const GroupParams& gp, size_t lds, hipStream_t st)
 {
     if (lds > 64 * 1024) {
         // more than the default 64 KiB of dynamic LDS has to be granted to the kernel first
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sbi_mfma_kernel<MB, NW, DEPTH, PW>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        const hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void*>(&sbi_mfma_kernel<MB, NW, DEPTH, PW, LN>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return (int)e;
     }
-    hipLaunchKernelGGL((sbi_mfma_kernel<MB, NW, DEPTH, PW>), dim3(gp.first_block[gp.G]), dim3(NW * 64), lds, st, gp);
+    hipLaunchKernelGGL((sbi_mfma_kernel<MB, NW, DEPTH, PW, LN>), dim3(gp.first_block[gp.G]), dim3(NW * 64), lds,
+                       st, gp);
     return (int)hipGetLastError();
 }
 
-template <int NW, int DEPTH, int PW>
+template <int NW, int DEPTH, int PW, bool LN>
 static int launch_mb(const GroupParams& gp, size_t lds, hipStream_t st)
 {
     switch ((gp.g[0].B + 15) / 16) {
-        case 1: return launch_one<1, NW, DEPTH, PW>(gp, lds, st);
-        case 2: return launch_one<2, NW, DEPTH, PW>(gp, lds, st);
-        case 3: return launch_one<3, NW, DEPTH, PW>(gp, lds, st);
-        case 4: return launch_one<4, NW, DEPTH, PW>(gp, lds, st);
+        case 1: return launch_one<1, NW, DEPTH, PW, LN>(gp, lds, st);
+        case 2: return launch_one<2, NW, DEPTH, PW, LN>(gp, lds, st);
+        case 3: return launch_one<3, NW, DEPTH, PW, LN>(gp, lds, st);
+        case 4: return launch_one<4, NW, DEPTH, PW, LN>(gp, lds, st);
     }
     return (int)hipErrorInvalidValue;
 }
 
-int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, size_t lds_bytes, hipStream_t st)
+int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, bool layernorm, size_t lds_bytes,
+                hipStream_t st)
 {
     if (gp.G < 1 || gp.G > kMaxGroup) return (int)hipErrorInvalidValue;
+    if (layernorm) {                   // layer-norm variants exist for the one-panel shapes the dispatcher uses
+        if (panels != 1) return (int)hipErrorInvalidValue;
+        if (waves == 4 && depth == 2) return launch_mb<4, 2, 1, true>(gp, lds_bytes, st);
+        if (waves == 4 && depth == 4) return launch_mb<4, 4, 1, true>(gp, lds_bytes, st);
+        if (waves == 8 && depth == 4) return launch_mb<8, 4, 1, true>(gp, lds_bytes, st);
+        return (int)hipErrorInvalidValue;
+    }
     if (panels == 1) {
-        if (waves == 4 && depth == 2) return launch_mb<4, 2, 1>(gp, lds_bytes, st);
-        if (waves == 4 && depth == 4) return launch_mb<4, 4, 1>(gp, lds_bytes, st);
-        if (waves == 4 && depth == 8) return launch_mb<4, 8, 1>(gp, lds_bytes, st);
-        if (waves == 8 && depth == 4) return launch_mb<8, 4, 1>(gp, lds_bytes, st);
-        if (waves == 8 && depth == 8) return launch_mb<8, 8, 1>(gp, lds_bytes, st);
+        if (waves == 4 && depth == 2) return launch_mb<4, 2, 1, false>(gp, lds_bytes, st);
+        if (waves == 4 && depth == 4) return launch_mb<4, 4, 1, false>(gp, lds_bytes, st);
+        if (waves == 4 && depth == 8) return launch_mb<4, 8, 1, false>(gp, lds_bytes, st);
+        if (waves == 8 && depth == 4) return launch_mb<8, 4, 1, false>(gp, lds_bytes, st);
+        if (waves == 8 && depth == 8) return launch_mb<8, 8, 1, false>(gp, lds_bytes, st);
     } else if (panels == 2) {
-        if (waves == 4 && depth == 2) return launch_mb<4, 2, 2>(gp, lds_bytes, st);
-        if (waves == 4 && depth == 4) return launch_mb<4, 4, 2>(gp, lds_bytes, st);
-        if (waves == 8 && depth == 2) return launch_mb<8, 2, 2>(gp, lds_bytes, st);
+        if (waves == 4 && depth == 2) return launch_mb<4, 2, 2, false>(gp, lds_bytes, st);
+        if (waves == 4 && depth == 4) return launch_mb<4, 4, 2, false>(gp, lds_bytes, st);
+        if (waves == 8 && depth == 2) return launch_mb<8, 2, 2, false>(gp, lds_bytes, st);
     }
     return (int)hipErrorInvalidValue;
 }

@@ -114,6 +114,25 @@ def make_gemm_inputs(K: int, N: int, B: int, seed: int = 0, config_id: int = 0, 
     return W, (bias if want_bias else None), X, (R if want_residual else None)
 
 
+def make_layernorm_inputs(K: int, B: int, seed: int = 0, config_id: int = 0, gemm_id: int = 0,
+                          row_shift: float = 0.5, row_scale: float = 2.0):
+    """Draw (gamma[K], beta[K], X[B,K]) as fp16 for a layer-norm in front of a GeMM.
+
+    gamma ~ 1 + 0.1 N(0,1), beta ~ 0.1 N(0,1) (trained layer-norm parameters stay close to their
+    initial 1 and 0).  X is the residual stream entering the norm: row b is
+    N(m_b, s_b^2) with m_b ~ row_shift * N(0,1) and s_b log-uniform in [1/row_scale, row_scale],
+    so rows differ in mean and spread.  Own generator stream (a fourth seed word), so the
+    draws of make_gemm_inputs for the same (seed, config, gemm) are unchanged.
+    """
+    rng = np.random.default_rng(np.random.SeedSequence([seed, config_id, gemm_id, 1]))
+    gamma = (1.0 + 0.1 * rng.standard_normal(K)).astype(np.float16)
+    beta = (0.1 * rng.standard_normal(K)).astype(np.float16)
+    m = row_shift * rng.standard_normal((B, 1))
+    sc = np.exp(rng.uniform(-np.log(row_scale), np.log(row_scale), size=(B, 1)))
+    X = (m + sc * rng.standard_normal((B, K))).astype(np.float16)
+    return gamma, beta, X
+
+
 def make_config_gemm(config_id: int, gemm_index: int, seed: int = 0, B: Optional[int] = None):
     """Inputs for one GeMM of a named configuration.
 

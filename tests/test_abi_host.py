@@ -176,6 +176,73 @@ def test_layer_argument_validation(lib):
     assert call(ctypes.byref(L4), 1, args) == 2
 
 
+def _gemm_ln(lib, gamma=FAKE + (5 << 30), beta=FAKE + (6 << 30), eps=1e-5, K=4096, N=4096, B=4, ln=True,
+             tune=None, ws_bytes=1 << 30):
+    lnp = ctypes.byref(sb.LayerNorm(gamma, beta, eps)) if ln else None
+    return lib.sbi_gemm_ln(FAKE, K, N, FAKE + (1 << 30), B, lnp, None, None, 0, FAKE + (2 << 30),
+                           FAKE + (3 << 30), ws_bytes, None, tune)
+
+
+def test_layernorm_argument_validation(lib):
+    assert _gemm_ln(lib, ln=False) == 1
+    assert _gemm_ln(lib, gamma=None) == 1 and _gemm_ln(lib, beta=None) == 1
+    assert _gemm_ln(lib, gamma=FAKE + 8) == 3 and _gemm_ln(lib, beta=FAKE + 2) == 3
+    assert _gemm_ln(lib, K=4100) == 2                              # rows must split into 128-bit pieces
+    assert _gemm_ln(lib, eps=-1.0) == 7 and _gemm_ln(lib, eps=float("nan")) == 7
+    assert _gemm_ln(lib, eps=float("inf")) == 7
+    for bad in (sb.Tuning(sb.PATH_STREAM, 0, 0, 0, 0, 0, 0), sb.Tuning(sb.PATH_STREAMK, 0, 0, 0, 0, 0, 0),
+                sb.Tuning(sb.PATH_MFMA, 0, 0, 0, 0, 2, 0), sb.Tuning(sb.PATH_MFMA, 0, 4, 8, 0, 0, 0),
+                sb.Tuning(sb.PATH_MFMA, 0, 8, 8, 0, 0, 0)):
+        assert _gemm_ln(lib, tune=ctypes.byref(bad)) == 10
+    need = sb.ln_workspace_bytes(4, 4096, 4096)
+    assert need == sb.plan(4, 4096, 4096, layernorm=True)["workspace_bytes"] > 0
+    assert _gemm_ln(lib, ws_bytes=need - 1) == 6
+    # the plain entry point has no layer-norm parameters and refuses the request
+    t = sb.Tuning(0, 0, 0, 0, 0, 0, 1)
+    assert lib.sbi_gemm_ex(FAKE, 4096, 4096, FAKE + (1 << 30), 4, None, None, 0, FAKE + (2 << 30),
+                           FAKE + (3 << 30), 1 << 30, None, ctypes.byref(t)) == 10
+
+
+@pytest.mark.parametrize("B", [1, 4, 8, 16, 33, 64])
+@pytest.mark.parametrize("K,N", [(8, 1), (1024, 3072), (4096, 12288), (4096, 16384), (12288, 4608), (1000, 130)])
+def test_layernorm_plan_invariants(B, K, N):
+    KS, P = 8 * -(-(-(-K // 32)) // 8), -(-N // 64)
+    pl = sb.plan(B, K, N, layernorm=True)
+    assert pl["path"] == sb.PATH_MFMA and pl["panels"] == 1
+    assert (pl["waves"], pl["depth"]) in ((4, 2), (4, 4), (8, 4))
+    S, ksps, kc = pl["split_k"], pl["ksteps_per_split"], pl["ksteps_per_chunk"]
+    assert 1 <= S <= KS and ksps * S >= KS and ksps * (S - 1) < KS and pl["grid"] == P * S
+    buffers = 1 if kc >= ksps else 2
+    assert 512 + buffers * kc * B * 64 <= pl["lds_bytes"] <= 128 * 1024    # statistics ahead of the X tile
+    with pytest.raises(sb.SbiError) as e:
+        sb.plan(B, K + 4, N, layernorm=True)
+    assert e.value.status == 10
+
+
+def test_layer_layernorm_validation(lib):
+    L = sb.Layer()
+    L.Wqkv = L.Wout = L.Wffn1 = L.Wffn2 = FAKE
+    L.h, L.n_qkv, L.k_out, L.n_ffn1, L.k_ffn2 = 1024, 3072, 1024, 4096, 4096
+    L.ln_eps = 1e-5
+    args = [FAKE + (i << 28) for i in range(1, 10)]
+    call = lambda layer: lib.sbi_layer_gemms(ctypes.byref(layer), 2, *args, FAKE, 1 << 30, None)
+    L.ln1_gamma = FAKE + (11 << 28)
+    assert call(L) == 1                                            # gamma without beta
+    L.ln1_beta = FAKE + (12 << 28) + 4
+    assert call(L) == 3
+    L.ln1_beta = FAKE + (12 << 28)
+    L.ln_eps = -1.0
+    assert call(L) == 7
+    L.ln_eps = 1e-5
+    L.ln2_beta = FAKE + (13 << 28)
+    assert call(L) == 1
+    L.ln2_beta = None
+    plans, grid = sb.layer_plan(L, 2, chained=True)
+    assert all(p["panels"] == 1 and p["lds_bytes"] >= 512 for p in plans)
+    L.h = 1028; L.k_out = 1028                                     # h % 8 != 0 cannot be layer-normalised
+    assert call(L) == 2
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(sb, "_lib", None)
     monkeypatch.setattr(sb, "LIB_PATH", str(tmp_path / "libsbi_gemm.so"))
