@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--graph", type=int, default=0, metavar="N",
                     help="capture N consecutive steps into one HIP graph and time replays of it "
                          "(removes host launch overhead; steps is rounded to a multiple of N)")
+    ap.add_argument("--layernorm", action="store_true",
+                    help="fuse a layer-norm in front of QKV and FFN1 (sbi_layer's ln1/ln2); also times the "
+                         "same layer with the two norms as separate torch kernels, for comparison")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run a few copy-kernel and layer launches and exit (for rocprofv3 --pmc runs)")
     return ap.parse_args()
@@ -48,7 +51,7 @@ def parse_args():
 def measured_traffic(args, batches):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE
     runs scaled against the copy kernel), if it covers exactly this workload; else None."""
-    if args.config != 2 or tuple(batches) != (1, 2, 4, 8) or args.path != "auto":
+    if args.config != 2 or tuple(batches) != (1, 2, 4, 8) or args.path != "auto" or args.layernorm:
         return None
     path = os.path.join(ROOT, "profiles", "sbi_mfma_kernel_config2_pmc_traffic.md")
     try:
@@ -88,6 +91,23 @@ def main():
     for gi, s in enumerate(specs):
         _, W, bias, X, R = wl.make_config_gemm(args.config, gi, seed=0, B=None)
         host.append((W, bias, X[:Bmax], R[:Bmax]))
+    LN_EPS = 1e-5
+    ln_host = None
+    if args.layernorm:
+        # A run of this mode ended in a GPU memory fault whose cause has not been found (the same
+        # launches pass the parity tests and run clean under AddressSanitizer in a CPU build), so
+        # the mode stays off the GPU until it is.
+        if os.environ.get("SBI_BENCH_LAYERNORM") != "cause-found":
+            print("bench.py: --layernorm is switched off (unexplained GPU memory fault in this mode)",
+                  file=sys.stderr)
+            sys.exit(2)
+        assert args.path == "auto", "--layernorm runs through sbi_layer_gemms"
+        # the inputs of QKV and FFN1 become residual-stream rows (own mean and spread per row)
+        ln_host = {gi: wl.make_layernorm_inputs(specs[gi].K, Bmax, seed=0, config_id=args.config, gemm_id=gi)
+                   for gi in (0, 2)}
+        for gi in (0, 2):
+            W, bias, _, R = host[gi]
+            host[gi] = (W, bias, ln_host[gi][2], R)
     use_bias = [s.epilogue in (wl.BIAS, wl.BIAS_GELU, wl.BIAS_RESIDUAL) for s in specs]
     use_res = specs[3].epilogue in (wl.BIAS_RESIDUAL, wl.RESIDUAL)
     gelu = specs[2].epilogue in (wl.BIAS_GELU, wl.GELU)
@@ -104,7 +124,15 @@ def main():
     layers = [sb.make_layer(*Wl[c], h_dim, specs[0].N, specs[1].K, specs[2].N, specs[3].K,
                             bqkv=bias_d[0], bout=bias_d[1], bffn1=bias_d[2], bffn2=bias_d[3], ffn1_gelu=gelu)
               for c in range(copies)]
+    plain_layers = layers
+    if args.layernorm:
+        ln_d = {gi: (torch.from_numpy(ln_host[gi][0]).to(dev), torch.from_numpy(ln_host[gi][1]).to(dev))
+                for gi in (0, 2)}
+        layers = [sb.make_layer(*Wl[c], h_dim, specs[0].N, specs[1].K, specs[2].N, specs[3].K,
+                                bqkv=bias_d[0], bout=bias_d[1], bffn1=bias_d[2], bffn2=bias_d[3], ffn1_gelu=gelu,
+                                ln1=ln_d[0], ln2=ln_d[2], ln_eps=LN_EPS) for c in range(copies)]
     ws = sb.new_workspace(max([sb.layer_workspace_bytes(layers[0], B) for B in batches] +
+                              [sb.layer_workspace_bytes(plain_layers[0], B) for B in batches] +
                               [sb.plan(B, s.K, s.N)["workspace_bytes"] for B in batches for s in specs]), dev)
     path = {"auto": sb.PATH_AUTO, "stream": sb.PATH_STREAM, "mfma": sb.PATH_MFMA,
             "streamk": sb.PATH_STREAMK}[args.path]
@@ -207,6 +235,21 @@ def main():
     for B in batches:
         timed_run("layer", B, sum(s.algorithmic_bytes(B) for s in specs), sum(s.flops(B) for s in specs),
                   lambda: launch_layer(B))
+    if args.layernorm:
+        # the unfused alternative: the two norms as kernels of their own (torch's), then the plain layer
+        Xn_d = {B: [torch.empty_like(X_d[B][0]), torch.empty_like(X_d[B][2])] for B in batches}
+
+        def launch_unfused(B):
+            x, y = X_d[B], Y_d[B]
+            c = next_copy()
+            for j, gi in enumerate((0, 2)):
+                Xn_d[B][j].copy_(torch.nn.functional.layer_norm(x[gi], (h_dim,), ln_d[gi][0], ln_d[gi][1], LN_EPS))
+            sb.layer_gemms(plain_layers[c], B, Xn_d[B][0], x[1], Xn_d[B][1], x[3], R_d[B],
+                           y[0], y[1], y[2], y[3], ws)
+
+        for B in batches:
+            timed_run("layer, norms as separate torch kernels", B, sum(s.algorithmic_bytes(B) for s in specs),
+                      sum(s.flops(B) for s in specs), lambda: launch_unfused(B))
     if args.per_gemm:
         for B in batches:
             for gi, s in enumerate(specs):
@@ -250,6 +293,8 @@ def main():
                 if gi == 3 and path == sb.PATH_AUTO:
                     xin = X[:B]      # sbi_layer_gemms was given FFN2's own input, not chained
                 c0 = time.perf_counter()
+                if args.layernorm and gi in (0, 2):
+                    xin = orc.layernorm(xin, ln_host[gi][0], ln_host[gi][1], LN_EPS)
                 want = orc.gemm(xin, W, bias, R[:B], epi=epi_map[s.epilogue])
                 t_cpu += time.perf_counter() - c0
                 cpu_bytes += s.algorithmic_bytes(B)
@@ -271,6 +316,7 @@ def main():
         "config": {"workload": f"config{args.config}:{cfg.name} four-GeMM layer, B in {list(batches)}, "
                                f"rotating over {copies} weight copies ({copies * layer_weight_bytes >> 20} MiB)",
                    "batches": list(batches), "weight_copies": copies, "dispatch": args.path,
+                   "fused_layernorm": bool(args.layernorm),
                    "graph_replay_steps": args.graph},
         "hbm_frac": round(value / HBM_PEAK_GBPS, 4),
         "us_per_gemm_mean": round(sec_per_step * 1e6 / (len(batches) * len(specs)), 2),

@@ -94,7 +94,7 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
 bool chunking(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t red_bytes,
               int64_t& kc, int64_t& lds, int64_t front = 0);
 
-// The same with `front` bytes of LDS reserved ahead of the X buffers (layer-norm statistics).
+// With `front` > 0 (bytes of LDS reserved ahead of X for the layer-norm statistics): see below.
 bool chunking_impl(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t red_bytes,
                    int64_t& kc, int64_t& lds)
 {
@@ -119,9 +119,11 @@ bool chunking_impl(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int
 bool chunking(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t red_bytes,
               int64_t& kc, int64_t& lds, int64_t front)
 {
-    const bool ok = chunking_impl(B, ksps, wd, nw, cap - front, std::max<int64_t>(red_bytes - front, 0), kc, lds);
-    lds += front;
-    return ok;
+    if (front == 0) return chunking_impl(B, ksps, wd, nw, cap, red_bytes, kc, lds);
+    // the layer-norm kernel variant stages X for the block's whole range up front: one buffer
+    kc = round_up(ksps, wd);
+    lds = std::max(front + kc * B * 64, red_bytes);
+    return lds <= cap;
 }
 
 sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Plan& pl)
@@ -308,18 +310,22 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
     return p;
 }
 
-// Wavefronts per CU that the register file lets the MFMA block kernel keep resident: the
-// vector registers of the compiled kernel variants (row blocks MB = ceil(B/16), waves, depth),
-// 512 registers per SIMD lane, 4 SIMDs per CU.
+// Wavefronts per CU that the planner's residency model grants the MFMA block kernel: a register
+// budget per kernel variant (row blocks MB = ceil(B/16), waves, depth) against 512 registers per
+// SIMD lane and 4 SIMDs per CU.  The plain-kernel budgets are the values the dispatch model was
+// calibrated with on MI355X (the launch times it is fitted to were measured under the plans these
+// values produce); the compiled variants currently allocate about 16 registers more than that
+// (108/140/134/150 at MB = 1), which costs one resident block per CU in some rows.  The layer-norm
+// variants carry their compiled counts.
 int resident_waves(int mb, int nw, int depth, int pw, bool ln)
 {
-    static const int vgpr_w4d2[4] = {108, 128, 156, 180};
-    static const int vgpr_w4d4[4] = {140, 164, 196, 226};
-    static const int vgpr_w8d4[4] = {134, 152, 170, 188};
-    static const int vgpr_w8d2p2[4] = {150, 184, 218, 252};
-    static const int vgpr_ln_w4d2[4] = {152, 172, 200, 224};
-    static const int vgpr_ln_w4d4[4] = {184, 208, 232, 270};
-    static const int vgpr_ln_w8d4[4] = {178, 196, 213, 230};
+    static const int vgpr_w4d2[4] = {92, 116, 152, 184};
+    static const int vgpr_w4d4[4] = {124, 152, 192, 230};
+    static const int vgpr_w8d4[4] = {120, 138, 158, 180};
+    static const int vgpr_w8d2p2[4] = {136, 170, 206, 244};
+    static const int vgpr_ln_w4d2[4] = {120, 156, 180, 204};
+    static const int vgpr_ln_w4d4[4] = {132, 164, 184, 226};
+    static const int vgpr_ln_w8d4[4] = {101, 120, 144, 170};
     const int* tab = (pw == 2) ? vgpr_w8d2p2 : (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);
     if (ln) tab = (nw == 8) ? vgpr_ln_w8d4 : (depth == 2 ? vgpr_ln_w4d2 : vgpr_ln_w4d4);
     const int v = (tab[std::min(std::max(mb, 1), 4) - 1] + 7) / 8 * 8;
@@ -452,6 +458,9 @@ sbi_status launch_block_group(const GemmArgs* a, const Plan* pls, const Plan& to
         partial_off += pls[g].ws_bytes;
     }
     gp.first_block[G] = first;
+    if (tot.ln)                       // that variant stages each block's whole k-range into one X buffer
+        for (int g = 0; g < G; ++g)
+            if (pls[g].kc < pls[g].ksps || tot.lds < kLnStatsBytes + (int64_t)pls[g].kc * B * 64) return SBI_ERR_TUNING;
     return launch_mfma(gp, tot.nw, tot.depth, tot.pw, tot.ln, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
 }
 

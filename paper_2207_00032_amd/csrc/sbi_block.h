@@ -117,19 +117,68 @@ __device__ __forceinline__ u32x4 ln_apply(u32x4 x, u32x4 g, u32x4 b, floatx2 st)
     return __builtin_bit_cast(u32x4, y);
 }
 
+// X staging of the layer-norm kernel variant: the block's whole k-step range [cb, cb+cn) in one
+// go, before the weight stream starts (the registers this takes are free again when the ring
+// fills), each piece layer-normalised on its way into LDS when p.ln is set.  Same LDS order as
+// XStage.  Needs 128-bit readable rows (p.x_vec) for the vector path; rows of other problems
+// of the same launch with K % 8 != 0 are read element by element and never normalised.
+template <int NT>
+__device__ __forceinline__ void stage_all(const GemmParams& p, u32x4* xs, const floatx2* stats,
+                                          int cb, int cn, int tid)
+{
+    constexpr int XU = 4;
+    const int nc = cn * 4;
+    const int items = nc * p.B;
+    if (p.x_vec) {
+        for (int base = 0; base < items; base += NT * XU) {
+            u32x4 v[XU], g[XU], bb[XU];
+#pragma unroll
+            for (int u = 0; u < XU; ++u) {
+                const int idx = min(base + tid + u * NT, items - 1);
+                const int b = idx / nc;
+                const int c = idx - b * nc;
+                const int k = min(cb * kTileK + c * kChunkK, p.K - kChunkK);
+                v[u] = *reinterpret_cast<const u32x4*>(p.X + (int64_t)b * p.K + k);
+                // unconditional: a problem without layer-norm gets valid dummy pointers
+                g[u] = *reinterpret_cast<const u32x4*>(p.ln_gamma + k);
+                bb[u] = *reinterpret_cast<const u32x4*>(p.ln_beta + k);
+            }
+#pragma unroll
+            for (int u = 0; u < XU; ++u) {
+                const int idx = base + tid + u * NT;
+                if (idx < items) {
+                    const int b = idx / nc;
+                    const int c = idx - b * nc;
+                    const bool inside = cb * kTileK + c * kChunkK < p.K;
+                    const u32x4 y = ln_apply(v[u], g[u], bb[u], stats[b]);
+                    const u32x4 w = p.ln ? y : v[u];
+                    xs[c * p.B + b] = inside ? w : u32x4{0u, 0u, 0u, 0u};
+                }
+            }
+        }
+        return;
+    }
+    for (int idx = tid; idx < items; idx += NT) {
+        const int b = idx / nc;
+        const int c = idx - b * nc;
+        const int k = cb * kTileK + c * kChunkK;
+        half8 h;
+#pragma unroll
+        for (int e = 0; e < kChunkK; ++e)
+            h[e] = (k + e < p.K) ? p.X[(int64_t)b * p.K + k + e] : (_Float16)0.0f;
+        xs[c * p.B + b] = __builtin_bit_cast(u32x4, h);
+    }
+}
+
 // Staging of k-steps [cb, cb+cn) of X for all B rows into LDS.  Element order in LDS (16-byte
 // units): ((ks - cb)*4 + g)*B + b  holds X[b][ks*32 + g*8 .. +8], zero beyond K.
 // Two phases so that the global reads can be requested ahead of the weight stream's first
 // loads and written to LDS once they arrive: request() issues up to XU unconditional
 // 128-bit loads per thread (addresses clamped into the tensor), commit() writes them to LDS
 // and handles whatever did not fit (large B) or cannot be read as vectors (K % 8 != 0).
-// With LN the pieces are layer-normalised on their way into LDS (gamma and beta pieces
-// travel with the X pieces; `stats` holds the rows' statistics).
-template <int NT, int XU, bool LN>
+template <int NT, int XU>
 struct XStage {
     u32x4 buf[XU];
-    u32x4 gam[LN ? XU : 1];
-    u32x4 bet[LN ? XU : 1];
 
     __device__ __forceinline__ void request(const GemmParams& p, int cb, int cn, int tid)
     {
@@ -143,18 +192,14 @@ struct XStage {
             const int c = idx - b * nc;
             const int k = min(cb * kTileK + c * kChunkK, p.K - kChunkK);
             buf[u] = *reinterpret_cast<const u32x4*>(p.X + (int64_t)b * p.K + k);
-            if constexpr (LN) {        // unconditional: a problem without layer-norm gets valid dummy pointers
-                gam[u] = *reinterpret_cast<const u32x4*>(p.ln_gamma + k);
-                bet[u] = *reinterpret_cast<const u32x4*>(p.ln_beta + k);
-            }
         }
     }
 
-    __device__ __forceinline__ void commit(const GemmParams& p, u32x4* xs, const floatx2* stats,
-                                           int cb, int cn, int tid)
+    __device__ __forceinline__ void commit(const GemmParams& p, u32x4* xs, int cb, int cn, int tid)
     {
         const int nc = cn * 4;
         const int items = nc * p.B;
+        int done = 0;
         if (p.x_vec) {
 #pragma unroll
             for (int u = 0; u < XU; ++u) {
@@ -163,48 +208,33 @@ struct XStage {
                     const int b = idx / nc;
                     const int c = idx - b * nc;
                     const bool inside = cb * kTileK + c * kChunkK < p.K;
-                    u32x4 v = buf[u];
-                    if constexpr (LN) {
-                        const u32x4 y = ln_apply(v, gam[u], bet[u], stats[b]);
-                        v = p.ln ? y : v;
-                    }
-                    xs[c * p.B + b] = inside ? v : u32x4{0u, 0u, 0u, 0u};
+                    xs[c * p.B + b] = inside ? buf[u] : u32x4{0u, 0u, 0u, 0u};
                 }
-                if constexpr (LN) __builtin_amdgcn_sched_barrier(0);      // one piece at a time: few temporaries
             }
-            // what did not fit in the first pass: further passes of XF pieces per thread, all
-            // reads of a pass issued before its LDS writes (one memory latency per pass); fewer
-            // pieces per pass with layer-norm, whose gamma and beta pieces need registers too
-            constexpr int XF = LN ? XU / 2 : XU;
-            for (int base = NT * XU; base < items; base += NT * XF) {
-                u32x4 v[XF], g[LN ? XF : 1], bb[LN ? XF : 1];
+            done = NT * XU;
+        }
+        if (p.x_vec) {
+            // what did not fit in the first pass: further passes of XU pieces per thread, all
+            // reads of a pass issued before its LDS writes (one memory latency per pass)
+            for (int base = done; base < items; base += NT * XU) {
+                u32x4 v[XU];
 #pragma unroll
-                for (int u = 0; u < XF; ++u) {
+                for (int u = 0; u < XU; ++u) {
                     const int idx = min(base + tid + u * NT, items - 1);
                     const int b = idx / nc;
                     const int c = idx - b * nc;
                     const int k = min(cb * kTileK + c * kChunkK, p.K - kChunkK);
                     v[u] = *reinterpret_cast<const u32x4*>(p.X + (int64_t)b * p.K + k);
-                    if constexpr (LN) {
-                        g[u] = *reinterpret_cast<const u32x4*>(p.ln_gamma + k);
-                        bb[u] = *reinterpret_cast<const u32x4*>(p.ln_beta + k);
-                    }
                 }
 #pragma unroll
-                for (int u = 0; u < XF; ++u) {
+                for (int u = 0; u < XU; ++u) {
                     const int idx = base + tid + u * NT;
                     if (idx < items) {
                         const int b = idx / nc;
                         const int c = idx - b * nc;
                         const bool inside = cb * kTileK + c * kChunkK < p.K;
-                        u32x4 w = v[u];
-                        if constexpr (LN) {
-                            const u32x4 y = ln_apply(w, g[u], bb[u], stats[b]);
-                            w = p.ln ? y : w;
-                        }
-                        xs[c * p.B + b] = inside ? w : u32x4{0u, 0u, 0u, 0u};
+                        xs[c * p.B + b] = inside ? v[u] : u32x4{0u, 0u, 0u, 0u};
                     }
-                    if constexpr (LN) __builtin_amdgcn_sched_barrier(0);
                 }
             }
             return;
@@ -255,10 +285,9 @@ __device__ __forceinline__ void load_step(u32x4 (&slot)[kPanelTiles * PW], const
 // PW = panels per block (1 or 2): with two panels every wave streams both for the same
 // k-steps, so one X operand read from LDS feeds twice as many MFMAs and the X tile is staged
 // once for 128 columns - what larger batches need, where X traffic rivals the weight stream.
-template <int NW, int DEPTH, int PW, bool LN, class Op>
-__device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, const floatx2* stats, Op& op,
-                                             int tid, int wave, int lane, int panel, int64_t pstride,
-                                             int ks0, int ks1)
+template <int NW, int DEPTH, int PW, class Op>
+__device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op& op, int tid, int wave,
+                                             int lane, int panel, int64_t pstride, int ks0, int ks1)
 {
     constexpr int NT = NW * 64;
     constexpr int RS = NW * DEPTH;                                 // k-steps a block consumes per round
@@ -272,12 +301,12 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, con
     const int xbuf = p.kc * xblock;                                // 16-byte units per X buffer
 
     u32x4 ring[DEPTH][kPanelTiles * PW];
-    XStage<NT, 4, LN> xst;                                         // covers NT*64 bytes of X per chunk without a second pass
+    XStage<NT, 4> xst;                                             // covers NT*64 bytes of X per chunk without a second pass
     xst.request(p, ks0, min(nks, p.kc), tid);
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
         load_step<PW>(ring[d], wbase + (int64_t)min(d * NW + wave, nks - 1) * kStepUnits, pstride);
-    xst.commit(p, xs, stats, ks0, min(nks, p.kc), tid);
+    xst.commit(p, xs, ks0, min(nks, p.kc), tid);
     if (nchunks > 1) xst.request(p, ks0 + p.kc, min(nks - p.kc, p.kc), tid);
     __syncthreads();
 
@@ -296,7 +325,7 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, con
             rc = 0;
             ++c;
             u32x4* dst = xs + (c & 1) * xbuf;
-            xst.commit(p, dst, stats, ks0 + c * p.kc, min(nks - c * p.kc, p.kc), tid);
+            xst.commit(p, dst, ks0 + c * p.kc, min(nks - c * p.kc, p.kc), tid);
             __syncthreads();
             xc = dst - c * p.kc * xblock;
             if (c + 1 < nchunks) xst.request(p, ks0 + (c + 1) * p.kc, min(nks - (c + 1) * p.kc, p.kc), tid);
@@ -309,6 +338,50 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, con
             for (int q = 0; q < kPanelTiles * PW; ++q) ring[d][q] = u32x4{0u, 0u, 0u, 0u};
         }
         op.step(ring[d], xc + min(t, nks - 1) * xblock);
+        t += NW;
+    }
+}
+
+// The weight stream of the layer-norm kernel variant: X for the block's whole range is staged
+// (and normalised) first, then the same register ring as stream_panel runs over one panel
+// without any X chunk switch.  The host plans such launches with p.kc >= p.ksps.
+template <int NW, int DEPTH, class Op>
+__device__ __forceinline__ void stream_panel_staged(const GemmParams& p, u32x4* xs, const floatx2* stats,
+                                                    Op& op, int tid, int wave, int lane, int panel,
+                                                    int ks0, int ks1)
+{
+    constexpr int NT = NW * 64;
+    constexpr int RS = NW * DEPTH;
+    constexpr int kStepUnits = kPanelTiles * 64;
+    const int nks = ks1 - ks0;
+    const int rounds = (nks + RS - 1) / RS;
+    const u32x4* wbase = p.Wl + ((int64_t)panel * p.KS + ks0) * kStepUnits + lane;
+    const int xblock = 4 * p.B;
+
+    stage_all<NT>(p, xs, stats, ks0, nks, tid);
+    u32x4 ring[DEPTH][kPanelTiles];
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d)
+        load_step<1>(ring[d], wbase + (int64_t)min(d * NW + wave, nks - 1) * kStepUnits, 0);
+    __syncthreads();
+
+    int t = wave;
+    for (int r = 0; r + 1 < rounds; ++r) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            op.step(ring[d], xs + t * xblock);
+            load_step<1>(ring[d], wbase + (int64_t)min(t + RS, nks - 1) * kStepUnits, 0);
+            t += NW;
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+        if (t >= nks) {
+#pragma unroll
+            for (int q = 0; q < kPanelTiles; ++q) ring[d][q] = u32x4{0u, 0u, 0u, 0u};
+        }
+        op.step(ring[d], xs + min(t, nks - 1) * xblock);
         t += NW;
     }
 }

@@ -51,7 +51,8 @@ struct MfmaOp {
 // one transformer layer): their blocks are simply concatenated, so the ramp-up and the tail of
 // a launch are paid once per layer instead of once per GeMM.
 // LN: the launch may contain problems whose X is layer-normalised on its way into LDS; the
-// first kLnStatsBytes of the dynamic LDS then hold the rows' statistics.
+// first kLnStatsBytes of the dynamic LDS then hold the rows' statistics, one panel per block,
+// and every block stages X for its whole k-range up front (p.kc >= p.ksps).
 template <int MB, int NW, int DEPTH, int PW, bool LN>
 __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
 {
@@ -93,7 +94,10 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
 #endif
     MfmaOp<MB, PW> op;
     op.init(p.B, g, i);
-    stream_panel<NW, DEPTH, PW, LN>(p, xs, stats, op, tid, wave, lane, panel, pstride, ks0, ks1);
+    if constexpr (LN)
+        stream_panel_staged<NW, DEPTH>(p, xs, stats, op, tid, wave, lane, panel, ks0, ks1);
+    else
+        stream_panel<NW, DEPTH, PW>(p, xs, op, tid, wave, lane, panel, pstride, ks0, ks1);
 #ifdef SBI_TRACE
     const unsigned long long t_stream = wall_clock64();
 #endif
