@@ -87,20 +87,16 @@ def main():
     copies = args.copies or max(3, -(-3 * 256 * 1000 * 1000 // layer_weight_bytes))
 
     # ---- seeded synthetic inputs (host), uploaded and laid out once ------------------------
+    # (drawn for the largest batch of THIS run: --batches may go beyond the configuration's own sweep)
     host = []
     for gi, s in enumerate(specs):
-        _, W, bias, X, R = wl.make_config_gemm(args.config, gi, seed=0, B=None)
-        host.append((W, bias, X[:Bmax], R[:Bmax]))
+        W, bias, X, R = wl.make_gemm_inputs(s.K, s.N, Bmax, 0, args.config, gi, cfg.outlier_channels,
+                                            cfg.outlier_scale)
+        assert X.shape == (Bmax, s.K) and R.shape == (Bmax, s.N)
+        host.append((W, bias, X, R))
     LN_EPS = 1e-5
     ln_host = None
     if args.layernorm:
-        # A run of this mode ended in a GPU memory fault whose cause has not been found (the same
-        # launches pass the parity tests and run clean under AddressSanitizer in a CPU build), so
-        # the mode stays off the GPU until it is.
-        if os.environ.get("SBI_BENCH_LAYERNORM") != "cause-found":
-            print("bench.py: --layernorm is switched off (unexplained GPU memory fault in this mode)",
-                  file=sys.stderr)
-            sys.exit(2)
         assert args.path == "auto", "--layernorm runs through sbi_layer_gemms"
         # the inputs of QKV and FFN1 become residual-stream rows (own mean and spread per row)
         ln_host = {gi: wl.make_layernorm_inputs(specs[gi].K, Bmax, seed=0, config_id=args.config, gemm_id=gi)

@@ -226,7 +226,8 @@ typedef struct sbi_layer {
  *   Yffn1 [B,n_ffn1]= act(LN2?(Xffn1[B,h]) . Wffn1 (+ bffn1))
  *   Yffn2 [B,h]     = Xffn2[B,k_ffn2] . Wffn2 (+ bffn2) (+ residual[B,h])
  * Xffn2 == NULL chains FFN1's output (requires n_ffn1 == k_ffn2).  residual may be NULL.
- * workspace_bytes >= sbi_layer_workspace_bytes(L, B).
+ * workspace_bytes >= sbi_layer_workspace_bytes(L, B) always suffices (a call checks against what
+ * its own launches need, which is never more).
  */
 sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
                            const void* Xqkv, const void* Xout, const void* Xffn1, const void* Xffn2,

@@ -137,6 +137,26 @@ def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
+def _need(t, shape, what):
+    """The C ABI takes bare pointers: make sure the tensor behind one really has the extent the call
+    will read or write (an undersized tensor would be a GPU memory fault, not an error code)."""
+    import torch
+    if t is None:
+        return
+    if not (t.is_cuda and t.dtype == torch.float16 and t.is_contiguous() and tuple(t.shape) == tuple(shape)):
+        raise ValueError(f"{what}: expected a contiguous CUDA fp16 tensor of shape {tuple(shape)}, got "
+                         f"{t.dtype} {tuple(t.shape)} on {t.device}")
+
+
+def _need_bytes(t, nbytes, what):
+    if t is None:
+        if nbytes:
+            raise ValueError(f"{what}: missing ({nbytes} bytes needed)")
+        return
+    if not t.is_cuda or not t.is_contiguous() or t.numel() * t.element_size() < nbytes:
+        raise ValueError(f"{what}: needs {nbytes} contiguous bytes on the GPU, has {t.numel() * t.element_size()}")
+
+
 def _stream():
     import torch
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
@@ -211,6 +231,14 @@ def gemm(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, wor
         epilogue = EPILOGUES[epilogue]
     if out is None:
         out = torch.empty((B, N), dtype=torch.float16, device=X.device)
+    _need(X, (B, K), "X")
+    _need(bias, (N,), "bias")
+    _need(residual, (B, N), "residual")
+    _need(out, (B, N), "out")
+    _need_bytes(Wl, layout_bytes(K, N), "laid-out weights")
+    if layernorm is not None:
+        _need(layernorm[0], (K,), "gamma")
+        _need(layernorm[1], (K,), "beta")
     tune = _tuning(path, split_k, waves, depth, blocks, panels)
     if workspace is None:
         if tune or layernorm is not None:
@@ -219,6 +247,8 @@ def gemm(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, wor
         else:
             need = workspace_bytes(B, K, N)
         workspace = new_workspace(need, X.device) if need else None
+    if workspace is not None:
+        _need_bytes(workspace, 0, "workspace")
     ws_ptr = _ptr(workspace)
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
     if layernorm is not None:
@@ -241,6 +271,15 @@ def gemm(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, wor
 def make_layer(Wqkv, Wout, Wffn1, Wffn2, h, n_qkv, k_out, n_ffn1, k_ffn2,
                bqkv=None, bout=None, bffn1=None, bffn2=None, ffn1_gelu=True, ln1=None, ln2=None, ln_eps=1e-5):
     """Fill an sbi_layer from laid-out weight tensors; keep the tensors alive yourself."""
+    for w, (K, N), name in ((Wqkv, (h, n_qkv), "Wqkv"), (Wout, (k_out, h), "Wout"),
+                            (Wffn1, (h, n_ffn1), "Wffn1"), (Wffn2, (k_ffn2, h), "Wffn2")):
+        _need_bytes(w, layout_bytes(K, N), name)
+    for b, N, name in ((bqkv, n_qkv, "bqkv"), (bout, h, "bout"), (bffn1, n_ffn1, "bffn1"), (bffn2, h, "bffn2")):
+        _need(b, (N,), name)
+    for ln, name in ((ln1, "ln1"), (ln2, "ln2")):
+        if ln is not None:
+            _need(ln[0], (h,), name + " gamma")
+            _need(ln[1], (h,), name + " beta")
     L = Layer()
     L.Wqkv, L.Wout, L.Wffn1, L.Wffn2 = (w.data_ptr() for w in (Wqkv, Wout, Wffn1, Wffn2))
     L.bqkv, L.bout, L.bffn1, L.bffn2 = (None if b is None else b.data_ptr() for b in (bqkv, bout, bffn1, bffn2))
@@ -268,6 +307,11 @@ def layer_plan(layer, B, chained=False):
 
 
 def layer_gemms(layer, B, Xqkv, Xout, Xffn1, Xffn2, residual, Yqkv, Yout, Yffn1, Yffn2, workspace):
+    for t, cols, name in ((Xqkv, layer.h, "Xqkv"), (Xout, layer.k_out, "Xout"), (Xffn1, layer.h, "Xffn1"),
+                          (Xffn2, layer.k_ffn2, "Xffn2"), (residual, layer.h, "residual"),
+                          (Yqkv, layer.n_qkv, "Yqkv"), (Yout, layer.h, "Yout"), (Yffn1, layer.n_ffn1, "Yffn1"),
+                          (Yffn2, layer.h, "Yffn2")):
+        _need(t, (B, cols), name)
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
     st = load().sbi_layer_gemms(ctypes.byref(layer), B, _ptr(Xqkv), _ptr(Xout), _ptr(Xffn1), _ptr(Xffn2),
                                 _ptr(residual), _ptr(Yqkv), _ptr(Yout), _ptr(Yffn1), _ptr(Yffn2),

@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstring>
 #ifdef SBI_TRACE
+#include <cstdio>
 #include <cstdlib>
 #endif
 
@@ -120,10 +121,11 @@ bool chunking(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t 
               int64_t& kc, int64_t& lds, int64_t front)
 {
     if (front == 0) return chunking_impl(B, ksps, wd, nw, cap, red_bytes, kc, lds);
-    // the layer-norm kernel variant stages X for the block's whole range up front: one buffer
-    kc = round_up(ksps, wd);
-    lds = std::max(front + kc * B * 64, red_bytes);
-    return lds <= cap;
+    // layer-norm kernel variant: the statistics take `front` bytes ahead of the X buffers, and
+    // every buffer carries its k-steps of gamma and beta as two more rows
+    const bool ok = chunking_impl(B + 2, ksps, wd, nw, cap - front, std::max<int64_t>(red_bytes - front, 0), kc, lds);
+    lds += front;
+    return ok;
 }
 
 sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Plan& pl)
@@ -310,22 +312,18 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
     return p;
 }
 
-// Wavefronts per CU that the planner's residency model grants the MFMA block kernel: a register
-// budget per kernel variant (row blocks MB = ceil(B/16), waves, depth) against 512 registers per
-// SIMD lane and 4 SIMDs per CU.  The plain-kernel budgets are the values the dispatch model was
-// calibrated with on MI355X (the launch times it is fitted to were measured under the plans these
-// values produce); the compiled variants currently allocate about 16 registers more than that
-// (108/140/134/150 at MB = 1), which costs one resident block per CU in some rows.  The layer-norm
-// variants carry their compiled counts.
+// Wavefronts per CU that the register file lets the MFMA block kernel keep resident: the vector
+// registers the compiled kernel variants allocate (row blocks MB = ceil(B/16), waves, depth; plain
+// and layer-norm), in granules of 8, against 512 registers per SIMD lane and 4 SIMDs per CU.
 int resident_waves(int mb, int nw, int depth, int pw, bool ln)
 {
-    static const int vgpr_w4d2[4] = {92, 116, 152, 184};
-    static const int vgpr_w4d4[4] = {124, 152, 192, 230};
-    static const int vgpr_w8d4[4] = {120, 138, 158, 180};
-    static const int vgpr_w8d2p2[4] = {136, 170, 206, 244};
-    static const int vgpr_ln_w4d2[4] = {120, 156, 180, 204};
-    static const int vgpr_ln_w4d4[4] = {132, 164, 184, 226};
-    static const int vgpr_ln_w8d4[4] = {101, 120, 144, 170};
+    static const int vgpr_w4d2[4] = {108, 128, 156, 180};
+    static const int vgpr_w4d4[4] = {140, 164, 196, 226};
+    static const int vgpr_w8d4[4] = {134, 152, 170, 188};
+    static const int vgpr_w8d2p2[4] = {150, 184, 218, 252};
+    static const int vgpr_ln_w4d2[4] = {120, 140, 164, 212};
+    static const int vgpr_ln_w4d4[4] = {144, 168, 196, 224};
+    static const int vgpr_ln_w8d4[4] = {138, 160, 180, 204};
     const int* tab = (pw == 2) ? vgpr_w8d2p2 : (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);
     if (ln) tab = (nw == 8) ? vgpr_ln_w8d4 : (depth == 2 ? vgpr_ln_w4d2 : vgpr_ln_w4d4);
     const int v = (tab[std::min(std::max(mb, 1), 4) - 1] + 7) / 8 * 8;
@@ -334,11 +332,11 @@ int resident_waves(int mb, int nw, int depth, int pw, bool ln)
 
 // Plans for `G` GeMMs that go out as one launch of the block kernel.  A common block size T
 // (k-steps) gives all blocks of the launch about the same work; problem g is split
-// S_g = ceil(KS_g / T) ways.  Measured on MI355X: the launch is fastest when ALL its blocks
-// are resident at once (a second dispatch round lands unevenly on the CUs), so candidates are
-// ranked by  rounds x blocks-per-CU x block time, where the blocks a CU can hold follow from
-// the LDS each block needs for its X chunk and from the register file.  Returns per-problem
-// plans plus the launch totals in `tot` (nw, depth, lds, grid, ws_bytes).
+// S_g = ceil(KS_g / T) ways.  Candidates (block shape, LDS budget, T) are ranked by a model of
+// the busiest CU: blocks it works through x (stream + per-block overhead), where the blocks a
+// CU can hold at once follow from the LDS each block needs for its X chunks and from the
+// register file.  Returns per-problem plans plus the launch totals in `tot` (nw, depth, lds,
+// grid, ws_bytes).
 sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot, bool ln)
 {
     if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
@@ -368,8 +366,13 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
             // the wide budget belongs to two-panel blocks, and to layer-norm blocks (their statistics
             // take the room that a batch of 64 needs for two X buffers within 64 KiB)
             if ((cap > kMaxLds) != (pw == 2) && !(ln && cap > kMaxLds)) continue;
-            for (int64_t T = wd; T < maxKS + wd; T += wd) {
-                int64_t blocks = 0, maxk = 0, lds = red_bytes, chunks = 1;
+            // block sizes worth a look: the ones at which the split of the longest problem changes
+            int64_t lastT = 0;
+            for (int64_t smax = std::min<int64_t>(ceil_div(maxKS, wd), 64); smax >= 1; --smax) {
+                const int64_t T = round_up(ceil_div(maxKS, smax), wd);
+                if (T == lastT) continue;
+                lastT = T;
+                int64_t blocks = 0, work = 0, lds = red_bytes, chunks = 1;
                 double partial = 0.0;
                 bool ok = true, slow_stage = false;   // slow: a chunk needs a second staging pass
                 for (int g = 0; g < G && ok; ++g) {
@@ -379,28 +382,34 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
                     ok = chunking(B, ksps, wd, nw, cap, red_bytes, kc, l, front);
                     if (!ok) break;
                     blocks += ceil_div(P[g], pw) * S;
-                    maxk = std::max(maxk, ksps * pw);
+                    work += ceil_div(P[g], pw) * S * ksps * pw;
                     lds = std::max(lds, l);
                     chunks = std::max(chunks, ceil_div(ksps, kc));
-                    if (ceil_div(ksps, kc) > 1 && kc * B * 64 > (int64_t)nw * 64 * 64) slow_stage = true;
+                    if (ceil_div(ksps, kc) > 1 && kc * (B + (ln ? 2 : 0)) * 64 > (int64_t)nw * 64 * 64) slow_stage = true;
                     if (S > 1) partial += (double)(P[g] * S) * (double)B * 512.0;
                 }
                 if (!ok) continue;
                 const int64_t fit = std::max<int64_t>(1, std::min<int64_t>(kLdsPerCU / lds,
                                                                            resident_waves(mb, nw, depth, pw, ln) / nw));
-                const int64_t per_cu = std::min<int64_t>(fit, ceil_div(blocks, kNumCU));   // concurrent blocks on a CU
-                const int64_t rounds = ceil_div(blocks, (int64_t)kNumCU * fit);
+                // A CU time-slices its share of HBM bandwidth over the blocks it holds, so what counts is
+                // how many blocks the busiest CU works through (quantised), each costing its stream plus
+                // a start/finish overhead; measured on MI355X (h=4096 layer, 512 MiB single GeMMs):
+                //   overhead about 9 k-steps of streaming time per block, 4.5 more when a block has the
+                //   CU to itself (nothing hides its ramp-up and epilogue), next to nothing per further
+                //   X chunk, about 4 per pass of the layer-norm statistics (16 when nothing hides it);
+                //   X staged per block rivals the weight stream once B/(64 pw) exceeds about 0.2;
+                //   fewer than 24 k-steps in flight per CU no longer cover the memory latency.
+                const int64_t per_cu_blocks = ceil_div(blocks, kNumCU);
+                const int64_t conc = std::min<int64_t>(fit, per_cu_blocks);              // concurrent blocks on a CU
                 const double busy = (double)std::min<int64_t>(blocks, kNumCU) / kNumCU;
-                // every block: ramp-up, reduction, epilogue (about 20 k-steps of streaming time);
-                // every further X chunk costs a barrier (about 1)
-                // X staged per block rivals the weight stream once B/(64 pw) exceeds about 0.2
                 const double x_ratio = (double)B / (64.0 * pw);
-                const double block_time = (double)maxk * (1.0 + 0.6 * std::max(0.0, x_ratio - 0.2)) + 20.0 +
-                                          1.0 * (double)(chunks - 1);
-                double cost = (double)rounds * (double)per_cu * block_time * (busy >= 0.75 ? 1.0 : 0.75 / busy) +
+                const double stream = (double)work / (double)blocks * (1.0 + 0.6 * std::max(0.0, x_ratio - 0.2));
+                double overhead = 9.0 + 0.15 * (double)(chunks - 1) + (conc == 1 ? 4.5 : 0.0);
+                if (ln) overhead += (conc == 1 ? 16.0 : 4.0) * (double)(ceil_div(B, 2 * nw) * ceil_div(maxKS, 128));
+                double cost = (double)per_cu_blocks * (stream + overhead) * (busy >= 0.75 ? 1.0 : 0.75 / busy) +
                               partial / kNumCU / 4096.0;
-                if ((int64_t)per_cu * nw < 8) cost *= 1.3;        // too few wavefronts to keep HBM busy
-                if (depth < 4) cost *= 1.1;                       // a shallow ring hides less latency
+                const int64_t inflight = conc * nw * depth;
+                if (inflight < 24) cost *= 1.0 + 0.3 * (double)(24 - inflight) / 24.0;
                 if (slow_stage) cost *= 1.1;
                 if (best_nw == 0 || cost < best) {
                     best = cost; best_nw = nw; best_depth = depth; best_pw = pw; bestT = T; best_cap = cap;
@@ -408,6 +417,21 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
             }
         }
     }
+#ifdef SBI_DEV
+    // development builds: SBI_PLAN_FORCE="waves,depth,panels,T,lds_cap" replaces the search
+    if (const char* f = getenv("SBI_PLAN_FORCE")) {
+        int a = 0, b = 0, c = 0;
+        long long t = 0, cap = 0;
+        if (sscanf(f, "%d,%d,%d,%lld,%lld", &a, &b, &c, &t, &cap) == 5) {
+            best_nw = a; best_depth = b; best_pw = c; bestT = t; best_cap = cap;
+            for (int g = 0; g < G; ++g) {
+                const int64_t S = ceil_div(KS[g], bestT), ksps = ceil_div(KS[g], S);
+                int64_t kc = 0, l = 0;
+                if (!chunking(B, ksps, (int64_t)a * b, a, cap, (int64_t)a * 16 * kRedPitch * 4, kc, l, front)) return SBI_ERR_TUNING;
+            }
+        }
+    }
+#endif
     if (best_nw == 0) return SBI_ERR_SHAPE;
     const int nw = best_nw, depth = best_depth, pw = best_pw;
     const int64_t wd = (int64_t)nw * depth;
@@ -458,9 +482,11 @@ sbi_status launch_block_group(const GemmArgs* a, const Plan* pls, const Plan& to
         partial_off += pls[g].ws_bytes;
     }
     gp.first_block[G] = first;
-    if (tot.ln)                       // that variant stages each block's whole k-range into one X buffer
-        for (int g = 0; g < G; ++g)
-            if (pls[g].kc < pls[g].ksps || tot.lds < kLnStatsBytes + (int64_t)pls[g].kc * B * 64) return SBI_ERR_TUNING;
+    if (tot.ln)                       // statistics, then per X buffer B rows plus gamma and beta
+        for (int g = 0; g < G; ++g) {
+            const int64_t buffers = pls[g].kc >= pls[g].ksps ? 1 : 2;
+            if (tot.lds < kLnStatsBytes + buffers * pls[g].kc * (B + 2) * 64) return SBI_ERR_TUNING;
+        }
     return launch_mfma(gp, tot.nw, tot.depth, tot.pw, tot.ln, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
 }
 
@@ -664,7 +690,16 @@ sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
         if (L->n_ffn1 != L->k_ffn2) return SBI_ERR_SHAPE;
         Xffn2 = Yffn1;
     }
-    const size_t need = sbi_layer_workspace_bytes(L, B);
+    // what THIS call needs (never more than sbi_layer_workspace_bytes, which covers both forms)
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int count = chained ? 3 : 4;
+    Plan pls[4], tot, last;
+    if (sbi_status s = layer_group_plan(L, B, count, pls, tot)) return s;
+    size_t need = (size_t)tot.ws_bytes;
+    if (chained) {
+        if (sbi_status s = make_plan(B, L->k_ffn2, L->h, nullptr, last)) return s;
+        need = std::max(need, (size_t)last.ws_bytes);
+    }
     if (workspace_bytes < need || (need > 0 && !workspace)) return SBI_ERR_WORKSPACE;
     if (need > 0 && !aligned(workspace, 256)) return SBI_ERR_ALIGN;
 
@@ -686,14 +721,11 @@ sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
                                            (int)epis[g], a[g].Y, a[g].flags)) return s;
 
     // one launch for the independent GeMMs; a chained FFN2 needs FFN1's output and follows
-    hipStream_t st = (hipStream_t)hip_stream;
-    const int count = chained ? 3 : 4;
-    Plan pls[4], tot;
-    if (sbi_status s = layer_group_plan(L, B, count, pls, tot)) return s;
     if (sbi_status s = launch_block_group(a, pls, tot, count, B, workspace, st)) return s;
     if (!chained) return SBI_OK;
-    return sbi_gemm(L->Wffn2, L->k_ffn2, L->h, Xffn2, B, L->bffn2, residual, e2, Yffn2,
-                    workspace, workspace_bytes, hip_stream);
+    Plan one = last;
+    one.ws_bytes = (last.S > 1) ? last.ws_bytes - last.counter_bytes : 0;
+    return launch_block_group(&a[3], &one, last, 1, B, workspace, st);
 }
 
 const char* sbi_status_string(sbi_status s)

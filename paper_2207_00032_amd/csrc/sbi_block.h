@@ -56,118 +56,91 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// Sum of the 8 halfs of a piece, and of their squared distances from `mean`, in fp32.
+__device__ __forceinline__ float piece_sum(u32x4 h)
+{
+    const half8 v = __builtin_bit_cast(half8, h);
+    float t = 0.f;
+#pragma unroll
+    for (int e = 0; e < kChunkK; ++e) t += (float)v[e];
+    return t;
+}
+__device__ __forceinline__ float piece_sqdev(u32x4 h, float mean)
+{
+    const half8 v = __builtin_bit_cast(half8, h);
+    float t = 0.f;
+#pragma unroll
+    for (int e = 0; e < kChunkK; ++e) {
+        const float d = (float)v[e] - mean;
+        t += d * d;
+    }
+    return t;
+}
+
+// R rows per wave at a time (rows r, r + NW, ...), so that their loads share one memory latency.
 template <int NW>
 __device__ __forceinline__ void ln_stats(const GemmParams& p, floatx2* stats, int wave, int lane)
 {
-    constexpr int U = 8;                       // 128-bit loads in flight per lane: 4096 elements of a row
+    constexpr int U = 8;                       // 128-bit loads in flight per lane and row: 4096 elements
+    constexpr int R = 2;
     const int pieces = p.K / kChunkK;
-    const bool resident = pieces <= 64 * U;    // the whole row stays in registers for the second pass
-    for (int r = wave; r < p.B; r += NW) {
-        const _Float16* row = p.X + (int64_t)r * p.K;
-        u32x4 h[U];
-        float s = 0.f;
+    const bool resident = pieces <= 64 * U;    // whole rows stay in registers for the second pass
+    for (int r0 = wave; r0 < p.B; r0 += R * NW) {
+        const _Float16* row[R];
+#pragma unroll
+        for (int j = 0; j < R; ++j) row[j] = p.X + (int64_t)min(r0 + j * NW, p.B - 1) * p.K;
+        u32x4 h[R][U];
+        float s[R], q[R], mean[R];
+#pragma unroll
+        for (int j = 0; j < R; ++j) s[j] = q[j] = 0.f;
         for (int c0 = 0; c0 < pieces; c0 += 64 * U) {
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                h[u] = *reinterpret_cast<const u32x4*>(row + min(c0 + u * 64 + lane, pieces - 1) * kChunkK);
+            for (int u = 0; u < U; ++u) {
+                const int c = min(c0 + u * 64 + lane, pieces - 1) * kChunkK;
+#pragma unroll
+                for (int j = 0; j < R; ++j) h[j][u] = *reinterpret_cast<const u32x4*>(row[j] + c);
+            }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const half8 v = __builtin_bit_cast(half8, h[u]);
-                float t = 0.f;
+                const bool in = c0 + u * 64 + lane < pieces;
 #pragma unroll
-                for (int e = 0; e < kChunkK; ++e) t += (float)v[e];
-                s += (c0 + u * 64 + lane < pieces) ? t : 0.f;
+                for (int j = 0; j < R; ++j) s[j] += in ? piece_sum(h[j][u]) : 0.f;
             }
         }
-        const float mean = wave_sum(s) / (float)p.K;
-        float q = 0.f;
+#pragma unroll
+        for (int j = 0; j < R; ++j) mean[j] = wave_sum(s[j]) / (float)p.K;
         for (int c0 = 0; c0 < pieces; c0 += 64 * U) {
             if (!resident) {
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    h[u] = *reinterpret_cast<const u32x4*>(row + min(c0 + u * 64 + lane, pieces - 1) * kChunkK);
+                for (int u = 0; u < U; ++u) {
+                    const int c = min(c0 + u * 64 + lane, pieces - 1) * kChunkK;
+#pragma unroll
+                    for (int j = 0; j < R; ++j) h[j][u] = *reinterpret_cast<const u32x4*>(row[j] + c);
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const half8 v = __builtin_bit_cast(half8, h[u]);
-                float t = 0.f;
+                const bool in = c0 + u * 64 + lane < pieces;
 #pragma unroll
-                for (int e = 0; e < kChunkK; ++e) {
-                    const float d = (float)v[e] - mean;
-                    t += d * d;
-                }
-                q += (c0 + u * 64 + lane < pieces) ? t : 0.f;
+                for (int j = 0; j < R; ++j) q[j] += in ? piece_sqdev(h[j][u], mean[j]) : 0.f;
             }
         }
-        const float var = wave_sum(q) / (float)p.K;
-        if (lane == 0) stats[r] = floatx2{mean, 1.0f / sqrtf(var + p.ln_eps)};
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const float var = wave_sum(q[j]) / (float)p.K;
+            if (lane == 0 && r0 + j * NW < p.B) stats[r0 + j * NW] = floatx2{mean[j], 1.0f / sqrtf(var + p.ln_eps)};
+        }
     }
 }
 
 // y = (x - mean) * rstd * gamma + beta on 8 halfs, computed in fp32, rounded once to fp16.
-__device__ __forceinline__ u32x4 ln_apply(u32x4 x, u32x4 g, u32x4 b, floatx2 st)
+__device__ __forceinline__ half8 ln_apply(half8 xh, half8 gh, half8 bh, floatx2 st)
 {
-    const half8 xh = __builtin_bit_cast(half8, x);
-    const half8 gh = __builtin_bit_cast(half8, g);
-    const half8 bh = __builtin_bit_cast(half8, b);
     half8 y;
 #pragma unroll
     for (int e = 0; e < kChunkK; ++e)
         y[e] = (_Float16)(((float)xh[e] - st[0]) * st[1] * (float)gh[e] + (float)bh[e]);
-    return __builtin_bit_cast(u32x4, y);
-}
-
-// X staging of the layer-norm kernel variant: the block's whole k-step range [cb, cb+cn) in one
-// go, before the weight stream starts (the registers this takes are free again when the ring
-// fills), each piece layer-normalised on its way into LDS when p.ln is set.  Same LDS order as
-// XStage.  Needs 128-bit readable rows (p.x_vec) for the vector path; rows of other problems
-// of the same launch with K % 8 != 0 are read element by element and never normalised.
-template <int NT>
-__device__ __forceinline__ void stage_all(const GemmParams& p, u32x4* xs, const floatx2* stats,
-                                          int cb, int cn, int tid)
-{
-    constexpr int XU = 4;
-    const int nc = cn * 4;
-    const int items = nc * p.B;
-    if (p.x_vec) {
-        for (int base = 0; base < items; base += NT * XU) {
-            u32x4 v[XU], g[XU], bb[XU];
-#pragma unroll
-            for (int u = 0; u < XU; ++u) {
-                const int idx = min(base + tid + u * NT, items - 1);
-                const int b = idx / nc;
-                const int c = idx - b * nc;
-                const int k = min(cb * kTileK + c * kChunkK, p.K - kChunkK);
-                v[u] = *reinterpret_cast<const u32x4*>(p.X + (int64_t)b * p.K + k);
-                // unconditional: a problem without layer-norm gets valid dummy pointers
-                g[u] = *reinterpret_cast<const u32x4*>(p.ln_gamma + k);
-                bb[u] = *reinterpret_cast<const u32x4*>(p.ln_beta + k);
-            }
-#pragma unroll
-            for (int u = 0; u < XU; ++u) {
-                const int idx = base + tid + u * NT;
-                if (idx < items) {
-                    const int b = idx / nc;
-                    const int c = idx - b * nc;
-                    const bool inside = cb * kTileK + c * kChunkK < p.K;
-                    const u32x4 y = ln_apply(v[u], g[u], bb[u], stats[b]);
-                    const u32x4 w = p.ln ? y : v[u];
-                    xs[c * p.B + b] = inside ? w : u32x4{0u, 0u, 0u, 0u};
-                }
-            }
-        }
-        return;
-    }
-    for (int idx = tid; idx < items; idx += NT) {
-        const int b = idx / nc;
-        const int c = idx - b * nc;
-        const int k = cb * kTileK + c * kChunkK;
-        half8 h;
-#pragma unroll
-        for (int e = 0; e < kChunkK; ++e)
-            h[e] = (k + e < p.K) ? p.X[(int64_t)b * p.K + k + e] : (_Float16)0.0f;
-        xs[c * p.B + b] = __builtin_bit_cast(u32x4, h);
-    }
+    return y;
 }
 
 // Staging of k-steps [cb, cb+cn) of X for all B rows into LDS.  Element order in LDS (16-byte
@@ -176,30 +149,52 @@ __device__ __forceinline__ void stage_all(const GemmParams& p, u32x4* xs, const 
 // loads and written to LDS once they arrive: request() issues up to XU unconditional
 // 128-bit loads per thread (addresses clamped into the tensor), commit() writes them to LDS
 // and handles whatever did not fit (large B) or cannot be read as vectors (K % 8 != 0).
-template <int NT, int XU>
+// LN (layer-norm kernel variant) and p.ln set: X is staged raw, and the same k-steps of gamma
+// and beta travel along as two further "rows", stored after the X chunk (which always occupies
+// p.kc k-steps): gamma piece (ks, g) at p.kc*4*B + (ks - cb)*4 + g, beta p.kc*4 pieces later.
+// The normalisation itself happens where the operand is read (see MfmaOp).
+template <int NT, int XU, bool LN>
 struct XStage {
     u32x4 buf[XU];
+
+    static __device__ __forceinline__ int rows(const GemmParams& p) { return p.B + ((LN && p.ln) ? 2 : 0); }
+
+    // source of piece c of staging row b (rows B and B+1 are gamma and beta)
+    static __device__ __forceinline__ const _Float16* src(const GemmParams& p, int b, int k)
+    {
+        const _Float16* base = p.X + (int64_t)b * p.K;
+        if constexpr (LN) {
+            base = (b == p.B) ? p.ln_gamma : base;
+            base = (b > p.B) ? p.ln_beta : base;
+        }
+        return base + k;
+    }
+    static __device__ __forceinline__ int dst(const GemmParams& p, int b, int c)
+    {
+        int d = c * p.B + b;
+        if constexpr (LN) d = (b >= p.B) ? p.kc * 4 * p.B + (b - p.B) * p.kc * 4 + c : d;
+        return d;
+    }
 
     __device__ __forceinline__ void request(const GemmParams& p, int cb, int cn, int tid)
     {
         if (!p.x_vec) return;
         const int nc = cn * 4;             // 16-byte pieces per row
-        const int items = nc * p.B;
+        const int items = nc * rows(p);
 #pragma unroll
         for (int u = 0; u < XU; ++u) {
             const int idx = min(tid + u * NT, items - 1);
             const int b = idx / nc;
             const int c = idx - b * nc;
             const int k = min(cb * kTileK + c * kChunkK, p.K - kChunkK);
-            buf[u] = *reinterpret_cast<const u32x4*>(p.X + (int64_t)b * p.K + k);
+            buf[u] = *reinterpret_cast<const u32x4*>(src(p, b, k));
         }
     }
 
     __device__ __forceinline__ void commit(const GemmParams& p, u32x4* xs, int cb, int cn, int tid)
     {
         const int nc = cn * 4;
-        const int items = nc * p.B;
-        int done = 0;
+        const int items = nc * rows(p);
         if (p.x_vec) {
 #pragma unroll
             for (int u = 0; u < XU; ++u) {
@@ -208,15 +203,12 @@ struct XStage {
                     const int b = idx / nc;
                     const int c = idx - b * nc;
                     const bool inside = cb * kTileK + c * kChunkK < p.K;
-                    xs[c * p.B + b] = inside ? buf[u] : u32x4{0u, 0u, 0u, 0u};
+                    xs[dst(p, b, c)] = inside ? buf[u] : u32x4{0u, 0u, 0u, 0u};
                 }
             }
-            done = NT * XU;
-        }
-        if (p.x_vec) {
             // what did not fit in the first pass: further passes of XU pieces per thread, all
             // reads of a pass issued before its LDS writes (one memory latency per pass)
-            for (int base = done; base < items; base += NT * XU) {
+            for (int base = NT * XU; base < items; base += NT * XU) {
                 u32x4 v[XU];
 #pragma unroll
                 for (int u = 0; u < XU; ++u) {
@@ -224,7 +216,7 @@ struct XStage {
                     const int b = idx / nc;
                     const int c = idx - b * nc;
                     const int k = min(cb * kTileK + c * kChunkK, p.K - kChunkK);
-                    v[u] = *reinterpret_cast<const u32x4*>(p.X + (int64_t)b * p.K + k);
+                    v[u] = *reinterpret_cast<const u32x4*>(src(p, b, k));
                 }
 #pragma unroll
                 for (int u = 0; u < XU; ++u) {
@@ -233,13 +225,13 @@ struct XStage {
                         const int b = idx / nc;
                         const int c = idx - b * nc;
                         const bool inside = cb * kTileK + c * kChunkK < p.K;
-                        xs[c * p.B + b] = inside ? v[u] : u32x4{0u, 0u, 0u, 0u};
+                        xs[dst(p, b, c)] = inside ? v[u] : u32x4{0u, 0u, 0u, 0u};
                     }
                 }
             }
             return;
         }
-        for (int idx = tid; idx < items; idx += NT) {      // K % 8 != 0: element-wise reads
+        for (int idx = tid; idx < items; idx += NT) {      // K % 8 != 0: element-wise reads (never layer-normed)
             const int b = idx / nc;
             const int c = idx - b * nc;
             const int k = cb * kTileK + c * kChunkK;
@@ -285,7 +277,9 @@ __device__ __forceinline__ void load_step(u32x4 (&slot)[kPanelTiles * PW], const
 // PW = panels per block (1 or 2): with two panels every wave streams both for the same
 // k-steps, so one X operand read from LDS feeds twice as many MFMAs and the X tile is staged
 // once for 128 columns - what larger batches need, where X traffic rivals the weight stream.
-template <int NW, int DEPTH, int PW, class Op>
+// LN: the layer-norm kernel variant; with p.ln set every X buffer also carries its k-steps of
+// gamma and beta (see XStage) and op.step receives their address as well.
+template <int NW, int DEPTH, int PW, bool LN, class Op>
 __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op& op, int tid, int wave,
                                              int lane, int panel, int64_t pstride, int ks0, int ks1)
 {
@@ -298,10 +292,11 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op&
     const int nchunks = (rounds + rpc - 1) / rpc;
     const u32x4* wbase = p.Wl + ((int64_t)panel * p.KS + ks0) * kStepUnits + lane;
     const int xblock = 4 * p.B;                                    // 16-byte units of X per k-step
-    const int xbuf = p.kc * xblock;                                // 16-byte units per X buffer
+    const int eblock = (LN && p.ln) ? 4 : 0;                       // 16-byte units of gamma (and of beta) per k-step
+    const int xbuf = p.kc * (xblock + 2 * eblock);                 // 16-byte units per X buffer
 
     u32x4 ring[DEPTH][kPanelTiles * PW];
-    XStage<NT, 4> xst;                                             // covers NT*64 bytes of X per chunk without a second pass
+    XStage<NT, 4, LN> xst;                                             // covers NT*64 bytes of X per chunk without a second pass
     xst.request(p, ks0, min(nks, p.kc), tid);
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
@@ -313,10 +308,11 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op&
     int t = wave;                                                  // this wave's k-step inside the range
     int c = 0, rc = 0;                                             // X chunk, round inside the chunk
     const u32x4* xc = xs;                                          // xc + t*xblock: X block of step t
+    const u32x4* ec = xs + p.kc * xblock;                          // ec + t*eblock: its gamma pieces
     for (int r = 0; r + 1 < rounds; ++r) {
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
-            op.step(ring[d], xc + t * xblock);                     // always inside the range here
+            op.step(ring[d], xc + t * xblock, ec + t * eblock);    // always inside the range here
             load_step<PW>(ring[d], wbase + (int64_t)min(t + RS, nks - 1) * kStepUnits, pstride);
             t += NW;
             __builtin_amdgcn_sched_barrier(0);
@@ -328,6 +324,7 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op&
             xst.commit(p, dst, ks0 + c * p.kc, min(nks - c * p.kc, p.kc), tid);
             __syncthreads();
             xc = dst - c * p.kc * xblock;
+            ec = dst + p.kc * xblock - c * p.kc * eblock;
             if (c + 1 < nchunks) xst.request(p, ks0 + (c + 1) * p.kc, min(nks - (c + 1) * p.kc, p.kc), tid);
         }
     }
@@ -337,51 +334,7 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op&
 #pragma unroll
             for (int q = 0; q < kPanelTiles * PW; ++q) ring[d][q] = u32x4{0u, 0u, 0u, 0u};
         }
-        op.step(ring[d], xc + min(t, nks - 1) * xblock);
-        t += NW;
-    }
-}
-
-// The weight stream of the layer-norm kernel variant: X for the block's whole range is staged
-// (and normalised) first, then the same register ring as stream_panel runs over one panel
-// without any X chunk switch.  The host plans such launches with p.kc >= p.ksps.
-template <int NW, int DEPTH, class Op>
-__device__ __forceinline__ void stream_panel_staged(const GemmParams& p, u32x4* xs, const floatx2* stats,
-                                                    Op& op, int tid, int wave, int lane, int panel,
-                                                    int ks0, int ks1)
-{
-    constexpr int NT = NW * 64;
-    constexpr int RS = NW * DEPTH;
-    constexpr int kStepUnits = kPanelTiles * 64;
-    const int nks = ks1 - ks0;
-    const int rounds = (nks + RS - 1) / RS;
-    const u32x4* wbase = p.Wl + ((int64_t)panel * p.KS + ks0) * kStepUnits + lane;
-    const int xblock = 4 * p.B;
-
-    stage_all<NT>(p, xs, stats, ks0, nks, tid);
-    u32x4 ring[DEPTH][kPanelTiles];
-#pragma unroll
-    for (int d = 0; d < DEPTH; ++d)
-        load_step<1>(ring[d], wbase + (int64_t)min(d * NW + wave, nks - 1) * kStepUnits, 0);
-    __syncthreads();
-
-    int t = wave;
-    for (int r = 0; r + 1 < rounds; ++r) {
-#pragma unroll
-        for (int d = 0; d < DEPTH; ++d) {
-            op.step(ring[d], xs + t * xblock);
-            load_step<1>(ring[d], wbase + (int64_t)min(t + RS, nks - 1) * kStepUnits, 0);
-            t += NW;
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-#pragma unroll
-    for (int d = 0; d < DEPTH; ++d) {
-        if (t >= nks) {
-#pragma unroll
-            for (int q = 0; q < kPanelTiles; ++q) ring[d][q] = u32x4{0u, 0u, 0u, 0u};
-        }
-        op.step(ring[d], xs + min(t, nks - 1) * xblock);
+        op.step(ring[d], xc + min(t, nks - 1) * xblock, ec + min(t, nks - 1) * eblock);
         t += NW;
     }
 }

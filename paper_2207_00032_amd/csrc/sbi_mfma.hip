@@ -16,12 +16,18 @@
 namespace sbi {
 
 // Per-wave contraction state: PW 64-column x (MB*16)-row fp32 tiles in MFMA result layout.
-template <int MB, int PW>
+// LN: the X pieces in LDS are raw; each is layer-normalised (fp32, rounded once to fp16) right
+// before it becomes the MFMA operand, with the row statistics of this lane's batch rows held
+// in registers and the k-step's gamma and beta pieces read from LDS next to the X chunk.
+template <int MB, int PW, bool LN>
 struct MfmaOp {
     floatx4 acc[kPanelTiles * PW][MB];
     int xoff[MB];     // this lane's 16-byte slot inside a k-step's X block
+    floatx2 st[LN ? MB : 1];
+    int goff, boff;   // this lane's gamma piece inside a k-step's gamma block; beta: boff further
+    int ln;
 
-    __device__ __forceinline__ void init(int B, int g, int i)
+    __device__ __forceinline__ void init(const GemmParams& p, const floatx2* stats, int g, int i)
     {
 #pragma unroll
         for (int t = 0; t < kPanelTiles * PW; ++t)
@@ -29,14 +35,32 @@ struct MfmaOp {
             for (int m = 0; m < MB; ++m) acc[t][m] = floatx4{0.f, 0.f, 0.f, 0.f};
         // rows beyond B re-read row B-1: they only feed result columns that are never stored
 #pragma unroll
-        for (int m = 0; m < MB; ++m) xoff[m] = g * B + min(m * 16 + i, B - 1);
+        for (int m = 0; m < MB; ++m) xoff[m] = g * p.B + min(m * 16 + i, p.B - 1);
+        goff = g;
+        boff = p.kc * 4;
+        ln = 0;
+        if constexpr (LN) {
+            ln = p.ln;
+            if (p.ln) {
+#pragma unroll
+                for (int m = 0; m < MB; ++m) st[m] = stats[min(m * 16 + i, p.B - 1)];
+            }
+        }
     }
 
-    __device__ __forceinline__ void step(const u32x4 (&w)[kPanelTiles * PW], const u32x4* xk)
+    __device__ __forceinline__ void step(const u32x4 (&w)[kPanelTiles * PW], const u32x4* xk, const u32x4* ek)
     {
         half8 xf[MB];
 #pragma unroll
         for (int m = 0; m < MB; ++m) xf[m] = __builtin_bit_cast(half8, xk[xoff[m]]);
+        if constexpr (LN) {
+            if (ln) {
+                const half8 gh = __builtin_bit_cast(half8, ek[goff]);
+                const half8 bh = __builtin_bit_cast(half8, ek[goff + boff]);
+#pragma unroll
+                for (int m = 0; m < MB; ++m) xf[m] = ln_apply(xf[m], gh, bh, st[m]);
+            }
+        }
 #pragma unroll
         for (int t = 0; t < kPanelTiles * PW; ++t) {
             const half8 wf = __builtin_bit_cast(half8, w[t]);
@@ -50,9 +74,9 @@ struct MfmaOp {
 // One launch may carry several independent GeMMs of the same batch size (the linear layers of
 // one transformer layer): their blocks are simply concatenated, so the ramp-up and the tail of
 // a launch are paid once per layer instead of once per GeMM.
-// LN: the launch may contain problems whose X is layer-normalised on its way into LDS; the
-// first kLnStatsBytes of the dynamic LDS then hold the rows' statistics, one panel per block,
-// and every block stages X for its whole k-range up front (p.kc >= p.ksps).
+// LN: the launch may contain problems whose X is layer-normalised (p.ln); the first
+// kLnStatsBytes of the dynamic LDS then hold the rows' statistics, which every block computes
+// for itself before it starts its weight stream.
 template <int MB, int NW, int DEPTH, int PW, bool LN>
 __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
 {
@@ -92,12 +116,9 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
 #ifdef SBI_TRACE
     const unsigned long long t_start = wall_clock64();
 #endif
-    MfmaOp<MB, PW> op;
-    op.init(p.B, g, i);
-    if constexpr (LN)
-        stream_panel_staged<NW, DEPTH>(p, xs, stats, op, tid, wave, lane, panel, ks0, ks1);
-    else
-        stream_panel<NW, DEPTH, PW>(p, xs, op, tid, wave, lane, panel, pstride, ks0, ks1);
+    MfmaOp<MB, PW, LN> op;
+    op.init(p, stats, g, i);
+    stream_panel<NW, DEPTH, PW, LN>(p, xs, op, tid, wave, lane, panel, pstride, ks0, ks1);
 #ifdef SBI_TRACE
     const unsigned long long t_stream = wall_clock64();
 #endif

@@ -29,7 +29,7 @@ struct DotOp {
         xoff = g * BT;
     }
 
-    __device__ __forceinline__ void step(const u32x4 (&w)[kPanelTiles], const u32x4* xk)
+    __device__ __forceinline__ void step(const u32x4 (&w)[kPanelTiles], const u32x4* xk, const u32x4*)
     {
         u32x4 xf[BT];
 #pragma unroll
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(NW * 64) void sbi_stream_kernel(const GemmParams p)
 
     DotOp<BT> op;
     op.init(g);
-    stream_panel<NW, DEPTH, 1>(p, xs, op, tid, wave, lane, panel, 0, ks0, ks1);
+    stream_panel<NW, DEPTH, 1, false>(p, xs, op, tid, wave, lane, panel, 0, ks0, ks1);
 
     // cross-lane K reduction over the four lane groups, then park the wave's tile in LDS
 #pragma unroll

@@ -163,7 +163,12 @@ def test_layer_argument_validation(lib):
     assert call(ctypes.byref(L), 0, args) == 4
     a = list(args); a[0] = None
     assert call(ctypes.byref(L), 1, a) == 1
-    assert call(ctypes.byref(L), 1, args, wb=ws - 1 if ws else 0) == (6 if ws else 0) or ws == 0
+    # a call needs what its own launches need (the four-GeMM launch here), never more than `ws`
+    plans, _ = sb.layer_plan(L, 1, chained=False)
+    assert any(p["split_k"] > 1 for p in plans)
+    need = 256 * 1024 + sum(p["workspace_bytes"] for p in plans)
+    assert 0 < need <= ws
+    assert call(ctypes.byref(L), 1, args, wb=need - 1) == 6
     L2 = sb.Layer.from_buffer_copy(L)
     L2.k_ffn2 = 2048                                              # chaining needs n_ffn1 == k_ffn2
     a = list(args); a[3] = None
@@ -213,7 +218,8 @@ def test_layernorm_plan_invariants(B, K, N):
     S, ksps, kc = pl["split_k"], pl["ksteps_per_split"], pl["ksteps_per_chunk"]
     assert 1 <= S <= KS and ksps * S >= KS and ksps * (S - 1) < KS and pl["grid"] == P * S
     buffers = 1 if kc >= ksps else 2
-    assert 512 + buffers * kc * B * 64 <= pl["lds_bytes"] <= 128 * 1024    # statistics ahead of the X tile
+    # statistics ahead of the X buffers; each buffer also holds its k-steps of gamma and beta
+    assert 512 + buffers * kc * (B + 2) * 64 <= pl["lds_bytes"] <= 128 * 1024
     with pytest.raises(sb.SbiError) as e:
         sb.plan(B, K + 4, N, layernorm=True)
     assert e.value.status == 10

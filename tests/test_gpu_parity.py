@@ -326,3 +326,28 @@ def test_layer_gemms_under_graph_replay(gpu):
     assert not ws[:256 * 1024].cpu().numpy().any()
     check(eager[3].cpu().numpy(), data[3][0], data[3][1], eager[2].cpu().numpy(), data[3][3],
           "bias_residual", "graph layer ffn2")
+
+
+def test_binding_rejects_tensors_smaller_than_the_call_reads(gpu):
+    """The C ABI takes bare pointers, so the binding checks extents before it passes them on."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    K, N, B = 256, 256, 4
+    W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=9, config_id=300)
+    Wl = sb.layout_weights(_dev(W, gpu))
+    Xd, bd, Rd = _dev(X, gpu), _dev(bias, gpu), _dev(R, gpu)
+    with pytest.raises(ValueError):
+        sb.gemm(Wl, K, N, Xd[:, :128].contiguous(), bd, None, "bias")          # fewer columns than K
+    with pytest.raises(ValueError):
+        sb.gemm(Wl, K, N, Xd, bd[:64].contiguous(), None, "bias")              # short bias
+    with pytest.raises(ValueError):
+        sb.gemm(Wl, K, N, Xd, bd, Rd[:2].contiguous(), "bias_residual")        # residual with fewer rows
+    with pytest.raises(ValueError):
+        sb.gemm(Wl[:1024], K, N, Xd, bd, None, "bias")                          # truncated weights
+    L = sb.make_layer(Wl, Wl, Wl, Wl, K, N, K, N, K)
+    Y = torch.empty((B, N), dtype=torch.float16, device=gpu)
+    ws = sb.new_workspace(sb.layer_workspace_bytes(L, B), gpu)
+    with pytest.raises(ValueError):
+        sb.layer_gemms(L, B, Xd[:2].contiguous(), Xd, Xd, Xd, None, Y, Y.clone(), Y.clone(), Y.clone(), ws)
+    with pytest.raises(ValueError):
+        sb.make_layer(Wl, Wl[:4096], Wl, Wl, K, N, K, N, K)
