@@ -52,6 +52,13 @@ def lib():
         L.sbi_oracle_layernorm.restype = ctypes.c_int
         L.sbi_oracle_layernorm.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_double, ctypes.c_int64, ctypes.c_int64,
                                            ctypes.c_void_p, ctypes.c_void_p]
+        vp, i64 = ctypes.c_void_p, ctypes.c_int64
+        L.sbi_oracle_quantize_rows.restype = ctypes.c_int
+        L.sbi_oracle_quantize_rows.argtypes = [vp, i64, i64, vp, vp]
+        L.sbi_oracle_quantize_columns.restype = ctypes.c_int
+        L.sbi_oracle_quantize_columns.argtypes = [vp, i64, i64, vp, vp]
+        L.sbi_oracle_gemm_i8.restype = ctypes.c_int
+        L.sbi_oracle_gemm_i8.argtypes = [vp] * 6 + [ctypes.c_int, i64, i64, i64, vp, vp]
         L.sbi_oracle_max_threads.restype = ctypes.c_int
         L.sbi_oracle_gemm.restype = ctypes.c_int
         L.sbi_oracle_gemm.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] + [ctypes.c_int64] * 3 + \
@@ -140,6 +147,95 @@ def layernorm(X, gamma, beta, eps, return_pre=False):
     if rc != 0:
         raise RuntimeError(f"sbi_oracle_layernorm failed rc={rc}")
     return (out.view(np.float16), pre) if return_pre else out.view(np.float16)
+
+
+# --------------------------------------------------------------------------------------
+# INT8 path: symmetric quantisation (binary32 decisions, see sbi_oracle.c) and the exact-integer GeMM.
+# --------------------------------------------------------------------------------------
+def quantize_rows(X):
+    """X [B,K] fp16 -> (Xq int8 [B,K], sx float32 [B]): one scale per row (per token)."""
+    Xb = _bits(X, "X")
+    if Xb.ndim != 2:
+        raise ValueError("quantize_rows wants [B,K]")
+    B, K = Xb.shape
+    q = np.empty((B, K), dtype=np.int8)
+    s = np.empty(B, dtype=np.float32)
+    if lib().sbi_oracle_quantize_rows(Xb.ctypes.data, B, K, q.ctypes.data, s.ctypes.data) != 0:
+        raise RuntimeError("sbi_oracle_quantize_rows failed")
+    return q, s
+
+
+def quantize_columns(W):
+    """W [K,N] fp16 -> (Wq int8 [K,N], sw float32 [N]): one scale per column (per output channel)."""
+    Wb = _bits(W, "W")
+    if Wb.ndim != 2:
+        raise ValueError("quantize_columns wants [K,N]")
+    K, N = Wb.shape
+    q = np.empty((K, N), dtype=np.int8)
+    s = np.empty(N, dtype=np.float32)
+    if lib().sbi_oracle_quantize_columns(Wb.ctypes.data, K, N, q.ctypes.data, s.ctypes.data) != 0:
+        raise RuntimeError("sbi_oracle_quantize_columns failed")
+    return q, s
+
+
+def gemm_i8(Xq, sx, Wq, sw, bias=None, residual=None, epi=0, return_pre=False):
+    """Y = epilogue((Xq @ Wq) * sx[:,None] * sw[None,:] + bias): exact integer product, fp64 epilogue,
+    one rounding to fp16.  Xq [B,K], Wq [K,N] int8; sx [B], sw [N] float32."""
+    Xq = np.ascontiguousarray(Xq, dtype=np.int8)
+    Wq = np.ascontiguousarray(Wq, dtype=np.int8)
+    sx = np.ascontiguousarray(sx, dtype=np.float32)
+    sw = np.ascontiguousarray(sw, dtype=np.float32)
+    if Xq.ndim != 2 or Wq.ndim != 2 or Xq.shape[1] != Wq.shape[0] or sx.shape != (Xq.shape[0],) or \
+            sw.shape != (Wq.shape[1],):
+        raise ValueError("gemm_i8 shapes")
+    B, K = Xq.shape
+    N = Wq.shape[1]
+    bb = rb = None
+    if epi & EPI_BIAS:
+        bb = _bits(bias, "bias")
+        if bb.shape != (N,):
+            raise ValueError("bias shape")
+    if epi & EPI_RES:
+        rb = _bits(residual, "residual")
+        if rb.shape != (B, N):
+            raise ValueError("residual shape")
+    Y = np.empty((B, N), dtype=np.uint16)
+    pre = np.empty((B, N), dtype=np.float64) if return_pre else None
+    rc = lib().sbi_oracle_gemm_i8(Xq.ctypes.data, sx.ctypes.data, Wq.ctypes.data, sw.ctypes.data,
+                                  bb.ctypes.data if bb is not None else None,
+                                  rb.ctypes.data if rb is not None else None, int(epi), B, K, N,
+                                  Y.ctypes.data, pre.ctypes.data if pre is not None else None)
+    if rc != 0:
+        raise RuntimeError(f"sbi_oracle_gemm_i8 failed rc={rc}")
+    Yh = Y.view(np.float16)
+    return (Yh, pre) if return_pre else Yh
+
+
+def gemm_i8_from_fp16(X, Wq, sw, bias=None, residual=None, epi=0):
+    """The whole INT8 path on fp16 activations: quantise the rows of X, then gemm_i8."""
+    Xq, sx = quantize_rows(X)
+    return gemm_i8(Xq, sx, Wq, sw, bias, residual, epi)
+
+
+I8_TILE_K = 64          # k per k-step of the int8 layout
+I8_CHUNK_K = 16         # consecutive k one lane owns (16 bytes)
+
+
+def layout_dims_i8(K, N):
+    KS = -(-(-(-K // I8_TILE_K)) // STEP_GROUP) * STEP_GROUP
+    return KS, -(-N // PANEL_N)
+
+
+def layout_weights_i8(Wq):
+    """Wq [K,N] int8 -> flat int8 array of P*KS*4*64*16 bytes (no header): the fp16 layout's
+    structure with 64-k steps, lane (g, i) owning k = 16g..16g+15 of column i."""
+    Wq = np.ascontiguousarray(Wq, dtype=np.int8)
+    K, N = Wq.shape
+    KS, P = layout_dims_i8(K, N)
+    Wp = np.zeros((KS * I8_TILE_K, P * PANEL_N), dtype=np.int8)
+    Wp[:K, :N] = Wq
+    T = Wp.reshape(KS, 4, I8_CHUNK_K, P, PANEL_TILES, TILE_N)          # ks, g, e, p, t, i
+    return np.ascontiguousarray(T.transpose(3, 0, 4, 1, 5, 2)).reshape(-1)   # p, ks, t, g, i, e
 
 
 # --------------------------------------------------------------------------------------

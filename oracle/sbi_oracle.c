@@ -25,7 +25,8 @@
  *
  * Every function here is pinned by tests/test_oracle_*.py (brute-force rational
  * arithmetic, identity / one-hot weights, linearity, GeLU closed forms, exhaustive
- * fp16 round trips): no part is "parity unpinned".
+ * fp16 round trips; layer-norm and the INT8 functions: hand-worked cases, exact integer
+ * brute force, reduction to the fp16 GeMM where the scales are 1): no part is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -126,6 +127,95 @@ int sbi_oracle_layernorm(const uint16_t* X, const uint16_t* gamma, const uint16_
             out[b * K + k] = sbi_oracle_double_to_half(y);
         }
     }
+    return 0;
+}
+
+/*
+ * INT8 path (paper Sec. III-D, "Support for Different Data Types": an INT8 GeMM with a quantize
+ * operation fused before it and the de-quantisation fused after it).  The paper gives no
+ * quantisation formula; the reading taken here is the plain symmetric one, per row of the
+ * activations (per token) and per column of the weights (per output channel):
+ *
+ *     amax  = max_j |v_j|              inv = 127 / amax          scale = amax / 127
+ *     q_j   = clamp(rint(v_j * inv), -127, 127)                   (amax = 0: q = 0, scale = 0)
+ *
+ * The code q_j is an INTEGER decided by floating point, so its arithmetic is fixed exactly and
+ * is the kernel's: IEEE binary32, `inv` and `scale` one correctly rounded division each, one
+ * correctly rounded multiplication, round-half-to-even to an integer.  (fp16 inputs are exact
+ * in binary32.)  Everything after the codes is exact or fp64:
+ *
+ *     acc[b,n] = sum_k Xq[b,k] * Wq[k,n]                          exact integer
+ *     v        = acc * sx[b] * sw[n] (+ bias) -> GeLU -> + residual   fp64, as in sbi_oracle_gemm
+ *     Y        = fp16(v)                                           one RNE step
+ */
+static void quantize_line(const uint16_t* v, int64_t n, int64_t stride, int8_t* q, float* scale)
+{
+    float amax = 0.0f;
+    for (int64_t j = 0; j < n; ++j) {
+        const float a = fabsf((float)sbi_oracle_half_to_double(v[j * stride]));
+        if (a > amax) amax = a;
+    }
+    if (!(amax > 0.0f)) {
+        for (int64_t j = 0; j < n; ++j) q[j * stride] = 0;
+        *scale = 0.0f;
+        return;
+    }
+    const volatile float inv = 127.0f / amax;
+    *scale = amax / 127.0f;
+    for (int64_t j = 0; j < n; ++j) {
+        const volatile float p = (float)sbi_oracle_half_to_double(v[j * stride]) * inv;   /* binary32 product */
+        float r = rintf(p);                       /* current rounding mode: to nearest, ties to even */
+        if (r > 127.0f) r = 127.0f;
+        if (r < -127.0f) r = -127.0f;
+        q[j * stride] = (int8_t)r;
+    }
+}
+
+/* X [B,K] fp16 bits -> Xq [B,K] int8 and sx [B]: one scale per row */
+int sbi_oracle_quantize_rows(const uint16_t* X, int64_t B, int64_t K, int8_t* Xq, float* sx)
+{
+    if (!X || !Xq || !sx || B <= 0 || K <= 0) return -1;
+    for (int64_t b = 0; b < B; ++b) quantize_line(X + b * K, K, 1, Xq + b * K, sx + b);
+    return 0;
+}
+
+/* W [K,N] fp16 bits -> Wq [K,N] int8 and sw [N]: one scale per column */
+int sbi_oracle_quantize_columns(const uint16_t* W, int64_t K, int64_t N, int8_t* Wq, float* sw)
+{
+    if (!W || !Wq || !sw || K <= 0 || N <= 0) return -1;
+    for (int64_t n = 0; n < N; ++n) quantize_line(W + n, K, N, Wq + n, sw + n);
+    return 0;
+}
+
+/* The INT8 GeMM on given codes and scales.  Xq [B,K], Wq [K,N] int8; sx [B], sw [N] binary32. */
+int sbi_oracle_gemm_i8(const int8_t* Xq, const float* sx, const int8_t* Wq, const float* sw,
+                       const uint16_t* bias, const uint16_t* R, int epi, int64_t B, int64_t K, int64_t N,
+                       uint16_t* Y, double* pre)
+{
+    if (!Xq || !sx || !Wq || !sw || !Y || B <= 0 || K <= 0 || N <= 0) return -1;
+    if ((epi & ORACLE_EPI_BIAS) && !bias) return -1;
+    if ((epi & ORACLE_EPI_RES) && !R) return -1;
+    if (epi & ~7) return -1;
+    int64_t* acc = (int64_t*)malloc(sizeof(int64_t) * (size_t)N);
+    if (!acc) return -1;
+    for (int64_t b = 0; b < B; ++b) {
+        for (int64_t n = 0; n < N; ++n) acc[n] = 0;
+        for (int64_t k = 0; k < K; ++k) {
+            const int64_t x = Xq[b * K + k];
+            if (x == 0) continue;
+            const int8_t* w = Wq + k * N;
+            for (int64_t n = 0; n < N; ++n) acc[n] += x * (int64_t)w[n];
+        }
+        for (int64_t n = 0; n < N; ++n) {
+            double v = (double)acc[n] * (double)sx[b] * (double)sw[n];
+            if (epi & ORACLE_EPI_BIAS) v += sbi_oracle_half_to_double(bias[n]);
+            if (epi & ORACLE_EPI_GELU) v = sbi_oracle_gelu(v);
+            if (epi & ORACLE_EPI_RES)  v += sbi_oracle_half_to_double(R[b * N + n]);
+            if (pre) pre[b * N + n] = v;
+            Y[b * N + n] = sbi_oracle_double_to_half(v);
+        }
+    }
+    free(acc);
     return 0;
 }
 

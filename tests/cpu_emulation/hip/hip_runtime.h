@@ -1,0 +1,102 @@
+// Host stand-in for the HIP runtime: lets the kernel sources compile as plain C++ so that
+// their addressing can run under AddressSanitizer on the CPU.  One OS thread per GPU thread.
+#pragma once
+#include <atomic>
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <functional>
+#include <algorithm>
+#include <pthread.h>
+
+#define __device__
+#define __host__
+#define __global__
+#define __forceinline__ inline __attribute__((always_inline))
+#define __launch_bounds__(...)
+#define __shared__ static
+
+struct dim3 { unsigned x, y, z; dim3(unsigned a = 1, unsigned b = 1, unsigned c = 1) : x(a), y(b), z(c) {} };
+typedef void* hipStream_t;
+typedef int hipError_t;
+enum { hipSuccess = 0, hipErrorInvalidValue = 1 };
+enum { hipFuncAttributeMaxDynamicSharedMemorySize = 8 };
+enum { hipMemcpyDeviceToHost = 2 };
+inline hipError_t hipGetLastError() { return hipSuccess; }
+inline hipError_t hipFuncSetAttribute(const void*, int, int) { return hipSuccess; }
+inline hipError_t hipMemcpyAsync(void* d, const void* s, size_t n, int, hipStream_t) { memcpy(d, s, n); return hipSuccess; }
+inline hipError_t hipStreamSynchronize(hipStream_t) { return hipSuccess; }
+
+namespace emu {
+struct Block {
+    int nthreads;
+    pthread_barrier_t all;
+    pthread_barrier_t wave[16];
+    unsigned char* lds;
+    size_t lds_bytes;
+    // exchange areas for wave-wide operations
+    float shf[16][64];
+    _Float16 ma[16][64][8], mb[16][64][8];
+};
+extern thread_local dim3 t_threadIdx, t_blockIdx, t_blockDim, t_gridDim;
+extern thread_local Block* t_block;
+void launch(unsigned grid, unsigned block, size_t lds, const std::function<void()>& body);
+inline unsigned char* lds() { return t_block->lds; }
+}
+#define threadIdx emu::t_threadIdx
+#define blockIdx emu::t_blockIdx
+#define blockDim emu::t_blockDim
+#define gridDim emu::t_gridDim
+
+inline void __syncthreads() { pthread_barrier_wait(&emu::t_block->all); }
+
+inline float __shfl_xor(float v, int mask, int width = 64)
+{
+    emu::Block* b = emu::t_block;
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    b->shf[w][l] = v;
+    pthread_barrier_wait(&b->wave[w]);
+    const float r = b->shf[w][l ^ mask];
+    pthread_barrier_wait(&b->wave[w]);
+    return r;
+}
+inline int __shfl_xor(int v, int mask, int width = 64)
+{
+    return __builtin_bit_cast(int, __shfl_xor(__builtin_bit_cast(float, v), mask, width));
+}
+
+typedef _Float16 emu_half8 __attribute__((ext_vector_type(8)));
+typedef float emu_floatx4 __attribute__((ext_vector_type(4)));
+// D[4*(l/16)+r][l%16] += sum_k A[row][k] * B[k][col];  lane l holds A[l%16][8*(l/16)..+8] and B[8*(l/16)..+8][l%16]
+inline emu_floatx4 __builtin_amdgcn_mfma_f32_16x16x32_f16(emu_half8 a, emu_half8 bb, emu_floatx4 c, int, int, int)
+{
+    emu::Block* b = emu::t_block;
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    for (int e = 0; e < 8; ++e) { b->ma[w][l][e] = a[e]; b->mb[w][l][e] = bb[e]; }
+    pthread_barrier_wait(&b->wave[w]);
+    const int col = l & 15;
+    for (int r = 0; r < 4; ++r) {
+        const int row = 4 * (l >> 4) + r;
+        float s = c[r];
+        for (int kg = 0; kg < 4; ++kg)
+            for (int e = 0; e < 8; ++e) s += (float)b->ma[w][kg * 16 + row][e] * (float)b->mb[w][kg * 16 + col][e];
+        c[r] = s;
+    }
+    pthread_barrier_wait(&b->wave[w]);
+    return c;
+}
+inline int __builtin_amdgcn_readfirstlane(int v) { return v; }
+#define __builtin_amdgcn_sched_barrier(x) ((void)0)
+#define __builtin_amdgcn_fence(order, scope) __atomic_thread_fence(__ATOMIC_SEQ_CST)
+#define __HIP_MEMORY_SCOPE_AGENT 0
+#define __hip_atomic_store(p, v, order, scope) __atomic_store_n(p, v, __ATOMIC_SEQ_CST)
+#define __hip_atomic_load(p, order, scope) __atomic_load_n(p, __ATOMIC_SEQ_CST)
+#define __hip_atomic_fetch_add(p, v, order, scope) __atomic_fetch_add(p, v, __ATOMIC_SEQ_CST)
+inline unsigned long long wall_clock64() { return 0; }
+using std::min;
+using std::max;
+
+#define hipLaunchKernelGGL(kernel, grid, block, lds, stream, ...) \
+    emu::launch((grid).x, (block).x, (lds), [=]() { kernel(__VA_ARGS__); })

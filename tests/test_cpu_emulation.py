@@ -1,0 +1,56 @@
+"""The library's host code and MFMA kernels compiled for the CPU under AddressSanitizer
+(tests/cpu_emulation/): every global and LDS access of every thread of every block is checked
+against buffers of exactly the documented size, and the results against an fp64 reference
+written out in the drivers.  No GPU, no oracle involved: this guards addressing (the kind of
+mistake that is a memory fault on the GPU), not numerics.
+
+The build takes about two minutes, so the test only runs on request:
+    SBI_RUN_EMULATION=1 python -m pytest tests/test_cpu_emulation.py -q
+"""
+import os
+import subprocess
+
+import pytest
+
+pytestmark = pytest.mark.skipif(os.environ.get("SBI_RUN_EMULATION") != "1",
+                                reason="set SBI_RUN_EMULATION=1 (two-minute sanitizer build)")
+
+
+@pytest.fixture(scope="module")
+def drivers(tmp_path_factory):
+    import importlib.util
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("emu_build", os.path.join(here, "cpu_emulation", "build.py"))
+    build = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(build)
+    out = tmp_path_factory.mktemp("emu")
+    gemm, layer = build.build(str(out))
+    return gemm, layer
+
+
+def run(cmd):
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0")
+    env.pop("EMU_BLOCKS", None)
+    r = subprocess.run(cmd, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=600)
+    assert r.returncode == 0 and "AddressSanitizer" not in r.stdout, r.stdout[-3000:]
+
+
+# B K N waves depth split panels layernorm   (waves 0 = automatic plan)
+GEMM_CASES = [
+    (1, 64, 64, 0, 0, 0, 0, 0), (3, 264, 200, 0, 0, 0, 0, 0), (5, 1001, 130, 4, 4, 2, 1, 0),
+    (8, 2048, 128, 8, 4, 1, 1, 0), (17, 1024, 136, 4, 2, 3, 1, 0), (33, 520, 192, 4, 4, 1, 2, 0),
+    (64, 512, 128, 8, 2, 2, 2, 0), (1, 12288, 128, 4, 4, 1, 1, 0),
+    (1, 64, 64, 0, 0, 0, 0, 1), (3, 264, 200, 0, 0, 0, 0, 1), (8, 2048, 128, 8, 4, 1, 1, 1),
+    (17, 1024, 136, 4, 2, 3, 1, 1), (40, 1024, 72, 4, 4, 2, 1, 1), (64, 512, 128, 4, 2, 2, 1, 1),
+    (2, 6144, 64, 4, 4, 1, 1, 1),
+]
+
+
+@pytest.mark.parametrize("case", GEMM_CASES)
+def test_single_gemm_under_asan(drivers, case):
+    run([drivers[0], *[str(v) for v in case]])
+
+
+@pytest.mark.parametrize("B,h,ln", [(2, 256, 0), (5, 512, 1), (33, 256, 1), (9, 1024, 1)])
+def test_layer_launch_under_asan(drivers, B, h, ln):
+    run([drivers[1], str(B), str(h), str(ln), "1"])

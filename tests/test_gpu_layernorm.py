@@ -161,3 +161,53 @@ def test_layer_gemms_with_fused_layernorms(gpu, cfg_id, B, chained, which):
             ok, report = orc.check_close(y, orc.gemm(x, d[0], d[1], r, epi=e), ulps=2, abs_tol=1e-3)
             assert ok, f"{name}: {report}"
     assert not ws[:256 * 1024].cpu().numpy().any()
+
+
+def test_ln_layer_under_graph_replay(gpu):
+    """The layer with both layer-norms fused, FFN2 chained, captured into a HIP graph: every replay
+    reproduces the eager bits (the fused variant, too, enqueues nothing but kernels)."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    cfg = wl.CONFIGS[1]
+    B = 2
+    data = [wl.make_gemm_inputs(s.K, s.N, B, seed=4, config_id=1, gemm_id=i) for i, s in enumerate(cfg.gemms)]
+    h = cfg.gemms[0].K
+    ln = [wl.make_layernorm_inputs(h, B, seed=4, config_id=1, gemm_id=i) for i in (0, 2)]
+    Wls = [sb.layout_weights(_dev(d[0], gpu)) for d in data]
+    biases = [_dev(d[1], gpu) for d in data]
+    lnd = [(_dev(g, gpu), _dev(b, gpu)) for g, b, _ in ln]
+    L = sb.make_layer(*Wls, h, cfg.gemms[0].N, cfg.gemms[1].K, cfg.gemms[2].N, cfg.gemms[3].K,
+                      bqkv=biases[0], bout=biases[1], bffn1=biases[2], bffn2=biases[3], ffn1_gelu=True,
+                      ln1=lnd[0], ln2=lnd[1], ln_eps=EPS)
+    ws = sb.new_workspace(sb.layer_workspace_bytes(L, B), gpu)
+    Xs = [_dev(ln[0][2], gpu), _dev(data[1][2], gpu), _dev(ln[1][2], gpu)]
+    Rd = _dev(data[3][3], gpu)
+    Ys = [torch.empty((B, s.N), dtype=torch.float16, device=gpu) for s in cfg.gemms]
+
+    def run():
+        sb.layer_gemms(L, B, Xs[0], Xs[1], Xs[2], None, Rd, Ys[0], Ys[1], Ys[2], Ys[3], ws)
+
+    run()
+    torch.cuda.synchronize()
+    eager = [y.clone() for y in Ys]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for y in Ys:
+            y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for y, e in zip(Ys, eager):
+            assert torch.equal(y.view(torch.int16), e.view(torch.int16)), f"replay {rep} differs"
+        run()
+        torch.cuda.synchronize()
+    x2 = orc.layernorm(ln[1][2], ln[1][0], ln[1][1], EPS)
+    ok, rep = orc.check_close(eager[2].cpu().numpy(),
+                              orc.gemm(x2, data[2][0], data[2][1], None, epi=orc.EPI_BIAS | orc.EPI_GELU),
+                              ulps=2, abs_tol=1e-3)
+    assert ok, rep
+    assert not ws[:256 * 1024].cpu().numpy().any()
