@@ -79,6 +79,8 @@ typedef struct sbi_tuning {
     int32_t layernorm; /* sbi_gemm_plan: nonzero plans the launch sbi_gemm_ln makes (layer-norm fused
                           in front: MFMA path, one panel per block, K % 8 == 0, (waves, depth) one of
                           (4,2), (4,4), (8,4)); sbi_gemm_ex rejects it, sbi_gemm_ln implies it */
+    int32_t int8;      /* sbi_gemm_plan: nonzero plans the launch sbi_gemm_i8 makes (same restrictions,
+                          K % 16 == 0, not together with layernorm); sbi_gemm_i8 implies it */
 } sbi_tuning;
 
 /* What the dispatcher decided for a problem (for reports and tests). */
@@ -196,6 +198,44 @@ sbi_status sbi_gemm_ln(const void* W_laid_out, int64_t K, int64_t N,
                        const sbi_tuning* tuning);
 
 size_t sbi_gemm_ln_workspace_bytes(int64_t B, int64_t K, int64_t N);
+
+/*
+ * INT8 GeMM (paper Sec. III-D, "Support for Different Data Types": an INT8 GeMM with the quantize
+ * operation fused in front of it and the de-quantisation fused into its epilogue; Sec. III-C
+ * "Leveraging Full Cache-line": INT8 gets its own, wider pre-layout).  The paper gives no
+ * quantisation formula; this library uses the plain symmetric one, per output channel for the
+ * weights and per row (token) for the activations, every step in IEEE binary32:
+ *
+ *     amax = max |v|      inv = 127 / amax      scale = amax / 127     (amax = 0: inv = scale = 0)
+ *     code = clamp(rint(v * inv), -127, 127)                            (ties to even)
+ *     Y[b,n] = epilogue( (sum_k Xq[b,k] * Wq[k,n]) * sx[b] * sw[n] + bias[n] )
+ *
+ * The integer sum is exact (int32; |sum| <= 127^2 K); the activations are quantised inside the
+ * kernel (every block finds the rows' maxima itself), so X, bias, residual and Y are fp16 as in
+ * sbi_gemm.  Half the weight bytes of the fp16 path are streamed.
+ *
+ * sbi_gemm_i8_quantize_weights: W fp16 [K,N] row-major (device) -> codes Wq int8 [K,N] row-major
+ *   and scales sw binary32 [N] (both device, caller-owned).  Optional: codes and scales that were
+ *   produced elsewhere under the same convention can be used directly.
+ * sbi_gemm_i8_layout_weights: codes [K,N] row-major -> laid-out buffer of
+ *   sbi_gemm_i8_layout_bytes(K,N) bytes (256-byte aligned): 256-byte header, then per panel of 64
+ *   columns and per step of 64 k four 1 KiB tiles in which lane (g, i) holds the 16 codes
+ *   k = 16g..16g+15 of column i; zero padded.
+ * sbi_gemm_i8: as sbi_gemm_ex with the laid-out codes and w_scales (device, binary32 [N], 4-byte
+ *   aligned).  Needs K % 16 == 0 (SBI_ERR_SHAPE).  Workspace: sbi_gemm_i8_workspace_bytes.
+ */
+size_t sbi_gemm_i8_layout_bytes(int64_t K, int64_t N);
+size_t sbi_gemm_i8_workspace_bytes(int64_t B, int64_t K, int64_t N);
+sbi_status sbi_gemm_i8_quantize_weights(const void* W_rowmajor, int64_t K, int64_t N,
+                                        void* Wq_rowmajor, void* w_scales, void* hip_stream);
+sbi_status sbi_gemm_i8_layout_weights(const void* Wq_rowmajor, int64_t K, int64_t N,
+                                      void* W_laid_out, size_t laid_out_bytes, void* hip_stream);
+sbi_status sbi_gemm_i8_layout_check(const void* W_laid_out, int64_t K, int64_t N, void* hip_stream);
+sbi_status sbi_gemm_i8(const void* W_laid_out, const void* w_scales, int64_t K, int64_t N,
+                       const void* X, int64_t B,
+                       const void* bias, const void* residual, sbi_epilogue epi,
+                       void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
+                       const sbi_tuning* tuning);
 
 /* Host-only: the launch the dispatcher would make for (B, K, N) under `tuning` (or NULL). */
 sbi_status sbi_gemm_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tuning, sbi_plan* plan);

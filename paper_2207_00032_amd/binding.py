@@ -30,7 +30,8 @@ EXPORTS = ["sbi_gemm_layout_bytes", "sbi_gemm_workspace_bytes", "sbi_gemm_layout
            "sbi_gemm_unlayout_weights", "sbi_gemm_layout_check", "sbi_gemm", "sbi_gemm_ex",
            "sbi_gemm_plan", "sbi_layer_gemms", "sbi_layer_workspace_bytes", "sbi_status_string",
            "sbi_version", "sbi_calib_read", "sbi_calib_copy", "sbi_layer_plan", "sbi_gemm_ln",
-           "sbi_gemm_ln_workspace_bytes"]
+           "sbi_gemm_ln_workspace_bytes", "sbi_gemm_i8_layout_bytes", "sbi_gemm_i8_workspace_bytes",
+           "sbi_gemm_i8_quantize_weights", "sbi_gemm_i8_layout_weights", "sbi_gemm_i8_layout_check", "sbi_gemm_i8"]
 
 
 class SbiError(RuntimeError):
@@ -43,7 +44,7 @@ class SbiError(RuntimeError):
 class Tuning(ctypes.Structure):
     _fields_ = [("path", ctypes.c_int32), ("split_k", ctypes.c_int32),
                 ("waves", ctypes.c_int32), ("depth", ctypes.c_int32), ("blocks", ctypes.c_int32),
-                ("panels", ctypes.c_int32), ("layernorm", ctypes.c_int32)]
+                ("panels", ctypes.c_int32), ("layernorm", ctypes.c_int32), ("int8", ctypes.c_int32)]
 
 
 class LayerNorm(ctypes.Structure):
@@ -104,6 +105,18 @@ def load():
                               ctypes.POINTER(Tuning)]
     L.sbi_gemm_ln_workspace_bytes.restype = sz
     L.sbi_gemm_ln_workspace_bytes.argtypes = [i64, i64, i64]
+    L.sbi_gemm_i8_layout_bytes.restype = sz
+    L.sbi_gemm_i8_layout_bytes.argtypes = [i64, i64]
+    L.sbi_gemm_i8_workspace_bytes.restype = sz
+    L.sbi_gemm_i8_workspace_bytes.argtypes = [i64, i64, i64]
+    L.sbi_gemm_i8_quantize_weights.restype = i32
+    L.sbi_gemm_i8_quantize_weights.argtypes = [vp, i64, i64, vp, vp, vp]
+    L.sbi_gemm_i8_layout_weights.restype = i32
+    L.sbi_gemm_i8_layout_weights.argtypes = [vp, i64, i64, vp, sz, vp]
+    L.sbi_gemm_i8_layout_check.restype = i32
+    L.sbi_gemm_i8_layout_check.argtypes = [vp, i64, i64, vp]
+    L.sbi_gemm_i8.restype = i32
+    L.sbi_gemm_i8.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp, i32, vp, vp, sz, vp, ctypes.POINTER(Tuning)]
     L.sbi_gemm_plan.restype = i32
     L.sbi_gemm_plan.argtypes = [i64, i64, i64, ctypes.POINTER(Tuning), ctypes.POINTER(Plan)]
     L.sbi_layer_gemms.restype = i32
@@ -162,11 +175,11 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def _tuning(path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0, panels=0, layernorm=0):
-    if path == PATH_AUTO and not (split_k or waves or depth or blocks or panels or layernorm):
+def _tuning(path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0, panels=0, layernorm=0, int8=0):
+    if path == PATH_AUTO and not (split_k or waves or depth or blocks or panels or layernorm or int8):
         return None
     return ctypes.pointer(Tuning(int(path), int(split_k), int(waves), int(depth), int(blocks), int(panels),
-                                 1 if layernorm else 0))
+                                 1 if layernorm else 0, 1 if int8 else 0))
 
 
 # ---------------------------------------------------------------------------------- sizes
@@ -182,9 +195,9 @@ def ln_workspace_bytes(B, K, N):
     return int(load().sbi_gemm_ln_workspace_bytes(B, K, N))
 
 
-def plan(B, K, N, path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0, panels=0, layernorm=False):
+def plan(B, K, N, path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0, panels=0, layernorm=False, int8=False):
     pl = Plan()
-    _check(load().sbi_gemm_plan(B, K, N, _tuning(path, split_k, waves, depth, blocks, panels, layernorm),
+    _check(load().sbi_gemm_plan(B, K, N, _tuning(path, split_k, waves, depth, blocks, panels, layernorm, int8),
                                 ctypes.byref(pl)), "sbi_gemm_plan")
     return pl.as_dict()
 
@@ -217,6 +230,69 @@ def unlayout_weights(Wl, K, N):
 def layout_check(Wl, K, N):
     """Status of the header check (0 = the buffer was laid out for exactly (K, N))."""
     return int(load().sbi_gemm_layout_check(_ptr(Wl), K, N, _stream()))
+
+
+def i8_layout_bytes(K, N):
+    return int(load().sbi_gemm_i8_layout_bytes(K, N))
+
+
+def i8_workspace_bytes(B, K, N):
+    return int(load().sbi_gemm_i8_workspace_bytes(B, K, N))
+
+
+def i8_quantize_weights(W):
+    """W: fp16 [K,N] CUDA tensor -> (codes int8 [K,N], scales float32 [N]), per output channel."""
+    import torch
+    K, N = W.shape
+    _need(W, (K, N), "W")
+    Wq = torch.empty((K, N), dtype=torch.int8, device=W.device)
+    sw = torch.empty((N,), dtype=torch.float32, device=W.device)
+    _check(load().sbi_gemm_i8_quantize_weights(_ptr(W), K, N, _ptr(Wq), _ptr(sw), _stream()),
+           "sbi_gemm_i8_quantize_weights")
+    return Wq, sw
+
+
+def i8_layout_weights(Wq):
+    """Wq: int8 [K,N] CUDA tensor of codes -> laid-out uint8 CUDA tensor (header + tiles)."""
+    import torch
+    assert Wq.is_cuda and Wq.dtype == torch.int8 and Wq.dim() == 2 and Wq.is_contiguous()
+    K, N = Wq.shape
+    out = torch.empty(i8_layout_bytes(K, N), dtype=torch.uint8, device=Wq.device)
+    _check(load().sbi_gemm_i8_layout_weights(_ptr(Wq), K, N, _ptr(out), out.numel(), _stream()),
+           "sbi_gemm_i8_layout_weights")
+    return out
+
+
+def i8_layout_check(Wl, K, N):
+    return int(load().sbi_gemm_i8_layout_check(_ptr(Wl), K, N, _stream()))
+
+
+def gemm_i8(Wl, sw, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, workspace=None,
+            path=PATH_AUTO, split_k=0, waves=0, depth=0):
+    """Y = epilogue((quantize(X) @ Wq) * sx * sw + bias) through sbi_gemm_i8.  Returns Y (fp16 [B,N])."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.is_contiguous()
+    B = X.shape[0]
+    if isinstance(epilogue, str):
+        epilogue = EPILOGUES[epilogue]
+    if out is None:
+        out = torch.empty((B, N), dtype=torch.float16, device=X.device)
+    _need(X, (B, K), "X")
+    _need(bias, (N,), "bias")
+    _need(residual, (B, N), "residual")
+    _need(out, (B, N), "out")
+    _need_bytes(Wl, i8_layout_bytes(K, N), "laid-out int8 weights")
+    if not (sw.is_cuda and sw.dtype == torch.float32 and sw.is_contiguous() and tuple(sw.shape) == (N,)):
+        raise ValueError("w_scales: expected a contiguous CUDA float32 tensor of shape (N,)")
+    tune = _tuning(path, split_k, waves, depth)
+    if workspace is None:
+        need = plan(B, K, N, path, split_k, waves, depth, int8=True)["workspace_bytes"]
+        workspace = new_workspace(need, X.device) if need else None
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    st = load().sbi_gemm_i8(_ptr(Wl), _ptr(sw), K, N, _ptr(X), B, _ptr(bias), _ptr(residual), int(epilogue),
+                            _ptr(out), _ptr(workspace), ws_len, _stream(), tune)
+    _check(st, "sbi_gemm_i8")
+    return out
 
 
 def gemm(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, workspace=None,

@@ -32,6 +32,7 @@ struct Plan {
     int upw, nwaves;          // STREAMK path: units per wavefront, wavefronts
     int pw;                   // MFMA path: panels per block
     bool ln;                  // MFMA path: the kernel variant that can layer-normalise X
+    bool i8;                  // the INT8 kernel (64-k steps, int8 X codes in LDS)
 };
 
 constexpr int kSkDefaultWaves = 2048;             // wavefronts of a STREAMK launch: 8 per CU
@@ -48,7 +49,7 @@ sbi_status plan_streamk(int64_t B, int64_t units, int64_t panels, const sbi_tuni
     const int64_t want = t.blocks ? (int64_t)t.blocks * nw : kSkDefaultWaves;
     const int64_t upw = round_up(ceil_div(units, want), kStepGroup);
     const int64_t nwaves = ceil_div(units, upw);
-    pl.ln = false; pl.path = SBI_PATH_STREAMK; pl.nw = nw; pl.depth = depth; pl.S = 0;
+    pl.ln = false; pl.i8 = false; pl.path = SBI_PATH_STREAMK; pl.nw = nw; pl.depth = depth; pl.S = 0;
     pl.ksps = (int)upw; pl.kc = 0; pl.pw = 1;
     pl.grid = (int)ceil_div(nwaves, nw); pl.block = nw * 64; pl.lds = 0;
     pl.upw = (int)upw; pl.nwaves = (int)nwaves;
@@ -85,66 +86,71 @@ double split_cost(int64_t KS, int64_t P, int64_t B, int S, int nw)
     return cost;
 }
 
-sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot, bool ln);
+sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot, bool ln,
+                      bool i8 = false);
 
 // X staging of a block of `nw` waves that streams `ksps` k-steps, `wd` = waves*depth k-steps per
 // round, with at most `cap` bytes of LDS (64 B per batch row per k-step).  One staging pass
 // moves 4 pieces of 16 bytes per thread, i.e. nw * 4 KiB; every further pass costs a memory
 // latency, so: one buffer if the whole range fits in one pass, else two buffers of `kc` k-steps,
 // each within one pass where a round of k-steps allows it.  False if not even one round fits.
-bool chunking(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t red_bytes,
-              int64_t& kc, int64_t& lds, int64_t front = 0);
+// Kernel flavours differ in what sits in LDS: the layer-norm variant keeps the row statistics in
+// `front` bytes ahead of the X buffers (reused by the reduction afterwards) and adds gamma and
+// beta as two more rows per buffer; the INT8 kernel keeps the rows' scales there through the
+// reduction, stores int8 codes (64 k per k-step, still 64 B per row) and stages half as many
+// LDS bytes per pass.
+enum Flavour { kPlain = 0, kLayerNorm = 1, kInt8 = 2 };
 
-// With `front` > 0 (bytes of LDS reserved ahead of X for the layer-norm statistics): see below.
-bool chunking_impl(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t red_bytes,
-                   int64_t& kc, int64_t& lds)
+bool chunking(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t red_bytes,
+              int64_t& kc, int64_t& lds, Flavour fl = kPlain)
 {
-    const int64_t pass_bytes = (int64_t)nw * 4096;
+    const int64_t front = (fl == kPlain) ? 0 : kLnStatsBytes;
+    const int64_t rows = B + (fl == kLayerNorm ? 2 : 0);
+    const int64_t pass_bytes = (int64_t)nw * (fl == kInt8 ? 2048 : 4096);
+    const int64_t red = (fl == kInt8) ? red_bytes : std::max<int64_t>(red_bytes - front, 0);
+    cap -= front;
     const int64_t whole = round_up(ksps, wd);
-    if (whole * B * 64 <= std::min(cap, pass_bytes)) {
+    bool ok = true;
+    if (whole * rows * 64 <= std::min(cap, pass_bytes)) {
         kc = whole;
-        lds = std::max(kc * B * 64, red_bytes);
-        return true;
+        lds = std::max(kc * rows * 64, red);
+    } else {
+        kc = (std::min(cap / 2, pass_bytes) / (rows * 64)) / wd * wd;
+        if (kc < wd) kc = (cap / 2 / (rows * 64) >= wd) ? wd : 0;    // a round needs more than one pass
+        if (kc >= whole) {                                           // fits in one buffer after all
+            kc = whole;
+            lds = std::max(kc * rows * 64, red);
+            ok = kc * rows * 64 <= cap;
+        } else {
+            lds = std::max(2 * kc * rows * 64, red);
+            ok = kc >= wd;
+        }
     }
-    kc = (std::min(cap / 2, pass_bytes) / (B * 64)) / wd * wd;
-    if (kc < wd) kc = (cap / 2 / (B * 64) >= wd) ? wd : 0;       // a round needs more than one pass
-    if (kc >= whole) {                                           // fits in one buffer after all
-        kc = whole;
-        lds = std::max(kc * B * 64, red_bytes);
-        return kc * B * 64 <= cap;
-    }
-    lds = std::max(2 * kc * B * 64, red_bytes);
-    return kc >= wd;
-}
-
-bool chunking(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t red_bytes,
-              int64_t& kc, int64_t& lds, int64_t front)
-{
-    if (front == 0) return chunking_impl(B, ksps, wd, nw, cap, red_bytes, kc, lds);
-    // layer-norm kernel variant: the statistics take `front` bytes ahead of the X buffers, and
-    // every buffer carries its k-steps of gamma and beta as two more rows
-    const bool ok = chunking_impl(B + 2, ksps, wd, nw, cap - front, std::max<int64_t>(red_bytes - front, 0), kc, lds);
     lds += front;
-    return ok;
+    return ok && lds <= cap + front;
 }
 
 sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Plan& pl)
 {
     if (sbi_status s = check_shape(K, N)) return s;
     if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
-    const int64_t KS = ksteps_of(K);
     const int64_t P = ceil_div(N, kPanelN);
 
-    sbi_tuning t = {0, 0, 0, 0, 0, 0, 0};
+    sbi_tuning t = {0, 0, 0, 0, 0, 0, 0, 0};
     if (tune) t = *tune;
     const bool ln = t.layernorm != 0;
+    const bool i8 = t.int8 != 0;
+    const int64_t KS = i8 ? ksteps_of_i8(K) : ksteps_of(K);
+    const Flavour fl = i8 ? kInt8 : (ln ? kLayerNorm : kPlain);
 
     if (t.split_k < 0 || t.blocks < 0 || t.panels < 0 || t.panels > 2) return SBI_ERR_TUNING;
     int path = t.path;
     const bool sk_ok = (K % kChunkK == 0);            // X rows readable as 128-bit pieces
-    if (path == SBI_PATH_AUTO) path = (B <= kAutoStreamBatch && !ln) ? SBI_PATH_STREAM : SBI_PATH_MFMA;
+    if (path == SBI_PATH_AUTO) path = (B <= kAutoStreamBatch && !ln && !i8) ? SBI_PATH_STREAM : SBI_PATH_MFMA;
     // layer-norm in front of the GeMM: matrix-core block kernel only, rows read as 128-bit pieces
     if (ln && (path != SBI_PATH_MFMA || K % kChunkK != 0 || t.panels == 2)) return SBI_ERR_TUNING;
+    // INT8: its own matrix-core kernel, rows read as 32-byte pieces; no layer-norm in front (yet)
+    if (i8 && (path != SBI_PATH_MFMA || K % kI8ChunkK != 0 || t.panels == 2 || ln)) return SBI_ERR_TUNING;
     if (path == SBI_PATH_STREAMK) {
         if (!sk_ok) return SBI_ERR_TUNING;
         return plan_streamk(B, KS * P, P, t, pl);
@@ -153,7 +159,7 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     if (path == SBI_PATH_STREAM && B > kStreamMaxBatch) return SBI_ERR_TUNING;
     if (path == SBI_PATH_MFMA && t.split_k == 0 && t.waves == 0 && t.depth == 0 && t.panels == 0) {
         Plan one;
-        if (sbi_status s = plan_group(B, &K, &N, 1, &one, pl, ln)) return s;
+        if (sbi_status s = plan_group(B, &K, &N, 1, &one, pl, ln, i8)) return s;
         pl.S = one.S; pl.ksps = one.ksps; pl.kc = one.kc; pl.pw = one.pw;
         return SBI_OK;
     }
@@ -166,7 +172,7 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     bool depth_ok = depth == 4 || depth == 8 || (depth == 2 && nw == 4 && path == SBI_PATH_MFMA);
     if (pw == 2) depth_ok = (nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 2);
     if ((nw != 4 && nw != 8) || !depth_ok) return SBI_ERR_TUNING;
-    if (ln && !((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))) return SBI_ERR_TUNING;
+    if ((ln || i8) && !((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))) return SBI_ERR_TUNING;
     int S = t.split_k;
     if (S < 0) return SBI_ERR_TUNING;
     if (S == 0) {
@@ -187,11 +193,11 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
 
     const int64_t wd = (int64_t)nw * depth;
     int64_t kc = 0, lds = 0;
-    if (!chunking(B, ksps, wd, nw, (pw == 2 || ln) ? kMaxLdsWide : kMaxLds, (int64_t)nw * 16 * kRedPitch * 4, kc, lds,
-                  ln ? kLnStatsBytes : 0))
+    if (!chunking(B, ksps, wd, nw, (pw == 2 || ln || i8) ? kMaxLdsWide : kMaxLds, (int64_t)nw * 16 * kRedPitch * 4,
+                  kc, lds, fl))
         return SBI_ERR_TUNING;
 
-    pl.ln = ln;
+    pl.ln = ln; pl.i8 = i8;
     pl.path = path; pl.nw = nw; pl.depth = depth; pl.S = S; pl.pw = pw;
     pl.ksps = (int)ksps; pl.kc = (int)kc;
     pl.grid = (int)(PG * S); pl.block = nw * 64;
@@ -221,6 +227,7 @@ inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintp
 struct GemmArgs {
     const void* Wl; int64_t K, N; const void* X; const void* bias; const void* R; int flags; void* Y;
     const void* gamma; const void* beta; float eps;     // layer-norm of X's rows when gamma != null
+    const void* sw;                                     // INT8: per-column weight scales (binary32 [N])
 };
 
 // Validation of a layer-norm request in front of a GeMM with K input features.
@@ -297,8 +304,9 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
     p.counters = (pl.S > 1) ? reinterpret_cast<unsigned int*>(ws) + panel_base : nullptr;
     p.partials = (pl.S > 1) ? reinterpret_cast<float*>(ws + kCounterBytes + partial_off) : nullptr;
     p.B = (int)B; p.K = (int)a.K; p.N = (int)a.N;
-    p.KS = (int)ksteps_of(a.K); p.P = (int)ceil_div(a.N, kPanelN);
+    p.KS = (int)(pl.i8 ? ksteps_of_i8(a.K) : ksteps_of(a.K)); p.P = (int)ceil_div(a.N, kPanelN);
     p.S = pl.S; p.ksps = pl.ksps; p.kc = pl.kc;
+    p.sw = reinterpret_cast<const float*>(a.sw);
     p.flags = a.flags; p.x_vec = (a.K % 8 == 0) ? 1 : 0;
     // the layer-norm kernel variant reads gamma and beta pieces unconditionally: a problem
     // without layer-norm points them at its X (K readable halfs) and ignores the values
@@ -315,8 +323,11 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
 // Wavefronts per CU that the register file lets the MFMA block kernel keep resident: the vector
 // registers the compiled kernel variants allocate (row blocks MB = ceil(B/16), waves, depth; plain
 // and layer-norm), in granules of 8, against 512 registers per SIMD lane and 4 SIMDs per CU.
-int resident_waves(int mb, int nw, int depth, int pw, bool ln)
+int resident_waves(int mb, int nw, int depth, int pw, bool ln, bool i8)
 {
+    static const int vgpr_i8_w4d2[4] = {108, 132, 200, 216};
+    static const int vgpr_i8_w4d4[4] = {164, 184, 212, 242};
+    static const int vgpr_i8_w8d4[4] = {138, 154, 164, 190};
     static const int vgpr_w4d2[4] = {108, 128, 156, 180};
     static const int vgpr_w4d4[4] = {140, 164, 196, 226};
     static const int vgpr_w8d4[4] = {134, 152, 170, 188};
@@ -326,6 +337,7 @@ int resident_waves(int mb, int nw, int depth, int pw, bool ln)
     static const int vgpr_ln_w8d4[4] = {138, 160, 180, 204};
     const int* tab = (pw == 2) ? vgpr_w8d2p2 : (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);
     if (ln) tab = (nw == 8) ? vgpr_ln_w8d4 : (depth == 2 ? vgpr_ln_w4d2 : vgpr_ln_w4d4);
+    if (i8) tab = (nw == 8) ? vgpr_i8_w8d4 : (depth == 2 ? vgpr_i8_w4d2 : vgpr_i8_w4d4);
     const int v = (tab[std::min(std::max(mb, 1), 4) - 1] + 7) / 8 * 8;
     return 4 * std::min(8, 512 / v);
 }
@@ -337,20 +349,20 @@ int resident_waves(int mb, int nw, int depth, int pw, bool ln)
 // CU can hold at once follow from the LDS each block needs for its X chunks and from the
 // register file.  Returns per-problem plans plus the launch totals in `tot` (nw, depth, lds,
 // grid, ws_bytes).
-sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot, bool ln)
+sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot, bool ln, bool i8)
 {
     if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
     const int mb = (int)ceil_div(B, 16);
     int64_t KS[kMaxGroup], P[kMaxGroup], maxKS = 0, panels = 0;
     for (int g = 0; g < G; ++g) {
         if (sbi_status s = check_shape(Ks[g], Ns[g])) return s;
-        KS[g] = ksteps_of(Ks[g]); P[g] = ceil_div(Ns[g], kPanelN);
+        KS[g] = i8 ? ksteps_of_i8(Ks[g]) : ksteps_of(Ks[g]); P[g] = ceil_div(Ns[g], kPanelN);
         maxKS = std::max(maxKS, KS[g]); panels += P[g];
     }
     if (panels > kCounterBytes / 4) return SBI_ERR_SHAPE;
     constexpr int64_t kLdsPerCU = 160 * 1024;
     const int64_t lds_caps[4] = {16 * 1024, 32 * 1024, kMaxLds, kMaxLdsWide};
-    const int64_t front = ln ? kLnStatsBytes : 0;
+    const Flavour fl = i8 ? kInt8 : (ln ? kLayerNorm : kPlain);
     // (waves, depth, panels per block) candidates; two-panel blocks only pay off for B > 16
     const int shapes[4][3] = {{4, 4, 1}, {8, 4, 1}, {4, 2, 1}, {8, 2, 2}};
 
@@ -359,13 +371,13 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
     double best = 0.0;
     for (const auto& shp : shapes) {
         const int nw = shp[0], depth = shp[1], pw = shp[2];
-        if (pw == 2 && (mb < 2 || ln)) continue;
+        if (pw == 2 && (mb < 2 || ln || i8)) continue;
         const int64_t wd = (int64_t)nw * depth;
         const int64_t red_bytes = (int64_t)nw * 16 * kRedPitch * 4;
         for (int64_t cap : lds_caps) {
             // the wide budget belongs to two-panel blocks, and to layer-norm blocks (their statistics
             // take the room that a batch of 64 needs for two X buffers within 64 KiB)
-            if ((cap > kMaxLds) != (pw == 2) && !(ln && cap > kMaxLds)) continue;
+            if ((cap > kMaxLds) != (pw == 2) && !((ln || i8) && cap > kMaxLds)) continue;
             // block sizes worth a look: the ones at which the split of the longest problem changes
             int64_t lastT = 0;
             for (int64_t smax = std::min<int64_t>(ceil_div(maxKS, wd), 64); smax >= 1; --smax) {
@@ -379,18 +391,18 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
                     const int64_t S = ceil_div(KS[g], T);
                     const int64_t ksps = ceil_div(KS[g], S);
                     int64_t kc = 0, l = 0;
-                    ok = chunking(B, ksps, wd, nw, cap, red_bytes, kc, l, front);
+                    ok = chunking(B, ksps, wd, nw, cap, red_bytes, kc, l, fl);
                     if (!ok) break;
                     blocks += ceil_div(P[g], pw) * S;
                     work += ceil_div(P[g], pw) * S * ksps * pw;
                     lds = std::max(lds, l);
                     chunks = std::max(chunks, ceil_div(ksps, kc));
-                    if (ceil_div(ksps, kc) > 1 && kc * (B + (ln ? 2 : 0)) * 64 > (int64_t)nw * 64 * 64) slow_stage = true;
+                    if (ceil_div(ksps, kc) > 1 && kc * (B + (ln ? 2 : 0)) * 64 > (int64_t)nw * (i8 ? 2048 : 4096)) slow_stage = true;
                     if (S > 1) partial += (double)(P[g] * S) * (double)B * 512.0;
                 }
                 if (!ok) continue;
                 const int64_t fit = std::max<int64_t>(1, std::min<int64_t>(kLdsPerCU / lds,
-                                                                           resident_waves(mb, nw, depth, pw, ln) / nw));
+                                                                           resident_waves(mb, nw, depth, pw, ln, i8) / nw));
                 // A CU time-slices its share of HBM bandwidth over the blocks it holds, so what counts is
                 // how many blocks the busiest CU works through (quantised), each costing its stream plus
                 // a start/finish overhead; measured on MI355X (h=4096 layer, 512 MiB single GeMMs):
@@ -406,6 +418,7 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
                 const double stream = (double)work / (double)blocks * (1.0 + 0.6 * std::max(0.0, x_ratio - 0.2));
                 double overhead = 9.0 + 0.15 * (double)(chunks - 1) + (conc == 1 ? 4.5 : 0.0);
                 if (ln) overhead += (conc == 1 ? 16.0 : 4.0) * (double)(ceil_div(B, 2 * nw) * ceil_div(maxKS, 128));
+                if (i8) overhead += (conc == 1 ? 8.0 : 2.0) * (double)(ceil_div(B, 2 * nw) * ceil_div(maxKS, 64));
                 double cost = (double)per_cu_blocks * (stream + overhead) * (busy >= 0.75 ? 1.0 : 0.75 / busy) +
                               partial / kNumCU / 4096.0;
                 const int64_t inflight = conc * nw * depth;
@@ -427,7 +440,7 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
             for (int g = 0; g < G; ++g) {
                 const int64_t S = ceil_div(KS[g], bestT), ksps = ceil_div(KS[g], S);
                 int64_t kc = 0, l = 0;
-                if (!chunking(B, ksps, (int64_t)a * b, a, cap, (int64_t)a * 16 * kRedPitch * 4, kc, l, front)) return SBI_ERR_TUNING;
+                if (!chunking(B, ksps, (int64_t)a * b, a, cap, (int64_t)a * 16 * kRedPitch * 4, kc, l, fl)) return SBI_ERR_TUNING;
             }
         }
     }
@@ -442,8 +455,8 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
         const int64_t S = ceil_div(KS[g], bestT);
         const int64_t ksps = ceil_div(KS[g], S);
         int64_t kc = 0, l = 0;
-        chunking(B, ksps, wd, nw, best_cap, (int64_t)nw * 16 * kRedPitch * 4, kc, l, front);
-        pl.path = SBI_PATH_MFMA; pl.nw = nw; pl.depth = depth; pl.pw = pw; pl.ln = ln;
+        chunking(B, ksps, wd, nw, best_cap, (int64_t)nw * 16 * kRedPitch * 4, kc, l, fl);
+        pl.path = SBI_PATH_MFMA; pl.nw = nw; pl.depth = depth; pl.pw = pw; pl.ln = ln; pl.i8 = i8;
         pl.S = (int)ceil_div(KS[g], ksps); pl.ksps = (int)ksps; pl.kc = (int)kc;
         pl.grid = (int)(ceil_div(P[g], pw) * pl.S); pl.block = nw * 64;
         pl.lds = l;
@@ -487,6 +500,14 @@ sbi_status launch_block_group(const GemmArgs* a, const Plan* pls, const Plan& to
             const int64_t buffers = pls[g].kc >= pls[g].ksps ? 1 : 2;
             if (tot.lds < kLnStatsBytes + buffers * pls[g].kc * (B + 2) * 64) return SBI_ERR_TUNING;
         }
+    if (tot.i8) {                     // scales through the reduction, then X buffers or the reduction tile
+        for (int g = 0; g < G; ++g) {
+            const int64_t buffers = pls[g].kc >= pls[g].ksps ? 1 : 2;
+            if (tot.lds < kLnStatsBytes + std::max<int64_t>(buffers * pls[g].kc * B * 64, (int64_t)tot.nw * 16 * kRedPitch * 4))
+                return SBI_ERR_TUNING;
+        }
+        return launch_i8(gp, tot.nw, tot.depth, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
+    }
     return launch_mfma(gp, tot.nw, tot.depth, tot.pw, tot.ln, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
 }
 
@@ -509,7 +530,7 @@ size_t sbi_gemm_workspace_bytes(int64_t B, int64_t K, int64_t N)
 
 size_t sbi_gemm_ln_workspace_bytes(int64_t B, int64_t K, int64_t N)
 {
-    const sbi_tuning t = {0, 0, 0, 0, 0, 0, 1};
+    const sbi_tuning t = {0, 0, 0, 0, 0, 0, 1, 0};
     Plan pl;
     if (make_plan(B, K, N, &t, pl) != SBI_OK) return 0;
     return (size_t)pl.ws_bytes;
@@ -546,7 +567,7 @@ sbi_status sbi_gemm_unlayout_weights(const void* W_laid_out, int64_t K, int64_t 
     return launch_unlayout(W_laid_out, K, N, W_rowmajor, (hipStream_t)hip_stream) == 0 ? SBI_OK : SBI_ERR_HIP;
 }
 
-sbi_status sbi_gemm_layout_check(const void* W_laid_out, int64_t K, int64_t N, void* hip_stream)
+static sbi_status layout_check_impl(const void* W_laid_out, int64_t K, int64_t N, void* hip_stream, bool want_i8)
 {
     if (!W_laid_out) return SBI_ERR_NULL;
     if (sbi_status s = check_shape(K, N)) return s;
@@ -556,26 +577,42 @@ sbi_status sbi_gemm_layout_check(const void* W_laid_out, int64_t K, int64_t N, v
     hipStream_t st = (hipStream_t)hip_stream;
     if (hipMemcpyAsync(&h, W_laid_out, sizeof h, hipMemcpyDeviceToHost, st) != hipSuccess) return SBI_ERR_HIP;
     if (hipStreamSynchronize(st) != hipSuccess) return SBI_ERR_HIP;
-    const bool ok = h.magic == kMagic && h.version == kLayoutVersion && h.K == K && h.N == N &&
-                    h.KS == ksteps_of(K) && h.P == ceil_div(N, kPanelN) &&
-                    h.tile_n == kTileN && h.tile_k == kTileK && h.panel_tiles == kPanelTiles &&
-                    h.chunk_k == kChunkK;
-    return ok ? SBI_OK : SBI_ERR_LAYOUT_MISMATCH;
+    const bool common = h.magic == kMagic && h.version == kLayoutVersion && h.K == K && h.N == N &&
+                        h.P == ceil_div(N, kPanelN) && h.tile_n == kTileN && h.panel_tiles == kPanelTiles;
+    const bool f16 = common && h.KS == ksteps_of(K) && h.tile_k == kTileK && h.chunk_k == kChunkK;
+    const bool i8 = common && h.KS == ksteps_of_i8(K) && h.tile_k == kI8TileK && h.chunk_k == kI8ChunkK;
+    return (want_i8 ? i8 : f16) ? SBI_OK : SBI_ERR_LAYOUT_MISMATCH;
+}
+
+sbi_status sbi_gemm_layout_check(const void* W_laid_out, int64_t K, int64_t N, void* hip_stream)
+{
+    return layout_check_impl(W_laid_out, K, N, hip_stream, false);
+}
+
+sbi_status sbi_gemm_i8_layout_check(const void* W_laid_out, int64_t K, int64_t N, void* hip_stream)
+{
+    return layout_check_impl(W_laid_out, K, N, hip_stream, true);
 }
 
 static sbi_status gemm_impl(const void* W_laid_out, int64_t K, int64_t N,
                             const void* X, int64_t B, const sbi_layernorm* ln,
                             const void* bias, const void* residual, sbi_epilogue epi,
                             void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
-                            const sbi_tuning* tuning)
+                            const sbi_tuning* tuning, const void* w_scales = nullptr, bool i8 = false)
 {
     int flags = 0;
     if (sbi_status s = check_gemm_args(W_laid_out, K, N, X, B, bias, residual, (int)epi, Y, flags)) return s;
-    sbi_tuning t = {0, 0, 0, 0, 0, 0, 0};
+    sbi_tuning t = {0, 0, 0, 0, 0, 0, 0, 0};
     if (tuning) t = *tuning;
     t.layernorm = ln ? 1 : 0;
+    t.int8 = i8 ? 1 : 0;
     if (ln)
         if (sbi_status s = check_layernorm(ln->gamma, ln->beta, ln->eps, K)) return s;
+    if (i8) {
+        if (!w_scales) return SBI_ERR_NULL;
+        if (K % kI8ChunkK != 0) return SBI_ERR_SHAPE;
+        if (!aligned(w_scales, 4)) return SBI_ERR_ALIGN;
+    }
     Plan pl;
     if (sbi_status s = make_plan(B, K, N, &t, pl)) return s;
     if (pl.ws_bytes > 0) {
@@ -583,7 +620,7 @@ static sbi_status gemm_impl(const void* W_laid_out, int64_t K, int64_t N,
         if (!aligned(workspace, 256)) return SBI_ERR_ALIGN;
     }
     hipStream_t st = (hipStream_t)hip_stream;
-    GemmArgs a = {W_laid_out, K, N, X, bias, residual, flags, Y, nullptr, nullptr, 0.0f};
+    GemmArgs a = {W_laid_out, K, N, X, bias, residual, flags, Y, nullptr, nullptr, 0.0f, w_scales};
     if (pl.path == SBI_PATH_STREAMK) return launch_group(&a, 1, B, pl, workspace, st);
     if (ln) { a.gamma = ln->gamma; a.beta = ln->beta; a.eps = ln->eps; }
     Plan one = pl;
@@ -599,7 +636,7 @@ sbi_status sbi_gemm_ex(const void* W_laid_out, int64_t K, int64_t N,
                        void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
                        const sbi_tuning* tuning)
 {
-    if (tuning && tuning->layernorm) return SBI_ERR_TUNING;      // layer-norm needs its parameters: sbi_gemm_ln
+    if (tuning && (tuning->layernorm || tuning->int8)) return SBI_ERR_TUNING;   // those have entry points of their own
     return gemm_impl(W_laid_out, K, N, X, B, nullptr, bias, residual, epi, Y, workspace, workspace_bytes,
                      hip_stream, tuning);
 }
@@ -620,8 +657,54 @@ sbi_status sbi_gemm_ln(const void* W_laid_out, int64_t K, int64_t N,
                        const sbi_tuning* tuning)
 {
     if (!ln) return SBI_ERR_NULL;
+    if (tuning && tuning->int8) return SBI_ERR_TUNING;
     return gemm_impl(W_laid_out, K, N, X, B, ln, bias, residual, epi, Y, workspace, workspace_bytes,
                      hip_stream, tuning);
+}
+
+size_t sbi_gemm_i8_layout_bytes(int64_t K, int64_t N)
+{
+    if (check_shape(K, N) != SBI_OK) return 0;
+    return (size_t)kHeaderBytes + (size_t)ksteps_of_i8(K) * (size_t)ceil_div(N, kPanelN) * 4096u;
+}
+
+size_t sbi_gemm_i8_workspace_bytes(int64_t B, int64_t K, int64_t N)
+{
+    const sbi_tuning t = {0, 0, 0, 0, 0, 0, 0, 1};
+    Plan pl;
+    if (make_plan(B, K, N, &t, pl) != SBI_OK) return 0;
+    return (size_t)pl.ws_bytes;
+}
+
+sbi_status sbi_gemm_i8_quantize_weights(const void* W_rowmajor, int64_t K, int64_t N,
+                                        void* Wq_rowmajor, void* w_scales, void* hip_stream)
+{
+    if (!W_rowmajor || !Wq_rowmajor || !w_scales) return SBI_ERR_NULL;
+    if (sbi_status s = check_shape(K, N)) return s;
+    if (!aligned(W_rowmajor, 2) || !aligned(w_scales, 4)) return SBI_ERR_ALIGN;
+    return launch_quantize_weights(W_rowmajor, K, N, Wq_rowmajor, w_scales, (hipStream_t)hip_stream) == 0
+               ? SBI_OK : SBI_ERR_HIP;
+}
+
+sbi_status sbi_gemm_i8_layout_weights(const void* Wq_rowmajor, int64_t K, int64_t N,
+                                      void* W_laid_out, size_t laid_out_bytes, void* hip_stream)
+{
+    if (!Wq_rowmajor || !W_laid_out) return SBI_ERR_NULL;
+    if (sbi_status s = check_shape(K, N)) return s;
+    if (!aligned(W_laid_out, 256)) return SBI_ERR_ALIGN;
+    if (laid_out_bytes < sbi_gemm_i8_layout_bytes(K, N)) return SBI_ERR_LAYOUT_MISMATCH;
+    return launch_layout_i8(Wq_rowmajor, K, N, W_laid_out, (hipStream_t)hip_stream) == 0 ? SBI_OK : SBI_ERR_HIP;
+}
+
+sbi_status sbi_gemm_i8(const void* W_laid_out, const void* w_scales, int64_t K, int64_t N,
+                       const void* X, int64_t B,
+                       const void* bias, const void* residual, sbi_epilogue epi,
+                       void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
+                       const sbi_tuning* tuning)
+{
+    if (tuning && tuning->layernorm) return SBI_ERR_TUNING;
+    return gemm_impl(W_laid_out, K, N, X, B, nullptr, bias, residual, epi, Y, workspace, workspace_bytes,
+                     hip_stream, tuning, w_scales, true);
 }
 
 static sbi_status layer_check(const sbi_layer* L, int64_t B)

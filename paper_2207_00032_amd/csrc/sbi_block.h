@@ -279,11 +279,12 @@ __device__ __forceinline__ void load_step(u32x4 (&slot)[kPanelTiles * PW], const
 // once for 128 columns - what larger batches need, where X traffic rivals the weight stream.
 // LN: the layer-norm kernel variant; with p.ln set every X buffer also carries its k-steps of
 // gamma and beta (see XStage) and op.step receives their address as well.
-template <int NW, int DEPTH, int PW, bool LN, class Op>
-__device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op& op, int tid, int wave,
-                                             int lane, int panel, int64_t pstride, int ks0, int ks1)
+// Stage: how X reaches LDS (XStage for fp16 operands, XStageI8 for int8 codes); both fill
+// 64 bytes per batch row and k-step, so the addressing below is the same.
+template <int NW, int DEPTH, int PW, bool LN, class Stage, class Op>
+__device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Stage& xst, Op& op, int tid,
+                                             int wave, int lane, int panel, int64_t pstride, int ks0, int ks1)
 {
-    constexpr int NT = NW * 64;
     constexpr int RS = NW * DEPTH;                                 // k-steps a block consumes per round
     constexpr int kStepUnits = kPanelTiles * 64;                  // 16-byte units per k-step of a panel
     const int nks = ks1 - ks0;                                     // >= 1
@@ -296,7 +297,6 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op&
     const int xbuf = p.kc * (xblock + 2 * eblock);                 // 16-byte units per X buffer
 
     u32x4 ring[DEPTH][kPanelTiles * PW];
-    XStage<NT, 4, LN> xst;                                             // covers NT*64 bytes of X per chunk without a second pass
     xst.request(p, ks0, min(nks, p.kc), tid);
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
@@ -339,6 +339,137 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Op&
     }
 }
 
+// ---- INT8 path (paper Sec. III-D "Support for Different Data Types": INT8 GeMM with the
+// quantisation fused in front and the de-quantisation in the epilogue) -----------------------
+// Symmetric per-row quantisation of the activations, decided in binary32 exactly as follows:
+//   amax = max_k |x_k|,  inv = 127 / amax,  scale = amax / 127   (amax = 0: inv = scale = 0)
+//   code = clamp(rint(x * inv), -127, 127)                        (rint: ties to even)
+// Every block computes (inv, scale) of all B rows before its weight stream starts (one pass,
+// two rows per wave at a time), results in the first kLnStatsBytes of LDS.
+template <int NW>
+__device__ __forceinline__ void i8_stats(const GemmParams& p, floatx2* stats, int wave, int lane)
+{
+    constexpr int U = 8;
+    const int pieces = p.K / kChunkK;
+    for (int r0 = wave; r0 < p.B; r0 += 2 * NW) {
+        const bool two = r0 + NW < p.B;
+        const _Float16* row0 = p.X + (int64_t)r0 * p.K;
+        const _Float16* row1 = p.X + (int64_t)(two ? r0 + NW : r0) * p.K;
+        float m0 = 0.f, m1 = 0.f;
+        for (int c0 = 0; c0 < pieces; c0 += 64 * U) {
+            u32x4 h0[U], h1[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = min(c0 + u * 64 + lane, pieces - 1) * kChunkK;     // a clamped piece is re-read: harmless for a maximum
+                h0[u] = *reinterpret_cast<const u32x4*>(row0 + c);
+                h1[u] = *reinterpret_cast<const u32x4*>(row1 + c);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const half8 a = __builtin_bit_cast(half8, h0[u]);
+                const half8 b = __builtin_bit_cast(half8, h1[u]);
+#pragma unroll
+                for (int e = 0; e < kChunkK; ++e) {
+                    m0 = fmaxf(m0, fabsf((float)a[e]));
+                    m1 = fmaxf(m1, fabsf((float)b[e]));
+                }
+            }
+        }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            m0 = fmaxf(m0, __shfl_xor(m0, m, 64));
+            m1 = fmaxf(m1, __shfl_xor(m1, m, 64));
+        }
+        if (lane == 0) {
+            stats[r0] = (m0 > 0.f) ? floatx2{127.0f / m0, m0 / 127.0f} : floatx2{0.f, 0.f};
+            if (two) stats[r0 + NW] = (m1 > 0.f) ? floatx2{127.0f / m1, m1 / 127.0f} : floatx2{0.f, 0.f};
+        }
+    }
+}
+
+// 16 halfs (two 128-bit pieces) -> 16 int8 codes in one 128-bit piece
+__device__ __forceinline__ u32x4 quantize16(u32x4 lo, u32x4 hi, float inv)
+{
+    const half8 a = __builtin_bit_cast(half8, lo);
+    const half8 b = __builtin_bit_cast(half8, hi);
+    unsigned int w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const float x = (e < 8) ? (float)a[e & 7] : (float)b[e & 7];
+        float r = rintf(x * inv);
+        r = fminf(fmaxf(r, -127.0f), 127.0f);
+        w[e >> 2] |= ((unsigned int)(int)r & 0xffu) << (8 * (e & 3));
+    }
+    return u32x4{w[0], w[1], w[2], w[3]};
+}
+
+// Staging of k-steps [cb, cb+cn) (64 k each) of X as int8 codes: same LDS order as XStage
+// (piece (ks, g) of row b at ((ks - cb)*4 + g)*B + b, here 16 codes = k 16g..16g+15), same
+// request/commit split; a piece needs two 128-bit reads of fp16.  Needs K % 16 == 0.
+template <int NT, int XU>
+struct XStageI8 {
+    u32x4 buf[XU][2];
+
+    __device__ __forceinline__ void request(const GemmParams& p, int cb, int cn, int tid)
+    {
+        const int nc = cn * 4;
+        const int items = nc * p.B;
+#pragma unroll
+        for (int u = 0; u < XU; ++u) {
+            const int idx = min(tid + u * NT, items - 1);
+            const int b = idx / nc;
+            const int c = idx - b * nc;
+            const int k = min(cb * 64 + c * 16, p.K - 16);
+            const u32x4* src = reinterpret_cast<const u32x4*>(p.X + (int64_t)b * p.K + k);
+            buf[u][0] = src[0];
+            buf[u][1] = src[1];
+        }
+    }
+
+    __device__ __forceinline__ void commit(const GemmParams& p, u32x4* xs, int cb, int cn, int tid)
+    {
+        const int nc = cn * 4;
+        const int items = nc * p.B;
+#pragma unroll
+        for (int u = 0; u < XU; ++u) {
+            const int idx = tid + u * NT;
+            if (idx < items) {
+                const int b = idx / nc;
+                const int c = idx - b * nc;
+                const bool inside = cb * 64 + c * 16 < p.K;
+                const u32x4 q = quantize16(buf[u][0], buf[u][1], p_stats[b][0]);
+                xs[c * p.B + b] = inside ? q : u32x4{0u, 0u, 0u, 0u};
+            }
+        }
+        for (int base = NT * XU; base < items; base += NT * XU) {
+            u32x4 v[XU][2];
+#pragma unroll
+            for (int u = 0; u < XU; ++u) {
+                const int idx = min(base + tid + u * NT, items - 1);
+                const int b = idx / nc;
+                const int c = idx - b * nc;
+                const int k = min(cb * 64 + c * 16, p.K - 16);
+                const u32x4* src = reinterpret_cast<const u32x4*>(p.X + (int64_t)b * p.K + k);
+                v[u][0] = src[0];
+                v[u][1] = src[1];
+            }
+#pragma unroll
+            for (int u = 0; u < XU; ++u) {
+                const int idx = base + tid + u * NT;
+                if (idx < items) {
+                    const int b = idx / nc;
+                    const int c = idx - b * nc;
+                    const bool inside = cb * 64 + c * 16 < p.K;
+                    const u32x4 q = quantize16(v[u][0], v[u][1], p_stats[b][0]);
+                    xs[c * p.B + b] = inside ? q : u32x4{0u, 0u, 0u, 0u};
+                }
+            }
+        }
+    }
+
+    const floatx2* p_stats;     // the rows' (inv, scale), set by the kernel before the first commit
+};
+
 // A pair of partial sums travels as one 64-bit device-scope access (see finish_split_k).
 __device__ __forceinline__ void store_partial(float* dst, float s0, float s1)
 {
@@ -357,11 +488,19 @@ __device__ __forceinline__ void load_partial(const float* src, float& s0, float&
 }
 
 // After every wave has written its 16-row x 64-column partial tile to `red`
-// ([wave][16][kRedPitch] floats), sum over waves and either finish the rows (S == 1) or
+// ([wave][16][kRedPitch] 32-bit values), sum over waves and either finish the rows (S == 1) or
 // park them in the workspace for the cross-block reduction.  mb selects rows mb*16..+15.
-template <int NW>
+// I8: the values are int32 sums of code products: added as integers (exactly), de-quantised
+// with the row's and the column's scale right before the epilogue; `stats` holds the rows'
+// (inv, scale).
+__device__ __forceinline__ float dequant(const GemmParams& p, int acc, int b, int n, const floatx2* stats)
+{
+    return (float)acc * (stats[b][1] * p.sw[min(n, p.N - 1)]);
+}
+
+template <int NW, bool I8 = false>
 __device__ __forceinline__ void reduce_rows(const GemmParams& p, const float* red, int mb,
-                                            int panel, int split, int tid)
+                                            int panel, int split, int tid, const floatx2* stats = nullptr)
 {
     constexpr int NT = NW * 64;
     for (int item = tid; item < 16 * 32; item += NT) {
@@ -370,17 +509,27 @@ __device__ __forceinline__ void reduce_rows(const GemmParams& p, const float* re
         const int b = mb * 16 + bl;
         if (b >= p.B) continue;
         float s0 = 0.f, s1 = 0.f;
+        int i0 = 0, i1 = 0;
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
             const floatx2 v = *reinterpret_cast<const floatx2*>(red + (w * 16 + bl) * kRedPitch + c2);
-            s0 += v[0];
-            s1 += v[1];
+            if constexpr (I8) {
+                const float f0 = v[0], f1 = v[1];        // (a bit cast straight from a vector element picks element 0)
+                i0 += __builtin_bit_cast(int, f0);
+                i1 += __builtin_bit_cast(int, f1);
+            } else {
+                s0 += v[0];
+                s1 += v[1];
+            }
         }
+        const int n = panel * kPanelN + c2;
         if (p.S == 1) {
-            store_pair(p, b, panel * kPanelN + c2, s0, s1);
+            if constexpr (I8) store_pair(p, b, n, dequant(p, i0, b, n, stats), dequant(p, i1, b, n + 1, stats));
+            else store_pair(p, b, n, s0, s1);
         } else {
             float* dst = p.partials + (((int64_t)panel * p.S + split) * p.B + b) * kPanelN + c2;
-            store_partial(dst, s0, s1);
+            if constexpr (I8) store_partial(dst, __builtin_bit_cast(float, i0), __builtin_bit_cast(float, i1));
+            else store_partial(dst, s0, s1);
         }
     }
 }
@@ -395,8 +544,9 @@ __device__ __forceinline__ void reduce_rows(const GemmParams& p, const float* re
 // be acknowledged before its arrival is counted, and the last block reads only after it
 // has seen the full count.  A device-wide release fence per block would write back the whole
 // L2 and serialise the grid (measured: about 0.1 us per block).
-template <int NT>
-__device__ __forceinline__ void finish_split_k(const GemmParams& p, int panel, int tid, int* s_flag)
+template <int NT, bool I8 = false>
+__device__ __forceinline__ void finish_split_k(const GemmParams& p, int panel, int tid, int* s_flag,
+                                               const floatx2* stats = nullptr)
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // wait for this wave's partial stores
     __syncthreads();
@@ -413,13 +563,21 @@ __device__ __forceinline__ void finish_split_k(const GemmParams& p, int panel, i
         const int b = item >> 5;
         const int c2 = (item & 31) * 2;
         float s0 = 0.f, s1 = 0.f;
+        int i0 = 0, i1 = 0;
         for (int s = 0; s < p.S; ++s) {
             float v0, v1;
             load_partial(base + ((int64_t)s * p.B + b) * kPanelN + c2, v0, v1);
-            s0 += v0;
-            s1 += v1;
+            if constexpr (I8) {
+                i0 += __builtin_bit_cast(int, v0);
+                i1 += __builtin_bit_cast(int, v1);
+            } else {
+                s0 += v0;
+                s1 += v1;
+            }
         }
-        store_pair(p, b, panel * kPanelN + c2, s0, s1);
+        const int n = panel * kPanelN + c2;
+        if constexpr (I8) store_pair(p, b, n, dequant(p, i0, b, n, stats), dequant(p, i1, b, n + 1, stats));
+        else store_pair(p, b, n, s0, s1);
     }
     if (tid == 0)
         __hip_atomic_store(p.counters + panel, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -62,6 +62,7 @@ struct GemmParams {
     const _Float16* ln_gamma;  // [K]; in a launch of the layer-norm kernel variant always readable
     const _Float16* ln_beta;   // [K]    (problems with ln == 0 point both at X)
     float ln_eps;
+    const float* sw;           // INT8 path: per-column weight scales [N]
 #ifdef SBI_TRACE
     unsigned long long* trace; // development builds: 4 timestamps per block
 #endif
@@ -106,6 +107,12 @@ struct SkParams {
 int launch_streamk(const SkParams& p, int waves, int depth, int grid, hipStream_t st);
 int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, bool layernorm, size_t lds_bytes,
                 hipStream_t st);
+int launch_i8(const GroupParams& gp, int waves, int depth, size_t lds_bytes, hipStream_t st);
+int launch_layout_i8(const void* Wq, int64_t K, int64_t N, void* out, hipStream_t st);
+int launch_quantize_weights(const void* W, int64_t K, int64_t N, void* Wq, void* scales, hipStream_t st);
+constexpr int kI8TileK = 64;                         // k per k-step of the int8 layout
+constexpr int kI8ChunkK = 16;                        // consecutive k one lane owns (16 bytes)
+inline int64_t ksteps_of_i8(int64_t K) { return ((K + kI8TileK - 1) / kI8TileK + kStepGroup - 1) / kStepGroup * kStepGroup; }
 constexpr int kLnStatsBytes = 512;                   // LDS in front of the X tile: (mean, 1/std) per batch row
 int launch_stream(const GemmParams& p, int waves, int depth, size_t lds_bytes, hipStream_t st);
 int launch_layout(const void* W, int64_t K, int64_t N, void* out, hipStream_t st);

@@ -1,0 +1,213 @@
+// INT8 variant of the small-batch GeMM (paper Sec. III-D, "Support for Different Data Types":
+// an INT8 GeMM with the quantize operation fused in front of it and the de-quantisation fused
+// into its epilogue; Sec. III-C "Leveraging Full Cache-line" gives INT8 its own wider layout).
+//
+// Same structure as the fp16 matrix-core kernel - one block per 64-column panel and k-range, the
+// weights streamed once through a register ring of 128-bit loads - with three differences:
+//   * a k-step is 64 k: a lane's 16 bytes are 16 consecutive k of one column, a 1 KiB tile
+//     (16 columns x 64 k) is the A operand of v_mfma_i32_16x16x64_i8, so the same 4 KiB per
+//     panel k-step carry twice the k and the weight stream is half as long;
+//   * every block first finds the absolute maximum of each of the B rows of X (one pass), then
+//     stages X as int8 codes (symmetric, per row; decided in binary32, see i8_stats);
+//   * sums are int32 and exact, across waves and across the blocks of a split panel; the
+//     de-quantisation acc * (sx[b] * sw[n]) happens once, right before the epilogue.
+#include "sbi_block.h"
+
+namespace sbi {
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+template <int MB>
+struct MfmaI8Op {
+    i32x4 acc[kPanelTiles][MB];
+    int xoff[MB];
+
+    __device__ __forceinline__ void init(int B, int g, int i)
+    {
+#pragma unroll
+        for (int t = 0; t < kPanelTiles; ++t)
+#pragma unroll
+            for (int m = 0; m < MB; ++m) acc[t][m] = i32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int m = 0; m < MB; ++m) xoff[m] = g * B + min(m * 16 + i, B - 1);
+    }
+
+    // A and B operands use the same lane -> k assignment (lane group g: k 16g..16g+15 of the
+    // k-step), which is all the contraction needs.
+    __device__ __forceinline__ void step(const u32x4 (&w)[kPanelTiles], const u32x4* xk, const u32x4*)
+    {
+        i32x4 xf[MB];
+#pragma unroll
+        for (int m = 0; m < MB; ++m) xf[m] = __builtin_bit_cast(i32x4, xk[xoff[m]]);
+#pragma unroll
+        for (int t = 0; t < kPanelTiles; ++t) {
+            const i32x4 wf = __builtin_bit_cast(i32x4, w[t]);
+#pragma unroll
+            for (int m = 0; m < MB; ++m)
+                acc[t][m] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf[m], acc[t][m], 0, 0, 0);
+        }
+    }
+};
+
+// LDS: [0, kLnStatsBytes) the rows' (inv, scale); behind it the X buffers during the stream and
+// the reduction tile afterwards (the scales are still needed then).
+template <int MB, int NW, int DEPTH>
+__global__ __launch_bounds__(NW * 64) void sbi_i8_kernel(const GroupParams gp)
+{
+    constexpr int NT = NW * 64;
+    int gi = 0;
+    while (gi + 1 < gp.G && (int)blockIdx.x >= gp.first_block[gi + 1]) ++gi;
+    const GemmParams& p = gp.g[gi];
+    const int bid = (int)blockIdx.x - gp.first_block[gi];
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    floatx2* stats = reinterpret_cast<floatx2*>(smem_raw);
+    u32x4* xs  = reinterpret_cast<u32x4*>(smem_raw + kLnStatsBytes);
+    float* red = reinterpret_cast<float*>(smem_raw + kLnStatsBytes);
+    __shared__ int s_flag;
+
+    const int tid  = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4;
+    const int i = lane & 15;
+
+    i8_stats<NW>(p, stats, wave, lane);
+    __syncthreads();
+
+    const int panel = bid / p.S;
+    const int split = bid - panel * p.S;
+    const int ks0 = split * p.ksps;
+    const int ks1 = min(p.KS, ks0 + p.ksps);
+
+    MfmaI8Op<MB> op;
+    op.init(p.B, g, i);
+    XStageI8<NT, 2> xst;           // two 32-byte reads per thread in flight: NT*32 bytes of LDS per pass
+    xst.p_stats = stats;
+    stream_panel<NW, DEPTH, 1, false>(p, xs, xst, op, tid, wave, lane, panel, 0, ks0, ks1);
+
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        __syncthreads();               // X buffers / previous pass no longer needed
+#pragma unroll
+        for (int t = 0; t < kPanelTiles; ++t)
+            *reinterpret_cast<i32x4*>(red + (wave * 16 + i) * kRedPitch + t * kTileN + 4 * g) = op.acc[t][m];
+        __syncthreads();
+        reduce_rows<NW, true>(p, red, m, panel, split, tid, stats);
+    }
+    if (p.S > 1) finish_split_k<NT, true>(p, panel, tid, &s_flag, stats);
+}
+
+template <int MB, int NW, int DEPTH>
+static int launch_one(const GroupParams& gp, size_t lds, hipStream_t st)
+{
+    if (lds > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sbi_i8_kernel<MB, NW, DEPTH>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return (int)e;
+    }
+    hipLaunchKernelGGL((sbi_i8_kernel<MB, NW, DEPTH>), dim3(gp.first_block[gp.G]), dim3(NW * 64), lds, st, gp);
+    return (int)hipGetLastError();
+}
+
+template <int NW, int DEPTH>
+static int launch_mb(const GroupParams& gp, size_t lds, hipStream_t st)
+{
+    switch ((gp.g[0].B + 15) / 16) {
+        case 1: return launch_one<1, NW, DEPTH>(gp, lds, st);
+        case 2: return launch_one<2, NW, DEPTH>(gp, lds, st);
+        case 3: return launch_one<3, NW, DEPTH>(gp, lds, st);
+        case 4: return launch_one<4, NW, DEPTH>(gp, lds, st);
+    }
+    return (int)hipErrorInvalidValue;
+}
+
+int launch_i8(const GroupParams& gp, int waves, int depth, size_t lds_bytes, hipStream_t st)
+{
+    if (gp.G < 1 || gp.G > kMaxGroup) return (int)hipErrorInvalidValue;
+    if (waves == 4 && depth == 2) return launch_mb<4, 2>(gp, lds_bytes, st);
+    if (waves == 4 && depth == 4) return launch_mb<4, 4>(gp, lds_bytes, st);
+    if (waves == 8 && depth == 4) return launch_mb<8, 4>(gp, lds_bytes, st);
+    return (int)hipErrorInvalidValue;
+}
+
+// ---- weight preparation (once, at initialisation) ------------------------------------------
+// Pre-layout of int8 codes Wq [K,N] row-major: block (p, ks) writes the 4 KiB of one panel
+// k-step; thread (t, g, i) gathers the 16 codes k = ks*64 + 16g .. +15 of column p*64 + 16t + i
+// and writes them as one 16-byte piece.  Zero beyond K and N.  Block 0 also writes the header.
+__global__ __launch_bounds__(256) void sbi_layout_i8_kernel(const signed char* __restrict__ Wq, int64_t K, int64_t N,
+                                                            int64_t KS, int64_t P, unsigned char* __restrict__ out)
+{
+    const int64_t blk = blockIdx.x;
+    const int64_t pn = blk / KS, ks = blk - pn * KS;
+    const int tid = threadIdx.x;
+    const int t = tid >> 6, lane = tid & 63, g = lane >> 4, i = lane & 15;
+    const int64_t n = pn * kPanelN + t * kTileN + i;
+    const int64_t k0 = ks * kI8TileK + g * kI8ChunkK;
+    unsigned int w[4] = {0u, 0u, 0u, 0u};
+    if (n < N) {
+#pragma unroll
+        for (int e = 0; e < kI8ChunkK; ++e) {
+            const int64_t k = k0 + e;
+            const unsigned int v = (k < K) ? (unsigned int)(unsigned char)Wq[k * N + n] : 0u;
+            w[e >> 2] |= v << (8 * (e & 3));
+        }
+    }
+    u32x4* dst = reinterpret_cast<u32x4*>(out + kHeaderBytes) + (blk * kPanelTiles + t) * 64 + lane;
+    *dst = u32x4{w[0], w[1], w[2], w[3]};
+    if (blk == 0) {
+        constexpr int kHeaderWords = (int)(sizeof(LayoutHeader) / 4);
+        if (tid == 0) {
+            LayoutHeader h;
+            h.magic = kMagic; h.version = kLayoutVersion;
+            h.K = K; h.N = N; h.KS = KS; h.P = P;
+            h.tile_n = kTileN; h.tile_k = kI8TileK; h.panel_tiles = kPanelTiles; h.chunk_k = kI8ChunkK;
+            *reinterpret_cast<LayoutHeader*>(out) = h;
+        } else if (tid >= kHeaderWords && tid < kHeaderBytes / 4) {
+            reinterpret_cast<uint32_t*>(out)[tid] = 0u;
+        }
+    }
+}
+
+int launch_layout_i8(const void* Wq, int64_t K, int64_t N, void* out, hipStream_t st)
+{
+    const int64_t KS = ksteps_of_i8(K), P = (N + kPanelN - 1) / kPanelN;
+    hipLaunchKernelGGL(sbi_layout_i8_kernel, dim3((unsigned)(KS * P)), dim3(256), 0, st,
+                       reinterpret_cast<const signed char*>(Wq), K, N, KS, P, reinterpret_cast<unsigned char*>(out));
+    return (int)hipGetLastError();
+}
+
+// Symmetric per-column quantisation of W [K,N] fp16 -> codes [K,N] int8 + scales [N] binary32,
+// the same decisions as for the activations (amax, inv = 127/amax, rint(w * inv), scale = amax/127).
+// One block per 64 columns: thread (r, c) scans rows r, r+4, ... of column c twice.
+__global__ __launch_bounds__(256) void sbi_quantize_weights_kernel(const _Float16* __restrict__ W, int64_t K, int64_t N,
+                                                                   signed char* __restrict__ Wq, float* __restrict__ scales)
+{
+    __shared__ float s_max[4][64];
+    const int c = threadIdx.x & 63, r = threadIdx.x >> 6;
+    const int64_t n = (int64_t)blockIdx.x * 64 + c;
+    float m = 0.f;
+    if (n < N)
+        for (int64_t k = r; k < K; k += 4) m = fmaxf(m, fabsf((float)W[k * N + n]));
+    s_max[r][c] = m;
+    __syncthreads();
+    const float amax = fmaxf(fmaxf(s_max[0][c], s_max[1][c]), fmaxf(s_max[2][c], s_max[3][c]));
+    const float inv = (amax > 0.f) ? 127.0f / amax : 0.f;
+    if (n < N) {
+        if (r == 0) scales[n] = (amax > 0.f) ? amax / 127.0f : 0.f;
+        for (int64_t k = r; k < K; k += 4) {
+            float q = rintf((float)W[k * N + n] * inv);
+            q = fminf(fmaxf(q, -127.0f), 127.0f);
+            Wq[k * N + n] = (signed char)(int)q;
+        }
+    }
+}
+
+int launch_quantize_weights(const void* W, int64_t K, int64_t N, void* Wq, void* scales, hipStream_t st)
+{
+    hipLaunchKernelGGL(sbi_quantize_weights_kernel, dim3((unsigned)((N + 63) / 64)), dim3(256), 0, st,
+                       reinterpret_cast<const _Float16*>(W), K, N, reinterpret_cast<signed char*>(Wq),
+                       reinterpret_cast<float*>(scales));
+    return (int)hipGetLastError();
+}
+
+}  // namespace sbi

@@ -118,7 +118,8 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
 #endif
     MfmaOp<MB, PW, LN> op;
     op.init(p, stats, g, i);
-    stream_panel<NW, DEPTH, PW, LN>(p, xs, op, tid, wave, lane, panel, pstride, ks0, ks1);
+    XStage<NT, 4, LN> xst;            // covers NT*64 bytes of X per chunk without a second pass
+    stream_panel<NW, DEPTH, PW, LN>(p, xs, xst, op, tid, wave, lane, panel, pstride, ks0, ks1);
 #ifdef SBI_TRACE
     const unsigned long long t_stream = wall_clock64();
 #endif

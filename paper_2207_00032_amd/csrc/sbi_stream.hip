@@ -73,7 +73,8 @@ __global__ __launch_bounds__(NW * 64) void sbi_stream_kernel(const GemmParams p)
 
     DotOp<BT> op;
     op.init(g);
-    stream_panel<NW, DEPTH, 1, false>(p, xs, op, tid, wave, lane, panel, 0, ks0, ks1);
+    XStage<NW * 64, 4, false> xst;
+    stream_panel<NW, DEPTH, 1, false>(p, xs, xst, op, tid, wave, lane, panel, 0, ks0, ks1);
 
     // cross-lane K reduction over the four lane groups, then park the wave's tile in LDS
 #pragma unroll

@@ -35,12 +35,44 @@ static void* layout(const _Float16* W, int64_t K, int64_t N)
         }
     return buf;
 }
+// symmetric int8 codes of n values with stride `stride` (binary32 decisions, as the library documents)
+static float quantize_line(const _Float16* v, int64_t n, int64_t stride, signed char* q)
+{
+    float amax = 0.f;
+    for (int64_t j = 0; j < n; ++j) amax = std::fmax(amax, std::fabs((float)v[j * stride]));
+    if (!(amax > 0.f)) { for (int64_t j = 0; j < n; ++j) q[j * stride] = 0; return 0.f; }
+    const volatile float inv = 127.0f / amax;
+    for (int64_t j = 0; j < n; ++j) {
+        const volatile float pr = (float)v[j * stride] * inv;
+        float r = std::rint(pr);
+        r = std::fmin(std::fmax(r, -127.f), 127.f);
+        q[j * stride] = (signed char)r;
+    }
+    return amax / 127.0f;
+}
+
+static void* layout_i8(const signed char* Wq, int64_t K, int64_t N)
+{
+    const size_t bytes = sbi_gemm_i8_layout_bytes(K, N);
+    unsigned char* buf = (unsigned char*)exact_alloc(256, bytes);
+    memset(buf, 0, bytes);
+    const int64_t KS = (((K + 63) / 64) + 7) / 8 * 8;
+    signed char* out = (signed char*)(buf + 256);
+    for (int64_t k = 0; k < K; ++k)
+        for (int64_t n = 0; n < N; ++n) {
+            const int64_t p = n / 64, t = (n % 64) / 16, i = n % 16, ks = k / 64, g = (k % 64) / 16, e = k % 16;
+            out[((((p * KS + ks) * 4 + t) * 64 + (g * 16 + i)) * 16) + e] = Wq[k * N + n];
+        }
+    return buf;
+}
+
 int main(int argc, char** argv)
 {
     if (argc < 9) { fprintf(stderr, "usage: B K N waves depth split panels ln\n"); return 9; }
     const int B = atoi(argv[1]); const int64_t K = atoll(argv[2]), N = atoll(argv[3]);
     sbi_tuning t = {SBI_PATH_MFMA, atoi(argv[6]), atoi(argv[4]), atoi(argv[5]), 0, atoi(argv[7]), 0};
-    const int ln = atoi(argv[8]);
+    const int mode = atoi(argv[8]);         // 0 plain, 1 layer-norm, 2 int8
+    const int ln = mode == 1, i8 = mode == 2;
     if (t.waves == 0) t.path = SBI_PATH_AUTO;
     std::mt19937 rng(7);
     _Float16* W = halfs((size_t)K * N, rng, 0.02f);
@@ -52,7 +84,19 @@ int main(int argc, char** argv)
     _Float16* Y = (_Float16*)exact_alloc(4, (size_t)B * N * 2);
     memset(Y, 0xFF, (size_t)B * N * 2);
     sbi_plan pl;
-    sbi_tuning tp = t; tp.layernorm = ln;
+    sbi_tuning tp = t; tp.layernorm = ln; tp.int8 = i8;
+    std::vector<signed char> Wq, Xq;
+    std::vector<float> sw, sx;
+    void* Wl8 = nullptr;
+    float* swd = nullptr;
+    if (i8) {
+        Wq.resize((size_t)K * N); sw.resize(N); Xq.resize((size_t)B * K); sx.resize(B);
+        for (int64_t n = 0; n < N; ++n) sw[n] = quantize_line(W + n, K, N, Wq.data() + n);
+        for (int b = 0; b < B; ++b) sx[b] = quantize_line(X + (size_t)b * K, K, 1, Xq.data() + (size_t)b * K);
+        Wl8 = layout_i8(Wq.data(), K, N);
+        swd = (float*)exact_alloc(4, (size_t)N * 4);
+        memcpy(swd, sw.data(), (size_t)N * 4);
+    }
     sbi_status st = sbi_gemm_plan(B, K, N, &tp, &pl);
     if (st) { fprintf(stderr, "plan: %s\n", sbi_status_string(st)); return 1; }
     fprintf(stderr, "B=%d K=%ld N=%ld ln=%d: w=%d d=%d pw=%d S=%d ksps=%d kc=%d grid=%d lds=%ld ws=%ld\n", B, (long)K, (long)N, ln,
@@ -61,7 +105,8 @@ int main(int argc, char** argv)
     void* ws = exact_alloc(256, wsb ? wsb : 256);
     memset(ws, 0, wsb ? wsb : 256);
     sbi_layernorm l = {g1, b1, 1e-5f};
-    if (ln) st = sbi_gemm_ln(Wl, K, N, X, B, &l, bias, R, SBI_EPI_BIAS_RESIDUAL, Y, ws, wsb, nullptr, &t);
+    if (i8) st = sbi_gemm_i8(Wl8, swd, K, N, X, B, bias, R, SBI_EPI_BIAS_RESIDUAL, Y, ws, wsb, nullptr, &t);
+    else if (ln) st = sbi_gemm_ln(Wl, K, N, X, B, &l, bias, R, SBI_EPI_BIAS_RESIDUAL, Y, ws, wsb, nullptr, &t);
     else st = sbi_gemm_ex(Wl, K, N, X, B, bias, R, SBI_EPI_BIAS_RESIDUAL, Y, ws, wsb, nullptr, &t);
     fprintf(stderr, "status %d (%s)\n", (int)st, sbi_status_string(st));
     if (st) return 1;
@@ -79,7 +124,13 @@ int main(int argc, char** argv)
                 xn[k] = ln ? (double)(_Float16)(((double)x[k] - mean) / std::sqrt(var + 1e-5) * (double)g1[k] + (double)b1[k]) : (double)x[k];
             for (int64_t n = 0; n < N; ++n) {
                 double acc = 0;
-                for (int64_t k = 0; k < K; ++k) acc += xn[k] * (double)W[k * N + n];
+                if (i8) {
+                    long long s = 0;
+                    for (int64_t k = 0; k < K; ++k) s += (long long)Xq[(size_t)b * K + k] * (long long)Wq[k * N + n];
+                    acc = (double)s * (double)sx[b] * (double)sw[n];
+                } else {
+                    for (int64_t k = 0; k < K; ++k) acc += xn[k] * (double)W[k * N + n];
+                }
                 acc += (double)bias[n] + (double)R[(size_t)b * N + n];
                 const double err = std::fabs((double)Y[(size_t)b * N + n] - acc);
                 if (!(err <= worst)) worst = err;

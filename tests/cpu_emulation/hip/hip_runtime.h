@@ -87,6 +87,31 @@ inline emu_floatx4 __builtin_amdgcn_mfma_f32_16x16x32_f16(emu_half8 a, emu_half8
     pthread_barrier_wait(&b->wave[w]);
     return c;
 }
+typedef int emu_i32x4 __attribute__((ext_vector_type(4)));
+// D[4*(l/16)+r][l%16] += sum_k A[row][k] * B[k][col] over 64 int8 k; lane l holds the 16 codes
+// k = 16*(l/16)..+15 of A's row l%16 and of B's column l%16 (the kernels rely only on A and B
+// using the same lane -> k assignment)
+inline emu_i32x4 __builtin_amdgcn_mfma_i32_16x16x64_i8(emu_i32x4 a, emu_i32x4 bb, emu_i32x4 c, int, int, int)
+{
+    emu::Block* b = emu::t_block;
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    memcpy(b->ma[w][l], &a, 16);
+    memcpy(b->mb[w][l], &bb, 16);
+    pthread_barrier_wait(&b->wave[w]);
+    const int col = l & 15;
+    for (int r = 0; r < 4; ++r) {
+        const int row = 4 * (l >> 4) + r;
+        int s = c[r];
+        for (int kg = 0; kg < 4; ++kg) {
+            const signed char* pa = reinterpret_cast<const signed char*>(b->ma[w][kg * 16 + row]);
+            const signed char* pb = reinterpret_cast<const signed char*>(b->mb[w][kg * 16 + col]);
+            for (int e = 0; e < 16; ++e) s += (int)pa[e] * (int)pb[e];
+        }
+        c[r] = s;
+    }
+    pthread_barrier_wait(&b->wave[w]);
+    return c;
+}
 inline int __builtin_amdgcn_readfirstlane(int v) { return v; }
 #define __builtin_amdgcn_sched_barrier(x) ((void)0)
 #define __builtin_amdgcn_fence(order, scope) __atomic_thread_fence(__ATOMIC_SEQ_CST)

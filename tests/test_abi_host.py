@@ -254,3 +254,43 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(sb, "LIB_PATH", str(tmp_path / "libsbi_gemm.so"))
     with pytest.raises(ImportError):
         sb.load()
+
+
+def test_int8_argument_validation_and_plans(lib):
+    sw = FAKE + (7 << 30)
+    call = lambda **kw: lib.sbi_gemm_i8(kw.get("W", FAKE), kw.get("sw", sw), kw.get("K", 4096), kw.get("N", 4096),
+                                        kw.get("X", FAKE + (1 << 30)), kw.get("B", 4), None, None, 0,
+                                        FAKE + (2 << 30), FAKE + (3 << 30), kw.get("wb", 1 << 30), None,
+                                        kw.get("tune"))
+    assert call(sw=None) == 1 and call(W=None) == 1
+    assert call(K=4104) == 2                                      # rows must split into 32-byte pieces
+    assert call(sw=sw + 2) == 3
+    assert call(B=65) == 4
+    for bad in (sb.Tuning(sb.PATH_STREAM, 0, 0, 0, 0, 0, 0, 0), sb.Tuning(sb.PATH_MFMA, 0, 0, 0, 0, 2, 0, 0),
+                sb.Tuning(sb.PATH_MFMA, 0, 8, 8, 0, 0, 0, 0), sb.Tuning(sb.PATH_MFMA, 0, 0, 0, 0, 0, 1, 0)):
+        assert call(tune=ctypes.byref(bad)) == 10
+    need = sb.i8_workspace_bytes(4, 4096, 4096)
+    assert need == sb.plan(4, 4096, 4096, int8=True)["workspace_bytes"] > 0
+    assert call(wb=need - 1) == 6
+    t = sb.Tuning(0, 0, 0, 0, 0, 0, 0, 1)
+    assert lib.sbi_gemm_ex(FAKE, 4096, 4096, FAKE + (1 << 30), 4, None, None, 0, FAKE + (2 << 30),
+                           FAKE + (3 << 30), 1 << 30, None, ctypes.byref(t)) == 10
+    # weight preparation
+    assert sb.i8_layout_bytes(4096, 4096) == 256 + 64 * 64 * 4096 and sb.i8_layout_bytes(0, 4) == 0
+    assert sb.i8_layout_bytes(100, 65) == 256 + 8 * 2 * 4096
+    assert lib.sbi_gemm_i8_layout_weights(None, 64, 64, FAKE, 1 << 20, None) == 1
+    assert lib.sbi_gemm_i8_layout_weights(FAKE, 64, 64, FAKE + 4096 + 8, 1 << 20, None) == 3
+    assert lib.sbi_gemm_i8_layout_weights(FAKE, 64, 64, FAKE + 4096, sb.i8_layout_bytes(64, 64) - 1, None) == 5
+    assert lib.sbi_gemm_i8_quantize_weights(FAKE, 64, 64, None, FAKE, None) == 1
+    assert lib.sbi_gemm_i8_quantize_weights(FAKE + 1, 64, 64, FAKE, FAKE, None) == 3
+    assert lib.sbi_gemm_i8_layout_check(None, 64, 64, None) == 1
+    for B in (1, 8, 16, 33, 64):
+        for K, N in ((16, 1), (4096, 12288), (16384, 4096), (1008, 130)):
+            KS, P = 8 * -(-(-(-K // 64)) // 8), -(-N // 64)
+            pl = sb.plan(B, K, N, int8=True)
+            assert pl["path"] == sb.PATH_MFMA and pl["panels"] == 1
+            assert (pl["waves"], pl["depth"]) in ((4, 2), (4, 4), (8, 4))
+            S, ksps, kc = pl["split_k"], pl["ksteps_per_split"], pl["ksteps_per_chunk"]
+            assert 1 <= S <= KS and ksps * S >= KS and ksps * (S - 1) < KS and pl["grid"] == P * S
+            buffers = 1 if kc >= ksps else 2
+            assert 512 + max(buffers * kc * B * 64, pl["waves"] * 16 * 68 * 4) <= pl["lds_bytes"] <= 128 * 1024

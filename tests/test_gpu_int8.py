@@ -1,0 +1,155 @@
+"""GPU parity of the INT8 path (sbi_gemm_i8 and its weight preparation) against the oracle.
+Integer work is compared bit for bit: weight codes and scales from sbi_gemm_i8_quantize_weights,
+the laid-out bytes from sbi_gemm_i8_layout_weights.  The GeMM is compared with the oracle's
+gemm_i8_from_fp16 on the same codes: the activation codes are decided in binary32 on both sides,
+so the integer sums agree exactly and only the fp32-vs-fp64 epilogue remains:
+|gpu - oracle| <= max(2 ulp16(oracle), 1e-3), bit-identical run to run."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2207_00032_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+EPI_ORACLE = {"none": 0, "bias": orc.EPI_BIAS, "bias_gelu": orc.EPI_BIAS | orc.EPI_GELU,
+              "bias_residual": orc.EPI_BIAS | orc.EPI_RES, "gelu": orc.EPI_GELU, "residual": orc.EPI_RES}
+
+
+def _dev(a, gpu):
+    import torch
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(gpu)
+
+
+def prepare(gpu, W):
+    """Quantise and lay out W on the GPU; return (laid-out tensor, scales tensor, host codes, host scales)."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    Wq_d, sw_d = sb.i8_quantize_weights(_dev(W, gpu))
+    Wl = sb.i8_layout_weights(Wq_d)
+    torch.cuda.synchronize()
+    return Wl, sw_d, Wq_d.cpu().numpy(), sw_d.cpu().numpy()
+
+
+def check(Y, X, Wq, sw, bias, R, epi, what):
+    want = orc.gemm_i8_from_fp16(X, Wq, sw, bias, R, EPI_ORACLE[epi])
+    ok, rep = orc.check_close(Y, want, ulps=2, abs_tol=1e-3)
+    assert ok, f"{what}: {rep}"
+
+
+@pytest.mark.parametrize("K,N", [(16, 1), (64, 64), (200, 150), (1000, 130), (2048, 520), (4096, 192)])
+def test_weight_quantisation_and_layout_bit_exact(gpu, K, N):
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    rng = np.random.default_rng(K * 31 + N)
+    W = (rng.standard_normal((K, N)) * 0.02 * np.exp(rng.uniform(-2, 2, (1, N)))).astype(np.float16)
+    if N > 3:
+        W[:, 3] = 0                                        # an all-zero output channel
+    Wl, sw_d, Wq, sw = prepare(gpu, W)
+    Wq_ref, sw_ref = orc.quantize_columns(W)
+    assert np.array_equal(Wq, Wq_ref)
+    assert np.array_equal(sw.view(np.uint32), sw_ref.view(np.uint32))
+    raw = Wl.cpu().numpy()
+    assert raw.size == sb.i8_layout_bytes(K, N)
+    assert np.array_equal(raw[256:].view(np.int8), orc.layout_weights_i8(Wq_ref))
+    hdr = raw[:256]
+    KS, P = orc.layout_dims_i8(K, N)
+    assert hdr[:4].tobytes() == b"SBIG" and not hdr[56:].any()
+    assert tuple(hdr[8:40].view(np.int64)) == (K, N, KS, P)
+    assert tuple(hdr[40:56].view(np.int32)) == (16, 64, 4, 16)
+    assert sb.i8_layout_check(Wl, K, N) == 0 and sb.layout_check(Wl, K, N) == 5
+    assert sb.i8_layout_check(Wl, K + 16, N) == 5
+    if K % 8 == 0:
+        assert sb.i8_layout_check(sb.layout_weights(_dev(W, gpu)), K, N) == 5      # an fp16 layout is not an int8 one
+
+
+@pytest.mark.parametrize("B,K,N", [(1, 16, 1), (1, 64, 64), (3, 272, 200), (8, 1008, 130), (8, 4096, 192),
+                                   (5, 4112, 72), (16, 2048, 320), (17, 4096, 136), (33, 1024, 192),
+                                   (64, 2048, 128), (2, 12288, 64), (48, 8192, 192), (64, 528, 72)])
+def test_int8_gemm_shapes_and_epilogues(gpu, B, K, N):
+    from paper_2207_00032_amd import binding as sb
+    W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=B + K + N, config_id=400)
+    Wl, sw_d, Wq, sw = prepare(gpu, W)
+    Xd, bd, Rd = _dev(X, gpu), _dev(bias, gpu), _dev(R, gpu)
+    for epi in ("none", "bias", "bias_gelu", "bias_residual", "gelu", "residual"):
+        Y = sb.gemm_i8(Wl, sw_d, K, N, Xd, bd if "bias" in epi else None, Rd if "residual" in epi else None, epi)
+        check(Y.cpu().numpy(), X, Wq, sw, bias, R, epi, f"B={B} K={K} N={N} {epi}")
+
+
+@pytest.mark.parametrize("B,K,N", [(1, 4096, 192), (8, 2048, 320), (16, 4096, 128), (40, 1024, 192),
+                                   (64, 2048, 128)])
+@pytest.mark.parametrize("waves,depth", [(4, 2), (4, 4), (8, 4)])
+def test_int8_gemm_split_k_and_tuning_variants(gpu, B, K, N, waves, depth):
+    from paper_2207_00032_amd import binding as sb
+    W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=3, config_id=401)
+    Wl, sw_d, Wq, sw = prepare(gpu, W)
+    Xd, bd, Rd = _dev(X, gpu), _dev(bias, gpu), _dev(R, gpu)
+    for S in (1, 2, 3, 7, 16):
+        try:
+            sb.plan(B, K, N, sb.PATH_MFMA, S, waves, depth, int8=True)
+        except sb.SbiError:
+            continue
+        Y = sb.gemm_i8(Wl, sw_d, K, N, Xd, bd, Rd, "bias_residual", path=sb.PATH_MFMA, split_k=S,
+                       waves=waves, depth=depth)
+        check(Y.cpu().numpy(), X, Wq, sw, bias, R, "bias_residual", f"B={B} K={K} N={N} S={S} w={waves} d={depth}")
+
+
+def test_int8_special_rows_and_determinism(gpu):
+    """An all-zero activation row (scale 0), a row dominated by one outlier (every other code 0 or
+    +-1), exact ties in the code decision, a shared workspace across differently shaped calls."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    K, N, B = 2048, 200, 5
+    W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=8, config_id=402)
+    X[1, :] = 0
+    X[2, :] = (np.random.default_rng(1).standard_normal(K) * 0.3).astype(np.float16)
+    X[2, 77] = 300.0
+    X[3, :] = np.tile(np.array([127, 0.5, 1.5, 2.5, -0.5, -1.5, 63.5, -2.5], np.float16), K // 8)   # inv = 1: ties
+    Wl, sw_d, Wq, sw = prepare(gpu, W)
+    Xd, bd = _dev(X, gpu), _dev(bias, gpu)
+    ws = sb.new_workspace(max(sb.i8_workspace_bytes(B, K, N), sb.i8_workspace_bytes(2, K, N)), gpu)
+    first = None
+    for rep in range(3):
+        Y = sb.gemm_i8(Wl, sw_d, K, N, Xd, bd, None, "bias", workspace=ws)
+        Y2 = sb.gemm_i8(Wl, sw_d, K, N, Xd[:2].contiguous(), bd, None, "bias", workspace=ws)
+        torch.cuda.synchronize()
+        if first is None:
+            first = Y.clone()
+        assert torch.equal(Y.view(torch.int16), first.view(torch.int16))
+        assert torch.equal(Y2.view(torch.int16), first[:2].view(torch.int16))
+    check(first.cpu().numpy(), X, Wq, sw, bias, None, "bias", "special rows")
+    assert not ws[:256 * 1024].cpu().numpy().any()
+
+
+def test_int8_with_unit_scales_equals_the_fp16_path_bits(gpu):
+    """Integer-valued operands with amax = 127: codes are the values, scales are 1, and the INT8
+    kernel must give the same fp16 bits as the fp16 kernel (both exact before the one rounding)."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    rng = np.random.default_rng(4)
+    B, K, N = 6, 1024, 136
+    X = rng.integers(-20, 21, (B, K)).astype(np.float16)
+    W = rng.integers(-3, 4, (K, N)).astype(np.float16)
+    X[:, 0] = 127
+    W[0, :] = -127
+    bias = rng.standard_normal(N).astype(np.float16)
+    Wl8, sw_d, Wq, sw = prepare(gpu, W)
+    assert np.all(sw == 1)
+    Y8 = sb.gemm_i8(Wl8, sw_d, K, N, _dev(X, gpu), _dev(bias, gpu), None, "bias")
+    Y16 = sb.gemm(sb.layout_weights(_dev(W, gpu)), K, N, _dev(X, gpu), _dev(bias, gpu), None, "bias")
+    torch.cuda.synchronize()
+    assert torch.equal(Y8.view(torch.int16), Y16.view(torch.int16))
+    assert np.array_equal(Y8.cpu().numpy().view(np.uint16), orc.gemm(X, W, bias, None, epi=orc.EPI_BIAS).view(np.uint16))
+
+
+@pytest.mark.parametrize("gi", [0, 1, 2, 3])
+@pytest.mark.parametrize("B", [1, 8])
+def test_int8_config2_h4096_gemms(gpu, gi, B):
+    from paper_2207_00032_amd import binding as sb
+    spec, W, bias, X, R = wl.make_config_gemm(2, gi, seed=0, B=B)
+    Wl, sw_d, Wq, sw = prepare(gpu, W)
+    epi = {wl.NONE: "none", wl.BIAS: "bias", wl.BIAS_GELU: "bias_gelu", wl.BIAS_RESIDUAL: "bias_residual",
+           wl.GELU: "gelu", wl.RESIDUAL: "residual"}[spec.epilogue]
+    Y = sb.gemm_i8(Wl, sw_d, spec.K, spec.N, _dev(X, gpu), _dev(bias, gpu) if "bias" in epi else None,
+                   _dev(R, gpu) if "residual" in epi else None, epi)
+    check(Y.cpu().numpy(), X, Wq, sw, bias, R, epi, f"config2 {spec.name} B={B}")
