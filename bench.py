@@ -43,6 +43,9 @@ def parse_args():
     ap.add_argument("--layernorm", action="store_true",
                     help="fuse a layer-norm in front of QKV and FFN1 (sbi_layer's ln1/ln2); also times the "
                          "same layer with the two norms as separate torch kernels, for comparison")
+    ap.add_argument("--int8", action="store_true",
+                    help="INT8 layer: weights quantised per output channel and laid out as int8, activations "
+                         "quantised inside the kernel (sbi_layer's scales); algorithmic bytes count one byte per weight")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run a few copy-kernel and layer launches and exit (for rocprofv3 --pmc runs)")
     return ap.parse_args()
@@ -51,7 +54,7 @@ def parse_args():
 def measured_traffic(args, batches):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE
     runs scaled against the copy kernel), if it covers exactly this workload; else None."""
-    if args.config != 2 or tuple(batches) != (1, 2, 4, 8) or args.path != "auto" or args.layernorm:
+    if args.config != 2 or tuple(batches) != (1, 2, 4, 8) or args.path != "auto" or args.layernorm or args.int8:
         return None
     path = os.path.join(ROOT, "profiles", "sbi_mfma_kernel_config2_pmc_traffic.md")
     try:
@@ -83,7 +86,7 @@ def main():
     batches = tuple(int(b) for b in args.batches.split(",")) if args.batches else cfg.batches
     Bmax = max(batches)
     specs = cfg.gemms
-    layer_weight_bytes = sum(s.weight_bytes for s in specs)
+    layer_weight_bytes = sum(s.weight_bytes for s in specs) // (2 if args.int8 else 1)
     copies = args.copies or max(3, -(-3 * 256 * 1000 * 1000 // layer_weight_bytes))
 
     # ---- seeded synthetic inputs (host), uploaded and laid out once ------------------------
@@ -108,9 +111,21 @@ def main():
     use_res = specs[3].epilogue in (wl.BIAS_RESIDUAL, wl.RESIDUAL)
     gelu = specs[2].epilogue in (wl.BIAS_GELU, wl.GELU)
 
-    Wl0 = [sb.layout_weights(torch.from_numpy(h[0]).to(dev)) for h in host]
-    for w, s in zip(Wl0, specs):
-        assert sb.layout_check(w, s.K, s.N) == 0
+    scales_d = None
+    if args.int8:
+        assert args.path == "auto" and not args.layernorm, "--int8 runs through sbi_layer_gemms, without --layernorm"
+        prepared = [sb.i8_quantize_weights(torch.from_numpy(h[0]).to(dev)) for h in host]
+        Wl0 = [sb.i8_layout_weights(q) for q, _ in prepared]
+        scales_d = [sc for _, sc in prepared]
+        Wq_host = [q.cpu().numpy() for q, _ in prepared]          # codes and scales for the oracle leg
+        sw_host = [sc.cpu().numpy() for sc in scales_d]
+        del prepared
+        for w, s in zip(Wl0, specs):
+            assert sb.i8_layout_check(w, s.K, s.N) == 0
+    else:
+        Wl0 = [sb.layout_weights(torch.from_numpy(h[0]).to(dev)) for h in host]
+        for w, s in zip(Wl0, specs):
+            assert sb.layout_check(w, s.K, s.N) == 0
     Wl = [Wl0] + [[w.clone() for w in Wl0] for _ in range(copies - 1)]
     bias_d = [torch.from_numpy(h[1]).to(dev) if ub else None for h, ub in zip(host, use_bias)]
     X_d = {B: [torch.from_numpy(np.ascontiguousarray(h[2][:B])).to(dev) for h in host] for B in batches}
@@ -118,7 +133,8 @@ def main():
     Y_d = {B: [torch.empty((B, s.N), dtype=torch.float16, device=dev) for s in specs] for B in batches}
     h_dim = specs[0].K
     layers = [sb.make_layer(*Wl[c], h_dim, specs[0].N, specs[1].K, specs[2].N, specs[3].K,
-                            bqkv=bias_d[0], bout=bias_d[1], bffn1=bias_d[2], bffn2=bias_d[3], ffn1_gelu=gelu)
+                            bqkv=bias_d[0], bout=bias_d[1], bffn1=bias_d[2], bffn2=bias_d[3], ffn1_gelu=gelu,
+                            scales=scales_d)
               for c in range(copies)]
     plain_layers = layers
     if args.layernorm:
@@ -129,7 +145,8 @@ def main():
                                 ln1=ln_d[0], ln2=ln_d[2], ln_eps=LN_EPS) for c in range(copies)]
     ws = sb.new_workspace(max([sb.layer_workspace_bytes(layers[0], B) for B in batches] +
                               [sb.layer_workspace_bytes(plain_layers[0], B) for B in batches] +
-                              [sb.plan(B, s.K, s.N)["workspace_bytes"] for B in batches for s in specs]), dev)
+                              [sb.plan(B, s.K, s.N, int8=args.int8)["workspace_bytes"] for B in batches for s in specs]),
+                          dev)
     path = {"auto": sb.PATH_AUTO, "stream": sb.PATH_STREAM, "mfma": sb.PATH_MFMA,
             "streamk": sb.PATH_STREAMK}[args.path]
 
@@ -167,7 +184,7 @@ def main():
             step(i)
         torch.cuda.synchronize()
         print(json.dumps({"pmc_probe": True, "copy_bytes": 256 << 20, "batches": list(batches),
-                          "layer_bytes": {str(B): sum(s.algorithmic_bytes(B) for s in specs) for B in batches}}))
+                          "layer_bytes": {str(B): sum(s.algorithmic_bytes(B, args.int8) for s in specs) for B in batches}}))
         return
 
     # ---- timed region: K steps, one event per step boundary on the launch stream -------------
@@ -201,7 +218,7 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     sec_per_step = (t1 - t0) / args.steps
-    bytes_per_step = sum(s.algorithmic_bytes(B) for B in batches for s in specs)
+    bytes_per_step = sum(s.algorithmic_bytes(B, args.int8) for B in batches for s in specs)
     flops_per_step = sum(s.flops(B) for B in batches for s in specs)
     value = bytes_per_step / sec_per_step / 1e9
     # dominant kernel: with the automatic dispatch a step is len(batches) launches of it, back to back
@@ -229,7 +246,7 @@ def main():
                            "TFLOPs": round(nflops / (med * 1e-6) / 1e12, 3)})
 
     for B in batches:
-        timed_run("layer", B, sum(s.algorithmic_bytes(B) for s in specs), sum(s.flops(B) for s in specs),
+        timed_run("layer", B, sum(s.algorithmic_bytes(B, args.int8) for s in specs), sum(s.flops(B) for s in specs),
                   lambda: launch_layer(B))
     if args.layernorm:
         # the unfused alternative: the two norms as kernels of their own (torch's), then the plain layer
@@ -244,12 +261,12 @@ def main():
                            y[0], y[1], y[2], y[3], ws)
 
         for B in batches:
-            timed_run("layer, norms as separate torch kernels", B, sum(s.algorithmic_bytes(B) for s in specs),
+            timed_run("layer, norms as separate torch kernels", B, sum(s.algorithmic_bytes(B, args.int8) for s in specs),
                       sum(s.flops(B) for s in specs), lambda: launch_unfused(B))
-    if args.per_gemm:
+    if args.per_gemm and not args.int8:
         for B in batches:
             for gi, s in enumerate(specs):
-                timed_run("single:" + s.name, B, s.algorithmic_bytes(B), s.flops(B),
+                timed_run("single:" + s.name, B, s.algorithmic_bytes(B, args.int8), s.flops(B),
                           lambda: sb.gemm(Wl[next_copy()][gi], s.K, s.N, X_d[B][gi], bias_d[gi],
                                           R_d[B] if gi == 3 else None, s.epilogue, out=Y_d[B][gi],
                                           workspace=ws, path=path))
@@ -259,6 +276,8 @@ def main():
         pl0 = lp[0]
     kname = {sb.PATH_STREAMK: "sbi_streamk_kernel", sb.PATH_MFMA: "sbi_mfma_kernel",
              sb.PATH_STREAM: "sbi_stream_kernel"}[pl0["path"]]
+    if args.int8:
+        kname = "sbi_i8_kernel"
     bytes_per_launch = bytes_per_step / launches_per_step
     achieved = bytes_per_launch / (avg_launch_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -291,9 +310,12 @@ def main():
                 c0 = time.perf_counter()
                 if args.layernorm and gi in (0, 2):
                     xin = orc.layernorm(xin, ln_host[gi][0], ln_host[gi][1], LN_EPS)
-                want = orc.gemm(xin, W, bias, R[:B], epi=epi_map[s.epilogue])
+                if args.int8:
+                    want = orc.gemm_i8_from_fp16(xin, Wq_host[gi], sw_host[gi], bias, R[:B], epi_map[s.epilogue])
+                else:
+                    want = orc.gemm(xin, W, bias, R[:B], epi=epi_map[s.epilogue])
                 t_cpu += time.perf_counter() - c0
-                cpu_bytes += s.algorithmic_bytes(B)
+                cpu_bytes += s.algorithmic_bytes(B, args.int8)
                 ok, rep = orc.check_close(Y_d[B][gi].cpu().numpy(), want)
                 worst["max_abs"] = max(worst["max_abs"], rep["max_abs"])
                 worst["n_bad"] += rep["n_bad"]
@@ -308,11 +330,11 @@ def main():
         "metric": "weight-stream HBM GB/s (algorithmic bytes of the layer's four GeMMs / time)",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(sec_per_step * 1e3, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "vs_baseline": None, "dtype": "i8" if args.int8 else "f16", "data": "synthetic",
         "config": {"workload": f"config{args.config}:{cfg.name} four-GeMM layer, B in {list(batches)}, "
                                f"rotating over {copies} weight copies ({copies * layer_weight_bytes >> 20} MiB)",
                    "batches": list(batches), "weight_copies": copies, "dispatch": args.path,
-                   "fused_layernorm": bool(args.layernorm),
+                   "fused_layernorm": bool(args.layernorm), "int8": bool(args.int8),
                    "graph_replay_steps": args.graph},
         "hbm_frac": round(value / HBM_PEAK_GBPS, 4),
         "us_per_gemm_mean": round(sec_per_step * 1e6 / (len(batches) * len(specs)), 2),

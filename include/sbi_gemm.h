@@ -257,6 +257,10 @@ typedef struct sbi_layer {
        set or both NULL; they need h % 8 == 0 */
     const void *ln1_gamma, *ln1_beta, *ln2_gamma, *ln2_beta;
     float ln_eps;
+    /* INT8 layer: all four set (device, binary32 per-column scales [n_qkv], [h], [n_ffn1], [h]) means
+       W* are laid-out int8 codes (sbi_gemm_i8_layout_weights) and the GeMMs run as sbi_gemm_i8;
+       all four NULL: fp16.  Needs h, k_out, k_ffn2 % 16 == 0; not together with ln1/ln2. */
+    const void *sqkv, *sout, *sffn1, *sffn2;
 } sbi_layer;
 
 /*

@@ -69,7 +69,9 @@ class Layer(ctypes.Structure):
                 ("h", ctypes.c_int64), ("n_qkv", ctypes.c_int64), ("k_out", ctypes.c_int64),
                 ("n_ffn1", ctypes.c_int64), ("k_ffn2", ctypes.c_int64), ("ffn1_gelu", ctypes.c_int32),
                 ("ln1_gamma", ctypes.c_void_p), ("ln1_beta", ctypes.c_void_p),
-                ("ln2_gamma", ctypes.c_void_p), ("ln2_beta", ctypes.c_void_p), ("ln_eps", ctypes.c_float)]
+                ("ln2_gamma", ctypes.c_void_p), ("ln2_beta", ctypes.c_void_p), ("ln_eps", ctypes.c_float),
+                ("sqkv", ctypes.c_void_p), ("sout", ctypes.c_void_p), ("sffn1", ctypes.c_void_p),
+                ("sffn2", ctypes.c_void_p)]
 
 
 _lib = None
@@ -345,11 +347,18 @@ def gemm(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, wor
 
 
 def make_layer(Wqkv, Wout, Wffn1, Wffn2, h, n_qkv, k_out, n_ffn1, k_ffn2,
-               bqkv=None, bout=None, bffn1=None, bffn2=None, ffn1_gelu=True, ln1=None, ln2=None, ln_eps=1e-5):
-    """Fill an sbi_layer from laid-out weight tensors; keep the tensors alive yourself."""
+               bqkv=None, bout=None, bffn1=None, bffn2=None, ffn1_gelu=True, ln1=None, ln2=None, ln_eps=1e-5,
+               scales=None):
+    """Fill an sbi_layer from laid-out weight tensors; keep the tensors alive yourself.
+    scales = (sqkv, sout, sffn1, sffn2) float32 tensors makes it an INT8 layer (int8 laid-out weights)."""
+    import torch
     for w, (K, N), name in ((Wqkv, (h, n_qkv), "Wqkv"), (Wout, (k_out, h), "Wout"),
                             (Wffn1, (h, n_ffn1), "Wffn1"), (Wffn2, (k_ffn2, h), "Wffn2")):
-        _need_bytes(w, layout_bytes(K, N), name)
+        _need_bytes(w, (i8_layout_bytes if scales is not None else layout_bytes)(K, N), name)
+    if scales is not None:
+        for sc, N in zip(scales, (n_qkv, h, n_ffn1, h)):
+            if not (sc.is_cuda and sc.dtype == torch.float32 and sc.is_contiguous() and tuple(sc.shape) == (N,)):
+                raise ValueError("scales: expected contiguous CUDA float32 tensors of shape (N,)")
     for b, N, name in ((bqkv, n_qkv, "bqkv"), (bout, h, "bout"), (bffn1, n_ffn1, "bffn1"), (bffn2, h, "bffn2")):
         _need(b, (N,), name)
     for ln, name in ((ln1, "ln1"), (ln2, "ln2")):
@@ -366,6 +375,8 @@ def make_layer(Wqkv, Wout, Wffn1, Wffn2, h, n_qkv, k_out, n_ffn1, k_ffn2,
     if ln2 is not None:
         L.ln2_gamma, L.ln2_beta = ln2[0].data_ptr(), ln2[1].data_ptr()
     L.ln_eps = float(ln_eps)
+    if scales is not None:
+        L.sqkv, L.sout, L.sffn1, L.sffn2 = (sc.data_ptr() for sc in scales)
     return L
 
 

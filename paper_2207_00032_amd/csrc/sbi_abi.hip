@@ -33,6 +33,8 @@ struct Plan {
     int pw;                   // MFMA path: panels per block
     bool ln;                  // MFMA path: the kernel variant that can layer-normalise X
     bool i8;                  // the INT8 kernel (64-k steps, int8 X codes in LDS)
+    bool preq;                // INT8: activations quantised by a kernel of their own, codes in the workspace
+    int64_t xq_bytes;         //   and the workspace bytes those codes and row scales take
 };
 
 constexpr int kSkDefaultWaves = 2048;             // wavefronts of a STREAMK launch: 8 per CU
@@ -49,7 +51,7 @@ sbi_status plan_streamk(int64_t B, int64_t units, int64_t panels, const sbi_tuni
     const int64_t want = t.blocks ? (int64_t)t.blocks * nw : kSkDefaultWaves;
     const int64_t upw = round_up(ceil_div(units, want), kStepGroup);
     const int64_t nwaves = ceil_div(units, upw);
-    pl.ln = false; pl.i8 = false; pl.path = SBI_PATH_STREAMK; pl.nw = nw; pl.depth = depth; pl.S = 0;
+    pl.ln = false; pl.i8 = false; pl.preq = false; pl.xq_bytes = 0; pl.path = SBI_PATH_STREAMK; pl.nw = nw; pl.depth = depth; pl.S = 0;
     pl.ksps = (int)upw; pl.kc = 0; pl.pw = 1;
     pl.grid = (int)ceil_div(nwaves, nw); pl.block = nw * 64; pl.lds = 0;
     pl.upw = (int)upw; pl.nwaves = (int)nwaves;
@@ -99,7 +101,12 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
 // beta as two more rows per buffer; the INT8 kernel keeps the rows' scales there through the
 // reduction, stores int8 codes (64 k per k-step, still 64 B per row) and stages half as many
 // LDS bytes per pass.
-enum Flavour { kPlain = 0, kLayerNorm = 1, kInt8 = 2 };
+enum Flavour { kPlain = 0, kLayerNorm = 1, kInt8 = 2, kInt8Codes = 3 };
+
+// INT8: up to this batch every block quantises the activations itself; above it a kernel of its
+// own does it once (measured on MI355X: fused is ahead up to B = 8, behind from B = 16 on).
+constexpr int64_t kI8FusedMaxBatch = 8;
+inline int64_t xq_bytes_of(int64_t B, int64_t K) { return round_up(B * K, 256) + round_up(B * 8, 256); }
 
 bool chunking(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t red_bytes,
               int64_t& kc, int64_t& lds, Flavour fl = kPlain)
@@ -107,7 +114,7 @@ bool chunking(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t 
     const int64_t front = (fl == kPlain) ? 0 : kLnStatsBytes;
     const int64_t rows = B + (fl == kLayerNorm ? 2 : 0);
     const int64_t pass_bytes = (int64_t)nw * (fl == kInt8 ? 2048 : 4096);
-    const int64_t red = (fl == kInt8) ? red_bytes : std::max<int64_t>(red_bytes - front, 0);
+    const int64_t red = (fl == kInt8 || fl == kInt8Codes) ? red_bytes : std::max<int64_t>(red_bytes - front, 0);
     cap -= front;
     const int64_t whole = round_up(ksps, wd);
     bool ok = true;
@@ -141,7 +148,8 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     const bool ln = t.layernorm != 0;
     const bool i8 = t.int8 != 0;
     const int64_t KS = i8 ? ksteps_of_i8(K) : ksteps_of(K);
-    const Flavour fl = i8 ? kInt8 : (ln ? kLayerNorm : kPlain);
+    const bool preq = i8 && B > kI8FusedMaxBatch;
+    const Flavour fl = i8 ? (preq ? kInt8Codes : kInt8) : (ln ? kLayerNorm : kPlain);
 
     if (t.split_k < 0 || t.blocks < 0 || t.panels < 0 || t.panels > 2) return SBI_ERR_TUNING;
     int path = t.path;
@@ -197,13 +205,13 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
                   kc, lds, fl))
         return SBI_ERR_TUNING;
 
-    pl.ln = ln; pl.i8 = i8;
+    pl.ln = ln; pl.i8 = i8; pl.preq = preq; pl.xq_bytes = preq ? xq_bytes_of(B, K) : 0;
     pl.path = path; pl.nw = nw; pl.depth = depth; pl.S = S; pl.pw = pw;
     pl.ksps = (int)ksps; pl.kc = (int)kc;
     pl.grid = (int)(PG * S); pl.block = nw * 64;
     pl.lds = lds;
-    pl.counter_bytes = (S > 1) ? kCounterBytes : 0;
-    pl.ws_bytes = (S > 1) ? pl.counter_bytes + P * S * B * kPanelN * 4 : 0;
+    pl.counter_bytes = (S > 1 || preq) ? kCounterBytes : 0;
+    pl.ws_bytes = (S > 1 || preq) ? pl.counter_bytes + (S > 1 ? P * S * B * kPanelN * 4 : 0) + pl.xq_bytes : 0;
     pl.upw = 0; pl.nwaves = 0;
     return SBI_OK;
 }
@@ -292,7 +300,7 @@ sbi_status launch_group(const GemmArgs* a, int G, int64_t B, const Plan& pl, voi
 // Block-kernel parameters of one validated GeMM under plan `pl`; its arrival counters start at
 // counter index `panel_base` and its partial sums at byte offset `partial_off` of the workspace.
 GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* workspace,
-                       int64_t panel_base, int64_t partial_off)
+                       int64_t panel_base, int64_t partial_off, int64_t xq_off = 0)
 {
     GemmParams p;
     p.Wl = reinterpret_cast<const u32x4*>(reinterpret_cast<const unsigned char*>(a.Wl) + kHeaderBytes);
@@ -307,6 +315,12 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
     p.KS = (int)(pl.i8 ? ksteps_of_i8(a.K) : ksteps_of(a.K)); p.P = (int)ceil_div(a.N, kPanelN);
     p.S = pl.S; p.ksps = pl.ksps; p.kc = pl.kc;
     p.sw = reinterpret_cast<const float*>(a.sw);
+    p.X16 = p.X;
+    p.xstats = nullptr;
+    if (pl.preq) {                      // codes and row scales live at byte offset xq_off of the workspace
+        p.X = reinterpret_cast<const _Float16*>(ws + xq_off);
+        p.xstats = reinterpret_cast<const floatx2*>(ws + xq_off + round_up(B * a.K, 256));
+    }
     p.flags = a.flags; p.x_vec = (a.K % 8 == 0) ? 1 : 0;
     // the layer-norm kernel variant reads gamma and beta pieces unconditionally: a problem
     // without layer-norm points them at its X (K readable halfs) and ignores the values
@@ -323,7 +337,7 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
 // Wavefronts per CU that the register file lets the MFMA block kernel keep resident: the vector
 // registers the compiled kernel variants allocate (row blocks MB = ceil(B/16), waves, depth; plain
 // and layer-norm), in granules of 8, against 512 registers per SIMD lane and 4 SIMDs per CU.
-int resident_waves(int mb, int nw, int depth, int pw, bool ln, bool i8)
+int resident_waves(int mb, int nw, int depth, int pw, bool ln, bool i8, bool preq = false)
 {
     static const int vgpr_i8_w4d2[4] = {108, 132, 200, 216};
     static const int vgpr_i8_w4d4[4] = {164, 184, 212, 242};
@@ -337,7 +351,8 @@ int resident_waves(int mb, int nw, int depth, int pw, bool ln, bool i8)
     static const int vgpr_ln_w8d4[4] = {138, 160, 180, 204};
     const int* tab = (pw == 2) ? vgpr_w8d2p2 : (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);
     if (ln) tab = (nw == 8) ? vgpr_ln_w8d4 : (depth == 2 ? vgpr_ln_w4d2 : vgpr_ln_w4d4);
-    if (i8) tab = (nw == 8) ? vgpr_i8_w8d4 : (depth == 2 ? vgpr_i8_w4d2 : vgpr_i8_w4d4);
+    if (i8 && preq) tab = (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);   // as the fp16 kernel's
+    else if (i8) tab = (nw == 8) ? vgpr_i8_w8d4 : (depth == 2 ? vgpr_i8_w4d2 : vgpr_i8_w4d4);
     const int v = (tab[std::min(std::max(mb, 1), 4) - 1] + 7) / 8 * 8;
     return 4 * std::min(8, 512 / v);
 }
@@ -362,7 +377,8 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
     if (panels > kCounterBytes / 4) return SBI_ERR_SHAPE;
     constexpr int64_t kLdsPerCU = 160 * 1024;
     const int64_t lds_caps[4] = {16 * 1024, 32 * 1024, kMaxLds, kMaxLdsWide};
-    const Flavour fl = i8 ? kInt8 : (ln ? kLayerNorm : kPlain);
+    const bool preq = i8 && B > kI8FusedMaxBatch;
+    const Flavour fl = i8 ? (preq ? kInt8Codes : kInt8) : (ln ? kLayerNorm : kPlain);
     // (waves, depth, panels per block) candidates; two-panel blocks only pay off for B > 16
     const int shapes[4][3] = {{4, 4, 1}, {8, 4, 1}, {4, 2, 1}, {8, 2, 2}};
 
@@ -397,12 +413,12 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
                     work += ceil_div(P[g], pw) * S * ksps * pw;
                     lds = std::max(lds, l);
                     chunks = std::max(chunks, ceil_div(ksps, kc));
-                    if (ceil_div(ksps, kc) > 1 && kc * (B + (ln ? 2 : 0)) * 64 > (int64_t)nw * (i8 ? 2048 : 4096)) slow_stage = true;
+                    if (ceil_div(ksps, kc) > 1 && kc * (B + (ln ? 2 : 0)) * 64 > (int64_t)nw * ((i8 && !preq) ? 2048 : 4096)) slow_stage = true;
                     if (S > 1) partial += (double)(P[g] * S) * (double)B * 512.0;
                 }
                 if (!ok) continue;
                 const int64_t fit = std::max<int64_t>(1, std::min<int64_t>(kLdsPerCU / lds,
-                                                                           resident_waves(mb, nw, depth, pw, ln, i8) / nw));
+                                                                           resident_waves(mb, nw, depth, pw, ln, i8, preq) / nw));
                 // A CU time-slices its share of HBM bandwidth over the blocks it holds, so what counts is
                 // how many blocks the busiest CU works through (quantised), each costing its stream plus
                 // a start/finish overhead; measured on MI355X (h=4096 layer, 512 MiB single GeMMs):
@@ -418,7 +434,7 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
                 const double stream = (double)work / (double)blocks * (1.0 + 0.6 * std::max(0.0, x_ratio - 0.2));
                 double overhead = 9.0 + 0.15 * (double)(chunks - 1) + (conc == 1 ? 4.5 : 0.0);
                 if (ln) overhead += (conc == 1 ? 16.0 : 4.0) * (double)(ceil_div(B, 2 * nw) * ceil_div(maxKS, 128));
-                if (i8) overhead += (conc == 1 ? 8.0 : 2.0) * (double)(ceil_div(B, 2 * nw) * ceil_div(maxKS, 64));
+                if (i8 && !preq) overhead += (conc == 1 ? 8.0 : 2.0) * (double)(ceil_div(B, 2 * nw) * ceil_div(maxKS, 64));
                 double cost = (double)per_cu_blocks * (stream + overhead) * (busy >= 0.75 ? 1.0 : 0.75 / busy) +
                               partial / kNumCU / 4096.0;
                 const int64_t inflight = conc * nw * depth;
@@ -456,20 +472,20 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
         const int64_t ksps = ceil_div(KS[g], S);
         int64_t kc = 0, l = 0;
         chunking(B, ksps, wd, nw, best_cap, (int64_t)nw * 16 * kRedPitch * 4, kc, l, fl);
-        pl.path = SBI_PATH_MFMA; pl.nw = nw; pl.depth = depth; pl.pw = pw; pl.ln = ln; pl.i8 = i8;
+        pl.path = SBI_PATH_MFMA; pl.nw = nw; pl.depth = depth; pl.pw = pw; pl.ln = ln; pl.i8 = i8; pl.preq = preq; pl.xq_bytes = preq ? xq_bytes_of(B, Ks[g]) : 0;
         pl.S = (int)ceil_div(KS[g], ksps); pl.ksps = (int)ksps; pl.kc = (int)kc;
         pl.grid = (int)(ceil_div(P[g], pw) * pl.S); pl.block = nw * 64;
         pl.lds = l;
         pl.counter_bytes = kCounterBytes;
         pl.ws_bytes = (pl.S > 1) ? P[g] * pl.S * B * kPanelN * 4 : 0;     // partial sums only
         pl.upw = 0; pl.nwaves = 0;
-        grid += pl.grid; partial_bytes += pl.ws_bytes; lds = std::max(lds, pl.lds);
+        grid += pl.grid; partial_bytes += pl.ws_bytes + pl.xq_bytes; lds = std::max(lds, pl.lds);
         any_split = any_split || pl.S > 1;
     }
     if (grid > (int64_t)0x7fffffff) return SBI_ERR_SHAPE;
     tot = pls[0];
     tot.grid = (int)grid; tot.lds = lds;
-    tot.ws_bytes = any_split ? kCounterBytes + partial_bytes : 0;
+    tot.ws_bytes = (any_split || preq) ? kCounterBytes + partial_bytes : 0;
     return SBI_OK;
 }
 
@@ -485,10 +501,13 @@ sbi_status launch_block_group(const GemmArgs* a, const Plan* pls, const Plan& to
     std::memset(&gp, 0, sizeof gp);
     gp.G = G;
     int64_t panel_base = 0, partial_off = 0;
+    int64_t xq_off = kCounterBytes;                      // codes follow the partial sums of all problems
+    for (int g = 0; g < G; ++g) xq_off += pls[g].ws_bytes;
     int first = 0;
     for (int k = 0; k < G; ++k) {
         const int g = order[k];
-        gp.g[k] = fill_params(a[g], B, pls[g], workspace, panel_base, partial_off);
+        gp.g[k] = fill_params(a[g], B, pls[g], workspace, panel_base, partial_off, xq_off);
+        xq_off += pls[g].xq_bytes;
         gp.first_block[k] = first;
         first += pls[g].grid;
         panel_base += gp.g[k].P;
@@ -506,7 +525,7 @@ sbi_status launch_block_group(const GemmArgs* a, const Plan* pls, const Plan& to
             if (tot.lds < kLnStatsBytes + std::max<int64_t>(buffers * pls[g].kc * B * 64, (int64_t)tot.nw * 16 * kRedPitch * 4))
                 return SBI_ERR_TUNING;
         }
-        return launch_i8(gp, tot.nw, tot.depth, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
+        return launch_i8(gp, tot.nw, tot.depth, tot.preq, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
     }
     return launch_mfma(gp, tot.nw, tot.depth, tot.pw, tot.ln, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
 }
@@ -624,7 +643,7 @@ static sbi_status gemm_impl(const void* W_laid_out, int64_t K, int64_t N,
     if (pl.path == SBI_PATH_STREAMK) return launch_group(&a, 1, B, pl, workspace, st);
     if (ln) { a.gamma = ln->gamma; a.beta = ln->beta; a.eps = ln->eps; }
     Plan one = pl;
-    one.ws_bytes = (pl.S > 1) ? pl.ws_bytes - pl.counter_bytes : 0;
+    one.ws_bytes = (pl.S > 1) ? ceil_div(N, kPanelN) * pl.S * B * kPanelN * 4 : 0;      // its partial sums
     if (pl.path == SBI_PATH_MFMA) return launch_block_group(&a, &one, pl, 1, B, workspace, st);
     const GemmParams p = fill_params(a, B, pl, workspace, 0, 0);
     return launch_stream(p, pl.nw, pl.depth, (size_t)pl.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
@@ -720,21 +739,31 @@ static sbi_status layer_check(const sbi_layer* L, int64_t B)
         if (sbi_status s = check_layernorm(L->ln1_gamma, L->ln1_beta, L->ln_eps, L->h)) return s;
     if (L->ln2_gamma || L->ln2_beta)
         if (sbi_status s = check_layernorm(L->ln2_gamma, L->ln2_beta, L->ln_eps, L->h)) return s;
+    if (L->sqkv || L->sout || L->sffn1 || L->sffn2) {            // INT8 layer: all four weight matrices
+        if (!L->sqkv || !L->sout || !L->sffn1 || !L->sffn2) return SBI_ERR_NULL;
+        if (L->h % kI8ChunkK || L->k_out % kI8ChunkK || L->k_ffn2 % kI8ChunkK) return SBI_ERR_SHAPE;
+        if (!aligned(L->sqkv, 4) || !aligned(L->sout, 4) || !aligned(L->sffn1, 4) || !aligned(L->sffn2, 4))
+            return SBI_ERR_ALIGN;
+        if (L->ln1_gamma || L->ln2_gamma) return SBI_ERR_TUNING;   // no layer-norm in front of the INT8 kernel yet
+    }
     return SBI_OK;
 }
+
+static bool layer_is_i8(const sbi_layer* L) { return L->sqkv != nullptr; }
 
 // Plans of a grouped launch over GeMMs [0, count) of the layer.
 static sbi_status layer_group_plan(const sbi_layer* L, int64_t B, int count, Plan* pls, Plan& tot)
 {
     const int64_t Ks[4] = {L->h, L->k_out, L->h, L->k_ffn2};
     const int64_t Ns[4] = {L->n_qkv, L->h, L->n_ffn1, L->h};
-    return plan_group(B, Ks, Ns, count, pls, tot, L->ln1_gamma || L->ln2_gamma);
+    return plan_group(B, Ks, Ns, count, pls, tot, L->ln1_gamma || L->ln2_gamma, layer_is_i8(L));
 }
 
 size_t sbi_layer_workspace_bytes(const sbi_layer* L, int64_t B)
 {
     if (layer_check(L, B) != SBI_OK) return 0;
-    size_t m = sbi_gemm_workspace_bytes(B, L->k_ffn2, L->h);        // a chained FFN2 runs on its own
+    // a chained FFN2 runs on its own
+    size_t m = layer_is_i8(L) ? sbi_gemm_i8_workspace_bytes(B, L->k_ffn2, L->h) : sbi_gemm_workspace_bytes(B, L->k_ffn2, L->h);
     Plan pls[4], tot;
     if (layer_group_plan(L, B, 4, pls, tot) == SBI_OK) m = std::max(m, (size_t)tot.ws_bytes);
     if (layer_group_plan(L, B, 3, pls, tot) == SBI_OK) m = std::max(m, (size_t)tot.ws_bytes);
@@ -754,7 +783,7 @@ sbi_status sbi_layer_plan(const sbi_layer* L, int64_t B, int32_t chained, sbi_pl
         plans[g].split_k = pls[g].S; plans[g].ksteps_per_split = pls[g].ksps;
         plans[g].ksteps_per_chunk = pls[g].kc; plans[g].grid = pls[g].grid; plans[g].block = tot.block;
         plans[g].panels = tot.pw;
-        plans[g].lds_bytes = tot.lds; plans[g].workspace_bytes = pls[g].ws_bytes;
+        plans[g].lds_bytes = tot.lds; plans[g].workspace_bytes = pls[g].ws_bytes + pls[g].xq_bytes;
     }
     *total_grid = tot.grid;
     return SBI_OK;
@@ -780,7 +809,8 @@ sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
     if (sbi_status s = layer_group_plan(L, B, count, pls, tot)) return s;
     size_t need = (size_t)tot.ws_bytes;
     if (chained) {
-        if (sbi_status s = make_plan(B, L->k_ffn2, L->h, nullptr, last)) return s;
+        const sbi_tuning t8 = {0, 0, 0, 0, 0, 0, 0, 1};
+        if (sbi_status s = make_plan(B, L->k_ffn2, L->h, layer_is_i8(L) ? &t8 : nullptr, last)) return s;
         need = std::max(need, (size_t)last.ws_bytes);
     }
     if (workspace_bytes < need || (need > 0 && !workspace)) return SBI_ERR_WORKSPACE;
@@ -793,10 +823,10 @@ sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
     const sbi_epilogue e2 = residual ? (L->bffn2 ? SBI_EPI_BIAS_RESIDUAL : SBI_EPI_RESIDUAL)
                                      : (L->bffn2 ? SBI_EPI_BIAS : SBI_EPI_NONE);
     GemmArgs a[4] = {
-        {L->Wqkv, L->h, L->n_qkv, Xqkv, L->bqkv, nullptr, 0, Yqkv, L->ln1_gamma, L->ln1_beta, L->ln_eps},
-        {L->Wout, L->k_out, L->h, Xout, L->bout, nullptr, 0, Yout, nullptr, nullptr, 0.0f},
-        {L->Wffn1, L->h, L->n_ffn1, Xffn1, L->bffn1, nullptr, 0, Yffn1, L->ln2_gamma, L->ln2_beta, L->ln_eps},
-        {L->Wffn2, L->k_ffn2, L->h, Xffn2, L->bffn2, residual, 0, Yffn2, nullptr, nullptr, 0.0f},
+        {L->Wqkv, L->h, L->n_qkv, Xqkv, L->bqkv, nullptr, 0, Yqkv, L->ln1_gamma, L->ln1_beta, L->ln_eps, L->sqkv},
+        {L->Wout, L->k_out, L->h, Xout, L->bout, nullptr, 0, Yout, nullptr, nullptr, 0.0f, L->sout},
+        {L->Wffn1, L->h, L->n_ffn1, Xffn1, L->bffn1, nullptr, 0, Yffn1, L->ln2_gamma, L->ln2_beta, L->ln_eps, L->sffn1},
+        {L->Wffn2, L->k_ffn2, L->h, Xffn2, L->bffn2, residual, 0, Yffn2, nullptr, nullptr, 0.0f, L->sffn2},
     };
     const sbi_epilogue epis[4] = {e0, eo, e1, e2};
     for (int g = 0; g < 4; ++g)
@@ -807,7 +837,7 @@ sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
     if (sbi_status s = launch_block_group(a, pls, tot, count, B, workspace, st)) return s;
     if (!chained) return SBI_OK;
     Plan one = last;
-    one.ws_bytes = (last.S > 1) ? last.ws_bytes - last.counter_bytes : 0;
+    one.ws_bytes = (last.S > 1) ? ceil_div(L->h, kPanelN) * last.S * B * kPanelN * 4 : 0;
     return launch_block_group(&a[3], &one, last, 1, B, workspace, st);
 }
 

@@ -63,6 +63,8 @@ struct GemmParams {
     const _Float16* ln_beta;   // [K]    (problems with ln == 0 point both at X)
     float ln_eps;
     const float* sw;           // INT8 path: per-column weight scales [N]
+    const _Float16* X16;       // INT8 path with activations quantised by a kernel of their own: the fp16 X
+    const floatx2* xstats;     //   (X then points at the codes [B,K] int8) and the rows' (inv, scale) [B]
 #ifdef SBI_TRACE
     unsigned long long* trace; // development builds: 4 timestamps per block
 #endif
@@ -107,7 +109,7 @@ struct SkParams {
 int launch_streamk(const SkParams& p, int waves, int depth, int grid, hipStream_t st);
 int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, bool layernorm, size_t lds_bytes,
                 hipStream_t st);
-int launch_i8(const GroupParams& gp, int waves, int depth, size_t lds_bytes, hipStream_t st);
+int launch_i8(const GroupParams& gp, int waves, int depth, bool prequantized, size_t lds_bytes, hipStream_t st);
 int launch_layout_i8(const void* Wq, int64_t K, int64_t N, void* out, hipStream_t st);
 int launch_quantize_weights(const void* W, int64_t K, int64_t N, void* Wq, void* scales, hipStream_t st);
 constexpr int kI8TileK = 64;                         // k per k-step of the int8 layout

@@ -49,9 +49,34 @@ struct MfmaI8Op {
     }
 };
 
+// Staging of activation codes that a kernel of their own has already produced (PREQ): the code
+// matrix [B,K] int8 is, byte for byte, a [B,K/2] matrix of 16-bit words, and a 64-k step of codes
+// is 64 bytes per row exactly like a 32-k step of fp16 - so the fp16 stage does the job on a
+// copy of the parameters that says so.
+template <int NT, int XU>
+struct XStageCodes {
+    XStage<NT, XU, false> inner;
+    GemmParams q;
+
+    __device__ __forceinline__ void init(const GemmParams& p)
+    {
+        q = p;
+        q.K = p.K / 2;
+        q.x_vec = 1;
+    }
+    __device__ __forceinline__ void request(const GemmParams&, int cb, int cn, int tid) { inner.request(q, cb, cn, tid); }
+    __device__ __forceinline__ void commit(const GemmParams&, u32x4* xs, int cb, int cn, int tid)
+    {
+        inner.commit(q, xs, cb, cn, tid);
+    }
+};
+
 // LDS: [0, kLnStatsBytes) the rows' (inv, scale); behind it the X buffers during the stream and
 // the reduction tile afterwards (the scales are still needed then).
-template <int MB, int NW, int DEPTH>
+// PREQ: p.X points at int8 codes and p.xstats at the rows' (inv, scale) in global memory, both
+// written by sbi_quantize_rows_kernel right before this launch (larger batches: quantising
+// B rows in every block would cost more than the weight stream).
+template <int MB, int NW, int DEPTH, bool PREQ>
 __global__ __launch_bounds__(NW * 64) void sbi_i8_kernel(const GroupParams gp)
 {
     constexpr int NT = NW * 64;
@@ -60,7 +85,8 @@ __global__ __launch_bounds__(NW * 64) void sbi_i8_kernel(const GroupParams gp)
     const GemmParams& p = gp.g[gi];
     const int bid = (int)blockIdx.x - gp.first_block[gi];
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    floatx2* stats = reinterpret_cast<floatx2*>(smem_raw);
+    floatx2* lds_stats = reinterpret_cast<floatx2*>(smem_raw);
+    const floatx2* stats = PREQ ? p.xstats : lds_stats;
     u32x4* xs  = reinterpret_cast<u32x4*>(smem_raw + kLnStatsBytes);
     float* red = reinterpret_cast<float*>(smem_raw + kLnStatsBytes);
     __shared__ int s_flag;
@@ -71,8 +97,10 @@ __global__ __launch_bounds__(NW * 64) void sbi_i8_kernel(const GroupParams gp)
     const int g = lane >> 4;
     const int i = lane & 15;
 
-    i8_stats<NW>(p, stats, wave, lane);
-    __syncthreads();
+    if constexpr (!PREQ) {
+        i8_stats<NW>(p, lds_stats, wave, lane);
+        __syncthreads();
+    }
 
     const int panel = bid / p.S;
     const int split = bid - panel * p.S;
@@ -81,9 +109,15 @@ __global__ __launch_bounds__(NW * 64) void sbi_i8_kernel(const GroupParams gp)
 
     MfmaI8Op<MB> op;
     op.init(p.B, g, i);
-    XStageI8<NT, 2> xst;           // two 32-byte reads per thread in flight: NT*32 bytes of LDS per pass
-    xst.p_stats = stats;
-    stream_panel<NW, DEPTH, 1, false>(p, xs, xst, op, tid, wave, lane, panel, 0, ks0, ks1);
+    if constexpr (PREQ) {
+        XStageCodes<NT, 4> xst;
+        xst.init(p);
+        stream_panel<NW, DEPTH, 1, false>(p, xs, xst, op, tid, wave, lane, panel, 0, ks0, ks1);
+    } else {
+        XStageI8<NT, 2> xst;       // two 32-byte reads per thread in flight: NT*32 bytes of LDS per pass
+        xst.p_stats = lds_stats;
+        stream_panel<NW, DEPTH, 1, false>(p, xs, xst, op, tid, wave, lane, panel, 0, ks0, ks1);
+    }
 
 #pragma unroll
     for (int m = 0; m < MB; ++m) {
@@ -97,36 +131,94 @@ __global__ __launch_bounds__(NW * 64) void sbi_i8_kernel(const GroupParams gp)
     if (p.S > 1) finish_split_k<NT, true>(p, panel, tid, &s_flag, stats);
 }
 
-template <int MB, int NW, int DEPTH>
+template <int MB, int NW, int DEPTH, bool PREQ>
 static int launch_one(const GroupParams& gp, size_t lds, hipStream_t st)
 {
     if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sbi_i8_kernel<MB, NW, DEPTH>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sbi_i8_kernel<MB, NW, DEPTH, PREQ>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return (int)e;
     }
-    hipLaunchKernelGGL((sbi_i8_kernel<MB, NW, DEPTH>), dim3(gp.first_block[gp.G]), dim3(NW * 64), lds, st, gp);
+    hipLaunchKernelGGL((sbi_i8_kernel<MB, NW, DEPTH, PREQ>), dim3(gp.first_block[gp.G]), dim3(NW * 64), lds, st, gp);
     return (int)hipGetLastError();
 }
 
-template <int NW, int DEPTH>
+template <int NW, int DEPTH, bool PREQ>
 static int launch_mb(const GroupParams& gp, size_t lds, hipStream_t st)
 {
     switch ((gp.g[0].B + 15) / 16) {
-        case 1: return launch_one<1, NW, DEPTH>(gp, lds, st);
-        case 2: return launch_one<2, NW, DEPTH>(gp, lds, st);
-        case 3: return launch_one<3, NW, DEPTH>(gp, lds, st);
-        case 4: return launch_one<4, NW, DEPTH>(gp, lds, st);
+        case 1: return launch_one<1, NW, DEPTH, PREQ>(gp, lds, st);
+        case 2: return launch_one<2, NW, DEPTH, PREQ>(gp, lds, st);
+        case 3: return launch_one<3, NW, DEPTH, PREQ>(gp, lds, st);
+        case 4: return launch_one<4, NW, DEPTH, PREQ>(gp, lds, st);
     }
     return (int)hipErrorInvalidValue;
 }
 
-int launch_i8(const GroupParams& gp, int waves, int depth, size_t lds_bytes, hipStream_t st)
+// Quantises the rows of up to kMaxGroup activation matrices [B,K_g] (one block per row): codes
+// to q.codes[g] ([B,K_g] int8), (inv, scale) per row to q.stats[g].  Same decisions as i8_stats /
+// quantize16.  K_g % 16 == 0.
+struct QuantRowsParams {
+    const _Float16* X[kMaxGroup];
+    signed char* codes[kMaxGroup];
+    floatx2* stats[kMaxGroup];
+    int K[kMaxGroup];
+    int B;
+};
+
+__global__ __launch_bounds__(256) void sbi_quantize_rows_kernel(const QuantRowsParams q)
+{
+    __shared__ float s_max[4];
+    const int g = (int)blockIdx.x / q.B, b = (int)blockIdx.x - g * q.B;
+    const int K = q.K[g];
+    const _Float16* row = q.X[g] + (int64_t)b * K;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int pieces = K / 16;
+    float m = 0.f;
+    for (int c = tid; c < pieces; c += 256) {
+        const u32x4* src = reinterpret_cast<const u32x4*>(row + c * 16);
+        const half8 a = __builtin_bit_cast(half8, src[0]);
+        const half8 h = __builtin_bit_cast(half8, src[1]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) m = fmaxf(m, fmaxf(fabsf((float)a[e]), fabsf((float)h[e])));
+    }
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
+    if (lane == 0) s_max[wave] = m;
+    __syncthreads();
+    const float amax = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+    const float inv = (amax > 0.f) ? 127.0f / amax : 0.f;
+    if (tid == 0) q.stats[g][b] = (amax > 0.f) ? floatx2{inv, amax / 127.0f} : floatx2{0.f, 0.f};
+    u32x4* dst = reinterpret_cast<u32x4*>(q.codes[g] + (int64_t)b * K);
+    for (int c = tid; c < pieces; c += 256) {
+        const u32x4* src = reinterpret_cast<const u32x4*>(row + c * 16);
+        dst[c] = quantize16(src[0], src[1], inv);
+    }
+}
+
+int launch_i8(const GroupParams& gp, int waves, int depth, bool prequantized, size_t lds_bytes, hipStream_t st)
 {
     if (gp.G < 1 || gp.G > kMaxGroup) return (int)hipErrorInvalidValue;
-    if (waves == 4 && depth == 2) return launch_mb<4, 2>(gp, lds_bytes, st);
-    if (waves == 4 && depth == 4) return launch_mb<4, 4>(gp, lds_bytes, st);
-    if (waves == 8 && depth == 4) return launch_mb<8, 4>(gp, lds_bytes, st);
+    if (prequantized) {
+        // gp.g[k].X already points at the codes' place in the workspace: fill it from gp.g[k].X16
+        QuantRowsParams q;
+        for (int k = 0; k < gp.G; ++k) {
+            q.X[k] = gp.g[k].X16;
+            q.codes[k] = reinterpret_cast<signed char*>(const_cast<_Float16*>(gp.g[k].X));
+            q.stats[k] = const_cast<floatx2*>(gp.g[k].xstats);
+            q.K[k] = gp.g[k].K;
+        }
+        q.B = gp.g[0].B;
+        hipLaunchKernelGGL(sbi_quantize_rows_kernel, dim3(gp.G * q.B), dim3(256), 0, st, q);
+        if (hipGetLastError() != hipSuccess) return (int)hipErrorInvalidValue;
+        if (waves == 4 && depth == 2) return launch_mb<4, 2, true>(gp, lds_bytes, st);
+        if (waves == 4 && depth == 4) return launch_mb<4, 4, true>(gp, lds_bytes, st);
+        if (waves == 8 && depth == 4) return launch_mb<8, 4, true>(gp, lds_bytes, st);
+        return (int)hipErrorInvalidValue;
+    }
+    if (waves == 4 && depth == 2) return launch_mb<4, 2, false>(gp, lds_bytes, st);
+    if (waves == 4 && depth == 4) return launch_mb<4, 4, false>(gp, lds_bytes, st);
+    if (waves == 8 && depth == 4) return launch_mb<8, 4, false>(gp, lds_bytes, st);
     return (int)hipErrorInvalidValue;
 }
 

@@ -30,9 +30,10 @@ class GemmSpec:
     def weight_bytes(self) -> int:
         return 2 * self.K * self.N
 
-    def algorithmic_bytes(self, B: int) -> int:
-        """HBM bytes one GeMM must move: W once, X, Y, plus bias / residual if used."""
-        n = 2 * self.K * self.N + 2 * B * self.K + 2 * B * self.N
+    def algorithmic_bytes(self, B: int, int8: bool = False) -> int:
+        """HBM bytes one GeMM must move: W once, X, Y, plus bias / residual if used.  INT8: one byte
+        per weight plus a binary32 scale per column; the activations stay fp16 at the boundary."""
+        n = (self.K * self.N + 4 * self.N if int8 else 2 * self.K * self.N) + 2 * B * self.K + 2 * B * self.N
         if self.epilogue in (BIAS, BIAS_GELU, BIAS_RESIDUAL):
             n += 2 * self.N
         if self.epilogue in (BIAS_RESIDUAL, RESIDUAL):

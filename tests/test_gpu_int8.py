@@ -153,3 +153,32 @@ def test_int8_config2_h4096_gemms(gpu, gi, B):
     Y = sb.gemm_i8(Wl, sw_d, spec.K, spec.N, _dev(X, gpu), _dev(bias, gpu) if "bias" in epi else None,
                    _dev(R, gpu) if "residual" in epi else None, epi)
     check(Y.cpu().numpy(), X, Wq, sw, bias, R, epi, f"config2 {spec.name} B={B}")
+
+
+@pytest.mark.parametrize("cfg_id,B,chained", [(1, 4, True), (1, 1, False), (2, 8, False), (2, 3, True)])
+def test_int8_layer_gemms(gpu, cfg_id, B, chained):
+    """sbi_layer_gemms with int8 weights and per-channel scales: the grouped launch runs the INT8
+    kernel; a chained FFN2 quantises the GPU's own fp16 FFN1 output."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    cfg = wl.CONFIGS[cfg_id]
+    data = [wl.make_gemm_inputs(s.K, s.N, B, seed=5, config_id=cfg_id, gemm_id=i) for i, s in enumerate(cfg.gemms)]
+    prep = [prepare(gpu, d[0]) for d in data]
+    biases = [_dev(d[1], gpu) for d in data]
+    h = cfg.gemms[0].K
+    L = sb.make_layer(*[p[0] for p in prep], h, cfg.gemms[0].N, cfg.gemms[1].K, cfg.gemms[2].N, cfg.gemms[3].K,
+                      bqkv=biases[0], bout=biases[1], bffn1=biases[2], bffn2=biases[3], ffn1_gelu=True,
+                      scales=[p[1] for p in prep])
+    ws = sb.new_workspace(sb.layer_workspace_bytes(L, B), gpu)
+    Xs = [_dev(d[2], gpu) for d in data]
+    Rd = _dev(data[3][3], gpu)
+    Ys = [torch.empty((B, s.N), dtype=torch.float16, device=gpu) for s in cfg.gemms]
+    for rep in range(2):
+        sb.layer_gemms(L, B, Xs[0], Xs[1], Xs[2], None if chained else Xs[3], Rd, Ys[0], Ys[1], Ys[2], Ys[3], ws)
+        torch.cuda.synchronize()
+        Yh = [y.cpu().numpy() for y in Ys]
+        for g, (epi, r) in enumerate((("bias", None), ("bias", None), ("bias_gelu", None),
+                                      ("bias_residual", data[3][3]))):
+            xin = Yh[2] if (g == 3 and chained) else data[g][2]
+            check(Yh[g], xin, prep[g][2], prep[g][3], data[g][1], r, epi, f"layer gemm {g}")
+    assert not ws[:256 * 1024].cpu().numpy().any()
