@@ -19,8 +19,9 @@
  *     work is enqueued on it and no call synchronises, except sbi_gemm_layout_check.
  *   - Arguments are validated on the host before any GPU call; a failed validation
  *     enqueues nothing.  No exception crosses the boundary; the result is an sbi_status.
- *   - There is no global mutable state; calls on different streams may overlap as long as
- *     they do not share a workspace.
+ *   - There is no global mutable state (each thread keeps a small memo of the launch plans it
+ *     computed last, nothing else); calls on different streams may overlap as long as they do
+ *     not share a workspace.
  */
 #ifndef SBI_GEMM_H
 #define SBI_GEMM_H
@@ -189,6 +190,8 @@ typedef struct sbi_layernorm {
     const void* gamma;
     const void* beta;
     float eps;
+    const void* moments; /* optional (NULL: the statistics are computed from X): per-panel row moments of X
+                            as written by sbi_gemm_moments for the GeMM that produced X; needs K % 64 == 0 */
 } sbi_layernorm;
 
 sbi_status sbi_gemm_ln(const void* W_laid_out, int64_t K, int64_t N,
@@ -198,6 +201,28 @@ sbi_status sbi_gemm_ln(const void* W_laid_out, int64_t K, int64_t N,
                        const sbi_tuning* tuning);
 
 size_t sbi_gemm_ln_workspace_bytes(int64_t B, int64_t K, int64_t N);
+
+/*
+ * The residual path of the fused layer (paper Sec. III-B fusion rule, Sec. III-D: "bias and
+ * residual addition" run into the next region, which starts with a layer-norm): a GeMM whose
+ * epilogue, besides Y = epilogue(X.W + bias (+ residual)), leaves what the FOLLOWING layer-norm
+ * needs of Y.  A full normalisation needs whole rows, which are spread over the 64-column panels
+ * of different thread blocks, so the epilogue finishes each panel's part:
+ *
+ *     row_moments[b][p] = ( mean, sum of squared deviations from that mean )
+ *                         of the stored fp16 values Y[b, 64p .. min(64p+64, N))      (float2)
+ *
+ * The consuming call (sbi_gemm_ln on Y with ln->moments = row_moments) merges a row's panels
+ * exactly (mean = sum n_p mean_p / K, M2 = sum (M2_p + n_p (mean_p - mean)^2)) instead of reading
+ * the row again for its statistics.  As sbi_gemm_ln (ln may be NULL: no layer-norm in front of
+ * THIS GeMM), fp16 matrix-core path only.
+ *   row_moments  device, 8-byte aligned, float2 [B][ceil(N/64)], written completely
+ */
+sbi_status sbi_gemm_moments(const void* W_laid_out, int64_t K, int64_t N,
+                            const void* X, int64_t B, const sbi_layernorm* ln,
+                            const void* bias, const void* residual, sbi_epilogue epi,
+                            void* Y, void* row_moments, void* workspace, size_t workspace_bytes, void* hip_stream,
+                            const sbi_tuning* tuning);
 
 /*
  * INT8 GeMM (paper Sec. III-D, "Support for Different Data Types": an INT8 GeMM with the quantize

@@ -31,7 +31,8 @@ EXPORTS = ["sbi_gemm_layout_bytes", "sbi_gemm_workspace_bytes", "sbi_gemm_layout
            "sbi_gemm_plan", "sbi_layer_gemms", "sbi_layer_workspace_bytes", "sbi_status_string",
            "sbi_version", "sbi_calib_read", "sbi_calib_copy", "sbi_layer_plan", "sbi_gemm_ln",
            "sbi_gemm_ln_workspace_bytes", "sbi_gemm_i8_layout_bytes", "sbi_gemm_i8_workspace_bytes",
-           "sbi_gemm_i8_quantize_weights", "sbi_gemm_i8_layout_weights", "sbi_gemm_i8_layout_check", "sbi_gemm_i8"]
+           "sbi_gemm_i8_quantize_weights", "sbi_gemm_i8_layout_weights", "sbi_gemm_i8_layout_check", "sbi_gemm_i8",
+           "sbi_gemm_moments"]
 
 
 class SbiError(RuntimeError):
@@ -48,7 +49,8 @@ class Tuning(ctypes.Structure):
 
 
 class LayerNorm(ctypes.Structure):
-    _fields_ = [("gamma", ctypes.c_void_p), ("beta", ctypes.c_void_p), ("eps", ctypes.c_float)]
+    _fields_ = [("gamma", ctypes.c_void_p), ("beta", ctypes.c_void_p), ("eps", ctypes.c_float),
+                ("moments", ctypes.c_void_p)]
 
 
 class Plan(ctypes.Structure):
@@ -105,6 +107,9 @@ def load():
     L.sbi_gemm_ln.restype = i32
     L.sbi_gemm_ln.argtypes = [vp, i64, i64, vp, i64, ctypes.POINTER(LayerNorm), vp, vp, i32, vp, vp, sz, vp,
                               ctypes.POINTER(Tuning)]
+    L.sbi_gemm_moments.restype = i32
+    L.sbi_gemm_moments.argtypes = [vp, i64, i64, vp, i64, ctypes.POINTER(LayerNorm), vp, vp, i32, vp, vp, vp, sz, vp,
+                                   ctypes.POINTER(Tuning)]
     L.sbi_gemm_ln_workspace_bytes.restype = sz
     L.sbi_gemm_ln_workspace_bytes.argtypes = [i64, i64, i64]
     L.sbi_gemm_i8_layout_bytes.restype = sz
@@ -298,9 +303,12 @@ def gemm_i8(Wl, sw, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=No
 
 
 def gemm(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, workspace=None,
-         path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0, panels=0, layernorm=None):
+         path=PATH_AUTO, split_k=0, waves=0, depth=0, blocks=0, panels=0, layernorm=None, moments_in=None,
+         moments_out=None):
     """Y = epilogue(X @ W + bias) through sbi_gemm / sbi_gemm_ex, or, with
     layernorm=(gamma, beta, eps), Y = epilogue(LN(X) @ W + bias) through sbi_gemm_ln.
+    moments_out (float32 [B, ceil(N/64), 2]) receives the per-panel row moments of Y
+    (sbi_gemm_moments); moments_in passes such moments of X to the layer-norm.
     Returns Y (fp16 [B,N])."""
     import torch
     assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.is_contiguous()
@@ -329,12 +337,31 @@ def gemm(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, wor
         _need_bytes(workspace, 0, "workspace")
     ws_ptr = _ptr(workspace)
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    if layernorm is not None:
-        gamma, beta, eps = layernorm
-        ln = LayerNorm(gamma.data_ptr(), beta.data_ptr(), float(eps))
-        st = load().sbi_gemm_ln(_ptr(Wl), K, N, _ptr(X), B, ctypes.byref(ln), _ptr(bias), _ptr(residual),
-                                int(epilogue), _ptr(out), ws_ptr, ws_len, _stream(), tune)
-        _check(st, "sbi_gemm_ln")
+    if moments_in is not None:
+        if layernorm is None:
+            raise ValueError("moments_in belongs to a layer-norm")
+        if not (moments_in.is_cuda and moments_in.dtype == torch.float32 and moments_in.is_contiguous()
+                and tuple(moments_in.shape) == (B, -(-K // 64), 2)):
+            raise ValueError("moments_in: expected contiguous CUDA float32 [B, ceil(K/64), 2]")
+    if moments_out is not None:
+        if not (moments_out.is_cuda and moments_out.dtype == torch.float32 and moments_out.is_contiguous()
+                and tuple(moments_out.shape) == (B, -(-N // 64), 2)):
+            raise ValueError("moments_out: expected contiguous CUDA float32 [B, ceil(N/64), 2]")
+    if layernorm is not None or moments_out is not None:
+        ln = None
+        if layernorm is not None:
+            gamma, beta, eps = layernorm
+            ln = LayerNorm(gamma.data_ptr(), beta.data_ptr(), float(eps),
+                           moments_in.data_ptr() if moments_in is not None else None)
+        lnp = ctypes.byref(ln) if ln is not None else None
+        if moments_out is not None:
+            st = load().sbi_gemm_moments(_ptr(Wl), K, N, _ptr(X), B, lnp, _ptr(bias), _ptr(residual),
+                                         int(epilogue), _ptr(out), _ptr(moments_out), ws_ptr, ws_len, _stream(), tune)
+            _check(st, "sbi_gemm_moments")
+        else:
+            st = load().sbi_gemm_ln(_ptr(Wl), K, N, _ptr(X), B, lnp, _ptr(bias), _ptr(residual),
+                                    int(epilogue), _ptr(out), ws_ptr, ws_len, _stream(), tune)
+            _check(st, "sbi_gemm_ln")
         return out
     if tune is None:
         st = load().sbi_gemm(_ptr(Wl), K, N, _ptr(X), B, _ptr(bias), _ptr(residual), int(epilogue),

@@ -236,6 +236,8 @@ struct GemmArgs {
     const void* Wl; int64_t K, N; const void* X; const void* bias; const void* R; int flags; void* Y;
     const void* gamma; const void* beta; float eps;     // layer-norm of X's rows when gamma != null
     const void* sw;                                     // INT8: per-column weight scales (binary32 [N])
+    void* moments_out;                                  // per-panel row moments of Y for a following layer-norm
+    const void* ln_moments;                             // such moments of X, for this call's layer-norm
 };
 
 // Validation of a layer-norm request in front of a GeMM with K input features.
@@ -315,6 +317,8 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
     p.KS = (int)(pl.i8 ? ksteps_of_i8(a.K) : ksteps_of(a.K)); p.P = (int)ceil_div(a.N, kPanelN);
     p.S = pl.S; p.ksps = pl.ksps; p.kc = pl.kc;
     p.sw = reinterpret_cast<const float*>(a.sw);
+    p.moments_out = reinterpret_cast<floatx2*>(a.moments_out);
+    p.ln_moments = reinterpret_cast<const floatx2*>(a.gamma ? a.ln_moments : nullptr);
     p.X16 = p.X;
     p.xstats = nullptr;
     if (pl.preq) {                      // codes and row scales live at byte offset xq_off of the workspace
@@ -364,7 +368,52 @@ int resident_waves(int mb, int nw, int depth, int pw, bool ln, bool i8, bool pre
 // CU can hold at once follow from the LDS each block needs for its X chunks and from the
 // register file.  Returns per-problem plans plus the launch totals in `tot` (nw, depth, lds,
 // grid, ws_bytes).
+sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot, bool ln,
+                             bool i8);
+
+// The search below is a pure function of its arguments and costs 10-25 us; a serving loop asks
+// for the same few launches over and over, so each thread remembers its last results.
 sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot, bool ln, bool i8)
+{
+    struct Entry {
+        int64_t B, Ks[kMaxGroup], Ns[kMaxGroup];
+        int G, flags;
+        Plan pls[kMaxGroup], tot;
+        sbi_status status;
+        bool used;
+    };
+    constexpr int kEntries = 16;
+    static thread_local Entry memo[kEntries];
+    static thread_local int next = 0;
+    if (G < 1 || G > kMaxGroup) return SBI_ERR_SHAPE;
+#ifdef SBI_DEV
+    if (getenv("SBI_PLAN_FORCE")) return plan_group_search(B, Ks, Ns, G, pls, tot, ln, i8);
+#endif
+    const int flags = (ln ? 1 : 0) | (i8 ? 2 : 0);
+    for (int e = 0; e < kEntries; ++e) {
+        const Entry& m = memo[e];
+        if (!m.used || m.B != B || m.G != G || m.flags != flags) continue;
+        bool same = true;
+        for (int g = 0; g < G; ++g) same = same && m.Ks[g] == Ks[g] && m.Ns[g] == Ns[g];
+        if (!same) continue;
+        for (int g = 0; g < G; ++g) pls[g] = m.pls[g];
+        tot = m.tot;
+        return m.status;
+    }
+    Entry& m = memo[next];
+    next = (next + 1) % kEntries;
+    m.used = false;
+    m.status = plan_group_search(B, Ks, Ns, G, m.pls, m.tot, ln, i8);
+    m.B = B; m.G = G; m.flags = flags;
+    for (int g = 0; g < G; ++g) { m.Ks[g] = Ks[g]; m.Ns[g] = Ns[g]; }
+    m.used = true;
+    for (int g = 0; g < G; ++g) pls[g] = m.pls[g];
+    tot = m.tot;
+    return m.status;
+}
+
+sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot, bool ln,
+                             bool i8)
 {
     if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
     const int mb = (int)ceil_div(B, 16);
@@ -617,7 +666,8 @@ static sbi_status gemm_impl(const void* W_laid_out, int64_t K, int64_t N,
                             const void* X, int64_t B, const sbi_layernorm* ln,
                             const void* bias, const void* residual, sbi_epilogue epi,
                             void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
-                            const sbi_tuning* tuning, const void* w_scales = nullptr, bool i8 = false)
+                            const sbi_tuning* tuning, const void* w_scales = nullptr, bool i8 = false,
+                            void* moments_out = nullptr)
 {
     int flags = 0;
     if (sbi_status s = check_gemm_args(W_laid_out, K, N, X, B, bias, residual, (int)epi, Y, flags)) return s;
@@ -625,8 +675,12 @@ static sbi_status gemm_impl(const void* W_laid_out, int64_t K, int64_t N,
     if (tuning) t = *tuning;
     t.layernorm = ln ? 1 : 0;
     t.int8 = i8 ? 1 : 0;
-    if (ln)
+    if (ln) {
         if (sbi_status s = check_layernorm(ln->gamma, ln->beta, ln->eps, K)) return s;
+        if (ln->moments && (K % kPanelN != 0)) return SBI_ERR_SHAPE;      // moments come in 64-feature panels
+        if (ln->moments && !aligned(ln->moments, 8)) return SBI_ERR_ALIGN;
+    }
+    if (moments_out && !aligned(moments_out, 8)) return SBI_ERR_ALIGN;
     if (i8) {
         if (!w_scales) return SBI_ERR_NULL;
         if (K % kI8ChunkK != 0) return SBI_ERR_SHAPE;
@@ -639,9 +693,10 @@ static sbi_status gemm_impl(const void* W_laid_out, int64_t K, int64_t N,
         if (!aligned(workspace, 256)) return SBI_ERR_ALIGN;
     }
     hipStream_t st = (hipStream_t)hip_stream;
-    GemmArgs a = {W_laid_out, K, N, X, bias, residual, flags, Y, nullptr, nullptr, 0.0f, w_scales};
+    GemmArgs a = {W_laid_out, K, N, X, bias, residual, flags, Y, nullptr, nullptr, 0.0f, w_scales, moments_out, nullptr};
+    if (moments_out && (pl.path != SBI_PATH_MFMA || i8)) return SBI_ERR_TUNING;   // only the fp16 matrix-core kernel emits them
     if (pl.path == SBI_PATH_STREAMK) return launch_group(&a, 1, B, pl, workspace, st);
-    if (ln) { a.gamma = ln->gamma; a.beta = ln->beta; a.eps = ln->eps; }
+    if (ln) { a.gamma = ln->gamma; a.beta = ln->beta; a.eps = ln->eps; a.ln_moments = ln->moments; }
     Plan one = pl;
     one.ws_bytes = (pl.S > 1) ? ceil_div(N, kPanelN) * pl.S * B * kPanelN * 4 : 0;      // its partial sums
     if (pl.path == SBI_PATH_MFMA) return launch_block_group(&a, &one, pl, 1, B, workspace, st);
@@ -679,6 +734,18 @@ sbi_status sbi_gemm_ln(const void* W_laid_out, int64_t K, int64_t N,
     if (tuning && tuning->int8) return SBI_ERR_TUNING;
     return gemm_impl(W_laid_out, K, N, X, B, ln, bias, residual, epi, Y, workspace, workspace_bytes,
                      hip_stream, tuning);
+}
+
+sbi_status sbi_gemm_moments(const void* W_laid_out, int64_t K, int64_t N,
+                            const void* X, int64_t B, const sbi_layernorm* ln,
+                            const void* bias, const void* residual, sbi_epilogue epi,
+                            void* Y, void* row_moments, void* workspace, size_t workspace_bytes, void* hip_stream,
+                            const sbi_tuning* tuning)
+{
+    if (!row_moments) return SBI_ERR_NULL;
+    if (tuning && tuning->int8) return SBI_ERR_TUNING;
+    return gemm_impl(W_laid_out, K, N, X, B, ln, bias, residual, epi, Y, workspace, workspace_bytes,
+                     hip_stream, tuning, nullptr, false, row_moments);
 }
 
 size_t sbi_gemm_i8_layout_bytes(int64_t K, int64_t N)

@@ -24,23 +24,57 @@ __device__ __forceinline__ float apply_epilogue(const GemmParams& p, float v, in
 
 // Store the column pair (n, n+1) of row b; n is even.  One 4-byte store when both
 // columns exist and the row pitch keeps it aligned, 2-byte stores otherwise.
-__device__ __forceinline__ void store_pair(const GemmParams& p, int b, int n, float s0, float s1)
+// Epilogue, one rounding to fp16 and store of two adjacent outputs; y0, y1 receive the stored
+// (rounded) values, 0 where the column does not exist.
+__device__ __forceinline__ void store_pair(const GemmParams& p, int b, int n, float s0, float s1,
+                                           float& y0, float& y1)
 {
+    y0 = y1 = 0.f;
     if (n >= p.N) return;
     const int64_t off = (int64_t)b * p.N + n;
-    const float v0 = apply_epilogue(p, s0, b, n);
+    const _Float16 h0 = (_Float16)apply_epilogue(p, s0, b, n);
+    y0 = (float)h0;
     if (n + 1 < p.N) {
-        const float v1 = apply_epilogue(p, s1, b, n + 1);
+        const _Float16 h1 = (_Float16)apply_epilogue(p, s1, b, n + 1);
+        y1 = (float)h1;
         if ((p.N & 1) == 0) {
-            half2v h = {(_Float16)v0, (_Float16)v1};
+            half2v h = {h0, h1};
             *reinterpret_cast<half2v*>(p.Y + off) = h;
         } else {
-            p.Y[off] = (_Float16)v0;
-            p.Y[off + 1] = (_Float16)v1;
+            p.Y[off] = h0;
+            p.Y[off + 1] = h1;
         }
     } else {
-        p.Y[off] = (_Float16)v0;
+        p.Y[off] = h0;
     }
+}
+
+__device__ __forceinline__ void store_pair(const GemmParams& p, int b, int n, float s0, float s1)
+{
+    float y0, y1;
+    store_pair(p, b, n, s0, s1, y0, y1);
+}
+
+// The next layer-norm's share of this epilogue (paper Sec. III-B / III-D: bias, residual and
+// the following layer-norm belong to one fused region; a full normalisation needs the whole
+// row, which is spread over the panels of different blocks, so what the epilogue can finish is
+// each panel's part): the 32 consecutive lanes that have just stored one row's 64 outputs of a
+// panel reduce (mean, sum of squared deviations from it) over the stored fp16 values and write
+// them to moments_out[b][panel]; the consuming kernel merges the panels of a row exactly
+// (ln_stats_from_moments) instead of reading the row again.
+__device__ __forceinline__ void emit_moments(const GemmParams& p, int b, int panel, int n, float y0, float y1, int lane)
+{
+    const int cnt = min(kPanelN, p.N - panel * kPanelN);         // columns of this panel that exist
+    float s = y0 + y1;                                            // absent columns were returned as 0
+#pragma unroll
+    for (int m = 16; m >= 1; m >>= 1) s += __shfl_xor(s, m, 32);  // the other half of the wave may hold another row, or none
+    const float mean = s / (float)cnt;
+    const float d0 = (n < p.N) ? y0 - mean : 0.f;
+    const float d1 = (n + 1 < p.N) ? y1 - mean : 0.f;
+    float q = d0 * d0 + d1 * d1;
+#pragma unroll
+    for (int m = 16; m >= 1; m >>= 1) q += __shfl_xor(q, m, 32);
+    if ((lane & 31) == 0) p.moments_out[(int64_t)b * p.P + panel] = floatx2{mean, q};
 }
 
 // ---- layer normalisation in front of the GeMM (paper Sec. III-D, regions 1 and 3) ----------
@@ -77,10 +111,37 @@ __device__ __forceinline__ float piece_sqdev(u32x4 h, float mean)
     return t;
 }
 
+// Row statistics from the per-panel moments the producing GeMM's epilogue left behind
+// (emit_moments; panels of 64 features, K % 64 == 0): the exact pairwise merge
+//   mean = sum_p n_p mean_p / K,   M2 = sum_p (M2_p + n_p (mean_p - mean)^2),   var = M2 / K.
+template <int NW>
+__device__ __forceinline__ void ln_stats_from_moments(const GemmParams& p, floatx2* stats, int wave, int lane)
+{
+    const int P = p.K / kPanelN;
+    for (int r = wave; r < p.B; r += NW) {
+        const floatx2* m = p.ln_moments + (int64_t)r * P;
+        float s = 0.f;
+        for (int j = lane; j < P; j += 64) s += m[j][0];
+        const float mean = wave_sum(s) / (float)P;
+        float q = 0.f;
+        for (int j = lane; j < P; j += 64) {
+            const floatx2 v = m[j];
+            const float d = v[0] - mean;
+            q += v[1] + (float)kPanelN * d * d;
+        }
+        const float var = wave_sum(q) / (float)p.K;
+        if (lane == 0) stats[r] = floatx2{mean, 1.0f / sqrtf(var + p.ln_eps)};
+    }
+}
+
 // R rows per wave at a time (rows r, r + NW, ...), so that their loads share one memory latency.
 template <int NW>
 __device__ __forceinline__ void ln_stats(const GemmParams& p, floatx2* stats, int wave, int lane)
 {
+    if (p.ln_moments) {
+        ln_stats_from_moments<NW>(p, stats, wave, lane);
+        return;
+    }
     constexpr int U = 8;                       // 128-bit loads in flight per lane and row: 4096 elements
     constexpr int R = 2;
     const int pieces = p.K / kChunkK;
@@ -524,8 +585,13 @@ __device__ __forceinline__ void reduce_rows(const GemmParams& p, const float* re
         }
         const int n = panel * kPanelN + c2;
         if (p.S == 1) {
-            if constexpr (I8) store_pair(p, b, n, dequant(p, i0, b, n, stats), dequant(p, i1, b, n + 1, stats));
-            else store_pair(p, b, n, s0, s1);
+            if constexpr (I8) {
+                store_pair(p, b, n, dequant(p, i0, b, n, stats), dequant(p, i1, b, n + 1, stats));
+            } else {
+                float y0, y1;
+                store_pair(p, b, n, s0, s1, y0, y1);
+                if (p.moments_out) emit_moments(p, b, panel, n, y0, y1, tid);      // tid & 31 == lane & 31
+            }
         } else {
             float* dst = p.partials + (((int64_t)panel * p.S + split) * p.B + b) * kPanelN + c2;
             if constexpr (I8) store_partial(dst, __builtin_bit_cast(float, i0), __builtin_bit_cast(float, i1));
@@ -576,8 +642,13 @@ __device__ __forceinline__ void finish_split_k(const GemmParams& p, int panel, i
             }
         }
         const int n = panel * kPanelN + c2;
-        if constexpr (I8) store_pair(p, b, n, dequant(p, i0, b, n, stats), dequant(p, i1, b, n + 1, stats));
-        else store_pair(p, b, n, s0, s1);
+        if constexpr (I8) {
+            store_pair(p, b, n, dequant(p, i0, b, n, stats), dequant(p, i1, b, n + 1, stats));
+        } else {
+            float y0, y1;
+            store_pair(p, b, n, s0, s1, y0, y1);
+            if (p.moments_out) emit_moments(p, b, panel, n, y0, y1, tid);
+        }
     }
     if (tid == 0)
         __hip_atomic_store(p.counters + panel, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -62,6 +62,8 @@ struct GemmParams {
     const _Float16* ln_gamma;  // [K]; in a launch of the layer-norm kernel variant always readable
     const _Float16* ln_beta;   // [K]    (problems with ln == 0 point both at X)
     float ln_eps;
+    floatx2* moments_out;      // or null: per row and 64-column panel (mean, sum of squared deviations) of Y
+    const floatx2* ln_moments; // or null: such moments of X's rows (64-wide panels), instead of reading the rows
     const float* sw;           // INT8 path: per-column weight scales [N]
     const _Float16* X16;       // INT8 path with activations quantised by a kernel of their own: the fp16 X
     const floatx2* xstats;     //   (X then points at the codes [B,K] int8) and the rows' (inv, scale) [B]

@@ -41,6 +41,8 @@ void launch(unsigned grid, unsigned block, size_t lds, const std::function<void(
         const unsigned nwaves = (block + 63) / 64;
         for (unsigned w = 0; w < nwaves; ++w)
             pthread_barrier_init(&blk.wave[w], nullptr, std::min(64u, block - w * 64));
+        for (unsigned h = 0; h < (block + 31) / 32; ++h)
+            pthread_barrier_init(&blk.half[h], nullptr, std::min(32u, block - h * 32));
         std::vector<std::thread> th;
         th.reserve(block);
         for (unsigned t = 0; t < block; ++t)
@@ -51,6 +53,7 @@ void launch(unsigned grid, unsigned block, size_t lds, const std::function<void(
             });
         for (auto& x : th) x.join();
         for (unsigned w = 0; w < nwaves; ++w) pthread_barrier_destroy(&blk.wave[w]);
+        for (unsigned h = 0; h < (block + 31) / 32; ++h) pthread_barrier_destroy(&blk.half[h]);
         pthread_barrier_destroy(&blk.all);
         free(blk.lds);
     }

@@ -71,8 +71,8 @@ int main(int argc, char** argv)
     if (argc < 9) { fprintf(stderr, "usage: B K N waves depth split panels ln\n"); return 9; }
     const int B = atoi(argv[1]); const int64_t K = atoll(argv[2]), N = atoll(argv[3]);
     sbi_tuning t = {SBI_PATH_MFMA, atoi(argv[6]), atoi(argv[4]), atoi(argv[5]), 0, atoi(argv[7]), 0};
-    const int mode = atoi(argv[8]);         // 0 plain, 1 layer-norm, 2 int8
-    const int ln = mode == 1, i8 = mode == 2;
+    const int mode = atoi(argv[8]);         // 0 plain, 1 layer-norm, 2 int8, 3 plain + emitted moments, 4 layer-norm fed by moments
+    const int ln = mode == 1 || mode == 4, i8 = mode == 2;
     if (t.waves == 0) t.path = SBI_PATH_AUTO;
     std::mt19937 rng(7);
     _Float16* W = halfs((size_t)K * N, rng, 0.02f);
@@ -104,8 +104,25 @@ int main(int argc, char** argv)
     const size_t wsb = pl.workspace_bytes;
     void* ws = exact_alloc(256, wsb ? wsb : 256);
     memset(ws, 0, wsb ? wsb : 256);
-    sbi_layernorm l = {g1, b1, 1e-5f};
-    if (i8) st = sbi_gemm_i8(Wl8, swd, K, N, X, B, bias, R, SBI_EPI_BIAS_RESIDUAL, Y, ws, wsb, nullptr, &t);
+    sbi_layernorm l = {g1, b1, 1e-5f, nullptr};
+    const int64_t Pn = (N + 63) / 64, Pk = (K + 63) / 64;
+    float* mom_out = (float*)exact_alloc(8, (size_t)B * Pn * 8);
+    float* mom_in = (float*)exact_alloc(8, (size_t)B * Pk * 8);
+    if (mode == 4) {                         // what a producing GeMM would have left for these rows
+        if (K % 64) { fprintf(stderr, "mode 4 needs K %% 64 == 0\n"); return 9; }
+        for (int b = 0; b < B; ++b)
+            for (int64_t pp = 0; pp < Pk; ++pp) {
+                double m = 0, q = 0;
+                for (int j = 0; j < 64; ++j) m += (double)X[(size_t)b * K + pp * 64 + j];
+                m /= 64;
+                for (int j = 0; j < 64; ++j) { const double d = (double)X[(size_t)b * K + pp * 64 + j] - m; q += d * d; }
+                mom_in[((size_t)b * Pk + pp) * 2] = (float)m;
+                mom_in[((size_t)b * Pk + pp) * 2 + 1] = (float)q;
+            }
+        l.moments = mom_in;
+    }
+    if (mode == 3) st = sbi_gemm_moments(Wl, K, N, X, B, nullptr, bias, R, SBI_EPI_BIAS_RESIDUAL, Y, mom_out, ws, wsb, nullptr, &t);
+    else if (i8) st = sbi_gemm_i8(Wl8, swd, K, N, X, B, bias, R, SBI_EPI_BIAS_RESIDUAL, Y, ws, wsb, nullptr, &t);
     else if (ln) st = sbi_gemm_ln(Wl, K, N, X, B, &l, bias, R, SBI_EPI_BIAS_RESIDUAL, Y, ws, wsb, nullptr, &t);
     else st = sbi_gemm_ex(Wl, K, N, X, B, bias, R, SBI_EPI_BIAS_RESIDUAL, Y, ws, wsb, nullptr, &t);
     fprintf(stderr, "status %d (%s)\n", (int)st, sbi_status_string(st));
@@ -138,6 +155,21 @@ int main(int argc, char** argv)
         }
         fprintf(stderr, "max abs error vs fp64 reference: %g\n", worst);
         if (!(worst < 6e-3)) return 2;
+        if (mode == 3) {
+            double werr = 0;
+            for (int b = 0; b < B; ++b)
+                for (int64_t pp = 0; pp < Pn; ++pp) {
+                    const int64_t n0 = pp * 64, n1 = (n0 + 64 < N) ? n0 + 64 : N;
+                    double m = 0, q = 0;
+                    for (int64_t n = n0; n < n1; ++n) m += (double)Y[(size_t)b * N + n];
+                    m /= (double)(n1 - n0);
+                    for (int64_t n = n0; n < n1; ++n) { const double d = (double)Y[(size_t)b * N + n] - m; q += d * d; }
+                    werr = std::fmax(werr, std::fabs(mom_out[((size_t)b * Pn + pp) * 2] - m) / (1e-6 + std::fabs(m)));
+                    werr = std::fmax(werr, std::fabs(mom_out[((size_t)b * Pn + pp) * 2 + 1] - q) / (1e-5 + q));
+                }
+            fprintf(stderr, "max relative error of the emitted moments: %g\n", werr);
+            if (!(werr < 1e-3)) return 3;
+        }
     }
     return 0;
 }

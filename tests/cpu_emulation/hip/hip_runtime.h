@@ -34,6 +34,7 @@ struct Block {
     int nthreads;
     pthread_barrier_t all;
     pthread_barrier_t wave[16];
+    pthread_barrier_t half[32];       // 32-lane halves of the waves, for shuffles of width 32
     unsigned char* lds;
     size_t lds_bytes;
     // exchange areas for wave-wide operations
@@ -52,14 +53,17 @@ inline unsigned char* lds() { return t_block->lds; }
 
 inline void __syncthreads() { pthread_barrier_wait(&emu::t_block->all); }
 
+// width 64: all lanes of the wave take part; width 32: the two halves of a wave are independent
+// (one of them may be elsewhere in the program), mask < 32
 inline float __shfl_xor(float v, int mask, int width = 64)
 {
     emu::Block* b = emu::t_block;
     const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    pthread_barrier_t* bar = (width == 32) ? &b->half[threadIdx.x >> 5] : &b->wave[w];
     b->shf[w][l] = v;
-    pthread_barrier_wait(&b->wave[w]);
+    pthread_barrier_wait(bar);
     const float r = b->shf[w][l ^ mask];
-    pthread_barrier_wait(&b->wave[w]);
+    pthread_barrier_wait(bar);
     return r;
 }
 inline int __shfl_xor(int v, int mask, int width = 64)

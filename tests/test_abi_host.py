@@ -182,8 +182,8 @@ def test_layer_argument_validation(lib):
 
 
 def _gemm_ln(lib, gamma=FAKE + (5 << 30), beta=FAKE + (6 << 30), eps=1e-5, K=4096, N=4096, B=4, ln=True,
-             tune=None, ws_bytes=1 << 30):
-    lnp = ctypes.byref(sb.LayerNorm(gamma, beta, eps)) if ln else None
+             tune=None, ws_bytes=1 << 30, moments=None):
+    lnp = ctypes.byref(sb.LayerNorm(gamma, beta, eps, moments)) if ln else None
     return lib.sbi_gemm_ln(FAKE, K, N, FAKE + (1 << 30), B, lnp, None, None, 0, FAKE + (2 << 30),
                            FAKE + (3 << 30), ws_bytes, None, tune)
 
@@ -294,3 +294,17 @@ def test_int8_argument_validation_and_plans(lib):
             assert 1 <= S <= KS and ksps * S >= KS and ksps * (S - 1) < KS and pl["grid"] == P * S
             buffers = 1 if kc >= ksps else 2
             assert 512 + max(buffers * kc * B * 64, pl["waves"] * 16 * 68 * 4) <= pl["lds_bytes"] <= 128 * 1024
+
+
+def test_moments_argument_validation(lib):
+    mom = FAKE + (8 << 30)
+    assert _gemm_ln(lib, moments=mom, ws_bytes=0) == 6             # (no launch without a workspace)
+    assert _gemm_ln(lib, moments=mom + 4, ws_bytes=0) == 3         # float2 entries: 8-byte aligned
+    assert _gemm_ln(lib, moments=mom, K=4128, ws_bytes=0) == 2     # moments come in 64-feature panels
+    call = lambda out=mom, tune=None, ws_bytes=0: lib.sbi_gemm_moments(
+        FAKE, 4096, 4096, FAKE + (1 << 30), 4, None, None, None, 0, FAKE + (2 << 30), out, FAKE + (3 << 30),
+        ws_bytes, None, tune)
+    assert call(out=None) == 1 and call(out=mom + 2) == 3 and call() == 6
+    for bad in (sb.Tuning(sb.PATH_STREAM, 0, 0, 0, 0, 0, 0, 0), sb.Tuning(sb.PATH_STREAMK, 0, 0, 0, 0, 0, 0, 0),
+                sb.Tuning(0, 0, 0, 0, 0, 0, 0, 1)):
+        assert call(tune=ctypes.byref(bad), ws_bytes=1 << 30) == 10

@@ -211,3 +211,60 @@ def test_ln_layer_under_graph_replay(gpu):
                               ulps=2, abs_tol=1e-3)
     assert ok, rep
     assert not ws[:256 * 1024].cpu().numpy().any()
+
+
+@pytest.mark.parametrize("B,K,N,split", [(1, 256, 64, 0), (4, 1024, 200, 0), (8, 2048, 4096, 0), (17, 512, 136, 0),
+                                         (5, 4096, 192, 4), (33, 1024, 72, 3), (64, 2048, 128, 2)])
+def test_epilogue_emits_panel_moments_of_the_stored_outputs(gpu, B, K, N, split):
+    """sbi_gemm_moments: per row and 64-column panel (mean, sum of squared deviations) of the fp16
+    values the call stored, also for ragged last panels and for split-K launches (where the
+    last-arriving block finishes the panel)."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=B + N, config_id=205)
+    Wl = sb.layout_weights(_dev(W, gpu))
+    P = -(-N // 64)
+    mom = torch.full((B, P, 2), float("nan"), dtype=torch.float32, device=gpu)
+    tune = dict(path=sb.PATH_MFMA, split_k=split, waves=4, depth=4 if B <= 16 else 2) if split else {}
+    Y = sb.gemm(Wl, K, N, _dev(X, gpu), _dev(bias, gpu), _dev(R, gpu), "bias_residual", moments_out=mom, **tune)
+    torch.cuda.synchronize()
+    Yh = Y.cpu().numpy()
+    ok, rep = orc.check_close(Yh, orc.gemm(X, W, bias, R, epi=orc.EPI_BIAS | orc.EPI_RES), ulps=2, abs_tol=1e-3)
+    assert ok, rep
+    m = mom.cpu().numpy().astype(np.float64)
+    Yd = Yh.astype(np.float64)
+    for p in range(P):
+        seg = Yd[:, 64 * p:min(64 * p + 64, N)]
+        mean = seg.mean(axis=1)
+        m2 = ((seg - mean[:, None]) ** 2).sum(axis=1)
+        assert np.allclose(m[:, p, 0], mean, rtol=1e-5, atol=1e-6), (p, m[:, p, 0], mean)
+        assert np.allclose(m[:, p, 1], m2, rtol=1e-4, atol=1e-5), (p, m[:, p, 1], m2)
+
+
+@pytest.mark.parametrize("B,K1,H,N2", [(1, 512, 1024, 192), (4, 1024, 4096, 200), (8, 4096, 4096, 1024),
+                                       (16, 256, 2048, 136), (40, 512, 1024, 72)])
+def test_residual_path_feeds_the_next_layernorm(gpu, B, K1, H, N2):
+    """A GeMM with bias + residual whose epilogue leaves the row moments of its output, and the
+    next GeMM whose layer-norm takes its statistics from them instead of reading the rows:
+    compared with the oracle (layer-norm of the fp16 rows the first call stored) and with the
+    same second call computing its statistics itself."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    W1, b1, X, R = wl.make_gemm_inputs(K1, H, B, seed=B + H, config_id=206)
+    W2, b2, _, _ = wl.make_gemm_inputs(H, N2, B, seed=B + H, config_id=207)
+    gamma, beta, _ = wl.make_layernorm_inputs(H, B, seed=B, config_id=206)
+    R = (R.astype(np.float32) * 3 + 0.7).astype(np.float16)          # a residual stream with its own mean and spread
+    Wl1, Wl2 = sb.layout_weights(_dev(W1, gpu)), sb.layout_weights(_dev(W2, gpu))
+    mom = torch.empty((B, H // 64, 2), dtype=torch.float32, device=gpu)
+    g, be = _dev(gamma, gpu), _dev(beta, gpu)
+    Y1 = sb.gemm(Wl1, K1, H, _dev(X, gpu), _dev(b1, gpu), _dev(R, gpu), "bias_residual", moments_out=mom)
+    Y2 = sb.gemm(Wl2, H, N2, Y1, _dev(b2, gpu), None, "bias_gelu", layernorm=(g, be, EPS), moments_in=mom)
+    Y2b = sb.gemm(Wl2, H, N2, Y1, _dev(b2, gpu), None, "bias_gelu", layernorm=(g, be, EPS))
+    torch.cuda.synchronize()
+    Y1h = Y1.cpu().numpy()
+    want = orc.gemm(orc.layernorm(Y1h, gamma, beta, EPS), W2, b2, None, epi=orc.EPI_BIAS | orc.EPI_GELU)
+    for y, name in ((Y2, "statistics from the moments"), (Y2b, "statistics from the rows")):
+        ok, rep = orc.check_close(y.cpu().numpy(), want, ulps=2, abs_tol=1e-3)
+        assert ok, f"{name}: {rep}"
+    ok, rep = orc.check_close(Y2.cpu().numpy(), Y2b.cpu().numpy(), ulps=1, abs_tol=5e-4)
+    assert ok, rep
