@@ -59,6 +59,8 @@ def lib():
         L.sbi_oracle_quantize_columns.argtypes = [vp, i64, i64, vp, vp]
         L.sbi_oracle_gemm_i8.restype = ctypes.c_int
         L.sbi_oracle_gemm_i8.argtypes = [vp] * 6 + [ctypes.c_int, i64, i64, i64, vp, vp]
+        L.sbi_oracle_attn_decode.restype = ctypes.c_int
+        L.sbi_oracle_attn_decode.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, ctypes.c_double, vp, vp]
         L.sbi_oracle_max_threads.restype = ctypes.c_int
         L.sbi_oracle_gemm.restype = ctypes.c_int
         L.sbi_oracle_gemm.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] + [ctypes.c_int64] * 3 + \
@@ -215,6 +217,31 @@ def gemm_i8_from_fp16(X, Wq, sw, bias=None, residual=None, epi=0):
     """The whole INT8 path on fp16 activations: quantise the rows of X, then gemm_i8."""
     Xq, sx = quantize_rows(X)
     return gemm_i8(Xq, sx, Wq, sw, bias, residual, epi)
+
+
+def attn_decode(qkv, Kc, Vc, pos, scale=None, return_pre=False):
+    """Single-token attention with a KV cache.  qkv [B,3,H,d] fp16 (query, new key, new value of
+    the token), Kc / Vc [B,H,S,d] fp16 caches with `pos` tokens in them.  Returns
+    (out [B,H*d] fp16, Kc', Vc') where the caches now also hold the new token at position pos
+    (the inputs are not modified); scale defaults to 1/sqrt(d)."""
+    q = np.ascontiguousarray(_bits(qkv, "qkv"))
+    K = np.array(_bits(Kc, "Kc"), copy=True)
+    V = np.array(_bits(Vc, "Vc"), copy=True)
+    if q.ndim != 4 or q.shape[1] != 3 or K.ndim != 4 or K.shape != V.shape or \
+            K.shape[:2] != (q.shape[0], q.shape[2]) or K.shape[3] != q.shape[3]:
+        raise ValueError("attn_decode shapes")
+    B, _, H, d = q.shape
+    S = K.shape[2]
+    if scale is None:
+        scale = 1.0 / np.sqrt(float(d))
+    out = np.empty((B, H * d), dtype=np.uint16)
+    pre = np.empty((B, H * d), dtype=np.float64) if return_pre else None
+    rc = lib().sbi_oracle_attn_decode(q.ctypes.data, K.ctypes.data, V.ctypes.data, B, H, d, S, int(pos),
+                                      float(scale), out.ctypes.data, pre.ctypes.data if pre is not None else None)
+    if rc != 0:
+        raise RuntimeError(f"sbi_oracle_attn_decode failed rc={rc}")
+    res = (out.view(np.float16), K.view(np.float16), V.view(np.float16))
+    return res + (pre,) if return_pre else res
 
 
 I8_TILE_K = 64          # k per k-step of the int8 layout

@@ -26,7 +26,8 @@
  * Every function here is pinned by tests/test_oracle_*.py (brute-force rational
  * arithmetic, identity / one-hot weights, linearity, GeLU closed forms, exhaustive
  * fp16 round trips; layer-norm and the INT8 functions: hand-worked cases, exact integer
- * brute force, reduction to the fp16 GeMM where the scales are 1): no part is "parity unpinned".
+ * brute force, reduction to the fp16 GeMM where the scales are 1; decode attention: closed-form
+ * weight patterns, invariances, an exact rational case): no part is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -216,6 +217,62 @@ int sbi_oracle_gemm_i8(const int8_t* Xq, const float* sx, const int8_t* Wq, cons
         }
     }
     free(acc);
+    return 0;
+}
+
+/*
+ * Single-token attention with a key/value cache (paper Sec. III-D region 2, "transposition plus
+ * attention", for the token-generation phase of Sec. IV in which "the new computation only
+ * depends on a single previously generated token" and everything older is re-used from the
+ * cache).  The paper relies on the standard scaled dot-product attention; written out for one
+ * new token per sequence:
+ *
+ *   qkv   [B][3][H][d]   the QKV GeMM's output row of the new token: query, key, value per head
+ *   Kc,Vc [B][H][S][d]   caches holding `pos` earlier tokens per sequence (positions 0..pos-1)
+ *
+ *   1. "transposition": the new key and value go to position `pos` of their head's cache
+ *      (token-major [3][H][d] -> head-major [H][S][d]), bit for bit;
+ *   2. s_j = scale * sum_e q[e] * K[j][e]                    j = 0..pos      (fp64)
+ *   3. p_j = exp(s_j - max_j s_j) / sum_j exp(s_j - max_j s_j)
+ *   4. out[b][h*d + e] = fp16( sum_j p_j * V[j][e] )         token-major again, one rounding
+ *
+ * No mask is needed: a cache only ever holds the past.  `pre` (optional, [B][H*d] doubles)
+ * receives the outputs before the rounding.
+ */
+int sbi_oracle_attn_decode(const uint16_t* qkv, uint16_t* Kc, uint16_t* Vc, int64_t B, int64_t H, int64_t d,
+                           int64_t S, int64_t pos, double scale, uint16_t* out, double* pre)
+{
+    if (!qkv || !Kc || !Vc || !out || B <= 0 || H <= 0 || d <= 0 || S <= 0 || pos < 0 || pos >= S) return -1;
+    double* sc = (double*)malloc(sizeof(double) * (size_t)(pos + 1));
+    if (!sc) return -1;
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t h = 0; h < H; ++h) {
+            const uint16_t* q = qkv + ((b * 3 + 0) * H + h) * d;
+            const uint16_t* kn = qkv + ((b * 3 + 1) * H + h) * d;
+            const uint16_t* vn = qkv + ((b * 3 + 2) * H + h) * d;
+            uint16_t* K = Kc + (b * H + h) * S * d;
+            uint16_t* V = Vc + (b * H + h) * S * d;
+            memcpy(K + pos * d, kn, sizeof(uint16_t) * (size_t)d);
+            memcpy(V + pos * d, vn, sizeof(uint16_t) * (size_t)d);
+            double mx = -INFINITY;
+            for (int64_t j = 0; j <= pos; ++j) {
+                double a = 0.0;
+                for (int64_t e = 0; e < d; ++e)
+                    a += sbi_oracle_half_to_double(q[e]) * sbi_oracle_half_to_double(K[j * d + e]);
+                sc[j] = a * scale;
+                if (sc[j] > mx) mx = sc[j];
+            }
+            double den = 0.0;
+            for (int64_t j = 0; j <= pos; ++j) { sc[j] = exp(sc[j] - mx); den += sc[j]; }
+            for (int64_t e = 0; e < d; ++e) {
+                double a = 0.0;
+                for (int64_t j = 0; j <= pos; ++j) a += sc[j] * sbi_oracle_half_to_double(V[j * d + e]);
+                a /= den;
+                if (pre) pre[b * H * d + h * d + e] = a;
+                out[b * H * d + h * d + e] = sbi_oracle_double_to_half(a);
+            }
+        }
+    free(sc);
     return 0;
 }
 
