@@ -46,6 +46,10 @@ def parse_args():
     ap.add_argument("--int8", action="store_true",
                     help="INT8 layer: weights quantised per output channel and laid out as int8, activations "
                          "quantised inside the kernel (sbi_layer's scales); algorithmic bytes count one byte per weight")
+    ap.add_argument("--attention", type=str, default=None, metavar="B:H:d:ctx[,...]", nargs="?",
+                    const="1:32:128:136,8:32:128:136,64:32:128:136,8:32:128:2048,64:32:128:2048,1:32:128:8192,8:32:128:8192",
+                    help="time the single-token attention with a KV cache (sbi_attn_decode) instead of the GeMMs: "
+                         "ctx = positions attended to, the new token's included; value = KV-cache streaming GB/s")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run a few copy-kernel and layer launches and exit (for rocprofv3 --pmc runs)")
     return ap.parse_args()
@@ -66,12 +70,117 @@ def measured_traffic(args, batches):
     return None
 
 
+def attention_bytes(B, H, d, ctx):
+    """HBM bytes one decode-attention call must move: ctx-1 cached rows of K and of V per
+    (sequence, head), q/k/v of the new token in, its k and v rows out to the caches, the context out."""
+    return 2 * (2 * B * H * (ctx - 1) * d) + 2 * (3 * B * H * d) + 2 * (2 * B * H * d) + 2 * B * H * d
+
+
+def attention_main(args):
+    """--attention: one JSON line; a step is one call per listed shape."""
+    import numpy as np
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    from paper_2207_00032_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    sb.load()
+    dev = torch.device("cuda:0")
+    shapes = [tuple(int(v) for v in item.split(":")) for item in args.attention.split(",")]
+    cases = []
+    for (B, H, d, ctx) in shapes:
+        qkv, K, V = wl.make_attention_inputs(B, H, d, ctx, seed=0, config_id=600)
+        cache_bytes = 2 * K.nbytes
+        copies = max(2, -(-3 * 256 * 1000 * 1000 // cache_bytes))      # rotate so the cache comes from HBM
+        Kd = [torch.from_numpy(K).to(dev) for _ in range(copies)]
+        Vd = [torch.from_numpy(V).to(dev) for _ in range(copies)]
+        cases.append({"shape": (B, H, d, ctx), "host": (qkv, K, V), "qkv": torch.from_numpy(qkv).to(dev), "K": Kd, "V": Vd,
+                      "out": torch.empty((B, H * d), dtype=torch.float16, device=dev), "n": 0,
+                      "ws": sb.new_workspace(max(256, sb.attn_workspace_bytes(B, H, d, ctx)), dev)})
+
+    def call(c):
+        j = c["n"] % len(c["K"])
+        c["n"] += 1
+        B, H, d, ctx = c["shape"]
+        sb.attn_decode(c["qkv"], c["K"][j], c["V"][j], ctx - 1, out=c["out"], workspace=c["ws"])
+
+    def step():
+        for c in cases:
+            call(c)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    sec_per_step = (time.perf_counter() - t0) / args.steps
+    bytes_per_step = sum(attention_bytes(*c["shape"]) for c in cases)
+
+    per_call = []
+    for c in cases:
+        us = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                call(c)
+            e1.record()
+            torch.cuda.synchronize()
+            us.append(e0.elapsed_time(e1) * 1e2)
+        med = sorted(us)[2]
+        nb = attention_bytes(*c["shape"])
+        B, H, d, ctx = c["shape"]
+        per_call.append({"B": B, "heads": H, "head_dim": d, "ctx": ctx, "us_median": round(med, 2),
+                         "GBps": round(nb / med / 1e3, 1), "hbm_frac": round(nb / med / 1e3 / HBM_PEAK_GBPS, 4),
+                         "bytes": nb})
+    big = max(per_call, key=lambda r: r["bytes"])
+    roofline = {"bound": "hbm", "achieved": big["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": big["hbm_frac"],
+                "traffic": None, "kernel": f"sbi_attn_decode_kernel<{big['head_dim']}>",
+                "avg_launch_us": big["us_median"], "avg_bytes_per_launch": big["bytes"],
+                "shape": f"B={big['B']} H={big['heads']} d={big['head_dim']} ctx={big['ctx']}"}
+
+    cpu = parity = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        t_cpu, nbytes, n_bad, max_abs = 0.0, 0, 0, 0.0
+        for c in cases:
+            B, H, d, ctx = c["shape"]
+            if attention_bytes(B, H, d, ctx) > (64 << 20):
+                continue
+            qkv, K, V = c["host"]
+            c0 = time.perf_counter()
+            want, _, _ = orc.attn_decode(qkv, K, V, ctx - 1)
+            t_cpu += time.perf_counter() - c0
+            nbytes += attention_bytes(B, H, d, ctx)
+            call(c)
+            torch.cuda.synchronize()
+            ok, rep = orc.check_close(c["out"].cpu().numpy(), want)
+            n_bad += rep["n_bad"]
+            max_abs = max(max_abs, rep["max_abs"])
+        if t_cpu > 0:
+            cpu = {"value": round(nbytes / t_cpu / 1e9, 3), "unit": "GB/s", "cores": orc.max_threads(), "kind": "oracle",
+                   "sample": f"the listed shapes of at most 64 MiB, {t_cpu:.1f} s of CPU time"}
+            parity = {"ok": n_bad == 0, "n_bad": n_bad, "max_abs": max_abs, "tolerance": "max(2 ulp16, 1e-3)"}
+    print(json.dumps({
+        "metric": "KV-cache HBM GB/s (algorithmic bytes of single-token attention / time)",
+        "value": round(bytes_per_step / sec_per_step / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(sec_per_step * 1e3, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "single-token attention over a KV cache, one call per shape "
+                               "(B:heads:head_dim:context) " + args.attention},
+        "roofline": roofline, "cpu_baseline": cpu, "parity": parity, "per_call": per_call}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.attention:
+        return attention_main(args)
 
     import numpy as np
     import torch

@@ -315,6 +315,33 @@ size_t sbi_layer_workspace_bytes(const sbi_layer* L, int64_t B);
 sbi_status sbi_layer_plan(const sbi_layer* L, int64_t B, int32_t chained, sbi_plan plans[4], int32_t* total_grid);
 
 /*
+ * Single-token attention with a key/value cache (paper Sec. III-D region 2, "transposition plus
+ * attention" in one kernel; Sec. IV: token generation re-uses the past through the KV cache and
+ * computes only for the one new token).  Standard scaled dot-product attention, per sequence b
+ * and head h, with the new token's query / key / value taken from the QKV GeMM's output row:
+ *
+ *     K[b][h][pos] = k_new,  V[b][h][pos] = v_new                      (the transposition)
+ *     s_j = scale * q . K[b][h][j]        p = softmax_j(s_j)           j = 0 .. pos
+ *     out[b][h*d .. h*d+d) = fp16( sum_j p_j V[b][h][j] )
+ *
+ *   qkv         device, fp16 [B][3][heads][head_dim] (query, key, value), 16-byte aligned
+ *   k_cache,
+ *   v_cache     device, fp16 [B][heads][max_seq][head_dim], 16-byte aligned, holding `pos` earlier
+ *               tokens of every sequence at positions 0 .. pos-1; position `pos` is written
+ *   pos         0 <= pos < max_seq: the same for all sequences of the batch
+ *   scale       > 0, or 0 for 1/sqrt(head_dim)
+ *   out         device, fp16 [B][heads*head_dim]
+ *   workspace   device, 256-byte aligned, zero-filled once before first use,
+ *               >= sbi_attn_decode_workspace_bytes(B, heads, head_dim, max_seq) (0 for short caches)
+ * head_dim is 64 or 128; B <= SBI_MAX_BATCH.  Accumulation in fp32, one rounding to fp16;
+ * deterministic.  Cached keys and values are read exactly once.
+ */
+size_t sbi_attn_decode_workspace_bytes(int64_t B, int32_t heads, int32_t head_dim, int64_t max_seq);
+sbi_status sbi_attn_decode(const void* qkv, void* k_cache, void* v_cache, int64_t B, int32_t heads, int32_t head_dim,
+                           int64_t max_seq, int64_t pos, float scale, void* out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Measurement helpers (no part of the GeMM path; for callers that profile it).
  * sbi_calib_read streams `bytes` (a multiple of 4096, 256-byte aligned, device) from src
  * with the GeMM's own access shape - `blocks` thread blocks of `waves` wavefronts (4, 8 or

@@ -32,7 +32,7 @@ EXPORTS = ["sbi_gemm_layout_bytes", "sbi_gemm_workspace_bytes", "sbi_gemm_layout
            "sbi_version", "sbi_calib_read", "sbi_calib_copy", "sbi_layer_plan", "sbi_gemm_ln",
            "sbi_gemm_ln_workspace_bytes", "sbi_gemm_i8_layout_bytes", "sbi_gemm_i8_workspace_bytes",
            "sbi_gemm_i8_quantize_weights", "sbi_gemm_i8_layout_weights", "sbi_gemm_i8_layout_check", "sbi_gemm_i8",
-           "sbi_gemm_moments"]
+           "sbi_gemm_moments", "sbi_attn_decode", "sbi_attn_decode_workspace_bytes"]
 
 
 class SbiError(RuntimeError):
@@ -110,6 +110,10 @@ def load():
     L.sbi_gemm_moments.restype = i32
     L.sbi_gemm_moments.argtypes = [vp, i64, i64, vp, i64, ctypes.POINTER(LayerNorm), vp, vp, i32, vp, vp, vp, sz, vp,
                                    ctypes.POINTER(Tuning)]
+    L.sbi_attn_decode_workspace_bytes.restype = sz
+    L.sbi_attn_decode_workspace_bytes.argtypes = [i64, i32, i32, i64]
+    L.sbi_attn_decode.restype = i32
+    L.sbi_attn_decode.argtypes = [vp, vp, vp, i64, i32, i32, i64, i64, ctypes.c_float, vp, vp, sz, vp]
     L.sbi_gemm_ln_workspace_bytes.restype = sz
     L.sbi_gemm_ln_workspace_bytes.argtypes = [i64, i64, i64]
     L.sbi_gemm_i8_layout_bytes.restype = sz
@@ -431,6 +435,33 @@ def layer_gemms(layer, B, Xqkv, Xout, Xffn1, Xffn2, residual, Yqkv, Yout, Yffn1,
                                 _ptr(residual), _ptr(Yqkv), _ptr(Yout), _ptr(Yffn1), _ptr(Yffn2),
                                 _ptr(workspace), ws_len, _stream())
     _check(st, "sbi_layer_gemms")
+
+
+def attn_workspace_bytes(B, heads, head_dim, max_seq):
+    return int(load().sbi_attn_decode_workspace_bytes(B, heads, head_dim, max_seq))
+
+
+def attn_decode(qkv, k_cache, v_cache, pos, scale=0.0, out=None, workspace=None):
+    """Single-token attention with a KV cache (sbi_attn_decode).  qkv fp16 [B,3,H,d]; caches fp16
+    [B,H,S,d], updated in place at position pos.  Returns out fp16 [B, H*d]."""
+    import torch
+    B, three, H, d = qkv.shape
+    S = k_cache.shape[2]
+    _need(qkv, (B, 3, H, d), "qkv")
+    _need(k_cache, (B, H, S, d), "k_cache")
+    _need(v_cache, (B, H, S, d), "v_cache")
+    if out is None:
+        out = torch.empty((B, H * d), dtype=torch.float16, device=qkv.device)
+    _need(out, (B, H * d), "out")
+    need = attn_workspace_bytes(B, H, d, S)
+    if workspace is None and need:
+        workspace = new_workspace(need, qkv.device)
+    if need:
+        _need_bytes(workspace, need, "workspace")
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load().sbi_attn_decode(_ptr(qkv), _ptr(k_cache), _ptr(v_cache), B, H, d, S, int(pos), float(scale),
+                                  _ptr(out), _ptr(workspace), ws_len, _stream()), "sbi_attn_decode")
+    return out
 
 
 # ---------------------------------------------------------------------------------- measurement helpers

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 PKG = os.path.dirname(HERE)
 LIB = os.path.join(PKG, "libsbi_gemm.so")
-SOURCES = ["sbi_abi.hip", "sbi_layout.hip", "sbi_mfma.hip", "sbi_stream.hip", "sbi_streamk.hip", "sbi_calib.hip", "sbi_i8.hip"]
+SOURCES = ["sbi_abi.hip", "sbi_layout.hip", "sbi_mfma.hip", "sbi_stream.hip", "sbi_streamk.hip", "sbi_calib.hip", "sbi_i8.hip", "sbi_attn.hip"]
 HEADERS = ["sbi_common.h", "sbi_block.h", os.path.join("..", "..", "include", "sbi_gemm.h")]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

@@ -908,6 +908,50 @@ sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
     return launch_block_group(&a[3], &one, last, 1, B, workspace, st);
 }
 
+// Position ranges per (sequence, head) of the attention kernel: enough blocks to fill the chip,
+// but no range shorter than 256 cached positions.
+static int attn_splits(int64_t B, int64_t H, int64_t n)
+{
+    const int64_t want = ceil_div(512, B * H);
+    const int64_t most = std::max<int64_t>(1, n / 256);
+    return (int)std::max<int64_t>(1, std::min<int64_t>(std::min(want, most), 32));
+}
+
+static sbi_status attn_check_dims(int64_t B, int32_t heads, int32_t head_dim, int64_t max_seq)
+{
+    if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
+    if (heads < 1 || heads > 1024 || (head_dim != 64 && head_dim != 128) || max_seq < 1 || max_seq > (int64_t(1) << 24))
+        return SBI_ERR_SHAPE;
+    return SBI_OK;
+}
+
+size_t sbi_attn_decode_workspace_bytes(int64_t B, int32_t heads, int32_t head_dim, int64_t max_seq)
+{
+    if (attn_check_dims(B, heads, head_dim, max_seq) != SBI_OK) return 0;
+    const int ns = attn_splits(B, heads, max_seq);
+    return ns > 1 ? (size_t)kAttnCounterBytes + (size_t)B * heads * ns * (head_dim + 2) * 4 : 0;
+}
+
+sbi_status sbi_attn_decode(const void* qkv, void* k_cache, void* v_cache, int64_t B, int32_t heads, int32_t head_dim,
+                           int64_t max_seq, int64_t pos, float scale, void* out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!qkv || !k_cache || !v_cache || !out) return SBI_ERR_NULL;
+    if (sbi_status s = attn_check_dims(B, heads, head_dim, max_seq)) return s;
+    if (pos < 0 || pos >= max_seq) return SBI_ERR_SHAPE;
+    if (!(scale >= 0.0f) || !std::isfinite(scale)) return SBI_ERR_EPILOGUE;
+    if (!aligned(qkv, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16) || !aligned(out, 2)) return SBI_ERR_ALIGN;
+    if (scale == 0.0f) scale = 1.0f / std::sqrt((float)head_dim);
+    const int ns = attn_splits(B, heads, pos + 1);
+    if (ns > 1) {
+        const size_t need = (size_t)kAttnCounterBytes + (size_t)B * heads * ns * (head_dim + 2) * 4;
+        if (!workspace || workspace_bytes < need) return SBI_ERR_WORKSPACE;
+        if (!aligned(workspace, 256)) return SBI_ERR_ALIGN;
+    }
+    return launch_attn_decode(qkv, k_cache, v_cache, B, heads, head_dim, max_seq, pos, scale, out,
+                              ns > 1 ? workspace : nullptr, ns, (hipStream_t)hip_stream) == 0 ? SBI_OK : SBI_ERR_HIP;
+}
+
 const char* sbi_status_string(sbi_status s)
 {
     switch (s) {

@@ -114,6 +114,9 @@ int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, bool la
 int launch_i8(const GroupParams& gp, int waves, int depth, bool prequantized, size_t lds_bytes, hipStream_t st);
 int launch_layout_i8(const void* Wq, int64_t K, int64_t N, void* out, hipStream_t st);
 int launch_quantize_weights(const void* W, int64_t K, int64_t N, void* Wq, void* scales, hipStream_t st);
+int launch_attn_decode(const void* qkv, void* Kc, void* Vc, int64_t B, int H, int D, int64_t S, int64_t pos,
+                       float scale, void* out, void* workspace, int nsplit, hipStream_t st);
+constexpr int kAttnCounterBytes = 256 * 1024;        // arrival counters of the attention kernel's workspace (one per sequence and head)
 constexpr int kI8TileK = 64;                         // k per k-step of the int8 layout
 constexpr int kI8ChunkK = 16;                        // consecutive k one lane owns (16 bytes)
 inline int64_t ksteps_of_i8(int64_t K) { return ((K + kI8TileK - 1) / kI8TileK + kStepGroup - 1) / kStepGroup * kStepGroup; }

@@ -134,6 +134,20 @@ def make_layernorm_inputs(K: int, B: int, seed: int = 0, config_id: int = 0, gem
     return gamma, beta, X
 
 
+def make_attention_inputs(B: int, heads: int, head_dim: int, max_seq: int, seed: int = 0, config_id: int = 0,
+                          key_scale: float = 1.0):
+    """Draw (qkv[B,3,H,d], K_cache[B,H,S,d], V_cache[B,H,S,d]) as fp16 for single-token attention:
+    N(0,1) queries, keys and values (the scale layer-normed activations give the QKV projection's
+    outputs); key_scale > 1 widens the score distribution, i.e. makes the softmax more peaked.
+    The whole cache is drawn; a test decides how many positions count as filled."""
+    rng = np.random.default_rng(np.random.SeedSequence([seed, config_id, 7]))
+    qkv = rng.standard_normal((B, 3, heads, head_dim))
+    qkv[:, 1] *= key_scale
+    K = _normal_fp16(rng, (B, heads, max_seq, head_dim), key_scale)
+    V = _normal_fp16(rng, (B, heads, max_seq, head_dim), 1.0)
+    return qkv.astype(np.float16), K, V
+
+
 def make_config_gemm(config_id: int, gemm_index: int, seed: int = 0, B: Optional[int] = None):
     """Inputs for one GeMM of a named configuration.
 

@@ -33,7 +33,7 @@ sbi_status sbi_calib_copy(const void*, void*, size_t, void*) { return SBI_ERR_HI
 def build(out_dir):
     gen = os.path.join(out_dir, "gen")
     os.makedirs(gen, exist_ok=True)
-    for name in ("sbi_common.h", "sbi_block.h", "sbi_abi.hip", "sbi_mfma.hip", "sbi_layout.hip", "sbi_i8.hip"):
+    for name in ("sbi_common.h", "sbi_block.h", "sbi_abi.hip", "sbi_mfma.hip", "sbi_layout.hip", "sbi_i8.hip", "sbi_attn.hip"):
         text = open(os.path.join(SRC, name)).read()
         text = text.replace(LDS_DECL, "unsigned char* smem_raw = emu::lds();")
         text = text.replace('"../../include/sbi_gemm.h"', '"sbi_gemm.h"')
@@ -41,7 +41,7 @@ def build(out_dir):
     open(os.path.join(gen, "sbi_gemm.h"), "w").write(open(os.path.join(ROOT, "include", "sbi_gemm.h")).read())
     open(os.path.join(gen, "stubs.cpp"), "w").write(STUBS)
     inc = ["-I", HERE, "-I", gen]
-    units = [os.path.join(gen, f) for f in ("sbi_abi.cpp", "sbi_mfma.cpp", "sbi_layout.cpp", "sbi_i8.cpp", "stubs.cpp")] + \
+    units = [os.path.join(gen, f) for f in ("sbi_abi.cpp", "sbi_mfma.cpp", "sbi_layout.cpp", "sbi_i8.cpp", "sbi_attn.cpp", "stubs.cpp")] + \
             [os.path.join(HERE, "emu.cpp")]
     procs = []
     objs = []
@@ -57,7 +57,7 @@ def build(out_dir):
     lib = os.path.join(out_dir, "libsbi_emu.so")
     subprocess.run([CXX, "-shared", "-fsanitize=address", "-pthread", "-o", lib, *objs], check=True)
     exes = []
-    for drv in ("emu_gemm", "emu_layer"):
+    for drv in ("emu_gemm", "emu_layer", "emu_attn"):
         exe = os.path.join(out_dir, drv)
         subprocess.run([CXX, "-std=c++17", "-O1", "-g", "-fsanitize=address", *inc, os.path.join(HERE, drv + ".cpp"),
                         "-o", exe, "-L", out_dir, "-lsbi_emu", "-Wl,-rpath," + out_dir, "-pthread"], check=True)

@@ -125,6 +125,9 @@ inline int __builtin_amdgcn_readfirstlane(int v) { return v; }
 #define __hip_atomic_fetch_add(p, v, order, scope) __atomic_fetch_add(p, v, __ATOMIC_SEQ_CST)
 inline unsigned long long wall_clock64() { return 0; }
 using std::min;
+#ifndef INFINITY
+#define INFINITY __builtin_inff()
+#endif
 using std::max;
 
 #define hipLaunchKernelGGL(kernel, grid, block, lds, stream, ...) \

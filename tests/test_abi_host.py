@@ -308,3 +308,22 @@ def test_moments_argument_validation(lib):
     for bad in (sb.Tuning(sb.PATH_STREAM, 0, 0, 0, 0, 0, 0, 0), sb.Tuning(sb.PATH_STREAMK, 0, 0, 0, 0, 0, 0, 0),
                 sb.Tuning(0, 0, 0, 0, 0, 0, 0, 1)):
         assert call(tune=ctypes.byref(bad), ws_bytes=1 << 30) == 10
+
+
+def test_attention_argument_validation(lib):
+    q, k, v, o, w = (FAKE + (i << 30) for i in range(1, 6))
+    call = lambda **kw: lib.sbi_attn_decode(kw.get("q", q), kw.get("k", k), kw.get("v", v), kw.get("B", 2), kw.get("H", 4),
+                                            kw.get("d", 128), kw.get("S", 4096), kw.get("pos", 4000),
+                                            ctypes.c_float(kw.get("scale", 0.0)), kw.get("o", o), kw.get("w", w),
+                                            kw.get("wb", 0), None)
+    assert call(q=None) == 1 and call(k=None) == 1 and call(v=None) == 1 and call(o=None) == 1
+    assert call(B=0) == 4 and call(B=65) == 4
+    assert call(H=0) == 2 and call(d=96) == 2 and call(S=0) == 2 and call(pos=-1) == 2 and call(pos=4096) == 2
+    assert call(scale=-1.0) == 7 and call(scale=float("nan")) == 7
+    assert call(q=q + 8) == 3 and call(k=k + 2) == 3 and call(o=o + 1) == 3
+    need = sb.attn_workspace_bytes(2, 4, 128, 4096)
+    assert need == 256 * 1024 + 2 * 4 * 16 * 130 * 4            # 16 position ranges of 256 per (sequence, head)
+    full = dict(pos=4095)                                        # the requirement follows the filled length
+    assert call(wb=need - 1, **full) == 6 and call(w=None, wb=need, **full) == 6 and call(w=w + 64, wb=need, **full) == 3
+    assert sb.attn_workspace_bytes(8, 32, 128, 136) == 0         # short caches: one block per (sequence, head)
+    assert sb.attn_workspace_bytes(2, 4, 100, 64) == 0 and sb.attn_workspace_bytes(0, 4, 128, 64) == 0

@@ -24,8 +24,7 @@ def drivers(tmp_path_factory):
     build = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(build)
     out = tmp_path_factory.mktemp("emu")
-    gemm, layer = build.build(str(out))
-    return gemm, layer
+    return build.build(str(out))
 
 
 def run(cmd):
@@ -60,3 +59,10 @@ def test_single_gemm_under_asan(drivers, case):
 @pytest.mark.parametrize("B,h,ln", [(2, 256, 0), (5, 512, 1), (33, 256, 1), (9, 1024, 1)])
 def test_layer_launch_under_asan(drivers, B, h, ln):
     run([drivers[1], str(B), str(h), str(ln), "1"])
+
+
+# B heads head_dim max_seq pos
+@pytest.mark.parametrize("case", [(1, 1, 64, 4, 0), (2, 3, 128, 40, 17), (1, 2, 64, 300, 299), (3, 2, 128, 130, 64),
+                                  (1, 1, 128, 1100, 1030), (2, 1, 64, 600, 520)])
+def test_attention_decode_under_asan(drivers, case):
+    run([drivers[2], *[str(v) for v in case]])
