@@ -912,9 +912,16 @@ sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
 // but no range shorter than 256 cached positions.
 static int attn_splits(int64_t B, int64_t H, int64_t n)
 {
-    const int64_t want = ceil_div(512, B * H);
-    const int64_t most = std::max<int64_t>(1, n / 256);
-    return (int)std::max<int64_t>(1, std::min<int64_t>(std::min(want, most), 32));
+    int64_t target = 512, shortest = 256, cap = 32;
+#ifdef SBI_DEV
+    if (const char* e = getenv("SBI_ATTN_SPLIT")) {
+        long long a, b, c;
+        if (sscanf(e, "%lld,%lld,%lld", &a, &b, &c) == 3) { target = a; shortest = b; cap = c; }
+    }
+#endif
+    const int64_t want = ceil_div(target, B * H);
+    const int64_t most = std::max<int64_t>(1, n / shortest);
+    return (int)std::max<int64_t>(1, std::min<int64_t>(std::min(want, most), std::min<int64_t>(cap, kAttnMaxSplits)));
 }
 
 static sbi_status attn_check_dims(int64_t B, int32_t heads, int32_t head_dim, int64_t max_seq)

@@ -41,12 +41,12 @@ __device__ __forceinline__ float attn_load(const float* src)
                                                        __HIP_MEMORY_SCOPE_AGENT));
 }
 
-template <int D>
+// D: head dimension; U: positions in flight per lane group
+template <int D, int U>
 __global__ __launch_bounds__(256) void sbi_attn_decode_kernel(const AttnParams p)
 {
     constexpr int LPP = D / 8;           // lanes per cached position
     constexpr int NG = 256 / LPP;        // lane groups per block
-    constexpr int U = 4;                 // positions in flight per group
     __shared__ float s_m[NG], s_l[NG];
     __shared__ float s_o[NG][D];
     __shared__ int s_flag;
@@ -144,17 +144,48 @@ __global__ __launch_bounds__(256) void sbi_attn_decode_kernel(const AttnParams p
     }
     __syncthreads();
     if (!s_flag) return;
-    if (tid < D) {
-        const float* base = p.partials + (int64_t)bh * p.nsplit * (D + 2);
-        float Mx = -INFINITY;
-        for (int s = 0; s < p.nsplit; ++s) Mx = fmaxf(Mx, attn_load(base + s * (D + 2) + D));
-        float Ls = 0.f, Os = 0.f;
-        for (int s = 0; s < p.nsplit; ++s) {
-            const float f = exp2f(attn_load(base + s * (D + 2) + D) - Mx);
-            Ls += f * attn_load(base + s * (D + 2) + D + 1);
-            Os += f * attn_load(base + s * (D + 2) + tid);
+    // All loads of the merge are independent of each other: every thread first fetches, then combines
+    // (one memory latency per batch of kMergeBatch loads instead of one per position range).
+    constexpr int Q = 256 / D;                                  // threads per output column
+    float* s_f = &s_o[0][0];                                    // [nsplit] factors, then the denominator
+    float* s_part = s_f + kAttnMaxSplits + 1;                   // [Q][D] partial column sums
+    const float* base = p.partials + (int64_t)bh * p.nsplit * (D + 2);
+    float mx = -INFINITY, lx = 0.f;
+    if (tid < p.nsplit) {
+        mx = attn_load(base + tid * (D + 2) + D);
+        lx = attn_load(base + tid * (D + 2) + D + 1);
+        s_f[tid] = mx;
+    }
+    __syncthreads();                                            // also: every thread is done with s_o
+    float Mx = -INFINITY;
+    for (int s = 0; s < p.nsplit; ++s) Mx = fmaxf(Mx, s_f[s]);
+    __syncthreads();
+    if (tid < p.nsplit) { s_f[tid] = exp2f(mx - Mx); s_part[tid] = lx; }
+    __syncthreads();
+    float Ls = 0.f;
+    for (int s = 0; s < p.nsplit; ++s) Ls += s_f[s] * s_part[s];   // fixed order, the same in every thread
+    __syncthreads();
+    const int col = tid % D, q = tid / D;
+    float Os = 0.f;
+    constexpr int kMergeBatch = 8;
+    for (int s0 = q; s0 < p.nsplit; s0 += Q * kMergeBatch) {
+        float v[kMergeBatch];
+#pragma unroll
+        for (int u = 0; u < kMergeBatch; ++u) {
+            const int sidx = min(s0 + u * Q, p.nsplit - 1);
+            v[u] = attn_load(base + sidx * (D + 2) + col);
         }
-        p.out[(int64_t)b * p.H * D + h * D + tid] = (_Float16)(Os / Ls);
+#pragma unroll
+        for (int u = 0; u < kMergeBatch; ++u)
+            if (s0 + u * Q < p.nsplit) Os += s_f[s0 + u * Q] * v[u];
+    }
+    s_part[q * D + col] = Os;
+    __syncthreads();
+    if (tid < D) {
+        float total = 0.f;
+#pragma unroll
+        for (int qq = 0; qq < Q; ++qq) total += s_part[qq * D + tid];
+        p.out[(int64_t)b * p.H * D + h * D + tid] = (_Float16)(total / Ls);
     }
     if (tid == 0) __hip_atomic_store(p.counters + bh, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -162,6 +193,7 @@ __global__ __launch_bounds__(256) void sbi_attn_decode_kernel(const AttnParams p
 int launch_attn_decode(const void* qkv, void* Kc, void* Vc, int64_t B, int H, int D, int64_t S, int64_t pos,
                        float scale, void* out, void* workspace, int nsplit, hipStream_t st)
 {
+    if (nsplit < 1 || nsplit > kAttnMaxSplits) return (int)hipErrorInvalidValue;
     AttnParams p;
     p.qkv = reinterpret_cast<const _Float16*>(qkv);
     p.Kc = reinterpret_cast<_Float16*>(Kc);
@@ -173,8 +205,15 @@ int launch_attn_decode(const void* qkv, void* Kc, void* Vc, int64_t B, int H, in
     p.per_split = (int)((pos + 1 + nsplit - 1) / nsplit);
     p.scale_log2 = scale * 1.44269504088896340736f;
     const dim3 grid((unsigned)(B * H * nsplit));
-    if (D == 128) hipLaunchKernelGGL(sbi_attn_decode_kernel<128>, grid, dim3(256), 0, st, p);
-    else if (D == 64) hipLaunchKernelGGL(sbi_attn_decode_kernel<64>, grid, dim3(256), 0, st, p);
+#ifdef SBI_DEV
+    if (const char* e = getenv("SBI_ATTN_U")) {
+        const int u = atoi(e);
+        if (D == 128 && u == 2) { hipLaunchKernelGGL((sbi_attn_decode_kernel<128, 2>), grid, dim3(256), 0, st, p); return (int)hipGetLastError(); }
+        if (D == 128 && u == 8) { hipLaunchKernelGGL((sbi_attn_decode_kernel<128, 8>), grid, dim3(256), 0, st, p); return (int)hipGetLastError(); }
+    }
+#endif
+    if (D == 128) hipLaunchKernelGGL((sbi_attn_decode_kernel<128, 4>), grid, dim3(256), 0, st, p);
+    else if (D == 64) hipLaunchKernelGGL((sbi_attn_decode_kernel<64, 4>), grid, dim3(256), 0, st, p);
     else return (int)hipErrorInvalidValue;
     return (int)hipGetLastError();
 }

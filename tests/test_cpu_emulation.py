@@ -63,6 +63,6 @@ def test_layer_launch_under_asan(drivers, B, h, ln):
 
 # B heads head_dim max_seq pos
 @pytest.mark.parametrize("case", [(1, 1, 64, 4, 0), (2, 3, 128, 40, 17), (1, 2, 64, 300, 299), (3, 2, 128, 130, 64),
-                                  (1, 1, 128, 1100, 1030), (2, 1, 64, 600, 520)])
+                                  (1, 1, 128, 1100, 1030), (2, 1, 64, 600, 520), (1, 1, 128, 2600, 2570), (1, 2, 64, 1600, 1590)])
 def test_attention_decode_under_asan(drivers, case):
     run([drivers[2], *[str(v) for v in case]])
