@@ -97,3 +97,17 @@ def test_invariances():
     assert np.array_equal(o2.view(np.uint16), out.view(np.uint16))
     with pytest.raises(RuntimeError):
         orc.attn_decode(qkv, Kc, Vc, 12)
+
+
+def test_against_library_softmax():
+    """The same definition assembled from library routines (scipy's softmax, numpy's einsum) in fp64."""
+    from scipy.special import softmax
+    qkv, Kc, Vc = _rand(3, 4, 40, 16, 4)
+    pos = 33
+    _, _, _, pre = orc.attn_decode(qkv, Kc, Vc, pos, return_pre=True)
+    q = qkv[:, 0].astype(np.float64)
+    keys = np.concatenate([Kc[:, :, :pos], qkv[:, 1][:, :, None]], axis=2).astype(np.float64)
+    vals = np.concatenate([Vc[:, :, :pos], qkv[:, 2][:, :, None]], axis=2).astype(np.float64)
+    w = softmax(np.einsum("bhd,bhsd->bhs", q, keys) / 4.0, axis=-1)
+    want = np.einsum("bhs,bhsd->bhd", w, vals).reshape(3, -1)
+    assert np.allclose(pre, want, rtol=1e-12, atol=1e-14)
