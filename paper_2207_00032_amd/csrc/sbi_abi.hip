@@ -17,8 +17,8 @@ namespace {
 using namespace sbi;
 
 constexpr int64_t kMaxDim = int64_t(1) << 22;     // K, N limit: keeps tile counts and grids in 32 bits
-constexpr int64_t kMaxLds = 64 * 1024;            // dynamic LDS budget per block (several blocks per CU)
-constexpr int64_t kMaxLdsWide = 128 * 1024;       // two-panel blocks of large batches: one block per CU
+constexpr int64_t kMaxLds = 72 * 1024;            // dynamic LDS budget per block (several blocks per CU)
+constexpr int64_t kMaxLdsWide = 144 * 1024;       // two-panel blocks of large batches: one block per CU
 constexpr int64_t kCounterBytes = (kMaxDim / kPanelN) * 4;   // one arrival counter per possible panel: 256 KiB
 constexpr int kStreamMaxBatch = 8;                // vector-ALU kernel instantiations exist for B <= 8
 constexpr int kAutoStreamBatch = 0;               // AUTO picks the vector-ALU kernel for B <= this
@@ -103,6 +103,10 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
 // LDS bytes per pass.
 enum Flavour { kPlain = 0, kLayerNorm = 1, kInt8 = 2, kInt8Codes = 3 };
 
+// Rows of 16-byte pieces a k-step's lane group occupies in LDS: B rounded up to an odd number, so
+// that a wave staging 64 consecutive pieces of one row hits every LDS bank.
+inline int64_t x_pitch(int64_t B) { return B | 1; }
+
 // INT8: up to this batch every block quantises the activations itself; above it a kernel of its
 // own does it once (measured on MI355X: fused is ahead up to B = 8, behind from B = 16 on).
 constexpr int64_t kI8FusedMaxBatch = 8;
@@ -112,7 +116,7 @@ bool chunking(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t 
               int64_t& kc, int64_t& lds, Flavour fl = kPlain)
 {
     const int64_t front = (fl == kPlain) ? 0 : kLnStatsBytes;
-    const int64_t rows = B + (fl == kLayerNorm ? 2 : 0);
+    const int64_t rows = x_pitch(B) + (fl == kLayerNorm ? 2 : 0);
     const int64_t pass_bytes = (int64_t)nw * (fl == kInt8 ? 2048 : 4096);
     const int64_t red = (fl == kInt8 || fl == kInt8Codes) ? red_bytes : std::max<int64_t>(red_bytes - front, 0);
     cap -= front;
@@ -315,7 +319,7 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
     p.partials = (pl.S > 1) ? reinterpret_cast<float*>(ws + kCounterBytes + partial_off) : nullptr;
     p.B = (int)B; p.K = (int)a.K; p.N = (int)a.N;
     p.KS = (int)(pl.i8 ? ksteps_of_i8(a.K) : ksteps_of(a.K)); p.P = (int)ceil_div(a.N, kPanelN);
-    p.S = pl.S; p.ksps = pl.ksps; p.kc = pl.kc;
+    p.S = pl.S; p.ksps = pl.ksps; p.kc = pl.kc; p.xpitch = (int)x_pitch(B);
     p.sw = reinterpret_cast<const float*>(a.sw);
     p.moments_out = reinterpret_cast<floatx2*>(a.moments_out);
     p.ln_moments = reinterpret_cast<const floatx2*>(a.gamma ? a.ln_moments : nullptr);
@@ -346,13 +350,13 @@ int resident_waves(int mb, int nw, int depth, int pw, bool ln, bool i8, bool pre
     static const int vgpr_i8_w4d2[4] = {108, 132, 200, 216};
     static const int vgpr_i8_w4d4[4] = {164, 184, 212, 242};
     static const int vgpr_i8_w8d4[4] = {138, 154, 164, 190};
-    static const int vgpr_w4d2[4] = {108, 128, 156, 180};
+    static const int vgpr_w4d2[4] = {108, 128, 152, 168};
     static const int vgpr_w4d4[4] = {140, 164, 196, 226};
     static const int vgpr_w8d4[4] = {134, 152, 170, 188};
-    static const int vgpr_w8d2p2[4] = {150, 184, 218, 252};
-    static const int vgpr_ln_w4d2[4] = {120, 140, 164, 212};
-    static const int vgpr_ln_w4d4[4] = {144, 168, 196, 224};
-    static const int vgpr_ln_w8d4[4] = {138, 160, 180, 204};
+    static const int vgpr_w8d2p2[4] = {150, 184, 210, 244};
+    static const int vgpr_ln_w4d2[4] = {124, 144, 152, 184};
+    static const int vgpr_ln_w4d4[4] = {156, 188, 200, 236};
+    static const int vgpr_ln_w8d4[4] = {150, 172, 180, 204};
     const int* tab = (pw == 2) ? vgpr_w8d2p2 : (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);
     if (ln) tab = (nw == 8) ? vgpr_ln_w8d4 : (depth == 2 ? vgpr_ln_w4d2 : vgpr_ln_w4d4);
     if (i8 && preq) tab = (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);   // as the fp16 kernel's
@@ -425,7 +429,7 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
     }
     if (panels > kCounterBytes / 4) return SBI_ERR_SHAPE;
     constexpr int64_t kLdsPerCU = 160 * 1024;
-    const int64_t lds_caps[4] = {16 * 1024, 32 * 1024, kMaxLds, kMaxLdsWide};
+    const int64_t lds_caps[4] = {18 * 1024, 36 * 1024, kMaxLds, kMaxLdsWide};   // 9/8 of a power of two: room for the odd pitch
     const bool preq = i8 && B > kI8FusedMaxBatch;
     const Flavour fl = i8 ? (preq ? kInt8Codes : kInt8) : (ln ? kLayerNorm : kPlain);
     // (waves, depth, panels per block) candidates; two-panel blocks only pay off for B > 16

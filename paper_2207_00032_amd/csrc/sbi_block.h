@@ -8,9 +8,20 @@
 
 namespace sbi {
 
+// GeLU(v) = v * Phi(v) with the exact-erf definition Phi(v) = (1 + erf(v / sqrt 2)) / 2.
+// erfc(|x|) from the rational-times-Gaussian approximation 7.1.26 of Abramowitz & Stegun
+// (|error| <= 1.5e-7 in erf): a dozen VALU operations instead of the math library's erff, whose
+// ~100 made the epilogue of the large-batch GeLU GeMM (64 x 128 outputs per block) the longest
+// part of a block's tail.  Forming Phi from erfc on the negative side keeps the small values of
+// the left tail relatively accurate; the error in GeLU is below 1e-7 * |v|, orders of magnitude
+// under the fp16 rounding that follows.
 __device__ __forceinline__ float gelu_erf(float v)
 {
-    return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+    const float x = fabsf(v) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * x);
+    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+    const float erfc_x = poly * __builtin_amdgcn_exp2f(-x * x * 1.44269504088896340736f);
+    return 0.5f * v * (v < 0.f ? erfc_x : 2.0f - erfc_x);
 }
 
 // Final value of one output element from its fp32 sum.
@@ -22,20 +33,59 @@ __device__ __forceinline__ float apply_epilogue(const GemmParams& p, float v, in
     return v;
 }
 
+// What the epilogue of the column pair (n, n+1) of row b reads from memory, fetched ahead of the
+// sums it will be applied to (so that the reads overlap the reduction instead of following it).
+struct EpiOperands {
+    float bias0, bias1, res0, res1;
+};
+
+__device__ __forceinline__ void load_bias_pair(const GemmParams& p, int n, EpiOperands& e)
+{
+    if ((p.flags & kEpiBias) && n < p.N) {
+        e.bias0 = (float)p.bias[n];
+        if (n + 1 < p.N) e.bias1 = (float)p.bias[n + 1];
+    }
+}
+
+__device__ __forceinline__ void load_residual_pair(const GemmParams& p, int b, int n, EpiOperands& e)
+{
+    if ((p.flags & kEpiRes) && b < p.B && n < p.N) {
+        const _Float16* r = p.R + (int64_t)b * p.N + n;
+        e.res0 = (float)r[0];
+        if (n + 1 < p.N) e.res1 = (float)r[1];
+    }
+}
+
+__device__ __forceinline__ EpiOperands load_epilogue_operands(const GemmParams& p, int b, int n)
+{
+    EpiOperands e = {0.f, 0.f, 0.f, 0.f};
+    load_bias_pair(p, n, e);
+    load_residual_pair(p, b, n, e);
+    return e;
+}
+
+__device__ __forceinline__ float apply_epilogue(const GemmParams& p, float v, float bias, float res)
+{
+    if (p.flags & kEpiBias) v += bias;
+    if (p.flags & kEpiGelu) v = gelu_erf(v);
+    if (p.flags & kEpiRes)  v += res;
+    return v;
+}
+
 // Store the column pair (n, n+1) of row b; n is even.  One 4-byte store when both
 // columns exist and the row pitch keeps it aligned, 2-byte stores otherwise.
 // Epilogue, one rounding to fp16 and store of two adjacent outputs; y0, y1 receive the stored
 // (rounded) values, 0 where the column does not exist.
 __device__ __forceinline__ void store_pair(const GemmParams& p, int b, int n, float s0, float s1,
-                                           float& y0, float& y1)
+                                           const EpiOperands& e, float& y0, float& y1)
 {
     y0 = y1 = 0.f;
     if (n >= p.N) return;
     const int64_t off = (int64_t)b * p.N + n;
-    const _Float16 h0 = (_Float16)apply_epilogue(p, s0, b, n);
+    const _Float16 h0 = (_Float16)apply_epilogue(p, s0, e.bias0, e.res0);
     y0 = (float)h0;
     if (n + 1 < p.N) {
-        const _Float16 h1 = (_Float16)apply_epilogue(p, s1, b, n + 1);
+        const _Float16 h1 = (_Float16)apply_epilogue(p, s1, e.bias1, e.res1);
         y1 = (float)h1;
         if ((p.N & 1) == 0) {
             half2v h = {h0, h1};
@@ -47,6 +97,12 @@ __device__ __forceinline__ void store_pair(const GemmParams& p, int b, int n, fl
     } else {
         p.Y[off] = h0;
     }
+}
+
+__device__ __forceinline__ void store_pair(const GemmParams& p, int b, int n, float s0, float s1,
+                                           float& y0, float& y1)
+{
+    store_pair(p, b, n, s0, s1, load_epilogue_operands(p, b, n), y0, y1);
 }
 
 __device__ __forceinline__ void store_pair(const GemmParams& p, int b, int n, float s0, float s1)
@@ -205,14 +261,17 @@ __device__ __forceinline__ half8 ln_apply(half8 xh, half8 gh, half8 bh, floatx2 
 }
 
 // Staging of k-steps [cb, cb+cn) of X for all B rows into LDS.  Element order in LDS (16-byte
-// units): ((ks - cb)*4 + g)*B + b  holds X[b][ks*32 + g*8 .. +8], zero beyond K.
+// units): ((ks - cb)*4 + g)*xpitch + b  holds X[b][ks*32 + g*8 .. +8], zero beyond K.  xpitch is B
+// rounded up to an odd number: a wave writes 64 consecutive pieces of one row, i.e. addresses
+// xpitch*16 bytes apart, and only an odd pitch spreads those over all LDS banks (an even B >= 8
+// would put every lane of the write on the same four banks).
 // Two phases so that the global reads can be requested ahead of the weight stream's first
 // loads and written to LDS once they arrive: request() issues up to XU unconditional
 // 128-bit loads per thread (addresses clamped into the tensor), commit() writes them to LDS
 // and handles whatever did not fit (large B) or cannot be read as vectors (K % 8 != 0).
 // LN (layer-norm kernel variant) and p.ln set: X is staged raw, and the same k-steps of gamma
 // and beta travel along as two further "rows", stored after the X chunk (which always occupies
-// p.kc k-steps): gamma piece (ks, g) at p.kc*4*B + (ks - cb)*4 + g, beta p.kc*4 pieces later.
+// p.kc k-steps): gamma piece (ks, g) at p.kc*4*xpitch + (ks - cb)*4 + g, beta p.kc*4 pieces later.
 // The normalisation itself happens where the operand is read (see MfmaOp).
 template <int NT, int XU, bool LN>
 struct XStage {
@@ -232,23 +291,42 @@ struct XStage {
     }
     static __device__ __forceinline__ int dst(const GemmParams& p, int b, int c)
     {
-        int d = c * p.B + b;
-        if constexpr (LN) d = (b >= p.B) ? p.kc * 4 * p.B + (b - p.B) * p.kc * 4 + c : d;
+        int d = c * p.xpitch + b;
+        if constexpr (LN) d = (b >= p.B) ? p.kc * 4 * p.xpitch + (b - p.B) * p.kc * 4 + c : d;
         return d;
     }
 
-    __device__ __forceinline__ void request(const GemmParams& p, int cb, int cn, int tid)
+    // Pass j of a chunk covers pieces [j*NT*XU, (j+1)*NT*XU); the plain request/commit pair is pass 0
+    // plus, inside commit, whatever is left.
+    __device__ __forceinline__ void request(const GemmParams& p, int cb, int cn, int tid, int j = 0)
     {
         if (!p.x_vec) return;
         const int nc = cn * 4;             // 16-byte pieces per row
         const int items = nc * rows(p);
 #pragma unroll
         for (int u = 0; u < XU; ++u) {
-            const int idx = min(tid + u * NT, items - 1);
+            const int idx = min(j * (NT * XU) + tid + u * NT, items - 1);
             const int b = idx / nc;
             const int c = idx - b * nc;
             const int k = min(cb * kTileK + c * kChunkK, p.K - kChunkK);
             buf[u] = *reinterpret_cast<const u32x4*>(src(p, b, k));
+        }
+    }
+
+    // Writes what request(..., j) fetched (vector-readable X only).
+    __device__ __forceinline__ void commit_pass(const GemmParams& p, u32x4* xs, int cb, int cn, int tid, int j)
+    {
+        const int nc = cn * 4;
+        const int items = nc * rows(p);
+#pragma unroll
+        for (int u = 0; u < XU; ++u) {
+            const int idx = j * (NT * XU) + tid + u * NT;
+            if (idx < items) {
+                const int b = idx / nc;
+                const int c = idx - b * nc;
+                const bool inside = cb * kTileK + c * kChunkK < p.K;
+                xs[dst(p, b, c)] = inside ? buf[u] : u32x4{0u, 0u, 0u, 0u};
+            }
         }
     }
 
@@ -257,16 +335,7 @@ struct XStage {
         const int nc = cn * 4;
         const int items = nc * rows(p);
         if (p.x_vec) {
-#pragma unroll
-            for (int u = 0; u < XU; ++u) {
-                const int idx = tid + u * NT;
-                if (idx < items) {
-                    const int b = idx / nc;
-                    const int c = idx - b * nc;
-                    const bool inside = cb * kTileK + c * kChunkK < p.K;
-                    xs[dst(p, b, c)] = inside ? buf[u] : u32x4{0u, 0u, 0u, 0u};
-                }
-            }
+            commit_pass(p, xs, cb, cn, tid, 0);
             // what did not fit in the first pass: further passes of XU pieces per thread, all
             // reads of a pass issued before its LDS writes (one memory latency per pass)
             for (int base = NT * XU; base < items; base += NT * XU) {
@@ -300,7 +369,7 @@ struct XStage {
 #pragma unroll
             for (int e = 0; e < kChunkK; ++e)
                 h[e] = (k + e < p.K) ? p.X[(int64_t)b * p.K + k + e] : (_Float16)0.0f;
-            xs[c * p.B + b] = __builtin_bit_cast(u32x4, h);
+            xs[c * p.xpitch + b] = __builtin_bit_cast(u32x4, h);
         }
     }
 };
@@ -321,7 +390,7 @@ struct XStage {
 // of chunk c+1 are requested when chunk c starts, written to the other buffer when chunk c
 // ends, and one barrier separates the chunks - the weight ring is not drained.
 // `op.step(w, xk)` receives the four tiles of one k-step and the LDS address of that
-// k-step's X block ([4 lane groups][B rows] of 16 bytes).
+// k-step's X block ([4 lane groups][xpitch rows] of 16 bytes).
 // ---------------------------------------------------------------------------------------
 // One k-step of PW adjacent panels: tiles 0..3 from the first panel, 4..7 from the next one
 // (`pstride` 16-byte units further on: the same k-step of the following panel).
@@ -342,10 +411,15 @@ __device__ __forceinline__ void load_step(u32x4 (&slot)[kPanelTiles * PW], const
 // gamma and beta (see XStage) and op.step receives their address as well.
 // Stage: how X reaches LDS (XStage for fp16 operands, XStageI8 for int8 codes); both fill
 // 64 bytes per batch row and k-step, so the addressing below is the same.
-template <int NW, int DEPTH, int PW, bool LN, class Stage, class Op>
+// XP = 2 (large batches, where a chunk of X is more than one staging pass of the block): p.kc is
+// exactly one round of k-steps and a chunk takes two passes; the second is not fetched while all
+// waves wait at the end of the chunk but half a round earlier - after step DEPTH/2 - 1 the first
+// pass goes to the idle buffer and the second is requested, so each has half a chunk to arrive.
+template <int NW, int DEPTH, int PW, bool LN, int XP = 1, class Stage, class Op>
 __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Stage& xst, Op& op, int tid,
                                              int wave, int lane, int panel, int64_t pstride, int ks0, int ks1)
 {
+    static_assert(XP == 1 || (XP == 2 && DEPTH % 2 == 0), "two staging passes per chunk need an even ring depth");
     constexpr int RS = NW * DEPTH;                                 // k-steps a block consumes per round
     constexpr int kStepUnits = kPanelTiles * 64;                  // 16-byte units per k-step of a panel
     const int nks = ks1 - ks0;                                     // >= 1
@@ -353,7 +427,7 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Sta
     const int rpc = p.kc / RS;                                     // rounds per X chunk
     const int nchunks = (rounds + rpc - 1) / rpc;
     const u32x4* wbase = p.Wl + ((int64_t)panel * p.KS + ks0) * kStepUnits + lane;
-    const int xblock = 4 * p.B;                                    // 16-byte units of X per k-step
+    const int xblock = 4 * p.xpitch;                               // 16-byte units of X per k-step
     const int eblock = (LN && p.ln) ? 4 : 0;                       // 16-byte units of gamma (and of beta) per k-step
     const int xbuf = p.kc * (xblock + 2 * eblock);                 // 16-byte units per X buffer
 
@@ -377,12 +451,29 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Sta
             load_step<PW>(ring[d], wbase + (int64_t)min(t + RS, nks - 1) * kStepUnits, pstride);
             t += NW;
             __builtin_amdgcn_sched_barrier(0);
+            if constexpr (XP == 2) {
+                if (d == DEPTH / 2 - 1) {                          // every round ends a chunk: c+1 exists
+                    const int cb = ks0 + (c + 1) * p.kc, cn = min(nks - (c + 1) * p.kc, p.kc);
+                    if (p.x_vec) {                                 // (rows that cannot be read as vectors: all at the chunk's end)
+                        xst.commit_pass(p, xs + ((c + 1) & 1) * xbuf, cb, cn, tid, 0);
+                        xst.request(p, cb, cn, tid, 1);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
         }
-        if (++rc == rpc) {                                         // chunk c is consumed, c+1 exists
+        if (XP == 2 || ++rc == rpc) {                              // chunk c is consumed, c+1 exists
             rc = 0;
             ++c;
             u32x4* dst = xs + (c & 1) * xbuf;
-            xst.commit(p, dst, ks0 + c * p.kc, min(nks - c * p.kc, p.kc), tid);
+            bool staged = false;
+            if constexpr (XP == 2) {
+                if (p.x_vec) {
+                    xst.commit_pass(p, dst, ks0 + c * p.kc, min(nks - c * p.kc, p.kc), tid, 1);
+                    staged = true;
+                }
+            }
+            if (!staged) xst.commit(p, dst, ks0 + c * p.kc, min(nks - c * p.kc, p.kc), tid);
             __syncthreads();
             xc = dst - c * p.kc * xblock;
             ec = dst + p.kc * xblock - c * p.kc * eblock;
@@ -465,7 +556,7 @@ __device__ __forceinline__ u32x4 quantize16(u32x4 lo, u32x4 hi, float inv)
 }
 
 // Staging of k-steps [cb, cb+cn) (64 k each) of X as int8 codes: same LDS order as XStage
-// (piece (ks, g) of row b at ((ks - cb)*4 + g)*B + b, here 16 codes = k 16g..16g+15), same
+// (piece (ks, g) of row b at ((ks - cb)*4 + g)*xpitch + b, here 16 codes = k 16g..16g+15), same
 // request/commit split; a piece needs two 128-bit reads of fp16.  Needs K % 16 == 0.
 template <int NT, int XU>
 struct XStageI8 {
@@ -499,7 +590,7 @@ struct XStageI8 {
                 const int c = idx - b * nc;
                 const bool inside = cb * 64 + c * 16 < p.K;
                 const u32x4 q = quantize16(buf[u][0], buf[u][1], p_stats[b][0]);
-                xs[c * p.B + b] = inside ? q : u32x4{0u, 0u, 0u, 0u};
+                xs[c * p.xpitch + b] = inside ? q : u32x4{0u, 0u, 0u, 0u};
             }
         }
         for (int base = NT * XU; base < items; base += NT * XU) {
@@ -522,7 +613,7 @@ struct XStageI8 {
                     const int c = idx - b * nc;
                     const bool inside = cb * 64 + c * 16 < p.K;
                     const u32x4 q = quantize16(v[u][0], v[u][1], p_stats[b][0]);
-                    xs[c * p.B + b] = inside ? q : u32x4{0u, 0u, 0u, 0u};
+                    xs[c * p.xpitch + b] = inside ? q : u32x4{0u, 0u, 0u, 0u};
                 }
             }
         }
@@ -559,12 +650,52 @@ __device__ __forceinline__ float dequant(const GemmParams& p, int acc, int b, in
     return (float)acc * (stats[b][1] * p.sw[min(n, p.N - 1)]);
 }
 
-template <int NW, bool I8 = false>
-__device__ __forceinline__ void reduce_rows(const GemmParams& p, const float* red, int mb,
-                                            int panel, int split, int tid, const floatx2* stats = nullptr)
+// The outputs reduce_rows will finish in this thread: 16 rows x 32 column pairs over NW*64 threads.
+template <int NW>
+struct RowOperands {
+    static constexpr int kItems = (16 * 32 + NW * 64 - 1) / (NW * 64);
+    EpiOperands e[kItems];
+};
+
+// Requests the epilogue operands of reduce_rows(…, mb, panel, …) - call it ahead of the barriers
+// that reduce_rows has to wait for anyway.  The bias of a thread's column pair is the same for
+// every mb of a panel: with `fresh_bias` false it is taken over from `bias_of` instead of loaded.
+template <int NW>
+__device__ __forceinline__ RowOperands<NW> request_row_operands(const GemmParams& p, int mb, int panel, int tid,
+                                                                bool fresh_bias, const RowOperands<NW>& bias_of)
 {
     constexpr int NT = NW * 64;
-    for (int item = tid; item < 16 * 32; item += NT) {
+    RowOperands<NW> ops;
+#pragma unroll
+    for (int j = 0; j < RowOperands<NW>::kItems; ++j) {
+        const int item = tid + j * NT;
+        const int b = mb * 16 + (item >> 5);
+        const int n = panel * kPanelN + (item & 31) * 2;
+        EpiOperands e = {0.f, 0.f, 0.f, 0.f};
+        if (p.S == 1 && item < 16 * 32) {
+            if (fresh_bias) {
+                load_bias_pair(p, n, e);
+            } else {
+                e.bias0 = bias_of.e[j].bias0;
+                e.bias1 = bias_of.e[j].bias1;
+            }
+            load_residual_pair(p, b, n, e);
+        }
+        ops.e[j] = e;
+    }
+    return ops;
+}
+
+template <int NW, bool I8 = false>
+__device__ __forceinline__ void reduce_rows(const GemmParams& p, const float* red, int mb,
+                                            int panel, int split, int tid, const RowOperands<NW>& ops,
+                                            const floatx2* stats = nullptr)
+{
+    constexpr int NT = NW * 64;
+#pragma unroll
+    for (int j = 0; j < RowOperands<NW>::kItems; ++j) {
+        const int item = tid + j * NT;
+        if (item >= 16 * 32) continue;
         const int bl = item >> 5;
         const int c2 = (item & 31) * 2;
         const int b = mb * 16 + bl;
@@ -585,11 +716,11 @@ __device__ __forceinline__ void reduce_rows(const GemmParams& p, const float* re
         }
         const int n = panel * kPanelN + c2;
         if (p.S == 1) {
+            float y0, y1;
             if constexpr (I8) {
-                store_pair(p, b, n, dequant(p, i0, b, n, stats), dequant(p, i1, b, n + 1, stats));
+                store_pair(p, b, n, dequant(p, i0, b, n, stats), dequant(p, i1, b, n + 1, stats), ops.e[j], y0, y1);
             } else {
-                float y0, y1;
-                store_pair(p, b, n, s0, s1, y0, y1);
+                store_pair(p, b, n, s0, s1, ops.e[j], y0, y1);
                 if (p.moments_out) emit_moments(p, b, panel, n, y0, y1, tid);      // tid & 31 == lane & 31
             }
         } else {
@@ -628,25 +759,36 @@ __device__ __forceinline__ void finish_split_k(const GemmParams& p, int panel, i
     for (int item = tid; item < items; item += NT) {
         const int b = item >> 5;
         const int c2 = (item & 31) * 2;
+        const int n = panel * kPanelN + c2;
+        const EpiOperands e = load_epilogue_operands(p, b, n);
         float s0 = 0.f, s1 = 0.f;
         int i0 = 0, i1 = 0;
-        for (int s = 0; s < p.S; ++s) {
-            float v0, v1;
-            load_partial(base + ((int64_t)s * p.B + b) * kPanelN + c2, v0, v1);
-            if constexpr (I8) {
-                i0 += __builtin_bit_cast(int, v0);
-                i1 += __builtin_bit_cast(int, v1);
-            } else {
-                s0 += v0;
-                s1 += v1;
+        // the slabs are fetched kSlabBatch at a time (independent loads, one latency per batch) and
+        // added in slab order
+        constexpr int kSlabBatch = 4;
+        for (int sb = 0; sb < p.S; sb += kSlabBatch) {
+            float v0[kSlabBatch], v1[kSlabBatch];
+#pragma unroll
+            for (int u = 0; u < kSlabBatch; ++u)
+                load_partial(base + ((int64_t)min(sb + u, p.S - 1) * p.B + b) * kPanelN + c2, v0[u], v1[u]);
+#pragma unroll
+            for (int u = 0; u < kSlabBatch; ++u) {
+                if (sb + u < p.S) {
+                    if constexpr (I8) {
+                        i0 += __builtin_bit_cast(int, v0[u]);
+                        i1 += __builtin_bit_cast(int, v1[u]);
+                    } else {
+                        s0 += v0[u];
+                        s1 += v1[u];
+                    }
+                }
             }
         }
-        const int n = panel * kPanelN + c2;
+        float y0, y1;
         if constexpr (I8) {
-            store_pair(p, b, n, dequant(p, i0, b, n, stats), dequant(p, i1, b, n + 1, stats));
+            store_pair(p, b, n, dequant(p, i0, b, n, stats), dequant(p, i1, b, n + 1, stats), e, y0, y1);
         } else {
-            float y0, y1;
-            store_pair(p, b, n, s0, s1, y0, y1);
+            store_pair(p, b, n, s0, s1, e, y0, y1);
             if (p.moments_out) emit_moments(p, b, panel, n, y0, y1, tid);
         }
     }

@@ -56,6 +56,7 @@ struct GemmParams {
     int S;                     // blocks per panel (split-K factor)
     int ksps;                  // k-steps per block
     int kc;                    // k-steps of X staged per chunk (multiple of waves*depth)
+    int xpitch;                // 16-byte pieces between the lane groups of a k-step's X block in LDS: B rounded up to odd
     int flags;                 // kEpi* bits
     int x_vec;                 // 1: X rows are 16-byte aligned and K % 8 == 0
     int ln;                    // 1: layer-normalise the rows of X on their way into LDS

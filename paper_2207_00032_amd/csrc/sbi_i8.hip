@@ -22,14 +22,14 @@ struct MfmaI8Op {
     i32x4 acc[kPanelTiles][MB];
     int xoff[MB];
 
-    __device__ __forceinline__ void init(int B, int g, int i)
+    __device__ __forceinline__ void init(int B, int pitch, int g, int i)
     {
 #pragma unroll
         for (int t = 0; t < kPanelTiles; ++t)
 #pragma unroll
             for (int m = 0; m < MB; ++m) acc[t][m] = i32x4{0, 0, 0, 0};
 #pragma unroll
-        for (int m = 0; m < MB; ++m) xoff[m] = g * B + min(m * 16 + i, B - 1);
+        for (int m = 0; m < MB; ++m) xoff[m] = g * pitch + min(m * 16 + i, B - 1);
     }
 
     // A and B operands use the same lane -> k assignment (lane group g: k 16g..16g+15 of the
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(NW * 64) void sbi_i8_kernel(const GroupParams gp)
     const int ks1 = min(p.KS, ks0 + p.ksps);
 
     MfmaI8Op<MB> op;
-    op.init(p.B, g, i);
+    op.init(p.B, p.xpitch, g, i);
     if constexpr (PREQ) {
         XStageCodes<NT, 4> xst;
         xst.init(p);
@@ -119,6 +119,9 @@ __global__ __launch_bounds__(NW * 64) void sbi_i8_kernel(const GroupParams gp)
         stream_panel<NW, DEPTH, 1, false>(p, xs, xst, op, tid, wave, lane, panel, 0, ks0, ks1);
     }
 
+    RowOperands<NW> ops[MB];           // bias / residual of all passes, requested ahead of the first barrier
+#pragma unroll
+    for (int m = 0; m < MB; ++m) ops[m] = request_row_operands<NW>(p, m, panel, tid, m == 0, ops[0]);
 #pragma unroll
     for (int m = 0; m < MB; ++m) {
         __syncthreads();               // X buffers / previous pass no longer needed
@@ -126,7 +129,7 @@ __global__ __launch_bounds__(NW * 64) void sbi_i8_kernel(const GroupParams gp)
         for (int t = 0; t < kPanelTiles; ++t)
             *reinterpret_cast<i32x4*>(red + (wave * 16 + i) * kRedPitch + t * kTileN + 4 * g) = op.acc[t][m];
         __syncthreads();
-        reduce_rows<NW, true>(p, red, m, panel, split, tid, stats);
+        reduce_rows<NW, true>(p, red, m, panel, split, tid, ops[m], stats);
     }
     if (p.S > 1) finish_split_k<NT, true>(p, panel, tid, &s_flag, stats);
 }

@@ -35,7 +35,7 @@ struct MfmaOp {
             for (int m = 0; m < MB; ++m) acc[t][m] = floatx4{0.f, 0.f, 0.f, 0.f};
         // rows beyond B re-read row B-1: they only feed result columns that are never stored
 #pragma unroll
-        for (int m = 0; m < MB; ++m) xoff[m] = g * p.B + min(m * 16 + i, p.B - 1);
+        for (int m = 0; m < MB; ++m) xoff[m] = g * p.xpitch + min(m * 16 + i, p.B - 1);
         goff = g;
         boff = p.kc * 4;
         ln = 0;
@@ -70,6 +70,13 @@ struct MfmaOp {
         }
     }
 };
+
+// Batches above 32 on the 8-wave two-panel shape: a chunk of X (one round of 16 k-steps, B rows)
+// is two staging passes of the block, taken half a round apart (see stream_panel).
+__host__ __device__ constexpr int staging_passes(int mb, int nw, int depth, int pw, bool ln)
+{
+    return (mb >= 3 && nw == 8 && depth == 2 && pw == 2 && !ln) ? 2 : 1;
+}
 
 // One launch may carry several independent GeMMs of the same batch size (the linear layers of
 // one transformer layer): their blocks are simply concatenated, so the ramp-up and the tail of
@@ -119,25 +126,39 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
     MfmaOp<MB, PW, LN> op;
     op.init(p, stats, g, i);
     XStage<NT, 4, LN> xst;            // covers NT*64 bytes of X per chunk without a second pass
-    stream_panel<NW, DEPTH, PW, LN>(p, xs, xst, op, tid, wave, lane, panel, pstride, ks0, ks1);
+    stream_panel<NW, DEPTH, PW, LN, staging_passes(MB, NW, DEPTH, PW, LN)>(p, xs, xst, op, tid, wave, lane, panel,
+                                                                           pstride, ks0, ks1);
 #ifdef SBI_TRACE
     const unsigned long long t_stream = wall_clock64();
+    unsigned long long t_sync = 0;
 #endif
 
     // In-block K-split reduction: each wave parks its 64-column x 16-row tile in LDS
     // (the MFMA result holds, per lane, 4 consecutive columns of one batch row).
+    // What the epilogues will read (bias, residual) is requested for all passes at once, before the
+    // first barrier: one memory latency in the shadow of the wait for the block's last wave,
+    // instead of one per pass.
+    RowOperands<NW> ops[PW][MB];
+#pragma unroll
+    for (int q = 0; q < PW; ++q)
+#pragma unroll
+        for (int m = 0; m < MB; ++m)
+            ops[q][m] = request_row_operands<NW>(p, m, min(panel + q, p.P - 1), tid, m == 0, ops[q][0]);
 #pragma unroll
     for (int q = 0; q < PW; ++q) {
         if (q < npanels) {
 #pragma unroll
             for (int m = 0; m < MB; ++m) {
                 __syncthreads();               // X tile / previous pass no longer needed
+#ifdef SBI_TRACE
+                if (q == 0 && m == 0) t_sync = wall_clock64();
+#endif
 #pragma unroll
                 for (int t = 0; t < kPanelTiles; ++t)
                     *reinterpret_cast<floatx4*>(red + (wave * 16 + i) * kRedPitch + t * kTileN + 4 * g) =
                         op.acc[q * kPanelTiles + t][m];
                 __syncthreads();
-                reduce_rows<NW>(p, red, m, panel + q, split, tid);
+                reduce_rows<NW>(p, red, m, panel + q, split, tid, ops[q][m]);
             }
             if (p.S > 1) finish_split_k<NT>(p, panel + q, tid, &s_flag);
         }
@@ -146,7 +167,12 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
     if (p.trace && tid == 0) {
         unsigned long long* t = p.trace + (size_t)blockIdx.x * 4;
         t[0] = t_start; t[1] = t_stream; t[2] = wall_clock64();
+#ifdef SBI_TRACE_SYNC
+        t[3] = t_sync;                 // when the block's last wave finished streaming
+#else
         t[3] = ((unsigned long long)gi << 32) | (unsigned)bid;
+        (void)t_sync;
+#endif
     }
 #endif
 }
@@ -182,6 +208,11 @@ int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, bool la
                 hipStream_t st)
 {
     if (gp.G < 1 || gp.G > kMaxGroup) return (int)hipErrorInvalidValue;
+    if (staging_passes((gp.g[0].B + 15) / 16, waves, depth, panels, layernorm) == 2) {
+        // the two-pass staging assumes a chunk is exactly one round and at most two passes long
+        for (int g = 0; g < gp.G; ++g)
+            if (gp.g[g].kc != waves * depth || gp.g[g].kc * 4 * gp.g[g].B > 2 * waves * 64 * 4) return (int)hipErrorInvalidValue;
+    }
     if (layernorm) {                   // layer-norm variants exist for the one-panel shapes the dispatcher uses
         if (panels != 1) return (int)hipErrorInvalidValue;
         if (waves == 4 && depth == 2) return launch_mb<4, 2, 1, true>(gp, lds_bytes, st);

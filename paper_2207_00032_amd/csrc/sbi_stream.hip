@@ -18,15 +18,15 @@ namespace sbi {
 template <int BT>
 struct DotOp {
     float acc[kPanelTiles][BT];
-    int xoff;         // g * BT: the lane group's 16-byte slots inside a k-step's X block
+    int xoff;         // the lane group's 16-byte slots inside a k-step's X block
 
-    __device__ __forceinline__ void init(int g)
+    __device__ __forceinline__ void init(int g, int pitch)
     {
 #pragma unroll
         for (int t = 0; t < kPanelTiles; ++t)
 #pragma unroll
             for (int b = 0; b < BT; ++b) acc[t][b] = 0.f;
-        xoff = g * BT;
+        xoff = g * pitch;
     }
 
     __device__ __forceinline__ void step(const u32x4 (&w)[kPanelTiles], const u32x4* xk, const u32x4*)
@@ -72,7 +72,7 @@ __global__ __launch_bounds__(NW * 64) void sbi_stream_kernel(const GemmParams p)
     const int ks1 = min(p.KS, ks0 + p.ksps);
 
     DotOp<BT> op;
-    op.init(g);
+    op.init(g, p.xpitch);
     XStage<NW * 64, 4, false> xst;
     stream_panel<NW, DEPTH, 1, false>(p, xs, xst, op, tid, wave, lane, panel, 0, ks0, ks1);
 
@@ -86,6 +86,8 @@ __global__ __launch_bounds__(NW * 64) void sbi_stream_kernel(const GemmParams p)
             v += __shfl_xor(v, 32, 64);
             op.acc[t][b] = v;
         }
+    RowOperands<NW> ops;               // bias / residual, requested ahead of the barriers
+    ops = request_row_operands<NW>(p, 0, panel, tid, true, ops);
     __syncthreads();                   // X tile no longer needed
     if (g == 0) {
 #pragma unroll
@@ -95,7 +97,7 @@ __global__ __launch_bounds__(NW * 64) void sbi_stream_kernel(const GemmParams p)
                 red[(wave * 16 + b) * kRedPitch + t * kTileN + i] = op.acc[t][b];
     }
     __syncthreads();
-    reduce_rows<NW>(p, red, 0, panel, split, tid);
+    reduce_rows<NW>(p, red, 0, panel, split, tid, ops);
 
     if (p.S > 1) finish_split_k<NT>(p, panel, tid, &s_flag);
 }

@@ -117,6 +117,8 @@ inline emu_i32x4 __builtin_amdgcn_mfma_i32_16x16x64_i8(emu_i32x4 a, emu_i32x4 bb
     return c;
 }
 inline int __builtin_amdgcn_readfirstlane(int v) { return v; }
+inline float __builtin_amdgcn_rcpf(float v) { return 1.0f / v; }
+inline float __builtin_amdgcn_exp2f(float v) { return exp2f(v); }
 #define __builtin_amdgcn_sched_barrier(x) ((void)0)
 #define __builtin_amdgcn_fence(order, scope) __atomic_thread_fence(__ATOMIC_SEQ_CST)
 #define __HIP_MEMORY_SCOPE_AGENT 0

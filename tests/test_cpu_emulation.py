@@ -40,6 +40,7 @@ GEMM_CASES = [
     (1, 64, 64, 0, 0, 0, 0, 0), (3, 264, 200, 0, 0, 0, 0, 0), (5, 1001, 130, 4, 4, 2, 1, 0),
     (8, 2048, 128, 8, 4, 1, 1, 0), (17, 1024, 136, 4, 2, 3, 1, 0), (33, 520, 192, 4, 4, 1, 2, 0),
     (64, 512, 128, 8, 2, 2, 2, 0), (1, 12288, 128, 4, 4, 1, 1, 0),
+    (64, 2048, 192, 8, 2, 1, 2, 0), (48, 1100, 128, 8, 2, 1, 2, 0), (40, 1544, 136, 8, 2, 2, 2, 0), (33, 3072, 128, 8, 2, 1, 2, 0),
     (1, 64, 64, 0, 0, 0, 0, 1), (3, 264, 200, 0, 0, 0, 0, 1), (8, 2048, 128, 8, 4, 1, 1, 1),
     (17, 1024, 136, 4, 2, 3, 1, 1), (40, 1024, 72, 4, 4, 2, 1, 1), (64, 512, 128, 4, 2, 2, 1, 1),
     (2, 6144, 64, 4, 4, 1, 1, 1),

@@ -123,7 +123,7 @@ def test_streamk_range_cuts(gpu, B, K, N):
 
 
 @pytest.mark.parametrize("B,K,N", [(1, 1024, 192), (8, 2048, 320), (16, 520, 72), (17, 4096, 136),
-                                   (33, 1024, 448), (48, 2048, 200), (64, 4096, 192)])
+                                   (33, 1024, 448), (48, 2048, 200), (64, 4096, 192), (40, 1100, 136), (64, 2500, 72)])
 def test_two_panel_blocks(gpu, B, K, N):
     """Blocks that stream two adjacent panels (odd panel counts leave a lone last panel)."""
     from paper_2207_00032_amd import binding as sb
