@@ -389,8 +389,8 @@ struct XStage {
 // straddles a chunk).  With more than one chunk the LDS holds two buffers: the global reads
 // of chunk c+1 are requested when chunk c starts, written to the other buffer when chunk c
 // ends, and one barrier separates the chunks - the weight ring is not drained.
-// `op.step(w, xk)` receives the four tiles of one k-step and the LDS address of that
-// k-step's X block ([4 lane groups][xpitch rows] of 16 bytes).
+// `op.begin(xk, ek)` receives the LDS address of a k-step's X block, `op.tile(t, w)` one of its
+// weight tiles; X block: ([4 lane groups][xpitch rows] of 16 bytes).
 // ---------------------------------------------------------------------------------------
 // One k-step of PW adjacent panels: tiles 0..3 from the first panel, 4..7 from the next one
 // (`pstride` 16-byte units further on: the same k-step of the following panel).
@@ -411,15 +411,40 @@ __device__ __forceinline__ void load_step(u32x4 (&slot)[kPanelTiles * PW], const
 // gamma and beta (see XStage) and op.step receives their address as well.
 // Stage: how X reaches LDS (XStage for fp16 operands, XStageI8 for int8 codes); both fill
 // 64 bytes per batch row and k-step, so the addressing below is the same.
-// XP = 2 (large batches, where a chunk of X is more than one staging pass of the block): p.kc is
-// exactly one round of k-steps and a chunk takes two passes; the second is not fetched while all
-// waves wait at the end of the chunk but half a round earlier - after step DEPTH/2 - 1 the first
-// pass goes to the idle buffer and the second is requested, so each has half a chunk to arrive.
+// XP > 1 (batches above 16, where a chunk of X is one round of k-steps and more than one staging
+// pass of the block): the passes are not all fetched while the waves wait at the end of the chunk,
+// but spread over the round - after every DEPTH/XP steps the pass that has arrived goes to the idle
+// buffer and the next one is requested, so each has DEPTH/XP steps of streaming to arrive in.
+// staging_passes() gives XP for a kernel shape: the passes the largest batch of its MB needs,
+// rounded up to a divisor of DEPTH (1, i.e. everything at the chunk's end, if there are more
+// passes than steps, and for MB = 1, where chunks may be longer than a round).
+__host__ __device__ constexpr int staging_passes(int mb, int depth, bool ln)
+{
+    if (mb < 2) return 1;
+    const int need = (depth * (16 * mb + (ln ? 2 : 0)) + 63) / 64;     // rows * RS * 4 pieces over NT * 4 per pass
+    for (int xp = 1; xp <= depth; ++xp)
+        if (depth % xp == 0 && xp >= need) return xp;
+    return 1;
+}
+
+// Host-side check of what spread staging assumes of every problem of a launch: a chunk is exactly
+// one round of k-steps and no longer than XP passes of the block.
+inline bool spread_staging_fits(const GroupParams& gp, int waves, int depth, bool layernorm)
+{
+    const int xp = staging_passes((gp.g[0].B + 15) / 16, depth, layernorm);
+    if (xp == 1) return true;
+    for (int g = 0; g < gp.G; ++g) {
+        const int rows = gp.g[g].B + ((layernorm && gp.g[g].ln) ? 2 : 0);
+        if (gp.g[g].kc != waves * depth || gp.g[g].kc * 4 * rows > xp * waves * 64 * 4) return false;
+    }
+    return true;
+}
+
 template <int NW, int DEPTH, int PW, bool LN, int XP = 1, class Stage, class Op>
 __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Stage& xst, Op& op, int tid,
                                              int wave, int lane, int panel, int64_t pstride, int ks0, int ks1)
 {
-    static_assert(XP == 1 || (XP == 2 && DEPTH % 2 == 0), "two staging passes per chunk need an even ring depth");
+    static_assert(XP >= 1 && DEPTH % XP == 0, "staging passes are spread evenly over the steps of a round");
     constexpr int RS = NW * DEPTH;                                 // k-steps a block consumes per round
     constexpr int kStepUnits = kPanelTiles * 64;                  // 16-byte units per k-step of a panel
     const int nks = ks1 - ks0;                                     // >= 1
@@ -447,29 +472,39 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Sta
     for (int r = 0; r + 1 < rounds; ++r) {
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
-            op.step(ring[d], xc + t * xblock, ec + t * eblock);    // always inside the range here
-            load_step<PW>(ring[d], wbase + (int64_t)min(t + RS, nks - 1) * kStepUnits, pstride);
+            // always inside the range here; every tile's registers are refilled right behind the
+            // products that read them, so a slot is out of flight for one tile's products, not a step's
+            op.begin(xc + t * xblock, ec + t * eblock);
+            const u32x4* src = wbase + (int64_t)min(t + RS, nks - 1) * kStepUnits;
+#pragma unroll
+            for (int q = 0; q < PW; ++q)
+#pragma unroll
+                for (int tt = 0; tt < kPanelTiles; ++tt) {
+                    op.tile(q * kPanelTiles + tt, ring[d][q * kPanelTiles + tt]);
+                    ring[d][q * kPanelTiles + tt] = __builtin_nontemporal_load(src + q * pstride + tt * 64);
+                }
             t += NW;
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (XP == 2) {
-                if (d == DEPTH / 2 - 1) {                          // every round ends a chunk: c+1 exists
+            if constexpr (XP > 1) {
+                if ((d + 1) % (DEPTH / XP) == 0 && d + 1 < DEPTH) { // every round ends a chunk: c+1 exists
+                    const int j = (d + 1) / (DEPTH / XP) - 1;
                     const int cb = ks0 + (c + 1) * p.kc, cn = min(nks - (c + 1) * p.kc, p.kc);
                     if (p.x_vec) {                                 // (rows that cannot be read as vectors: all at the chunk's end)
-                        xst.commit_pass(p, xs + ((c + 1) & 1) * xbuf, cb, cn, tid, 0);
-                        xst.request(p, cb, cn, tid, 1);
+                        xst.commit_pass(p, xs + ((c + 1) & 1) * xbuf, cb, cn, tid, j);
+                        xst.request(p, cb, cn, tid, j + 1);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
-        if (XP == 2 || ++rc == rpc) {                              // chunk c is consumed, c+1 exists
+        if (XP > 1 || ++rc == rpc) {                               // chunk c is consumed, c+1 exists
             rc = 0;
             ++c;
             u32x4* dst = xs + (c & 1) * xbuf;
             bool staged = false;
-            if constexpr (XP == 2) {
+            if constexpr (XP > 1) {
                 if (p.x_vec) {
-                    xst.commit_pass(p, dst, ks0 + c * p.kc, min(nks - c * p.kc, p.kc), tid, 1);
+                    xst.commit_pass(p, dst, ks0 + c * p.kc, min(nks - c * p.kc, p.kc), tid, XP - 1);
                     staged = true;
                 }
             }
@@ -486,7 +521,9 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Sta
 #pragma unroll
             for (int q = 0; q < kPanelTiles * PW; ++q) ring[d][q] = u32x4{0u, 0u, 0u, 0u};
         }
-        op.step(ring[d], xc + min(t, nks - 1) * xblock, ec + min(t, nks - 1) * eblock);
+        op.begin(xc + min(t, nks - 1) * xblock, ec + min(t, nks - 1) * eblock);
+#pragma unroll
+        for (int q = 0; q < kPanelTiles * PW; ++q) op.tile(q, ring[d][q]);
         t += NW;
     }
 }

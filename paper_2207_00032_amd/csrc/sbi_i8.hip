@@ -34,18 +34,20 @@ struct MfmaI8Op {
 
     // A and B operands use the same lane -> k assignment (lane group g: k 16g..16g+15 of the
     // k-step), which is all the contraction needs.
-    __device__ __forceinline__ void step(const u32x4 (&w)[kPanelTiles], const u32x4* xk, const u32x4*)
+    i32x4 xf[MB];
+
+    __device__ __forceinline__ void begin(const u32x4* xk, const u32x4*)
     {
-        i32x4 xf[MB];
 #pragma unroll
         for (int m = 0; m < MB; ++m) xf[m] = __builtin_bit_cast(i32x4, xk[xoff[m]]);
+    }
+
+    __device__ __forceinline__ void tile(int t, u32x4 w)
+    {
+        const i32x4 wf = __builtin_bit_cast(i32x4, w);
 #pragma unroll
-        for (int t = 0; t < kPanelTiles; ++t) {
-            const i32x4 wf = __builtin_bit_cast(i32x4, w[t]);
-#pragma unroll
-            for (int m = 0; m < MB; ++m)
-                acc[t][m] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf[m], acc[t][m], 0, 0, 0);
-        }
+        for (int m = 0; m < MB; ++m)
+            acc[t][m] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf[m], acc[t][m], 0, 0, 0);
     }
 };
 
@@ -64,7 +66,11 @@ struct XStageCodes {
         q.K = p.K / 2;
         q.x_vec = 1;
     }
-    __device__ __forceinline__ void request(const GemmParams&, int cb, int cn, int tid) { inner.request(q, cb, cn, tid); }
+    __device__ __forceinline__ void request(const GemmParams&, int cb, int cn, int tid, int j = 0) { inner.request(q, cb, cn, tid, j); }
+    __device__ __forceinline__ void commit_pass(const GemmParams&, u32x4* xs, int cb, int cn, int tid, int j)
+    {
+        inner.commit_pass(q, xs, cb, cn, tid, j);
+    }
     __device__ __forceinline__ void commit(const GemmParams&, u32x4* xs, int cb, int cn, int tid)
     {
         inner.commit(q, xs, cb, cn, tid);
@@ -112,7 +118,7 @@ __global__ __launch_bounds__(NW * 64) void sbi_i8_kernel(const GroupParams gp)
     if constexpr (PREQ) {
         XStageCodes<NT, 4> xst;
         xst.init(p);
-        stream_panel<NW, DEPTH, 1, false>(p, xs, xst, op, tid, wave, lane, panel, 0, ks0, ks1);
+        stream_panel<NW, DEPTH, 1, false, staging_passes(MB, DEPTH, false)>(p, xs, xst, op, tid, wave, lane, panel, 0, ks0, ks1);
     } else {
         XStageI8<NT, 2> xst;       // two 32-byte reads per thread in flight: NT*32 bytes of LDS per pass
         xst.p_stats = lds_stats;
@@ -203,6 +209,7 @@ int launch_i8(const GroupParams& gp, int waves, int depth, bool prequantized, si
 {
     if (gp.G < 1 || gp.G > kMaxGroup) return (int)hipErrorInvalidValue;
     if (prequantized) {
+        if (!spread_staging_fits(gp, waves, depth, false)) return (int)hipErrorInvalidValue;
         // gp.g[k].X already points at the codes' place in the workspace: fill it from gp.g[k].X16
         QuantRowsParams q;
         for (int k = 0; k < gp.G; ++k) {

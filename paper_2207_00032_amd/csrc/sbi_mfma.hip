@@ -48,9 +48,13 @@ struct MfmaOp {
         }
     }
 
-    __device__ __forceinline__ void step(const u32x4 (&w)[kPanelTiles * PW], const u32x4* xk, const u32x4* ek)
+    // A k-step in two parts, so that the caller can refill each weight tile's registers right after
+    // the MFMAs that read them: begin() fetches (and, with LN, normalises) the X operand, tile()
+    // multiplies one 16-column tile by it.
+    half8 xf[MB];
+
+    __device__ __forceinline__ void begin(const u32x4* xk, const u32x4* ek)
     {
-        half8 xf[MB];
 #pragma unroll
         for (int m = 0; m < MB; ++m) xf[m] = __builtin_bit_cast(half8, xk[xoff[m]]);
         if constexpr (LN) {
@@ -61,22 +65,16 @@ struct MfmaOp {
                 for (int m = 0; m < MB; ++m) xf[m] = ln_apply(xf[m], gh, bh, st[m]);
             }
         }
+    }
+
+    __device__ __forceinline__ void tile(int t, u32x4 w)
+    {
+        const half8 wf = __builtin_bit_cast(half8, w);
 #pragma unroll
-        for (int t = 0; t < kPanelTiles * PW; ++t) {
-            const half8 wf = __builtin_bit_cast(half8, w[t]);
-#pragma unroll
-            for (int m = 0; m < MB; ++m)
-                acc[t][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf, xf[m], acc[t][m], 0, 0, 0);
-        }
+        for (int m = 0; m < MB; ++m)
+            acc[t][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf, xf[m], acc[t][m], 0, 0, 0);
     }
 };
-
-// Batches above 32 on the 8-wave two-panel shape: a chunk of X (one round of 16 k-steps, B rows)
-// is two staging passes of the block, taken half a round apart (see stream_panel).
-__host__ __device__ constexpr int staging_passes(int mb, int nw, int depth, int pw, bool ln)
-{
-    return (mb >= 3 && nw == 8 && depth == 2 && pw == 2 && !ln) ? 2 : 1;
-}
 
 // One launch may carry several independent GeMMs of the same batch size (the linear layers of
 // one transformer layer): their blocks are simply concatenated, so the ramp-up and the tail of
@@ -126,7 +124,7 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
     MfmaOp<MB, PW, LN> op;
     op.init(p, stats, g, i);
     XStage<NT, 4, LN> xst;            // covers NT*64 bytes of X per chunk without a second pass
-    stream_panel<NW, DEPTH, PW, LN, staging_passes(MB, NW, DEPTH, PW, LN)>(p, xs, xst, op, tid, wave, lane, panel,
+    stream_panel<NW, DEPTH, PW, LN, staging_passes(MB, DEPTH, LN)>(p, xs, xst, op, tid, wave, lane, panel,
                                                                            pstride, ks0, ks1);
 #ifdef SBI_TRACE
     const unsigned long long t_stream = wall_clock64();
@@ -208,11 +206,7 @@ int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, bool la
                 hipStream_t st)
 {
     if (gp.G < 1 || gp.G > kMaxGroup) return (int)hipErrorInvalidValue;
-    if (staging_passes((gp.g[0].B + 15) / 16, waves, depth, panels, layernorm) == 2) {
-        // the two-pass staging assumes a chunk is exactly one round and at most two passes long
-        for (int g = 0; g < gp.G; ++g)
-            if (gp.g[g].kc != waves * depth || gp.g[g].kc * 4 * gp.g[g].B > 2 * waves * 64 * 4) return (int)hipErrorInvalidValue;
-    }
+    if (!spread_staging_fits(gp, waves, depth, layernorm)) return (int)hipErrorInvalidValue;
     if (layernorm) {                   // layer-norm variants exist for the one-panel shapes the dispatcher uses
         if (panels != 1) return (int)hipErrorInvalidValue;
         if (waves == 4 && depth == 2) return launch_mb<4, 2, 1, true>(gp, lds_bytes, st);

@@ -29,24 +29,26 @@ struct DotOp {
         xoff = g * pitch;
     }
 
-    __device__ __forceinline__ void step(const u32x4 (&w)[kPanelTiles], const u32x4* xk, const u32x4*)
+    u32x4 xf[BT];
+
+    __device__ __forceinline__ void begin(const u32x4* xk, const u32x4*)
     {
-        u32x4 xf[BT];
 #pragma unroll
         for (int b = 0; b < BT; ++b) xf[b] = xk[xoff + b];     // same address in all 16 lanes: broadcast
+    }
+
+    __device__ __forceinline__ void tile(int t, u32x4 w)
+    {
+        const unsigned int wq[4] = {w.x, w.y, w.z, w.w};      // k pairs (0,1) (2,3) (4,5) (6,7)
 #pragma unroll
-        for (int t = 0; t < kPanelTiles; ++t) {
-            const unsigned int wq[4] = {w[t].x, w[t].y, w[t].z, w[t].w};      // k pairs (0,1) (2,3) (4,5) (6,7)
-#pragma unroll
-            for (int b = 0; b < BT; ++b) {
-                const unsigned int xq[4] = {xf[b].x, xf[b].y, xf[b].z, xf[b].w};
-                float a = acc[t][b];
-                a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, wq[0]), __builtin_bit_cast(half2v, xq[0]), a, false);
-                a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, wq[1]), __builtin_bit_cast(half2v, xq[1]), a, false);
-                a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, wq[2]), __builtin_bit_cast(half2v, xq[2]), a, false);
-                a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, wq[3]), __builtin_bit_cast(half2v, xq[3]), a, false);
-                acc[t][b] = a;
-            }
+        for (int b = 0; b < BT; ++b) {
+            const unsigned int xq[4] = {xf[b].x, xf[b].y, xf[b].z, xf[b].w};
+            float a = acc[t][b];
+            a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, wq[0]), __builtin_bit_cast(half2v, xq[0]), a, false);
+            a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, wq[1]), __builtin_bit_cast(half2v, xq[1]), a, false);
+            a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, wq[2]), __builtin_bit_cast(half2v, xq[2]), a, false);
+            a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, wq[3]), __builtin_bit_cast(half2v, xq[3]), a, false);
+            acc[t][b] = a;
         }
     }
 };

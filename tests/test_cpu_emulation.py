@@ -41,6 +41,9 @@ GEMM_CASES = [
     (8, 2048, 128, 8, 4, 1, 1, 0), (17, 1024, 136, 4, 2, 3, 1, 0), (33, 520, 192, 4, 4, 1, 2, 0),
     (64, 512, 128, 8, 2, 2, 2, 0), (1, 12288, 128, 4, 4, 1, 1, 0),
     (64, 2048, 192, 8, 2, 1, 2, 0), (48, 1100, 128, 8, 2, 1, 2, 0), (40, 1544, 136, 8, 2, 2, 2, 0), (33, 3072, 128, 8, 2, 1, 2, 0),
+    # several rounds with the X staging passes spread over the steps of a round (batches above 16)
+    (40, 4096, 72, 4, 2, 1, 1, 0), (40, 4096, 72, 4, 4, 1, 1, 1), (40, 4096, 72, 4, 4, 1, 1, 2),
+    (24, 4096, 72, 4, 4, 1, 1, 0), (24, 4096, 72, 8, 4, 1, 1, 1), (24, 4100, 72, 4, 4, 1, 1, 0), (24, 4096, 72, 8, 4, 1, 1, 2), (64, 8192, 64, 4, 4, 1, 1, 2),
     (1, 64, 64, 0, 0, 0, 0, 1), (3, 264, 200, 0, 0, 0, 0, 1), (8, 2048, 128, 8, 4, 1, 1, 1),
     (17, 1024, 136, 4, 2, 3, 1, 1), (40, 1024, 72, 4, 4, 2, 1, 1), (64, 512, 128, 4, 2, 2, 1, 1),
     (2, 6144, 64, 4, 4, 1, 1, 1),
