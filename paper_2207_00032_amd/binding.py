@@ -279,7 +279,7 @@ def i8_layout_check(Wl, K, N):
 
 
 def gemm_i8(Wl, sw, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, workspace=None,
-            path=PATH_AUTO, split_k=0, waves=0, depth=0):
+            path=PATH_AUTO, split_k=0, waves=0, depth=0, panels=0):
     """Y = epilogue((quantize(X) @ Wq) * sx * sw + bias) through sbi_gemm_i8.  Returns Y (fp16 [B,N])."""
     import torch
     assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.is_contiguous()
@@ -295,9 +295,9 @@ def gemm_i8(Wl, sw, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=No
     _need_bytes(Wl, i8_layout_bytes(K, N), "laid-out int8 weights")
     if not (sw.is_cuda and sw.dtype == torch.float32 and sw.is_contiguous() and tuple(sw.shape) == (N,)):
         raise ValueError("w_scales: expected a contiguous CUDA float32 tensor of shape (N,)")
-    tune = _tuning(path, split_k, waves, depth)
+    tune = _tuning(path, split_k, waves, depth, panels=panels)
     if workspace is None:
-        need = plan(B, K, N, path, split_k, waves, depth, int8=True)["workspace_bytes"]
+        need = plan(B, K, N, path, split_k, waves, depth, panels=panels, int8=True)["workspace_bytes"]
         workspace = new_workspace(need, X.device) if need else None
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
     st = load().sbi_gemm_i8(_ptr(Wl), _ptr(sw), K, N, _ptr(X), B, _ptr(bias), _ptr(residual), int(epilogue),

@@ -162,7 +162,7 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     // layer-norm in front of the GeMM: matrix-core block kernel only, rows read as 128-bit pieces
     if (ln && (path != SBI_PATH_MFMA || K % kChunkK != 0 || t.panels == 2)) return SBI_ERR_TUNING;
     // INT8: its own matrix-core kernel, rows read as 32-byte pieces; no layer-norm in front (yet)
-    if (i8 && (path != SBI_PATH_MFMA || K % kI8ChunkK != 0 || t.panels == 2 || ln)) return SBI_ERR_TUNING;
+    if (i8 && (path != SBI_PATH_MFMA || K % kI8ChunkK != 0 || (t.panels == 2 && !preq) || ln)) return SBI_ERR_TUNING;
     if (path == SBI_PATH_STREAMK) {
         if (!sk_ok) return SBI_ERR_TUNING;
         return plan_streamk(B, KS * P, P, t, pl);
@@ -184,7 +184,9 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     bool depth_ok = depth == 4 || depth == 8 || (depth == 2 && nw == 4 && path == SBI_PATH_MFMA);
     if (pw == 2) depth_ok = (nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 2);
     if ((nw != 4 && nw != 8) || !depth_ok) return SBI_ERR_TUNING;
-    if ((ln || i8) && !((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))) return SBI_ERR_TUNING;
+    if (ln && !((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))) return SBI_ERR_TUNING;
+    if (i8 && !(pw == 2 ? (nw == 8 && depth == 2) : ((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))))
+        return SBI_ERR_TUNING;
     int S = t.split_k;
     if (S < 0) return SBI_ERR_TUNING;
     if (S == 0) {
@@ -359,7 +361,7 @@ int resident_waves(int mb, int nw, int depth, int pw, bool ln, bool i8, bool pre
     static const int vgpr_ln_w8d4[4] = {150, 172, 180, 204};
     const int* tab = (pw == 2) ? vgpr_w8d2p2 : (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);
     if (ln) tab = (nw == 8) ? vgpr_ln_w8d4 : (depth == 2 ? vgpr_ln_w4d2 : vgpr_ln_w4d4);
-    if (i8 && preq) tab = (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);   // as the fp16 kernel's
+    if (i8 && preq) tab = (pw == 2) ? vgpr_w8d2p2 : (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);   // as the fp16 kernel's
     else if (i8) tab = (nw == 8) ? vgpr_i8_w8d4 : (depth == 2 ? vgpr_i8_w4d2 : vgpr_i8_w4d4);
     const int v = (tab[std::min(std::max(mb, 1), 4) - 1] + 7) / 8 * 8;
     return 4 * std::min(8, 512 / v);
@@ -440,7 +442,8 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
     double best = 0.0;
     for (const auto& shp : shapes) {
         const int nw = shp[0], depth = shp[1], pw = shp[2];
-        if (pw == 2 && (mb < 2 || ln || i8)) continue;
+        // INT8 (from pre-quantised codes at these batch sizes): measured ahead only above 32 rows
+        if (pw == 2 && (mb < 2 || ln || (i8 && mb < 3))) continue;
         const int64_t wd = (int64_t)nw * depth;
         const int64_t red_bytes = (int64_t)nw * 16 * kRedPitch * 4;
         for (int64_t cap : lds_caps) {
@@ -570,15 +573,15 @@ sbi_status launch_block_group(const GemmArgs* a, const Plan* pls, const Plan& to
     if (tot.ln)                       // statistics, then per X buffer B rows plus gamma and beta
         for (int g = 0; g < G; ++g) {
             const int64_t buffers = pls[g].kc >= pls[g].ksps ? 1 : 2;
-            if (tot.lds < kLnStatsBytes + buffers * pls[g].kc * (B + 2) * 64) return SBI_ERR_TUNING;
+            if (tot.lds < kLnStatsBytes + buffers * pls[g].kc * (x_pitch(B) + 2) * 64) return SBI_ERR_TUNING;
         }
     if (tot.i8) {                     // scales through the reduction, then X buffers or the reduction tile
         for (int g = 0; g < G; ++g) {
             const int64_t buffers = pls[g].kc >= pls[g].ksps ? 1 : 2;
-            if (tot.lds < kLnStatsBytes + std::max<int64_t>(buffers * pls[g].kc * B * 64, (int64_t)tot.nw * 16 * kRedPitch * 4))
+            if (tot.lds < kLnStatsBytes + std::max<int64_t>(buffers * pls[g].kc * x_pitch(B) * 64, (int64_t)tot.nw * 16 * kRedPitch * 4))
                 return SBI_ERR_TUNING;
         }
-        return launch_i8(gp, tot.nw, tot.depth, tot.preq, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
+        return launch_i8(gp, tot.nw, tot.depth, tot.pw, tot.preq, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
     }
     return launch_mfma(gp, tot.nw, tot.depth, tot.pw, tot.ln, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
 }

@@ -17,15 +17,15 @@ namespace sbi {
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-template <int MB>
+template <int MB, int PW>
 struct MfmaI8Op {
-    i32x4 acc[kPanelTiles][MB];
+    i32x4 acc[kPanelTiles * PW][MB];
     int xoff[MB];
 
     __device__ __forceinline__ void init(int B, int pitch, int g, int i)
     {
 #pragma unroll
-        for (int t = 0; t < kPanelTiles; ++t)
+        for (int t = 0; t < kPanelTiles * PW; ++t)
 #pragma unroll
             for (int m = 0; m < MB; ++m) acc[t][m] = i32x4{0, 0, 0, 0};
 #pragma unroll
@@ -82,7 +82,9 @@ struct XStageCodes {
 // PREQ: p.X points at int8 codes and p.xstats at the rows' (inv, scale) in global memory, both
 // written by sbi_quantize_rows_kernel right before this launch (larger batches: quantising
 // B rows in every block would cost more than the weight stream).
-template <int MB, int NW, int DEPTH, bool PREQ>
+// PW = 2 (batches above 16, codes from the workspace): a block streams two adjacent panels for the
+// same k-steps, as in the fp16 kernel - one staged X tile and one operand read serve 128 columns.
+template <int MB, int NW, int DEPTH, int PW, bool PREQ>
 __global__ __launch_bounds__(NW * 64) void sbi_i8_kernel(const GroupParams gp)
 {
     constexpr int NT = NW * 64;
@@ -108,58 +110,72 @@ __global__ __launch_bounds__(NW * 64) void sbi_i8_kernel(const GroupParams gp)
         __syncthreads();
     }
 
-    const int panel = bid / p.S;
-    const int split = bid - panel * p.S;
+    const int pgroup = bid / p.S;     // group of PW adjacent panels
+    const int split = bid - pgroup * p.S;
+    const int panel = pgroup * PW;
+    const int npanels = min(PW, p.P - panel);       // the last group of an odd P has one panel
     const int ks0 = split * p.ksps;
     const int ks1 = min(p.KS, ks0 + p.ksps);
+    // a missing second panel streams the first one again; its result is dropped
+    const int64_t pstride = (npanels > 1) ? (int64_t)p.KS * (kPanelTiles * 64) : 0;
 
-    MfmaI8Op<MB> op;
+    MfmaI8Op<MB, PW> op;
     op.init(p.B, p.xpitch, g, i);
     if constexpr (PREQ) {
         XStageCodes<NT, 4> xst;
         xst.init(p);
-        stream_panel<NW, DEPTH, 1, false, staging_passes(MB, DEPTH, false)>(p, xs, xst, op, tid, wave, lane, panel, 0, ks0, ks1);
+        stream_panel<NW, DEPTH, PW, false, staging_passes(MB, DEPTH, false)>(p, xs, xst, op, tid, wave, lane, panel,
+                                                                             pstride, ks0, ks1);
     } else {
         XStageI8<NT, 2> xst;       // two 32-byte reads per thread in flight: NT*32 bytes of LDS per pass
         xst.p_stats = lds_stats;
-        stream_panel<NW, DEPTH, 1, false>(p, xs, xst, op, tid, wave, lane, panel, 0, ks0, ks1);
+        stream_panel<NW, DEPTH, PW, false>(p, xs, xst, op, tid, wave, lane, panel, pstride, ks0, ks1);
     }
 
-    RowOperands<NW> ops[MB];           // bias / residual of all passes, requested ahead of the first barrier
+    RowOperands<NW> ops[PW][MB];       // bias / residual of all passes, requested ahead of the first barrier
 #pragma unroll
-    for (int m = 0; m < MB; ++m) ops[m] = request_row_operands<NW>(p, m, panel, tid, m == 0, ops[0]);
+    for (int q = 0; q < PW; ++q)
 #pragma unroll
-    for (int m = 0; m < MB; ++m) {
-        __syncthreads();               // X buffers / previous pass no longer needed
+        for (int m = 0; m < MB; ++m)
+            ops[q][m] = request_row_operands<NW>(p, m, min(panel + q, p.P - 1), tid, m == 0, ops[q][0]);
 #pragma unroll
-        for (int t = 0; t < kPanelTiles; ++t)
-            *reinterpret_cast<i32x4*>(red + (wave * 16 + i) * kRedPitch + t * kTileN + 4 * g) = op.acc[t][m];
-        __syncthreads();
-        reduce_rows<NW, true>(p, red, m, panel, split, tid, ops[m], stats);
+    for (int q = 0; q < PW; ++q) {
+        if (q < npanels) {
+#pragma unroll
+            for (int m = 0; m < MB; ++m) {
+                __syncthreads();               // X buffers / previous pass no longer needed
+#pragma unroll
+                for (int t = 0; t < kPanelTiles; ++t)
+                    *reinterpret_cast<i32x4*>(red + (wave * 16 + i) * kRedPitch + t * kTileN + 4 * g) =
+                        op.acc[q * kPanelTiles + t][m];
+                __syncthreads();
+                reduce_rows<NW, true>(p, red, m, panel + q, split, tid, ops[q][m], stats);
+            }
+            if (p.S > 1) finish_split_k<NT, true>(p, panel + q, tid, &s_flag, stats);
+        }
     }
-    if (p.S > 1) finish_split_k<NT, true>(p, panel, tid, &s_flag, stats);
 }
 
-template <int MB, int NW, int DEPTH, bool PREQ>
+template <int MB, int NW, int DEPTH, int PW, bool PREQ>
 static int launch_one(const GroupParams& gp, size_t lds, hipStream_t st)
 {
     if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sbi_i8_kernel<MB, NW, DEPTH, PREQ>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sbi_i8_kernel<MB, NW, DEPTH, PW, PREQ>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return (int)e;
     }
-    hipLaunchKernelGGL((sbi_i8_kernel<MB, NW, DEPTH, PREQ>), dim3(gp.first_block[gp.G]), dim3(NW * 64), lds, st, gp);
+    hipLaunchKernelGGL((sbi_i8_kernel<MB, NW, DEPTH, PW, PREQ>), dim3(gp.first_block[gp.G]), dim3(NW * 64), lds, st, gp);
     return (int)hipGetLastError();
 }
 
-template <int NW, int DEPTH, bool PREQ>
+template <int NW, int DEPTH, int PW, bool PREQ>
 static int launch_mb(const GroupParams& gp, size_t lds, hipStream_t st)
 {
     switch ((gp.g[0].B + 15) / 16) {
-        case 1: return launch_one<1, NW, DEPTH, PREQ>(gp, lds, st);
-        case 2: return launch_one<2, NW, DEPTH, PREQ>(gp, lds, st);
-        case 3: return launch_one<3, NW, DEPTH, PREQ>(gp, lds, st);
-        case 4: return launch_one<4, NW, DEPTH, PREQ>(gp, lds, st);
+        case 1: return launch_one<1, NW, DEPTH, PW, PREQ>(gp, lds, st);
+        case 2: return launch_one<2, NW, DEPTH, PW, PREQ>(gp, lds, st);
+        case 3: return launch_one<3, NW, DEPTH, PW, PREQ>(gp, lds, st);
+        case 4: return launch_one<4, NW, DEPTH, PW, PREQ>(gp, lds, st);
     }
     return (int)hipErrorInvalidValue;
 }
@@ -205,9 +221,11 @@ __global__ __launch_bounds__(256) void sbi_quantize_rows_kernel(const QuantRowsP
     }
 }
 
-int launch_i8(const GroupParams& gp, int waves, int depth, bool prequantized, size_t lds_bytes, hipStream_t st)
+int launch_i8(const GroupParams& gp, int waves, int depth, int panels, bool prequantized, size_t lds_bytes, hipStream_t st)
 {
     if (gp.G < 1 || gp.G > kMaxGroup) return (int)hipErrorInvalidValue;
+    if (panels == 2 && !(prequantized && waves == 8 && depth == 2)) return (int)hipErrorInvalidValue;
+    if (panels != 1 && panels != 2) return (int)hipErrorInvalidValue;
     if (prequantized) {
         if (!spread_staging_fits(gp, waves, depth, false)) return (int)hipErrorInvalidValue;
         // gp.g[k].X already points at the codes' place in the workspace: fill it from gp.g[k].X16
@@ -221,14 +239,15 @@ int launch_i8(const GroupParams& gp, int waves, int depth, bool prequantized, si
         q.B = gp.g[0].B;
         hipLaunchKernelGGL(sbi_quantize_rows_kernel, dim3(gp.G * q.B), dim3(256), 0, st, q);
         if (hipGetLastError() != hipSuccess) return (int)hipErrorInvalidValue;
-        if (waves == 4 && depth == 2) return launch_mb<4, 2, true>(gp, lds_bytes, st);
-        if (waves == 4 && depth == 4) return launch_mb<4, 4, true>(gp, lds_bytes, st);
-        if (waves == 8 && depth == 4) return launch_mb<8, 4, true>(gp, lds_bytes, st);
+        if (panels == 2) return launch_mb<8, 2, 2, true>(gp, lds_bytes, st);
+        if (waves == 4 && depth == 2) return launch_mb<4, 2, 1, true>(gp, lds_bytes, st);
+        if (waves == 4 && depth == 4) return launch_mb<4, 4, 1, true>(gp, lds_bytes, st);
+        if (waves == 8 && depth == 4) return launch_mb<8, 4, 1, true>(gp, lds_bytes, st);
         return (int)hipErrorInvalidValue;
     }
-    if (waves == 4 && depth == 2) return launch_mb<4, 2, false>(gp, lds_bytes, st);
-    if (waves == 4 && depth == 4) return launch_mb<4, 4, false>(gp, lds_bytes, st);
-    if (waves == 8 && depth == 4) return launch_mb<8, 4, false>(gp, lds_bytes, st);
+    if (waves == 4 && depth == 2) return launch_mb<4, 2, 1, false>(gp, lds_bytes, st);
+    if (waves == 4 && depth == 4) return launch_mb<4, 4, 1, false>(gp, lds_bytes, st);
+    if (waves == 8 && depth == 4) return launch_mb<8, 4, 1, false>(gp, lds_bytes, st);
     return (int)hipErrorInvalidValue;
 }
 

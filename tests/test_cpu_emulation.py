@@ -43,6 +43,7 @@ GEMM_CASES = [
     (64, 2048, 192, 8, 2, 1, 2, 0), (48, 1100, 128, 8, 2, 1, 2, 0), (40, 1544, 136, 8, 2, 2, 2, 0), (33, 3072, 128, 8, 2, 1, 2, 0),
     # several rounds with the X staging passes spread over the steps of a round (batches above 16)
     (40, 4096, 72, 4, 2, 1, 1, 0), (40, 4096, 72, 4, 4, 1, 1, 1), (40, 4096, 72, 4, 4, 1, 1, 2),
+    (40, 4096, 136, 8, 2, 1, 2, 2), (64, 2048, 128, 8, 2, 2, 2, 2), (24, 1040, 72, 8, 2, 1, 2, 2),
     (24, 4096, 72, 4, 4, 1, 1, 0), (24, 4096, 72, 8, 4, 1, 1, 1), (24, 4100, 72, 4, 4, 1, 1, 0), (24, 4096, 72, 8, 4, 1, 1, 2), (64, 8192, 64, 4, 4, 1, 1, 2),
     (1, 64, 64, 0, 0, 0, 0, 1), (3, 264, 200, 0, 0, 0, 0, 1), (8, 2048, 128, 8, 4, 1, 1, 1),
     (17, 1024, 136, 4, 2, 3, 1, 1), (40, 1024, 72, 4, 4, 2, 1, 1), (64, 512, 128, 4, 2, 2, 1, 1),

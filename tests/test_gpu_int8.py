@@ -94,6 +94,27 @@ def test_int8_gemm_split_k_and_tuning_variants(gpu, B, K, N, waves, depth):
         check(Y.cpu().numpy(), X, Wq, sw, bias, R, "bias_residual", f"B={B} K={K} N={N} S={S} w={waves} d={depth}")
 
 
+@pytest.mark.parametrize("B,K,N", [(17, 4096, 136), (24, 1040, 72), (33, 8192, 200), (48, 2048, 448), (64, 4096, 192)])
+def test_int8_two_panel_blocks(gpu, B, K, N):
+    """Batches above 16: blocks that stream two adjacent panels of int8 weights against codes from
+    the workspace (odd panel counts leave a lone last panel); automatic plan and forced splits."""
+    from paper_2207_00032_amd import binding as sb
+    W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=4, config_id=402)
+    Wl, sw_d, Wq, sw = prepare(gpu, W)
+    Xd, bd, Rd = _dev(X, gpu), _dev(bias, gpu), _dev(R, gpu)
+    ran = 0
+    for S in (0, 1, 2, 5):
+        try:
+            sb.plan(B, K, N, sb.PATH_MFMA, S, 8, 2, panels=2, int8=True)
+        except sb.SbiError:
+            continue
+        for epi in ("bias_gelu", "bias_residual"):
+            Y = sb.gemm_i8(Wl, sw_d, K, N, Xd, bd, Rd, epi, path=sb.PATH_MFMA, split_k=S, waves=8, depth=2, panels=2)
+            check(Y.cpu().numpy(), X, Wq, sw, bias, R, epi, f"2-panel B={B} K={K} N={N} S={S} {epi}")
+            ran += 1
+    assert ran > 0
+
+
 def test_int8_special_rows_and_determinism(gpu):
     """An all-zero activation row (scale 0), a row dominated by one outlier (every other code 0 or
     +-1), exact ties in the code decision, a shared workspace across differently shaped calls."""
