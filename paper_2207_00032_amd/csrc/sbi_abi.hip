@@ -181,7 +181,7 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     if (t.panels == 2 && path != SBI_PATH_MFMA) return SBI_ERR_TUNING;
     if (nw == 0) nw = (B <= 32 && KS >= 32) ? 8 : 4;
     if (depth == 0) depth = (B > 32 || pw == 2) ? 2 : 4;
-    bool depth_ok = depth == 4 || depth == 8 || (depth == 2 && nw == 4 && path == SBI_PATH_MFMA);
+    bool depth_ok = depth == 4 || depth == 8 || (depth == 2 && path == SBI_PATH_MFMA);
     if (pw == 2) depth_ok = (nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 2);
     if ((nw != 4 && nw != 8) || !depth_ok) return SBI_ERR_TUNING;
     if (ln && !((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))) return SBI_ERR_TUNING;
@@ -356,10 +356,11 @@ int resident_waves(int mb, int nw, int depth, int pw, bool ln, bool i8, bool pre
     static const int vgpr_w4d4[4] = {140, 164, 196, 226};
     static const int vgpr_w8d4[4] = {134, 152, 170, 188};
     static const int vgpr_w8d2p2[4] = {150, 184, 210, 244};
+    static const int vgpr_w8d2[4] = {102, 120, 130, 146};
     static const int vgpr_ln_w4d2[4] = {124, 144, 152, 184};
     static const int vgpr_ln_w4d4[4] = {156, 188, 200, 236};
     static const int vgpr_ln_w8d4[4] = {150, 172, 180, 204};
-    const int* tab = (pw == 2) ? vgpr_w8d2p2 : (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);
+    const int* tab = (pw == 2) ? vgpr_w8d2p2 : (nw == 8) ? (depth == 2 ? vgpr_w8d2 : vgpr_w8d4) : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);
     if (ln) tab = (nw == 8) ? vgpr_ln_w8d4 : (depth == 2 ? vgpr_ln_w4d2 : vgpr_ln_w4d4);
     if (i8 && preq) tab = (pw == 2) ? vgpr_w8d2p2 : (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);   // as the fp16 kernel's
     else if (i8) tab = (nw == 8) ? vgpr_i8_w8d4 : (depth == 2 ? vgpr_i8_w4d2 : vgpr_i8_w4d4);
@@ -435,7 +436,11 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
     const bool preq = i8 && B > kI8FusedMaxBatch;
     const Flavour fl = i8 ? (preq ? kInt8Codes : kInt8) : (ln ? kLayerNorm : kPlain);
     // (waves, depth, panels per block) candidates; two-panel blocks only pay off for B > 16
-    const int shapes[4][3] = {{4, 4, 1}, {8, 4, 1}, {4, 2, 1}, {8, 2, 2}};
+    // (ties go to the earlier shape: the measured order at equal modelled cost - the fp16 kernels do
+    // best with the shallow ring, the INT8 kernel with the deep one)
+    const int shapes_f16[5][3] = {{4, 2, 1}, {8, 4, 1}, {4, 4, 1}, {8, 2, 2}, {8, 2, 2}};
+    const int shapes_i8[5][3] = {{4, 4, 1}, {8, 4, 1}, {4, 2, 1}, {8, 2, 2}, {8, 2, 2}};
+    const auto& shapes = i8 ? shapes_i8 : shapes_f16;
 
     int best_nw = 0, best_depth = 0, best_pw = 1;
     int64_t bestT = 0, best_cap = 0;
@@ -493,8 +498,14 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
                 if (i8 && !preq) overhead += (conc == 1 ? 8.0 : 2.0) * (double)(ceil_div(B, 2 * nw) * ceil_div(maxKS, 64));
                 double cost = (double)per_cu_blocks * (stream + overhead) * (busy >= 0.75 ? 1.0 : 0.75 / busy) +
                               partial / kNumCU / 4096.0;
-                const int64_t inflight = conc * nw * depth;
-                if (inflight < 24) cost *= 1.0 + 0.3 * (double)(24 - inflight) / 24.0;
+                // several blocks per CU are several weight streams per CU: on launches of gigabytes that
+                // costs (h=12288 layer, 3.6 GB: one 8-wave block per CU 523 us, two 540 us, three 4-wave
+                // blocks 543 us), on a few hundred megabytes it does not
+                const double gbytes = (double)work * 4096.0 / 1e9;
+                cost *= 1.0 + 0.045 * std::min((double)(conc - 1), 1.2) * std::min(1.0, std::max(0.0, (gbytes - 0.5) / 2.0));
+                // (k-steps in flight on an average CU: a launch of 2.8 blocks per CU leaves some with two)
+                const double inflight = std::min((double)fit, (double)blocks / kNumCU) * nw * depth;
+                if (inflight < 24.0) cost *= 1.0 + 0.3 * (24.0 - inflight) / 24.0;
                 if (slow_stage) cost *= 1.1;
                 if (best_nw == 0 || cost < best) {
                     best = cost; best_nw = nw; best_depth = depth; best_pw = pw; bestT = T; best_cap = cap;

@@ -218,6 +218,7 @@ int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, bool la
         if (waves == 4 && depth == 2) return launch_mb<4, 2, 1, false>(gp, lds_bytes, st);
         if (waves == 4 && depth == 4) return launch_mb<4, 4, 1, false>(gp, lds_bytes, st);
         if (waves == 4 && depth == 8) return launch_mb<4, 8, 1, false>(gp, lds_bytes, st);
+        if (waves == 8 && depth == 2) return launch_mb<8, 2, 1, false>(gp, lds_bytes, st);
         if (waves == 8 && depth == 4) return launch_mb<8, 4, 1, false>(gp, lds_bytes, st);
         if (waves == 8 && depth == 8) return launch_mb<8, 8, 1, false>(gp, lds_bytes, st);
     } else if (panels == 2) {
