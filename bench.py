@@ -50,6 +50,10 @@ def parse_args():
                     const="1:32:128:136,8:32:128:136,64:32:128:136,8:32:128:2048,64:32:128:2048,1:32:128:8192,8:32:128:8192",
                     help="time the single-token attention with a KV cache (sbi_attn_decode) instead of the GeMMs: "
                          "ctx = positions attended to, the new token's included; value = KV-cache streaming GB/s")
+    ap.add_argument("--decoder-layer", type=str, default=None, metavar="B:ctx[,...]", nargs="?", const="1:136,4:136,8:136,8:2048",
+                    help="time one token-generation step of a whole h=4096 layer (32 heads): layer-norm + QKV, attention "
+                         "over the KV cache, attention output + residual, layer-norm + FFN1 + GeLU, FFN2 + residual as five "
+                         "dependent launches replayed from a HIP graph; value = algorithmic bytes of the step / time")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run a few copy-kernel and layer launches and exit (for rocprofv3 --pmc runs)")
     return ap.parse_args()
@@ -173,6 +177,82 @@ def attention_main(args):
         "roofline": roofline, "cpu_baseline": cpu, "parity": parity, "per_call": per_call}))
 
 
+def decoder_main(args):
+    """--decoder-layer: one JSON line; a step is one token-generation step per listed (B, context)."""
+    import numpy as np
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    from paper_2207_00032_amd import decoder
+    from paper_2207_00032_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    sb.load()
+    dev = torch.device("cuda:0")
+    h, heads, f = 4096, 32, 16384
+    d = h // heads
+    cases = [tuple(int(v) for v in item.split(":")) for item in args.decoder_layer.split(",")]
+    Bmax = max(B for B, _ in cases)
+    hw = {}
+    for gi, (name, K, N) in enumerate((("qkv", h, 3 * h), ("out", h, h), ("ffn1", h, f), ("ffn2", f, h))):
+        W, bias, _, _ = wl.make_gemm_inputs(K, N, 1, seed=0, config_id=2, gemm_id=gi)
+        hw["W" + name], hw["b" + name] = torch.from_numpy(W).to(dev), torch.from_numpy(bias).to(dev)
+    g1, be1, x_host = wl.make_layernorm_inputs(h, Bmax, seed=0, config_id=2, gemm_id=0)
+    g2, be2, _ = wl.make_layernorm_inputs(h, Bmax, seed=0, config_id=2, gemm_id=2)
+    g1, be1, g2, be2 = (torch.from_numpy(a).to(dev) for a in (g1, be1, g2, be2))
+    copies = 3                                                    # 3 x 384 MiB of weights: every step streams from HBM
+    layers = [decoder.DecoderLayer(h, heads, hw["Wqkv"], hw["bqkv"], hw["Wout"], hw["bout"], hw["Wffn1"], hw["bffn1"],
+                                   hw["Wffn2"], hw["bffn2"], g1, be1, g2, be2) for _ in range(copies)]
+    del hw["Wqkv"], hw["Wout"], hw["Wffn1"], hw["Wffn2"]
+    weight_bytes = 2 * (3 * h * h + h * h + 2 * h * f)
+    results = []
+    total_bytes = total_sec = 0.0
+    for B, ctx in cases:
+        _, Kc, Vc = wl.make_attention_inputs(B, heads, d, ctx, seed=0, config_id=2)
+        x = torch.from_numpy(np.ascontiguousarray(x_host[:B])).to(dev)
+        states = [layers[c].new_state(B, ctx, dev, torch.from_numpy(Kc).to(dev), torch.from_numpy(Vc).to(dev))
+                  for c in range(copies)]
+        nbytes = weight_bytes + attention_bytes(B, heads, d, ctx) + 2 * B * (3 * h + 4 * h + f) * 2
+
+        def run():
+            for c in range(copies):
+                layers[c].step(x, ctx - 1, states[c])
+
+        run()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                run()
+        torch.cuda.synchronize()
+        reps = max(1, args.steps // copies)
+        us = {}
+        for label, fn in (("graph", graph.replay), ("eager", run)):
+            for _ in range(max(1, args.warmup // copies)):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            us[label] = (time.perf_counter() - t0) / (reps * copies) * 1e6
+        total_bytes += nbytes
+        total_sec += us["graph"] * 1e-6
+        results.append({"B": B, "ctx": ctx, "us_per_layer_step_graph": round(us["graph"], 2),
+                        "us_per_layer_step_eager": round(us["eager"], 2), "GBps": round(nbytes / us["graph"] / 1e3, 1),
+                        "bytes": nbytes})
+        del states
+        torch.cuda.empty_cache()
+    print(json.dumps({
+        "metric": "HBM GB/s of a whole layer's token-generation step (algorithmic bytes of its five dependent launches / time)",
+        "value": round(total_bytes / total_sec / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(total_sec * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "h=4096 layer (32 heads of 128, FFN 16384), one generated token per step, "
+                               "(B:context) " + args.decoder_layer + ", HIP-graph replay, 3 weight copies"},
+        "roofline": None, "cpu_baseline": None, "per_case": results}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -181,6 +261,8 @@ def main():
         sys.exit(2)
     if args.attention:
         return attention_main(args)
+    if args.decoder_layer:
+        return decoder_main(args)
 
     import numpy as np
     import torch

@@ -1,0 +1,98 @@
+"""The token-generation step of a whole layer (paper Sec. III-D: the four fused regions in sequence)
+through paper_2207_00032_amd.decoder: every stage against the oracle fed with the GPU's own
+previous stage (the per-call parity bar), the whole chain against the oracle's own chain (errors of
+five roundings to fp16 compound: a looser, stated bound), and a HIP-graph replay against eager."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2207_00032_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+EPS = 1e-5
+
+
+def _make(gpu, h, heads, f, B, S, seed):
+    import torch
+    from paper_2207_00032_amd import decoder
+    host = {}
+    for gi, (name, K, N) in enumerate((("qkv", h, 3 * h), ("out", h, h), ("ffn1", h, f), ("ffn2", f, h))):
+        W, bias, _, _ = wl.make_gemm_inputs(K, N, 1, seed=seed, config_id=700, gemm_id=gi)
+        host["W" + name], host["b" + name] = W, bias
+    host["g1"], host["be1"], x = wl.make_layernorm_inputs(h, B, seed=seed, config_id=700, gemm_id=0)
+    host["g2"], host["be2"], _ = wl.make_layernorm_inputs(h, B, seed=seed, config_id=700, gemm_id=2)
+    _, Kc, Vc = wl.make_attention_inputs(B, heads, h // heads, S, seed=seed, config_id=700)
+    d = {k: torch.from_numpy(v).to(gpu) for k, v in host.items()}
+    layer = decoder.DecoderLayer(h, heads, d["Wqkv"], d["bqkv"], d["Wout"], d["bout"], d["Wffn1"], d["bffn1"],
+                                 d["Wffn2"], d["bffn2"], d["g1"], d["be1"], d["g2"], d["be2"], EPS)
+    return layer, host, x, Kc, Vc
+
+
+def _oracle_step(hw, x, Kc, Vc, pos):
+    qkv = orc.gemm(orc.layernorm(x, hw["g1"], hw["be1"], EPS), hw["Wqkv"], hw["bqkv"], None, epi=orc.EPI_BIAS)
+    B = x.shape[0]
+    H, d = Kc.shape[1], Kc.shape[3]
+    ctx, K2, V2 = orc.attn_decode(qkv.reshape(B, 3, H, d), Kc, Vc, pos)
+    x2 = orc.gemm(ctx, hw["Wout"], hw["bout"], x, epi=orc.EPI_BIAS | orc.EPI_RES)
+    f = orc.gemm(orc.layernorm(x2, hw["g2"], hw["be2"], EPS), hw["Wffn1"], hw["bffn1"], None, epi=orc.EPI_BIAS | orc.EPI_GELU)
+    y = orc.gemm(f, hw["Wffn2"], hw["bffn2"], x2, epi=orc.EPI_BIAS | orc.EPI_RES)
+    return y, K2, V2
+
+
+@pytest.mark.parametrize("h,heads,f,B,S,pos", [(512, 4, 2048, 3, 200, 150), (1024, 16, 4096, 8, 700, 640), (256, 2, 1024, 1, 8, 0)])
+def test_decoder_step_stage_by_stage_and_end_to_end(gpu, h, heads, f, B, S, pos):
+    import torch
+    layer, hw, x, Kc, Vc = _make(gpu, h, heads, f, B, S, seed=h + B)
+    d = h // heads
+    st = layer.new_state(B, S, gpu, torch.from_numpy(Kc).to(gpu), torch.from_numpy(Vc).to(gpu))
+    y = layer.step(torch.from_numpy(x).to(gpu), pos, st)
+    torch.cuda.synchronize()
+    g = {k: getattr(st, k).cpu().numpy() for k in ("qkv", "ctx", "x2", "f", "y")}
+    stages = [
+        ("qkv", g["qkv"].reshape(B, 3 * h), orc.gemm(orc.layernorm(x, hw["g1"], hw["be1"], EPS), hw["Wqkv"], hw["bqkv"], None, epi=orc.EPI_BIAS)),
+        ("attention", g["ctx"], orc.attn_decode(g["qkv"], Kc, Vc, pos)[0]),
+        ("attn-out", g["x2"], orc.gemm(g["ctx"], hw["Wout"], hw["bout"], x, epi=orc.EPI_BIAS | orc.EPI_RES)),
+        ("ffn1", g["f"], orc.gemm(orc.layernorm(g["x2"], hw["g2"], hw["be2"], EPS), hw["Wffn1"], hw["bffn1"], None,
+                                  epi=orc.EPI_BIAS | orc.EPI_GELU)),
+        ("ffn2", g["y"], orc.gemm(g["f"], hw["Wffn2"], hw["bffn2"], g["x2"], epi=orc.EPI_BIAS | orc.EPI_RES)),
+    ]
+    for name, got, want in stages:
+        ok, rep = orc.check_close(got, want, ulps=2, abs_tol=1e-3)
+        assert ok, (name, rep)
+    _, K2, V2 = orc.attn_decode(g["qkv"], Kc, Vc, pos)
+    assert np.array_equal(st.k_cache.cpu().numpy().view(np.uint16), K2.view(np.uint16))
+    assert np.array_equal(st.v_cache.cpu().numpy().view(np.uint16), V2.view(np.uint16))
+    # the whole chain against the oracle's own chain: five fp16 roundings in sequence, each stage's
+    # 1-ulp differences amplified by at most the next stage's gain
+    want, _, _ = _oracle_step(hw, x, Kc, Vc, pos)
+    ok, rep = orc.check_close(y.cpu().numpy(), want, ulps=8, abs_tol=8e-3)
+    assert ok, ("end to end", rep)
+
+
+def test_decoder_steps_under_graph_replay(gpu):
+    """Three generated tokens, each step replayed from one captured graph per position, with eager
+    work in between; every replay must give the eager bits."""
+    import torch
+    h, heads, f, B, S = 512, 4, 2048, 2, 64
+    layer, hw, x, Kc, Vc = _make(gpu, h, heads, f, B, S, seed=9)
+    xd = torch.from_numpy(x).to(gpu)
+    st_e = layer.new_state(B, S, gpu, torch.from_numpy(Kc).to(gpu), torch.from_numpy(Vc).to(gpu))
+    st_g = layer.new_state(B, S, gpu, torch.from_numpy(Kc).to(gpu), torch.from_numpy(Vc).to(gpu))
+    for pos in (40, 41, 42):
+        want = layer.step(xd, pos, st_e).clone()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            layer.step(xd, pos, st_g)                      # warm-up outside the capture
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                layer.step(xd, pos, st_g)
+        for _ in range(3):
+            st_g.y.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(st_g.y.view(torch.int16), want.view(torch.int16))
+            (st_g.y.float() * 2).sum().item()              # unrelated eager work between replays
+        assert torch.equal(st_g.k_cache.view(torch.int16), st_e.k_cache.view(torch.int16))
+        xd = want                                          # the next token's input: this step's output
