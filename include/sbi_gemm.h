@@ -73,15 +73,17 @@ typedef struct sbi_tuning {
     int32_t path;    /* sbi_path */
     int32_t split_k; /* blocks that share one 64-column panel's K range (STREAM / MFMA paths) */
     int32_t waves;   /* wavefronts per block: 4 or 8 */
-    int32_t depth;   /* k-steps of W each wavefront keeps in flight: 4 or 8 */
+    int32_t depth;   /* k-steps of W each wavefront keeps in flight: 2 (MFMA path), 4 or 8 */
     int32_t blocks;  /* STREAMK path: upper bound on the number of thread blocks */
     int32_t panels;  /* MFMA path: 64-column panels per block, 1 or 2 (2: X is staged and read once
                         for 128 columns; for larger batches) */
     int32_t layernorm; /* sbi_gemm_plan: nonzero plans the launch sbi_gemm_ln makes (layer-norm fused
                           in front: MFMA path, one panel per block, K % 8 == 0, (waves, depth) one of
                           (4,2), (4,4), (8,4)); sbi_gemm_ex rejects it, sbi_gemm_ln implies it */
-    int32_t int8;      /* sbi_gemm_plan: nonzero plans the launch sbi_gemm_i8 makes (same restrictions,
-                          K % 16 == 0, not together with layernorm); sbi_gemm_i8 implies it */
+    int32_t int8;      /* sbi_gemm_plan: nonzero plans the launch sbi_gemm_i8 makes (MFMA path, K % 16 == 0,
+                          not together with layernorm; (waves, depth) one of (4,2), (4,4), (8,4) with one
+                          panel per block, or (8,2) with two panels per block for B > 8);
+                          sbi_gemm_i8 implies it */
 } sbi_tuning;
 
 /* What the dispatcher decided for a problem (for reports and tests). */
@@ -235,9 +237,11 @@ sbi_status sbi_gemm_moments(const void* W_laid_out, int64_t K, int64_t N,
  *     code = clamp(rint(v * inv), -127, 127)                            (ties to even)
  *     Y[b,n] = epilogue( (sum_k Xq[b,k] * Wq[k,n]) * sx[b] * sw[n] + bias[n] )
  *
- * The integer sum is exact (int32; |sum| <= 127^2 K); the activations are quantised inside the
- * kernel (every block finds the rows' maxima itself), so X, bias, residual and Y are fp16 as in
- * sbi_gemm.  Half the weight bytes of the fp16 path are streamed.
+ * The integer sum is exact (int32; |sum| <= 127^2 K); the activations are quantised by the call
+ * itself (up to B = 8 every block of the GeMM kernel finds the rows' maxima and quantises what it
+ * stages; above that a kernel of its own writes codes and row scales to the workspace first), so
+ * X, bias, residual and Y are fp16 as in sbi_gemm.  Half the weight bytes of the fp16 path are
+ * streamed.
  *
  * sbi_gemm_i8_quantize_weights: W fp16 [K,N] row-major (device) -> codes Wq int8 [K,N] row-major
  *   and scales sw binary32 [N] (both device, caller-owned).  Optional: codes and scales that were
