@@ -485,7 +485,8 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
                 // a start/finish overhead; measured on MI355X (h=4096 layer, 512 MiB single GeMMs):
                 //   overhead about 9 k-steps of streaming time per block, 4.5 more when a block has the
                 //   CU to itself (nothing hides its ramp-up and epilogue), next to nothing per further
-                //   X chunk, about 4 per pass of the layer-norm statistics (16 when nothing hides it);
+                //   X chunk, about 2 per pass of the layer-norm statistics plus 4 per launch (10 when a
+                //   block has its CU to itself);
                 //   X staged per block rivals the weight stream once B/(64 pw) exceeds about 0.2;
                 //   fewer than 24 k-steps in flight per CU no longer cover the memory latency.
                 const int64_t per_cu_blocks = ceil_div(blocks, kNumCU);
@@ -494,10 +495,13 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
                 const double x_ratio = (double)B / (64.0 * pw);
                 const double stream = (double)work / (double)blocks * (1.0 + 0.6 * std::max(0.0, x_ratio - 0.2));
                 double overhead = 9.0 + 0.15 * (double)(chunks - 1) + (conc == 1 ? 4.5 : 0.0);
-                if (ln) overhead += (conc == 1 ? 16.0 : 4.0) * (double)(ceil_div(B, 2 * nw) * ceil_div(maxKS, 128));
+                // layer-norm statistics: what a block spends on them is absorbed by the other CUs' streams
+                // except at the start of the launch, where every block computes them at once
+                const double ln_passes = ln ? (double)(ceil_div(B, 2 * nw) * ceil_div(maxKS, 128)) : 0.0;
+                overhead += 2.0 * ln_passes;
                 if (i8 && !preq) overhead += (conc == 1 ? 8.0 : 2.0) * (double)(ceil_div(B, 2 * nw) * ceil_div(maxKS, 64));
                 double cost = (double)per_cu_blocks * (stream + overhead) * (busy >= 0.75 ? 1.0 : 0.75 / busy) +
-                              partial / kNumCU / 4096.0;
+                              partial / kNumCU / 4096.0 + (conc == 1 ? 10.0 : 4.0) * ln_passes;
                 // several blocks per CU are several weight streams per CU: on launches of gigabytes that
                 // costs (h=12288 layer, 3.6 GB: one 8-wave block per CU 523 us, two 540 us, three 4-wave
                 // blocks 543 us), on a few hundred megabytes it does not
