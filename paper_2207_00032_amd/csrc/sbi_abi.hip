@@ -112,6 +112,13 @@ inline int64_t x_pitch(int64_t B) { return B | 1; }
 constexpr int64_t kI8FusedMaxBatch = 8;
 inline int64_t xq_bytes_of(int64_t B, int64_t K) { return round_up(B * K, 256) + round_up(B * 8, 256); }
 
+// k-steps a block consumes per round of its rings.  (8 waves, depth 4, two panels) is the shape whose
+// waves form two groups of four, one panel each: a round is 16 k-steps there.
+inline int64_t round_ksteps(int nw, int depth, int pw)
+{
+    return (pw == 2 && nw == 8 && depth == 4) ? 16 : (int64_t)nw * depth;
+}
+
 bool chunking(int64_t B, int64_t ksps, int64_t wd, int nw, int64_t cap, int64_t red_bytes,
               int64_t& kc, int64_t& lds, Flavour fl = kPlain)
 {
@@ -182,7 +189,7 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     if (nw == 0) nw = (B <= 32 && KS >= 32) ? 8 : 4;
     if (depth == 0) depth = (B > 32 || pw == 2) ? 2 : 4;
     bool depth_ok = depth == 4 || depth == 8 || (depth == 2 && path == SBI_PATH_MFMA);
-    if (pw == 2) depth_ok = (nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 2);
+    if (pw == 2) depth_ok = (nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && (depth == 2 || (depth == 4 && B > 16 && !i8)));
     if ((nw != 4 && nw != 8) || !depth_ok) return SBI_ERR_TUNING;
     if (ln && !((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))) return SBI_ERR_TUNING;
     if (i8 && !(pw == 2 ? (nw == 8 && depth == 2) : ((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))))
@@ -205,7 +212,7 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     const int64_t PG = ceil_div(P, pw);                          // panel groups = blocks per split
     if (PG * S > (int64_t)0x7fffffff) return SBI_ERR_SHAPE;
 
-    const int64_t wd = (int64_t)nw * depth;
+    const int64_t wd = round_ksteps(nw, depth, pw);
     int64_t kc = 0, lds = 0;
     if (!chunking(B, ksps, wd, nw, (pw == 2 || ln || i8) ? kMaxLdsWide : kMaxLds, (int64_t)nw * 16 * kRedPitch * 4,
                   kc, lds, fl))
@@ -357,10 +364,11 @@ int resident_waves(int mb, int nw, int depth, int pw, bool ln, bool i8, bool pre
     static const int vgpr_w8d4[4] = {134, 152, 170, 188};
     static const int vgpr_w8d2p2[4] = {150, 184, 210, 244};
     static const int vgpr_w8d2[4] = {102, 120, 130, 146};
+    static const int vgpr_w8d4p2[4] = {152, 152, 180, 212};     // two wave groups, one panel each (batches above 16)
     static const int vgpr_ln_w4d2[4] = {124, 144, 152, 184};
     static const int vgpr_ln_w4d4[4] = {156, 188, 200, 236};
     static const int vgpr_ln_w8d4[4] = {150, 172, 180, 204};
-    const int* tab = (pw == 2) ? vgpr_w8d2p2 : (nw == 8) ? (depth == 2 ? vgpr_w8d2 : vgpr_w8d4) : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);
+    const int* tab = (pw == 2) ? (depth == 4 && nw == 8 ? vgpr_w8d4p2 : vgpr_w8d2p2) : (nw == 8) ? (depth == 2 ? vgpr_w8d2 : vgpr_w8d4) : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);
     if (ln) tab = (nw == 8) ? vgpr_ln_w8d4 : (depth == 2 ? vgpr_ln_w4d2 : vgpr_ln_w4d4);
     if (i8 && preq) tab = (pw == 2) ? vgpr_w8d2p2 : (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);   // as the fp16 kernel's
     else if (i8) tab = (nw == 8) ? vgpr_i8_w8d4 : (depth == 2 ? vgpr_i8_w4d2 : vgpr_i8_w4d4);
@@ -438,7 +446,7 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
     // (waves, depth, panels per block) candidates; two-panel blocks only pay off for B > 16
     // (ties go to the earlier shape: the measured order at equal modelled cost - the fp16 kernels do
     // best with the shallow ring, the INT8 kernel with the deep one)
-    const int shapes_f16[5][3] = {{4, 2, 1}, {8, 4, 1}, {4, 4, 1}, {8, 2, 2}, {8, 2, 2}};
+    const int shapes_f16[5][3] = {{4, 2, 1}, {8, 4, 1}, {4, 4, 1}, {8, 4, 2}, {8, 2, 2}};   // (8, 4, 2): two wave groups
     const int shapes_i8[5][3] = {{4, 4, 1}, {8, 4, 1}, {4, 2, 1}, {8, 2, 2}, {8, 2, 2}};
     const auto& shapes = i8 ? shapes_i8 : shapes_f16;
 
@@ -449,7 +457,7 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
         const int nw = shp[0], depth = shp[1], pw = shp[2];
         // INT8 (from pre-quantised codes at these batch sizes): measured ahead only above 32 rows
         if (pw == 2 && (mb < 2 || ln || (i8 && mb < 3))) continue;
-        const int64_t wd = (int64_t)nw * depth;
+        const int64_t wd = round_ksteps(nw, depth, pw);
         const int64_t red_bytes = (int64_t)nw * 16 * kRedPitch * 4;
         for (int64_t cap : lds_caps) {
             // the wide budget belongs to two-panel blocks, and to layer-norm blocks (their statistics
@@ -487,20 +495,31 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
                 //   CU to itself (nothing hides its ramp-up and epilogue), next to nothing per further
                 //   X chunk, about 2 per pass of the layer-norm statistics plus 4 per launch (10 when a
                 //   block has its CU to itself);
-                //   X staged per block rivals the weight stream once B/(64 pw) exceeds about 0.2;
+                //   X staged per block rivals the weight stream once B/(64 pw) exceeds about 0.2, and steeply
+                //   so beyond 0.75;
                 //   fewer than 24 k-steps in flight per CU no longer cover the memory latency.
                 const int64_t per_cu_blocks = ceil_div(blocks, kNumCU);
                 const int64_t conc = std::min<int64_t>(fit, per_cu_blocks);              // concurrent blocks on a CU
                 const double busy = (double)std::min<int64_t>(blocks, kNumCU) / kNumCU;
                 const double x_ratio = (double)B / (64.0 * pw);
-                const double stream = (double)work / (double)blocks * (1.0 + 0.6 * std::max(0.0, x_ratio - 0.2));
+                const double stream = (double)work / (double)blocks *
+                                      (1.0 + 0.6 * std::max(0.0, x_ratio - 0.2) + 1.4 * std::max(0.0, x_ratio - 0.75));
                 double overhead = 9.0 + 0.15 * (double)(chunks - 1) + (conc == 1 ? 4.5 : 0.0);
+                // a block of more than 16 rows that has its CU to itself: two staging passes before its first
+                // k-step and a reduction of mb (x pw) passes after its last, none of it hidden
+                // (h=4096 layer, 64 k-steps x 2 panels per block: 67 / 83 / 96 k-steps at B = 32 / 48 / 64)
+                if (conc == 1 && mb >= 2) overhead = 30.0 + 16.0 * mb + 0.15 * (double)(chunks - 1);
                 // layer-norm statistics: what a block spends on them is absorbed by the other CUs' streams
                 // except at the start of the launch, where every block computes them at once
                 const double ln_passes = ln ? (double)(ceil_div(B, 2 * nw) * ceil_div(maxKS, 128)) : 0.0;
                 overhead += 2.0 * ln_passes;
                 if (i8 && !preq) overhead += (conc == 1 ? 8.0 : 2.0) * (double)(ceil_div(B, 2 * nw) * ceil_div(maxKS, 64));
-                double cost = (double)per_cu_blocks * (stream + overhead) * (busy >= 0.75 ? 1.0 : 0.75 / busy) +
+                // Long single-resident blocks of large batches (384 blocks on 256 CUs): the CUs that hold
+                // fewer blocks than the busiest one leave it more of the bandwidth - halfway between the
+                // busiest CU's count and the average (h=4096 layer at B = 64: 384 blocks 90 us, 768 blocks 107 us)
+                const double eff_blocks = (conc == 1 && mb >= 2)
+                    ? 0.5 * ((double)per_cu_blocks + std::max(1.0, (double)blocks / kNumCU)) : (double)per_cu_blocks;
+                double cost = eff_blocks * (stream + overhead) * (busy >= 0.75 ? 1.0 : 0.75 / busy) +
                               partial / kNumCU / 4096.0 + (conc == 1 ? 10.0 : 4.0) * ln_passes;
                 // several blocks per CU are several weight streams per CU: on launches of gigabytes that
                 // costs (h=12288 layer, 3.6 GB: one 8-wave block per CU 523 us, two 540 us, three 4-wave
@@ -527,14 +546,14 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
             for (int g = 0; g < G; ++g) {
                 const int64_t S = ceil_div(KS[g], bestT), ksps = ceil_div(KS[g], S);
                 int64_t kc = 0, l = 0;
-                if (!chunking(B, ksps, (int64_t)a * b, a, cap, (int64_t)a * 16 * kRedPitch * 4, kc, l, fl)) return SBI_ERR_TUNING;
+                if (!chunking(B, ksps, round_ksteps(a, b, c), a, cap, (int64_t)a * 16 * kRedPitch * 4, kc, l, fl)) return SBI_ERR_TUNING;
             }
         }
     }
 #endif
     if (best_nw == 0) return SBI_ERR_SHAPE;
     const int nw = best_nw, depth = best_depth, pw = best_pw;
-    const int64_t wd = (int64_t)nw * depth;
+    const int64_t wd = round_ksteps(nw, depth, pw);
     int64_t grid = 0, partial_bytes = 0, lds = 0;
     bool any_split = false;
     for (int g = 0; g < G; ++g) {

@@ -418,10 +418,12 @@ __device__ __forceinline__ void load_step(u32x4 (&slot)[kPanelTiles * PW], const
 // staging_passes() gives XP for a kernel shape: the passes the largest batch of its MB needs,
 // rounded up to a divisor of DEPTH (1, i.e. everything at the chunk's end, if there are more
 // passes than steps, and for MB = 1, where chunks may be longer than a round).
-__host__ __device__ constexpr int staging_passes(int mb, int depth, bool ln)
+// `wg` = wave groups a block's waves are divided into (each streams its own panel, so a round is
+// 1/wg as many k-steps for the same number of staging threads).
+__host__ __device__ constexpr int staging_passes(int mb, int depth, bool ln, int wg = 1)
 {
     if (mb < 2) return 1;
-    const int need = (depth * (16 * mb + (ln ? 2 : 0)) + 63) / 64;     // rows * RS * 4 pieces over NT * 4 per pass
+    const int need = (depth * (16 * mb + (ln ? 2 : 0)) + 64 * wg - 1) / (64 * wg);   // rows * RS * 4 pieces over NT * 4 per pass
     for (int xp = 1; xp <= depth; ++xp)
         if (depth % xp == 0 && xp >= need) return xp;
     return 1;
@@ -429,13 +431,13 @@ __host__ __device__ constexpr int staging_passes(int mb, int depth, bool ln)
 
 // Host-side check of what spread staging assumes of every problem of a launch: a chunk is exactly
 // one round of k-steps and no longer than XP passes of the block.
-inline bool spread_staging_fits(const GroupParams& gp, int waves, int depth, bool layernorm)
+inline bool spread_staging_fits(const GroupParams& gp, int waves, int depth, bool layernorm, int wg = 1)
 {
-    const int xp = staging_passes((gp.g[0].B + 15) / 16, depth, layernorm);
+    const int xp = staging_passes((gp.g[0].B + 15) / 16, depth, layernorm, wg);
     if (xp == 1) return true;
     for (int g = 0; g < gp.G; ++g) {
         const int rows = gp.g[g].B + ((layernorm && gp.g[g].ln) ? 2 : 0);
-        if (gp.g[g].kc != waves * depth || gp.g[g].kc * 4 * rows > xp * waves * 64 * 4) return false;
+        if (gp.g[g].kc != waves / wg * depth || gp.g[g].kc * 4 * rows > xp * waves * 64 * 4) return false;
     }
     return true;
 }

@@ -175,6 +175,88 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
 #endif
 }
 
+// Two-panel blocks for the largest batches, second form: the block's eight waves are two groups of
+// four, each group streaming ONE of the two panels (its four waves share that panel's k-steps),
+// both reading the same staged X tile.  Against the form above (every wave streams both panels) a
+// wave carries half the accumulators, so the ring can be four deep, and the reduction at the end of
+// the block is four-way instead of eight-way and runs for both panels side by side: half the LDS
+// traffic, half the additions, half the barriers - the part of a block that grows with the batch.
+template <int MB, int DEPTH>
+__global__ __launch_bounds__(512) void sbi_mfma_wg_kernel(const GroupParams gp)
+{
+    constexpr int NT = 512, GW = 4;   // threads per block, waves per group
+    int gi = 0;
+    while (gi + 1 < gp.G && (int)blockIdx.x >= gp.first_block[gi + 1]) ++gi;
+    const GemmParams& p = gp.g[gi];
+    const int bid = (int)blockIdx.x - gp.first_block[gi];
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    u32x4* xs  = reinterpret_cast<u32x4*>(smem_raw);
+    __shared__ int s_flag;
+
+    const int tid  = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave / GW, kwave = wave - grp * GW;
+    const int g = lane >> 4;
+    const int i = lane & 15;
+
+    const int pgroup = bid / p.S;
+    const int split = bid - pgroup * p.S;
+    const int panel0 = pgroup * 2;
+    const int npanels = min(2, p.P - panel0);
+    const int panel = panel0 + min(grp, npanels - 1);   // a missing second panel: its group streams the first again, result dropped
+    const int ks0 = split * p.ksps;
+    const int ks1 = min(p.KS, ks0 + p.ksps);
+
+    MfmaOp<MB, 1, false> op;
+    op.init(p, nullptr, g, i);
+    XStage<NT, 4, false> xst;
+    stream_panel<GW, DEPTH, 1, false, staging_passes(MB, DEPTH, false, 2)>(p, xs, xst, op, tid, kwave, lane, panel, 0,
+                                                                            ks0, ks1);
+
+    float* red = reinterpret_cast<float*>(smem_raw) + grp * (GW * 16 * kRedPitch);
+    const int gtid = tid & (GW * 64 - 1);
+    RowOperands<GW> ops[MB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m) ops[m] = request_row_operands<GW>(p, m, panel, gtid, m == 0, ops[0]);
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        __syncthreads();               // X tile / previous pass no longer needed
+#pragma unroll
+        for (int t = 0; t < kPanelTiles; ++t)
+            *reinterpret_cast<floatx4*>(red + (kwave * 16 + i) * kRedPitch + t * kTileN + 4 * g) = op.acc[t][m];
+        __syncthreads();
+        if (grp < npanels) reduce_rows<GW>(p, red, m, panel, split, gtid, ops[m]);
+    }
+    if (p.S > 1) {
+        for (int q = 0; q < npanels; ++q) finish_split_k<NT>(p, panel0 + q, tid, &s_flag);
+    }
+}
+
+template <int MB, int DEPTH>
+static int launch_wg_one(const GroupParams& gp, size_t lds, hipStream_t st)
+{
+    if (lds > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sbi_mfma_wg_kernel<MB, DEPTH>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return (int)e;
+    }
+    hipLaunchKernelGGL((sbi_mfma_wg_kernel<MB, DEPTH>), dim3(gp.first_block[gp.G]), dim3(512), lds, st, gp);
+    return (int)hipGetLastError();
+}
+
+static int launch_wg(const GroupParams& gp, size_t lds, hipStream_t st)
+{
+    if (!spread_staging_fits(gp, 8, 4, false, 2)) return (int)hipErrorInvalidValue;
+    if (lds < 2 * 4 * 16 * kRedPitch * sizeof(float)) return (int)hipErrorInvalidValue;   // two groups' reduction tiles
+    switch ((gp.g[0].B + 15) / 16) {
+        case 2: return launch_wg_one<2, 4>(gp, lds, st);
+        case 3: return launch_wg_one<3, 4>(gp, lds, st);
+        case 4: return launch_wg_one<4, 4>(gp, lds, st);
+    }
+    return (int)hipErrorInvalidValue;
+}
+
 template <int MB, int NW, int DEPTH, int PW, bool LN>
 static int launch_one(const GroupParams& gp, size_t lds, hipStream_t st)
 {
@@ -206,7 +288,7 @@ int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, bool la
                 hipStream_t st)
 {
     if (gp.G < 1 || gp.G > kMaxGroup) return (int)hipErrorInvalidValue;
-    if (!spread_staging_fits(gp, waves, depth, layernorm)) return (int)hipErrorInvalidValue;
+    if (!(panels == 2 && waves == 8 && depth == 4) && !spread_staging_fits(gp, waves, depth, layernorm)) return (int)hipErrorInvalidValue;
     if (layernorm) {                   // layer-norm variants exist for the one-panel shapes the dispatcher uses
         if (panels != 1) return (int)hipErrorInvalidValue;
         if (waves == 4 && depth == 2) return launch_mb<4, 2, 1, true>(gp, lds_bytes, st);
@@ -222,6 +304,7 @@ int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, bool la
         if (waves == 8 && depth == 4) return launch_mb<8, 4, 1, false>(gp, lds_bytes, st);
         if (waves == 8 && depth == 8) return launch_mb<8, 8, 1, false>(gp, lds_bytes, st);
     } else if (panels == 2) {
+        if (waves == 8 && depth == 4) return launch_wg(gp, lds_bytes, st);      // two wave groups, one panel each
         if (waves == 4 && depth == 2) return launch_mb<4, 2, 2, false>(gp, lds_bytes, st);
         if (waves == 4 && depth == 4) return launch_mb<4, 4, 2, false>(gp, lds_bytes, st);
         if (waves == 8 && depth == 2) return launch_mb<8, 2, 2, false>(gp, lds_bytes, st);

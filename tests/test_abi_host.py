@@ -82,7 +82,9 @@ def test_plan_invariants(B, K, N):
         pw = pl["panels"]
         assert pw in (1, 2) and (pw == 1 or B > 16)
         assert pl["grid"] == -(-P // pw) * S
-        assert kc % (pl["waves"] * pl["depth"]) == 0 and kc >= pl["waves"] * pl["depth"]
+        # k-steps per round: waves x depth, except the two-wave-group shape (8 waves, depth 4, 2 panels)
+        rnd = 16 if (pw, pl["waves"], pl["depth"]) == (2, 8, 4) else pl["waves"] * pl["depth"]
+        assert kc % rnd == 0 and kc >= rnd
         buffers = 1 if kc >= ksps else 2                         # X is double-buffered when chunked
         assert pl["lds_bytes"] <= (144 if pw == 2 else 72) * 1024 and pl["lds_bytes"] >= buffers * kc * (B | 1) * 64
         if S == 1:

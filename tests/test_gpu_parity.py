@@ -130,7 +130,7 @@ def test_two_panel_blocks(gpu, B, K, N):
     W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=7, config_id=105)
     Wl = None
     ran = 0
-    for waves, depth in ((4, 2), (4, 4), (8, 2)):
+    for waves, depth in ((4, 2), (4, 4), (8, 2), (8, 4)):      # (8, 4): two wave groups, one panel each (B > 16)
         for S in (1, 2, 5):
             try:
                 sb.plan(B, K, N, sb.PATH_MFMA, S, waves, depth, panels=2)
