@@ -189,10 +189,10 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     if (nw == 0) nw = (B <= 32 && KS >= 32) ? 8 : 4;
     if (depth == 0) depth = (B > 32 || pw == 2) ? 2 : 4;
     bool depth_ok = depth == 4 || depth == 8 || (depth == 2 && path == SBI_PATH_MFMA);
-    if (pw == 2) depth_ok = (nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && (depth == 2 || (depth == 4 && B > 16 && !i8)));
+    if (pw == 2) depth_ok = (nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && (depth == 2 || (depth == 4 && B > 16)));
     if ((nw != 4 && nw != 8) || !depth_ok) return SBI_ERR_TUNING;
     if (ln && !((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))) return SBI_ERR_TUNING;
-    if (i8 && !(pw == 2 ? (nw == 8 && depth == 2) : ((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))))
+    if (i8 && !(pw == 2 ? (nw == 8 && (depth == 2 || depth == 4)) : ((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))))
         return SBI_ERR_TUNING;
     int S = t.split_k;
     if (S < 0) return SBI_ERR_TUNING;
@@ -370,7 +370,7 @@ int resident_waves(int mb, int nw, int depth, int pw, bool ln, bool i8, bool pre
     static const int vgpr_ln_w8d4[4] = {150, 172, 180, 204};
     const int* tab = (pw == 2) ? (depth == 4 && nw == 8 ? vgpr_w8d4p2 : vgpr_w8d2p2) : (nw == 8) ? (depth == 2 ? vgpr_w8d2 : vgpr_w8d4) : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);
     if (ln) tab = (nw == 8) ? vgpr_ln_w8d4 : (depth == 2 ? vgpr_ln_w4d2 : vgpr_ln_w4d4);
-    if (i8 && preq) tab = (pw == 2) ? vgpr_w8d2p2 : (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);   // as the fp16 kernel's
+    if (i8 && preq) tab = (pw == 2) ? (depth == 4 ? vgpr_w8d4p2 : vgpr_w8d2p2) : (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);   // as the fp16 kernel's
     else if (i8) tab = (nw == 8) ? vgpr_i8_w8d4 : (depth == 2 ? vgpr_i8_w4d2 : vgpr_i8_w4d4);
     const int v = (tab[std::min(std::max(mb, 1), 4) - 1] + 7) / 8 * 8;
     return 4 * std::min(8, 512 / v);
@@ -447,7 +447,7 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
     // (ties go to the earlier shape: the measured order at equal modelled cost - the fp16 kernels do
     // best with the shallow ring, the INT8 kernel with the deep one)
     const int shapes_f16[5][3] = {{4, 2, 1}, {8, 4, 1}, {4, 4, 1}, {8, 4, 2}, {8, 2, 2}};   // (8, 4, 2): two wave groups
-    const int shapes_i8[5][3] = {{4, 4, 1}, {8, 4, 1}, {4, 2, 1}, {8, 2, 2}, {8, 2, 2}};
+    const int shapes_i8[5][3] = {{4, 4, 1}, {8, 4, 1}, {4, 2, 1}, {8, 4, 2}, {8, 2, 2}};
     const auto& shapes = i8 ? shapes_i8 : shapes_f16;
 
     int best_nw = 0, best_depth = 0, best_pw = 1;

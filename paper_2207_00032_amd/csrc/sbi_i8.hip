@@ -156,6 +156,86 @@ __global__ __launch_bounds__(NW * 64) void sbi_i8_kernel(const GroupParams gp)
     }
 }
 
+// Two-panel blocks, second form (as sbi_mfma_wg_kernel): eight waves in two groups of four, each group
+// streaming one of the two panels against the same staged tile of pre-quantised codes; four-way
+// integer reductions, the two panels side by side.
+template <int MB, int DEPTH>
+__global__ __launch_bounds__(512) void sbi_i8_wg_kernel(const GroupParams gp)
+{
+    constexpr int NT = 512, GW = 4;
+    int gi = 0;
+    while (gi + 1 < gp.G && (int)blockIdx.x >= gp.first_block[gi + 1]) ++gi;
+    const GemmParams& p = gp.g[gi];
+    const int bid = (int)blockIdx.x - gp.first_block[gi];
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    const floatx2* stats = p.xstats;
+    u32x4* xs  = reinterpret_cast<u32x4*>(smem_raw + kLnStatsBytes);
+    __shared__ int s_flag;
+
+    const int tid  = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave / GW, kwave = wave - grp * GW;
+    const int g = lane >> 4;
+    const int i = lane & 15;
+
+    const int pgroup = bid / p.S;
+    const int split = bid - pgroup * p.S;
+    const int panel0 = pgroup * 2;
+    const int npanels = min(2, p.P - panel0);
+    const int panel = panel0 + min(grp, npanels - 1);   // a missing second panel: its group streams the first again, result dropped
+    const int ks0 = split * p.ksps;
+    const int ks1 = min(p.KS, ks0 + p.ksps);
+
+    MfmaI8Op<MB, 1> op;
+    op.init(p.B, p.xpitch, g, i);
+    XStageCodes<NT, 4> xst;
+    xst.init(p);
+    stream_panel<GW, DEPTH, 1, false, staging_passes(MB, DEPTH, false, 2)>(p, xs, xst, op, tid, kwave, lane, panel, 0,
+                                                                            ks0, ks1);
+
+    float* red = reinterpret_cast<float*>(smem_raw + kLnStatsBytes) + grp * (GW * 16 * kRedPitch);
+    const int gtid = tid & (GW * 64 - 1);
+    RowOperands<GW> ops[MB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m) ops[m] = request_row_operands<GW>(p, m, panel, gtid, m == 0, ops[0]);
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < kPanelTiles; ++t)
+            *reinterpret_cast<i32x4*>(red + (kwave * 16 + i) * kRedPitch + t * kTileN + 4 * g) = op.acc[t][m];
+        __syncthreads();
+        if (grp < npanels) reduce_rows<GW, true>(p, red, m, panel, split, gtid, ops[m], stats);
+    }
+    if (p.S > 1) {
+        for (int q = 0; q < npanels; ++q) finish_split_k<NT, true>(p, panel0 + q, tid, &s_flag, stats);
+    }
+}
+
+template <int MB, int DEPTH>
+static int launch_wg_one(const GroupParams& gp, size_t lds, hipStream_t st)
+{
+    if (lds > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sbi_i8_wg_kernel<MB, DEPTH>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return (int)e;
+    }
+    hipLaunchKernelGGL((sbi_i8_wg_kernel<MB, DEPTH>), dim3(gp.first_block[gp.G]), dim3(512), lds, st, gp);
+    return (int)hipGetLastError();
+}
+
+static int launch_wg(const GroupParams& gp, size_t lds, hipStream_t st)
+{
+    if (lds < kLnStatsBytes + 2 * 4 * 16 * kRedPitch * sizeof(float)) return (int)hipErrorInvalidValue;
+    switch ((gp.g[0].B + 15) / 16) {
+        case 2: return launch_wg_one<2, 4>(gp, lds, st);
+        case 3: return launch_wg_one<3, 4>(gp, lds, st);
+        case 4: return launch_wg_one<4, 4>(gp, lds, st);
+    }
+    return (int)hipErrorInvalidValue;
+}
+
 template <int MB, int NW, int DEPTH, int PW, bool PREQ>
 static int launch_one(const GroupParams& gp, size_t lds, hipStream_t st)
 {
@@ -224,10 +304,11 @@ __global__ __launch_bounds__(256) void sbi_quantize_rows_kernel(const QuantRowsP
 int launch_i8(const GroupParams& gp, int waves, int depth, int panels, bool prequantized, size_t lds_bytes, hipStream_t st)
 {
     if (gp.G < 1 || gp.G > kMaxGroup) return (int)hipErrorInvalidValue;
-    if (panels == 2 && !(prequantized && waves == 8 && depth == 2)) return (int)hipErrorInvalidValue;
+    if (panels == 2 && !(prequantized && waves == 8 && (depth == 2 || depth == 4))) return (int)hipErrorInvalidValue;
     if (panels != 1 && panels != 2) return (int)hipErrorInvalidValue;
     if (prequantized) {
-        if (!spread_staging_fits(gp, waves, depth, false)) return (int)hipErrorInvalidValue;
+        const bool groups = panels == 2 && depth == 4;      // two wave groups, one panel each
+        if (!spread_staging_fits(gp, waves, depth, false, groups ? 2 : 1)) return (int)hipErrorInvalidValue;
         // gp.g[k].X already points at the codes' place in the workspace: fill it from gp.g[k].X16
         QuantRowsParams q;
         for (int k = 0; k < gp.G; ++k) {
@@ -239,6 +320,7 @@ int launch_i8(const GroupParams& gp, int waves, int depth, int panels, bool preq
         q.B = gp.g[0].B;
         hipLaunchKernelGGL(sbi_quantize_rows_kernel, dim3(gp.G * q.B), dim3(256), 0, st, q);
         if (hipGetLastError() != hipSuccess) return (int)hipErrorInvalidValue;
+        if (groups) return launch_wg(gp, lds_bytes, st);
         if (panels == 2) return launch_mb<8, 2, 2, true>(gp, lds_bytes, st);
         if (waves == 4 && depth == 2) return launch_mb<4, 2, 1, true>(gp, lds_bytes, st);
         if (waves == 4 && depth == 4) return launch_mb<4, 4, 1, true>(gp, lds_bytes, st);

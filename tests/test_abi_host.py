@@ -292,7 +292,7 @@ def test_int8_argument_validation_and_plans(lib):
             pl = sb.plan(B, K, N, int8=True)
             pw = pl["panels"]
             assert pl["path"] == sb.PATH_MFMA and pw in (1, 2) and (pw == 1 or B > 16)
-            assert (pl["waves"], pl["depth"]) in (((4, 2), (4, 4), (8, 4)) if pw == 1 else ((8, 2),))
+            assert (pl["waves"], pl["depth"]) in (((4, 2), (4, 4), (8, 4)) if pw == 1 else ((8, 2), (8, 4)))
             S, ksps, kc = pl["split_k"], pl["ksteps_per_split"], pl["ksteps_per_chunk"]
             assert 1 <= S <= KS and ksps * S >= KS and ksps * (S - 1) < KS and pl["grid"] == -(-P // pw) * S
             buffers = 1 if kc >= ksps else 2

@@ -43,6 +43,7 @@ GEMM_CASES = [
     (64, 2048, 192, 8, 2, 1, 2, 0), (48, 1100, 128, 8, 2, 1, 2, 0), (40, 1544, 136, 8, 2, 2, 2, 0), (33, 3072, 128, 8, 2, 1, 2, 0),
     # two wave groups, one panel each (waves 8, depth 4, panels 2)
     (64, 2048, 192, 8, 4, 1, 2, 0), (48, 1100, 128, 8, 4, 1, 2, 0), (40, 1544, 136, 8, 4, 2, 2, 0), (33, 3072, 128, 8, 4, 1, 2, 0), (17, 520, 72, 8, 4, 3, 2, 0),
+    (64, 2048, 128, 8, 4, 2, 2, 2), (40, 4096, 136, 8, 4, 1, 2, 2), (24, 1040, 72, 8, 4, 1, 2, 2),
     # several rounds with the X staging passes spread over the steps of a round (batches above 16)
     (40, 4096, 72, 4, 2, 1, 1, 0), (40, 4096, 72, 4, 4, 1, 1, 1), (40, 4096, 72, 4, 4, 1, 1, 2),
     (40, 4096, 136, 8, 2, 1, 2, 2), (64, 2048, 128, 8, 2, 2, 2, 2), (24, 1040, 72, 8, 2, 1, 2, 2),

@@ -103,15 +103,16 @@ def test_int8_two_panel_blocks(gpu, B, K, N):
     Wl, sw_d, Wq, sw = prepare(gpu, W)
     Xd, bd, Rd = _dev(X, gpu), _dev(bias, gpu), _dev(R, gpu)
     ran = 0
-    for S in (0, 1, 2, 5):
-        try:
-            sb.plan(B, K, N, sb.PATH_MFMA, S, 8, 2, panels=2, int8=True)
-        except sb.SbiError:
-            continue
-        for epi in ("bias_gelu", "bias_residual"):
-            Y = sb.gemm_i8(Wl, sw_d, K, N, Xd, bd, Rd, epi, path=sb.PATH_MFMA, split_k=S, waves=8, depth=2, panels=2)
-            check(Y.cpu().numpy(), X, Wq, sw, bias, R, epi, f"2-panel B={B} K={K} N={N} S={S} {epi}")
-            ran += 1
+    for depth in (2, 4):                                   # 4: two wave groups, one panel each
+        for S in (0, 1, 2, 5):
+            try:
+                sb.plan(B, K, N, sb.PATH_MFMA, S, 8, depth, panels=2, int8=True)
+            except sb.SbiError:
+                continue
+            for epi in ("bias_gelu", "bias_residual"):
+                Y = sb.gemm_i8(Wl, sw_d, K, N, Xd, bd, Rd, epi, path=sb.PATH_MFMA, split_k=S, waves=8, depth=depth, panels=2)
+                check(Y.cpu().numpy(), X, Wq, sw, bias, R, epi, f"2-panel B={B} K={K} N={N} S={S} d={depth} {epi}")
+                ran += 1
     assert ran > 0
 
 
