@@ -527,6 +527,10 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
                 const double gbytes = (double)work * 4096.0 / 1e9;
                 cost *= 1.0 + 0.045 * std::min((double)(conc - 1), 1.2) * std::min(1.0, std::max(0.0, (gbytes - 0.5) / 2.0));
                 // (k-steps in flight on an average CU: a launch of 2.8 blocks per CU leaves some with two)
+                // a launch with split panels ends in a chain the stream cannot hide: partial sums out,
+                // arrival count, the last block's loads of the slabs, its epilogue (h=4096 QKV, 192
+                // panels: unsplit on 192 CUs 18.5 us, split four ways on all of them 19.8 us)
+                if (partial > 0.0) cost += 20.0;
                 const double inflight = std::min((double)fit, (double)blocks / kNumCU) * nw * depth;
                 if (inflight < 24.0) cost *= 1.0 + 0.3 * (24.0 - inflight) / 24.0;
                 if (slow_stage) cost *= 1.1;
