@@ -953,11 +953,12 @@ sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
     return launch_block_group(&a[3], &one, last, 1, B, workspace, st);
 }
 
-// Position ranges per (sequence, head) of the attention kernel: enough blocks to fill the chip,
-// but no range shorter than 256 cached positions.
+// Position ranges per (sequence, head) of the attention kernel: one block per CU where the
+// context allows it, but no range shorter than 256 cached positions (more, shorter ranges were
+// measured slower at every shape: a block's fixed cost is about the time to stream 128 positions).
 static int attn_splits(int64_t B, int64_t H, int64_t n)
 {
-    int64_t target = 512, shortest = 256, cap = 32;
+    int64_t target = 256, shortest = 256, cap = 32;
 #ifdef SBI_DEV
     if (const char* e = getenv("SBI_ATTN_SPLIT")) {
         long long a, b, c;
