@@ -75,8 +75,9 @@ typedef struct sbi_tuning {
     int32_t waves;   /* wavefronts per block: 4 or 8 */
     int32_t depth;   /* k-steps of W each wavefront keeps in flight: 2 (MFMA path), 4 or 8 */
     int32_t blocks;  /* STREAMK path: upper bound on the number of thread blocks */
-    int32_t panels;  /* MFMA path: 64-column panels per block, 1 or 2 (2: X is staged and read once
-                        for 128 columns; for larger batches) */
+    int32_t panels;  /* MFMA path: 64-column panels per block, 1 or 2 (2: X is staged once for 128
+                        columns; for larger batches.  With waves = 8: depth 2 - every wave streams both
+                        panels; depth 4, B > 16 - two groups of four waves, one panel each) */
     int32_t layernorm; /* sbi_gemm_plan: nonzero plans the launch sbi_gemm_ln makes (layer-norm fused
                           in front: MFMA path, one panel per block, K % 8 == 0, (waves, depth) one of
                           (4,2), (4,4), (8,4)); sbi_gemm_ex rejects it, sbi_gemm_ln implies it */
