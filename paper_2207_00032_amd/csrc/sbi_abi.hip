@@ -33,6 +33,8 @@ struct Plan {
     int pw;                   // MFMA path: panels per block
     bool ln;                  // MFMA path: the kernel variant that can layer-normalise X
     bool i8;                  // the INT8 kernel (64-k steps, int8 X codes in LDS)
+    bool prenorm;             // layer-norm requested, batch above kLnFusedMaxBatch: a kernel of its own writes the
+                              //   normalised rows to the workspace (xq_bytes) and the plain kernels run on those
     bool preq;                // INT8: activations quantised by a kernel of their own, codes in the workspace
     int64_t xq_bytes;         //   and the workspace bytes those codes and row scales take
 };
@@ -51,7 +53,7 @@ sbi_status plan_streamk(int64_t B, int64_t units, int64_t panels, const sbi_tuni
     const int64_t want = t.blocks ? (int64_t)t.blocks * nw : kSkDefaultWaves;
     const int64_t upw = round_up(ceil_div(units, want), kStepGroup);
     const int64_t nwaves = ceil_div(units, upw);
-    pl.ln = false; pl.i8 = false; pl.preq = false; pl.xq_bytes = 0; pl.path = SBI_PATH_STREAMK; pl.nw = nw; pl.depth = depth; pl.S = 0;
+    pl.ln = false; pl.i8 = false; pl.preq = false; pl.prenorm = false; pl.xq_bytes = 0; pl.path = SBI_PATH_STREAMK; pl.nw = nw; pl.depth = depth; pl.S = 0;
     pl.ksps = (int)upw; pl.kc = 0; pl.pw = 1;
     pl.grid = (int)ceil_div(nwaves, nw); pl.block = nw * 64; pl.lds = 0;
     pl.upw = (int)upw; pl.nwaves = (int)nwaves;
@@ -110,6 +112,14 @@ inline int64_t x_pitch(int64_t B) { return B | 1; }
 // INT8: up to this batch every block quantises the activations itself; above it a kernel of its
 // own does it once (measured on MI355X: fused is ahead up to B = 8, behind from B = 16 on).
 constexpr int64_t kI8FusedMaxBatch = 8;
+// Layer-norm: up to this batch every block normalises what it stages; above it the rows are normalised
+// once by a kernel of their own and the plain kernels run on the result.  Measured, fused against
+// that pass plus the plain launch: h=1024 layer B = 1 16.3 / 18.4 us; h=4096 layer B = 8 67.3 / 67.9,
+// B = 16 70.3 / 69.1, B = 32 104 / 74 us; h=12288 layer (3.6 GB, where the plain launch can use one
+// 8-wave block per CU) B = 4 535 / 532, B = 8 561 / 527, B = 16 600 / 534 us.
+constexpr int64_t kLnFusedMaxBatch = 8;
+constexpr int64_t kLnFusedMaxBatchLarge = 4;     // launches of a gigabyte and more
+inline int64_t xn_bytes_of(int64_t B, int64_t K) { return round_up(B * K * 2, 256); }
 inline int64_t xq_bytes_of(int64_t B, int64_t K) { return round_up(B * K, 256) + round_up(B * 8, 256); }
 
 // k-steps a block consumes per round of its rings.  (8 waves, depth 4, two panels) is the shape whose
@@ -218,7 +228,7 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
                   kc, lds, fl))
         return SBI_ERR_TUNING;
 
-    pl.ln = ln; pl.i8 = i8; pl.preq = preq; pl.xq_bytes = preq ? xq_bytes_of(B, K) : 0;
+    pl.ln = ln; pl.i8 = i8; pl.preq = preq; pl.prenorm = false; pl.xq_bytes = preq ? xq_bytes_of(B, K) : 0;
     pl.path = path; pl.nw = nw; pl.depth = depth; pl.S = S; pl.pw = pw;
     pl.ksps = (int)ksps; pl.kc = (int)kc;
     pl.grid = (int)(PG * S); pl.block = nw * 64;
@@ -345,6 +355,10 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
     p.ln_gamma = reinterpret_cast<const _Float16*>(a.gamma ? a.gamma : a.X);
     p.ln_beta = reinterpret_cast<const _Float16*>(a.gamma ? a.beta : a.X);
     p.ln_eps = a.eps;
+    if (pl.prenorm && a.gamma) {        // sbi_layernorm_rows_kernel leaves the normalised rows at xq_off of the workspace:
+        p.X = reinterpret_cast<const _Float16*>(ws + xq_off);     // the GeMM kernel reads those (X16 keeps the raw rows)
+        p.ln = 0;
+    }
 #ifdef SBI_TRACE
     p.trace = getenv("SBI_TRACE_PTR") ? reinterpret_cast<unsigned long long*>(strtoull(getenv("SBI_TRACE_PTR"), nullptr, 16)) : nullptr;
 #endif
@@ -427,10 +441,16 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
     return m.status;
 }
 
-sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot, bool ln,
+sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot, bool ln_wanted,
                              bool i8)
 {
     if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
+    // layer-norm: inside the GeMM blocks for the smallest batches, as a pass of its own otherwise
+    double launch_bytes = 0.0;
+    for (int g = 0; g < G; ++g) launch_bytes += 2.0 * (double)Ks[g] * (double)Ns[g];
+    const int64_t fused_max = launch_bytes >= 1e9 ? kLnFusedMaxBatchLarge : kLnFusedMaxBatch;
+    const bool prenorm = ln_wanted && B > fused_max;          // normalise once, then the plain kernels
+    const bool ln = ln_wanted && !prenorm;
     const int mb = (int)ceil_div(B, 16);
     int64_t KS[kMaxGroup], P[kMaxGroup], maxKS = 0, panels = 0;
     for (int g = 0; g < G; ++g) {
@@ -566,7 +586,8 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
         const int64_t ksps = ceil_div(KS[g], S);
         int64_t kc = 0, l = 0;
         chunking(B, ksps, wd, nw, best_cap, (int64_t)nw * 16 * kRedPitch * 4, kc, l, fl);
-        pl.path = SBI_PATH_MFMA; pl.nw = nw; pl.depth = depth; pl.pw = pw; pl.ln = ln; pl.i8 = i8; pl.preq = preq; pl.xq_bytes = preq ? xq_bytes_of(B, Ks[g]) : 0;
+        pl.path = SBI_PATH_MFMA; pl.nw = nw; pl.depth = depth; pl.pw = pw; pl.ln = ln; pl.i8 = i8; pl.preq = preq; pl.prenorm = prenorm;
+        pl.xq_bytes = preq ? xq_bytes_of(B, Ks[g]) : (prenorm ? xn_bytes_of(B, Ks[g]) : 0);
         pl.S = (int)ceil_div(KS[g], ksps); pl.ksps = (int)ksps; pl.kc = (int)kc;
         pl.grid = (int)(ceil_div(P[g], pw) * pl.S); pl.block = nw * 64;
         pl.lds = l;
@@ -579,7 +600,7 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
     if (grid > (int64_t)0x7fffffff) return SBI_ERR_SHAPE;
     tot = pls[0];
     tot.grid = (int)grid; tot.lds = lds;
-    tot.ws_bytes = (any_split || preq) ? kCounterBytes + partial_bytes : 0;
+    tot.ws_bytes = (any_split || preq || prenorm) ? kCounterBytes + partial_bytes : 0;
     return SBI_OK;
 }
 
@@ -621,6 +642,7 @@ sbi_status launch_block_group(const GemmArgs* a, const Plan* pls, const Plan& to
         }
         return launch_i8(gp, tot.nw, tot.depth, tot.pw, tot.preq, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
     }
+    if (tot.prenorm && launch_layernorm_rows(gp, st) != 0) return SBI_ERR_HIP;
     return launch_mfma(gp, tot.nw, tot.depth, tot.pw, tot.ln, (size_t)tot.lds, st) == 0 ? SBI_OK : SBI_ERR_HIP;
 }
 

@@ -113,6 +113,9 @@ int launch_streamk(const SkParams& p, int waves, int depth, int grid, hipStream_
 int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, bool layernorm, size_t lds_bytes,
                 hipStream_t st);
 int launch_i8(const GroupParams& gp, int waves, int depth, int panels, bool prequantized, size_t lds_bytes, hipStream_t st);
+// Normalises the rows of every problem of `gp` whose X16 (raw rows) differs from its X (where the
+// GeMM kernel will read the normalised rows), one block per row.
+int launch_layernorm_rows(const GroupParams& gp, hipStream_t st);
 int launch_layout_i8(const void* Wq, int64_t K, int64_t N, void* out, hipStream_t st);
 int launch_quantize_weights(const void* W, int64_t K, int64_t N, void* Wq, void* scales, hipStream_t st);
 int launch_attn_decode(const void* qkv, void* Kc, void* Vc, int64_t B, int H, int D, int64_t S, int64_t pos,

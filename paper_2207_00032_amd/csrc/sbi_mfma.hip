@@ -11,6 +11,8 @@
 // The paper tiles the output dimension first and splits the input dimension only when the
 // output is too narrow to fill the machine (Sec. III-C, "Tiling Strategies"); the same two
 // levels appear here as panels (grid) x k-split (waves of a block, then blocks of a panel).
+#include <cstring>
+
 #include "sbi_block.h"
 
 namespace sbi {
@@ -282,6 +284,74 @@ static int launch_mb(const GroupParams& gp, size_t lds, hipStream_t st)
         case 4: return launch_one<4, NW, DEPTH, PW, LN>(gp, lds, st);
     }
     return (int)hipErrorInvalidValue;
+}
+
+// Layer-norm as a pass of its own, for batches where normalising inside every GeMM block costs more
+// than this (above 16 rows): one block per row, mean and biased variance in fp32 (two passes over
+// the row, the second and third from cache), the same (x - mean) * rstd * gamma + beta and the same
+// single rounding to fp16 as the fused variant (ln_apply).  K % 8 == 0.
+struct NormRowsParams {
+    const _Float16* X[kMaxGroup];
+    _Float16* out[kMaxGroup];
+    const _Float16* gamma[kMaxGroup];
+    const _Float16* beta[kMaxGroup];
+    int K[kMaxGroup];
+    float eps[kMaxGroup];
+    int B, G;
+};
+
+__global__ __launch_bounds__(256) void sbi_layernorm_rows_kernel(const NormRowsParams q)
+{
+    __shared__ float s_part[4];
+    const int g = (int)blockIdx.x / q.B, b = (int)blockIdx.x - g * q.B;
+    if (!q.X[g]) return;                               // a problem of the launch without layer-norm
+    const int K = q.K[g];
+    const int pieces = K / kChunkK;
+    const u32x4* row = reinterpret_cast<const u32x4*>(q.X[g] + (int64_t)b * K);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    float s = 0.f;
+    for (int c = tid; c < pieces; c += 256) s += piece_sum(row[c]);
+    s = wave_sum(s);
+    if (lane == 0) s_part[wave] = s;
+    __syncthreads();
+    const float mean = (s_part[0] + s_part[1] + s_part[2] + s_part[3]) / (float)K;
+    __syncthreads();
+    float v = 0.f;
+    for (int c = tid; c < pieces; c += 256) v += piece_sqdev(row[c], mean);
+    v = wave_sum(v);
+    if (lane == 0) s_part[wave] = v;
+    __syncthreads();
+    const float var = (s_part[0] + s_part[1] + s_part[2] + s_part[3]) / (float)K;
+    const floatx2 st = {mean, 1.0f / sqrtf(var + q.eps[g])};
+
+    const u32x4* gam = reinterpret_cast<const u32x4*>(q.gamma[g]);
+    const u32x4* bet = reinterpret_cast<const u32x4*>(q.beta[g]);
+    u32x4* dst = reinterpret_cast<u32x4*>(q.out[g] + (int64_t)b * K);
+    for (int c = tid; c < pieces; c += 256) {
+        const half8 y = ln_apply(__builtin_bit_cast(half8, row[c]), __builtin_bit_cast(half8, gam[c]),
+                                 __builtin_bit_cast(half8, bet[c]), st);
+        dst[c] = __builtin_bit_cast(u32x4, y);
+    }
+}
+
+int launch_layernorm_rows(const GroupParams& gp, hipStream_t st)
+{
+    NormRowsParams q;
+    std::memset(&q, 0, sizeof q);
+    q.B = gp.g[0].B; q.G = gp.G;
+    bool any = false;
+    for (int k = 0; k < gp.G; ++k) {
+        const GemmParams& p = gp.g[k];
+        if (p.X16 == p.X) continue;                    // nothing to normalise for this problem
+        if (p.K % kChunkK != 0) return (int)hipErrorInvalidValue;
+        q.X[k] = p.X16; q.out[k] = const_cast<_Float16*>(p.X);
+        q.gamma[k] = p.ln_gamma; q.beta[k] = p.ln_beta; q.K[k] = p.K; q.eps[k] = p.ln_eps;
+        any = true;
+    }
+    if (!any) return 0;
+    hipLaunchKernelGGL(sbi_layernorm_rows_kernel, dim3(gp.G * q.B), dim3(256), 0, st, q);
+    return (int)hipGetLastError();
 }
 
 int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, bool layernorm, size_t lds_bytes,

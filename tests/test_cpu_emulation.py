@@ -51,6 +51,8 @@ GEMM_CASES = [
     (1, 64, 64, 0, 0, 0, 0, 1), (3, 264, 200, 0, 0, 0, 0, 1), (8, 2048, 128, 8, 4, 1, 1, 1),
     (17, 1024, 136, 4, 2, 3, 1, 1), (40, 1024, 72, 4, 4, 2, 1, 1), (64, 512, 128, 4, 2, 2, 1, 1),
     (2, 6144, 64, 4, 4, 1, 1, 1),
+    # above 16 rows the automatic plan normalises the rows with a kernel of its own first
+    (33, 1024, 200, 0, 0, 0, 0, 1), (64, 520, 72, 0, 0, 0, 0, 1), (40, 1024, 72, 0, 0, 0, 0, 4),
     (1, 64, 64, 0, 0, 0, 0, 2), (3, 272, 200, 0, 0, 0, 0, 2), (8, 2048, 128, 8, 4, 1, 1, 2),
     (17, 1024, 136, 4, 2, 3, 1, 2), (40, 1024, 72, 4, 4, 2, 1, 2), (64, 512, 128, 4, 2, 2, 1, 2),
     (5, 4096, 64, 4, 4, 1, 1, 2), (2, 8192, 64, 0, 0, 0, 0, 2), (17, 1024, 136, 4, 2, 3, 1, 2), (33, 4096, 64, 0, 0, 0, 0, 2),
