@@ -185,8 +185,9 @@ sbi_status sbi_gemm_ex(const void* W_laid_out, int64_t K, int64_t N,
  * statistics (fp32, two passes) and normalises its share of X on the way into the matrix-core
  * operand; above that a kernel of its own normalises the rows once into the workspace and the
  * plain GeMM kernels run on the result (with automatic tuning; an explicit `tuning` keeps the
- * fused form, and `moments` are then the only case in which they are used).  Either way Xn is
- * rounded to fp16 once: it is the matrix-core operand.
+ * fused form).  `moments` shorten the statistics of the fused form only; the separate kernel
+ * recomputes them from the rows.  Either way Xn is rounded to fp16 once: it is the matrix-core
+ * operand.
  *   gamma, beta  device, fp16 [K], 16-byte aligned
  *   eps          finite, >= 0
  * Needs K % 8 == 0 (SBI_ERR_SHAPE otherwise).  Everything else as for sbi_gemm_ex; `tuning`
