@@ -46,10 +46,11 @@ def parse_args():
     ap.add_argument("--int8", action="store_true",
                     help="INT8 layer: weights quantised per output channel and laid out as int8, activations "
                          "quantised inside the kernel (sbi_layer's scales); algorithmic bytes count one byte per weight")
-    ap.add_argument("--attention", type=str, default=None, metavar="B:H:d:ctx[,...]", nargs="?",
+    ap.add_argument("--attention", type=str, default=None, metavar="B:H:d:ctx[:r][,...]", nargs="?",
                     const="1:32:128:136,8:32:128:136,64:32:128:136,8:32:128:2048,64:32:128:2048,1:32:128:8192,8:32:128:8192",
                     help="time the single-token attention with a KV cache (sbi_attn_decode) instead of the GeMMs: "
-                         "ctx = positions attended to, the new token's included; value = KV-cache streaming GB/s")
+                         "ctx = positions attended to, the new token's included; a shape ending in :r is a ragged batch "
+                         "(sbi_attn_decode_ragged, lengths spread evenly from ctx/8 to ctx); value = KV-cache streaming GB/s")
     ap.add_argument("--decoder-layer", type=str, default=None, metavar="B:ctx[,...]", nargs="?", const="1:136,4:136,8:136,8:2048",
                     help="time one token-generation step of a whole h=4096 layer (32 heads): layer-norm + QKV, attention "
                          "over the KV cache, attention output + residual, layer-norm + FFN1 + GeLU, FFN2 + residual as five "
@@ -90,15 +91,20 @@ def attention_main(args):
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     sb.load()
     dev = torch.device("cuda:0")
-    shapes = [tuple(int(v) for v in item.split(":")) for item in args.attention.split(",")]
+    # B:H:d:ctx, or B:H:d:ctx:r for a ragged batch (sbi_attn_decode_ragged): sequence b attends to
+    # ctx/8 + b (ctx - ctx/8) / max(B-1, 1) positions, i.e. lengths spread evenly up to ctx, bound ctx - 1
+    shapes = [(tuple(int(v) for v in item.split(":")[:4]), item.split(":")[4:] == ["r"]) for item in args.attention.split(",")]
     cases = []
-    for (B, H, d, ctx) in shapes:
+    for (B, H, d, ctx), ragged in shapes:
+        lens = [ctx // 8 + b * (ctx - ctx // 8) // max(B - 1, 1) for b in range(B)] if ragged else [ctx] * B
         qkv, K, V = wl.make_attention_inputs(B, H, d, ctx, seed=0, config_id=600)
         cache_bytes = 2 * K.nbytes
         copies = max(2, -(-3 * 256 * 1000 * 1000 // cache_bytes))      # rotate so the cache comes from HBM
         Kd = [torch.from_numpy(K).to(dev) for _ in range(copies)]
         Vd = [torch.from_numpy(V).to(dev) for _ in range(copies)]
-        cases.append({"shape": (B, H, d, ctx), "host": (qkv, K, V), "qkv": torch.from_numpy(qkv).to(dev), "K": Kd, "V": Vd,
+        cases.append({"shape": (B, H, d, ctx), "lens": lens,
+                      "pos": torch.tensor([n - 1 for n in lens], dtype=torch.int32, device=dev) if ragged else None,
+                      "host": (qkv, K, V), "qkv": torch.from_numpy(qkv).to(dev), "K": Kd, "V": Vd,
                       "out": torch.empty((B, H * d), dtype=torch.float16, device=dev), "n": 0,
                       "ws": sb.new_workspace(max(256, sb.attn_workspace_bytes(B, H, d, ctx)), dev)})
 
@@ -106,7 +112,10 @@ def attention_main(args):
         j = c["n"] % len(c["K"])
         c["n"] += 1
         B, H, d, ctx = c["shape"]
-        sb.attn_decode(c["qkv"], c["K"][j], c["V"][j], ctx - 1, out=c["out"], workspace=c["ws"])
+        if c["pos"] is not None:
+            sb.attn_decode_ragged(c["qkv"], c["K"][j], c["V"][j], c["pos"], ctx - 1, out=c["out"], workspace=c["ws"])
+        else:
+            sb.attn_decode(c["qkv"], c["K"][j], c["V"][j], ctx - 1, out=c["out"], workspace=c["ws"])
 
     def step():
         for c in cases:
@@ -120,7 +129,11 @@ def attention_main(args):
         step()
     torch.cuda.synchronize()
     sec_per_step = (time.perf_counter() - t0) / args.steps
-    bytes_per_step = sum(attention_bytes(*c["shape"]) for c in cases)
+    def case_bytes(c):                                          # every sequence moves what its own length asks for
+        B, H, d, ctx = c["shape"]
+        return sum(attention_bytes(1, H, d, n) for n in c["lens"])
+
+    bytes_per_step = sum(case_bytes(c) for c in cases)
 
     per_call = []
     for c in cases:
@@ -134,9 +147,10 @@ def attention_main(args):
             torch.cuda.synchronize()
             us.append(e0.elapsed_time(e1) * 1e2)
         med = sorted(us)[2]
-        nb = attention_bytes(*c["shape"])
+        nb = case_bytes(c)
         B, H, d, ctx = c["shape"]
-        per_call.append({"B": B, "heads": H, "head_dim": d, "ctx": ctx, "us_median": round(med, 2),
+        per_call.append({"B": B, "heads": H, "head_dim": d, "ctx": ctx, "ragged": c["pos"] is not None,
+                         "us_median": round(med, 2),
                          "GBps": round(nb / med / 1e3, 1), "hbm_frac": round(nb / med / 1e3 / HBM_PEAK_GBPS, 4),
                          "bytes": nb})
     big = max(per_call, key=lambda r: r["bytes"])
@@ -151,7 +165,7 @@ def attention_main(args):
         t_cpu, nbytes, n_bad, max_abs = 0.0, 0, 0, 0.0
         for c in cases:
             B, H, d, ctx = c["shape"]
-            if attention_bytes(B, H, d, ctx) > (64 << 20):
+            if attention_bytes(B, H, d, ctx) > (64 << 20) or c["pos"] is not None:
                 continue
             qkv, K, V = c["host"]
             c0 = time.perf_counter()

@@ -352,6 +352,24 @@ sbi_status sbi_attn_decode(const void* qkv, void* k_cache, void* v_cache, int64_
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The same attention (paper Sec. III-D region 2; Sec. IV token-generation phase) for a batch whose
+ * sequences are at different lengths, as a serving batch's are: sequence b's new token goes to
+ * position pos[b] of its cache and attends to positions 0 .. pos[b].
+ *
+ *   pos         device, int32 [B], 4-byte aligned; read by the kernel, never by the host
+ *   pos_bound   host value with 0 <= pos_bound < max_seq; the caller guarantees pos[b] <= pos_bound.
+ *               It sizes the launch (position ranges per sequence and head are cut for pos_bound + 1
+ *               positions; a shorter sequence's surplus ranges are empty), so a tight bound is
+ *               faster.  An entry outside 0 .. pos_bound is not an error the kernel can report: it is
+ *               forced to the nearer end of that interval, so no entry reaches outside the caches.
+ * Everything else as for sbi_attn_decode, whose result row b equals this call's when pos[b] == pos
+ * (bit for bit when pos_bound == pos as well: the same ranges are summed in the same order).
+ */
+sbi_status sbi_attn_decode_ragged(const void* qkv, void* k_cache, void* v_cache, int64_t B, int32_t heads,
+                                  int32_t head_dim, int64_t max_seq, const int32_t* pos, int64_t pos_bound, float scale,
+                                  void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Measurement helpers (no part of the GeMM path; for callers that profile it).
  * sbi_calib_read streams `bytes` (a multiple of 4096, 256-byte aligned, device) from src
  * with the GeMM's own access shape - `blocks` thread blocks of `waves` wavefronts (4, 8 or

@@ -32,7 +32,8 @@ EXPORTS = ["sbi_gemm_layout_bytes", "sbi_gemm_workspace_bytes", "sbi_gemm_layout
            "sbi_version", "sbi_calib_read", "sbi_calib_copy", "sbi_layer_plan", "sbi_gemm_ln",
            "sbi_gemm_ln_workspace_bytes", "sbi_gemm_i8_layout_bytes", "sbi_gemm_i8_workspace_bytes",
            "sbi_gemm_i8_quantize_weights", "sbi_gemm_i8_layout_weights", "sbi_gemm_i8_layout_check", "sbi_gemm_i8",
-           "sbi_gemm_moments", "sbi_attn_decode", "sbi_attn_decode_workspace_bytes"]
+           "sbi_gemm_moments", "sbi_attn_decode", "sbi_attn_decode_workspace_bytes",
+           "sbi_attn_decode_ragged"]
 
 
 class SbiError(RuntimeError):
@@ -114,6 +115,8 @@ def load():
     L.sbi_attn_decode_workspace_bytes.argtypes = [i64, i32, i32, i64]
     L.sbi_attn_decode.restype = i32
     L.sbi_attn_decode.argtypes = [vp, vp, vp, i64, i32, i32, i64, i64, ctypes.c_float, vp, vp, sz, vp]
+    L.sbi_attn_decode_ragged.restype = i32
+    L.sbi_attn_decode_ragged.argtypes = [vp, vp, vp, i64, i32, i32, i64, vp, i64, ctypes.c_float, vp, vp, sz, vp]
     L.sbi_gemm_ln_workspace_bytes.restype = sz
     L.sbi_gemm_ln_workspace_bytes.argtypes = [i64, i64, i64]
     L.sbi_gemm_i8_layout_bytes.restype = sz
@@ -461,6 +464,32 @@ def attn_decode(qkv, k_cache, v_cache, pos, scale=0.0, out=None, workspace=None)
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(load().sbi_attn_decode(_ptr(qkv), _ptr(k_cache), _ptr(v_cache), B, H, d, S, int(pos), float(scale),
                                   _ptr(out), _ptr(workspace), ws_len, _stream()), "sbi_attn_decode")
+    return out
+
+
+def attn_decode_ragged(qkv, k_cache, v_cache, pos, pos_bound, scale=0.0, out=None, workspace=None):
+    """sbi_attn_decode_ragged: as attn_decode, with one position per sequence (pos: int32 device
+    tensor [B]) and the host-side bound pos_bound >= every entry."""
+    import torch
+    B, three, H, d = qkv.shape
+    S = k_cache.shape[2]
+    _need(qkv, (B, 3, H, d), "qkv")
+    _need(k_cache, (B, H, S, d), "k_cache")
+    _need(v_cache, (B, H, S, d), "v_cache")
+    if pos.dtype != torch.int32 or tuple(pos.shape) != (B,) or not pos.is_contiguous() or pos.device != qkv.device:
+        raise ValueError("pos: expected a contiguous int32 tensor [B] on the inputs' device")
+    if out is None:
+        out = torch.empty((B, H * d), dtype=torch.float16, device=qkv.device)
+    _need(out, (B, H * d), "out")
+    need = attn_workspace_bytes(B, H, d, S)
+    if workspace is None and need:
+        workspace = new_workspace(need, qkv.device)
+    if need:
+        _need_bytes(workspace, need, "workspace")
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load().sbi_attn_decode_ragged(_ptr(qkv), _ptr(k_cache), _ptr(v_cache), B, H, d, S, _ptr(pos),
+                                         int(pos_bound), float(scale), _ptr(out), _ptr(workspace), ws_len, _stream()),
+           "sbi_attn_decode_ragged")
     return out
 
 

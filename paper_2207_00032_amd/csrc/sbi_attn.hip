@@ -26,7 +26,8 @@ struct AttnParams {
     _Float16* out;            // [B][H*D]
     float* partials;          // [B*H][nsplit][D+2]: unnormalised value sums, then (max, denominator)
     unsigned int* counters;   // [B*H]
-    int B, H, S, pos, nsplit, per_split;
+    const int* pos_of;        // [B] positions of the new tokens, or NULL: `pos` for every sequence
+    int B, H, S, pos, nsplit, per_split;   // pos: the common position, or the bound of pos_of's entries
     float scale_log2;         // scale * log2(e)
 };
 
@@ -54,6 +55,9 @@ __global__ __launch_bounds__(NT) void sbi_attn_decode_kernel(const AttnParams p)
     const int bh = (int)blockIdx.x / p.nsplit, split = (int)blockIdx.x - bh * p.nsplit;
     const int b = bh / p.H, h = bh - b * p.H;
     const int tid = threadIdx.x, grp = tid / LPP, li = tid - grp * LPP;
+    // ragged batch: this sequence's own position, forced into 0 .. p.pos so that no entry can
+    // address outside the cache; ranges past a shorter sequence's end come out empty
+    const int pos = p.pos_of ? min(max(p.pos_of[b], 0), p.pos) : p.pos;
 
     const _Float16* qrow = p.qkv + (((int64_t)b * 3 + 0) * p.H + h) * D + li * 8;
     const u32x4 knew = *reinterpret_cast<const u32x4*>(qrow + (int64_t)p.H * D);
@@ -69,19 +73,19 @@ __global__ __launch_bounds__(NT) void sbi_attn_decode_kernel(const AttnParams p)
 
     // the transposition: the new token's key and value into their head's cache rows
     if (split == 0 && tid < 2 * LPP) {
-        _Float16* dst = (tid < LPP ? p.Kc : p.Vc) + ((int64_t)bh * p.S + p.pos) * D + (tid % LPP) * 8;
+        _Float16* dst = (tid < LPP ? p.Kc : p.Vc) + ((int64_t)bh * p.S + pos) * D + (tid % LPP) * 8;
         const _Float16* src = p.qkv + (((int64_t)b * 3 + (tid < LPP ? 1 : 2)) * p.H + h) * D + (tid % LPP) * 8;
         *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(src);
     }
 
-    const int n = p.pos + 1;                                   // positions to attend to; the last one is the new token
+    const int n = pos + 1;                                     // positions to attend to; the last one is the new token
     const int j0 = split * p.per_split, j1 = min(n, j0 + p.per_split);
-    const int last_cached = max(p.pos - 1, 0);                 // loads are clamped to rows that exist
+    const int last_cached = max(pos - 1, 0);                   // loads are clamped to rows that exist
     float m = -INFINITY, l = 0.f, o[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = 0.f;
 
-    const int iters = (j1 - j0 + NG * U - 1) / (NG * U);       // the same for every thread of the block
+    const int iters = j1 > j0 ? (j1 - j0 + NG * U - 1) / (NG * U) : 0;   // the same for every thread of the block
     for (int it = 0; it < iters; ++it) {
         u32x4 kk[U], vv[U];
 #pragma unroll
@@ -93,7 +97,7 @@ __global__ __launch_bounds__(NT) void sbi_attn_decode_kernel(const AttnParams p)
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = j0 + (it * U + u) * NG + grp;
-            const bool is_new = (j == p.pos);
+            const bool is_new = (j == pos);
             const half8 kh = __builtin_bit_cast(half8, is_new ? knew : kk[u]);
             const half8 vh = __builtin_bit_cast(half8, is_new ? vnew : vv[u]);
             float s = 0.f;
@@ -122,7 +126,8 @@ __global__ __launch_bounds__(NT) void sbi_attn_decode_kernel(const AttnParams p)
     if (tid < D) {
         for (int g = 0; g < NG; ++g) M = fmaxf(M, s_m[g]);
         for (int g = 0; g < NG; ++g) {
-            const float f = exp2f(s_m[g] - M);                 // groups that saw no position: exp2(-inf) = 0
+            // groups that saw no position count nothing (also when the whole range was empty, M = -inf)
+            const float f = s_m[g] == -INFINITY ? 0.f : exp2f(s_m[g] - M);
             Lsum += f * s_l[g];
             O += f * s_o[g][tid];
         }
@@ -191,7 +196,7 @@ __global__ __launch_bounds__(NT) void sbi_attn_decode_kernel(const AttnParams p)
 }
 
 int launch_attn_decode(const void* qkv, void* Kc, void* Vc, int64_t B, int H, int D, int64_t S, int64_t pos,
-                       float scale, void* out, void* workspace, int nsplit, hipStream_t st)
+                       const int* pos_of, float scale, void* out, void* workspace, int nsplit, hipStream_t st)
 {
     if (nsplit < 1 || nsplit > kAttnMaxSplits) return (int)hipErrorInvalidValue;
     AttnParams p;
@@ -201,6 +206,7 @@ int launch_attn_decode(const void* qkv, void* Kc, void* Vc, int64_t B, int H, in
     p.out = reinterpret_cast<_Float16*>(out);
     p.counters = reinterpret_cast<unsigned int*>(workspace);
     p.partials = workspace ? reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(workspace) + kAttnCounterBytes) : nullptr;
+    p.pos_of = pos_of;
     p.B = (int)B; p.H = H; p.S = (int)S; p.pos = (int)pos; p.nsplit = nsplit;
     p.per_split = (int)((pos + 1 + nsplit - 1) / nsplit);
     p.scale_log2 = scale * 1.44269504088896340736f;

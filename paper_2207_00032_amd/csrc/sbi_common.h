@@ -119,7 +119,7 @@ int launch_layernorm_rows(const GroupParams& gp, hipStream_t st);
 int launch_layout_i8(const void* Wq, int64_t K, int64_t N, void* out, hipStream_t st);
 int launch_quantize_weights(const void* W, int64_t K, int64_t N, void* Wq, void* scales, hipStream_t st);
 int launch_attn_decode(const void* qkv, void* Kc, void* Vc, int64_t B, int H, int D, int64_t S, int64_t pos,
-                       float scale, void* out, void* workspace, int nsplit, hipStream_t st);
+                       const int* pos_of, float scale, void* out, void* workspace, int nsplit, hipStream_t st);
 constexpr int kAttnMaxSplits = 128;                  // most position ranges one (sequence, head) of the attention kernel is split into
 constexpr int kAttnCounterBytes = 256 * 1024;        // arrival counters of the attention kernel's workspace (one per sequence and head)
 constexpr int kI8TileK = 64;                         // k per k-step of the int8 layout

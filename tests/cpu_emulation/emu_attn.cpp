@@ -17,10 +17,20 @@ static void* exact_alloc(size_t align, size_t bytes)
 
 int main(int argc, char** argv)
 {
-    if (argc < 6) { fprintf(stderr, "usage: B H d S pos\n"); return 9; }
+    if (argc < 6) { fprintf(stderr, "usage: B H d S pos [ragged]\n"); return 9; }
     const int64_t B = atoll(argv[1]); const int H = atoi(argv[2]), d = atoi(argv[3]);
-    const int64_t S = atoll(argv[4]), pos = atoll(argv[5]);
+    const int64_t S = atoll(argv[4]), bound = atoll(argv[5]);
+    const bool ragged = argc > 6 && atoi(argv[6]) != 0;
     std::mt19937 rng(11);
+    // ragged: one position per sequence through sbi_attn_decode_ragged - the first at the bound, one at
+    // 0, one out of range on either side (the kernel forces those to the ends of 0 .. bound), the rest drawn
+    int32_t* pos_of = (int32_t*)exact_alloc(4, (size_t)B * 4);
+    std::vector<int64_t> pos_eff(B, bound);
+    for (int64_t b = 0; ragged && b < B; ++b) {
+        int64_t v = b == 0 ? bound : b == 1 ? 0 : b == 2 ? bound + 7 : b == 3 ? -3 : (int64_t)(rng() % (uint64_t)(bound + 1));
+        pos_of[b] = (int32_t)v;
+        pos_eff[b] = v < 0 ? 0 : v > bound ? bound : v;
+    }
     std::normal_distribution<float> nd(0.f, 1.f);
     const size_t nq = (size_t)B * 3 * H * d, nc = (size_t)B * H * S * d;
     _Float16* qkv = (_Float16*)exact_alloc(16, nq * 2);
@@ -33,14 +43,16 @@ int main(int argc, char** argv)
     const size_t wsb = sbi_attn_decode_workspace_bytes(B, H, d, S);
     void* ws = exact_alloc(256, wsb ? wsb : 256);
     memset(ws, 0, wsb ? wsb : 256);
-    const sbi_status st = sbi_attn_decode(qkv, Kc, Vc, B, H, d, S, pos, 0.0f, out, wsb ? ws : nullptr, wsb, nullptr);
-    fprintf(stderr, "B=%ld H=%d d=%d S=%ld pos=%ld ws=%zu status %d (%s)\n", (long)B, H, d, (long)S, (long)pos, wsb, (int)st,
-            sbi_status_string(st));
+    const sbi_status st = ragged ? sbi_attn_decode_ragged(qkv, Kc, Vc, B, H, d, S, pos_of, bound, 0.0f, out, wsb ? ws : nullptr, wsb, nullptr)
+                                 : sbi_attn_decode(qkv, Kc, Vc, B, H, d, S, bound, 0.0f, out, wsb ? ws : nullptr, wsb, nullptr);
+    fprintf(stderr, "B=%ld H=%d d=%d S=%ld pos=%ld ragged=%d ws=%zu status %d (%s)\n", (long)B, H, d, (long)S, (long)bound,
+            (int)ragged, wsb, (int)st, sbi_status_string(st));
     if (st) return 1;
     double worst = 0;
     const double scale = 1.0 / std::sqrt((double)d);
     for (int64_t b = 0; b < B; ++b)
         for (int h = 0; h < H; ++h) {
+            const int64_t pos = pos_eff[b];
             const _Float16* q = qkv + ((b * 3 + 0) * H + h) * d;
             const _Float16* kn = qkv + ((b * 3 + 1) * H + h) * d;
             const _Float16* vn = qkv + ((b * 3 + 2) * H + h) * d;

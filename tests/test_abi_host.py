@@ -339,3 +339,17 @@ def test_attention_argument_validation(lib):
     assert call(wb=need - 1, **full) == 6 and call(w=None, wb=need, **full) == 6 and call(w=w + 64, wb=need, **full) == 3
     assert sb.attn_workspace_bytes(8, 32, 128, 136) == 0         # short caches: one block per (sequence, head)
     assert sb.attn_workspace_bytes(2, 4, 100, 64) == 0 and sb.attn_workspace_bytes(0, 4, 128, 64) == 0
+
+
+def test_ragged_attention_argument_validation(lib):
+    q, k, v, o, w, pp = (FAKE + (i << 30) for i in range(1, 7))
+    call = lambda **kw: lib.sbi_attn_decode_ragged(kw.get("q", q), kw.get("k", k), kw.get("v", v), kw.get("B", 2),
+                                                   kw.get("H", 4), kw.get("d", 128), kw.get("S", 4096), kw.get("p", pp),
+                                                   kw.get("bound", 4095), ctypes.c_float(kw.get("scale", 0.0)),
+                                                   kw.get("o", o), kw.get("w", w), kw.get("wb", 0), None)
+    assert call() == 6                                           # every call here stops at a check: no launch
+    assert call(p=None) == 1 and call(p=pp + 2) == 3 and call(q=None) == 1 and call(o=None) == 1
+    assert call(bound=-1) == 2 and call(bound=4096) == 2 and call(B=65) == 4 and call(d=96) == 2
+    assert call(scale=-1.0) == 7 and call(k=k + 2) == 3
+    need = sb.attn_workspace_bytes(2, 4, 128, 4096)
+    assert call(wb=need - 1) == 6 and call(w=None, wb=need) == 6 and call(w=w + 64, wb=need) == 3

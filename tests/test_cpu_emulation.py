@@ -76,3 +76,10 @@ def test_layer_launch_under_asan(drivers, B, h, ln):
                                   (1, 1, 128, 1100, 1030), (2, 1, 64, 600, 520), (1, 1, 128, 2600, 2570), (1, 2, 64, 1600, 1590)])
 def test_attention_decode_under_asan(drivers, case):
     run([drivers[2], *[str(v) for v in case]])
+
+
+# the same with one position per sequence (sbi_attn_decode_ragged); `pos` is the bound
+@pytest.mark.parametrize("case", [(5, 2, 64, 40, 17), (6, 1, 128, 1100, 1030), (7, 2, 64, 1600, 1590), (2, 1, 128, 300, 299),
+                                  (1, 1, 64, 4, 0)])
+def test_ragged_attention_decode_under_asan(drivers, case):
+    run([drivers[2], *[str(v) for v in case], "1"])

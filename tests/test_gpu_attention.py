@@ -84,3 +84,78 @@ def test_attention_special_cases(gpu):
     mean = (Vc[0, :, :pos].astype(np.float64).sum(axis=1) + qkv[0, 2].astype(np.float64)) / (pos + 1)
     ok, rep = orc.check_close(o[0].reshape(H, d), mean.astype(np.float16), ulps=2, abs_tol=1e-3)
     assert ok, rep
+
+
+# B, H, d, S, positions (one per sequence), bound handed to the call
+RAGGED = [
+    (4, 3, 128, 136, [135, 0, 17, 64], 135),
+    (8, 32, 128, 2048, [2047, 5, 1000, 256, 255, 1, 1999, 640], 2047),      # long and short sequences side by side
+    (5, 2, 64, 1200, [1100, 3, 700, 0, 512], 1150),                          # a bound above every position
+    (3, 40, 128, 520, [100, 511, 300], 511),
+    (64, 8, 64, 300, None, 299),                                             # drawn positions
+    (1, 1, 64, 8, [0], 0),
+]
+
+
+@pytest.mark.parametrize("B,H,d,S,pos,bound", RAGGED)
+def test_ragged_batch_matches_the_oracle_sequence_by_sequence(gpu, B, H, d, S, pos, bound):
+    """sbi_attn_decode_ragged: sequences of one batch at different lengths.  The oracle is the same
+    definition as for the common position, applied to each sequence with its own (a batch of one)."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    qkv, Kc, Vc = wl.make_attention_inputs(B, H, d, S, seed=B + H + S, config_id=510)
+    if pos is None:
+        pos = np.random.default_rng(B).integers(0, bound + 1, size=B).tolist()
+        pos[0], pos[1] = bound, 0
+    want = np.empty((B, H * d), dtype=np.float16)
+    K2, V2 = Kc.copy(), Vc.copy()
+    for b in range(B):
+        want[b:b + 1], K2[b:b + 1], V2[b:b + 1] = orc.attn_decode(qkv[b:b + 1], Kc[b:b + 1], Vc[b:b + 1], pos[b])
+    Kd, Vd = _dev(Kc, gpu), _dev(Vc, gpu)
+    pd = torch.tensor(pos, dtype=torch.int32, device=gpu)
+    ws = sb.new_workspace(sb.attn_workspace_bytes(B, H, d, S), gpu)
+    first = None
+    for rep in range(2):
+        out = sb.attn_decode_ragged(_dev(qkv, gpu), Kd, Vd, pd, bound, workspace=ws)
+        torch.cuda.synchronize()
+        if first is None:
+            first = out.clone()
+        assert torch.equal(out.view(torch.int16), first.view(torch.int16))
+    ok, rep = orc.check_close(first.cpu().numpy(), want, ulps=2, abs_tol=1e-3)
+    assert ok, rep
+    assert np.array_equal(Kd.cpu().numpy().view(np.uint16), K2.view(np.uint16))
+    assert np.array_equal(Vd.cpu().numpy().view(np.uint16), V2.view(np.uint16))
+    assert not ws[:256 * 1024].cpu().numpy().any()
+
+
+def test_ragged_call_with_equal_positions_is_the_common_call_bit_for_bit(gpu):
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    B, H, d, S, pos = 8, 32, 128, 1100, 1029
+    qkv, Kc, Vc = wl.make_attention_inputs(B, H, d, S, seed=3, config_id=511)
+    a = sb.attn_decode(_dev(qkv, gpu), _dev(Kc, gpu), _dev(Vc, gpu), pos)
+    pd = torch.full((B,), pos, dtype=torch.int32, device=gpu)
+    b = sb.attn_decode_ragged(_dev(qkv, gpu), _dev(Kc, gpu), _dev(Vc, gpu), pd, pos)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_ragged_positions_outside_the_bound_are_forced_into_it(gpu):
+    """The host cannot see the device-side positions; the kernel forces an entry outside 0 .. bound to
+    the nearer end, so the call stays inside the caches whatever the array holds."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    B, H, d, S, bound = 4, 2, 64, 96, 60
+    qkv, Kc, Vc = wl.make_attention_inputs(B, H, d, S, seed=4, config_id=512)
+    given, effective = [61, -1, 2 ** 31 - 1, 30], [60, 0, 60, 30]
+    want = np.empty((B, H * d), dtype=np.float16)
+    K2, V2 = Kc.copy(), Vc.copy()
+    for b in range(B):
+        want[b:b + 1], K2[b:b + 1], V2[b:b + 1] = orc.attn_decode(qkv[b:b + 1], Kc[b:b + 1], Vc[b:b + 1], effective[b])
+    Kd, Vd = _dev(Kc, gpu), _dev(Vc, gpu)
+    out = sb.attn_decode_ragged(_dev(qkv, gpu), Kd, Vd, torch.tensor(given, dtype=torch.int32, device=gpu), bound)
+    torch.cuda.synchronize()
+    ok, rep = orc.check_close(out.cpu().numpy(), want, ulps=2, abs_tol=1e-3)
+    assert ok, rep
+    assert np.array_equal(Kd.cpu().numpy().view(np.uint16), K2.view(np.uint16))
+    assert np.array_equal(Vd.cpu().numpy().view(np.uint16), V2.view(np.uint16))
