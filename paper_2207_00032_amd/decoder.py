@@ -63,14 +63,19 @@ class DecoderLayer:
                             torch.empty((B, f), **half), torch.empty((B, h), **half),
                             sb.new_workspace(self.workspace_bytes(B, max_seq), device))
 
-    def step(self, x, pos, st):
-        """x fp16 [B,h]: the layer's input for the token at position pos.  Returns st.y [B,h]."""
+    def step(self, x, pos, st, pos_bound=None):
+        """x fp16 [B,h]: the layer's input for the token at position pos.  Returns st.y [B,h].
+        pos: one position for the whole batch (int), or an int32 device tensor [B] with one position
+        per sequence together with pos_bound >= every entry (a batch of sequences of different lengths)."""
         h, f = self.h, self.f
         B = x.shape[0]
         ws = st.workspace
         sb.gemm(self.Wqkv, h, 3 * h, x, self.bqkv, None, "bias", out=st.qkv.view(B, 3 * h), workspace=ws,
                 layernorm=self.ln1)
-        sb.attn_decode(st.qkv, st.k_cache, st.v_cache, pos, out=st.ctx, workspace=ws)
+        if pos_bound is None:
+            sb.attn_decode(st.qkv, st.k_cache, st.v_cache, pos, out=st.ctx, workspace=ws)
+        else:
+            sb.attn_decode_ragged(st.qkv, st.k_cache, st.v_cache, pos, pos_bound, out=st.ctx, workspace=ws)
         sb.gemm(self.Wout, h, h, st.ctx, self.bout, x, "bias_residual", out=st.x2, workspace=ws,
                 moments_out=st.moments)
         sb.gemm(self.Wffn1, h, f, st.x2, self.bffn1, None, "bias_gelu", out=st.f, workspace=ws,

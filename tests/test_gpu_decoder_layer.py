@@ -96,3 +96,50 @@ def test_decoder_steps_under_graph_replay(gpu):
             (st_g.y.float() * 2).sum().item()              # unrelated eager work between replays
         assert torch.equal(st_g.k_cache.view(torch.int16), st_e.k_cache.view(torch.int16))
         xd = want                                          # the next token's input: this step's output
+
+
+def test_ragged_decoder_steps_from_one_graph(gpu):
+    """Sequences of different lengths (sbi_attn_decode_ragged inside the step).  The positions live on
+    the device, so ONE captured graph serves consecutive tokens: between replays only the position
+    array is advanced.  Every replay's attention stage is checked against the oracle sequence by
+    sequence on the GPU's own QKV rows, the caches bit for bit, the output against an eager twin."""
+    import torch
+    h, heads, f, B, S, bound = 512, 4, 2048, 3, 80, 70
+    d = h // heads
+    layer, hw, x, Kc, Vc = _make(gpu, h, heads, f, B, S, seed=11)
+    xd = torch.from_numpy(x).to(gpu)
+    st_e = layer.new_state(B, S, gpu, torch.from_numpy(Kc).to(gpu), torch.from_numpy(Vc).to(gpu))
+    st_g = layer.new_state(B, S, gpu, torch.from_numpy(Kc).to(gpu), torch.from_numpy(Vc).to(gpu))
+    pos = [60, 0, 33]
+    pos_g = torch.tensor(pos, dtype=torch.int32, device=gpu)
+    x_g = xd.clone()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    warm = layer.new_state(B, S, gpu)                      # the warm-up and the capture run must not touch st_g's caches
+    with torch.cuda.stream(side):
+        layer.step(x_g, pos_g, warm, pos_bound=bound)
+        side.synchronize()
+    keep = {k: getattr(st_g, k) for k in ("k_cache", "v_cache")}
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            layer.step(x_g, pos_g, st_g, pos_bound=bound)
+    Ko, Vo = Kc, Vc
+    for token in range(3):
+        want = layer.step(xd, torch.tensor(pos, dtype=torch.int32, device=gpu), st_e, pos_bound=bound).clone()
+        x_g.copy_(xd)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(st_g.y.view(torch.int16), want.view(torch.int16)), token
+        qkv = st_g.qkv.cpu().numpy()
+        ctx = st_g.ctx.cpu().numpy()
+        Kn, Vn = Ko.copy(), Vo.copy()
+        for b in range(B):
+            w, Kn[b:b + 1], Vn[b:b + 1] = orc.attn_decode(qkv[b:b + 1], Ko[b:b + 1], Vo[b:b + 1], pos[b])
+            ok, rep = orc.check_close(ctx[b:b + 1], w, ulps=2, abs_tol=1e-3)
+            assert ok, (token, b, rep)
+        Ko, Vo = Kn, Vn
+        assert np.array_equal(keep["k_cache"].cpu().numpy().view(np.uint16), Ko.view(np.uint16))
+        assert np.array_equal(keep["v_cache"].cpu().numpy().view(np.uint16), Vo.view(np.uint16))
+        pos = [p + 1 for p in pos]
+        pos_g.add_(1)                                      # eager work between the replays
+        xd = want
