@@ -42,8 +42,9 @@ __device__ __forceinline__ float attn_load(const float* src)
                                                        __HIP_MEMORY_SCOPE_AGENT));
 }
 
-// D: head dimension; U: positions in flight per lane group; NT: threads per block
-template <int D, int U, int NT>
+// D: head dimension; U: positions in flight per lane group; NT: threads per block; AHEAD: a second
+// set of U positions is requested while the first is consumed
+template <int D, int U, int NT, bool AHEAD>
 __global__ __launch_bounds__(NT) void sbi_attn_decode_kernel(const AttnParams p)
 {
     constexpr int LPP = D / 8;           // lanes per cached position
@@ -86,33 +87,86 @@ __global__ __launch_bounds__(NT) void sbi_attn_decode_kernel(const AttnParams p)
     for (int e = 0; e < 8; ++e) o[e] = 0.f;
 
     const int iters = j1 > j0 ? (j1 - j0 + NG * U - 1) / (NG * U) : 0;   // the same for every thread of the block
-    for (int it = 0; it < iters; ++it) {
-        u32x4 kk[U], vv[U];
+    // AHEAD: two register sets of U positions each; the loads of round it + 1 are issued before
+    // round it is consumed.  That is for the ragged batch, whose long sequences' blocks end up
+    // alone on the chip and then stream at the rate their own requests in flight allow (8 x 32
+    // heads, 256 .. 2048 positions: 37.5 -> 34.5 us; up to 8192: 128 -> 113 us).  A batch of equal
+    // lengths keeps every CU busy to the end; there the 36 extra registers only cost resident
+    // blocks (8 x 32 heads at 2048 positions: 44.3 -> 46.4 us), so it runs the plain loop.
+    // (The products and sums of both loops are written as explicit fused operations: left to the
+    // compiler's contraction, the two variants rounded differently.)
+    struct Rows { u32x4 k[U], v[U]; };
+    auto fetch = [&](Rows& r, int it) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = min(j0 + (it * U + u) * NG + grp, last_cached);
-            kk[u] = __builtin_nontemporal_load(K + (int64_t)j * LPP);
-            vv[u] = __builtin_nontemporal_load(V + (int64_t)j * LPP);
+            r.k[u] = __builtin_nontemporal_load(K + (int64_t)j * LPP);
+            r.v[u] = __builtin_nontemporal_load(V + (int64_t)j * LPP);
         }
+    };
+    auto consume = [&](const Rows& r, int it) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = j0 + (it * U + u) * NG + grp;
             const bool is_new = (j == pos);
-            const half8 kh = __builtin_bit_cast(half8, is_new ? knew : kk[u]);
-            const half8 vh = __builtin_bit_cast(half8, is_new ? vnew : vv[u]);
+            const half8 kh = __builtin_bit_cast(half8, is_new ? knew : r.k[u]);
+            const half8 vh = __builtin_bit_cast(half8, is_new ? vnew : r.v[u]);
             float s = 0.f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) s += qf[e] * (float)kh[e];
+            for (int e = 0; e < 8; ++e) s = fmaf(qf[e], (float)kh[e], s);
 #pragma unroll
             for (int msk = LPP / 2; msk >= 1; msk >>= 1) s += __shfl_xor(s, msk, 64);   // stays inside the lane group
             if (j < j1) {
                 const float m_new = fmaxf(m, s);
                 const float alpha = exp2f(m - m_new);
                 const float w = exp2f(s - m_new);
-                l = l * alpha + w;
+                l = fmaf(l, alpha, w);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) o[e] = o[e] * alpha + w * (float)vh[e];
+                for (int e = 0; e < 8; ++e) o[e] = fmaf(w, (float)vh[e], o[e] * alpha);
                 m = m_new;
+            }
+        }
+    };
+    if constexpr (AHEAD) {
+        Rows ra, rb;
+        if (iters > 0) fetch(ra, 0);
+        for (int it = 0; it < iters; it += 2) {
+            if (it + 1 < iters) fetch(rb, it + 1);
+            consume(ra, it);
+            if (it + 1 < iters) {
+                if (it + 2 < iters) fetch(ra, it + 2);
+                consume(rb, it + 1);
+            }
+        }
+    } else {
+        for (int it = 0; it < iters; ++it) {
+            u32x4 kk[U], vv[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int j = min(j0 + (it * U + u) * NG + grp, last_cached);
+                kk[u] = __builtin_nontemporal_load(K + (int64_t)j * LPP);
+                vv[u] = __builtin_nontemporal_load(V + (int64_t)j * LPP);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int j = j0 + (it * U + u) * NG + grp;
+                const bool is_new = (j == pos);
+                const half8 kh = __builtin_bit_cast(half8, is_new ? knew : kk[u]);
+                const half8 vh = __builtin_bit_cast(half8, is_new ? vnew : vv[u]);
+                float s = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s = fmaf(qf[e], (float)kh[e], s);
+#pragma unroll
+                for (int msk = LPP / 2; msk >= 1; msk >>= 1) s += __shfl_xor(s, msk, 64);   // stays inside the lane group
+                if (j < j1) {
+                    const float m_new = fmaxf(m, s);
+                    const float alpha = exp2f(m - m_new);
+                    const float w = exp2f(s - m_new);
+                    l = fmaf(l, alpha, w);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] = fmaf(w, (float)vh[e], o[e] * alpha);
+                    m = m_new;
+                }
             }
         }
     }
@@ -215,11 +269,18 @@ int launch_attn_decode(const void* qkv, void* Kc, void* Vc, int64_t B, int H, in
     // the second half of a bigger block would mostly idle (B = 64, 32 heads, 136 positions: 28 us
     // with 256 threads, 31 us with 512; 8 x 32 heads at 2048 positions: 47.8 us against 44.9 us).
     const bool small_blocks = p.per_split <= 192 && (int64_t)B * H * nsplit > 512;
-    if (D == 128 && small_blocks) hipLaunchKernelGGL((sbi_attn_decode_kernel<128, 4, 256>), grid, dim3(256), 0, st, p);
-    else if (D == 128) hipLaunchKernelGGL((sbi_attn_decode_kernel<128, 4, 512>), grid, dim3(512), 0, st, p);
-    else if (D == 64 && small_blocks) hipLaunchKernelGGL((sbi_attn_decode_kernel<64, 4, 256>), grid, dim3(256), 0, st, p);
-    else if (D == 64) hipLaunchKernelGGL((sbi_attn_decode_kernel<64, 4, 512>), grid, dim3(512), 0, st, p);
-    else return (int)hipErrorInvalidValue;
+    if (D != 64 && D != 128) return (int)hipErrorInvalidValue;
+    const int variant = (D == 128 ? 4 : 0) + (small_blocks ? 2 : 0) + (pos_of ? 1 : 0);
+    switch (variant) {
+        case 0: hipLaunchKernelGGL((sbi_attn_decode_kernel<64, 4, 512, false>), grid, dim3(512), 0, st, p); break;
+        case 1: hipLaunchKernelGGL((sbi_attn_decode_kernel<64, 4, 512, true>), grid, dim3(512), 0, st, p); break;
+        case 2: hipLaunchKernelGGL((sbi_attn_decode_kernel<64, 4, 256, false>), grid, dim3(256), 0, st, p); break;
+        case 3: hipLaunchKernelGGL((sbi_attn_decode_kernel<64, 4, 256, true>), grid, dim3(256), 0, st, p); break;
+        case 4: hipLaunchKernelGGL((sbi_attn_decode_kernel<128, 4, 512, false>), grid, dim3(512), 0, st, p); break;
+        case 5: hipLaunchKernelGGL((sbi_attn_decode_kernel<128, 4, 512, true>), grid, dim3(512), 0, st, p); break;
+        case 6: hipLaunchKernelGGL((sbi_attn_decode_kernel<128, 4, 256, false>), grid, dim3(256), 0, st, p); break;
+        case 7: hipLaunchKernelGGL((sbi_attn_decode_kernel<128, 4, 256, true>), grid, dim3(256), 0, st, p); break;
+    }
     return (int)hipGetLastError();
 }
 
