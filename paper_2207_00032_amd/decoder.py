@@ -5,7 +5,8 @@ calls the paper's Deep-Fusion draws for small batches (Sec. III-D, Fig. 1(c): fo
   2. transposition + attention over the KV cache                sbi_attn_decode
   3. attention-output GeMM + bias + residual                    sbi_gemm_moments (leaves the row moments)
      post-attention layer-norm + FFN1 GeMM + bias + GeLU        sbi_gemm_ln (statistics from the moments)
-  4. FFN2 GeMM + bias + residual                                sbi_gemm
+  4. FFN2 GeMM + bias + residual                                sbi_gemm_moments (leaves the row moments
+                                                                of the layer's output for the next layer's step 1)
 
 Sequencing only: every value is produced by the kernels behind those calls.  All buffers are
 allocated once (`DecoderLayer.__init__`, `new_state`), so a step allocates nothing and can be
@@ -28,6 +29,7 @@ class DecoderState:
     f: object
     y: object
     workspace: object
+    y_moments: object = None      # per-panel row moments of y: the next layer's input layer-norm can start from them
 
 
 class DecoderLayer:
@@ -61,17 +63,20 @@ class DecoderLayer:
                             torch.empty((B, h), **half), torch.empty((B, h), **half),
                             torch.empty((B, h // 64, 2), dtype=torch.float32, device=device),
                             torch.empty((B, f), **half), torch.empty((B, h), **half),
-                            sb.new_workspace(self.workspace_bytes(B, max_seq), device))
+                            sb.new_workspace(self.workspace_bytes(B, max_seq), device),
+                            torch.empty((B, h // 64, 2), dtype=torch.float32, device=device))
 
-    def step(self, x, pos, st, pos_bound=None):
+    def step(self, x, pos, st, pos_bound=None, x_moments=None):
         """x fp16 [B,h]: the layer's input for the token at position pos.  Returns st.y [B,h].
         pos: one position for the whole batch (int), or an int32 device tensor [B] with one position
-        per sequence together with pos_bound >= every entry (a batch of sequences of different lengths)."""
+        per sequence together with pos_bound >= every entry (a batch of sequences of different lengths).
+        x_moments: the previous layer's st.y_moments when x is that layer's st.y - the input layer-norm
+        then takes its statistics from them instead of reading the rows again."""
         h, f = self.h, self.f
         B = x.shape[0]
         ws = st.workspace
         sb.gemm(self.Wqkv, h, 3 * h, x, self.bqkv, None, "bias", out=st.qkv.view(B, 3 * h), workspace=ws,
-                layernorm=self.ln1)
+                layernorm=self.ln1, moments_in=x_moments)
         if pos_bound is None:
             sb.attn_decode(st.qkv, st.k_cache, st.v_cache, pos, out=st.ctx, workspace=ws)
         else:
@@ -80,5 +85,6 @@ class DecoderLayer:
                 moments_out=st.moments)
         sb.gemm(self.Wffn1, h, f, st.x2, self.bffn1, None, "bias_gelu", out=st.f, workspace=ws,
                 layernorm=self.ln2, moments_in=st.moments)
-        sb.gemm(self.Wffn2, f, h, st.f, self.bffn2, st.x2, "bias_residual", out=st.y, workspace=ws)
+        sb.gemm(self.Wffn2, f, h, st.f, self.bffn2, st.x2, "bias_residual", out=st.y, workspace=ws,
+                moments_out=st.y_moments)
         return st.y

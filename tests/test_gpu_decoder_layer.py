@@ -143,3 +143,30 @@ def test_ragged_decoder_steps_from_one_graph(gpu):
         pos = [p + 1 for p in pos]
         pos_g.add_(1)                                      # eager work between the replays
         xd = want
+
+
+def test_two_layers_chained_through_the_output_moments(gpu):
+    """Layer 2's input layer-norm takes its row statistics from the moments layer 1's FFN2 epilogue left
+    (no second pass over the rows).  Its QKV stage is checked against the oracle fed with layer 1's
+    GPU output, and the two-layer result against the same chain run with recomputed statistics."""
+    import torch
+    h, heads, f, B, S, pos = 1024, 8, 4096, 5, 96, 70
+    layer, hw, x, Kc, Vc = _make(gpu, h, heads, f, B, S, seed=21)
+    xd = torch.from_numpy(x).to(gpu)
+    mk = lambda: layer.new_state(B, S, gpu, torch.from_numpy(Kc).to(gpu), torch.from_numpy(Vc).to(gpu))
+    s1, s2, s2_ref = mk(), mk(), mk()
+    y1 = layer.step(xd, pos, s1)
+    y2 = layer.step(y1, pos, s2, x_moments=s1.y_moments)
+    y2_ref = layer.step(y1, pos, s2_ref)
+    torch.cuda.synchronize()
+    y1h = y1.cpu().numpy()
+    want_qkv = orc.gemm(orc.layernorm(y1h, hw["g1"], hw["be1"], EPS), hw["Wqkv"], hw["bqkv"], None, epi=orc.EPI_BIAS)
+    ok, rep = orc.check_close(s2.qkv.cpu().numpy().reshape(B, 3 * h), want_qkv, ulps=2, abs_tol=1e-3)
+    assert ok, rep
+    # moments of y1 against their definition (per 64-feature panel: mean and sum of squared deviations)
+    m = s1.y_moments.cpu().numpy().astype(np.float64)
+    panels = y1h.astype(np.float64).reshape(B, h // 64, 64)
+    assert np.allclose(m[..., 0], panels.mean(-1), rtol=0, atol=2e-3)
+    assert np.allclose(m[..., 1], ((panels - panels.mean(-1, keepdims=True)) ** 2).sum(-1), rtol=2e-3, atol=1e-2)
+    ok, rep = orc.check_close(y2.cpu().numpy(), y2_ref.cpu().numpy(), ulps=8, abs_tol=8e-3)
+    assert ok, rep
