@@ -195,8 +195,9 @@ __global__ __launch_bounds__(NT) void sbi_attn_decode_kernel(const AttnParams p)
     float* mine = p.partials + ((int64_t)bh * p.nsplit + split) * (D + 2);
     if (tid < D) attn_store(mine + tid, O);
     if (tid == 0) { attn_store(mine + D, M); attn_store(mine + D + 1, Lsum); }
+    wait_stores_acknowledged();                // this wave's partial results have reached memory before the
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();
+    __syncthreads();                           // block is counted
     if (tid == 0) {
         const unsigned int old = __hip_atomic_fetch_add(p.counters + bh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_flag = (old == (unsigned int)(p.nsplit - 1));

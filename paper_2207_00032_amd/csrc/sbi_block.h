@@ -776,16 +776,19 @@ __device__ __forceinline__ void reduce_rows(const GemmParams& p, const float* re
 //
 // Coherence across the chip's eight L2 caches without cache-wide flushes: partial sums are
 // written and read with device-scope accesses (they go to, and come from, the memory-side
-// coherence point, never a stale or dirty line of one L2); a block waits for its stores to
-// be acknowledged before its arrival is counted, and the last block reads only after it
-// has seen the full count.  A device-wide release fence per block would write back the whole
-// L2 and serialise the grid (measured: about 0.1 us per block).
+// coherence point, never a stale or dirty line of one L2).  Order: every wave waits until its own
+// partial stores have been acknowledged (wait_stores_acknowledged), the block's barrier collects
+// all waves, and only then one thread counts the arrival; the last block issues its loads after
+// it has read the full count back (the atomic's return value decides the branch, and a barrier
+// separates that branch from the loads).  A device-wide release fence per block would write back
+// the whole L2 and serialise the grid (measured: about 0.1 us per block).
 template <int NT, bool I8 = false>
 __device__ __forceinline__ void finish_split_k(const GemmParams& p, int panel, int tid, int* s_flag,
                                                const floatx2* stats = nullptr)
 {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // wait for this wave's partial stores
-    __syncthreads();
+    wait_stores_acknowledged();                               // this wave's partial sums have reached memory
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();                                          // ... and so have every other wave's of the block
     if (tid == 0) {
         const unsigned int old = __hip_atomic_fetch_add(p.counters + panel, 1u, __ATOMIC_RELAXED,
                                                         __HIP_MEMORY_SCOPE_AGENT);

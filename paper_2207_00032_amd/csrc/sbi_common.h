@@ -39,6 +39,23 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 
 constexpr int kEpiBias = 1, kEpiGelu = 2, kEpiRes = 4;
 
+// Hand-over of partial results between blocks (split-K, attention position ranges): the producer
+// writes them with device-scope stores (write-through, they never sit dirty in one XCD's L2), then
+// calls this, then its arrival is counted with a device-scope atomic; the consumer reads them with
+// device-scope loads only after it has seen the full count.  What orders "partials visible" before
+// "arrival counted" is this wait: on gfx9-family targets loads and stores share one counter
+// (vmcnt), and a store leaves it only when the memory system has acknowledged the write.  It is
+// the s_waitcnt half of the device-scope release the compiler would emit; the other half, a
+// write-back of the whole L2, has nothing to write back here (no ordinary stores are handed over)
+// and was measured at twice the kernel time.  The empty statements on either side keep the compiler
+// from moving memory accesses across the wait.
+__device__ __forceinline__ void wait_stores_acknowledged()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0); expcnt and lgkmcnt fields at their maxima = not waited for
+    asm volatile("" ::: "memory");
+}
+
 // Pitch (in floats) of one row of the in-block reduction buffer: 64 columns + 4 so that
 // the 16 lanes of a group, which write 16-byte pieces of 16 different rows, hit distinct banks.
 constexpr int kRedPitch = 68;

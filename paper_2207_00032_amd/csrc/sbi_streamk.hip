@@ -264,7 +264,7 @@ __global__ __launch_bounds__(NW * 64) void sbi_streamk_kernel(const SkParams p)
     if (head_g < 0 && tail_g < 0) return;
 
     // ---- arrivals: all of this wave's partial tiles have been acknowledged before it is counted
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    wait_stores_acknowledged();
 #pragma unroll
     for (int which = 0; which < 2; ++which) {
         const int g = which == 0 ? head_g : tail_g;

@@ -94,12 +94,13 @@ def _normal_fp16(rng: np.random.Generator, shape, sigma: float) -> np.ndarray:
 
 def make_gemm_inputs(K: int, N: int, B: int, seed: int = 0, config_id: int = 0, gemm_id: int = 0,
                      outlier_channels: float = 0.0, outlier_scale: float = 1.0,
-                     want_bias: bool = True, want_residual: bool = True):
+                     want_bias: bool = True, want_residual: bool = True, outlier_rows: float = 0.0):
     """Draw (W[K,N], bias[N], X[B,K], R[B,N]) as fp16, always in that order.
 
     Weights/bias sigma = 0.02, activations/residual sigma = 1.  When outlier_channels > 0,
     ceil(outlier_channels*K) input channels (columns of X) picked by the same generator are
-    multiplied by outlier_scale before the fp16 rounding.
+    multiplied by outlier_scale before the fp16 rounding.  outlier_rows > 0 is the other reading
+    of "1 % of rows": ceil(outlier_rows*B) batch rows of X, picked after the channels, are scaled.
     """
     rng = np.random.default_rng(np.random.SeedSequence([seed, config_id, gemm_id]))
     W = _normal_fp16(rng, (K, N), 0.02)
@@ -109,6 +110,9 @@ def make_gemm_inputs(K: int, N: int, B: int, seed: int = 0, config_id: int = 0, 
         n_out = int(np.ceil(outlier_channels * K))
         ch = rng.choice(K, size=n_out, replace=False)
         Xf[:, ch] *= outlier_scale
+    if outlier_rows > 0.0:
+        rows = rng.choice(B, size=int(np.ceil(outlier_rows * B)), replace=False)
+        Xf[rows, :] *= outlier_scale
     X = Xf.astype(np.float16)
     R = _normal_fp16(rng, (B, N), 1.0)
     assert np.isfinite(W.astype(np.float32)).all() and np.isfinite(X.astype(np.float32)).all()

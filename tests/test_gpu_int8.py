@@ -170,6 +170,10 @@ def test_int8_config2_h4096_gemms(gpu, gi, B):
     from paper_2207_00032_amd import binding as sb
     spec, W, bias, X, R = wl.make_config_gemm(2, gi, seed=0, B=B)
     Wl, sw_d, Wq, sw = prepare(gpu, W)
+    # the GPU's weight codes and scales are the oracle's, bit for bit, before they are handed to it
+    Wq_ref, sw_ref = orc.quantize_columns(W)
+    assert np.array_equal(Wq, Wq_ref) and np.array_equal(sw.view(np.uint32), sw_ref.view(np.uint32))
+    assert np.array_equal(Wl.cpu().numpy()[256:].view(np.int8), orc.layout_weights_i8(Wq_ref))
     epi = {wl.NONE: "none", wl.BIAS: "bias", wl.BIAS_GELU: "bias_gelu", wl.BIAS_RESIDUAL: "bias_residual",
            wl.GELU: "gelu", wl.RESIDUAL: "residual"}[spec.epilogue]
     Y = sb.gemm_i8(Wl, sw_d, spec.K, spec.N, _dev(X, gpu), _dev(bias, gpu) if "bias" in epi else None,

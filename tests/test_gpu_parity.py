@@ -240,16 +240,103 @@ def test_config3_h12288_tp_slice(gpu, gi):
     _config_case(gpu, 3, gi, 0, wl.CONFIGS[3].batches)
 
 
-@pytest.mark.parametrize("gi", [1, 3])
+@pytest.mark.parametrize("gi", [0, 1, 2, 3])
 def test_config4_h12288_full_size(gpu, gi):
-    """Full-size matrices of the unsliced h=12288 layer (attention output and FFN2: the
-    longest K), every output element compared."""
+    """Full-size matrices of the unsliced h=12288 layer (QKV [12288,36864], attention output,
+    FFN1 [12288,49152] + GeLU, FFN2 [49152,12288]), every output element compared."""
     _config_case(gpu, 4, gi, 0, wl.CONFIGS[4].batches)
 
 
 def test_config5_crossover_sweep_with_outliers(gpu):
+    """The h=8192 FFN1 over the whole batch sweep, 1 % of the input channels scaled by 50, on the
+    dispatcher's own pick and on every forced path; then the literal reading of "1 % of rows" at
+    B = 64 (one batch row of X scaled by 50) on the same weights."""
     from paper_2207_00032_amd import binding as sb
-    _config_case(gpu, 5, 0, 0, wl.CONFIGS[5].batches, [sb.PATH_STREAMK, sb.PATH_MFMA, sb.PATH_STREAM])
+    _config_case(gpu, 5, 0, 0, wl.CONFIGS[5].batches, [sb.PATH_AUTO, sb.PATH_STREAMK, sb.PATH_MFMA, sb.PATH_STREAM])
+    spec = wl.CONFIGS[5].gemms[0]
+    W, bias, X, R = wl.make_gemm_inputs(spec.K, spec.N, 64, 0, 5, 0, outlier_rows=0.01, outlier_scale=50.0)
+    assert (np.abs(X.astype(np.float32)).max(axis=1) > 60).sum() == 1      # exactly one scaled row
+    Wl = None
+    for path in (sb.PATH_AUTO, sb.PATH_MFMA):
+        Y, Wl = gpu_gemm(gpu, W, bias, X, R, spec.epilogue, Wl=Wl, path=path)
+        check(Y, W, bias, X, R, spec.epilogue, f"config 5, one row of 64 scaled by 50, path={path}")
+
+
+EPI_NAME = {wl.NONE: "none", wl.BIAS: "bias", wl.BIAS_GELU: "bias_gelu", wl.BIAS_RESIDUAL: "bias_residual",
+            wl.GELU: "gelu", wl.RESIDUAL: "residual"}
+
+
+@pytest.mark.parametrize("cfg_id", [3, 4])
+def test_layer_gemms_at_h12288_matches_oracle(gpu, cfg_id):
+    """sbi_layer_gemms on the h=12288 configurations (one GPU's tensor-parallel slice at B = 1, 4, 16;
+    the full 3.6 GB layer at B = 1, 8) with the configurations' own epilogues: the grouped launch
+    and the plan the dispatcher picks for it, every output element of all four GeMMs compared."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    cfg = wl.CONFIGS[cfg_id]
+    Bmax = max(cfg.batches)
+    Wls, host = [], []
+    for i, s in enumerate(cfg.gemms):
+        W, bias, X, R = wl.make_gemm_inputs(s.K, s.N, Bmax, seed=0, config_id=cfg_id, gemm_id=i)
+        Wls.append(sb.layout_weights(_dev(W, gpu)))
+        torch.cuda.synchronize()
+        host.append((W, bias, X, R))
+    epis = [EPI_NAME[s.epilogue] for s in cfg.gemms]
+    assert not any("residual" in e for e in epis)
+    biases = [_dev(d[1], gpu) if "bias" in e else None for d, e in zip(host, epis)]
+    g = cfg.gemms
+    L = sb.make_layer(*Wls, g[0].K, g[0].N, g[1].K, g[2].N, g[3].K, bqkv=biases[0], bout=biases[1],
+                      bffn1=biases[2], bffn2=biases[3], ffn1_gelu="gelu" in epis[2])
+    for B in cfg.batches:
+        ws = sb.new_workspace(sb.layer_workspace_bytes(L, B), gpu)
+        Xs = [_dev(d[2][:B], gpu) for d in host]
+        Ys = [torch.full((B, s.N), float("nan"), dtype=torch.float16, device=gpu) for s in g]
+        sb.layer_gemms(L, B, Xs[0], Xs[1], Xs[2], Xs[3], None, Ys[0], Ys[1], Ys[2], Ys[3], ws)
+        torch.cuda.synchronize()
+        for i, s in enumerate(g):
+            W, bias, X, _ = host[i]
+            check(Ys[i].cpu().numpy(), W, bias, X[:B], None, epis[i], f"config {cfg_id} layer launch {s.name} B={B}")
+        assert not ws[:256 * 1024].cpu().numpy().any()
+
+
+@pytest.mark.parametrize("B", [1, 5, 8, 24, 64])
+def test_split_k_hand_over_soak(gpu, B):
+    """Many split panels in flight at once, several split factors, one workspace reused by every call
+    (so a partial sum read before it was written would be the previous call's): every call must give
+    the bits of the first call of its shape, which is compared with the oracle.  Stops at the first
+    mismatch."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    K, N = 8192, 4096
+    W, bias, X, R = wl.make_gemm_inputs(K, N, B, seed=11, config_id=106)
+    Wd, Xd, bd, Rd = _dev(W, gpu), _dev(X, gpu), _dev(bias, gpu), _dev(R, gpu)
+    Wl = sb.layout_weights(Wd)
+    splits = [s for s in (2, 3, 4, 8, 16, 32) if _plan_ok(sb, B, K, N, s)]
+    assert len(splits) >= 4
+    ws = sb.new_workspace(max(sb.plan(B, K, N, sb.PATH_MFMA, s)["workspace_bytes"] for s in splits), gpu)
+    first = {}
+    for rep in range(12):
+        # the activations change from call to call, so stale partial sums could not go unnoticed
+        Xr = Xd if rep % 2 == 0 else (Xd * 0.5).contiguous()
+        for s in splits:
+            Y = sb.gemm(Wl, K, N, Xr, bd, Rd, "bias_residual", workspace=ws, path=sb.PATH_MFMA, split_k=s)
+            key = (s, rep % 2)
+            if key not in first:
+                torch.cuda.synchronize()
+                first[key] = Y.clone()
+                check(Y.cpu().numpy(), W, bias, Xr.cpu().numpy(), R, "bias_residual", f"soak B={B} S={s} rep={rep}")
+            else:
+                assert torch.equal(Y.view(torch.int16), first[key].view(torch.int16)), f"B={B} S={s} rep={rep}"
+    torch.cuda.synchronize()
+    assert not ws[:256 * 1024].cpu().numpy().any()
+
+
+def _plan_ok(sb, B, K, N, s):
+    try:
+        sb.plan(B, K, N, sb.PATH_MFMA, s)
+        return True
+    except sb.SbiError:
+        return False
 
 
 @pytest.mark.parametrize("cfg_id,B,chained", [(1, 4, True), (1, 1, False), (2, 8, False), (2, 3, True)])
