@@ -193,40 +193,49 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
         return SBI_OK;
     }
 
-    int nw = t.waves, depth = t.depth;
     const int pw = (t.panels == 2 && path == SBI_PATH_MFMA) ? 2 : 1;
     if (t.panels == 2 && path != SBI_PATH_MFMA) return SBI_ERR_TUNING;
-    if (nw == 0) nw = (B <= 32 && KS >= 32) ? 8 : 4;
-    if (depth == 0) depth = (B > 32 || pw == 2) ? 2 : 4;
-    bool depth_ok = depth == 4 || depth == 8 || (depth == 2 && path == SBI_PATH_MFMA);
-    if (pw == 2) depth_ok = (nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && (depth == 2 || (depth == 4 && B > 16)));
-    if ((nw != 4 && nw != 8) || !depth_ok) return SBI_ERR_TUNING;
-    if (ln && !((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))) return SBI_ERR_TUNING;
-    if (i8 && !(pw == 2 ? (nw == 8 && (depth == 2 || depth == 4)) : ((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))))
-        return SBI_ERR_TUNING;
-    int S = t.split_k;
-    if (S < 0) return SBI_ERR_TUNING;
-    if (S == 0) {
-        const int64_t smax = std::max<int64_t>(1, std::min<int64_t>(KS / nw, 64));
-        double best = 0.0;
-        for (int s = 1; s <= smax; ++s) {
-            const int64_t ksps = ceil_div(KS, s);
-            if (ceil_div(KS, ksps) != s) continue;          // same launch as a smaller s
-            const double c = split_cost(KS, P, B, s, nw);
-            if (S == 0 || c < best) { best = c; S = s; }
+    if (t.split_k < 0) return SBI_ERR_TUNING;
+    // Block shape: what the caller fixed stays; what it left open takes the preferred value first
+    // and, if that shape cannot stage its X chunks in LDS at this batch size, smaller ones.
+    const int pref_nw = (B <= 32 && KS >= 32) ? 8 : 4;
+    const int pref_depth = (B > 32 || pw == 2) ? 2 : 4;
+    const int nw_try[3] = {t.waves ? t.waves : pref_nw, 4, 8};
+    const int depth_try[3] = {t.depth ? t.depth : pref_depth, 2, 4};
+    int nw = 0, depth = 0, S = 0;
+    int64_t ksps = 0, PG = 0, kc = 0, lds = 0;
+    sbi_status why = SBI_ERR_TUNING;
+    bool found = false;
+    for (int a = 0; a < (t.waves ? 1 : 3) && !found; ++a)
+        for (int b = 0; b < (t.depth ? 1 : 3) && !found; ++b) {
+            if ((a > 0 && nw_try[a] == nw_try[0]) || (b > 0 && depth_try[b] == depth_try[0])) continue;
+            nw = nw_try[a]; depth = depth_try[b];
+            bool depth_ok = depth == 4 || depth == 8 || (depth == 2 && path == SBI_PATH_MFMA);
+            if (pw == 2) depth_ok = (nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && (depth == 2 || (depth == 4 && B > 16)));
+            if ((nw != 4 && nw != 8) || !depth_ok) continue;
+            if (ln && !((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))) continue;
+            if (i8 && !(pw == 2 ? (nw == 8 && (depth == 2 || depth == 4)) : ((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))))
+                continue;
+            S = t.split_k;
+            if (S == 0) {
+                const int64_t smax = std::max<int64_t>(1, std::min<int64_t>(KS / nw, 64));
+                double best = 0.0;
+                for (int s = 1; s <= smax; ++s) {
+                    const int64_t k = ceil_div(KS, s);
+                    if (ceil_div(KS, k) != s) continue;          // same launch as a smaller s
+                    const double c = split_cost(KS, P, B, s, nw);
+                    if (S == 0 || c < best) { best = c; S = s; }
+                }
+            }
+            if (S > KS) S = (int)KS;
+            ksps = ceil_div(KS, S);
+            S = (int)ceil_div(KS, ksps);                             // no empty blocks
+            PG = ceil_div(P, pw);                                    // panel groups = blocks per split
+            if (PG * S > (int64_t)0x7fffffff) { why = SBI_ERR_SHAPE; continue; }
+            found = chunking(B, ksps, round_ksteps(nw, depth, pw), nw, (pw == 2 || ln || i8) ? kMaxLdsWide : kMaxLds,
+                             (int64_t)nw * 16 * kRedPitch * 4, kc, lds, fl);
         }
-    }
-    if (S > KS) S = (int)KS;
-    const int64_t ksps = ceil_div(KS, S);
-    S = (int)ceil_div(KS, ksps);                             // no empty blocks
-    const int64_t PG = ceil_div(P, pw);                          // panel groups = blocks per split
-    if (PG * S > (int64_t)0x7fffffff) return SBI_ERR_SHAPE;
-
-    const int64_t wd = round_ksteps(nw, depth, pw);
-    int64_t kc = 0, lds = 0;
-    if (!chunking(B, ksps, wd, nw, (pw == 2 || ln || i8) ? kMaxLdsWide : kMaxLds, (int64_t)nw * 16 * kRedPitch * 4,
-                  kc, lds, fl))
-        return SBI_ERR_TUNING;
+    if (!found) return why;
 
     pl.ln = ln; pl.i8 = i8; pl.preq = preq; pl.prenorm = false; pl.xq_bytes = preq ? xq_bytes_of(B, K) : 0;
     pl.path = path; pl.nw = nw; pl.depth = depth; pl.S = S; pl.pw = pw;
