@@ -165,6 +165,28 @@ sbi_status sbi_gemm(const void* W_laid_out, int64_t K, int64_t N,
                     const void* bias, const void* residual, sbi_epilogue epi,
                     void* Y, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * sbi_gemm for callers that cannot provide (or allocate) a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same kernels,
+ * same launch plan and therefore the same bits as sbi_gemm; the arrival counters and cross-block
+ * partial sums live in a device array of SBI_STATIC_SCRATCH_BYTES that is part of the library's
+ * code object (every GPU the library runs on holds its own copy until the process ends).  The
+ * call allocates and frees nothing.
+ *   - A problem whose plan needs more than SBI_STATIC_SCRATCH_BYTES of workspace
+ *     (sbi_gemm_workspace_bytes(B,K,N); e.g. B = 64 with K = 131072, N = 12288) is refused with
+ *     SBI_ERR_WORKSPACE and nothing is enqueued: use sbi_gemm with a workspace for those.
+ *   - All calls on one GPU share that GPU's array: two calls that may run concurrently on one GPU
+ *     (different streams, different host threads) race on it.  Calls on one stream are safe.
+ *   - The first call on a GPU looks the array's address up and enqueues a small kernel on
+ *     `hip_stream` that clears the counters; make that first call outside graph capture.
+ * Arguments as for sbi_gemm.
+ */
+#define SBI_STATIC_SCRATCH_BYTES (16u << 20)
+sbi_status sbi_gemm_static(const void* W_laid_out, int64_t K, int64_t N,
+                           const void* X, int64_t B,
+                           const void* bias, const void* residual, sbi_epilogue epi,
+                           void* Y, void* hip_stream);
+
 /* sbi_gemm with explicit tuning (NULL = automatic).  Workspace need: see sbi_gemm_plan. */
 sbi_status sbi_gemm_ex(const void* W_laid_out, int64_t K, int64_t N,
                        const void* X, int64_t B,

@@ -33,7 +33,7 @@ EXPORTS = ["sbi_gemm_layout_bytes", "sbi_gemm_workspace_bytes", "sbi_gemm_layout
            "sbi_gemm_ln_workspace_bytes", "sbi_gemm_i8_layout_bytes", "sbi_gemm_i8_workspace_bytes",
            "sbi_gemm_i8_quantize_weights", "sbi_gemm_i8_layout_weights", "sbi_gemm_i8_layout_check", "sbi_gemm_i8",
            "sbi_gemm_moments", "sbi_attn_decode", "sbi_attn_decode_workspace_bytes",
-           "sbi_attn_decode_ragged"]
+           "sbi_attn_decode_ragged", "sbi_gemm_static"]
 
 
 class SbiError(RuntimeError):
@@ -103,6 +103,8 @@ def load():
     L.sbi_gemm_layout_check.argtypes = [vp, i64, i64, vp]
     L.sbi_gemm.restype = i32
     L.sbi_gemm.argtypes = [vp, i64, i64, vp, i64, vp, vp, i32, vp, vp, sz, vp]
+    L.sbi_gemm_static.restype = i32
+    L.sbi_gemm_static.argtypes = [vp, i64, i64, vp, i64, vp, vp, i32, vp, vp]
     L.sbi_gemm_ex.restype = i32
     L.sbi_gemm_ex.argtypes = [vp, i64, i64, vp, i64, vp, vp, i32, vp, vp, sz, vp, ctypes.POINTER(Tuning)]
     L.sbi_gemm_ln.restype = i32
@@ -377,6 +379,30 @@ def gemm(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, wor
         st = load().sbi_gemm_ex(_ptr(Wl), K, N, _ptr(X), B, _ptr(bias), _ptr(residual), int(epilogue),
                                 _ptr(out), ws_ptr, ws_len, _stream(), tune)
     _check(st, "sbi_gemm")
+    return out
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def gemm_static(Wl, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None):
+    """sbi_gemm_static: sbi_gemm with the workspace in the library's own device array.  `out` is
+    allocated here only if the caller passes none; the library call itself allocates nothing."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.is_contiguous()
+    B = X.shape[0]
+    if isinstance(epilogue, str):
+        epilogue = EPILOGUES[epilogue]
+    if out is None:
+        out = torch.empty((B, N), dtype=torch.float16, device=X.device)
+    _need(X, (B, K), "X")
+    _need(bias, (N,), "bias")
+    _need(residual, (B, N), "residual")
+    _need(out, (B, N), "out")
+    _need_bytes(Wl, layout_bytes(K, N), "laid-out weights")
+    st = load().sbi_gemm_static(_ptr(Wl), K, N, _ptr(X), B, _ptr(bias), _ptr(residual), int(epilogue),
+                                _ptr(out), _stream())
+    _check(st, "sbi_gemm_static")
     return out
 
 

@@ -7,7 +7,8 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
-#ifdef SBI_TRACE
+#include <mutex>
+#if defined(SBI_TRACE) || defined(SBI_DEV)
 #include <cstdio>
 #include <cstdlib>
 #endif
@@ -807,6 +808,67 @@ sbi_status sbi_gemm_ln(const void* W_laid_out, int64_t K, int64_t N,
                        const sbi_tuning* tuning)
 {
     if (!ln) return SBI_ERR_NULL;
+}  // extern "C"
+
+// ---- sbi_gemm_static: the workspace of sbi_gemm in device memory the library owns -------------
+// `scratch` is this translation unit's name for the array; in host code that name is a stand-in,
+// not a device address.  Each GPU holds its own copy at its own address, which scratch_of() asks
+// the runtime for once per device and keeps.
+namespace {
+
+static __device__ __align__(256) unsigned char scratch[SBI_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];                  // per device: address of its copy of `scratch`, or null
+std::mutex g_scratch_mutex;
+
+__global__ __launch_bounds__(256) void sbi_zero_words_kernel(unsigned int* dst, int n)
+{
+    for (int i = (int)(blockIdx.x * 256 + threadIdx.x); i < n; i += (int)(gridDim.x * 256)) dst[i] = 0u;
+}
+
+// Address of the current device's scratch array.  On the first call on a device the arrival
+// counters at its start are cleared on `st` (by a kernel, so that the call can sit in a captured
+// graph); after that every call leaves them at zero.  Calls no allocating routine.
+sbi_status scratch_of(hipStream_t st, void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SBI_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SBI_ERR_HIP;
+        hipLaunchKernelGGL(sbi_zero_words_kernel, dim3(64), dim3(256), 0, st,
+                           reinterpret_cast<unsigned int*>(ptr), (int)(kCounterBytes / 4));
+        if (hipGetLastError() != hipSuccess) return SBI_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SBI_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+sbi_status sbi_gemm_static(const void* W_laid_out, int64_t K, int64_t N,
+                           const void* X, int64_t B,
+                           const void* bias, const void* residual, sbi_epilogue epi,
+                           void* Y, void* hip_stream)
+{
+    // everything the call can refuse is refused before the device is touched
+    int flags = 0;
+    if (sbi_status s = check_gemm_args(W_laid_out, K, N, X, B, bias, residual, (int)epi, Y, flags)) return s;
+    Plan pl;
+    if (sbi_status s = make_plan(B, K, N, nullptr, pl)) return s;
+    if (pl.ws_bytes > (int64_t)SBI_STATIC_SCRATCH_BYTES) return SBI_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if (pl.ws_bytes > 0)
+        if (sbi_status s = scratch_of((hipStream_t)hip_stream, &ws)) return s;
+    return gemm_impl(W_laid_out, K, N, X, B, nullptr, bias, residual, epi, Y, ws, (size_t)pl.ws_bytes,
+                     hip_stream, nullptr);
+}
+
     if (tuning && tuning->int8) return SBI_ERR_TUNING;
     return gemm_impl(W_laid_out, K, N, X, B, ln, bias, residual, epi, Y, workspace, workspace_bytes,
                      hip_stream, tuning);

@@ -138,6 +138,22 @@ def test_gemm_argument_validation(lib):
     assert _gemm(lib, ws=FAKE + (3 << 30) + 64, ws_bytes=need) == 3
 
 
+def test_static_scratch_entry_point_validates_before_touching_the_device(lib):
+    """sbi_gemm_static: the same argument checks as sbi_gemm, and a problem whose plan needs more than
+    the library's scratch array is refused on the host (no GPU is present here, so any device call
+    would come back as SBI_ERR_HIP instead)."""
+    X, Y = FAKE + (1 << 30), FAKE + (2 << 30)
+    call = lambda W=FAKE, K=4096, N=4096, x=X, B=4, bias=None, res=None, epi=sb.EPI_NONE, y=Y: \
+        lib.sbi_gemm_static(W, K, N, x, B, bias, res, epi, y, None)
+    assert call(W=None) == 1 and call(x=None) == 1 and call(y=None) == 1
+    assert call(K=0) == 2 and call(B=65) == 4 and call(epi=sb.EPI_BIAS) == 7
+    assert call(W=FAKE + 128) == 3 and call(y=X + 4096) == 9
+    assert sb.workspace_bytes(64, 131072, 12288) > sb.STATIC_SCRATCH_BYTES
+    assert call(K=131072, N=12288, B=64, y=FAKE + (2 << 40)) == 6
+    text = open(HEADER).read()
+    assert re.search(r"#define SBI_STATIC_SCRATCH_BYTES \((\d+)u << 20\)", text).group(1) == str(sb.STATIC_SCRATCH_BYTES >> 20)
+
+
 def test_layout_argument_validation(lib):
     nb = sb.layout_bytes(64, 64)
     assert lib.sbi_gemm_layout_weights(None, 64, 64, FAKE, nb, None) == 1
