@@ -369,6 +369,9 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
         p.X = reinterpret_cast<const _Float16*>(ws + xq_off);     // the GeMM kernel reads those (X16 keeps the raw rows)
         p.ln = 0;
     }
+#ifdef SBI_DEV
+    if (const char* e = getenv("SBI_ABLATE")) p.flags |= (int)strtol(e, nullptr, 0) << 8;      // development: switch parts of the kernel off
+#endif
 #ifdef SBI_TRACE
     p.trace = getenv("SBI_TRACE_PTR") ? reinterpret_cast<unsigned long long*>(strtoull(getenv("SBI_TRACE_PTR"), nullptr, 16)) : nullptr;
 #endif
@@ -455,6 +458,8 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
                              bool i8)
 {
     if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
+    for (int g = 0; g < G; ++g)
+        if (sbi_status s = check_shape(Ks[g], Ns[g])) return s;
     // layer-norm: inside the GeMM blocks for the smallest batches, as a pass of its own otherwise
     double launch_bytes = 0.0;
     for (int g = 0; g < G; ++g) launch_bytes += 2.0 * (double)Ks[g] * (double)Ns[g];
@@ -476,8 +481,8 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
     // (waves, depth, panels per block) candidates; two-panel blocks only pay off for B > 16
     // (ties go to the earlier shape: the measured order at equal modelled cost - the fp16 kernels do
     // best with the shallow ring, the INT8 kernel with the deep one)
-    const int shapes_f16[5][3] = {{4, 2, 1}, {8, 4, 1}, {4, 4, 1}, {8, 4, 2}, {8, 2, 2}};   // (8, 4, 2): two wave groups
-    const int shapes_i8[5][3] = {{4, 4, 1}, {8, 4, 1}, {4, 2, 1}, {8, 4, 2}, {8, 2, 2}};
+    const int shapes_f16[6][3] = {{4, 2, 1}, {8, 4, 1}, {4, 4, 1}, {8, 4, 2}, {8, 2, 2}, {8, 2, 1}};   // (8, 4, 2): two wave groups
+    const int shapes_i8[6][3] = {{4, 4, 1}, {8, 4, 1}, {4, 2, 1}, {8, 4, 2}, {8, 2, 2}, {0, 0, 0}};
     const auto& shapes = i8 ? shapes_i8 : shapes_f16;
 
     int best_nw = 0, best_depth = 0, best_pw = 1;
@@ -485,6 +490,9 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
     double best = 0.0;
     for (const auto& shp : shapes) {
         const int nw = shp[0], depth = shp[1], pw = shp[2];
+        // 8 waves with the shallow ring, one panel: measured ahead only for grouped launches of up to 16
+        // rows (below); no layer-norm variant of it exists
+        if (nw == 0 || ((ln || mb > 1 || G == 1) && nw == 8 && depth == 2 && pw == 1)) continue;
         // INT8 (from pre-quantised codes at these batch sizes): measured ahead only above 32 rows
         if (pw == 2 && (mb < 2 || ln || (i8 && mb < 3))) continue;
         const int64_t wd = round_ksteps(nw, depth, pw);
@@ -499,7 +507,7 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
                 const int64_t T = round_up(ceil_div(maxKS, smax), wd);
                 if (T == lastT) continue;
                 lastT = T;
-                int64_t blocks = 0, work = 0, lds = red_bytes, chunks = 1;
+                int64_t blocks = 0, work = 0, lds = red_bytes, chunks = 1, longest = 0, nsplit = 0;
                 double partial = 0.0;
                 bool ok = true, slow_stage = false;   // slow: a chunk needs a second staging pass
                 for (int g = 0; g < G && ok; ++g) {
@@ -510,10 +518,12 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
                     if (!ok) break;
                     blocks += ceil_div(P[g], pw) * S;
                     work += ceil_div(P[g], pw) * S * ksps * pw;
+                    longest = std::max(longest, ksps * pw);
                     lds = std::max(lds, l);
                     chunks = std::max(chunks, ceil_div(ksps, kc));
                     if (ceil_div(ksps, kc) > 1 && kc * (B + (ln ? 2 : 0)) * 64 > (int64_t)nw * ((i8 && !preq) ? 2048 : 4096)) slow_stage = true;
                     if (S > 1) partial += (double)(P[g] * S) * (double)B * 512.0;
+                    if (S > 1) ++nsplit;
                 }
                 if (!ok) continue;
                 const int64_t fit = std::max<int64_t>(1, std::min<int64_t>(kLdsPerCU / lds,
@@ -547,10 +557,27 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
                 // Long single-resident blocks of large batches (384 blocks on 256 CUs): the CUs that hold
                 // fewer blocks than the busiest one leave it more of the bandwidth - halfway between the
                 // busiest CU's count and the average (h=4096 layer at B = 64: 384 blocks 90 us, 768 blocks 107 us)
+                // When a launch holds more blocks than the chip has room for, several to a CU, blocks start as
+                // others end and every CU stays busy to the end: what counts then is the average number of
+                // blocks per CU, not the busiest CU's (h=4096 layer, B = 1..16: 640 blocks of 8 waves, two
+                // resident per CU, 61.4-62.0 us; 768 blocks of 4 waves, all resident, 62.3-64.1 us).
+                // (measured for the plain fp16 kernel's 8-wave, depth-2 blocks only; the other shapes keep the
+                // busiest CU's count)
+                // and for launches in which at most one problem is split: with the h=12288 tensor-parallel slice,
+                // whose QKV and FFN1 are both split, the same shape is behind by up to 5 %)
+                const bool rolling = !ln && !i8 && nw == 8 && depth == 2 && pw == 1 && nsplit <= 1 && fit >= 2 && blocks > fit * kNumCU;
+                if (nw == 8 && depth == 2 && pw == 1 && !rolling) continue;     // this shape was only measured ahead when rolling
                 const double eff_blocks = (conc == 1 && mb >= 2)
-                    ? 0.5 * ((double)per_cu_blocks + std::max(1.0, (double)blocks / kNumCU)) : (double)per_cu_blocks;
+                    ? 0.5 * ((double)per_cu_blocks + std::max(1.0, (double)blocks / kNumCU))
+                    : rolling ? (double)blocks / kNumCU : (double)per_cu_blocks;
                 double cost = eff_blocks * (stream + overhead) * (busy >= 0.75 ? 1.0 : 0.75 / busy) +
                               partial / kNumCU / 4096.0 + (conc == 1 ? 10.0 : 4.0) * ln_passes;
+                // no launch ends before its longest block, which streams at about a CU's full share when it
+                // was dispatched early (same layer: FFN2 in 64 blocks of 512 k-steps next to 128-k-step
+                // blocks, 78.9 us)
+                if (rolling)
+                    cost = std::max(cost, (double)longest * (double)std::max<int64_t>(1, std::min<int64_t>(conc, 2)) * 0.5 *
+                                          (busy >= 0.75 ? 1.0 : 0.75 / busy) + overhead + (double)longest * 0.5);
                 // several blocks per CU are several weight streams per CU: on launches of gigabytes that
                 // costs (h=12288 layer, 3.6 GB: one 8-wave block per CU 523 us, two 540 us, three 4-wave
                 // blocks 543 us), on a few hundred megabytes it does not
@@ -564,6 +591,11 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
                 const double inflight = std::min((double)fit, (double)blocks / kNumCU) * nw * depth;
                 if (inflight < 24.0) cost *= 1.0 + 0.3 * (24.0 - inflight) / 24.0;
                 if (slow_stage) cost *= 1.1;
+#ifdef SBI_DEV
+                if (getenv("SBI_PLAN_DEBUG"))
+                    fprintf(stderr, "plan B=%lld nw=%d depth=%d pw=%d cap=%lld T=%lld blocks=%lld fit=%lld conc=%lld cost=%.1f\n", (long long)B, nw,
+                            depth, pw, (long long)cap, (long long)T, (long long)blocks, (long long)fit, (long long)conc, cost);
+#endif
                 if (best_nw == 0 || cost < best) {
                     best = cost; best_nw = nw; best_depth = depth; best_pw = pw; bestT = T; best_cap = cap;
                 }
@@ -801,13 +833,6 @@ sbi_status sbi_gemm(const void* W_laid_out, int64_t K, int64_t N,
                      hip_stream, nullptr);
 }
 
-sbi_status sbi_gemm_ln(const void* W_laid_out, int64_t K, int64_t N,
-                       const void* X, int64_t B, const sbi_layernorm* ln,
-                       const void* bias, const void* residual, sbi_epilogue epi,
-                       void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
-                       const sbi_tuning* tuning)
-{
-    if (!ln) return SBI_ERR_NULL;
 }  // extern "C"
 
 // ---- sbi_gemm_static: the workspace of sbi_gemm in device memory the library owns -------------
@@ -869,6 +894,13 @@ sbi_status sbi_gemm_static(const void* W_laid_out, int64_t K, int64_t N,
                      hip_stream, nullptr);
 }
 
+sbi_status sbi_gemm_ln(const void* W_laid_out, int64_t K, int64_t N,
+                       const void* X, int64_t B, const sbi_layernorm* ln,
+                       const void* bias, const void* residual, sbi_epilogue epi,
+                       void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
+                       const sbi_tuning* tuning)
+{
+    if (!ln) return SBI_ERR_NULL;
     if (tuning && tuning->int8) return SBI_ERR_TUNING;
     return gemm_impl(W_laid_out, K, N, X, B, ln, bias, residual, epi, Y, workspace, workspace_bytes,
                      hip_stream, tuning);

@@ -444,7 +444,8 @@ inline bool spread_staging_fits(const GroupParams& gp, int waves, int depth, boo
 
 template <int NW, int DEPTH, int PW, bool LN, int XP = 1, class Stage, class Op>
 __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Stage& xst, Op& op, int tid,
-                                             int wave, int lane, int panel, int64_t pstride, int ks0, int ks1)
+                                             int wave, int lane, int panel, int64_t pstride, int ks0, int ks1,
+                                             unsigned long long* tmark = nullptr)
 {
     static_assert(XP >= 1 && DEPTH % XP == 0, "staging passes are spread evenly over the steps of a round");
     constexpr int RS = NW * DEPTH;                                 // k-steps a block consumes per round
@@ -459,13 +460,27 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Sta
     const int xbuf = p.kc * (xblock + 2 * eblock);                 // 16-byte units per X buffer
 
     u32x4 ring[DEPTH][kPanelTiles * PW];
+#ifdef SBI_DEV
+    const bool no_x = (p.flags >> 8) & 2;                          // development: X is not staged at all
+    if (!no_x)
+#endif
     xst.request(p, ks0, min(nks, p.kc), tid);
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
         load_step<PW>(ring[d], wbase + (int64_t)min(d * NW + wave, nks - 1) * kStepUnits, pstride);
+#ifdef SBI_DEV
+    if (!no_x) {
+#endif
     xst.commit(p, xs, ks0, min(nks, p.kc), tid);
     if (nchunks > 1) xst.request(p, ks0 + p.kc, min(nks - p.kc, p.kc), tid);
     __syncthreads();
+#ifdef SBI_DEV
+    }
+#endif
+#ifdef SBI_TRACE
+    if (tmark) tmark[0] = wall_clock64();                          // X staged
+    bool first_step = true;
+#endif
 
     int t = wave;                                                  // this wave's k-step inside the range
     int c = 0, rc = 0;                                             // X chunk, round inside the chunk
@@ -487,6 +502,9 @@ __device__ __forceinline__ void stream_panel(const GemmParams& p, u32x4* xs, Sta
                 }
             t += NW;
             __builtin_amdgcn_sched_barrier(0);
+#ifdef SBI_TRACE
+            if (tmark && first_step) { tmark[1] = wall_clock64(); first_step = false; }   // first k-step's weights consumed
+#endif
             if constexpr (XP > 1) {
                 if ((d + 1) % (DEPTH / XP) == 0 && d + 1 < DEPTH) { // every round ends a chunk: c+1 exists
                     const int j = (d + 1) / (DEPTH / XP) - 1;

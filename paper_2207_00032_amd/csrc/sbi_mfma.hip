@@ -28,6 +28,9 @@ struct MfmaOp {
     floatx2 st[LN ? MB : 1];
     int goff, boff;   // this lane's gamma piece inside a k-step's gamma block; beta: boff further
     int ln;
+#ifdef SBI_DEV
+    int ablate;
+#endif
 
     __device__ __forceinline__ void init(const GemmParams& p, const floatx2* stats, int g, int i)
     {
@@ -41,6 +44,11 @@ struct MfmaOp {
         goff = g;
         boff = p.kc * 4;
         ln = 0;
+#ifdef SBI_DEV
+        ablate = p.flags >> 8;
+#pragma unroll
+        for (int m = 0; m < MB; ++m) xf[m] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+#endif
         if constexpr (LN) {
             ln = p.ln;
             if (p.ln) {
@@ -57,6 +65,9 @@ struct MfmaOp {
 
     __device__ __forceinline__ void begin(const u32x4* xk, const u32x4* ek)
     {
+#ifdef SBI_DEV
+        if (ablate & 8) return;                                  // no operand read from LDS
+#endif
 #pragma unroll
         for (int m = 0; m < MB; ++m) xf[m] = __builtin_bit_cast(half8, xk[xoff[m]]);
         if constexpr (LN) {
@@ -71,6 +82,12 @@ struct MfmaOp {
 
     __device__ __forceinline__ void tile(int t, u32x4 w)
     {
+#ifdef SBI_DEV
+        if (ablate & 1) {                                        // no matrix-core work: keep the loaded registers alive only
+            acc[t][0][0] += __builtin_bit_cast(float, w[0] ^ w[1] ^ w[2] ^ w[3]);
+            return;
+        }
+#endif
         const half8 wf = __builtin_bit_cast(half8, w);
 #pragma unroll
         for (int m = 0; m < MB; ++m)
@@ -120,14 +137,29 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
     // a missing second panel streams the first one again; its result is dropped
     const int64_t pstride = (npanels > 1) ? (int64_t)p.KS * (kPanelTiles * 64) : 0;
 
+#ifdef SBI_DEV
+    if ((p.flags >> 8) & 48) {                                   // development: wave priority by dispatch order
+        const int third = (int)(blockIdx.x * 3u / gridDim.x);
+        const bool up = ((p.flags >> 8) & 16) != 0;                // 16: later blocks higher, 32: earlier blocks higher
+        const int pr = up ? third : 2 - third;
+        if (pr == 1) __builtin_amdgcn_s_setprio(1);
+        else if (pr == 2) __builtin_amdgcn_s_setprio(3);
+    }
+#endif
 #ifdef SBI_TRACE
     const unsigned long long t_start = wall_clock64();
+    unsigned long long tmark[2] = {0ull, 0ull};
 #endif
     MfmaOp<MB, PW, LN> op;
     op.init(p, stats, g, i);
     XStage<NT, 4, LN> xst;            // covers NT*64 bytes of X per chunk without a second pass
+#ifdef SBI_TRACE
+    stream_panel<NW, DEPTH, PW, LN, staging_passes(MB, DEPTH, LN)>(p, xs, xst, op, tid, wave, lane, panel,
+                                                                           pstride, ks0, ks1, tmark);
+#else
     stream_panel<NW, DEPTH, PW, LN, staging_passes(MB, DEPTH, LN)>(p, xs, xst, op, tid, wave, lane, panel,
                                                                            pstride, ks0, ks1);
+#endif
 #ifdef SBI_TRACE
     const unsigned long long t_stream = wall_clock64();
     unsigned long long t_sync = 0;
@@ -138,6 +170,12 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
     // What the epilogues will read (bias, residual) is requested for all passes at once, before the
     // first barrier: one memory latency in the shadow of the wait for the block's last wave,
     // instead of one per pass.
+#ifdef SBI_DEV
+    if ((p.flags >> 8) & 4) {                                    // no reduction, no epilogue: keep the sums alive only
+        if (op.acc[0][0][0] == 1.2345e-30f) p.Y[0] = (_Float16)1.0f;
+        return;
+    }
+#endif
     RowOperands<NW> ops[PW][MB];
 #pragma unroll
     for (int q = 0; q < PW; ++q)
@@ -165,14 +203,13 @@ __global__ __launch_bounds__(NW * 64) void sbi_mfma_kernel(const GroupParams gp)
     }
 #ifdef SBI_TRACE
     if (p.trace && tid == 0) {
-        unsigned long long* t = p.trace + (size_t)blockIdx.x * 4;
+        unsigned long long* t = p.trace + (size_t)blockIdx.x * 8;
         t[0] = t_start; t[1] = t_stream; t[2] = wall_clock64();
-#ifdef SBI_TRACE_SYNC
-        t[3] = t_sync;                 // when the block's last wave finished streaming
-#else
         t[3] = ((unsigned long long)gi << 32) | (unsigned)bid;
-        (void)t_sync;
-#endif
+        t[4] = t_sync;                 // when the block's last wave finished streaming
+        t[5] = tmark[0]; t[6] = tmark[1];
+        t[7] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11)) |                 // HW_ID
+               ((unsigned long long)__builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (31 << 11)) << 32);   // XCC_ID
     }
 #endif
 }
