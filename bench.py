@@ -31,7 +31,15 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="workload configuration (2, 3 or 4)")
+    ap.add_argument("--config", type=int, default=2,
+                    help="workload configuration: 1-4 time the four-GeMM layer (2 = h=4096, the headline); 5 is the "
+                         "batch crossover sweep of the h=8192 FFN1 GeMM (per batch: every forced path and the dispatcher's pick)")
+    ap.add_argument("--no-tune", action="store_true",
+                    help="keep the cost model's launch plans instead of measuring the candidates once at set-up "
+                         "(sbi_layer_tune / sbi_gemm_tune, untimed, as a serving engine does at model load)")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="default run only: skip the rows beyond the headline workload (single-GeMM launches, B=16, "
+                         "the h=12288 configurations 3 and 4)")
     ap.add_argument("--batches", type=str, default="", help="comma list overriding the batch sweep")
     ap.add_argument("--copies", type=int, default=0, help="weight copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -273,6 +281,134 @@ def decoder_main(args):
         "roofline": None, "cpu_baseline": None, "per_case": results}))
 
 
+MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X dense fp16 matrix-core peak, published
+
+
+def _median_us(torch, fn, reps=10, runs=5):
+    """Median over `runs` of the time per call of `reps` back-to-back calls (events on the current stream)."""
+    us = []
+    for _ in range(runs):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        us.append(e0.elapsed_time(e1) * 1e3 / reps)
+    return sorted(us)[len(us) // 2]
+
+
+def crossover_main(args):
+    """--config 5: the batch crossover sweep on the h=8192 FFN1 GeMM [8192,32768] + bias + GeLU with
+    outlier input channels.  Per batch size: the time under every forced path (vector-ALU stream
+    kernel up to 8 rows, matrix-core block kernel, work-balanced kernel) and under the dispatcher's own
+    pick with the plan it made, weights cold (three copies in rotation, 1.5 GiB); then, for the
+    matrix-core rate at the large-batch end, a 128 MiB slice of the same matrix cold (six copies in
+    rotation) and warm (one copy, resident in the 256 MB last-level cache), with the ceiling
+    B x achieved bytes/s beside it.  One JSON line; value = algorithmic bytes / time of the
+    dispatcher's picks over the whole sweep."""
+    import numpy as np
+    import torch
+    from oracle import oracle as orc
+    from paper_2207_00032_amd import binding as sb
+    from paper_2207_00032_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    sb.load()
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS[5]
+    spec = cfg.gemms[0]
+    K, N = spec.K, spec.N
+    batches = tuple(int(b) for b in args.batches.split(",")) if args.batches else cfg.batches
+    Bmax = max(batches)
+    W, bias, X, R = wl.make_gemm_inputs(K, N, Bmax, 0, 5, 0, cfg.outlier_channels, cfg.outlier_scale)
+    Wd = torch.from_numpy(W).to(dev)
+    Wl0 = sb.layout_weights(Wd)
+    Wl = [Wl0, Wl0.clone(), Wl0.clone()]
+    bias_d = torch.from_numpy(bias).to(dev)
+    paths = [("auto", sb.PATH_AUTO), ("mfma", sb.PATH_MFMA), ("stream", sb.PATH_STREAM), ("streamk", sb.PATH_STREAMK)]
+    need = max(sb.plan(B, K, N, p)["workspace_bytes"] for B in batches for _, p in paths
+               if not (p == sb.PATH_STREAM and B > 8))
+    ws = sb.new_workspace(max(need, 256), dev)
+    n = [0]
+    rows = []
+    auto_us = {}
+    for B in batches:
+        Xd = torch.from_numpy(np.ascontiguousarray(X[:B])).to(dev)
+        Yd = torch.empty((B, N), dtype=torch.float16, device=dev)
+        want = None if args.no_cpu_baseline else orc.gemm(X[:B], W, bias, None, epi=orc.EPI_BIAS | orc.EPI_GELU)
+        for name, path in paths:
+            if path == sb.PATH_STREAM and B > 8:
+                continue
+            pl = sb.plan(B, K, N, path)
+
+            def call():
+                sb.gemm(Wl[n[0] % 3], K, N, Xd, bias_d, None, "bias_gelu", out=Yd, workspace=ws, path=path)
+                n[0] += 1
+
+            for _ in range(3):
+                call()
+            us = _median_us(torch, call)
+            torch.cuda.synchronize()
+            ok = None
+            if want is not None:
+                ok, _rep = orc.check_close(Yd.cpu().numpy(), want)
+            nbytes, nflops = spec.algorithmic_bytes(B), spec.flops(B)
+            rows.append({"B": B, "path": name, "kernel": sb.PATH_NAMES[pl["path"]], "waves": pl["waves"], "depth": pl["depth"],
+                         "split_k": pl["split_k"], "panels": pl["panels"], "us": round(us, 2),
+                         "GBps": round(nbytes / us / 1e3, 1), "hbm_frac": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
+                         "TFLOPs": round(nflops / us / 1e6, 2),
+                         "mfma_frac": round(nflops / us / 1e6 / MFMA_F16_PEAK_TFLOPS, 4), "parity_ok": ok})
+            if name == "auto":
+                auto_us[B] = us
+    del Wl, Wl0, Wd
+    torch.cuda.empty_cache()
+
+    # matrix-core rate with the weights in the last-level cache: a 128 MiB column slice of the same matrix
+    Ns = 8192
+    Ws = np.ascontiguousarray(W[:, :Ns])
+    Wls0 = sb.layout_weights(torch.from_numpy(Ws).to(dev))
+    Wls = [Wls0] + [Wls0.clone() for _ in range(5)]
+    bs_d = torch.from_numpy(np.ascontiguousarray(bias[:Ns])).to(dev)
+    sspec = wl.GemmSpec("ffn1_slice", K, Ns, wl.BIAS_GELU)
+    warm = []
+    for B in [b for b in (1, 16, 32, 64) if b <= Bmax]:
+        Xd = torch.from_numpy(np.ascontiguousarray(X[:B])).to(dev)
+        Yd = torch.empty((B, Ns), dtype=torch.float16, device=dev)
+        ws2 = sb.new_workspace(max(sb.workspace_bytes(B, K, Ns), 256), dev)
+        res = {}
+        for label, ncopy in (("cold", 6), ("warm", 1)):
+            def call():
+                sb.gemm(Wls[n[0] % ncopy], K, Ns, Xd, bs_d, None, "bias_gelu", out=Yd, workspace=ws2)
+                n[0] += 1
+            for _ in range(5):
+                call()
+            res[label] = _median_us(torch, call, reps=20)
+        nbytes, nflops = sspec.algorithmic_bytes(B), sspec.flops(B)
+        warm.append({"B": B, "us_cold": round(res["cold"], 2), "us_warm": round(res["warm"], 2),
+                     "GBps_cold": round(nbytes / res["cold"] / 1e3, 1), "GBps_warm": round(nbytes / res["warm"] / 1e3, 1),
+                     "TFLOPs_cold": round(nflops / res["cold"] / 1e6, 1), "TFLOPs_warm": round(nflops / res["warm"] / 1e6, 1),
+                     "mfma_frac_cold": round(nflops / res["cold"] / 1e6 / MFMA_F16_PEAK_TFLOPS, 4),
+                     "mfma_frac_warm": round(nflops / res["warm"] / 1e6 / MFMA_F16_PEAK_TFLOPS, 4),
+                     # what HBM alone allows at this batch: B flop per byte streamed at the achieved cold rate
+                     "hbm_ceiling_TFLOPs": round(B * nbytes / res["cold"] / 1e6, 1)})
+    total_bytes = sum(spec.algorithmic_bytes(B) for B in batches)
+    total_us = sum(auto_us[B] for B in batches)
+    dom = max(batches)
+    print(json.dumps({
+        "metric": "weight-stream HBM GB/s over the batch crossover sweep (dispatcher's picks) and us per GeMM per path",
+        "value": round(total_bytes / total_us / 1e3, 1), "unit": "GB/s", "n_gpus": 1, "steps": 50, "warmup": 3,
+        "ms_per_step": round(total_us / 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"config5:{cfg.name} [8192,32768] + bias + GeLU, 1 % of input channels x 50, B in {list(batches)}, "
+                               "3 weight copies in rotation (1.5 GiB); every path per batch"},
+        "roofline": {"bound": "hbm", "achieved": round(spec.algorithmic_bytes(dom) / auto_us[dom] / 1e3, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(spec.algorithmic_bytes(dom) / auto_us[dom] / 1e3 / HBM_PEAK_GBPS, 4),
+                     "traffic": None, "kernel": f"dispatcher's pick at B={dom}", "avg_launch_us": round(auto_us[dom], 2)},
+        "cpu_baseline": None, "per_case": rows, "cache_resident_slice_8192x8192": warm}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -283,6 +419,8 @@ def main():
         return attention_main(args)
     if args.decoder_layer:
         return decoder_main(args)
+    if args.config == 5:
+        return crossover_main(args)
 
     import numpy as np
     import torch
@@ -295,7 +433,11 @@ def main():
     cfg = wl.CONFIGS[args.config]
     assert len(cfg.gemms) == 4, "bench.py times a four-GeMM layer configuration"
     batches = tuple(int(b) for b in args.batches.split(",")) if args.batches else cfg.batches
-    Bmax = max(batches)
+    # the rows beyond the headline workload: only with the default command (config 2, automatic dispatch)
+    extras = (not args.no_extra and args.config == 2 and not args.batches and args.path == "auto"
+              and not args.layernorm and not args.int8 and not args.graph and not args.pmc_probe)
+    row_batches = batches + ((16,) if extras else ())          # batches that get a per-launch row
+    Bmax = max(row_batches)
     specs = cfg.gemms
     layer_weight_bytes = sum(s.weight_bytes for s in specs) // (2 if args.int8 else 1)
     copies = args.copies or max(3, -(-3 * 256 * 1000 * 1000 // layer_weight_bytes))
@@ -339,9 +481,9 @@ def main():
             assert sb.layout_check(w, s.K, s.N) == 0
     Wl = [Wl0] + [[w.clone() for w in Wl0] for _ in range(copies - 1)]
     bias_d = [torch.from_numpy(h[1]).to(dev) if ub else None for h, ub in zip(host, use_bias)]
-    X_d = {B: [torch.from_numpy(np.ascontiguousarray(h[2][:B])).to(dev) for h in host] for B in batches}
-    R_d = {B: torch.from_numpy(np.ascontiguousarray(host[3][3][:B])).to(dev) if use_res else None for B in batches}
-    Y_d = {B: [torch.empty((B, s.N), dtype=torch.float16, device=dev) for s in specs] for B in batches}
+    X_d = {B: [torch.from_numpy(np.ascontiguousarray(h[2][:B])).to(dev) for h in host] for B in row_batches}
+    R_d = {B: torch.from_numpy(np.ascontiguousarray(host[3][3][:B])).to(dev) if use_res else None for B in row_batches}
+    Y_d = {B: [torch.empty((B, s.N), dtype=torch.float16, device=dev) for s in specs] for B in row_batches}
     h_dim = specs[0].K
     layers = [sb.make_layer(*Wl[c], h_dim, specs[0].N, specs[1].K, specs[2].N, specs[3].K,
                             bqkv=bias_d[0], bout=bias_d[1], bffn1=bias_d[2], bffn2=bias_d[3], ffn1_gelu=gelu,
@@ -354,12 +496,25 @@ def main():
         layers = [sb.make_layer(*Wl[c], h_dim, specs[0].N, specs[1].K, specs[2].N, specs[3].K,
                                 bqkv=bias_d[0], bout=bias_d[1], bffn1=bias_d[2], bffn2=bias_d[3], ffn1_gelu=gelu,
                                 ln1=ln_d[0], ln2=ln_d[2], ln_eps=LN_EPS) for c in range(copies)]
-    ws = sb.new_workspace(max([sb.layer_workspace_bytes(layers[0], B) for B in batches] +
-                              [sb.layer_workspace_bytes(plain_layers[0], B) for B in batches] +
-                              [sb.plan(B, s.K, s.N, int8=args.int8)["workspace_bytes"] for B in batches for s in specs]),
+    ws = sb.new_workspace(max([64 << 20] + [sb.layer_workspace_bytes(layers[0], B) for B in row_batches] +
+                              [sb.layer_workspace_bytes(plain_layers[0], B) for B in row_batches] +
+                              [sb.plan(B, s.K, s.N, int8=args.int8)["workspace_bytes"] for B in row_batches for s in specs]),
                           dev)
     path = {"auto": sb.PATH_AUTO, "stream": sb.PATH_STREAM, "mfma": sb.PATH_MFMA,
             "streamk": sb.PATH_STREAMK}[args.path]
+
+    # ---- launch plans measured once at set-up (untimed), as at model load ---------------------
+    tuned = {}
+    if not args.no_tune and path == sb.PATH_AUTO and not args.pmc_probe:
+        for B in row_batches:
+            x, y = X_d[B], Y_d[B]
+            tuned[f"layer B={B}"] = sb.layer_tune(layers, B, x[0], x[1], x[2], x[3], R_d[B], y[0], y[1], y[2], y[3], ws)
+        if (args.per_gemm or extras) and not args.int8 and not args.layernorm:
+            for B in (batches if args.per_gemm else (1, 8)):
+                for gi, s in enumerate(specs):
+                    tuned[f"single:{s.name} B={B}"] = sb.gemm_tune(
+                        [Wl[c][gi] for c in range(copies)], s.K, s.N, X_d[B][gi], bias_d[gi], R_d[B] if gi == 3 else None,
+                        s.epilogue, out=Y_d[B][gi], workspace=ws)
 
     launch_no = [0]
 
@@ -456,7 +611,7 @@ def main():
                            "hbm_frac": round(nbytes / (med * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
                            "TFLOPs": round(nflops / (med * 1e-6) / 1e12, 3)})
 
-    for B in batches:
+    for B in row_batches:
         timed_run("layer", B, sum(s.algorithmic_bytes(B, args.int8) for s in specs), sum(s.flops(B) for s in specs),
                   lambda: launch_layer(B))
     if args.layernorm:
@@ -474,16 +629,18 @@ def main():
         for B in batches:
             timed_run("layer, norms as separate torch kernels", B, sum(s.algorithmic_bytes(B, args.int8) for s in specs),
                       sum(s.flops(B) for s in specs), lambda: launch_unfused(B))
-    if args.per_gemm and not args.int8:
-        for B in batches:
+    if (args.per_gemm or extras) and not args.int8:
+        # every GeMM as a launch of its own (sbi_gemm): what a caller with dependent GeMMs gets
+        for B in (batches if args.per_gemm else (1, 8)):
             for gi, s in enumerate(specs):
                 timed_run("single:" + s.name, B, s.algorithmic_bytes(B, args.int8), s.flops(B),
                           lambda: sb.gemm(Wl[next_copy()][gi], s.K, s.N, X_d[B][gi], bias_d[gi],
                                           R_d[B] if gi == 3 else None, s.epilogue, out=Y_d[B][gi],
                                           workspace=ws, path=path))
-    pl0 = sb.plan(Bmax, specs[0].K, specs[0].N, path)
+    Bk = max(batches)                  # the timed region's largest batch names the kernel variant
+    pl0 = sb.plan(Bk, specs[0].K, specs[0].N, path)
     if path == sb.PATH_AUTO:
-        lp, _ = sb.layer_plan(layers[0], Bmax)
+        lp, _ = sb.layer_plan(layers[0], Bk)
         pl0 = lp[0]
     kname = {sb.PATH_STREAMK: "sbi_streamk_kernel", sb.PATH_MFMA: "sbi_mfma_kernel",
              sb.PATH_STREAM: "sbi_stream_kernel"}[pl0["path"]]
@@ -493,7 +650,7 @@ def main():
     achieved = bytes_per_launch / (avg_launch_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(args, batches),
-                "kernel": f"{kname}<{(Bmax + 15) // 16 if pl0['path'] != sb.PATH_STREAM else Bmax},"
+                "kernel": f"{kname}<{(Bk + 15) // 16 if pl0['path'] != sb.PATH_STREAM else Bk},"
                           f"{pl0['waves']},{pl0['depth']}>",
                 "launches": args.steps * launches_per_step, "avg_launch_us": round(avg_launch_us, 2),
                 "avg_bytes_per_launch": round(bytes_per_launch)}
@@ -506,12 +663,13 @@ def main():
         epi_map = {wl.NONE: 0, wl.BIAS: orc.EPI_BIAS, wl.BIAS_GELU: orc.EPI_BIAS | orc.EPI_GELU,
                    wl.BIAS_RESIDUAL: orc.EPI_BIAS | orc.EPI_RES, wl.GELU: orc.EPI_GELU, wl.RESIDUAL: orc.EPI_RES}
         torch.cuda.synchronize()
-        step(0)                      # outputs of copy 0 for the parity check below
+        for B in row_batches:        # outputs of one more launch per batch for the parity check below
+            launch_layer(B)
         torch.cuda.synchronize()
         t_cpu = 0.0
         cpu_bytes = 0
         worst = {"max_abs": 0.0, "n_bad": 0}
-        sample_batches = batches if layer_weight_bytes < (1 << 30) else (Bmax,)
+        sample_batches = row_batches if layer_weight_bytes < (1 << 30) else (Bmax,)
         for B in sample_batches:
             for gi, s in enumerate(specs):
                 W, bias, X, R = host[gi]
@@ -530,12 +688,68 @@ def main():
                 ok, rep = orc.check_close(Y_d[B][gi].cpu().numpy(), want)
                 worst["max_abs"] = max(worst["max_abs"], rep["max_abs"])
                 worst["n_bad"] += rep["n_bad"]
+        # the same oracle on ONE host thread, on one GeMM of the sample (QKV at the largest sampled batch)
+        W0, b0, X0, R0 = host[0]
+        c0 = time.perf_counter()
+        if not args.int8:
+            orc.gemm(X0[:Bmax], W0, b0, R0[:Bmax], epi=epi_map[specs[0].epilogue], threads=1)
+        t_one = time.perf_counter() - c0
         cpu = {"value": round(cpu_bytes / t_cpu / 1e9, 3), "unit": "GB/s", "cores": orc.max_threads(),
                "kind": "oracle",
                "sample": f"{len(sample_batches) * len(specs)} GeMMs (config {args.config}, B in "
-                         f"{list(sample_batches)}), {t_cpu:.1f} s of CPU time"}
+                         f"{list(sample_batches)}), {t_cpu:.1f} s of CPU time",
+               "value_1_thread": None if args.int8 else round(specs[0].algorithmic_bytes(Bmax) / t_one / 1e9, 3),
+               "sample_1_thread": None if args.int8 else f"{specs[0].name} at B={Bmax}, {t_one:.1f} s"}
         parity = {"ok": worst["n_bad"] == 0, "n_bad": worst["n_bad"], "max_abs": worst["max_abs"],
                   "tolerance": "max(2 ulp16, 1e-3)"}
+
+    # ---- the rest of the metric's range (h = 12288): configurations 3 and 4 as layer launches ------
+    if extras:
+        del Wl, Wl0, layers, plain_layers
+        torch.cuda.empty_cache()
+        for cid in (3, 4):
+            xcfg = wl.CONFIGS[cid]
+            xs_ = xcfg.gemms
+            xB = max(xcfg.batches)
+            xhost = [wl.make_gemm_inputs(s.K, s.N, xB, 0, cid, gi) for gi, s in enumerate(xs_)]
+            xbytes = sum(s.weight_bytes for s in xs_)
+            ncopy = 1 if xbytes > (1 << 30) else 3            # 3.6 GB of weights are cold by themselves
+            xWl0 = [sb.layout_weights(torch.from_numpy(h[0]).to(dev)) for h in xhost]
+            xWl = [xWl0] + [[w.clone() for w in xWl0] for _ in range(ncopy - 1)]
+            xbias = [torch.from_numpy(h[1]).to(dev) if s.epilogue in (wl.BIAS, wl.BIAS_GELU, wl.BIAS_RESIDUAL) else None
+                     for h, s in zip(xhost, xs_)]
+            xlayers = [sb.make_layer(*xWl[c], xs_[0].K, xs_[0].N, xs_[1].K, xs_[2].N, xs_[3].K, bqkv=xbias[0], bout=xbias[1],
+                                     bffn1=xbias[2], bffn2=xbias[3], ffn1_gelu=xs_[2].epilogue in (wl.BIAS_GELU, wl.GELU))
+                       for c in range(ncopy)]
+            for B in xcfg.batches:
+                xws = sb.new_workspace(max(sb.layer_workspace_bytes(xlayers[0], B), 64 << 20), dev)
+                xX = [torch.from_numpy(np.ascontiguousarray(h[2][:B])).to(dev) for h in xhost]
+                xY = [torch.empty((B, s.N), dtype=torch.float16, device=dev) for s in xs_]
+                k = [0]
+
+                def launch_x():
+                    sb.layer_gemms(xlayers[k[0] % ncopy], B, xX[0], xX[1], xX[2], xX[3], None, xY[0], xY[1], xY[2], xY[3], xws)
+                    k[0] += 1
+
+                if not args.no_tune:
+                    tuned[f"layer config{cid} B={B}"] = sb.layer_tune(xlayers, B, xX[0], xX[1], xX[2], xX[3], None,
+                                                                      xY[0], xY[1], xY[2], xY[3], xws)
+                for _ in range(2):
+                    launch_x()
+                timed_run(f"layer config{cid}:{xcfg.name}", B, sum(s.algorithmic_bytes(B) for s in xs_),
+                          sum(s.flops(B) for s in xs_), launch_x, reps=5 if ncopy == 1 else 10)
+                if not args.no_cpu_baseline:
+                    torch.cuda.synchronize()
+                    bad = 0
+                    for gi, s in enumerate(xs_):
+                        want = orc.gemm(xhost[gi][2][:B], xhost[gi][0], xhost[gi][1] if xbias[gi] is not None else None, None,
+                                        epi=epi_map[s.epilogue])
+                        bad += orc.check_close(xY[gi].cpu().numpy(), want)[1]["n_bad"]
+                    per_launch[-1]["parity_ok"] = bad == 0
+                    parity["n_bad"] += bad
+                    parity["ok"] = parity["n_bad"] == 0
+            del xWl, xWl0, xlayers, xhost
+            torch.cuda.empty_cache()
 
     out = {
         "metric": "weight-stream HBM GB/s (algorithmic bytes of the layer's four GeMMs / time)",
@@ -544,7 +758,8 @@ def main():
         "vs_baseline": None, "dtype": "i8" if args.int8 else "f16", "data": "synthetic",
         "config": {"workload": f"config{args.config}:{cfg.name} four-GeMM layer, B in {list(batches)}, "
                                f"rotating over {copies} weight copies ({copies * layer_weight_bytes >> 20} MiB)",
-                   "batches": list(batches), "weight_copies": copies, "dispatch": args.path,
+                   "batches": list(batches), "weight_copies": copies,
+                   "dispatch": args.path + (", plans measured at set-up (sbi_layer_tune / sbi_gemm_tune)" if tuned else ""),
                    "fused_layernorm": bool(args.layernorm), "int8": bool(args.int8),
                    "graph_replay_steps": args.graph},
         "hbm_frac": round(value / HBM_PEAK_GBPS, 4),
@@ -554,6 +769,9 @@ def main():
         "cpu_baseline": cpu,
         "parity": parity,
         "per_launch": per_launch,
+        "tuned_plans": {k: {"waves": v["waves"], "depth": v["depth"], "panels": v["panels"], "block_ksteps": v["block_ksteps"],
+                            "candidates": v["candidates"], "us_best": round(v["us_best"], 2), "us_model": round(v["us_model"], 2)}
+                        for k, v in tuned.items()},
     }
     print(json.dumps(out))
 

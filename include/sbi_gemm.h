@@ -19,9 +19,9 @@
  *     work is enqueued on it and no call synchronises, except sbi_gemm_layout_check.
  *   - Arguments are validated on the host before any GPU call; a failed validation
  *     enqueues nothing.  No exception crosses the boundary; the result is an sbi_status.
- *   - There is no global mutable state (each thread keeps a small memo of the launch plans it
- *     computed last, nothing else); calls on different streams may overlap as long as they do
- *     not share a workspace.
+ *   - Mutable state: each thread keeps a small memo of the launch plans it computed last; the
+ *     plans measured by sbi_layer_tune / sbi_gemm_tune live in a process-wide table behind a mutex.
+ *     Calls on different streams may overlap as long as they do not share a workspace.
  */
 #ifndef SBI_GEMM_H
 #define SBI_GEMM_H
@@ -345,6 +345,48 @@ size_t sbi_layer_workspace_bytes(const sbi_layer* L, int64_t B);
  * lds_bytes are those of the common launch.  *total_grid receives the launch's block count.
  */
 sbi_status sbi_layer_plan(const sbi_layer* L, int64_t B, int32_t chained, sbi_plan plans[4], int32_t* total_grid);
+
+/*
+ * Measured launch plans.  The dispatcher ranks block shapes and splits with a cost model; which of
+ * its near-best candidates is fastest depends on the shapes of the launch and on the machine, so
+ * a caller that runs the same launches many times (every layer of a model, every generated token)
+ * can have them measured once, at model load: the call runs the launch under each candidate plan
+ * the model puts within 30 % of its best estimate (at most 48 distinct plans, about 30 launches
+ * each), on the caller's own tensors, and records the fastest for (B, shapes, data type, layer-norm
+ * or not) in a process-wide table that every later plan, workspace-size and launch call of this
+ * library consults first.  This serves the paper's aim for the small-batch GeMM, "as fast as the
+ * memory can supply the weights" (Sec. I, "Latency Challenges"; Sec. III-C tiles "based on the problem
+ * size"): here the tiling is chosen by measurement.
+ *   layers / W_laid_out  n weight sets of ONE shape (a model's consecutive layers): trial launch i uses
+ *                        set i mod n, so that with enough sets the weights come from HBM as they do in
+ *                        the model, not from the last-level cache
+ *   workspace            as for the call being tuned; candidates that would need more are left out
+ *   report               optional: how many plans were tried, the winner, its time and the time of the
+ *                        model's own pick
+ * The call synchronises the stream (it times with events) and creates and destroys two events; it
+ * allocates no device memory.  The outputs hold valid results of the last trial.  Results are
+ * deterministic per plan; a different plan may round differently in the last bit (another order of
+ * the fp32 additions).  Not for use under graph capture.
+ * sbi_gemm_tune tunes the plain fp16 sbi_gemm; sbi_layer_tune the launch sbi_layer_gemms makes for
+ * the layer's independent GeMMs (with Xffn2 == NULL: QKV, attention output, FFN1).
+ */
+typedef struct sbi_tune_report {
+    int32_t candidates;     /* distinct plans measured */
+    int32_t waves, depth, panels, block_ksteps; /* the winner: block shape and common block size */
+    float us_best;          /* its time per launch */
+    float us_model;         /* time per launch of the plan the cost model ranks first */
+} sbi_tune_report;
+
+sbi_status sbi_layer_tune(const sbi_layer* layers, int32_t n_layers, int64_t B,
+                          const void* Xqkv, const void* Xout, const void* Xffn1, const void* Xffn2,
+                          const void* residual,
+                          void* Yqkv, void* Yout, void* Yffn1, void* Yffn2,
+                          void* workspace, size_t workspace_bytes, void* hip_stream, sbi_tune_report* report);
+
+sbi_status sbi_gemm_tune(const void* const* W_laid_out, int32_t n_weights, int64_t K, int64_t N,
+                         const void* X, int64_t B,
+                         const void* bias, const void* residual, sbi_epilogue epi,
+                         void* Y, void* workspace, size_t workspace_bytes, void* hip_stream, sbi_tune_report* report);
 
 /*
  * Single-token attention with a key/value cache (paper Sec. III-D region 2, "transposition plus

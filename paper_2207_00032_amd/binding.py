@@ -33,7 +33,7 @@ EXPORTS = ["sbi_gemm_layout_bytes", "sbi_gemm_workspace_bytes", "sbi_gemm_layout
            "sbi_gemm_ln_workspace_bytes", "sbi_gemm_i8_layout_bytes", "sbi_gemm_i8_workspace_bytes",
            "sbi_gemm_i8_quantize_weights", "sbi_gemm_i8_layout_weights", "sbi_gemm_i8_layout_check", "sbi_gemm_i8",
            "sbi_gemm_moments", "sbi_attn_decode", "sbi_attn_decode_workspace_bytes",
-           "sbi_attn_decode_ragged", "sbi_gemm_static"]
+           "sbi_attn_decode_ragged", "sbi_gemm_static", "sbi_layer_tune", "sbi_gemm_tune"]
 
 
 class SbiError(RuntimeError):
@@ -141,6 +141,10 @@ def load():
     L.sbi_layer_workspace_bytes.argtypes = [ctypes.POINTER(Layer), i64]
     L.sbi_layer_plan.restype = i32
     L.sbi_layer_plan.argtypes = [ctypes.POINTER(Layer), i64, i32, ctypes.POINTER(Plan), ctypes.POINTER(i32)]
+    L.sbi_layer_tune.restype = i32
+    L.sbi_layer_tune.argtypes = [vp, i32, i64] + [vp] * 9 + [vp, sz, vp, vp]
+    L.sbi_gemm_tune.restype = i32
+    L.sbi_gemm_tune.argtypes = [vp, i32, i64, i64, vp, i64, vp, vp, i32, vp, vp, sz, vp, vp]
     L.sbi_calib_read.restype = i32
     L.sbi_calib_read.argtypes = [vp, sz, vp, sz, i32, i32, i32, i32, vp]
     L.sbi_calib_copy.restype = i32
@@ -464,6 +468,58 @@ def layer_gemms(layer, B, Xqkv, Xout, Xffn1, Xffn2, residual, Yqkv, Yout, Yffn1,
                                 _ptr(residual), _ptr(Yqkv), _ptr(Yout), _ptr(Yffn1), _ptr(Yffn2),
                                 _ptr(workspace), ws_len, _stream())
     _check(st, "sbi_layer_gemms")
+
+
+class TuneReport(ctypes.Structure):
+    _fields_ = [("candidates", ctypes.c_int32), ("waves", ctypes.c_int32), ("depth", ctypes.c_int32),
+                ("panels", ctypes.c_int32), ("block_ksteps", ctypes.c_int32), ("us_best", ctypes.c_float),
+                ("us_model", ctypes.c_float)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+def layer_tune(layers, B, Xqkv, Xout, Xffn1, Xffn2, residual, Yqkv, Yout, Yffn1, Yffn2, workspace):
+    """sbi_layer_tune over the weight sets `layers` (Layer structs of one shape): measures the
+    candidate plans of the layer launch and makes the fastest the plan of later calls.  Returns the
+    report as a dict."""
+    layer = layers[0]
+    for t, cols, name in ((Xqkv, layer.h, "Xqkv"), (Xout, layer.k_out, "Xout"), (Xffn1, layer.h, "Xffn1"),
+                          (Xffn2, layer.k_ffn2, "Xffn2"), (residual, layer.h, "residual"),
+                          (Yqkv, layer.n_qkv, "Yqkv"), (Yout, layer.h, "Yout"), (Yffn1, layer.n_ffn1, "Yffn1"),
+                          (Yffn2, layer.h, "Yffn2")):
+        _need(t, (B, cols), name)
+    arr = (Layer * len(layers))(*layers)
+    rep = TuneReport()
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    st = load().sbi_layer_tune(arr, len(layers), B, _ptr(Xqkv), _ptr(Xout), _ptr(Xffn1), _ptr(Xffn2), _ptr(residual),
+                               _ptr(Yqkv), _ptr(Yout), _ptr(Yffn1), _ptr(Yffn2), _ptr(workspace), ws_len, _stream(),
+                               ctypes.byref(rep))
+    _check(st, "sbi_layer_tune")
+    return rep.as_dict()
+
+
+def gemm_tune(Wls, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, workspace=None):
+    """sbi_gemm_tune over the laid-out weight copies `Wls` (one shape).  Returns the report as a dict."""
+    import torch
+    B = X.shape[0]
+    if isinstance(epilogue, str):
+        epilogue = EPILOGUES[epilogue]
+    if out is None:
+        out = torch.empty((B, N), dtype=torch.float16, device=X.device)
+    _need(X, (B, K), "X")
+    _need(bias, (N,), "bias")
+    _need(residual, (B, N), "residual")
+    _need(out, (B, N), "out")
+    for w in Wls:
+        _need_bytes(w, layout_bytes(K, N), "laid-out weights")
+    ptrs = (ctypes.c_void_p * len(Wls))(*[w.data_ptr() for w in Wls])
+    rep = TuneReport()
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    st = load().sbi_gemm_tune(ptrs, len(Wls), K, N, _ptr(X), B, _ptr(bias), _ptr(residual), int(epilogue), _ptr(out),
+                              _ptr(workspace), ws_len, _stream(), ctypes.byref(rep))
+    _check(st, "sbi_gemm_tune")
+    return rep.as_dict()
 
 
 def attn_workspace_bytes(B, heads, head_dim, max_seq):

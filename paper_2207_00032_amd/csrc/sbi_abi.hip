@@ -7,7 +7,9 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <atomic>
 #include <mutex>
+#include <vector>
 #if defined(SBI_TRACE) || defined(SBI_DEV)
 #include <cstdio>
 #include <cstdlib>
@@ -403,6 +405,36 @@ int resident_waves(int mb, int nw, int depth, int pw, bool ln, bool i8, bool pre
     return 4 * std::min(8, 512 / v);
 }
 
+// One point of the dispatcher's search space: block shape (waves, depth, panels per block), the
+// common block size T in k-steps and the LDS budget the X chunks are cut for.
+struct Candidate {
+    int nw, depth, pw;
+    int64_t T, cap;
+    double cost;               // the model's estimate (k-steps of streaming time on the busiest CU)
+};
+
+// Launches measured by sbi_layer_tune / sbi_gemm_tune: (batch, shapes, flavour) -> the candidate that
+// ran fastest on this machine.  plan_group consults it before the model.  Process-wide, guarded
+// by a mutex; g_tuned_version lets the per-thread plan memos notice a new entry.
+struct TunedEntry {
+    int64_t B, Ks[kMaxGroup], Ns[kMaxGroup];
+    int G, flags;
+    Candidate c;
+};
+std::vector<TunedEntry> g_tuned;
+std::mutex g_tuned_mutex;
+std::atomic<int> g_tuned_version{0};
+thread_local const TunedEntry* t_trial = nullptr;     // set by the tuner around its trial launches: this thread's
+                                                      //   plans for exactly that problem use the trial's candidate
+
+bool same_problem(const TunedEntry& e, int64_t B, const int64_t* Ks, const int64_t* Ns, int G, int flags)
+{
+    if (e.B != B || e.G != G || e.flags != flags) return false;
+    for (int g = 0; g < G; ++g)
+        if (e.Ks[g] != Ks[g] || e.Ns[g] != Ns[g]) return false;
+    return true;
+}
+
 // Plans for `G` GeMMs that go out as one launch of the block kernel.  A common block size T
 // (k-steps) gives all blocks of the launch about the same work; problem g is split
 // S_g = ceil(KS_g / T) ways.  Candidates (block shape, LDS budget, T) are ranked by a model of
@@ -411,7 +443,8 @@ int resident_waves(int mb, int nw, int depth, int pw, bool ln, bool i8, bool pre
 // register file.  Returns per-problem plans plus the launch totals in `tot` (nw, depth, lds,
 // grid, ws_bytes).
 sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot, bool ln,
-                             bool i8);
+                             bool i8, const Candidate* forced = nullptr, std::vector<Candidate>* all = nullptr,
+                             Candidate* picked = nullptr);
 
 // The search below is a pure function of its arguments and costs 10-25 us; a serving loop asks
 // for the same few launches over and over, so each thread remembers its last results.
@@ -419,7 +452,7 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
 {
     struct Entry {
         int64_t B, Ks[kMaxGroup], Ns[kMaxGroup];
-        int G, flags;
+        int G, flags, version;
         Plan pls[kMaxGroup], tot;
         sbi_status status;
         bool used;
@@ -432,9 +465,12 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
     if (getenv("SBI_PLAN_FORCE")) return plan_group_search(B, Ks, Ns, G, pls, tot, ln, i8);
 #endif
     const int flags = (ln ? 1 : 0) | (i8 ? 2 : 0);
+    if (t_trial && same_problem(*t_trial, B, Ks, Ns, G, flags))
+        return plan_group_search(B, Ks, Ns, G, pls, tot, ln, i8, &t_trial->c);
+    const int version = g_tuned_version.load(std::memory_order_acquire);
     for (int e = 0; e < kEntries; ++e) {
         const Entry& m = memo[e];
-        if (!m.used || m.B != B || m.G != G || m.flags != flags) continue;
+        if (!m.used || m.B != B || m.G != G || m.flags != flags || m.version != version) continue;
         bool same = true;
         for (int g = 0; g < G; ++g) same = same && m.Ks[g] == Ks[g] && m.Ns[g] == Ns[g];
         if (!same) continue;
@@ -445,8 +481,15 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
     Entry& m = memo[next];
     next = (next + 1) % kEntries;
     m.used = false;
-    m.status = plan_group_search(B, Ks, Ns, G, m.pls, m.tot, ln, i8);
-    m.B = B; m.G = G; m.flags = flags;
+    Candidate tuned;
+    bool have_tuned = false;
+    if (version > 0) {
+        std::lock_guard<std::mutex> lock(g_tuned_mutex);
+        for (const TunedEntry& t : g_tuned)
+            if (same_problem(t, B, Ks, Ns, G, flags)) { tuned = t.c; have_tuned = true; }
+    }
+    m.status = plan_group_search(B, Ks, Ns, G, m.pls, m.tot, ln, i8, have_tuned ? &tuned : nullptr);
+    m.B = B; m.G = G; m.flags = flags; m.version = version;
     for (int g = 0; g < G; ++g) { m.Ks[g] = Ks[g]; m.Ns[g] = Ns[g]; }
     m.used = true;
     for (int g = 0; g < G; ++g) pls[g] = m.pls[g];
@@ -455,7 +498,7 @@ sbi_status plan_group(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Pl
 }
 
 sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, Plan* pls, Plan& tot, bool ln_wanted,
-                             bool i8)
+                             bool i8, const Candidate* forced, std::vector<Candidate>* all, Candidate* picked)
 {
     if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
     for (int g = 0; g < G; ++g)
@@ -489,10 +532,11 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
     int64_t bestT = 0, best_cap = 0;
     double best = 0.0;
     for (const auto& shp : shapes) {
+        if (forced && !all) break;                             // nothing to search
         const int nw = shp[0], depth = shp[1], pw = shp[2];
         // 8 waves with the shallow ring, one panel: measured ahead only for grouped launches of up to 16
         // rows (below); no layer-norm variant of it exists
-        if (nw == 0 || ((ln || mb > 1 || G == 1) && nw == 8 && depth == 2 && pw == 1)) continue;
+        if (nw == 0 || ((ln || ((mb > 1 || G == 1) && !all)) && nw == 8 && depth == 2 && pw == 1)) continue;
         // INT8 (from pre-quantised codes at these batch sizes): measured ahead only above 32 rows
         if (pw == 2 && (mb < 2 || ln || (i8 && mb < 3))) continue;
         const int64_t wd = round_ksteps(nw, depth, pw);
@@ -566,7 +610,7 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
                 // and for launches in which at most one problem is split: with the h=12288 tensor-parallel slice,
                 // whose QKV and FFN1 are both split, the same shape is behind by up to 5 %)
                 const bool rolling = !ln && !i8 && nw == 8 && depth == 2 && pw == 1 && nsplit <= 1 && fit >= 2 && blocks > fit * kNumCU;
-                if (nw == 8 && depth == 2 && pw == 1 && !rolling) continue;     // this shape was only measured ahead when rolling
+                if (nw == 8 && depth == 2 && pw == 1 && !rolling && !all) continue;   // this shape was only measured ahead when rolling
                 const double eff_blocks = (conc == 1 && mb >= 2)
                     ? 0.5 * ((double)per_cu_blocks + std::max(1.0, (double)blocks / kNumCU))
                     : rolling ? (double)blocks / kNumCU : (double)per_cu_blocks;
@@ -596,6 +640,7 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
                     fprintf(stderr, "plan B=%lld nw=%d depth=%d pw=%d cap=%lld T=%lld blocks=%lld fit=%lld conc=%lld cost=%.1f\n", (long long)B, nw,
                             depth, pw, (long long)cap, (long long)T, (long long)blocks, (long long)fit, (long long)conc, cost);
 #endif
+                if (all) all->push_back(Candidate{nw, depth, pw, T, cap, cost});
                 if (best_nw == 0 || cost < best) {
                     best = cost; best_nw = nw; best_depth = depth; best_pw = pw; bestT = T; best_cap = cap;
                 }
@@ -617,7 +662,18 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
         }
     }
 #endif
+    if (forced) {                       // a measured (or trial) candidate replaces the model's pick
+        best_nw = forced->nw; best_depth = forced->depth; best_pw = forced->pw; bestT = forced->T; best_cap = forced->cap;
+        for (int g = 0; g < G; ++g) {
+            const int64_t S = ceil_div(KS[g], bestT), ksps = ceil_div(KS[g], S);
+            int64_t kc = 0, l = 0;
+            if (!chunking(B, ksps, round_ksteps(best_nw, best_depth, best_pw), best_nw, best_cap,
+                          (int64_t)best_nw * 16 * kRedPitch * 4, kc, l, fl))
+                return SBI_ERR_TUNING;
+        }
+    }
     if (best_nw == 0) return SBI_ERR_SHAPE;
+    if (picked) *picked = Candidate{best_nw, best_depth, best_pw, bestT, best_cap, best};
     const int nw = best_nw, depth = best_depth, pw = best_pw;
     const int64_t wd = round_ksteps(nw, depth, pw);
     int64_t grid = 0, partial_bytes = 0, lds = 0;
@@ -1076,6 +1132,150 @@ sbi_status sbi_layer_gemms(const sbi_layer* L, int64_t B,
     Plan one = last;
     one.ws_bytes = (last.S > 1) ? ceil_div(L->h, kPanelN) * last.S * B * kPanelN * 4 : 0;
     return launch_block_group(&a[3], &one, last, 1, B, workspace, st);
+}
+
+
+}  // extern "C"
+
+// ---- measured plans ---------------------------------------------------------------------------
+namespace {
+
+// Average microseconds per call of `n` back-to-back calls of fn() on `st` (fn returns an sbi_status);
+// negative if a call or the timing failed.
+template <class F>
+double time_calls(hipStream_t st, hipEvent_t e0, hipEvent_t e1, int n, F&& fn)
+{
+    if (hipEventRecord(e0, st) != hipSuccess) return -1.0;
+    for (int i = 0; i < n; ++i)
+        if (fn(i) != SBI_OK) return -1.0;
+    if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) return -1.0;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) return -1.0;
+    return (double)ms * 1e3 / n;
+}
+
+// Tries the dispatcher's candidates for one problem (those the model puts within 30 % of its best
+// estimate, at most 48, distinct plans only) with run(i) = one launch on weight set i, and records
+// the fastest.  `ws_limit`: candidates that need a larger workspace are left out.
+template <class F>
+sbi_status tune_problem(int64_t B, const int64_t* Ks, const int64_t* Ns, int G, bool ln, bool i8, size_t ws_limit,
+                        hipStream_t st, int n_sets, sbi_tune_report* report, F&& run)
+{
+    std::vector<Candidate> all;
+    Plan pls[kMaxGroup], tot;
+    Candidate model;                    // what the dispatcher picks without measurements: always trial 0
+    if (sbi_status s = plan_group_search(B, Ks, Ns, G, pls, tot, ln, i8, nullptr, nullptr, &model)) return s;
+    if (sbi_status s = plan_group_search(B, Ks, Ns, G, pls, tot, ln, i8, nullptr, &all)) return s;
+    std::stable_sort(all.begin(), all.end(), [](const Candidate& a, const Candidate& b) { return a.cost < b.cost; });
+    const double limit = std::min(model.cost, all.empty() ? model.cost : all.front().cost) * 1.3;
+    all.insert(all.begin(), model);
+    struct Trial { Candidate c; Plan pls[kMaxGroup]; Plan tot; };
+    std::vector<Trial> trials;
+    for (const Candidate& c : all) {
+        if (c.cost > limit || trials.size() >= 48) break;
+        Trial t;
+        t.c = c;
+        if (plan_group_search(B, Ks, Ns, G, t.pls, t.tot, ln, i8, &c) != SBI_OK) continue;
+        if ((size_t)t.tot.ws_bytes > ws_limit) continue;
+        bool seen = false;
+        for (const Trial& o : trials) {
+            bool same = o.tot.nw == t.tot.nw && o.tot.depth == t.tot.depth && o.tot.pw == t.tot.pw && o.tot.lds == t.tot.lds;
+            for (int g = 0; g < G && same; ++g)
+                same = o.pls[g].S == t.pls[g].S && o.pls[g].ksps == t.pls[g].ksps && o.pls[g].kc == t.pls[g].kc;
+            seen = seen || same;
+        }
+        if (!seen) trials.push_back(t);
+    }
+    if (trials.empty()) return SBI_ERR_WORKSPACE;
+
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return SBI_ERR_HIP;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return SBI_ERR_HIP; }
+    TunedEntry entry;
+    entry.B = B; entry.G = G; entry.flags = (ln ? 1 : 0) | (i8 ? 2 : 0);
+    for (int g = 0; g < kMaxGroup; ++g) { entry.Ks[g] = g < G ? Ks[g] : 0; entry.Ns[g] = g < G ? Ns[g] : 0; }
+    const int per_run = std::max(6, 2 * n_sets);
+    double best_us = -1.0, model_us = -1.0;
+    size_t best = 0;
+    for (size_t k = 0; k < trials.size(); ++k) {
+        entry.c = trials[k].c;
+        t_trial = &entry;
+        double us = time_calls(st, e0, e1, 3, run) < 0.0 ? -1.0 : 1e30;          // warm-up (code, translations)
+        for (int rep = 0; rep < 3 && us >= 0.0; ++rep) {
+            const double t = time_calls(st, e0, e1, per_run, run);
+            us = t < 0.0 ? -1.0 : std::min(us, t);
+        }
+        t_trial = nullptr;
+        if (us < 0.0) continue;                                                 // this candidate cannot be launched
+        if (k == 0) model_us = us;
+        if (best_us < 0.0 || us < best_us) { best_us = us; best = k; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (best_us < 0.0) return SBI_ERR_HIP;
+    entry.c = trials[best].c;
+    {
+        std::lock_guard<std::mutex> lock(g_tuned_mutex);
+        bool replaced = false;
+        for (TunedEntry& t : g_tuned)
+            if (same_problem(t, B, Ks, Ns, G, entry.flags)) { t = entry; replaced = true; }
+        if (!replaced) g_tuned.push_back(entry);
+        g_tuned_version.fetch_add(1, std::memory_order_release);
+    }
+    if (report) {
+        report->candidates = (int32_t)trials.size();
+        report->waves = entry.c.nw; report->depth = entry.c.depth; report->panels = entry.c.pw;
+        report->block_ksteps = (int32_t)entry.c.T;
+        report->us_best = (float)best_us; report->us_model = (float)model_us;
+    }
+    return SBI_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+sbi_status sbi_layer_tune(const sbi_layer* layers, int32_t n_layers, int64_t B,
+                          const void* Xqkv, const void* Xout, const void* Xffn1, const void* Xffn2,
+                          const void* residual,
+                          void* Yqkv, void* Yout, void* Yffn1, void* Yffn2,
+                          void* workspace, size_t workspace_bytes, void* hip_stream, sbi_tune_report* report)
+{
+    if (!layers || n_layers < 1 || n_layers > 4096) return SBI_ERR_NULL;
+    for (int i = 0; i < n_layers; ++i) {
+        if (sbi_status s = layer_check(&layers[i], B)) return s;
+        const sbi_layer &a = layers[0], &b = layers[i];
+        if (a.h != b.h || a.n_qkv != b.n_qkv || a.k_out != b.k_out || a.n_ffn1 != b.n_ffn1 || a.k_ffn2 != b.k_ffn2 ||
+            layer_is_i8(&a) != layer_is_i8(&b) || (a.ln1_gamma || a.ln2_gamma) != (b.ln1_gamma || b.ln2_gamma))
+            return SBI_ERR_SHAPE;                          // one shape and one flavour per call
+    }
+    const sbi_layer* L = &layers[0];
+    const int count = Xffn2 ? 4 : 3;
+    const int64_t Ks[4] = {L->h, L->k_out, L->h, L->k_ffn2};
+    const int64_t Ns[4] = {L->n_qkv, L->h, L->n_ffn1, L->h};
+    // a first call under the model's plan: reports every argument error before anything is measured
+    if (sbi_status s = sbi_layer_gemms(L, B, Xqkv, Xout, Xffn1, Xffn2, residual, Yqkv, Yout, Yffn1, Yffn2, workspace,
+                                       workspace_bytes, hip_stream)) return s;
+    return tune_problem(B, Ks, Ns, count, L->ln1_gamma || L->ln2_gamma, layer_is_i8(L), workspace_bytes,
+                        (hipStream_t)hip_stream, n_layers, report, [&](int i) {
+                            return sbi_layer_gemms(&layers[i % n_layers], B, Xqkv, Xout, Xffn1, Xffn2, residual, Yqkv, Yout,
+                                                   Yffn1, Yffn2, workspace, workspace_bytes, hip_stream);
+                        });
+}
+
+sbi_status sbi_gemm_tune(const void* const* W_laid_out, int32_t n_weights, int64_t K, int64_t N,
+                         const void* X, int64_t B,
+                         const void* bias, const void* residual, sbi_epilogue epi,
+                         void* Y, void* workspace, size_t workspace_bytes, void* hip_stream, sbi_tune_report* report)
+{
+    if (!W_laid_out || n_weights < 1 || n_weights > 4096) return SBI_ERR_NULL;
+    for (int i = 0; i < n_weights; ++i)
+        if (!W_laid_out[i] || !aligned(W_laid_out[i], 256)) return W_laid_out[i] ? SBI_ERR_ALIGN : SBI_ERR_NULL;
+    if (sbi_status s = sbi_gemm(W_laid_out[0], K, N, X, B, bias, residual, epi, Y, workspace, workspace_bytes, hip_stream))
+        return s;
+    return tune_problem(B, &K, &N, 1, false, false, workspace_bytes, (hipStream_t)hip_stream, n_weights, report, [&](int i) {
+        return sbi_gemm(W_laid_out[i % n_weights], K, N, X, B, bias, residual, epi, Y, workspace, workspace_bytes, hip_stream);
+    });
 }
 
 // Position ranges per (sequence, head) of the attention kernel: one block per CU where the

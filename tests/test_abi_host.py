@@ -154,6 +154,34 @@ def test_static_scratch_entry_point_validates_before_touching_the_device(lib):
     assert re.search(r"#define SBI_STATIC_SCRATCH_BYTES \((\d+)u << 20\)", text).group(1) == str(sb.STATIC_SCRATCH_BYTES >> 20)
 
 
+def test_tuner_argument_validation(lib):
+    """sbi_layer_tune / sbi_gemm_tune refuse bad arguments on the host (nothing is launched or timed)."""
+    L = sb.Layer()
+    L.Wqkv = L.Wout = L.Wffn1 = L.Wffn2 = FAKE
+    L.h, L.n_qkv, L.k_out, L.n_ffn1, L.k_ffn2 = 256, 768, 256, 1024, 1024
+    X, Y = FAKE + (1 << 30), FAKE + (2 << 30)
+    tune = lambda arr, n, B=2: lib.sbi_layer_tune(arr, n, B, X, X, X, X, None, Y, Y + (1 << 20), Y + (2 << 20), Y + (3 << 20),
+                                                  FAKE + (3 << 30), 1 << 26, None, None)
+    one = (sb.Layer * 1)(L)
+    assert tune(None, 1) == 1 and tune(one, 0) == 1
+    assert tune(one, 1, B=0) == 4 and tune(one, 1, B=65) == 4
+    L2 = sb.Layer()
+    ctypes.memmove(ctypes.byref(L2), ctypes.byref(L), ctypes.sizeof(L))
+    L2.n_ffn1 = L2.k_ffn2 = 2048
+    assert tune((sb.Layer * 2)(L, L2), 2) == 2                      # two shapes in one call
+    bad = sb.Layer()
+    ctypes.memmove(ctypes.byref(bad), ctypes.byref(L), ctypes.sizeof(L))
+    bad.Wout = None
+    assert tune((sb.Layer * 1)(bad), 1) == 1
+    ptrs = (ctypes.c_void_p * 2)(FAKE, FAKE + 128)
+    gt = lambda p, n, K=256, B=2: lib.sbi_gemm_tune(p, n, K, 256, X, B, None, None, sb.EPI_NONE, Y, FAKE + (3 << 30),
+                                                    1 << 26, None, None)
+    assert gt(None, 1) == 1 and gt(ptrs, 0) == 1
+    assert gt(ptrs, 2) == 3                                         # second weight set not 256-byte aligned
+    assert gt((ctypes.c_void_p * 1)(None), 1) == 1
+    assert gt(ptrs, 1, K=0) == 2 and gt(ptrs, 1, B=99) == 4
+
+
 def test_layout_argument_validation(lib):
     nb = sb.layout_bytes(64, 64)
     assert lib.sbi_gemm_layout_weights(None, 64, 64, FAKE, nb, None) == 1
