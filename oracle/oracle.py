@@ -219,6 +219,14 @@ def gemm_i8_from_fp16(X, Wq, sw, bias=None, residual=None, epi=0):
     return gemm_i8(Xq, sx, Wq, sw, bias, residual, epi)
 
 
+def gemm_i8_ln_from_fp16(X, gamma, beta, eps, Wq, sw, bias=None, residual=None, epi=0):
+    """Layer-norm in front of the INT8 GeMM (the paper's fused regions start with the layer-norm
+    whatever the GeMM's data type, Sec. III-D): the composition of the definitions above and
+    nothing else - layernorm() in fp64 rounded once to fp16 (the GeMM's operand), those fp16
+    values quantised per row by quantize_rows() (binary32 decisions), then gemm_i8()."""
+    return gemm_i8_from_fp16(layernorm(X, gamma, beta, eps), Wq, sw, bias, residual, epi)
+
+
 def attn_decode(qkv, Kc, Vc, pos, scale=None, return_pre=False):
     """Single-token attention with a KV cache.  qkv [B,3,H,d] fp16 (query, new key, new value of
     the token), Kc / Vc [B,H,S,d] fp16 caches with `pos` tokens in them.  Returns

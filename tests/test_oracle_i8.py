@@ -180,6 +180,38 @@ def test_quantisation_error_of_the_whole_path_is_what_the_step_sizes_allow():
     assert np.abs(p8 - p16).max() > 1e-4               # and it is not the same computation
 
 
+def test_layernorm_in_front_of_int8_closed_forms():
+    """Layer-norm, then INT8.  Rows of alternating +-a have mean 0 and variance a^2, so they
+    normalise to +-1/sqrt(1 + eps/a^2), which rounds to +-1 in fp16 for eps = 1e-5: with gamma = g
+    (a power of two) and beta = 0 every code is +-127 and the row scale g/127, hence
+    Y[b,n] = g * sum_k (+-1) * Wq[k,n] * sw[n], exactly (small integers).  A second case keeps beta:
+    the normalised values +-g + c must be quantised AFTER the rounding to fp16."""
+    K, N, B = 64, 5, 3
+    rng = np.random.default_rng(5)
+    sign = np.where(np.arange(K) % 2 == 0, 1.0, -1.0)
+    X = np.stack([sign * a for a in (0.5, 3.0, 40.0)]).astype(np.float16)
+    Wq = rng.integers(-127, 128, (K, N)).astype(np.int8)
+    sw = np.array([1.0, 0.5, 2.0, 0.25, 1.0], np.float32)
+    for g in (1.0, 0.25, 4.0):
+        gamma = np.full(K, g, np.float16)
+        beta = np.zeros(K, np.float16)
+        Y = orc.gemm_i8_ln_from_fp16(X, gamma, beta, 1e-5, Wq, sw)
+        want = g * (sign[:, None] * Wq.astype(np.float64)).sum(axis=0) * sw
+        assert np.array_equal(Y, np.tile(want, (B, 1)).astype(np.float16))
+    # with beta = 0.5 and gamma = 1: values 1.5 and -0.5, amax 1.5, codes 127 and rint(-0.5 * 127/1.5) = -42
+    gamma = np.ones(K, np.float16)
+    beta = np.full(K, 0.5, np.float16)
+    Xq, sx = orc.quantize_rows(orc.layernorm(X, gamma, beta, 1e-5))
+    assert np.array_equal(Xq, np.tile(np.where(sign > 0, 127, -42).astype(np.int8), (B, 1)))
+    assert np.array_equal(sx, np.full(B, np.float32(1.5) / np.float32(127), np.float32))
+    Y = orc.gemm_i8_ln_from_fp16(X, gamma, beta, 1e-5, Wq, sw)
+    want = (np.where(sign > 0, 127, -42)[:, None] * Wq.astype(np.float64)).sum(axis=0) * np.float64(sx[0]) * sw
+    assert np.array_equal(Y, np.tile(want, (B, 1)).astype(np.float16))
+    # and it is the composition, step by step
+    Xn = orc.layernorm(X, gamma, beta, 1e-5)
+    assert np.array_equal(Y, orc.gemm_i8_from_fp16(Xn, Wq, sw))
+
+
 def test_layout_i8_index_formula():
     rng = np.random.default_rng(2)
     K, N = 200, 150
