@@ -466,7 +466,7 @@ def main():
 
     scales_d = None
     if args.int8:
-        assert args.path == "auto" and not args.layernorm, "--int8 runs through sbi_layer_gemms, without --layernorm"
+        assert args.path == "auto", "--int8 runs through sbi_layer_gemms"
         prepared = [sb.i8_quantize_weights(torch.from_numpy(h[0]).to(dev)) for h in host]
         Wl0 = [sb.i8_layout_weights(q) for q, _ in prepared]
         scales_d = [sc for _, sc in prepared]
@@ -495,7 +495,7 @@ def main():
                 for gi in (0, 2)}
         layers = [sb.make_layer(*Wl[c], h_dim, specs[0].N, specs[1].K, specs[2].N, specs[3].K,
                                 bqkv=bias_d[0], bout=bias_d[1], bffn1=bias_d[2], bffn2=bias_d[3], ffn1_gelu=gelu,
-                                ln1=ln_d[0], ln2=ln_d[2], ln_eps=LN_EPS) for c in range(copies)]
+                                ln1=ln_d[0], ln2=ln_d[2], ln_eps=LN_EPS, scales=scales_d) for c in range(copies)]
     ws = sb.new_workspace(max([64 << 20] + [sb.layer_workspace_bytes(layers[0], B) for B in row_batches] +
                               [sb.layer_workspace_bytes(plain_layers[0], B) for B in row_batches] +
                               [sb.plan(B, s.K, s.N, int8=args.int8)["workspace_bytes"] for B in row_batches for s in specs]),

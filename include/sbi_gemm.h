@@ -81,10 +81,10 @@ typedef struct sbi_tuning {
     int32_t layernorm; /* sbi_gemm_plan: nonzero plans the launch sbi_gemm_ln makes (layer-norm fused
                           in front: MFMA path, one panel per block, K % 8 == 0, (waves, depth) one of
                           (4,2), (4,4), (8,4)); sbi_gemm_ex rejects it, sbi_gemm_ln implies it */
-    int32_t int8;      /* sbi_gemm_plan: nonzero plans the launch sbi_gemm_i8 makes (MFMA path, K % 16 == 0,
-                          not together with layernorm; (waves, depth) one of (4,2), (4,4), (8,4) with one
-                          panel per block, or (8,2) with two panels per block for B > 8);
-                          sbi_gemm_i8 implies it */
+    int32_t int8;      /* sbi_gemm_plan: nonzero plans the launch sbi_gemm_i8 makes (MFMA path, K % 16 == 0;
+                          (waves, depth) one of (4,2), (4,4), (8,4) with one panel per block, or (8,2) with two
+                          panels per block for B > 8); sbi_gemm_i8 implies it.  Together with layernorm: the
+                          launches sbi_gemm_i8_ln makes */
 } sbi_tuning;
 
 /* What the dispatcher decided for a problem (for reports and tests). */
@@ -280,6 +280,15 @@ sbi_status sbi_gemm_moments(const void* W_laid_out, int64_t K, int64_t N,
  *   k = 16g..16g+15 of column i; zero padded.
  * sbi_gemm_i8: as sbi_gemm_ex with the laid-out codes and w_scales (device, binary32 [N], 4-byte
  *   aligned).  Needs K % 16 == 0 (SBI_ERR_SHAPE).  Workspace: sbi_gemm_i8_workspace_bytes.
+ * sbi_gemm_i8_ln: the layer normalisation of sbi_gemm_ln in front of the INT8 GeMM (the paper's
+ *   fused regions 1 and 3 start with the input layer-norm whatever the GeMM's data type):
+ *       Xn = fp16( layernorm(X) )     then     Y = sbi_gemm_i8 on Xn.
+ *   The fp16 value Xn[b,k] decides an integer code, so it must be THE correctly rounded value of
+ *   the definition: one kernel (a block per row) evaluates the row statistics and
+ *   (x - mean) / sqrt(var + eps) * gamma + beta in binary64, rounds once to fp16, quantises the row
+ *   as above and leaves codes and row scales in the workspace; the INT8 GeMM kernels then run from
+ *   those codes at every batch size.  ln->moments must be NULL.  Workspace: sbi_gemm_plan with
+ *   tuning->int8 and tuning->layernorm both set.
  */
 size_t sbi_gemm_i8_layout_bytes(int64_t K, int64_t N);
 size_t sbi_gemm_i8_workspace_bytes(int64_t B, int64_t K, int64_t N);
@@ -293,6 +302,11 @@ sbi_status sbi_gemm_i8(const void* W_laid_out, const void* w_scales, int64_t K, 
                        const void* bias, const void* residual, sbi_epilogue epi,
                        void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
                        const sbi_tuning* tuning);
+sbi_status sbi_gemm_i8_ln(const void* W_laid_out, const void* w_scales, int64_t K, int64_t N,
+                          const void* X, int64_t B, const sbi_layernorm* ln,
+                          const void* bias, const void* residual, sbi_epilogue epi,
+                          void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
+                          const sbi_tuning* tuning);
 
 /* Host-only: the launch the dispatcher would make for (B, K, N) under `tuning` (or NULL). */
 sbi_status sbi_gemm_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tuning, sbi_plan* plan);
@@ -316,7 +330,7 @@ typedef struct sbi_layer {
     float ln_eps;
     /* INT8 layer: all four set (device, binary32 per-column scales [n_qkv], [h], [n_ffn1], [h]) means
        W* are laid-out int8 codes (sbi_gemm_i8_layout_weights) and the GeMMs run as sbi_gemm_i8;
-       all four NULL: fp16.  Needs h, k_out, k_ffn2 % 16 == 0; not together with ln1/ln2. */
+       all four NULL: fp16.  Needs h, k_out, k_ffn2 % 16 == 0.  With ln1/ln2: as sbi_gemm_i8_ln. */
     const void *sqkv, *sout, *sffn1, *sffn2;
 } sbi_layer;
 

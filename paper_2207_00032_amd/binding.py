@@ -33,7 +33,7 @@ EXPORTS = ["sbi_gemm_layout_bytes", "sbi_gemm_workspace_bytes", "sbi_gemm_layout
            "sbi_gemm_ln_workspace_bytes", "sbi_gemm_i8_layout_bytes", "sbi_gemm_i8_workspace_bytes",
            "sbi_gemm_i8_quantize_weights", "sbi_gemm_i8_layout_weights", "sbi_gemm_i8_layout_check", "sbi_gemm_i8",
            "sbi_gemm_moments", "sbi_attn_decode", "sbi_attn_decode_workspace_bytes",
-           "sbi_attn_decode_ragged", "sbi_gemm_static", "sbi_layer_tune", "sbi_gemm_tune"]
+           "sbi_attn_decode_ragged", "sbi_gemm_static", "sbi_layer_tune", "sbi_gemm_tune", "sbi_gemm_i8_ln"]
 
 
 class SbiError(RuntimeError):
@@ -133,6 +133,9 @@ def load():
     L.sbi_gemm_i8_layout_check.argtypes = [vp, i64, i64, vp]
     L.sbi_gemm_i8.restype = i32
     L.sbi_gemm_i8.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp, i32, vp, vp, sz, vp, ctypes.POINTER(Tuning)]
+    L.sbi_gemm_i8_ln.restype = i32
+    L.sbi_gemm_i8_ln.argtypes = [vp, vp, i64, i64, vp, i64, ctypes.POINTER(LayerNorm), vp, vp, i32, vp, vp, sz, vp,
+                                 ctypes.POINTER(Tuning)]
     L.sbi_gemm_plan.restype = i32
     L.sbi_gemm_plan.argtypes = [i64, i64, i64, ctypes.POINTER(Tuning), ctypes.POINTER(Plan)]
     L.sbi_layer_gemms.restype = i32
@@ -288,8 +291,10 @@ def i8_layout_check(Wl, K, N):
 
 
 def gemm_i8(Wl, sw, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, workspace=None,
-            path=PATH_AUTO, split_k=0, waves=0, depth=0, panels=0):
-    """Y = epilogue((quantize(X) @ Wq) * sx * sw + bias) through sbi_gemm_i8.  Returns Y (fp16 [B,N])."""
+            path=PATH_AUTO, split_k=0, waves=0, depth=0, panels=0, layernorm=None):
+    """Y = epilogue((quantize(X) @ Wq) * sx * sw + bias) through sbi_gemm_i8, or, with
+    layernorm=(gamma, beta, eps), the same on the layer-normalised rows through sbi_gemm_i8_ln.
+    Returns Y (fp16 [B,N])."""
     import torch
     assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.is_contiguous()
     B = X.shape[0]
@@ -306,9 +311,19 @@ def gemm_i8(Wl, sw, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=No
         raise ValueError("w_scales: expected a contiguous CUDA float32 tensor of shape (N,)")
     tune = _tuning(path, split_k, waves, depth, panels=panels)
     if workspace is None:
-        need = plan(B, K, N, path, split_k, waves, depth, panels=panels, int8=True)["workspace_bytes"]
+        need = plan(B, K, N, path, split_k, waves, depth, panels=panels, int8=True,
+                    layernorm=layernorm is not None)["workspace_bytes"]
         workspace = new_workspace(need, X.device) if need else None
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    if layernorm is not None:
+        gamma, beta, eps = layernorm
+        _need(gamma, (K,), "gamma")
+        _need(beta, (K,), "beta")
+        ln = LayerNorm(gamma.data_ptr(), beta.data_ptr(), float(eps), None)
+        st = load().sbi_gemm_i8_ln(_ptr(Wl), _ptr(sw), K, N, _ptr(X), B, ctypes.byref(ln), _ptr(bias), _ptr(residual),
+                                   int(epilogue), _ptr(out), _ptr(workspace), ws_len, _stream(), tune)
+        _check(st, "sbi_gemm_i8_ln")
+        return out
     st = load().sbi_gemm_i8(_ptr(Wl), _ptr(sw), K, N, _ptr(X), B, _ptr(bias), _ptr(residual), int(epilogue),
                             _ptr(out), _ptr(workspace), ws_len, _stream(), tune)
     _check(st, "sbi_gemm_i8")

@@ -172,7 +172,8 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     const bool ln = t.layernorm != 0;
     const bool i8 = t.int8 != 0;
     const int64_t KS = i8 ? ksteps_of_i8(K) : ksteps_of(K);
-    const bool preq = i8 && B > kI8FusedMaxBatch;
+    // INT8 with a layer-norm in front: always from codes (the kernel that quantises the rows normalises them first)
+    const bool preq = i8 && (B > kI8FusedMaxBatch || ln);
     const Flavour fl = i8 ? (preq ? kInt8Codes : kInt8) : (ln ? kLayerNorm : kPlain);
 
     if (t.split_k < 0 || t.blocks < 0 || t.panels < 0 || t.panels > 2) return SBI_ERR_TUNING;
@@ -180,9 +181,9 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
     const bool sk_ok = (K % kChunkK == 0);            // X rows readable as 128-bit pieces
     if (path == SBI_PATH_AUTO) path = (B <= kAutoStreamBatch && !ln && !i8) ? SBI_PATH_STREAM : SBI_PATH_MFMA;
     // layer-norm in front of the GeMM: matrix-core block kernel only, rows read as 128-bit pieces
-    if (ln && (path != SBI_PATH_MFMA || K % kChunkK != 0 || t.panels == 2)) return SBI_ERR_TUNING;
-    // INT8: its own matrix-core kernel, rows read as 32-byte pieces; no layer-norm in front (yet)
-    if (i8 && (path != SBI_PATH_MFMA || K % kI8ChunkK != 0 || (t.panels == 2 && !preq) || ln)) return SBI_ERR_TUNING;
+    if (ln && !i8 && (path != SBI_PATH_MFMA || K % kChunkK != 0 || t.panels == 2)) return SBI_ERR_TUNING;
+    // INT8: its own matrix-core kernel, rows read as 32-byte pieces
+    if (i8 && (path != SBI_PATH_MFMA || K % kI8ChunkK != 0 || (t.panels == 2 && !preq))) return SBI_ERR_TUNING;
     if (path == SBI_PATH_STREAMK) {
         if (!sk_ok) return SBI_ERR_TUNING;
         return plan_streamk(B, KS * P, P, t, pl);
@@ -216,7 +217,7 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
             bool depth_ok = depth == 4 || depth == 8 || (depth == 2 && path == SBI_PATH_MFMA);
             if (pw == 2) depth_ok = (nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && (depth == 2 || (depth == 4 && B > 16)));
             if ((nw != 4 && nw != 8) || !depth_ok) continue;
-            if (ln && !((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))) continue;
+            if (ln && !i8 && !((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))) continue;
             if (i8 && !(pw == 2 ? (nw == 8 && (depth == 2 || depth == 4)) : ((nw == 4 && (depth == 2 || depth == 4)) || (nw == 8 && depth == 4))))
                 continue;
             S = t.split_k;
@@ -240,7 +241,7 @@ sbi_status make_plan(int64_t B, int64_t K, int64_t N, const sbi_tuning* tune, Pl
         }
     if (!found) return why;
 
-    pl.ln = ln; pl.i8 = i8; pl.preq = preq; pl.prenorm = false; pl.xq_bytes = preq ? xq_bytes_of(B, K) : 0;
+    pl.ln = ln && !i8; pl.i8 = i8; pl.preq = preq; pl.prenorm = false; pl.xq_bytes = preq ? xq_bytes_of(B, K) : 0;
     pl.path = path; pl.nw = nw; pl.depth = depth; pl.S = S; pl.pw = pw;
     pl.ksps = (int)ksps; pl.kc = (int)kc;
     pl.grid = (int)(PG * S); pl.block = nw * 64;
@@ -507,8 +508,8 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
     double launch_bytes = 0.0;
     for (int g = 0; g < G; ++g) launch_bytes += 2.0 * (double)Ks[g] * (double)Ns[g];
     const int64_t fused_max = launch_bytes >= 1e9 ? kLnFusedMaxBatchLarge : kLnFusedMaxBatch;
-    const bool prenorm = ln_wanted && B > fused_max;          // normalise once, then the plain kernels
-    const bool ln = ln_wanted && !prenorm;
+    const bool prenorm = ln_wanted && !i8 && B > fused_max;   // normalise once, then the plain kernels
+    const bool ln = ln_wanted && !i8 && !prenorm;              // (INT8: the kernel that quantises the rows normalises them)
     const int mb = (int)ceil_div(B, 16);
     int64_t KS[kMaxGroup], P[kMaxGroup], maxKS = 0, panels = 0;
     for (int g = 0; g < G; ++g) {
@@ -519,7 +520,7 @@ sbi_status plan_group_search(int64_t B, const int64_t* Ks, const int64_t* Ns, in
     if (panels > kCounterBytes / 4) return SBI_ERR_SHAPE;
     constexpr int64_t kLdsPerCU = 160 * 1024;
     const int64_t lds_caps[4] = {18 * 1024, 36 * 1024, kMaxLds, kMaxLdsWide};   // 9/8 of a power of two: room for the odd pitch
-    const bool preq = i8 && B > kI8FusedMaxBatch;
+    const bool preq = i8 && (B > kI8FusedMaxBatch || ln_wanted);
     const Flavour fl = i8 ? (preq ? kInt8Codes : kInt8) : (ln ? kLayerNorm : kPlain);
     // (waves, depth, panels per block) candidates; two-panel blocks only pay off for B > 16
     // (ties go to the earlier shape: the measured order at equal modelled cost - the fp16 kernels do
@@ -846,6 +847,7 @@ static sbi_status gemm_impl(const void* W_laid_out, int64_t K, int64_t N,
         if (ln->moments && !aligned(ln->moments, 8)) return SBI_ERR_ALIGN;
     }
     if (moments_out && !aligned(moments_out, 8)) return SBI_ERR_ALIGN;
+    if (i8 && ln && ln->moments) return SBI_ERR_TUNING;          // the fp64 statistics of the INT8 path read the rows
     if (i8) {
         if (!w_scales) return SBI_ERR_NULL;
         if (K % kI8ChunkK != 0) return SBI_ERR_SHAPE;
@@ -1019,6 +1021,17 @@ sbi_status sbi_gemm_i8(const void* W_laid_out, const void* w_scales, int64_t K, 
                      hip_stream, tuning, w_scales, true);
 }
 
+sbi_status sbi_gemm_i8_ln(const void* W_laid_out, const void* w_scales, int64_t K, int64_t N,
+                          const void* X, int64_t B, const sbi_layernorm* ln,
+                          const void* bias, const void* residual, sbi_epilogue epi,
+                          void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
+                          const sbi_tuning* tuning)
+{
+    if (!ln) return SBI_ERR_NULL;
+    return gemm_impl(W_laid_out, K, N, X, B, ln, bias, residual, epi, Y, workspace, workspace_bytes,
+                     hip_stream, tuning, w_scales, true);
+}
+
 static sbi_status layer_check(const sbi_layer* L, int64_t B)
 {
     if (!L) return SBI_ERR_NULL;
@@ -1037,7 +1050,6 @@ static sbi_status layer_check(const sbi_layer* L, int64_t B)
         if (L->h % kI8ChunkK || L->k_out % kI8ChunkK || L->k_ffn2 % kI8ChunkK) return SBI_ERR_SHAPE;
         if (!aligned(L->sqkv, 4) || !aligned(L->sout, 4) || !aligned(L->sffn1, 4) || !aligned(L->sffn2, 4))
             return SBI_ERR_ALIGN;
-        if (L->ln1_gamma || L->ln2_gamma) return SBI_ERR_TUNING;   // no layer-norm in front of the INT8 kernel yet
     }
     return SBI_OK;
 }

@@ -267,23 +267,106 @@ struct QuantRowsParams {
     const _Float16* X[kMaxGroup];
     signed char* codes[kMaxGroup];
     floatx2* stats[kMaxGroup];
+    const _Float16* gamma[kMaxGroup];     // not null: layer-normalise the row first (see below)
+    const _Float16* beta[kMaxGroup];
+    float eps[kMaxGroup];
     int K[kMaxGroup];
     int B;
 };
 
+// fp64 -> fp16 in ONE rounding step (to nearest, ties to even): the value goes to binary32 rounded to
+// odd (truncate, then set the last bit if anything was lost), which keeps enough information for
+// the final rounding to the 11-bit significand to be the correct one.
+__device__ __forceinline__ _Float16 double_to_half_rn(double d)
+{
+    float f = __double2float_rz(d);
+    if ((double)f != d) f = __builtin_bit_cast(float, __builtin_bit_cast(unsigned int, f) | 1u);
+    return (_Float16)f;
+}
+
+__device__ __forceinline__ double block_sum_256(double v, double* s_part, int lane, int wave)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    __syncthreads();                       // s_part may still be read from the previous use
+    if (lane == 0) s_part[wave] = v;
+    __syncthreads();
+    return (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
+}
+
+// Layer-norm in front of the INT8 GeMM (paper Sec. III-D: the fused regions start with the input
+// layer-norm whatever the GeMM's data type).  The normalised fp16 value decides an integer code, so
+// it has to be THE fp16 value of the definition, not one that is an ulp off now and then: the row
+// statistics and (x - mean) * rstd * gamma + beta are evaluated in fp64 here (a few thousand
+// operations per row: nothing next to the weight stream) and rounded once to fp16, after which
+// the quantisation is the plain one.  Returns the row's normalised piece c (16 values).
+__device__ __forceinline__ void ln_piece16(const _Float16* row, const _Float16* gamma, const _Float16* beta, int c,
+                                           double mean, double rstd, u32x4& lo, u32x4& hi)
+{
+    half8 y[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const half8 x = __builtin_bit_cast(half8, *reinterpret_cast<const u32x4*>(row + c * 16 + h * 8));
+        const half8 gm = __builtin_bit_cast(half8, *reinterpret_cast<const u32x4*>(gamma + c * 16 + h * 8));
+        const half8 bt = __builtin_bit_cast(half8, *reinterpret_cast<const u32x4*>(beta + c * 16 + h * 8));
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            y[h][e] = double_to_half_rn(((double)x[e] - mean) * rstd * (double)gm[e] + (double)bt[e]);
+    }
+    lo = __builtin_bit_cast(u32x4, y[0]);
+    hi = __builtin_bit_cast(u32x4, y[1]);
+}
+
 __global__ __launch_bounds__(256) void sbi_quantize_rows_kernel(const QuantRowsParams q)
 {
     __shared__ float s_max[4];
+    __shared__ double s_part[4];
     const int g = (int)blockIdx.x / q.B, b = (int)blockIdx.x - g * q.B;
     const int K = q.K[g];
     const _Float16* row = q.X[g] + (int64_t)b * K;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int pieces = K / 16;
+    const _Float16* gamma = q.gamma[g];
+    const _Float16* beta = q.beta[g];
+    double mean = 0.0, rstd = 0.0;
+    if (gamma) {                           // block-uniform
+        double s = 0.0;
+        for (int c = tid; c < pieces; c += 256) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const half8 x = __builtin_bit_cast(half8, *reinterpret_cast<const u32x4*>(row + c * 16 + h * 8));
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s += (double)x[e];
+            }
+        }
+        mean = block_sum_256(s, s_part, lane, wave) / (double)K;
+        double v = 0.0;
+        for (int c = tid; c < pieces; c += 256) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const half8 x = __builtin_bit_cast(half8, *reinterpret_cast<const u32x4*>(row + c * 16 + h * 8));
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const double d = (double)x[e] - mean;
+                    v += d * d;
+                }
+            }
+        }
+        const double var = block_sum_256(v, s_part, lane, wave) / (double)K;
+        rstd = 1.0 / sqrt(var + (double)q.eps[g]);
+    }
     float m = 0.f;
     for (int c = tid; c < pieces; c += 256) {
-        const u32x4* src = reinterpret_cast<const u32x4*>(row + c * 16);
-        const half8 a = __builtin_bit_cast(half8, src[0]);
-        const half8 h = __builtin_bit_cast(half8, src[1]);
+        u32x4 lo, hi;
+        if (gamma) {
+            ln_piece16(row, gamma, beta, c, mean, rstd, lo, hi);
+        } else {
+            const u32x4* src = reinterpret_cast<const u32x4*>(row + c * 16);
+            lo = src[0];
+            hi = src[1];
+        }
+        const half8 a = __builtin_bit_cast(half8, lo);
+        const half8 h = __builtin_bit_cast(half8, hi);
 #pragma unroll
         for (int e = 0; e < 8; ++e) m = fmaxf(m, fmaxf(fabsf((float)a[e]), fabsf((float)h[e])));
     }
@@ -296,8 +379,15 @@ __global__ __launch_bounds__(256) void sbi_quantize_rows_kernel(const QuantRowsP
     if (tid == 0) q.stats[g][b] = (amax > 0.f) ? floatx2{inv, amax / 127.0f} : floatx2{0.f, 0.f};
     u32x4* dst = reinterpret_cast<u32x4*>(q.codes[g] + (int64_t)b * K);
     for (int c = tid; c < pieces; c += 256) {
-        const u32x4* src = reinterpret_cast<const u32x4*>(row + c * 16);
-        dst[c] = quantize16(src[0], src[1], inv);
+        u32x4 lo, hi;
+        if (gamma) {                       // the same arithmetic as in the pass above: the same fp16 values
+            ln_piece16(row, gamma, beta, c, mean, rstd, lo, hi);
+        } else {
+            const u32x4* src = reinterpret_cast<const u32x4*>(row + c * 16);
+            lo = src[0];
+            hi = src[1];
+        }
+        dst[c] = quantize16(lo, hi, inv);
     }
 }
 
@@ -316,7 +406,11 @@ int launch_i8(const GroupParams& gp, int waves, int depth, int panels, bool preq
             q.codes[k] = reinterpret_cast<signed char*>(const_cast<_Float16*>(gp.g[k].X));
             q.stats[k] = const_cast<floatx2*>(gp.g[k].xstats);
             q.K[k] = gp.g[k].K;
+            q.gamma[k] = gp.g[k].ln ? gp.g[k].ln_gamma : nullptr;       // layer-norm, then quantise
+            q.beta[k] = gp.g[k].ln ? gp.g[k].ln_beta : nullptr;
+            q.eps[k] = gp.g[k].ln_eps;
         }
+        for (int k = gp.G; k < kMaxGroup; ++k) { q.X[k] = nullptr; q.codes[k] = nullptr; q.stats[k] = nullptr; q.gamma[k] = nullptr; q.beta[k] = nullptr; q.eps[k] = 0.f; q.K[k] = 0; }
         q.B = gp.g[0].B;
         hipLaunchKernelGGL(sbi_quantize_rows_kernel, dim3(gp.G * q.B), dim3(256), 0, st, q);
         if (hipGetLastError() != hipSuccess) return (int)hipErrorInvalidValue;

@@ -71,8 +71,9 @@ int main(int argc, char** argv)
     if (argc < 9) { fprintf(stderr, "usage: B K N waves depth split panels ln\n"); return 9; }
     const int B = atoi(argv[1]); const int64_t K = atoll(argv[2]), N = atoll(argv[3]);
     sbi_tuning t = {SBI_PATH_MFMA, atoi(argv[6]), atoi(argv[4]), atoi(argv[5]), 0, atoi(argv[7]), 0};
-    const int mode = atoi(argv[8]);         // 0 plain, 1 layer-norm, 2 int8, 3 plain + emitted moments, 4 layer-norm fed by moments
-    const int ln = mode == 1 || mode == 4, i8 = mode == 2;
+    const int mode = atoi(argv[8]);         // 0 plain, 1 layer-norm, 2 int8, 3 plain + emitted moments, 4 layer-norm fed by moments,
+                                            // 5 layer-norm in front of int8
+    const int ln = mode == 1 || mode == 4 || mode == 5, i8 = mode == 2 || mode == 5;
     if (t.waves == 0) t.path = SBI_PATH_AUTO;
     std::mt19937 rng(7);
     _Float16* W = halfs((size_t)K * N, rng, 0.02f);
@@ -92,7 +93,18 @@ int main(int argc, char** argv)
     if (i8) {
         Wq.resize((size_t)K * N); sw.resize(N); Xq.resize((size_t)B * K); sx.resize(B);
         for (int64_t n = 0; n < N; ++n) sw[n] = quantize_line(W + n, K, N, Wq.data() + n);
-        for (int b = 0; b < B; ++b) sx[b] = quantize_line(X + (size_t)b * K, K, 1, Xq.data() + (size_t)b * K);
+        std::vector<_Float16> xn16((size_t)B * K);
+        for (int b = 0; b < B; ++b) {       // mode 5: the rows that are quantised are the normalised ones, rounded to fp16
+            const _Float16* x = X + (size_t)b * K;
+            double mean = 0, var = 0;
+            for (int64_t k = 0; k < K; ++k) mean += (double)x[k];
+            mean /= K;
+            for (int64_t k = 0; k < K; ++k) var += ((double)x[k] - mean) * ((double)x[k] - mean);
+            var /= K;
+            for (int64_t k = 0; k < K; ++k)
+                xn16[(size_t)b * K + k] = ln ? (_Float16)(((double)x[k] - mean) * (1.0 / std::sqrt(var + (double)1e-5f)) * (double)g1[k] + (double)b1[k]) : x[k];
+        }
+        for (int b = 0; b < B; ++b) sx[b] = quantize_line(xn16.data() + (size_t)b * K, K, 1, Xq.data() + (size_t)b * K);
         Wl8 = layout_i8(Wq.data(), K, N);
         swd = (float*)exact_alloc(4, (size_t)N * 4);
         memcpy(swd, sw.data(), (size_t)N * 4);
@@ -122,6 +134,7 @@ int main(int argc, char** argv)
         l.moments = mom_in;
     }
     if (mode == 3) st = sbi_gemm_moments(Wl, K, N, X, B, nullptr, bias, R, SBI_EPI_BIAS_RESIDUAL, Y, mom_out, ws, wsb, nullptr, &t);
+    else if (i8 && ln) st = sbi_gemm_i8_ln(Wl8, swd, K, N, X, B, &l, bias, R, SBI_EPI_BIAS_RESIDUAL, Y, ws, wsb, nullptr, &t);
     else if (i8) st = sbi_gemm_i8(Wl8, swd, K, N, X, B, bias, R, SBI_EPI_BIAS_RESIDUAL, Y, ws, wsb, nullptr, &t);
     else if (ln) st = sbi_gemm_ln(Wl, K, N, X, B, &l, bias, R, SBI_EPI_BIAS_RESIDUAL, Y, ws, wsb, nullptr, &t);
     else st = sbi_gemm_ex(Wl, K, N, X, B, bias, R, SBI_EPI_BIAS_RESIDUAL, Y, ws, wsb, nullptr, &t);

@@ -28,6 +28,17 @@ inline hipError_t hipGetLastError() { return hipSuccess; }
 inline hipError_t hipFuncSetAttribute(const void*, int, int) { return hipSuccess; }
 inline hipError_t hipMemcpyAsync(void* d, const void* s, size_t n, int, hipStream_t) { memcpy(d, s, n); return hipSuccess; }
 inline hipError_t hipStreamSynchronize(hipStream_t) { return hipSuccess; }
+// a file-scope device array is an ordinary array here and its "device address" its own
+#define __align__(n) __attribute__((aligned(n)))
+#define HIP_SYMBOL(x) (x)
+inline hipError_t hipGetDevice(int* d) { *d = 0; return hipSuccess; }
+template <class T> inline hipError_t hipGetSymbolAddress(void** p, T& symbol) { *p = (void*)&symbol; return hipSuccess; }
+typedef int hipEvent_t;
+inline hipError_t hipEventCreate(hipEvent_t* e) { *e = 0; return hipSuccess; }
+inline hipError_t hipEventDestroy(hipEvent_t) { return hipSuccess; }
+inline hipError_t hipEventRecord(hipEvent_t, hipStream_t) { return hipSuccess; }
+inline hipError_t hipEventSynchronize(hipEvent_t) { return hipSuccess; }
+inline hipError_t hipEventElapsedTime(float* ms, hipEvent_t, hipEvent_t) { *ms = 1.0f; return hipSuccess; }
 
 namespace emu {
 struct Block {
@@ -69,6 +80,21 @@ inline float __shfl_xor(float v, int mask, int width = 64)
 inline int __shfl_xor(int v, int mask, int width = 64)
 {
     return __builtin_bit_cast(int, __shfl_xor(__builtin_bit_cast(float, v), mask, width));
+}
+
+inline double __shfl_xor(double v, int mask, int width = 64)
+{
+    unsigned long long bits = __builtin_bit_cast(unsigned long long, v);
+    const unsigned int lo = (unsigned int)__shfl_xor((int)(bits & 0xffffffffull), mask, width);
+    const unsigned int hi = (unsigned int)__shfl_xor((int)(bits >> 32), mask, width);
+    return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+}
+// binary64 -> binary32 rounded toward zero
+inline float __double2float_rz(double d)
+{
+    float f = (float)d;
+    if (f == f && !__builtin_isinf(f) && __builtin_fabs((double)f) > __builtin_fabs(d)) f = __builtin_nextafterf(f, 0.0f);
+    return f;
 }
 
 typedef _Float16 emu_half8 __attribute__((ext_vector_type(8)));

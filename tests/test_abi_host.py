@@ -154,6 +154,42 @@ def test_static_scratch_entry_point_validates_before_touching_the_device(lib):
     assert re.search(r"#define SBI_STATIC_SCRATCH_BYTES \((\d+)u << 20\)", text).group(1) == str(sb.STATIC_SCRATCH_BYTES >> 20)
 
 
+def test_int8_layernorm_argument_validation_and_plans(lib):
+    """sbi_gemm_i8_ln: the layer-norm's and the INT8 call's checks both apply; its plans always run
+    from codes in the workspace (a kernel of its own normalises and quantises the rows)."""
+    sw = FAKE + (5 << 30)
+    g, b = FAKE + (6 << 30), FAKE + (7 << 30)
+
+    def call(**kw):
+        ln = sb.LayerNorm(kw.get("gamma", g), kw.get("beta", b), kw.get("eps", 1e-5), kw.get("moments", None))
+        return lib.sbi_gemm_i8_ln(kw.get("W", FAKE), kw.get("sw", sw), kw.get("K", 4096), 4096, FAKE + (1 << 30),
+                                  kw.get("B", 4), None if kw.get("no_ln") else ctypes.byref(ln), None, None, 0,
+                                  FAKE + (2 << 30), FAKE + (3 << 30), kw.get("wb", 1 << 30), None, None)
+    assert call(no_ln=True) == 1 and call(gamma=None) == 1 and call(sw=None) == 1
+    assert call(gamma=g + 8) == 3 and call(eps=-1.0) == 7
+    assert call(K=4104) == 2 and call(B=0) == 4
+    assert call(moments=FAKE + (8 << 30)) == 10                   # the fp64 statistics read the rows
+    for B in (1, 8, 16, 40, 64):
+        for K, N in ((4096, 12288), (16384, 4096), (1008, 130)):
+            pl = sb.plan(B, K, N, int8=True, layernorm=True)
+            plain = sb.plan(B, K, N, int8=True)
+            assert pl["path"] == sb.PATH_MFMA
+            assert pl["workspace_bytes"] >= 256 * 1024 + B * K      # counters, codes, row scales
+            if B > 8:
+                assert pl == plain                                  # above 8 rows the INT8 call runs from codes anyway
+    need = sb.plan(4, 4096, 4096, int8=True, layernorm=True)["workspace_bytes"]
+    assert call(wb=need - 1) == 6
+    # an INT8 layer may carry layer-norms now
+    L = sb.Layer()
+    L.Wqkv = L.Wout = L.Wffn1 = L.Wffn2 = FAKE
+    L.h, L.n_qkv, L.k_out, L.n_ffn1, L.k_ffn2 = 256, 768, 256, 1024, 1024
+    L.sqkv = L.sout = L.sffn1 = L.sffn2 = sw
+    L.ln1_gamma, L.ln1_beta, L.ln2_gamma, L.ln2_beta, L.ln_eps = g, b, g, b, 1e-5
+    assert lib.sbi_layer_workspace_bytes(ctypes.byref(L), 4) >= 256 * 1024 + 4 * (256 + 256 + 256 + 1024)
+    L.ln1_beta = None
+    assert lib.sbi_layer_workspace_bytes(ctypes.byref(L), 4) == 0   # gamma without beta
+
+
 def test_tuner_argument_validation(lib):
     """sbi_layer_tune / sbi_gemm_tune refuse bad arguments on the host (nothing is launched or timed)."""
     L = sb.Layer()

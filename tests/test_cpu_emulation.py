@@ -34,7 +34,8 @@ def run(cmd):
     assert r.returncode == 0 and "AddressSanitizer" not in r.stdout, r.stdout[-3000:]
 
 
-# B K N waves depth split panels mode (0 plain, 1 layer-norm, 2 int8, 3 moments out, 4 layer-norm from moments)
+# B K N waves depth split panels mode (0 plain, 1 layer-norm, 2 int8, 3 moments out, 4 layer-norm from moments,
+# 5 layer-norm in front of int8)
 # (waves 0 = automatic plan)
 GEMM_CASES = [
     (1, 64, 64, 0, 0, 0, 0, 0), (3, 264, 200, 0, 0, 0, 0, 0), (5, 1001, 130, 4, 4, 2, 1, 0),
@@ -58,6 +59,8 @@ GEMM_CASES = [
     (5, 4096, 64, 4, 4, 1, 1, 2), (2, 8192, 64, 0, 0, 0, 0, 2), (17, 1024, 136, 4, 2, 3, 1, 2), (33, 4096, 64, 0, 0, 0, 0, 2),
     (3, 264, 200, 0, 0, 0, 0, 3), (17, 1024, 136, 4, 2, 3, 1, 3), (64, 512, 128, 4, 2, 1, 1, 3), (5, 512, 72, 4, 4, 1, 1, 3),
     (3, 320, 200, 0, 0, 0, 0, 4), (40, 1024, 72, 4, 4, 2, 1, 4), (2, 6144, 64, 4, 4, 1, 1, 4),
+    (1, 64, 64, 0, 0, 0, 0, 5), (3, 272, 200, 0, 0, 0, 0, 5), (8, 2048, 128, 8, 4, 1, 1, 5), (17, 1024, 136, 4, 2, 3, 1, 5),
+    (40, 1024, 72, 0, 0, 0, 0, 5), (64, 2048, 128, 8, 4, 2, 2, 5),
 ]
 
 

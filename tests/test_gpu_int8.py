@@ -208,3 +208,87 @@ def test_int8_layer_gemms(gpu, cfg_id, B, chained):
             xin = Yh[2] if (g == 3 and chained) else data[g][2]
             check(Yh[g], xin, prep[g][2], prep[g][3], data[g][1], r, epi, f"layer gemm {g}")
     assert not ws[:256 * 1024].cpu().numpy().any()
+
+
+# ------------------------------------------------------------------------------ layer-norm in front
+def check_ln(Y, X, gamma, beta, Wq, sw, bias, R, epi, what):
+    want = orc.gemm_i8_ln_from_fp16(X, gamma, beta, 1e-5, Wq, sw, bias, R, EPI_ORACLE[epi])
+    ok, rep = orc.check_close(Y, want, ulps=2, abs_tol=1e-3)
+    assert ok, f"{what}: {rep}"
+
+
+@pytest.mark.parametrize("B,K,N", [(1, 64, 64), (3, 272, 200), (8, 4096, 192), (5, 4112, 72), (16, 2048, 320),
+                                   (33, 1024, 192), (64, 2048, 128), (2, 12288, 64), (48, 8192, 192)])
+def test_int8_gemm_with_layernorm_in_front(gpu, B, K, N):
+    """sbi_gemm_i8_ln against the oracle's composition layernorm -> quantize_rows -> gemm_i8."""
+    from paper_2207_00032_amd import binding as sb
+    W, bias, _, R = wl.make_gemm_inputs(K, N, B, seed=B + K + N, config_id=403)
+    gamma, beta, X = wl.make_layernorm_inputs(K, B, seed=B + K, config_id=403)
+    Wl, sw_d, Wq, sw = prepare(gpu, W)
+    ln = (_dev(gamma, gpu), _dev(beta, gpu), 1e-5)
+    Xd, bd, Rd = _dev(X, gpu), _dev(bias, gpu), _dev(R, gpu)
+    for epi in ("none", "bias_gelu", "bias_residual"):
+        Y = sb.gemm_i8(Wl, sw_d, K, N, Xd, bd if "bias" in epi else None, Rd if "residual" in epi else None, epi,
+                       layernorm=ln)
+        check_ln(Y.cpu().numpy(), X, gamma, beta, Wq, sw, bias, R, epi, f"LN+INT8 B={B} K={K} N={N} {epi}")
+
+
+def test_int8_layernorm_codes_are_the_oracles(gpu):
+    """Weights 127 * identity (codes 127 on the diagonal, column scales 1) make Y[b,n] = code[b,n] * amax_b:
+    one activation code off by one would move an output by a whole amax, far beyond the tolerance.  Rows
+    with very different means and spreads, a constant row (variance 0), 2048 features."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    K = N = 2048
+    B = 9
+    gamma, beta, X = wl.make_layernorm_inputs(K, B, seed=77, config_id=404, row_shift=3.0, row_scale=8.0)
+    X[4, :] = np.float16(1.25)                                   # constant row: normalises to beta
+    W = (127.0 * np.eye(K)).astype(np.float16)
+    Wl, sw_d, Wq, sw = prepare(gpu, W)
+    assert np.all(sw == 1) and np.array_equal(np.diag(Wq), np.full(K, 127, np.int8))
+    Y = sb.gemm_i8(Wl, sw_d, K, N, _dev(X, gpu), None, None, "none", layernorm=(_dev(gamma, gpu), _dev(beta, gpu), 1e-5))
+    torch.cuda.synchronize()
+    want = orc.gemm_i8_ln_from_fp16(X, gamma, beta, 1e-5, Wq, sw)
+    ok, rep = orc.check_close(Y.cpu().numpy(), want, ulps=2, abs_tol=1e-3)
+    assert ok, rep
+    Xq, sx = orc.quantize_rows(orc.layernorm(X, gamma, beta, 1e-5))
+    assert np.abs(Xq).max() == 127 and len(np.unique(Xq)) > 200    # the case does exercise the code range
+    # a code off by one moves an output by the row's amax = 127 * sx; the tolerance is far below that everywhere
+    step = (127.0 * sx.astype(np.float64))[:, None]
+    diff = np.abs(Y.cpu().numpy().astype(np.float64) - want.astype(np.float64))
+    assert (diff < 0.25 * np.maximum(step, 1e-6)).all() or (step == 0).any()
+    assert (diff[sx > 0] < 0.25 * step[sx > 0]).all()
+
+
+@pytest.mark.parametrize("cfg_id,B,chained", [(1, 4, True), (1, 1, False), (2, 8, False), (1, 24, False)])
+def test_int8_layer_gemms_with_layernorms(gpu, cfg_id, B, chained):
+    """sbi_layer_gemms with int8 weights and ln1 / ln2: QKV and FFN1 see normalised rows, the attention
+    output and FFN2 plain ones, all four in one INT8 launch behind one quantisation kernel."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    cfg = wl.CONFIGS[cfg_id]
+    data = [wl.make_gemm_inputs(s.K, s.N, B, seed=6, config_id=cfg_id, gemm_id=i) for i, s in enumerate(cfg.gemms)]
+    h = cfg.gemms[0].K
+    lns = {gi: wl.make_layernorm_inputs(h, B, seed=6, config_id=cfg_id, gemm_id=gi) for gi in (0, 2)}
+    prep = [prepare(gpu, d[0]) for d in data]
+    biases = [_dev(d[1], gpu) for d in data]
+    ln_d = {gi: (_dev(lns[gi][0], gpu), _dev(lns[gi][1], gpu)) for gi in (0, 2)}     # the layer struct holds bare pointers
+    L = sb.make_layer(*[p[0] for p in prep], h, cfg.gemms[0].N, cfg.gemms[1].K, cfg.gemms[2].N, cfg.gemms[3].K,
+                      bqkv=biases[0], bout=biases[1], bffn1=biases[2], bffn2=biases[3], ffn1_gelu=True,
+                      scales=[p[1] for p in prep], ln1=ln_d[0], ln2=ln_d[2])
+    ws = sb.new_workspace(sb.layer_workspace_bytes(L, B), gpu)
+    Xh = [lns[0][2], data[1][2], lns[2][2], data[3][2]]
+    Xs = [_dev(x, gpu) for x in Xh]
+    Rd = _dev(data[3][3], gpu)
+    Ys = [torch.empty((B, s.N), dtype=torch.float16, device=gpu) for s in cfg.gemms]
+    for rep in range(2):
+        sb.layer_gemms(L, B, Xs[0], Xs[1], Xs[2], None if chained else Xs[3], Rd, Ys[0], Ys[1], Ys[2], Ys[3], ws)
+        torch.cuda.synchronize()
+        Yh = [y.cpu().numpy() for y in Ys]
+        for g, (epi, r) in enumerate((("bias", None), ("bias", None), ("bias_gelu", None), ("bias_residual", data[3][3]))):
+            xin = Yh[2] if (g == 3 and chained) else Xh[g]
+            if g in (0, 2):
+                check_ln(Yh[g], xin, lns[g][0], lns[g][1], prep[g][2], prep[g][3], data[g][1], r, epi, f"LN INT8 layer gemm {g}")
+            else:
+                check(Yh[g], xin, prep[g][2], prep[g][3], data[g][1], r, epi, f"LN INT8 layer gemm {g}")
+    assert not ws[:256 * 1024].cpu().numpy().any()
