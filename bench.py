@@ -63,6 +63,15 @@ def parse_args():
                     help="time one token-generation step of a whole h=4096 layer (32 heads): layer-norm + QKV, attention "
                          "over the KV cache, attention output + residual, layer-norm + FFN1 + GeLU, FFN2 + residual as five "
                          "dependent launches replayed from a HIP graph; value = algorithmic bytes of the step / time")
+    ap.add_argument("--read-ceiling", action="store_true",
+                    help="time pure streaming reads of the layer's bytes (sbi_calib_read: the weight stream's access shape, "
+                         "nothing else) over block shapes, cold, and exit: the ceiling the GeMM launch is measured against")
+    ap.add_argument("--timeline", action="store_true",
+                    help="measurement build only (python paper_2207_00032_amd/csrc/build.py --dev): per-block timestamps of "
+                         "the layer launch - start, X staged, first k-step, end of stream, end of block - as percentiles")
+    ap.add_argument("--ablate", action="store_true",
+                    help="measurement build only: time the layer launch with parts of the kernel switched off "
+                         "(matrix-core work, operand reads, X staging, reduction + epilogue)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run a few copy-kernel and layer launches and exit (for rocprofv3 --pmc runs)")
     return ap.parse_args()
@@ -334,6 +343,17 @@ def crossover_main(args):
     n = [0]
     rows = []
     auto_us = {}
+    if args.pmc_probe:                  # a few launches of the dispatcher's pick per batch, for rocprofv3 --pmc runs
+        for B in batches:
+            Xd = torch.from_numpy(np.ascontiguousarray(X[:B])).to(dev)
+            Yd = torch.empty((B, N), dtype=torch.float16, device=dev)
+            for i in range(4):
+                sb.gemm(Wl[i % 3], K, N, Xd, bias_d, None, "bias_gelu", out=Yd, workspace=ws)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_probe": True, "config": 5, "batches": list(batches), "launches_per_batch": 4,
+                          "bytes": {str(B): spec.algorithmic_bytes(B) for B in batches},
+                          "plans": {str(B): sb.plan(B, K, N) for B in batches}}))
+        return
     for B in batches:
         Xd = torch.from_numpy(np.ascontiguousarray(X[:B])).to(dev)
         Yd = torch.empty((B, N), dtype=torch.float16, device=dev)
@@ -359,7 +379,9 @@ def crossover_main(args):
                          "split_k": pl["split_k"], "panels": pl["panels"], "us": round(us, 2),
                          "GBps": round(nbytes / us / 1e3, 1), "hbm_frac": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
                          "TFLOPs": round(nflops / us / 1e6, 2),
-                         "mfma_frac": round(nflops / us / 1e6 / MFMA_F16_PEAK_TFLOPS, 4), "parity_ok": ok})
+                         "mfma_frac": round(nflops / us / 1e6 / MFMA_F16_PEAK_TFLOPS, 4),
+                         "hbm_ceiling_mfma_frac": round(nflops / nbytes * HBM_PEAK_GBPS / 1e3 / MFMA_F16_PEAK_TFLOPS, 4),
+                         "parity_ok": ok})
             if name == "auto":
                 auto_us[B] = us
     del Wl, Wl0, Wd
@@ -391,8 +413,9 @@ def crossover_main(args):
                      "TFLOPs_cold": round(nflops / res["cold"] / 1e6, 1), "TFLOPs_warm": round(nflops / res["warm"] / 1e6, 1),
                      "mfma_frac_cold": round(nflops / res["cold"] / 1e6 / MFMA_F16_PEAK_TFLOPS, 4),
                      "mfma_frac_warm": round(nflops / res["warm"] / 1e6 / MFMA_F16_PEAK_TFLOPS, 4),
-                     # what HBM alone allows at this batch: B flop per byte streamed at the achieved cold rate
-                     "hbm_ceiling_TFLOPs": round(B * nbytes / res["cold"] / 1e6, 1)})
+                     # what HBM alone allows at this batch: flops per algorithmic byte x the 8 TB/s peak
+                     "hbm_ceiling_TFLOPs": round(nflops / nbytes * HBM_PEAK_GBPS / 1e3, 1),
+                     "hbm_ceiling_mfma_frac": round(nflops / nbytes * HBM_PEAK_GBPS / 1e3 / MFMA_F16_PEAK_TFLOPS, 4)})
     total_bytes = sum(spec.algorithmic_bytes(B) for B in batches)
     total_us = sum(auto_us[B] for B in batches)
     dom = max(batches)
@@ -409,6 +432,110 @@ def crossover_main(args):
         "cpu_baseline": None, "per_case": rows, "cache_resident_slice_8192x8192": warm}))
 
 
+def measure_main(args):
+    """--read-ceiling, --timeline, --ablate: where the time of the layer launch goes.  One JSON line each."""
+    import numpy as np
+    if args.timeline or args.ablate:
+        dev_lib = os.path.join(ROOT, "paper_2207_00032_amd", "libsbi_gemm_dev.so")
+        assert os.path.exists(dev_lib), "build the measurement library first: python paper_2207_00032_amd/csrc/build.py --dev"
+        os.environ["SBI_GEMM_LIB"] = dev_lib
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    from paper_2207_00032_amd import workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS[args.config]
+    specs = cfg.gemms
+    batches = tuple(int(b) for b in args.batches.split(",")) if args.batches else (1, 8)
+    copies = 3
+    layer_bytes = sum(s.weight_bytes for s in specs)
+
+    if args.read_ceiling:
+        sink = torch.zeros(1 << 20, dtype=torch.uint8, device=dev)
+        bufs = [torch.randint(0, 255, (layer_bytes,), dtype=torch.uint8, device=dev) for _ in range(copies)]
+        n = [0]
+        rows = []
+        for blocks, waves, depth in ((256, 8, 4), (256, 8, 8), (256, 16, 4), (512, 8, 4), (768, 4, 4), (768, 4, 8), (768, 8, 4),
+                                     (1024, 4, 4), (1536, 4, 4)):
+            for nt in (1, 0):
+                def call():
+                    sb.calib_read(bufs[n[0] % copies], sink, blocks, waves, depth, bool(nt))
+                    n[0] += 1
+                for _ in range(3):
+                    call()
+                us = _median_us(torch, call, reps=20)
+                rows.append({"blocks": blocks, "waves": waves, "depth": depth, "nontemporal": nt, "us": round(us, 2),
+                             "GBps": round(layer_bytes / us / 1e3, 1), "hbm_frac": round(layer_bytes / us / 1e3 / HBM_PEAK_GBPS, 4)})
+        best = min(rows, key=lambda r: r["us"])
+        print(json.dumps({"read_ceiling": {"bytes": layer_bytes, "copies_in_rotation": copies, "best": best, "rows": rows}}))
+        return
+
+    # seeded random weights of the configuration's shapes (values do not matter for timing; parity is not checked here)
+    g = torch.Generator(device=dev).manual_seed(0)
+    Wl0 = [sb.layout_weights((torch.randn(s.K, s.N, device=dev, generator=g) * 0.02).half()) for s in specs]
+    Wl = [Wl0] + [[w.clone() for w in Wl0] for _ in range(copies - 1)]
+    bias = [(torch.randn(s.N, device=dev, generator=g) * 0.02).half() for s in specs]
+    use_bias = [s.epilogue in (wl.BIAS, wl.BIAS_GELU, wl.BIAS_RESIDUAL) for s in specs]
+    layers = [sb.make_layer(*Wl[c], specs[0].K, specs[0].N, specs[1].K, specs[2].N, specs[3].K,
+                            bqkv=bias[0] if use_bias[0] else None, bout=bias[1] if use_bias[1] else None,
+                            bffn1=bias[2] if use_bias[2] else None, bffn2=bias[3] if use_bias[3] else None,
+                            ffn1_gelu=specs[2].epilogue in (wl.BIAS_GELU, wl.GELU)) for c in range(copies)]
+    ws = sb.new_workspace(64 << 20, dev)
+    trace = torch.zeros(8 * 16384, dtype=torch.int64, device=dev)
+    out = []
+    for B in batches:
+        X = [torch.randn(B, s.K, device=dev, generator=g).half() for s in specs]
+        R = torch.randn(B, specs[3].N, device=dev, generator=g).half() if specs[3].epilogue in (wl.BIAS_RESIDUAL, wl.RESIDUAL) else None
+        Y = [torch.empty(B, s.N, dtype=torch.float16, device=dev) for s in specs]
+        n = [0]
+
+        def call():
+            sb.layer_gemms(layers[n[0] % copies], B, X[0], X[1], X[2], X[3], R, Y[0], Y[1], Y[2], Y[3], ws)
+            n[0] += 1
+
+        plans, grid = sb.layer_plan(layers[0], B)
+        plan = {"grid": grid, "waves": plans[0]["waves"], "depth": plans[0]["depth"],
+                "split_k": [p["split_k"] for p in plans], "ksteps_per_block": [p["ksteps_per_split"] for p in plans]}
+        if args.ablate:
+            res = {}
+            for mask, name in ((0, "full kernel"), (1, "no matrix-core work"), (8, "no operand reads from LDS"), (2, "no X staging"),
+                               (4, "no reduction, no epilogue"), (6, "no X staging, no reduction, no epilogue"),
+                               (15, "weight stream only")):
+                os.environ["SBI_ABLATE"] = str(mask)
+                for _ in range(3):
+                    call()
+                res[name] = round(_median_us(torch, call, reps=20), 2)
+            os.environ.pop("SBI_ABLATE", None)
+            out.append({"B": B, "plan": plan, "us": res})
+            continue
+        for _ in range(5):
+            call()
+        us = _median_us(torch, call, reps=20)
+        os.environ["SBI_TRACE_PTR"] = hex(trace.data_ptr())
+        call()
+        torch.cuda.synchronize()
+        os.environ.pop("SBI_TRACE_PTR", None)
+        t = trace.cpu().numpy().reshape(-1, 8)[:grid].astype(np.int64)
+        t0 = t[:, 0].min()
+        col = lambda c: (t[:, c] - t0) / 100.0                      # 100 MHz counter -> microseconds
+        start, stream0, end, last, xst, first = col(0), col(1), col(2), col(4), col(5), col(6)
+        slot = t[:, 3] >> 32
+        pct = lambda a: [round(float(np.percentile(a, q)), 2) for q in (0, 10, 50, 90, 100)]
+        out.append({"B": B, "plan": plan, "us_per_launch_untraced": round(us, 2), "span_us": round(float(end.max()), 2),
+                    "percentiles": "min p10 p50 p90 max",
+                    "block_start": pct(start), "x_staged": pct(xst), "first_kstep_done": pct(first),
+                    "wave0_stream_done": pct(stream0), "last_wave_stream_done": pct(last), "block_end": pct(end),
+                    "end_minus_last_wave": pct(end - last),
+                    "per_problem_slot": [{"slot": int(k), "blocks": int((slot == k).sum()),
+                                          "last_wave_stream_done_p50": round(float(np.median(last[slot == k])), 2),
+                                          "last_wave_stream_done_max": round(float(last[slot == k].max()), 2),
+                                          "block_end_max": round(float(end[slot == k].max()), 2)}
+                                         for k in sorted(set(slot.tolist()))],
+                    "blocks_done_streaming_by_us": {str(q): round(float(np.quantile(last, q / 100)), 2) for q in (50, 80, 90, 95, 99)}})
+    print(json.dumps({"ablation" if args.ablate else "timeline": out, "workload": f"config{args.config}:{cfg.name} layer launch, "
+                      f"{copies} weight copies in rotation"}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -421,6 +548,8 @@ def main():
         return decoder_main(args)
     if args.config == 5:
         return crossover_main(args)
+    if args.read_ceiling or args.timeline or args.ablate:
+        return measure_main(args)
 
     import numpy as np
     import torch

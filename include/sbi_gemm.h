@@ -447,21 +447,6 @@ sbi_status sbi_attn_decode_ragged(const void* qkv, void* k_cache, void* v_cache,
                                   int32_t head_dim, int64_t max_seq, const int32_t* pos, int64_t pos_bound, float scale,
                                   void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/*
- * Measurement helpers (no part of the GeMM path; for callers that profile it).
- * sbi_calib_read streams `bytes` (a multiple of 4096, 256-byte aligned, device) from src
- * with the GeMM's own access shape - `blocks` thread blocks of `waves` wavefronts (4, 8 or
- * 16), each wavefront keeping `depth` (4 or 8) 4 KiB units in flight, 128-bit loads,
- * non-temporal if `nontemporal` - and writes nothing in practice (sink, device, >= 16 bytes
- * per block, only keeps the loads alive).  Its bandwidth is the ceiling this access pattern
- * can reach.  sbi_calib_copy copies `bytes` (a multiple of 16; both pointers 16-byte
- * aligned, device) with plain 128-bit loads and stores: a kernel of known HBM traffic
- * against which hardware byte counters are scaled.
- */
-sbi_status sbi_calib_read(const void* src, size_t bytes, void* sink, size_t sink_bytes,
-                          int32_t blocks, int32_t waves, int32_t depth, int32_t nontemporal, void* hip_stream);
-sbi_status sbi_calib_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
-
 const char* sbi_status_string(sbi_status s);
 
 /* Library version: major*10000 + minor*100 + patch. */

@@ -3,7 +3,7 @@
 // HBM read bandwidth this access pattern can reach at all (the honest ceiling next to the
 // 8 TB/s data-sheet figure); the copy kernel is the reference against which hardware
 // counters (FETCH_SIZE / WRITE_SIZE) are scaled.
-#include "../../include/sbi_gemm.h"
+#include "sbi_calib.h"
 #include "sbi_common.h"
 
 namespace sbi {
