@@ -54,9 +54,10 @@ def test_tuned_layer_launch_matches_oracle(gpu, B, ln):
     g = cfg.gemms
     gamma, beta, _ = wl.make_layernorm_inputs(g[0].K, B, seed=2, config_id=109)
     lnp = (_dev(gamma, gpu), _dev(beta, gpu)) if ln else None
-    layers = [sb.make_layer(*[w if c == 0 else w.clone() for w in Wl0], g[0].K, g[0].N, g[1].K, g[2].N, g[3].K,
+    sets = [Wl0, [w.clone() for w in Wl0]]          # make_layer keeps bare pointers: the tensors must outlive the layers
+    layers = [sb.make_layer(*ws_, g[0].K, g[0].N, g[1].K, g[2].N, g[3].K,
                             bqkv=biases[0], bout=biases[1], bffn1=biases[2], bffn2=biases[3], ffn1_gelu=True,
-                            ln1=lnp, ln2=lnp) for c in range(2)]
+                            ln1=lnp, ln2=lnp) for ws_ in sets]
     ws = sb.new_workspace(64 << 20, gpu)
     Xs = [_dev(d[2], gpu) for d in data]
     Rd = _dev(data[3][3], gpu)
