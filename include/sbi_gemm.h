@@ -447,6 +447,19 @@ sbi_status sbi_attn_decode_ragged(const void* qkv, void* k_cache, void* v_cache,
                                   int32_t head_dim, int64_t max_seq, const int32_t* pos, int64_t pos_bound, float scale,
                                   void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Diagnostic (needs a GPU, enqueues nothing): vector registers per lane of the GeMM kernel variant that
+ * serves `B` rows with blocks of `waves` wavefronts, a weight ring of `depth` and `panels` panels per
+ * block.  flavour: 0 fp16, 1 fp16 with the layer-norm in front, 2 INT8 quantising X in the block,
+ * 3 INT8 from pre-quantised codes.  *allocated is what the compiled kernel uses (the runtime's figure),
+ * *assumed what the dispatcher's occupancy model takes for it: the model counts resident blocks per
+ * compute unit from the latter (Sec. III-C: the kernel's schedule is chosen for the memory bandwidth it
+ * reaches, which depends on how many blocks a unit holds), so the two must land in the same register
+ * granule.  SBI_ERR_TUNING: no such variant.  SBI_ERR_HIP: the runtime refused the query.
+ */
+sbi_status sbi_kernel_registers(int64_t B, int32_t waves, int32_t depth, int32_t panels, int32_t flavour,
+                                int32_t* allocated, int32_t* assumed);
+
 const char* sbi_status_string(sbi_status s);
 
 /* Library version: major*10000 + minor*100 + patch. */

@@ -33,7 +33,8 @@ EXPORTS = ["sbi_gemm_layout_bytes", "sbi_gemm_workspace_bytes", "sbi_gemm_layout
            "sbi_gemm_ln_workspace_bytes", "sbi_gemm_i8_layout_bytes", "sbi_gemm_i8_workspace_bytes",
            "sbi_gemm_i8_quantize_weights", "sbi_gemm_i8_layout_weights", "sbi_gemm_i8_layout_check", "sbi_gemm_i8",
            "sbi_gemm_moments", "sbi_attn_decode", "sbi_attn_decode_workspace_bytes",
-           "sbi_attn_decode_ragged", "sbi_gemm_static", "sbi_layer_tune", "sbi_gemm_tune", "sbi_gemm_i8_ln"]
+           "sbi_attn_decode_ragged", "sbi_gemm_static", "sbi_layer_tune", "sbi_gemm_tune", "sbi_gemm_i8_ln",
+           "sbi_kernel_registers"]
 
 
 class SbiError(RuntimeError):
@@ -148,6 +149,8 @@ def load():
     L.sbi_layer_tune.argtypes = [vp, i32, i64] + [vp] * 9 + [vp, sz, vp, vp]
     L.sbi_gemm_tune.restype = i32
     L.sbi_gemm_tune.argtypes = [vp, i32, i64, i64, vp, i64, vp, vp, i32, vp, vp, sz, vp, vp]
+    L.sbi_kernel_registers.restype = i32
+    L.sbi_kernel_registers.argtypes = [i64, i32, i32, i32, i32, vp, vp]
     L.sbi_calib_read.restype = i32
     L.sbi_calib_read.argtypes = [vp, sz, vp, sz, i32, i32, i32, i32, vp]
     L.sbi_calib_copy.restype = i32
@@ -512,6 +515,21 @@ def layer_tune(layers, B, Xqkv, Xout, Xffn1, Xffn2, residual, Yqkv, Yout, Yffn1,
                                ctypes.byref(rep))
     _check(st, "sbi_layer_tune")
     return rep.as_dict()
+
+
+FLAVOURS = {"fp16": 0, "fp16_ln": 1, "int8": 2, "int8_codes": 3}
+
+
+def kernel_registers(B, waves, depth, panels=1, flavour="fp16"):
+    """(allocated, assumed) vector registers per lane of one GeMM kernel variant, or None if the
+    library has no such variant."""
+    a, m = ctypes.c_int32(0), ctypes.c_int32(0)
+    st = load().sbi_kernel_registers(int(B), int(waves), int(depth), int(panels), FLAVOURS[flavour],
+                                     ctypes.byref(a), ctypes.byref(m))
+    if st == 10:                      # SBI_ERR_TUNING: no such variant
+        return None
+    _check(st, "sbi_kernel_registers")
+    return a.value, m.value
 
 
 def gemm_tune(Wls, K, N, X, bias=None, residual=None, epilogue=EPI_NONE, out=None, workspace=None):

@@ -384,26 +384,39 @@ GemmParams fill_params(const GemmArgs& a, int64_t B, const Plan& pl, void* works
 // Wavefronts per CU that the register file lets the MFMA block kernel keep resident: the vector
 // registers the compiled kernel variants allocate (row blocks MB = ceil(B/16), waves, depth; plain
 // and layer-norm), in granules of 8, against 512 registers per SIMD lane and 4 SIMDs per CU.
-int resident_waves(int mb, int nw, int depth, int pw, bool ln, bool i8, bool preq = false)
+int assumed_vgprs(int mb, int nw, int depth, int pw, bool ln, bool i8, bool preq = false)
 {
-    static const int vgpr_i8_w4d2[4] = {108, 132, 200, 216};
-    static const int vgpr_i8_w4d4[4] = {164, 184, 212, 242};
+    // (a 4-wave kernel's figure is its vector registers rounded up to 4 plus its accumulation registers)
+    static const int vgpr_i8_w4d2[4] = {108, 180, 200, 220};
+    static const int vgpr_i8_w4d4[4] = {168, 188, 222, 232};
     static const int vgpr_i8_w8d4[4] = {138, 154, 164, 190};
-    static const int vgpr_w4d2[4] = {108, 128, 152, 168};
-    static const int vgpr_w4d4[4] = {140, 164, 196, 226};
-    static const int vgpr_w8d4[4] = {134, 152, 170, 188};
+    static const int vgpr_i8q_w4d2[4] = {108, 128, 152, 176};   // INT8 from pre-quantised codes
+    static const int vgpr_i8q_w4d4[4] = {148, 180, 208, 232};
+    static const int vgpr_i8q_w8d4[4] = {133, 156, 198, 226};
+    static const int vgpr_i8q_w8d2p2[4] = {149, 183, 219, 252};
+    static const int vgpr_i8q_w8d4p2[4] = {151, 151, 180, 212};
+    static const int vgpr_w4d2[4] = {108, 128, 152, 176};
+    static const int vgpr_w4d4[4] = {148, 176, 216, 248};
+    static const int vgpr_w8d4[4] = {134, 158, 201, 225};
     static const int vgpr_w8d2p2[4] = {150, 184, 210, 244};
     static const int vgpr_w8d2[4] = {102, 120, 130, 146};
     static const int vgpr_w8d4p2[4] = {152, 152, 180, 212};     // two wave groups, one panel each (batches above 16)
-    static const int vgpr_ln_w4d2[4] = {124, 144, 152, 184};
-    static const int vgpr_ln_w4d4[4] = {156, 188, 200, 236};
-    static const int vgpr_ln_w8d4[4] = {150, 172, 180, 204};
+    static const int vgpr_ln_w4d2[4] = {124, 136, 160, 188};
+    static const int vgpr_ln_w4d4[4] = {156, 188, 216, 244};
+    static const int vgpr_ln_w8d4[4] = {150, 168, 192, 208};
     const int* tab = (pw == 2) ? (depth == 4 && nw == 8 ? vgpr_w8d4p2 : vgpr_w8d2p2) : (nw == 8) ? (depth == 2 ? vgpr_w8d2 : vgpr_w8d4) : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);
     if (ln) tab = (nw == 8) ? vgpr_ln_w8d4 : (depth == 2 ? vgpr_ln_w4d2 : vgpr_ln_w4d4);
-    if (i8 && preq) tab = (pw == 2) ? (depth == 4 ? vgpr_w8d4p2 : vgpr_w8d2p2) : (nw == 8) ? vgpr_w8d4 : (depth == 2 ? vgpr_w4d2 : vgpr_w4d4);   // as the fp16 kernel's
+    if (i8 && preq) tab = (pw == 2) ? (depth == 4 ? vgpr_i8q_w8d4p2 : vgpr_i8q_w8d2p2) : (nw == 8) ? vgpr_i8q_w8d4 : (depth == 2 ? vgpr_i8q_w4d2 : vgpr_i8q_w4d4);
     else if (i8) tab = (nw == 8) ? vgpr_i8_w8d4 : (depth == 2 ? vgpr_i8_w4d2 : vgpr_i8_w4d4);
-    const int v = (tab[std::min(std::max(mb, 1), 4) - 1] + 7) / 8 * 8;
-    return 4 * std::min(8, 512 / v);
+    return tab[std::min(std::max(mb, 1), 4) - 1];
+}
+
+// wavefronts per CU for a kernel of `vgprs` vector registers per lane
+int waves_per_cu(int vgprs) { return 4 * std::min(8, 512 / ((vgprs + 7) / 8 * 8)); }
+
+int resident_waves(int mb, int nw, int depth, int pw, bool ln, bool i8, bool preq = false)
+{
+    return waves_per_cu(assumed_vgprs(mb, nw, depth, pw, ln, i8, preq));
 }
 
 // One point of the dispatcher's search space: block shape (waves, depth, panels per block), the
@@ -1380,6 +1393,23 @@ const char* sbi_status_string(sbi_status s)
         case SBI_ERR_TUNING: return "unsupported tuning request";
     }
     return "unknown status";
+}
+
+sbi_status sbi_kernel_registers(int64_t B, int32_t waves, int32_t depth, int32_t panels, int32_t flavour,
+                                int32_t* allocated, int32_t* assumed)
+{
+    if (!allocated || !assumed) return SBI_ERR_NULL;
+    if (B < 1 || B > SBI_MAX_BATCH) return SBI_ERR_BATCH;
+    if (flavour < 0 || flavour > 3) return SBI_ERR_TUNING;
+    const int mb = (int)((B + 15) / 16);
+    const bool ln = flavour == 1, i8 = flavour >= 2, preq = flavour == 3;
+    const void* fn = i8 ? sbi::i8_kernel_entry(mb, waves, depth, panels, preq) : sbi::mfma_kernel_entry(mb, waves, depth, panels, ln);
+    if (!fn) return SBI_ERR_TUNING;
+    hipFuncAttributes attr;
+    if (hipFuncGetAttributes(&attr, fn) != hipSuccess) return SBI_ERR_HIP;
+    *allocated = attr.numRegs;
+    *assumed = assumed_vgprs(mb, waves, depth, panels, ln, i8, preq);
+    return SBI_OK;
 }
 
 int32_t sbi_version(void) { return 100; }

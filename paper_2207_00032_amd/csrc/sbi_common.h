@@ -130,6 +130,9 @@ int launch_streamk(const SkParams& p, int waves, int depth, int grid, hipStream_
 int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, bool layernorm, size_t lds_bytes,
                 hipStream_t st);
 int launch_i8(const GroupParams& gp, int waves, int depth, int panels, bool prequantized, size_t lds_bytes, hipStream_t st);
+// the kernel those two would start (null: no such variant), for queries of its compiled resources
+const void* mfma_kernel_entry(int mb, int waves, int depth, int panels, bool layernorm);
+const void* i8_kernel_entry(int mb, int waves, int depth, int panels, bool prequantized);
 // Normalises the rows of every problem of `gp` whose X16 (raw rows) differs from its X (where the
 // GeMM kernel will read the normalised rows), one block per row.
 int launch_layernorm_rows(const GroupParams& gp, hipStream_t st);

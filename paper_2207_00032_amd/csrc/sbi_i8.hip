@@ -427,6 +427,43 @@ int launch_i8(const GroupParams& gp, int waves, int depth, int panels, bool preq
     return (int)hipErrorInvalidValue;
 }
 
+template <int NW, int DEPTH, int PW, bool PREQ>
+static const void* entry_mb(int mb)
+{
+    switch (mb) {
+        case 1: return reinterpret_cast<const void*>(&sbi_i8_kernel<1, NW, DEPTH, PW, PREQ>);
+        case 2: return reinterpret_cast<const void*>(&sbi_i8_kernel<2, NW, DEPTH, PW, PREQ>);
+        case 3: return reinterpret_cast<const void*>(&sbi_i8_kernel<3, NW, DEPTH, PW, PREQ>);
+        case 4: return reinterpret_cast<const void*>(&sbi_i8_kernel<4, NW, DEPTH, PW, PREQ>);
+    }
+    return nullptr;
+}
+
+// The GeMM kernel launch_i8 would start for this block shape, as mfma_kernel_entry.
+const void* i8_kernel_entry(int mb, int waves, int depth, int panels, bool prequantized)
+{
+    if (prequantized) {
+        if (panels == 2 && waves == 8 && depth == 4) {
+            switch (mb) {
+                case 2: return reinterpret_cast<const void*>(&sbi_i8_wg_kernel<2, 4>);
+                case 3: return reinterpret_cast<const void*>(&sbi_i8_wg_kernel<3, 4>);
+                case 4: return reinterpret_cast<const void*>(&sbi_i8_wg_kernel<4, 4>);
+            }
+            return nullptr;
+        }
+        if (panels == 2) return (waves == 8 && depth == 2) ? entry_mb<8, 2, 2, true>(mb) : nullptr;
+        if (waves == 4 && depth == 2) return entry_mb<4, 2, 1, true>(mb);
+        if (waves == 4 && depth == 4) return entry_mb<4, 4, 1, true>(mb);
+        if (waves == 8 && depth == 4) return entry_mb<8, 4, 1, true>(mb);
+        return nullptr;
+    }
+    if (panels != 1) return nullptr;
+    if (waves == 4 && depth == 2) return entry_mb<4, 2, 1, false>(mb);
+    if (waves == 4 && depth == 4) return entry_mb<4, 4, 1, false>(mb);
+    if (waves == 8 && depth == 4) return entry_mb<8, 4, 1, false>(mb);
+    return nullptr;
+}
+
 // ---- weight preparation (once, at initialisation) ------------------------------------------
 // Pre-layout of int8 codes Wq [K,N] row-major: block (p, ks) writes the 4 KiB of one panel
 // k-step; thread (t, g, i) gathers the 16 codes k = ks*64 + 16g .. +15 of column p*64 + 16t + i

@@ -419,4 +419,50 @@ int launch_mfma(const GroupParams& gp, int waves, int depth, int panels, bool la
     return (int)hipErrorInvalidValue;
 }
 
+template <int NW, int DEPTH, int PW, bool LN>
+static const void* entry_mb(int mb)
+{
+    switch (mb) {
+        case 1: return reinterpret_cast<const void*>(&sbi_mfma_kernel<1, NW, DEPTH, PW, LN>);
+        case 2: return reinterpret_cast<const void*>(&sbi_mfma_kernel<2, NW, DEPTH, PW, LN>);
+        case 3: return reinterpret_cast<const void*>(&sbi_mfma_kernel<3, NW, DEPTH, PW, LN>);
+        case 4: return reinterpret_cast<const void*>(&sbi_mfma_kernel<4, NW, DEPTH, PW, LN>);
+    }
+    return nullptr;
+}
+
+// The kernel launch_mfma would start for this block shape and mb = ceil(B/16) row blocks, for queries
+// of its compiled resources (hipFuncGetAttributes); null where launch_mfma has no variant.
+const void* mfma_kernel_entry(int mb, int waves, int depth, int panels, bool layernorm)
+{
+    if (layernorm) {
+        if (panels != 1) return nullptr;
+        if (waves == 4 && depth == 2) return entry_mb<4, 2, 1, true>(mb);
+        if (waves == 4 && depth == 4) return entry_mb<4, 4, 1, true>(mb);
+        if (waves == 8 && depth == 4) return entry_mb<8, 4, 1, true>(mb);
+        return nullptr;
+    }
+    if (panels == 1) {
+        if (waves == 4 && depth == 2) return entry_mb<4, 2, 1, false>(mb);
+        if (waves == 4 && depth == 4) return entry_mb<4, 4, 1, false>(mb);
+        if (waves == 4 && depth == 8) return entry_mb<4, 8, 1, false>(mb);
+        if (waves == 8 && depth == 2) return entry_mb<8, 2, 1, false>(mb);
+        if (waves == 8 && depth == 4) return entry_mb<8, 4, 1, false>(mb);
+        if (waves == 8 && depth == 8) return entry_mb<8, 8, 1, false>(mb);
+    } else if (panels == 2) {
+        if (waves == 8 && depth == 4) {
+            switch (mb) {
+                case 2: return reinterpret_cast<const void*>(&sbi_mfma_wg_kernel<2, 4>);
+                case 3: return reinterpret_cast<const void*>(&sbi_mfma_wg_kernel<3, 4>);
+                case 4: return reinterpret_cast<const void*>(&sbi_mfma_wg_kernel<4, 4>);
+            }
+            return nullptr;
+        }
+        if (waves == 4 && depth == 2) return entry_mb<4, 2, 2, false>(mb);
+        if (waves == 4 && depth == 4) return entry_mb<4, 4, 2, false>(mb);
+        if (waves == 8 && depth == 2) return entry_mb<8, 2, 2, false>(mb);
+    }
+    return nullptr;
+}
+
 }  // namespace sbi

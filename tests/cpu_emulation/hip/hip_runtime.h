@@ -33,6 +33,8 @@ inline hipError_t hipStreamSynchronize(hipStream_t) { return hipSuccess; }
 #define HIP_SYMBOL(x) (x)
 inline hipError_t hipGetDevice(int* d) { *d = 0; return hipSuccess; }
 template <class T> inline hipError_t hipGetSymbolAddress(void** p, T& symbol) { *p = (void*)&symbol; return hipSuccess; }
+struct hipFuncAttributes { int numRegs; };
+inline hipError_t hipFuncGetAttributes(hipFuncAttributes* a, const void*) { a->numRegs = 0; return hipSuccess; }
 typedef int hipEvent_t;
 inline hipError_t hipEventCreate(hipEvent_t* e) { *e = 0; return hipSuccess; }
 inline hipError_t hipEventDestroy(hipEvent_t) { return hipSuccess; }

@@ -83,3 +83,34 @@ def test_tuned_layer_launch_matches_oracle(gpu, B, ln):
         first = [y.clone() for y in Ys] if first is None else first
         assert all(torch.equal(y.view(torch.int16), f.view(torch.int16)) for y, f in zip(Ys, first))
     assert not ws[:256 * 1024].cpu().numpy().any()
+
+
+def test_occupancy_table_matches_the_compiled_kernels(gpu):
+    """The dispatcher counts resident blocks per compute unit from a table of registers per lane; for
+    every variant it can choose, the compiled kernel's allocation must give the same number of resident
+    wavefronts (512 registers per lane and SIMD, allocated in eights, at most 8 wavefronts per SIMD)."""
+    from paper_2207_00032_amd import binding as sb
+
+    def waves(v):
+        return min(8, 512 // ((v + 7) // 8 * 8))
+    reachable = []
+    for mb in (1, 2, 3, 4):
+        for shp in ((4, 2, 1), (8, 4, 1), (4, 4, 1)):
+            reachable += [(mb, shp, f) for f in ("fp16", "fp16_ln", "int8_codes")]
+            if mb == 1:
+                reachable.append((mb, shp, "int8"))
+        reachable.append((mb, (8, 2, 1), "fp16"))
+        if mb >= 2:
+            reachable += [(mb, (8, 4, 2), "fp16"), (mb, (8, 2, 2), "fp16")]
+        if mb >= 3:
+            reachable += [(mb, (8, 4, 2), "int8_codes"), (mb, (8, 2, 2), "int8_codes")]
+    bad = []
+    for mb, (nw, depth, pw), flavour in reachable:
+        got = sb.kernel_registers(16 * mb, nw, depth, pw, flavour)
+        assert got is not None, (mb, nw, depth, pw, flavour)
+        allocated, assumed = got
+        assert 0 < allocated <= 512
+        if waves(allocated) != waves(assumed):
+            bad.append((mb, nw, depth, pw, flavour, allocated, assumed))
+    assert not bad, bad
+    assert sb.kernel_registers(16, 8, 8, 2, "fp16") is None          # no such variant
