@@ -72,6 +72,10 @@ def parse_args():
     ap.add_argument("--ablate", action="store_true",
                     help="measurement build only: time the layer launch with parts of the kernel switched off "
                          "(matrix-core work, operand reads, X staging, reduction + epilogue)")
+    ap.add_argument("--split-cost", action="store_true",
+                    help="measurement build only: the same 384 MiB of weights as one GeMM without split-K ([4096,49152]) and "
+                         "with it ([16384,12288] split 2 and 4), identical block streams: time per launch, span of the blocks "
+                         "and what a block spends between the end of its stream and its own end (the split-K hand-over)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run a few copy-kernel and layer launches and exit (for rocprofv3 --pmc runs)")
     return ap.parse_args()
@@ -432,6 +436,55 @@ def crossover_main(args):
         "cpu_baseline": None, "per_case": rows, "cache_resident_slice_8192x8192": warm}))
 
 
+def split_cost_main(args):
+    """--split-cost: what the cross-block split-K hand-over costs.  One JSON line."""
+    import numpy as np
+    dev_lib = os.path.join(ROOT, "paper_2207_00032_amd", "libsbi_gemm_dev.so")
+    assert os.path.exists(dev_lib), "build the measurement library first: python paper_2207_00032_amd/csrc/build.py --dev"
+    os.environ["SBI_GEMM_LIB"] = dev_lib
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev).manual_seed(0)
+    ws = sb.new_workspace(64 << 20, dev)
+    trace = torch.zeros(8 * 16384, dtype=torch.int64, device=dev)
+    pct = lambda a: [round(float(np.percentile(a, q)), 2) for q in (0, 10, 50, 90, 100)]
+    rows = []
+    for K, N, S in ((4096, 49152, 1), (16384, 12288, 2), (16384, 12288, 4)):
+        W = (torch.randn(K, N, device=dev, generator=g) * 0.02).half()
+        Wl = [sb.layout_weights(W)]
+        del W
+        Wl += [Wl[0].clone() for _ in range(2)]
+        X = torch.randn(1, K, device=dev, generator=g).half()
+        Y = torch.empty(1, N, dtype=torch.float16, device=dev)
+        for waves, depth in ((4, 4), (8, 2)):
+            n = [0]
+
+            def call():
+                sb.gemm(Wl[n[0] % 3], K, N, X, None, None, "none", out=Y, workspace=ws, path=sb.PATH_MFMA,
+                        split_k=S, waves=waves, depth=depth)
+                n[0] += 1
+            pl = sb.plan(1, K, N, sb.PATH_MFMA, split_k=S, waves=waves, depth=depth)
+            for _ in range(5):
+                call()
+            us = _median_us(torch, call, reps=20)
+            os.environ["SBI_TRACE_PTR"] = hex(trace.data_ptr())
+            call()
+            torch.cuda.synchronize()
+            os.environ.pop("SBI_TRACE_PTR", None)
+            t = trace.cpu().numpy().reshape(-1, 8)[:pl["grid"]].astype(np.int64)
+            t0 = t[:, 0].min()
+            col = lambda c: (t[:, c] - t0) / 100.0                  # 100 MHz counter -> microseconds
+            rows.append({"K": K, "N": N, "split_k": S, "waves": waves, "depth": depth, "grid": pl["grid"],
+                         "ksteps_per_block": pl["ksteps_per_split"], "us_per_launch": round(us, 2),
+                         "span_us": round(float(col(2).max()), 2), "percentiles": "min p10 p50 p90 max",
+                         "x_staged": pct(col(5)), "last_wave_stream_done": pct(col(4)), "block_end": pct(col(2)),
+                         "end_minus_last_wave": pct(col(2) - col(4))})
+        del Wl
+    print(json.dumps({"split_cost": rows, "workload": "384 MiB of fp16 weights as one GeMM, B = 1, no epilogue, 3 copies in rotation"}))
+
+
 def measure_main(args):
     """--read-ceiling, --timeline, --ablate: where the time of the layer launch goes.  One JSON line each."""
     import numpy as np
@@ -548,6 +601,8 @@ def main():
         return decoder_main(args)
     if args.config == 5:
         return crossover_main(args)
+    if args.split_cost:
+        return split_cost_main(args)
     if args.read_ceiling or args.timeline or args.ablate:
         return measure_main(args)
 

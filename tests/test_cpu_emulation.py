@@ -59,6 +59,8 @@ GEMM_CASES = [
     (5, 4096, 64, 4, 4, 1, 1, 2), (2, 8192, 64, 0, 0, 0, 0, 2), (17, 1024, 136, 4, 2, 3, 1, 2), (33, 4096, 64, 0, 0, 0, 0, 2),
     (3, 264, 200, 0, 0, 0, 0, 3), (17, 1024, 136, 4, 2, 3, 1, 3), (64, 512, 128, 4, 2, 1, 1, 3), (5, 512, 72, 4, 4, 1, 1, 3),
     (3, 320, 200, 0, 0, 0, 0, 4), (40, 1024, 72, 4, 4, 2, 1, 4), (2, 6144, 64, 4, 4, 1, 1, 4),
+    # 8 waves, depth 2, one panel
+    (8, 2048, 128, 8, 2, 1, 1, 0), (1, 4096, 64, 8, 2, 2, 1, 0),
     (1, 64, 64, 0, 0, 0, 0, 5), (3, 272, 200, 0, 0, 0, 0, 5), (8, 2048, 128, 8, 4, 1, 1, 5), (17, 1024, 136, 4, 2, 3, 1, 5),
     (40, 1024, 72, 0, 0, 0, 0, 5), (64, 2048, 128, 8, 4, 2, 2, 5),
 ]
