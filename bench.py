@@ -569,12 +569,26 @@ def measure_main(args):
         torch.cuda.synchronize()
         os.environ.pop("SBI_TRACE_PTR", None)
         t = trace.cpu().numpy().reshape(-1, 8)[:grid].astype(np.int64)
+        # six launches back to back, each into a trace buffer of its own: how far apart they run
+        more = [torch.zeros(8 * grid, dtype=torch.int64, device=dev) for _ in range(6)]
+        for tb in more:
+            os.environ["SBI_TRACE_PTR"] = hex(tb.data_ptr())
+            call()
+        torch.cuda.synchronize()
+        os.environ.pop("SBI_TRACE_PTR", None)
+        tm = [tb.cpu().numpy().reshape(-1, 8).astype(np.int64) for tb in more]
+        back_to_back = {"span_us": [round(float(x[:, 2].max() - x[:, 0].min()) / 100.0, 2) for x in tm],
+                        "last_end_to_next_first_start_us": [round(float(b[:, 0].min() - a[:, 2].max()) / 100.0, 2)
+                                                            for a, b in zip(tm, tm[1:])],
+                        "first_start_to_next_first_start_us": [round(float(b[:, 0].min() - a[:, 0].min()) / 100.0, 2)
+                                                               for a, b in zip(tm, tm[1:])]}
         t0 = t[:, 0].min()
         col = lambda c: (t[:, c] - t0) / 100.0                      # 100 MHz counter -> microseconds
         start, stream0, end, last, xst, first = col(0), col(1), col(2), col(4), col(5), col(6)
         slot = t[:, 3] >> 32
         pct = lambda a: [round(float(np.percentile(a, q)), 2) for q in (0, 10, 50, 90, 100)]
         out.append({"B": B, "plan": plan, "us_per_launch_untraced": round(us, 2), "span_us": round(float(end.max()), 2),
+                    "back_to_back": back_to_back,
                     "percentiles": "min p10 p50 p90 max",
                     "block_start": pct(start), "x_staged": pct(xst), "first_kstep_done": pct(first),
                     "wave0_stream_done": pct(stream0), "last_wave_stream_done": pct(last), "block_end": pct(end),
