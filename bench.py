@@ -76,6 +76,10 @@ def parse_args():
                     help="measurement build only: the same 384 MiB of weights as one GeMM without split-K ([4096,49152]) and "
                          "with it ([16384,12288] split 2 and 4), identical block streams: time per launch, span of the blocks "
                          "and what a block spends between the end of its stream and its own end (the split-K hand-over)")
+    ap.add_argument("--single-timeline", action="store_true",
+                    help="measurement build only: each of the configuration's four GeMMs as a launch of its own at B = 1 "
+                         "(the dispatcher's plan): time per launch, span of the blocks, per-block timestamps as percentiles, "
+                         "and what lies between two such launches")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run a few copy-kernel and layer launches and exit (for rocprofv3 --pmc runs)")
     return ap.parse_args()
@@ -485,6 +489,69 @@ def split_cost_main(args):
     print(json.dumps({"split_cost": rows, "workload": "384 MiB of fp16 weights as one GeMM, B = 1, no epilogue, 3 copies in rotation"}))
 
 
+def single_timeline_main(args):
+    """--single-timeline: where the time of a single sbi_gemm launch goes.  One JSON line."""
+    import numpy as np
+    dev_lib = os.path.join(ROOT, "paper_2207_00032_amd", "libsbi_gemm_dev.so")
+    assert os.path.exists(dev_lib), "build the measurement library first: python paper_2207_00032_amd/csrc/build.py --dev"
+    os.environ["SBI_GEMM_LIB"] = dev_lib
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    from paper_2207_00032_amd import workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS[args.config]
+    g = torch.Generator(device=dev).manual_seed(0)
+    ws = sb.new_workspace(64 << 20, dev)
+    pct = lambda a: [round(float(np.percentile(a, q)), 2) for q in (0, 10, 50, 90, 100)]
+    B = 1
+    rows = []
+    for spec in cfg.gemms:
+        K, N = spec.K, spec.N
+        W = (torch.randn(K, N, device=dev, generator=g) * 0.02).half()
+        Wl = [sb.layout_weights(W)]
+        del W
+        copies = max(3, -(-(768 << 20) // spec.weight_bytes))        # at least 768 MiB in rotation: cold
+        Wl += [Wl[0].clone() for _ in range(copies - 1)]
+        X = torch.randn(B, K, device=dev, generator=g).half()
+        bias = (torch.randn(N, device=dev, generator=g) * 0.02).half() if "bias" in spec.epilogue else None
+        R = torch.randn(B, N, device=dev, generator=g).half() if "residual" in spec.epilogue else None
+        Y = torch.empty(B, N, dtype=torch.float16, device=dev)
+        n = [0]
+
+        def call():
+            sb.gemm(Wl[n[0] % copies], K, N, X, bias, R, spec.epilogue, out=Y, workspace=ws)
+            n[0] += 1
+        pl = sb.plan(B, K, N)
+        for _ in range(2 * copies):
+            call()
+        us = _median_us(torch, call, reps=20)
+        traces = [torch.zeros(8 * pl["grid"], dtype=torch.int64, device=dev) for _ in range(6)]
+        for tb in traces:
+            os.environ["SBI_TRACE_PTR"] = hex(tb.data_ptr())
+            call()
+        torch.cuda.synchronize()
+        os.environ.pop("SBI_TRACE_PTR", None)
+        tm = [tb.cpu().numpy().reshape(-1, 8).astype(np.int64) for tb in traces]
+        t = tm[3]
+        t0 = t[:, 0].min()
+        col = lambda c: (t[:, c] - t0) / 100.0                      # 100 MHz counter -> microseconds
+        rows.append({"gemm": spec.name, "K": K, "N": N, "weight_MiB": spec.weight_bytes >> 20, "plan": {k: pl[k] for k in (
+                         "waves", "depth", "split_k", "ksteps_per_split", "grid")},
+                     "us_per_launch": round(us, 2), "read_time_at_7_TBps_us": round(spec.weight_bytes / 7.0e6, 2),
+                     "span_us": [round(float(x[:, 2].max() - x[:, 0].min()) / 100.0, 2) for x in tm],
+                     "last_end_to_next_first_start_us": [round(float(b[:, 0].min() - a[:, 2].max()) / 100.0, 2)
+                                                         for a, b in zip(tm, tm[1:])],
+                     "percentiles": "min p10 p50 p90 max", "block_start": pct(col(0)), "x_staged": pct(col(5)),
+                     # (no such mark in a block whose waves take a single round of k-steps)
+                     "first_kstep_done": pct(col(6)) if (t[:, 6] > 0).all() else None,
+                     "last_wave_stream_done": pct(col(4)), "block_end": pct(col(2)),
+                     "end_minus_last_wave": pct(col(2) - col(4))})
+        del Wl
+    print(json.dumps({"single_timeline": rows, "workload": f"config{args.config}:{cfg.name}, each GeMM a launch of its own, B = 1, "
+                      "weights cold (at least 768 MiB of copies in rotation)"}))
+
+
 def measure_main(args):
     """--read-ceiling, --timeline, --ablate: where the time of the layer launch goes.  One JSON line each."""
     import numpy as np
@@ -617,6 +684,8 @@ def main():
         return crossover_main(args)
     if args.split_cost:
         return split_cost_main(args)
+    if args.single_timeline:
+        return single_timeline_main(args)
     if args.read_ceiling or args.timeline or args.ablate:
         return measure_main(args)
 
