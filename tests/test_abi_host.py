@@ -158,6 +158,21 @@ def test_static_scratch_entry_point_validates_before_touching_the_device(lib):
     assert re.search(r"#define SBI_STATIC_SCRATCH_BYTES \((\d+)u << 20\)", text).group(1) == str(sb.STATIC_SCRATCH_BYTES >> 20)
 
 
+def test_kernel_registers_argument_validation(lib):
+    """sbi_kernel_registers refuses bad arguments and shapes without a kernel variant before it asks the
+    runtime anything."""
+    import ctypes
+    a, m = ctypes.c_int32(0), ctypes.c_int32(0)
+    pa, pm = ctypes.byref(a), ctypes.byref(m)
+    assert lib.sbi_kernel_registers(8, 4, 2, 1, 0, None, pm) == 1
+    assert lib.sbi_kernel_registers(8, 4, 2, 1, 0, pa, None) == 1
+    assert lib.sbi_kernel_registers(0, 4, 2, 1, 0, pa, pm) == 4 and lib.sbi_kernel_registers(65, 4, 2, 1, 0, pa, pm) == 4
+    assert lib.sbi_kernel_registers(8, 4, 2, 1, 4, pa, pm) == 10 and lib.sbi_kernel_registers(8, 4, 2, 1, -1, pa, pm) == 10
+    # no such variants: 16 waves; a layer-norm kernel of two panels; 8 waves x depth 2 with the layer-norm; INT8 depth 8
+    for B, w, d, pw, fl in ((8, 16, 4, 1, 0), (40, 8, 2, 2, 1), (8, 8, 2, 1, 1), (8, 4, 8, 1, 2), (8, 8, 4, 2, 0)):
+        assert lib.sbi_kernel_registers(B, w, d, pw, fl, pa, pm) == 10, (B, w, d, pw, fl)
+
+
 def test_int8_layernorm_argument_validation_and_plans(lib):
     """sbi_gemm_i8_ln: the layer-norm's and the INT8 call's checks both apply; its plans always run
     from codes in the workspace (a kernel of its own normalises and quantises the rows)."""
