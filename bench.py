@@ -896,6 +896,33 @@ def main():
         for B in batches:
             timed_run("layer, norms as separate torch kernels", B, sum(s.algorithmic_bytes(B, args.int8) for s in specs),
                       sum(s.flops(B) for s in specs), lambda: launch_unfused(B))
+    ceiling = None
+    if extras:
+        # the same weights on every launch ("warm"): 384 MiB do not fit the 256 MB last-level cache, so this
+        # row says how much of the rotation's effect is cache and how much is address translation
+        B0 = batches[0]
+        x, y = X_d[B0], Y_d[B0]
+        timed_run("layer, same weight copy every launch (warm)", B0, sum(s.algorithmic_bytes(B0) for s in specs),
+                  sum(s.flops(B0) for s in specs),
+                  lambda: sb.layer_gemms(layers[0], B0, x[0], x[1], x[2], x[3], R_d[B0], y[0], y[1], y[2], y[3], ws))
+        # pure streaming read of the layer's weight bytes with the weight stream's access shape (non-temporal
+        # 128-bit loads, 768 blocks x 8 waves x 4 deep, the best shape of bench.py --read-ceiling), rotating over
+        # the same copies: the calibrated ceiling beside the 8 TB/s data-sheet peak
+        sink = torch.zeros(1 << 16, dtype=torch.uint8, device=dev)
+        flat = [torch.cat([w.view(torch.uint8).reshape(-1)[256:256 + sp.weight_bytes] for w, sp in zip(Wl[c], specs)])
+                for c in range(copies)]
+        k = [0]
+
+        def read_once():
+            sb.calib_read(flat[k[0] % copies], sink, 768, 8, 4, True)
+            k[0] += 1
+        for _ in range(3):
+            read_once()
+        r_us = _median_us(torch, read_once, reps=20)
+        nb = flat[0].numel()
+        ceiling = {"us": round(r_us, 2), "bytes": nb, "GBps": round(nb / r_us / 1e3, 1),
+                   "frac_of_peak": round(nb / r_us / 1e3 / HBM_PEAK_GBPS, 4), "shape": "768 blocks x 8 waves x 4 deep, non-temporal"}
+        del flat
     if (args.per_gemm or extras) and not args.int8:
         # every GeMM as a launch of its own (sbi_gemm): what a caller with dependent GeMMs gets
         for B in (batches if args.per_gemm else (1, 8)):
@@ -1035,6 +1062,9 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "parity": parity,
+        "calibrated_read_ceiling": None if ceiling is None else dict(
+            ceiling, value_as_frac_of_ceiling=round(value / ceiling["GBps"], 4),
+            dominant_kernel_as_frac_of_ceiling=round(roofline["achieved"] / ceiling["GBps"], 4)),
         "per_launch": per_launch,
         "tuned_plans": {k: {"waves": v["waves"], "depth": v["depth"], "panels": v["panels"], "block_ksteps": v["block_ksteps"],
                             "candidates": v["candidates"], "us_best": round(v["us_best"], 2), "us_model": round(v["us_model"], 2)}
