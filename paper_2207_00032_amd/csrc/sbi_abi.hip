@@ -961,7 +961,8 @@ sbi_status sbi_gemm_static(const void* W_laid_out, int64_t K, int64_t N,
     void* ws = nullptr;
     if (pl.ws_bytes > 0)
         if (sbi_status s = scratch_of((hipStream_t)hip_stream, &ws)) return s;
-    return gemm_impl(W_laid_out, K, N, X, B, nullptr, bias, residual, epi, Y, ws, (size_t)pl.ws_bytes,
+    // (the whole array is offered: the launch below plans for itself and checks its need against it)
+    return gemm_impl(W_laid_out, K, N, X, B, nullptr, bias, residual, epi, Y, ws, ws ? (size_t)SBI_STATIC_SCRATCH_BYTES : 0,
                      hip_stream, nullptr);
 }
 
