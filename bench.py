@@ -587,7 +587,27 @@ def measure_main(args):
                 rows.append({"blocks": blocks, "waves": waves, "depth": depth, "nontemporal": nt, "us": round(us, 2),
                              "GBps": round(layer_bytes / us / 1e3, 1), "hbm_frac": round(layer_bytes / us / 1e3 / HBM_PEAK_GBPS, 4)})
         best = min(rows, key=lambda r: r["us"])
-        print(json.dumps({"read_ceiling": {"bytes": layer_bytes, "copies_in_rotation": copies, "best": best, "rows": rows}}))
+        # the same read from the last-level cache: one buffer read again and again ("same") against buffers in
+        # rotation (at least 1 GiB of them), 768 blocks x 8 waves x 4 deep, non-temporal and ordinary loads
+        del bufs
+        sizes = []
+        for mib in (64, 128, 256, 384):
+            many = [torch.randint(0, 255, (mib << 20,), dtype=torch.uint8, device=dev) for _ in range(max(2, -(-1024 // mib)))]
+            for nt in (1, 0):
+                us = {}
+                for mode in ("same", "rotating"):
+                    def call():
+                        sb.calib_read(many[n[0] % len(many)] if mode == "rotating" else many[0], sink, 768, 8, 4, bool(nt))
+                        n[0] += 1
+                    for _ in range(3):
+                        call()
+                    us[mode] = _median_us(torch, call, reps=20)
+                sizes.append({"MiB": mib, "nontemporal": nt, "us_same_buffer": round(us["same"], 2),
+                              "GBps_same_buffer": round((mib << 20) / us["same"] / 1e3, 1),
+                              "us_rotating": round(us["rotating"], 2), "GBps_rotating": round((mib << 20) / us["rotating"] / 1e3, 1)})
+            del many
+        print(json.dumps({"read_ceiling": {"bytes": layer_bytes, "copies_in_rotation": copies, "best": best, "rows": rows,
+                                           "cache_resident_against_rotating": sizes}}))
         return
 
     # seeded random weights of the configuration's shapes (values do not matter for timing; parity is not checked here)
