@@ -368,9 +368,10 @@ sbi_status sbi_layer_plan(const sbi_layer* L, int64_t B, int32_t chained, sbi_pl
  * the model puts within 30 % of its best estimate (at most 48 distinct plans, about 30 launches
  * each), on the caller's own tensors, and records the fastest for (B, shapes, data type, layer-norm
  * or not) in a process-wide table that every later plan, workspace-size and launch call of this
- * library consults first.  This serves the paper's aim for the small-batch GeMM, "as fast as the
- * memory can supply the weights" (Sec. I, "Latency Challenges"; Sec. III-C tiles "based on the problem
- * size"): here the tiling is chosen by measurement.
+ * library consults first (a candidate displaces the model's own pick only if it is more than 1 %
+ * faster: less than that is the spread of such measurements).  This serves the paper's aim for the
+ * small-batch GeMM - a launch that takes no longer than reading the weights once (Sec. I, latency
+ * challenges; Sec. III-C picks its tiling by problem size): here the tiling is chosen by measurement.
  *   layers / W_laid_out  n weight sets of ONE shape (a model's consecutive layers): trial launch i uses
  *                        set i mod n, so that with enough sets the weights come from HBM as they do in
  *                        the model, not from the last-level cache
