@@ -114,3 +114,47 @@ def test_occupancy_table_matches_the_compiled_kernels(gpu):
             bad.append((mb, nw, depth, pw, flavour, allocated, assumed))
     assert not bad, bad
     assert sb.kernel_registers(16, 8, 8, 2, "fp16") is None          # no such variant
+
+
+@pytest.mark.parametrize("B,ln", [(2, False), (8, True), (24, False), (40, True)])
+def test_tuned_int8_layer_launch_matches_oracle(gpu, B, ln):
+    """sbi_layer_tune on an INT8 layer (quantising in the blocks up to 8 rows, from codes above; with the
+    layer-norms in front: always from codes): whichever plan wins, every GeMM stays within the bar of the
+    INT8 oracle on the same weight codes, and the results are bit-identical from call to call."""
+    import torch
+    from paper_2207_00032_amd import binding as sb
+    from test_gpu_int8 import prepare, check, check_ln
+    cfg = wl.CONFIGS[1]
+    g = cfg.gemms
+    data = [wl.make_gemm_inputs(s.K, s.N, B, seed=4, config_id=110, gemm_id=i) for i, s in enumerate(g)]
+    prep = [prepare(gpu, d[0]) for d in data]
+    biases = [_dev(d[1], gpu) for d in data]
+    lns = {gi: wl.make_layernorm_inputs(g[0].K, B, seed=4, config_id=110, gemm_id=gi) for gi in (0, 2)}
+    ln_d = {gi: (_dev(lns[gi][0], gpu), _dev(lns[gi][1], gpu)) for gi in (0, 2)}    # kept alive: the struct holds pointers
+    sets = [[p[0] for p in prep], [p[0].clone() for p in prep]]
+    layers = [sb.make_layer(*ws_, g[0].K, g[0].N, g[1].K, g[2].N, g[3].K,
+                            bqkv=biases[0], bout=biases[1], bffn1=biases[2], bffn2=biases[3], ffn1_gelu=True,
+                            scales=[p[1] for p in prep], ln1=ln_d[0] if ln else None, ln2=ln_d[2] if ln else None)
+              for ws_ in sets]
+    ws = sb.new_workspace(64 << 20, gpu)
+    Xh = [lns[0][2] if ln else data[0][2], data[1][2], lns[2][2] if ln else data[2][2], data[3][2]]
+    Xs = [_dev(x, gpu) for x in Xh]
+    Rd = _dev(data[3][3], gpu)
+    Ys = [torch.empty((B, s.N), dtype=torch.float16, device=gpu) for s in g]
+    rep = sb.layer_tune(layers, B, Xs[0], Xs[1], Xs[2], Xs[3], Rd, Ys[0], Ys[1], Ys[2], Ys[3], ws)
+    assert rep["candidates"] >= 1 and 0 < rep["us_best"] <= rep["us_model"]
+    assert sb.layer_workspace_bytes(layers[0], B) <= ws.numel()
+    first = None
+    for it in range(2):
+        sb.layer_gemms(layers[it], B, Xs[0], Xs[1], Xs[2], Xs[3], Rd, Ys[0], Ys[1], Ys[2], Ys[3], ws)
+        torch.cuda.synchronize()
+        Yh = [y.cpu().numpy() for y in Ys]
+        for gi, (epi, r) in enumerate((("bias", None), ("bias", None), ("bias_gelu", None), ("bias_residual", data[3][3]))):
+            what = f"tuned INT8 layer B={B} ln={ln} gemm {gi}"
+            if ln and gi in (0, 2):
+                check_ln(Yh[gi], Xh[gi], lns[gi][0], lns[gi][1], prep[gi][2], prep[gi][3], data[gi][1], r, epi, what)
+            else:
+                check(Yh[gi], Xh[gi], prep[gi][2], prep[gi][3], data[gi][1], r, epi, what)
+        first = [y.clone() for y in Ys] if first is None else first
+        assert all(torch.equal(y.view(torch.int16), f.view(torch.int16)) for y, f in zip(Ys, first))
+    assert not ws[:256 * 1024].cpu().numpy().any()
