@@ -244,6 +244,7 @@ def decoder_main(args):
     del hw["Wqkv"], hw["Wout"], hw["Wffn1"], hw["Wffn2"]
     weight_bytes = 2 * (3 * h * h + h * h + 2 * h * f)
     results = []
+    tuned = {}
     total_bytes = total_sec = 0.0
     for B, ctx in cases:
         _, Kc, Vc = wl.make_attention_inputs(B, heads, d, ctx, seed=0, config_id=2)
@@ -262,6 +263,16 @@ def decoder_main(args):
             for c in range(copies):
                 layers[c].step(x, ctx - 1, states[c], x_moments=x_moments)
 
+        if not args.no_tune:
+            # the two plain GeMMs of the step (attention output, FFN2) get their launch plans measured, within the
+            # workspace the states were given; the layer-norm launches keep the model's plans
+            st0 = states[0]
+            st0.ctx.zero_()
+            st0.f.zero_()
+            tuned[f"out B={B}"] = sb.gemm_tune([l.Wout for l in layers], h, h, st0.ctx, layers[0].bout, x, "bias_residual",
+                                               out=st0.x2, workspace=st0.workspace)
+            tuned[f"ffn2 B={B}"] = sb.gemm_tune([l.Wffn2 for l in layers], f, h, st0.f, layers[0].bffn2, st0.x2,
+                                                "bias_residual", out=st0.y, workspace=st0.workspace)
         run()
         torch.cuda.synchronize()
         side = torch.cuda.Stream()
@@ -295,7 +306,9 @@ def decoder_main(args):
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": "h=4096 layer (32 heads of 128, FFN 16384), one generated token per step, "
                                "(B:context) " + args.decoder_layer + ", HIP-graph replay, 3 weight copies"},
-        "roofline": None, "cpu_baseline": None, "per_case": results}))
+        "roofline": None, "cpu_baseline": None, "per_case": results,
+        "tuned_plans": {k: {"waves": v["waves"], "depth": v["depth"], "block_ksteps": v["block_ksteps"],
+                            "us_best": round(v["us_best"], 2), "us_model": round(v["us_model"], 2)} for k, v in tuned.items()}}))
 
 
 MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X dense fp16 matrix-core peak, published
